@@ -1,0 +1,438 @@
+"""CPU oracle for ABFT-protected matrix multiplication -- TEST INFRASTRUCTURE ONLY.
+
+Plain fp64 / int64 definitions of what the protected GEMM path computes, written
+from the paper ("Arithmetic-Intensity-Guided Fault Tolerance for Neural Network
+Inference on GPUs", SC '21).  Only tests, the smoke check and the benchmark's
+CPU-baseline leg may import this package; the product never does, and this
+package imports nothing from the product.
+
+The heavy loops live in ``abft_oracle.c`` (built by ``oracle/build.py`` into
+``libabft_oracle.so``); this module marshals numpy arrays into them and adds the
+few scalar formulas (tolerance, comparison, selector) on top.
+
+Conventions (Sec. 2.1): A is M x K activations, B is K x N weights, C = A.B.
+Floating-point operands arrive as *storage* arrays -- ``numpy.float16`` for fp16,
+``numpy.uint16`` bit patterns for bf16 -- and are widened exactly to fp64 before
+any arithmetic; int8 operands are widened to int64.
+
+Parity pins (tests/test_oracle_*.py): the GEMM against brute force and
+``numpy.matmul``; the checksum identity exactly over integers and within a
+rigorous rounding bound in fp64; the tile checks against the global identity
+they telescope to; detection exhaustively over every bit of every element on
+small integer cases; arithmetic intensity / CMR / selector against every value
+the paper prints (Fig. 5, Fig. 11 axis labels, Fig. 10 labels, Sec. 3.3).
+Parity unpinned: the constant ``C_TOL`` of the floating-point tolerance -- the
+paper never states a tolerance (it says "equality check"), so only the rounding
+model and the clean-run campaigns of this build support it.
+"""
+from __future__ import annotations
+
+import ctypes
+import math
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "libabft_oracle.so")
+_lib = None
+
+F16, BF16, I8 = "f16", "bf16", "i8"
+
+# Floating-point tolerance of the checksum comparison (this build's reading; the
+# paper is silent).  Accumulators are binary32, so one rounding is at most
+# U32 = 2^-24 relative.  An accumulator that receives K products one after the
+# other carries a random-walk error of about U32 * sqrt(K) * |C_ij| / 2.4, and
+# the errors of the entries of C add in quadrature when C is summed, giving
+# about 0.4 * U32 * sqrt(K) * ||C||_F; the checksum side of the thread-level
+# scheme is accumulated the same way and contributes as much again.  C_TOL = 8
+# therefore sits more than ten standard deviations above the noise.
+U32 = 2.0 ** -24
+C_TOL = 8.0
+
+
+def _load():
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise RuntimeError(
+            f"{_LIB_PATH} not built: run `python oracle/build.py` (or __graft_entry__.build())")
+    lib = ctypes.CDLL(_LIB_PATH)
+    dp = ctypes.POINTER(ctypes.c_double)
+    i8p = ctypes.POINTER(ctypes.c_int8)
+    i64p = ctypes.POINTER(ctypes.c_int64)
+    u16p = ctypes.POINTER(ctypes.c_uint16)
+    ip = ctypes.POINTER(ctypes.c_int)
+    ci, cd = ctypes.c_int, ctypes.c_double
+    sig = {
+        "orc_threads": (ci, []),
+        "orc_f16_bits_to_f64": (cd, [ctypes.c_uint16]),
+        "orc_bf16_bits_to_f64": (cd, [ctypes.c_uint16]),
+        "orc_widen_f16": (None, [u16p, ctypes.c_size_t, dp]),
+        "orc_widen_bf16": (None, [u16p, ctypes.c_size_t, dp]),
+        "orc_gemm_f64": (None, [ci, ci, ci, dp, dp, dp]),
+        "orc_gemm_i8": (None, [ci, ci, ci, i8p, i8p, i64p]),
+        "orc_gemm_rows_f64": (None, [ci, ip, ci, ci, dp, dp, dp]),
+        "orc_gemm_rows_i8": (None, [ci, ip, ci, ci, i8p, i8p, i64p]),
+        "orc_partial_dot_f64": (cd, [ci, ci, dp, dp, ci, ci, ci, ci]),
+        "orc_partial_dot_i8": (ctypes.c_int64, [ci, ci, i8p, i8p, ci, ci, ci, ci]),
+        "orc_col_checksum_f64": (None, [ci, ci, dp, dp]),
+        "orc_row_checksum_f64": (None, [ci, ci, dp, dp]),
+        "orc_col_checksum_i8": (None, [ci, ci, i8p, i64p]),
+        "orc_row_checksum_i8": (None, [ci, ci, i8p, i64p]),
+        "orc_dot_f64": (cd, [ci, dp, dp]),
+        "orc_dot_i64": (ctypes.c_int64, [ci, i64p, i64p]),
+        "orc_block_sum_f64": (cd, [ci, dp, ci, ci, ci, ci]),
+        "orc_block_sum_i64": (ctypes.c_int64, [ci, i64p, ci, ci, ci, ci]),
+        "orc_phi_f64": (cd, [ci, ci, ci, dp, dp]),
+        "orc_sabs_f64": (cd, [ci, ci, ci, dp, dp]),
+        "orc_tile_one_sided_f64": (None, [ci, ci, dp, dp, dp, ci, ci, ci, ci, dp, dp]),
+        "orc_tile_one_sided_i8": (None, [ci, ci, i8p, i8p, i64p, ci, ci, ci, ci, i64p, i64p]),
+        "orc_tile_two_sided_f64": (None, [ci, ci, dp, dp, dp, ci, ci, ci, ci, dp, dp]),
+        "orc_flip_bit_f32": (cd, [cd, ci]),
+        "orc_flip_bit_i32": (ctypes.c_int64, [ctypes.c_int64, ci]),
+        "orc_flops": (cd, [cd, cd, cd, ci]),
+        "orc_bytes": (cd, [cd, cd, cd, cd, cd, cd, ci]),
+        "orc_arithmetic_intensity": (cd, [cd, cd, cd, cd, cd, cd, ci]),
+        "orc_cmr": (cd, [cd, cd]),
+        "orc_compute_bound": (ci, [cd, cd]),
+        "orc_select": (ci, [cd, cd]),
+        "orc_im2col_f64": (None, [ci, ci, ci, ci, ci, ci, ci, ci, dp, dp]),
+    }
+    for name, (res, args) in sig.items():
+        fn = getattr(lib, name)
+        fn.restype = res
+        fn.argtypes = args
+    _lib = lib
+    return lib
+
+
+def _p(a, ty):
+    return a.ctypes.data_as(ctypes.POINTER(ty))
+
+
+def _d(a):
+    return _p(a, ctypes.c_double)
+
+
+def threads() -> int:
+    """Host threads the OpenMP loops of the oracle use."""
+    return _load().orc_threads()
+
+
+# --------------------------------------------------------------------------- #
+# widening
+# --------------------------------------------------------------------------- #
+def widen(x: np.ndarray, dtype: str) -> np.ndarray:
+    """Storage array -> exact fp64 (fp16/bf16) or the int8 array itself, C-contiguous."""
+    lib = _load()
+    x = np.ascontiguousarray(x)
+    if x.dtype == np.float64 and dtype in (F16, BF16):
+        return x  # already widened (e.g. the output of im2col)
+    if dtype == F16:
+        bits = x.view(np.uint16) if x.dtype == np.float16 else x
+        assert bits.dtype == np.uint16
+        out = np.empty(bits.shape, dtype=np.float64)
+        lib.orc_widen_f16(_p(bits, ctypes.c_uint16), bits.size, _d(out))
+        return out
+    if dtype == BF16:
+        assert x.dtype == np.uint16, "bf16 operands are passed as uint16 bit patterns"
+        out = np.empty(x.shape, dtype=np.float64)
+        lib.orc_widen_bf16(_p(x, ctypes.c_uint16), x.size, _d(out))
+        return out
+    if dtype == I8:
+        assert x.dtype == np.int8
+        return x
+    raise ValueError(dtype)
+
+
+# --------------------------------------------------------------------------- #
+# GEMM
+# --------------------------------------------------------------------------- #
+def gemm(A: np.ndarray, B: np.ndarray, dtype: str) -> np.ndarray:
+    """C = A.B from storage operands: fp64 for fp16/bf16 inputs, int64 for int8 (Sec. 2.1)."""
+    lib = _load()
+    Aw, Bw = widen(A, dtype), widen(B, dtype)
+    M, K = Aw.shape
+    K2, N = Bw.shape
+    assert K == K2
+    if dtype == I8:
+        C = np.empty((M, N), dtype=np.int64)
+        lib.orc_gemm_i8(M, N, K, _p(Aw, ctypes.c_int8), _p(Bw, ctypes.c_int8), _p(C, ctypes.c_int64))
+    else:
+        C = np.empty((M, N), dtype=np.float64)
+        lib.orc_gemm_f64(M, N, K, _d(Aw), _d(Bw), _d(C))
+    return C
+
+
+def gemm_rows(A: np.ndarray, B: np.ndarray, dtype: str, rows) -> np.ndarray:
+    """Rows ``rows`` of C = A.B only (spot checks at sizes where all of C is too slow)."""
+    lib = _load()
+    Aw, Bw = widen(A, dtype), widen(B, dtype)
+    M, K = Aw.shape
+    N = Bw.shape[1]
+    rows = np.ascontiguousarray(rows, dtype=np.int32)
+    assert rows.min() >= 0 and rows.max() < M
+    if dtype == I8:
+        out = np.empty((len(rows), N), dtype=np.int64)
+        lib.orc_gemm_rows_i8(len(rows), _p(rows, ctypes.c_int), N, K, _p(Aw, ctypes.c_int8),
+                             _p(Bw, ctypes.c_int8), _p(out, ctypes.c_int64))
+    else:
+        out = np.empty((len(rows), N), dtype=np.float64)
+        lib.orc_gemm_rows_f64(len(rows), _p(rows, ctypes.c_int), N, K, _d(Aw), _d(Bw), _d(out))
+    return out
+
+
+def partial_dot(A, B, dtype, i, j, k_begin, k_end):
+    """sum_{k_begin <= k < k_end} A[i,k] B[k,j]: the running accumulator of element (i, j)."""
+    lib = _load()
+    Aw, Bw = widen(A, dtype), widen(B, dtype)
+    K, N = Bw.shape
+    if dtype == I8:
+        return int(lib.orc_partial_dot_i8(N, K, _p(Aw, ctypes.c_int8), _p(Bw, ctypes.c_int8), i, j,
+                                          k_begin, k_end))
+    return float(lib.orc_partial_dot_f64(N, K, _d(Aw), _d(Bw), i, j, k_begin, k_end))
+
+
+# --------------------------------------------------------------------------- #
+# the ABFT checksums (Sec. 2.4 steps 1-3)
+# --------------------------------------------------------------------------- #
+def col_checksum(A, dtype):
+    """alpha[k] = sum_i A[i,k]: the 1 x K activation checksum."""
+    lib = _load()
+    Aw = widen(A, dtype)
+    M, K = Aw.shape
+    if dtype == I8:
+        out = np.empty(K, dtype=np.int64)
+        lib.orc_col_checksum_i8(M, K, _p(Aw, ctypes.c_int8), _p(out, ctypes.c_int64))
+    else:
+        out = np.empty(K, dtype=np.float64)
+        lib.orc_col_checksum_f64(M, K, _d(Aw), _d(out))
+    return out
+
+
+def row_checksum(B, dtype):
+    """beta[k] = sum_j B[k,j]: the K x 1 weight checksum."""
+    lib = _load()
+    Bw = widen(B, dtype)
+    K, N = Bw.shape
+    if dtype == I8:
+        out = np.empty(K, dtype=np.int64)
+        lib.orc_row_checksum_i8(K, N, _p(Bw, ctypes.c_int8), _p(out, ctypes.c_int64))
+    else:
+        out = np.empty(K, dtype=np.float64)
+        lib.orc_row_checksum_f64(K, N, _d(Bw), _d(out))
+    return out
+
+
+def checksum_dot(alpha, beta):
+    lib = _load()
+    if alpha.dtype == np.int64:
+        return int(lib.orc_dot_i64(len(alpha), _p(alpha, ctypes.c_int64), _p(beta, ctypes.c_int64)))
+    return float(lib.orc_dot_f64(len(alpha), _d(alpha), _d(beta)))
+
+
+def block_sum(C, r0=0, r1=None, c0=0, c1=None):
+    """Sum of C[r0:r1, c0:c1] (the output summation; whole matrix by default)."""
+    lib = _load()
+    C = np.ascontiguousarray(C)
+    M, N = C.shape
+    r1 = M if r1 is None else r1
+    c1 = N if c1 is None else c1
+    if C.dtype == np.int64:
+        return int(lib.orc_block_sum_i64(N, _p(C, ctypes.c_int64), r0, r1, c0, c1))
+    return float(lib.orc_block_sum_f64(N, _d(C), r0, r1, c0, c1))
+
+
+def phi(A, B, dtype):
+    lib = _load()
+    Aw, Bw = widen(A, dtype).astype(np.float64), widen(B, dtype).astype(np.float64)
+    M, K = Aw.shape
+    N = Bw.shape[1]
+    return float(lib.orc_phi_f64(M, N, K, _d(np.ascontiguousarray(Aw)), _d(np.ascontiguousarray(Bw))))
+
+
+def s_abs(A, B, dtype):
+    lib = _load()
+    Aw, Bw = widen(A, dtype).astype(np.float64), widen(B, dtype).astype(np.float64)
+    M, K = Aw.shape
+    N = Bw.shape[1]
+    return float(lib.orc_sabs_f64(M, N, K, _d(np.ascontiguousarray(Aw)), _d(np.ascontiguousarray(Bw))))
+
+
+# --------------------------------------------------------------------------- #
+# tolerance and comparison (Sec. 2.4 step 4)
+# --------------------------------------------------------------------------- #
+def frob(C, r0=0, r1=None, c0=0, c1=None) -> float:
+    blk = np.asarray(C, dtype=np.float64)[r0:r1, c0:c1]
+    with np.errstate(over="ignore", invalid="ignore"):
+        return float(np.sqrt(np.sum(blk * blk)))
+
+
+def tolerance(K: int, frob_norm: float, dtype: str) -> float:
+    """tau = C_TOL * 2^-24 * sqrt(K) * ||C||_F for fp16/bf16 (fp32 accumulators); 0 for int8."""
+    if dtype == I8:
+        return 0.0
+    return C_TOL * U32 * math.sqrt(K) * frob_norm
+
+
+def rigorous_bound(M, N, K, sabs):
+    """|s_C - s_AB| <= gamma * S_abs can never be violated by rounding alone in binary32
+    accumulation (K adds per entry, ceil(log2(MN)) levels of summation, slack 4)."""
+    return (K + math.ceil(math.log2(max(M * N, 2))) + 4) * U32 * sabs
+
+
+def mismatch(lhs, rhs, tau) -> bool:
+    """True when the two checksums disagree.  Written so that NaN and infinities flag."""
+    if isinstance(lhs, (int, np.integer)) and isinstance(rhs, (int, np.integer)):
+        return int(lhs) != int(rhs)
+    if not (math.isfinite(lhs) and math.isfinite(rhs)):
+        return True
+    return not (abs(lhs - rhs) <= tau)
+
+
+@dataclass
+class Check:
+    lhs: float  # output summation (of C or of the tile)
+    rhs: float  # checksum product
+    tau: float
+    flag: bool
+
+    @property
+    def residual(self):
+        return self.lhs - self.rhs
+
+
+def global_check(A, B, C, dtype) -> Check:
+    """Global ABFT (Sec. 2.4): (1^T A)(B 1) against sum(C) for the C that is passed in."""
+    K = A.shape[1]
+    s_ab = checksum_dot(col_checksum(A, dtype), row_checksum(B, dtype))
+    s_c = block_sum(C)
+    tau = tolerance(K, frob(C), dtype)
+    return Check(s_c, s_ab, tau, mismatch(s_c, s_ab, tau))
+
+
+def tiles(M, N, tile_m, tile_n):
+    """The partition of C into register tiles (edge tiles clipped), row-major order."""
+    for r0 in range(0, M, tile_m):
+        for c0 in range(0, N, tile_n):
+            yield r0, min(r0 + tile_m, M), c0, min(c0 + tile_n, N)
+
+
+def tile_check(A, B, C, dtype, r0, r1, c0, c1, two_sided=False) -> Check:
+    """Thread-level ABFT for one tile (Sec. 5.2.2): one-sided by default."""
+    lib = _load()
+    Aw, Bw = widen(A, dtype), widen(B, dtype)
+    K, N = Bw.shape
+    C = np.ascontiguousarray(C)
+    if dtype == I8:
+        assert not two_sided
+        lhs, rhs = ctypes.c_int64(), ctypes.c_int64()
+        lib.orc_tile_one_sided_i8(N, K, _p(Aw, ctypes.c_int8), _p(Bw, ctypes.c_int8),
+                                  _p(C, ctypes.c_int64), r0, r1, c0, c1, ctypes.byref(lhs),
+                                  ctypes.byref(rhs))
+        return Check(lhs.value, rhs.value, 0.0, lhs.value != rhs.value)
+    lhs, rhs = ctypes.c_double(), ctypes.c_double()
+    fn = lib.orc_tile_two_sided_f64 if two_sided else lib.orc_tile_one_sided_f64
+    fn(N, K, _d(Aw), _d(Bw), _d(C), r0, r1, c0, c1, ctypes.byref(lhs), ctypes.byref(rhs))
+    tau = tolerance(K, frob(C, r0, r1, c0, c1), dtype)
+    return Check(lhs.value, rhs.value, tau, mismatch(lhs.value, rhs.value, tau))
+
+
+def thread_check(A, B, C, dtype, tile_m, tile_n, two_sided=False):
+    """All tile checks of a partition; the layer is flagged when any tile is."""
+    M, N = C.shape
+    checks = [tile_check(A, B, C, dtype, *t, two_sided=two_sided) for t in tiles(M, N, tile_m, tile_n)]
+    return any(c.flag for c in checks), checks
+
+
+# --------------------------------------------------------------------------- #
+# fault injection (fault model of Sec. 2.3)
+# --------------------------------------------------------------------------- #
+def flip_bit(value, bit: int, dtype: str):
+    """One flipped bit in the accumulator that holds ``value``: binary32 for the
+    floating-point paths, int32 for int8."""
+    lib = _load()
+    assert 0 <= bit < 32
+    if dtype == I8:
+        return int(lib.orc_flip_bit_i32(int(value), bit))
+    return float(lib.orc_flip_bit_f32(float(value), bit))
+
+
+def inject(A, B, C, dtype, row, col, bit, k_after=-1):
+    """Copy of C with one fault in element (row, col).
+
+    k_after < 0: the final accumulator value is flipped.  Otherwise the running
+    sum after the products k < k_after is flipped and the remaining products are
+    added to the corrupted value (the fault persists to the end of the loop).
+    """
+    Cf = np.array(C, copy=True)
+    K = A.shape[1]
+    if k_after < 0 or k_after >= K:
+        Cf[row, col] = flip_bit(C[row, col], bit, dtype)
+        return Cf
+    head = partial_dot(A, B, dtype, row, col, 0, k_after)
+    tail = partial_dot(A, B, dtype, row, col, k_after, K)
+    Cf[row, col] = flip_bit(head, bit, dtype) + tail
+    return Cf
+
+
+# --------------------------------------------------------------------------- #
+# arithmetic intensity, CMR, selector (Sec. 3.1 Eq. 1, Sec. 5.3)
+# --------------------------------------------------------------------------- #
+STORAGE_BYTES = {F16: (2, 2, 2), BF16: (2, 2, 2), I8: (1, 1, 4)}  # (A, B, C) bytes per element
+
+GLOBAL, THREAD = 1, 2
+
+
+def flops(M, N, K, pad_to=1):
+    return _load().orc_flops(M, N, K, pad_to)
+
+
+def bytes_moved(M, N, K, dtype=F16, pad_to=1):
+    sa, sb, sc = STORAGE_BYTES[dtype]
+    return _load().orc_bytes(M, N, K, sa, sb, sc, pad_to)
+
+
+def arithmetic_intensity(M, N, K, dtype=F16, pad_to=1):
+    sa, sb, sc = STORAGE_BYTES[dtype]
+    return _load().orc_arithmetic_intensity(M, N, K, sa, sb, sc, pad_to)
+
+
+def aggregate_intensity(layers, dtype=F16, pad_to=1):
+    """Sum of FLOPs over sum of bytes across the linear layers of a network (Sec. 3.2)."""
+    f = sum(flops(M, N, K, pad_to) for (M, N, K) in layers)
+    b = sum(bytes_moved(M, N, K, dtype, pad_to) for (M, N, K) in layers)
+    return f / b
+
+
+def cmr(peak_ops_per_s, bytes_per_s):
+    return _load().orc_cmr(peak_ops_per_s, bytes_per_s)
+
+
+def select(M, N, K, dtype, cmr_value, pad_to=1):
+    """GLOBAL when the layer is compute bound by Eq. 1, THREAD otherwise (Sec. 5.3)."""
+    return _load().orc_select(arithmetic_intensity(M, N, K, dtype, pad_to), cmr_value)
+
+
+# --------------------------------------------------------------------------- #
+# convolution as a matrix product (Sec. 2.1)
+# --------------------------------------------------------------------------- #
+def conv_out_hw(H, W, KH, KW, stride, pad):
+    return (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+
+
+def im2col(x, dtype, KH, KW, stride, pad):
+    """NHWC activations -> the (batch*OH*OW) x (KH*KW*Cin) matrix A, in fp64 (int8: int8)."""
+    lib = _load()
+    xw = widen(x, dtype)
+    n, H, W, Cin = xw.shape
+    OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
+    xd = np.ascontiguousarray(xw, dtype=np.float64)
+    out = np.empty((n * OH * OW, KH * KW * Cin), dtype=np.float64)
+    lib.orc_im2col_f64(n, H, W, Cin, KH, KW, stride, pad, _d(xd), _d(out))
+    if dtype == I8:
+        return out.astype(np.int8)
+    return out

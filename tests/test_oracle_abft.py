@@ -1,0 +1,222 @@
+"""Pins for the oracle's checksum schemes, fault injection and tolerance (CPU only)."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2104_09455_amd import workloads as wl
+
+SHAPES = [(8, 8, 8), (64, 64, 64), (33, 70, 129), (1, 5, 13), (16, 1, 256)]
+
+
+# ------------------------------------------------------------------ invariant
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_integer_invariant_is_exact(M, N, K):
+    """sum(C) == (1^T A)(B 1) exactly over the integers (Sec. 2.4)."""
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=M + N + K)
+    C = oracle.gemm(A, B, "i8")
+    alpha, beta = oracle.col_checksum(A, "i8"), oracle.row_checksum(B, "i8")
+    # checksums against numpy's own reductions
+    assert np.array_equal(alpha, A.astype(np.int64).sum(axis=0))
+    assert np.array_equal(beta, B.astype(np.int64).sum(axis=1))
+    assert alpha.shape == (K,) and beta.shape == (K,)
+    assert oracle.checksum_dot(alpha, beta) == oracle.block_sum(C) == int(C.sum())
+    chk = oracle.global_check(A, B, C, "i8")
+    assert chk.tau == 0.0 and not chk.flag and chk.residual == 0
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("M,N,K", SHAPES)
+def test_fp_invariant_within_rigorous_bound(M, N, K, dtype):
+    A, B = wl.gemm_operands(M, N, K, dtype, seed=1)
+    C = oracle.gemm(A, B, dtype)
+    chk = oracle.global_check(A, B, C, dtype)
+    # everything is fp64 here: the residual is far below even the fp32 bound
+    sabs = oracle.s_abs(A, B, dtype)
+    assert abs(chk.residual) <= (K + M * N) * 2.0 ** -52 * sabs
+    assert abs(chk.residual) <= oracle.rigorous_bound(M, N, K, sabs)
+    assert not chk.flag
+
+
+def test_a_dropped_row_or_column_breaks_the_invariant():
+    """The pins above would catch a checksum that skips a row/column or mixes up axes."""
+    A, B = wl.gemm_operands(7, 9, 11, "i8", seed=2)
+    C = oracle.gemm(A, B, "i8")
+    alpha, beta = oracle.col_checksum(A, "i8"), oracle.row_checksum(B, "i8")
+    assert oracle.checksum_dot(alpha, beta) == int(C.sum())
+    assert oracle.checksum_dot(oracle.col_checksum(A[:-1], "i8"), beta) != int(C.sum())
+    assert oracle.checksum_dot(alpha, oracle.row_checksum(B[:, :-1], "i8")) != int(C.sum())
+
+
+def test_phi_and_sabs_closed_forms():
+    # all-ones operands: Phi = sqrt(K * M * N), S_abs = K * M * N, sum(C) = K * M * N
+    M, N, K = 6, 10, 12
+    A = np.ones((M, K), dtype=np.float16)
+    B = np.ones((K, N), dtype=np.float16)
+    assert oracle.phi(A, B, "f16") == pytest.approx(math.sqrt(K * M * N))
+    assert oracle.s_abs(A, B, "f16") == K * M * N
+    C = oracle.gemm(A, B, "f16")
+    assert oracle.block_sum(C) == K * M * N
+    assert oracle.frob(C) == pytest.approx(K * math.sqrt(M * N))
+    assert oracle.tolerance(K, oracle.frob(C), "f16") == pytest.approx(
+        8 * 2.0 ** -24 * math.sqrt(K) * K * math.sqrt(M * N))
+    assert oracle.tolerance(K, 123.0, "i8") == 0.0
+
+
+# ----------------------------------------------------------------- tile scheme
+@pytest.mark.parametrize("tile", [(4, 4), (8, 16), (32, 32), (5, 3), (64, 64), (128, 16)])
+def test_tile_checks_telescope_to_the_global_identity(tile):
+    M, N, K = 40, 50, 24
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=3)
+    C = oracle.gemm(A, B, "i8")
+    flag, checks = oracle.thread_check(A, B, C, "i8", *tile)
+    assert not flag
+    assert len(checks) == math.ceil(M / tile[0]) * math.ceil(N / tile[1])
+    assert all(c.lhs == c.rhs for c in checks)
+    assert sum(c.lhs for c in checks) == int(C.sum())
+    g = oracle.global_check(A, B, C, "i8")
+    assert sum(c.rhs for c in checks) == g.rhs
+
+
+def test_tile_one_sided_matches_definition_by_numpy():
+    """rho_i = sum_k A[i,k] * (sum_{j in T} B[k,j]) written with numpy slices."""
+    M, N, K = 24, 40, 16
+    A, B = wl.gemm_operands(M, N, K, "f16", seed=4)
+    C = oracle.gemm(A, B, "f16")
+    Aw, Bw = A.astype(np.float64), B.astype(np.float64)
+    r0, r1, c0, c1 = 8, 24, 16, 33
+    chk = oracle.tile_check(A, B, C, "f16", r0, r1, c0, c1)
+    chi = Bw[:, c0:c1].sum(axis=1)
+    rho = Aw[r0:r1] @ chi
+    assert chk.rhs == pytest.approx(rho.sum(), rel=1e-13)
+    assert chk.lhs == pytest.approx(C[r0:r1, c0:c1].sum(), rel=1e-13)
+    two = oracle.tile_check(A, B, C, "f16", r0, r1, c0, c1, two_sided=True)
+    assert two.rhs == pytest.approx(chk.rhs, rel=1e-12)
+    assert two.rhs == pytest.approx(float(Aw[r0:r1].sum(axis=0) @ chi), rel=1e-13)
+    # a tile check must not see elements outside its tile
+    C2 = C.copy()
+    C2[0, 0] += 100.0
+    assert oracle.tile_check(A, B, C2, "f16", r0, r1, c0, c1).lhs == chk.lhs
+
+
+# ------------------------------------------------------------------- injection
+def test_flip_bit_semantics():
+    assert oracle.flip_bit(1.0, 31, "f16") == -1.0            # sign
+    assert oracle.flip_bit(1.0, 23, "f16") == 0.5             # lowest exponent bit of 1.0 (127 -> 126)
+    assert oracle.flip_bit(1.0, 22, "f16") == 1.5             # top mantissa bit
+    assert oracle.flip_bit(1.0, 0, "f16") == 1.0 + 2.0 ** -23
+    assert oracle.flip_bit(1.0, 30, "f16") == math.inf        # exponent 0x7f -> 0xff
+    assert math.isnan(oracle.flip_bit(1.5, 30, "f16"))
+    assert oracle.flip_bit(0, 0, "i8") == 1
+    assert oracle.flip_bit(0, 31, "i8") == -2 ** 31
+    assert oracle.flip_bit(-1, 31, "i8") == 2 ** 31 - 1
+    assert oracle.flip_bit(5, 2, "i8") == 1
+
+
+@pytest.mark.parametrize("M,N,K,tile", [(8, 8, 8, (4, 4)), (64, 64, 64, (32, 32))])
+def test_int8_every_single_bit_flip_is_detected(M, N, K, tile):
+    """Exhaustive: all 32 bits of every element of C (Sec. 2.3: one faulty value)."""
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=5)
+    C = oracle.gemm(A, B, "i8")
+    s_ab = oracle.global_check(A, B, C, "i8").rhs
+    s_c = int(C.sum())
+    tile_rhs = {t: oracle.tile_check(A, B, C, "i8", *t).rhs for t in oracle.tiles(M, N, *tile)}
+    step = 1 if M <= 8 else 7  # 64^3: every 7th element keeps the loop short
+    n = 0
+    for i in range(0, M, step):
+        for j in range(0, N, step):
+            for bit in range(32):
+                bad = oracle.flip_bit(C[i, j], bit, "i8")
+                delta = bad - int(C[i, j])
+                assert delta != 0
+                assert oracle.mismatch(s_c + delta, s_ab, 0.0)
+                t = (i // tile[0] * tile[0], min(i // tile[0] * tile[0] + tile[0], M),
+                     j // tile[1] * tile[1], min(j // tile[1] * tile[1] + tile[1], N))
+                assert oracle.mismatch(tile_rhs[t] + delta, tile_rhs[t], 0.0)
+                n += 1
+    assert n >= 32 * 64
+
+
+def test_incremental_evaluation_matches_full_recomputation():
+    """s_C' = s_C + delta (used by large campaigns) == recomputing the check on corrupted C."""
+    M, N, K = 48, 40, 96
+    for dtype in ("i8", "f16"):
+        A, B = wl.gemm_operands(M, N, K, dtype, seed=6)
+        C = oracle.gemm(A, B, dtype)
+        rng = np.random.default_rng(7)
+        for _ in range(40):
+            i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
+            k_after = int(rng.choice([-1, 32, 64]))
+            Cf = oracle.inject(A, B, C, dtype, i, j, bit, k_after)
+            full = oracle.global_check(A, B, Cf, dtype)
+            clean = oracle.global_check(A, B, C, dtype)
+            if dtype == "i8":
+                assert full.lhs == clean.lhs + (int(Cf[i, j]) - int(C[i, j]))
+                assert full.flag
+            elif math.isfinite(Cf[i, j]):
+                assert full.lhs == pytest.approx(clean.lhs + (Cf[i, j] - C[i, j]), rel=1e-12, abs=1e-9)
+            assert np.array_equal(np.delete(Cf.ravel(), i * N + j), np.delete(C.ravel(), i * N + j))
+
+
+def test_mid_loop_injection_persists_additively():
+    A, B = wl.gemm_operands(4, 4, 64, "i8", seed=8)
+    C = oracle.gemm(A, B, "i8")
+    head = oracle.partial_dot(A, B, "i8", 1, 2, 0, 16)
+    Cf = oracle.inject(A, B, C, "i8", 1, 2, 3, k_after=16)
+    assert Cf[1, 2] - C[1, 2] == oracle.flip_bit(head, 3, "i8") - head
+    assert abs(Cf[1, 2] - C[1, 2]) == 8
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_fp_flips_outside_the_dont_care_band(dtype):
+    """|delta| >= 2 tau must flag, |delta| <= tau/2 must not; NaN/Inf must flag."""
+    M, N, K = 64, 64, 64
+    A, B = wl.gemm_operands(M, N, K, dtype, seed=9)
+    C = oracle.gemm(A, B, dtype)
+    rng = np.random.default_rng(10)
+    seen = {"flag": 0, "quiet": 0, "nonfinite": 0}
+    for _ in range(300):
+        i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
+        Cf = oracle.inject(A, B, C, dtype, i, j, bit)
+        g = oracle.global_check(A, B, Cf, dtype)
+        t_flag, _ = oracle.thread_check(A, B, Cf, dtype, 32, 32)
+        if not math.isfinite(Cf[i, j]):
+            assert g.flag and t_flag
+            seen["nonfinite"] += 1
+            continue
+        delta = abs(Cf[i, j] - float(np.float32(C[i, j])))
+        if delta >= 2 * g.tau:
+            assert g.flag
+            seen["flag"] += 1
+        elif delta <= g.tau / 2:
+            assert not g.flag
+            seen["quiet"] += 1
+    assert min(seen.values()) > 0
+
+
+# --------------------------------------------------------------- clean campaigns
+@pytest.mark.parametrize("dist_a,dist_b", [("uniform_pm1", "uniform_pm1"), ("uniform_01", "weights"),
+                                           ("normal", "normal"), ("uniform_01", "uniform_01")])
+def test_no_false_alarm_on_fp32_accumulated_products(dist_a, dist_b):
+    """The tolerance must clear real binary32 accumulation noise.  numpy's float32 matmul
+    (a library SGEMM, binary32 accumulators) stands in for the accelerator here; 1000 seeds."""
+    M, N, K = 64, 64, 64
+    worst = 0.0
+    for seed in range(1000):
+        A, B = wl.gemm_operands(M, N, K, "f16", seed=seed, dist_a=dist_a, dist_b=dist_b)
+        C32 = np.matmul(A.astype(np.float32), B.astype(np.float32)).astype(np.float64)
+        g = oracle.global_check(A, B, C32, "f16")
+        assert not g.flag, (seed, g)
+        worst = max(worst, abs(g.residual) / g.tau)
+    assert worst < 0.5  # comfortable margin, not a near miss
+
+
+def test_no_false_alarm_tiles_fp32_accumulated_larger():
+    M, N, K = 256, 256, 1024
+    for seed in range(3):
+        A, B = wl.gemm_operands(M, N, K, "f16", seed=seed, dist_a="uniform_01", dist_b="weights")
+        C32 = np.matmul(A.astype(np.float32), B.astype(np.float32)).astype(np.float64)
+        flag, checks = oracle.thread_check(A, B, C32, "f16", 128, 128)
+        assert not flag
+        assert not oracle.global_check(A, B, C32, "f16").flag

@@ -1,0 +1,213 @@
+/*
+ * abft.h -- C ABI of the ABFT-protected matrix-multiplication library for MI355X (gfx950).
+ *
+ * The library computes C = A.B for the linear layers of neural-network inference
+ * (fully-connected layers and convolutions lowered to a matrix product) and checks
+ * the result with algorithm-based fault tolerance, following Kosaian & Rashmi,
+ * "Arithmetic-Intensity-Guided Fault Tolerance for Neural Network Inference on
+ * GPUs" (SC '21).  Notation is the paper's (Sec. 2.1): A is M x K (activations),
+ * B is K x N (weights, known before inference), C is M x N.
+ *
+ * General conventions
+ *  - Every matrix / vector pointer is a DEVICE pointer owned by the caller unless
+ *    the parameter says "host".  The library allocates device memory only inside a
+ *    plan (abft_plan_create), released by abft_plan_destroy.
+ *  - All work is enqueued asynchronously on the HIP stream passed as `stream`
+ *    (a hipStream_t cast to void*, NULL = the default stream).  Results, the fault
+ *    flag and the report are valid once that stream has been synchronised.
+ *  - Functions returning int return ABFT_OK (0) or a negative ABFT_E_* code.  They
+ *    never abort and never throw.  A detected fault is NOT an error return: C is
+ *    always written (the method detects, it does not correct; Sec. 2.3) and the
+ *    fault flag is raised.
+ *  - Leading dimensions are in elements.  Operands may have any alignment and any
+ *    leading dimension; 16-byte aligned pointers with K and the leading dimensions
+ *    multiples of 16 bytes take the fast vectorised path.
+ *  - Thread safety: calls on different streams with different workspaces, flags and
+ *    reports do not interfere.
+ */
+#ifndef ABFT_H
+#define ABFT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* ---- error codes -------------------------------------------------------- */
+#define ABFT_OK 0
+#define ABFT_E_NULL (-1)       /* a required pointer is NULL */
+#define ABFT_E_SHAPE (-2)      /* M, N or K <= 0, or a convolution geometry with no output */
+#define ABFT_E_LD (-3)         /* a leading dimension is smaller than the row length */
+#define ABFT_E_ENUM (-4)       /* unknown dtype / mode / layout value */
+#define ABFT_E_WORKSPACE (-5)  /* workspace missing, misaligned (256 B) or too small */
+#define ABFT_E_INJECT (-6)     /* fault descriptor out of range */
+#define ABFT_E_HIP (-7)        /* a HIP runtime call failed (launch, allocation) */
+#define ABFT_E_PLAN (-8)       /* bad plan handle or layer index */
+
+/* ---- enums --------------------------------------------------------------- */
+/* Protection scheme.  GLOBAL: one checksum comparison for the whole product
+ * (Sec. 2.4-2.5).  THREAD: the paper's one-sided thread-level scheme (Sec. 5.2.2),
+ * carried out per wavefront register tile.  AUTO: whatever abft_select returns
+ * (intensity-guided ABFT, Sec. 5.3). */
+typedef enum { ABFT_NONE = 0, ABFT_GLOBAL = 1, ABFT_THREAD = 2, ABFT_AUTO = 3 } abft_mode_t;
+
+/* Operand type.  F16 / BF16: A, B and C are fp16 / bf16, accumulation in fp32.
+ * I8: A and B are int8, C is int32, accumulation in int32 (exact). */
+typedef enum { ABFT_F16 = 0, ABFT_BF16 = 1, ABFT_I8 = 2 } abft_dtype_t;
+
+/* Storage order of the weight matrix B.
+ *  ABFT_B_NK: element B[k][n] is at B[n*ldb + k]  (each output channel's K weights
+ *             contiguous -- the order inference frameworks keep linear / NHWC conv
+ *             weights in; the fast path).
+ *  ABFT_B_KN: element B[k][n] is at B[k*ldb + n]  (row-major K x N). */
+typedef enum { ABFT_B_NK = 0, ABFT_B_KN = 1 } abft_blayout_t;
+
+/* ---- small structs -------------------------------------------------------- */
+/* Test hook for the fault model of Sec. 2.3 (one wrong value in C caused by
+ * processing logic): flip bit `bit` (0..31) of the fp32 / int32 accumulator of
+ * element (row, col).  k_after < 0: the finished accumulator is flipped just
+ * before the checksum epilogue.  k_after >= 0: the running accumulator is flipped
+ * once the products with k < k_after have been added (must be a positive multiple
+ * of the k_step reported by abft_tile_shape and < K); the corruption then stays
+ * until the end of the loop. */
+typedef struct {
+    int64_t row, col;
+    int32_t bit;
+    int32_t k_after;
+} abft_fault_t;
+
+/* Convolution geometry for the implicit-GEMM path.  Activations are NHWC
+ * (batch, H, W, Cin) dense; the lowered problem has M = batch*OH*OW,
+ * K = KH*KW*Cin with k = (kh*KW + kw)*Cin + c, and N = output channels. */
+typedef struct {
+    int32_t batch, H, W, Cin;
+    int32_t KH, KW, stride, pad;
+} abft_conv_t;
+
+/* What the checksum comparison saw; optional diagnostics written by the device.
+ *  GLOBAL: lhs = output summation sum(C), rhs = checksum dot product (1^T A)(B 1),
+ *          tau = tolerance used, worst_ratio = |lhs - rhs| / tau (0 if tau = 0 and equal,
+ *          +inf if tau = 0 and different), tiles = 1.
+ *  THREAD: lhs / rhs / tau are those of the tile with the largest ratio seen,
+ *          worst_ratio that ratio, tiles = number of tile comparisons made.
+ * Must be zero-filled by the caller before the call. */
+typedef struct {
+    double lhs, rhs, tau, worst_ratio;
+    uint64_t tiles;
+    uint64_t reserved[3];
+} abft_report_t;
+
+/* ---- the protected product ------------------------------------------------ */
+/*
+ * C = A.B with the checks of `mode` (Sec. 2.4 / 5.2.2 / 5.3).
+ *   A   : M x K row-major, lda >= K.
+ *   B   : K x N in the order `b_layout` says, ldb >= K (NK) or >= N (KN).
+ *   C   : M x N row-major, ldc >= N; fp16 / bf16 (rounded to nearest even from the
+ *         fp32 accumulators) or int32.
+ *   beta: optional weight checksum beta[k] = sum_n B[k][n] made earlier by
+ *         abft_weight_checksum (K doubles, or K int64 for I8).  Used by GLOBAL only;
+ *         NULL makes the call compute it into the workspace first.  THREAD never
+ *         reads it: it recomputes tile-local weight checksums in registers (Sec. 5.2.1).
+ *   workspace / workspace_bytes: scratch of at least abft_workspace_bytes(...) bytes,
+ *         256-byte aligned; may be NULL when that size is 0.
+ *   fault_flag: device uint32, OR-ed with 1 when a comparison fails.  The caller
+ *         zeroes it.  May be NULL only for ABFT_NONE.
+ *   report: optional device abft_report_t (zero-filled by the caller), else NULL.
+ *   inject: optional HOST pointer to a fault to plant (testing), else NULL.
+ */
+int abft_gemm(int M, int N, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
+              int b_layout, void *C, int64_t ldc, int dtype, int mode, const void *beta,
+              void *workspace, size_t workspace_bytes, uint32_t *fault_flag, abft_report_t *report,
+              const abft_fault_t *inject, void *stream);
+
+/* Same for a convolution executed as an implicit matrix product (Sec. 2.1): x is
+ * the NHWC activation tensor; B holds the filters as the K x N matrix described at
+ * abft_conv_t; C is (batch*OH*OW) x N row-major, i.e. the NHWC output. */
+int abft_conv(const abft_conv_t *conv /* host */, int N, const void *x, const void *B, int64_t ldb,
+              int b_layout, void *C, int64_t ldc, int dtype, int mode, const void *beta,
+              void *workspace, size_t workspace_bytes, uint32_t *fault_flag, abft_report_t *report,
+              const abft_fault_t *inject, void *stream);
+
+/* Bytes of workspace abft_gemm / abft_conv need for this problem (0 for NONE / THREAD). */
+size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
+
+/* Offline weight checksum (Sec. 2.5): beta[k] = sum_n B[k][n], k = 0..K-1, written as
+ * K doubles (F16 / BF16) or K int64 (I8) to `beta`. */
+int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, void *beta,
+                         void *stream);
+
+/* Activation checksum (Sec. 2.4 step 1): alpha[k] = sum_m A[m][k] as K doubles / int64.
+ * `conv` (host, may be NULL) makes A the lowered matrix of the NHWC tensor passed as A. */
+int abft_activation_checksum(int M, int K, const void *A, int64_t lda, const abft_conv_t *conv, int dtype,
+                             void *alpha, void *stream);
+
+/* ---- selector (Sec. 3.1 Eq. 1, Sec. 5.3) ---------------------------------- */
+/* FLOPs / bytes with FLOPs = 2MNK and bytes = sA*M*K + sB*K*N + sC*M*N for the
+ * storage sizes of `dtype` (2,2,2 for F16/BF16; 1,1,4 for I8); unpadded dimensions. */
+double abft_arithmetic_intensity(int M, int N, int K, int dtype);
+/* Compute-to-memory-bandwidth ratio used for `dtype`: dense MFMA peak over HBM
+ * bandwidth of MI355X (2516.6 TFLOP/s resp. 5033.2 TOP/s over 8 TB/s) unless
+ * overridden by abft_set_cmr. */
+double abft_cmr(int dtype);
+/* Override the ratio (e.g. with a measured one); value <= 0 restores the default. */
+void abft_set_cmr(int dtype, double value);
+/* ABFT_GLOBAL if the layer is compute bound by Eq. 1 (intensity > CMR, strictly),
+ * else ABFT_THREAD.  Negative error code on bad arguments. */
+int abft_select(int M, int N, int K, int dtype);
+
+/* Register-tile partition the THREAD scheme uses for this problem: C is cut into
+ * tile_m x tile_n tiles starting at (0,0) (edge tiles clipped), one comparison each.
+ * `aligned` is non-zero when every operand pointer and leading dimension (and K, or
+ * Cin for a convolution) is a multiple of 16 bytes, which makes the largest tile
+ * eligible.  k_step is the granularity of abft_fault_t.k_after.  Any of the outputs
+ * may be NULL. */
+int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int *tile_m, int *tile_n, int *k_step);
+
+/* Comparison tolerance (the paper states none; Sec. 2.4 step 4 says "compare"): a
+ * comparison passes when |lhs - rhs| <= coeff * ||C_S||_F, where C_S is the part of C
+ * the comparison covers (all of C for GLOBAL, one tile for THREAD) and ||.||_F is taken
+ * from the fp32 accumulators.  coeff = 8 * (2^-24 * sqrt(K) + u), with u = 0 for GLOBAL
+ * and u = 2^-22 (F16) / 2^-23 (BF16) for THREAD (precision of the in-register tile
+ * checksum).  Returns coeff; 0 for I8 (exact comparison). */
+double abft_tolerance_coeff(int K, int dtype, int mode);
+
+/* ---- plans: per-layer selection for a network (Sec. 5.3) ------------------- */
+typedef struct {
+    int32_t M, N, K;
+    int32_t dtype;           /* abft_dtype_t */
+    int32_t b_layout;        /* abft_blayout_t */
+    int32_t has_conv;        /* non-zero: `conv` describes the layer, M and K must match it */
+    abft_conv_t conv;
+    const void *B;           /* device weights; must stay valid for the life of the plan */
+    int64_t ldb;
+} abft_layer_t;
+
+typedef struct abft_plan abft_plan_t;
+
+/* Build a plan for `n_layers` layers (host array).  Per layer: picks the scheme
+ * (profile = 0: abft_select; profile = 1: times NONE / GLOBAL / THREAD on the device
+ * with scratch inputs and keeps the faster protected one, the paper's pre-deployment
+ * procedure), computes the offline weight checksum and allocates workspace. */
+int abft_plan_create(abft_plan_t **plan, const abft_layer_t *layers, int n_layers, int profile,
+                     void *stream);
+/* Run layer `layer` of the plan with its chosen scheme on input A (or NHWC x), output C. */
+int abft_plan_run(abft_plan_t *plan, int layer, const void *A, int64_t lda, void *C, int64_t ldc,
+                  uint32_t *fault_flag, void *stream);
+/* Scheme chosen for a layer (abft_mode_t) or a negative error. */
+int abft_plan_mode(const abft_plan_t *plan, int layer);
+/* Times measured at creation with profile = 1, in microseconds: out[0..2] = NONE, GLOBAL,
+ * THREAD (zeros when profile = 0). */
+int abft_plan_times(const abft_plan_t *plan, int layer, double *out3 /* host */);
+void abft_plan_destroy(abft_plan_t *plan);
+
+/* ---- misc ------------------------------------------------------------------ */
+const char *abft_strerror(int code);
+/* Library version, e.g. 100 = 1.0.0. */
+int abft_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* ABFT_H */

@@ -271,11 +271,21 @@ def frob(C, r0=0, r1=None, c0=0, c1=None) -> float:
         return float(np.sqrt(np.sum(blk * blk)))
 
 
-def tolerance(K: int, frob_norm: float, dtype: str) -> float:
-    """tau = C_TOL * 2^-24 * sqrt(K) * ||C||_F for fp16/bf16 (fp32 accumulators); 0 for int8."""
+# Precision of the tile checksum operand in the thread-level scheme: the checksum of
+# B_t is formed in binary32 and handed to the matrix unit as two fp16 pieces (22 bits)
+# or three bf16 pieces (24 bits), so it adds a relative 2^-22 / 2^-23 on top of the
+# accumulation noise.  The global scheme keeps its checksums in fp64 and adds nothing.
+U_CHI = {F16: 2.0 ** -22, BF16: 2.0 ** -23}
+
+
+def tolerance(K: int, frob_norm: float, dtype: str, scheme: int = 1) -> float:
+    """tau = C_TOL * (2^-24 * sqrt(K) + u_chi) * ||C_S||_F for fp16/bf16 (fp32 accumulators),
+    u_chi = 0 for the global scheme (scheme=1), U_CHI[dtype] for thread-level (scheme=2);
+    0 for int8 (exact comparison)."""
     if dtype == I8:
         return 0.0
-    return C_TOL * U32 * math.sqrt(K) * frob_norm
+    u_chi = U_CHI[dtype] if scheme == 2 else 0.0
+    return C_TOL * (U32 * math.sqrt(K) + u_chi) * frob_norm
 
 
 def rigorous_bound(M, N, K, sabs):
@@ -337,7 +347,7 @@ def tile_check(A, B, C, dtype, r0, r1, c0, c1, two_sided=False) -> Check:
     lhs, rhs = ctypes.c_double(), ctypes.c_double()
     fn = lib.orc_tile_two_sided_f64 if two_sided else lib.orc_tile_one_sided_f64
     fn(N, K, _d(Aw), _d(Bw), _d(C), r0, r1, c0, c1, ctypes.byref(lhs), ctypes.byref(rhs))
-    tau = tolerance(K, frob(C, r0, r1, c0, c1), dtype)
+    tau = tolerance(K, frob(C, r0, r1, c0, c1), dtype, scheme=2)
     return Check(lhs.value, rhs.value, tau, mismatch(lhs.value, rhs.value, tau))
 
 

@@ -1,0 +1,236 @@
+"""ctypes binding of libabft.so: the same entry points as include/abft.h.
+
+Argument marshalling only -- every step of the path runs in the library's HIP
+kernels.  Tensors are PyTorch device tensors (PyTorch is used for device memory
+and streams, nothing else); their ``data_ptr()`` goes straight through the C ABI.
+There is no fallback: if the library has not been built, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libabft.so")
+
+# enums of abft.h
+NONE, GLOBAL, THREAD, AUTO = 0, 1, 2, 3
+F16, BF16, I8 = 0, 1, 2
+B_NK, B_KN = 0, 1
+OK = 0
+
+MODE_NAMES = {NONE: "none", GLOBAL: "global", THREAD: "thread", AUTO: "auto"}
+DTYPE_NAMES = {F16: "f16", BF16: "bf16", I8: "i8"}
+
+
+class Fault(ctypes.Structure):
+    _fields_ = [("row", ctypes.c_int64), ("col", ctypes.c_int64), ("bit", ctypes.c_int32),
+                ("k_after", ctypes.c_int32)]
+
+
+class Conv(ctypes.Structure):
+    _fields_ = [("batch", ctypes.c_int32), ("H", ctypes.c_int32), ("W", ctypes.c_int32),
+                ("Cin", ctypes.c_int32), ("KH", ctypes.c_int32), ("KW", ctypes.c_int32),
+                ("stride", ctypes.c_int32), ("pad", ctypes.c_int32)]
+
+
+class Report(ctypes.Structure):
+    _fields_ = [("lhs", ctypes.c_double), ("rhs", ctypes.c_double), ("tau", ctypes.c_double),
+                ("worst_ratio", ctypes.c_double), ("tiles", ctypes.c_uint64),
+                ("reserved", ctypes.c_uint64 * 3)]
+
+
+class Layer(ctypes.Structure):
+    _fields_ = [("M", ctypes.c_int32), ("N", ctypes.c_int32), ("K", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("b_layout", ctypes.c_int32), ("has_conv", ctypes.c_int32),
+                ("conv", Conv), ("B", ctypes.c_void_p), ("ldb", ctypes.c_int64)]
+
+
+EXPORTS = [
+    "abft_gemm", "abft_conv", "abft_workspace_bytes", "abft_weight_checksum",
+    "abft_activation_checksum", "abft_arithmetic_intensity", "abft_cmr", "abft_set_cmr",
+    "abft_select", "abft_tile_shape", "abft_tolerance_coeff", "abft_plan_create", "abft_plan_run",
+    "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
+]
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Load libabft.so (once).  Raises if it was not built: there is no other path."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2104_09455_amd.build`")
+    L = ctypes.CDLL(LIB_PATH)
+    vp, ci, i64, sz, dbl = ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_size_t, ctypes.c_double
+    ip = ctypes.POINTER(ctypes.c_int)
+    L.abft_gemm.restype = ci
+    L.abft_gemm.argtypes = [ci, ci, ci, vp, i64, vp, i64, ci, vp, i64, ci, ci, vp, vp, sz, vp, vp,
+                            ctypes.POINTER(Fault), vp]
+    L.abft_conv.restype = ci
+    L.abft_conv.argtypes = [ctypes.POINTER(Conv), ci, vp, vp, i64, ci, vp, i64, ci, ci, vp, vp, sz, vp, vp,
+                            ctypes.POINTER(Fault), vp]
+    L.abft_workspace_bytes.restype = sz
+    L.abft_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    L.abft_weight_checksum.restype = ci
+    L.abft_weight_checksum.argtypes = [ci, ci, vp, i64, ci, ci, vp, vp]
+    L.abft_activation_checksum.restype = ci
+    L.abft_activation_checksum.argtypes = [ci, ci, vp, i64, ctypes.POINTER(Conv), ci, vp, vp]
+    L.abft_arithmetic_intensity.restype = dbl
+    L.abft_arithmetic_intensity.argtypes = [ci, ci, ci, ci]
+    L.abft_cmr.restype = dbl
+    L.abft_cmr.argtypes = [ci]
+    L.abft_set_cmr.restype = None
+    L.abft_set_cmr.argtypes = [ci, dbl]
+    L.abft_select.restype = ci
+    L.abft_select.argtypes = [ci, ci, ci, ci]
+    L.abft_tile_shape.restype = ci
+    L.abft_tile_shape.argtypes = [ci, ci, ci, ci, ci, ip, ip, ip]
+    L.abft_tolerance_coeff.restype = dbl
+    L.abft_tolerance_coeff.argtypes = [ci, ci, ci]
+    L.abft_plan_create.restype = ci
+    L.abft_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Layer), ci, ci, vp]
+    L.abft_plan_run.restype = ci
+    L.abft_plan_run.argtypes = [vp, ci, vp, i64, vp, i64, vp, vp]
+    L.abft_plan_mode.restype = ci
+    L.abft_plan_mode.argtypes = [vp, ci]
+    L.abft_plan_times.restype = ci
+    L.abft_plan_times.argtypes = [vp, ci, ctypes.POINTER(dbl)]
+    L.abft_plan_destroy.restype = None
+    L.abft_plan_destroy.argtypes = [vp]
+    L.abft_strerror.restype = ctypes.c_char_p
+    L.abft_strerror.argtypes = [ci]
+    L.abft_version.restype = ci
+    L.abft_version.argtypes = []
+    _lib = L
+    return L
+
+
+class AbftError(RuntimeError):
+    def __init__(self, code: int):
+        self.code = code
+        super().__init__(f"abft error {code}: {abft_strerror(code)}")
+
+
+def _check(rc: int) -> None:
+    if rc != OK:
+        raise AbftError(rc)
+
+
+def _ptr(t) -> Optional[int]:
+    """Device pointer of a torch tensor (or pass an int / None through)."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(stream) -> Optional[int]:
+    if stream is None:
+        import torch
+        return torch.cuda.current_stream().cuda_stream or None
+    if isinstance(stream, int):
+        return stream or None
+    return stream.cuda_stream or None
+
+
+# ---- thin wrappers, one per entry point ------------------------------------
+def abft_strerror(code: int) -> str:
+    return lib().abft_strerror(code).decode()
+
+
+def abft_version() -> int:
+    return lib().abft_version()
+
+
+def abft_arithmetic_intensity(M, N, K, dtype) -> float:
+    return lib().abft_arithmetic_intensity(M, N, K, dtype)
+
+
+def abft_cmr(dtype) -> float:
+    return lib().abft_cmr(dtype)
+
+
+def abft_set_cmr(dtype, value) -> None:
+    lib().abft_set_cmr(dtype, value)
+
+
+def abft_select(M, N, K, dtype) -> int:
+    rc = lib().abft_select(M, N, K, dtype)
+    if rc < 0:
+        raise AbftError(rc)
+    return rc
+
+
+def abft_tile_shape(M, N, K, dtype, aligned=True):
+    tm, tn, ks = ctypes.c_int(), ctypes.c_int(), ctypes.c_int()
+    _check(lib().abft_tile_shape(M, N, K, dtype, 1 if aligned else 0, ctypes.byref(tm), ctypes.byref(tn),
+                                 ctypes.byref(ks)))
+    return tm.value, tn.value, ks.value
+
+
+def abft_tolerance_coeff(K, dtype, mode) -> float:
+    return lib().abft_tolerance_coeff(K, dtype, mode)
+
+
+def abft_workspace_bytes(M, N, K, dtype, mode) -> int:
+    return lib().abft_workspace_bytes(M, N, K, dtype, mode)
+
+
+def abft_weight_checksum(K, N, B, ldb, b_layout, dtype, beta, stream=None) -> None:
+    _check(lib().abft_weight_checksum(K, N, _ptr(B), ldb, b_layout, dtype, _ptr(beta), _stream(stream)))
+
+
+def abft_activation_checksum(M, K, A, lda, dtype, alpha, conv: Optional[Conv] = None, stream=None) -> None:
+    cp = ctypes.byref(conv) if conv is not None else None
+    _check(lib().abft_activation_checksum(M, K, _ptr(A), lda, cp, dtype, _ptr(alpha), _stream(stream)))
+
+
+def abft_gemm(M, N, K, A, lda, B, ldb, b_layout, C, ldc, dtype, mode, beta=None, workspace=None,
+              workspace_bytes=0, fault_flag=None, report=None, inject: Optional[Fault] = None,
+              stream=None) -> None:
+    ip = ctypes.byref(inject) if inject is not None else None
+    _check(lib().abft_gemm(M, N, K, _ptr(A), lda, _ptr(B), ldb, b_layout, _ptr(C), ldc, dtype, mode,
+                           _ptr(beta), _ptr(workspace), workspace_bytes, _ptr(fault_flag), _ptr(report),
+                           ip, _stream(stream)))
+
+
+def abft_conv(conv: Conv, N, x, B, ldb, b_layout, C, ldc, dtype, mode, beta=None, workspace=None,
+              workspace_bytes=0, fault_flag=None, report=None, inject: Optional[Fault] = None,
+              stream=None) -> None:
+    ip = ctypes.byref(inject) if inject is not None else None
+    _check(lib().abft_conv(ctypes.byref(conv), N, _ptr(x), _ptr(B), ldb, b_layout, _ptr(C), ldc, dtype, mode,
+                           _ptr(beta), _ptr(workspace), workspace_bytes, _ptr(fault_flag), _ptr(report), ip,
+                           _stream(stream)))
+
+
+def abft_plan_create(layers, profile=False, stream=None) -> int:
+    arr = (Layer * len(layers))(*layers)
+    handle = ctypes.c_void_p()
+    _check(lib().abft_plan_create(ctypes.byref(handle), arr, len(layers), 1 if profile else 0, _stream(stream)))
+    return handle.value
+
+
+def abft_plan_run(plan, layer, A, lda, C, ldc, fault_flag, stream=None) -> None:
+    _check(lib().abft_plan_run(plan, layer, _ptr(A), lda, _ptr(C), ldc, _ptr(fault_flag), _stream(stream)))
+
+
+def abft_plan_mode(plan, layer) -> int:
+    rc = lib().abft_plan_mode(plan, layer)
+    if rc < 0:
+        raise AbftError(rc)
+    return rc
+
+
+def abft_plan_times(plan, layer):
+    out = (ctypes.c_double * 3)()
+    _check(lib().abft_plan_times(plan, layer, out))
+    return list(out)
+
+
+def abft_plan_destroy(plan) -> None:
+    lib().abft_plan_destroy(plan)

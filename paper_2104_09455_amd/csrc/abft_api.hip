@@ -1,0 +1,762 @@
+// C-ABI entry points of the ABFT GEMM library (see include/abft.h) and the small
+// kernels around the GEMM: weight checksum (offline, paper Sec. 2.5), activation
+// checksum fused with the checksum dot product (Sec. 2.4 steps 1-2) and the final
+// reduction + comparison (Sec. 2.4 steps 3-4, Sec. 2.5 step 5).
+#include <hip/hip_runtime.h>
+
+#include <cmath>
+#include <type_traits>
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "../../include/abft.h"
+#include "gemm_configs.h"
+
+using namespace abft;
+
+namespace {
+
+// ------------------------------------------------------------------------- //
+// constants of the method as built here
+// ------------------------------------------------------------------------- //
+// Tolerance: tau = C_TOL * (2^-24 * sqrt(K) + u_chi) * ||C_S||_F.  2^-24 is the unit
+// roundoff of the fp32 accumulators; an accumulator that takes K products carries a
+// random-walk error ~ 2^-24 sqrt(K) |C_ij| / 2.4 and the errors of the entries add in
+// quadrature under the output summation.  u_chi covers the tile checksum operand of the
+// thread-level scheme, which is exact to 22 (fp16: two pieces) / 24 (bf16: three
+// pieces) bits of the fp32 column sums.
+constexpr double C_TOL = 8.0;
+constexpr double U_ACC = 5.9604644775390625e-08;  // 2^-24
+constexpr double U_CHI_F16 = 2.384185791015625e-07;  // 2^-22
+constexpr double U_CHI_BF16 = 1.1920928955078125e-07;  // 2^-23
+
+// MI355X spec-sheet peaks (dense) and HBM3E bandwidth
+constexpr double PEAK_F16 = 2516.6e12, PEAK_I8 = 5033.2e12, HBM_BW = 8.0e12;
+double g_cmr_override[3] = {0.0, 0.0, 0.0};
+
+inline int esize(int dt) { return dt == ABFT_I8 ? 1 : 2; }
+inline int csize(int dt) { return dt == ABFT_I8 ? 4 : 2; }
+inline bool valid_dtype(int dt) { return dt == ABFT_F16 || dt == ABFT_BF16 || dt == ABFT_I8; }
+inline long long cdiv(long long a, long long b) { return (a + b - 1) / b; }
+inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+// ------------------------------------------------------------------------- //
+// tile configuration choice (host logic)
+// ------------------------------------------------------------------------- //
+int pick_cfg(int M, int N, int K, int dt, bool aligned16) {
+    (void)K;
+    (void)dt;
+    if (M <= 16) return CFG_T;
+    auto tiles = [&](int id) {
+        CfgInfo ci = cfg_info_host(id);
+        return cdiv(M, ci.bm) * cdiv(N, ci.bn);
+    };
+    // fill the 256 compute units before growing the tile
+    if (aligned16 && tiles(CFG_L) >= 224) return CFG_L;
+    if (tiles(CFG_M) >= 192) return CFG_M;
+    if (tiles(CFG_S) >= 1024) return CFG_M;
+    return CFG_S;
+}
+
+// ------------------------------------------------------------------------- //
+// auxiliary kernels
+// ------------------------------------------------------------------------- //
+struct PreArgs {
+    const char* A;
+    int M, K;
+    long long lda;
+    int vec;
+    int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
+    const void* beta;     // K doubles / int64, or null
+    void* alpha_out;      // K doubles / int64 (only with gridDim.y == 1), or null
+    void* partial_ab;     // one double / int64 per block, or null
+    int rows_per_slab;
+};
+
+// Activation checksum alpha[k] = sum_m A[m][k] over a slab of rows, multiplied by
+// beta[k] and summed over the block's k range.  Block = 32 chunk columns x 8 row lanes.
+template <int DT>
+__global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
+    constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
+    constexpr int EPC = 16 / ESIZE;
+    typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
+    __shared__ Wide red[8][32][EPC];
+
+    const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
+    const int k0 = (blockIdx.x * 32 + tx) * EPC;
+    const int row_begin = blockIdx.y * p.rows_per_slab;
+    const int row_end = min(p.M, row_begin + p.rows_per_slab);
+
+    // per-element filter tap for the implicit-GEMM view (k is fixed per thread)
+    int e_off[EPC], e_kh[EPC], e_kw[EPC];
+    if (p.conv) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+            int k = k0 + e;
+            int tap = k / p.Cin;
+            e_off[e] = k - tap * p.Cin;
+            e_kh[e] = tap / p.KW;
+            e_kw[e] = tap - e_kh[e] * p.KW;
+        }
+    }
+
+    Wide s[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) s[e] = 0;
+
+    for (int m0 = row_begin + ty; m0 < row_end; m0 += 64) {
+        // int8: up to eight rows are summed in int32 first (exact); fp16 / bf16 values are
+        // widened and added in fp64 one by one, so the checksum side carries no rounding
+        // that could show up in the comparison
+        typename std::conditional<DT == DT_I8, int, double>::type f[EPC];
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) f[e] = 0;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const int m = m0 + 8 * u;
+            if (m >= row_end || k0 >= p.K) continue;
+            i32x4 v = {0, 0, 0, 0};
+            if (!p.conv) {
+                const char* src = p.A + ((long long)m * p.lda + k0) * ESIZE;
+                v = p.vec ? ld16(src) : gather16<ESIZE>(src, ESIZE, p.K - k0);
+            } else {
+                int img = m / (p.OH * p.OW);
+                int rem = m - img * (p.OH * p.OW);
+                int oh = rem / p.OW, ow = rem - oh * p.OW;
+                int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
+                const char* base = p.A + (long long)img * p.H * p.W * p.Cin * ESIZE;
+                if (p.vec) {
+                    int ih = ih0 + e_kh[0], iw = iw0 + e_kw[0];
+                    if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
+                        v = ld16(base + (((long long)ih * p.W + iw) * p.Cin + e_off[0]) * ESIZE);
+                } else {
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) {
+                        int ih = ih0 + e_kh[e], iw = iw0 + e_kw[e];
+                        unsigned x = 0;
+                        if (k0 + e < p.K && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
+                            const char* src = base + (((long long)ih * p.W + iw) * p.Cin + e_off[e]) * ESIZE;
+                            x = ESIZE == 2 ? (unsigned)*reinterpret_cast<const unsigned short*>(src)
+                                           : (unsigned)*reinterpret_cast<const unsigned char*>(src);
+                        }
+                        if (ESIZE == 2) v[e >> 1] |= (int)(x << (16 * (e & 1)));
+                        else v[e >> 2] |= (int)(x << (8 * (e & 3)));
+                    }
+                }
+            }
+            if constexpr (DT == DT_F16) {
+                f16x8 h = bitcast<f16x8>(v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] += (double)(float)h[e];
+            } else if constexpr (DT == DT_BF16) {
+                bf16x8 h = bitcast<bf16x8>(v);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) f[e] += (double)(float)h[e];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) f[e] += (int)(signed char)(v[e >> 2] >> (8 * (e & 3)));
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) s[e] += (Wide)f[e];
+    }
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) red[ty][tx][e] = s[e];
+    __syncthreads();
+    Wide dot = 0;
+    if (ty == 0) {
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+            Wide a = 0;
+            for (int y = 0; y < 8; ++y) a += red[y][tx][e];
+            const int k = k0 + e;
+            if (k < p.K) {
+                if (p.alpha_out) reinterpret_cast<Wide*>(p.alpha_out)[k] = a;
+                if (p.beta) dot += a * reinterpret_cast<const Wide*>(p.beta)[k];
+            }
+        }
+    }
+    if (tid < 64 && p.partial_ab) {
+        dot = wave_sum(dot);
+        if (tid == 0) reinterpret_cast<Wide*>(p.partial_ab)[blockIdx.y * gridDim.x + blockIdx.x] = dot;
+    }
+}
+
+// Weight checksum beta[k] = sum_n B[k][n] for any storage order (element strides).
+// Block = 32 values of k x 8 lanes over n.  Offline step: not tuned.
+template <int DT>
+__global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int K, int N, long long sn,
+                                                              long long sk, void* beta) {
+    constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
+    typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
+    __shared__ Wide red[8][32];
+    const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
+    const int k = blockIdx.x * 32 + tx;
+    Wide s = 0;
+    if (k < K) {
+        for (int n = ty; n < N; n += 8) {
+            const char* src = B + ((long long)n * sn + (long long)k * sk) * ESIZE;
+            if constexpr (DT == DT_F16) s += (double)(float)*reinterpret_cast<const _Float16*>(src);
+            else if constexpr (DT == DT_BF16) s += (double)(float)*reinterpret_cast<const __bf16*>(src);
+            else s += (long long)*reinterpret_cast<const signed char*>(src);
+        }
+    }
+    red[ty][tx] = s;
+    __syncthreads();
+    if (ty == 0 && k < K) {
+        Wide a = 0;
+        for (int y = 0; y < 8; ++y) a += red[y][tx];
+        reinterpret_cast<Wide*>(beta)[k] = a;
+    }
+}
+
+// Final reduction and comparison of the global scheme: one workgroup.
+template <bool IS_INT>
+__global__ __launch_bounds__(256) void compare_kernel(const void* partials_c, int n_c, const void* partials_ab,
+                                                      int n_ab, double tol_coeff, unsigned int* flag,
+                                                      Report* report) {
+    typedef typename std::conditional<IS_INT, long long, double>::type Wide;
+    __shared__ Wide red[3][4];
+    const Wide* pc = reinterpret_cast<const Wide*>(partials_c);
+    const Wide* pab = reinterpret_cast<const Wide*>(partials_ab);
+    Wide sc = 0, f2 = 0, sab = 0;
+    for (int i = threadIdx.x; i < n_c; i += 256) {
+        sc += pc[2 * i];
+        f2 += pc[2 * i + 1];
+    }
+    for (int i = threadIdx.x; i < n_ab; i += 256) sab += pab[i];
+    sc = wave_sum(sc);
+    f2 = wave_sum(f2);
+    sab = wave_sum(sab);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        red[0][wave] = sc;
+        red[1][wave] = f2;
+        red[2][wave] = sab;
+    }
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        sc = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        f2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+        sab = (red[2][0] + red[2][1]) + (red[2][2] + red[2][3]);
+        bool bad;
+        double tau = 0.0, ratio;
+        if constexpr (IS_INT) {
+            bad = sc != sab;
+            ratio = bad ? __builtin_huge_val() : 0.0;
+        } else {
+            tau = tol_coeff * __builtin_sqrt(f2);
+            double res = __builtin_fabs(sc - sab);
+            bool finite = __builtin_isfinite(sc) && __builtin_isfinite(sab) && __builtin_isfinite(f2);
+            bad = !finite || !(res <= tau);
+            ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+        }
+        if (bad) atomicOr(flag, 1u);
+        if (report) {
+            report->lhs = (double)sc;
+            report->rhs = (double)sab;
+            report->tau = tau;
+            report->worst_ratio = ratio;
+            report->tiles = 1;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------- //
+// host helpers
+// ------------------------------------------------------------------------- //
+struct Problem {
+    int M, N, K, dtype, b_layout;
+    const void* A;
+    long long lda;
+    const void* B;
+    long long ldb;
+    void* C;
+    long long ldc;
+    bool conv;
+    abft_conv_t cg;
+    int OH, OW;
+};
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+bool a_vectorisable(const Problem& pr) {
+    const int es = esize(pr.dtype);
+    if (!aligned16(pr.A)) return false;
+    if (pr.conv) return (pr.cg.Cin * es) % 16 == 0;
+    return (pr.K * es) % 16 == 0 && (pr.lda * es) % 16 == 0;
+}
+bool b_vectorisable(const Problem& pr) {
+    const int es = esize(pr.dtype);
+    return pr.b_layout == ABFT_B_NK && aligned16(pr.B) && (pr.K * es) % 16 == 0 && (pr.ldb * es) % 16 == 0;
+}
+
+int conv_out(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
+
+struct WsLayout {
+    size_t off_pc, off_pab, off_beta, total;
+    int n_pc_max, n_pab;
+};
+
+int pre_grid_x(int K, int dt) { return (int)cdiv(K, 32 * (16 / esize(dt))); }
+constexpr int PRE_ROWS_PER_SLAB = 256;
+
+WsLayout ws_layout(int M, int N, int K, int dt) {
+    WsLayout w;
+    long long n_pc = 0;
+    for (int id = 0; id < CFG_COUNT; ++id) {
+        CfgInfo ci = cfg_info_host(id);
+        long long t = cdiv(M, ci.bm) * cdiv(N, ci.bn);
+        if (t > n_pc) n_pc = t;
+    }
+    w.n_pc_max = (int)n_pc;
+    w.n_pab = pre_grid_x(K, dt) * (int)cdiv(M, PRE_ROWS_PER_SLAB);
+    w.off_pc = 0;
+    w.off_pab = align_up(w.off_pc + (size_t)n_pc * 16, 256);
+    w.off_beta = align_up(w.off_pab + (size_t)w.n_pab * 8, 256);
+    w.total = align_up(w.off_beta + (size_t)K * 8, 256);
+    return w;
+}
+
+double tol_coeff(int K, int dt, int mode) {
+    if (dt == ABFT_I8) return 0.0;
+    double u_chi = 0.0;
+    if (mode == ABFT_THREAD) u_chi = dt == ABFT_F16 ? U_CHI_F16 : U_CHI_BF16;
+    return C_TOL * (U_ACC * std::sqrt((double)K) + u_chi);
+}
+
+double cmr_of(int dt) {
+    if (g_cmr_override[dt] > 0.0) return g_cmr_override[dt];
+    return (dt == ABFT_I8 ? PEAK_I8 : PEAK_F16) / HBM_BW;
+}
+
+double intensity(int M, int N, int K, int dt) {
+    const double sa = esize(dt), sb = esize(dt), sc = csize(dt);
+    const double m = M, n = N, k = K;
+    return 2.0 * m * n * k / (sa * m * k + sb * k * n + sc * m * n);
+}
+
+int select_mode(int M, int N, int K, int dt) {
+    return intensity(M, N, K, dt) > cmr_of(dt) ? ABFT_GLOBAL : ABFT_THREAD;
+}
+
+hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, int layout, int dt, void* beta,
+                                  hipStream_t st) {
+    long long sn = layout == ABFT_B_NK ? ldb : 1, sk = layout == ABFT_B_NK ? 1 : ldb;
+    dim3 grid((unsigned)cdiv(K, 32)), block(256);
+    const char* b = reinterpret_cast<const char*>(B);
+    if (dt == ABFT_F16) hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, beta);
+    else if (dt == ABFT_BF16) hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, beta);
+    else hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, beta);
+    return hipGetLastError();
+}
+
+hipError_t launch_act_checksum(const Problem& pr, const void* beta, void* alpha_out, void* partial_ab,
+                               int rows_per_slab, hipStream_t st) {
+    PreArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.A = reinterpret_cast<const char*>(pr.A);
+    a.M = pr.M;
+    a.K = pr.K;
+    a.lda = pr.lda;
+    a.vec = a_vectorisable(pr) ? 1 : 0;
+    a.conv = pr.conv ? 1 : 0;
+    if (pr.conv) {
+        a.H = pr.cg.H; a.W = pr.cg.W; a.Cin = pr.cg.Cin; a.KH = pr.cg.KH; a.KW = pr.cg.KW;
+        a.stride = pr.cg.stride; a.pad = pr.cg.pad; a.OH = pr.OH; a.OW = pr.OW;
+    }
+    a.beta = beta;
+    a.alpha_out = alpha_out;
+    a.partial_ab = partial_ab;
+    a.rows_per_slab = rows_per_slab;
+    dim3 grid((unsigned)pre_grid_x(pr.K, pr.dtype), (unsigned)cdiv(pr.M, rows_per_slab)), block(256);
+    if (pr.dtype == ABFT_F16) hipLaunchKernelGGL(act_checksum_kernel<DT_F16>, grid, block, 0, st, a);
+    else if (pr.dtype == ABFT_BF16) hipLaunchKernelGGL(act_checksum_kernel<DT_BF16>, grid, block, 0, st, a);
+    else hipLaunchKernelGGL(act_checksum_kernel<DT_I8>, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
+int validate_common(const Problem& pr, int mode, const uint32_t* flag) {
+    if (!valid_dtype(pr.dtype)) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_AUTO) return ABFT_E_ENUM;
+    if (pr.b_layout != ABFT_B_NK && pr.b_layout != ABFT_B_KN) return ABFT_E_ENUM;
+    if (pr.M <= 0 || pr.N <= 0 || pr.K <= 0) return ABFT_E_SHAPE;
+    if (!pr.A || !pr.B || !pr.C) return ABFT_E_NULL;
+    if (mode != ABFT_NONE && !flag) return ABFT_E_NULL;
+    if (!pr.conv && pr.lda < pr.K) return ABFT_E_LD;
+    if (pr.b_layout == ABFT_B_NK ? pr.ldb < pr.K : pr.ldb < pr.N) return ABFT_E_LD;
+    if (pr.ldc < pr.N) return ABFT_E_LD;
+    return ABFT_OK;
+}
+
+int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, size_t ws_bytes, uint32_t* flag,
+                abft_report_t* report, const abft_fault_t* inject, hipStream_t st) {
+    int rc = validate_common(pr, mode, flag);
+    if (rc != ABFT_OK) return rc;
+    if (mode == ABFT_AUTO) mode = select_mode(pr.M, pr.N, pr.K, pr.dtype);
+
+    const bool avec = a_vectorisable(pr), bvec = b_vectorisable(pr);
+    const bool all16 = avec && bvec;
+    const int cfg = pick_cfg(pr.M, pr.N, pr.K, pr.dtype, all16);
+    const CfgInfo ci = cfg_info_host(cfg);
+    const int bk = ci.bk_bytes / esize(pr.dtype);
+
+    GemmArgs g;
+    std::memset(&g, 0, sizeof g);
+    g.A = reinterpret_cast<const char*>(pr.A);
+    g.B = reinterpret_cast<const char*>(pr.B);
+    g.C = reinterpret_cast<char*>(pr.C);
+    g.M = pr.M; g.N = pr.N; g.K = pr.K;
+    g.lda = pr.lda; g.ldb = pr.ldb; g.ldc = pr.ldc;
+    g.b_sn = pr.b_layout == ABFT_B_NK ? pr.ldb : 1;
+    g.b_sk = pr.b_layout == ABFT_B_NK ? 1 : pr.ldb;
+    g.a_vec = avec; g.b_vec = bvec;
+    g.conv = pr.conv ? 1 : 0;
+    if (pr.conv) {
+        g.H = pr.cg.H; g.W = pr.cg.W; g.Cin = pr.cg.Cin; g.KH = pr.cg.KH; g.KW = pr.cg.KW;
+        g.stride = pr.cg.stride; g.pad = pr.cg.pad; g.OH = pr.OH; g.OW = pr.OW;
+    }
+    g.tiles_m = (int)cdiv(pr.M, ci.bm);
+    g.tiles_n = (int)cdiv(pr.N, ci.bn);
+    g.flag = flag;
+    g.report = reinterpret_cast<Report*>(report);
+    g.tol_coeff = tol_coeff(pr.K, pr.dtype, mode);
+    g.f_row = g.f_col = -1; g.f_bit = 0; g.f_kt = -1;
+
+    bool inj = false;
+    if (inject) {
+        if (pr.conv) return ABFT_E_INJECT;
+        if (inject->row < 0 || inject->row >= pr.M || inject->col < 0 || inject->col >= pr.N) return ABFT_E_INJECT;
+        if (inject->bit < 0 || inject->bit > 31) return ABFT_E_INJECT;
+        if (inject->k_after >= 0) {
+            if (inject->k_after == 0 || inject->k_after % bk != 0 || inject->k_after >= pr.K) return ABFT_E_INJECT;
+            g.f_kt = inject->k_after / bk - 1;
+        }
+        g.f_row = (int)inject->row; g.f_col = (int)inject->col; g.f_bit = inject->bit;
+        inj = true;
+    }
+
+    WsLayout w;
+    char* ws = reinterpret_cast<char*>(workspace);
+    const void* beta_used = beta;
+    if (mode == ABFT_GLOBAL) {
+        w = ws_layout(pr.M, pr.N, pr.K, pr.dtype);
+        if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.total) return ABFT_E_WORKSPACE;
+        g.partials = reinterpret_cast<double*>(ws + w.off_pc);
+        if (!beta_used) {
+            if (launch_weight_checksum(pr.K, pr.N, pr.B, pr.ldb, pr.b_layout, pr.dtype, ws + w.off_beta, st) != hipSuccess)
+                return ABFT_E_HIP;
+            beta_used = ws + w.off_beta;
+        }
+        // steps 1-2: activation checksum and its dot product with the weight checksum
+        if (launch_act_checksum(pr, beta_used, nullptr, ws + w.off_pab, PRE_ROWS_PER_SLAB, st) != hipSuccess)
+            return ABFT_E_HIP;
+    }
+
+    hipError_t e;
+    if (pr.dtype == ABFT_F16) e = launch_gemm_f16(cfg, mode, inj, g, st);
+    else if (pr.dtype == ABFT_BF16) e = launch_gemm_bf16(cfg, mode, inj, g, st);
+    else e = launch_gemm_i8(cfg, mode, inj, g, st);
+    if (e != hipSuccess) return ABFT_E_HIP;
+
+    if (mode == ABFT_GLOBAL) {
+        const int n_c = g.tiles_m * g.tiles_n;
+        if (pr.dtype == ABFT_I8)
+            hipLaunchKernelGGL(compare_kernel<true>, dim3(1), dim3(256), 0, st, (const void*)g.partials, n_c,
+                               (const void*)(ws + w.off_pab), w.n_pab, 0.0, flag, reinterpret_cast<Report*>(report));
+        else
+            hipLaunchKernelGGL(compare_kernel<false>, dim3(1), dim3(256), 0, st, (const void*)g.partials, n_c,
+                               (const void*)(ws + w.off_pab), w.n_pab, g.tol_coeff, flag,
+                               reinterpret_cast<Report*>(report));
+        if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
+    }
+    return ABFT_OK;
+}
+
+int conv_problem(const abft_conv_t* conv, int N, Problem& pr) {
+    if (!conv) return ABFT_E_NULL;
+    if (conv->batch <= 0 || conv->H <= 0 || conv->W <= 0 || conv->Cin <= 0 || conv->KH <= 0 || conv->KW <= 0 ||
+        conv->stride <= 0 || conv->pad < 0)
+        return ABFT_E_SHAPE;
+    if (conv->H + 2 * conv->pad < conv->KH || conv->W + 2 * conv->pad < conv->KW) return ABFT_E_SHAPE;
+    pr.conv = true;
+    pr.cg = *conv;
+    pr.OH = conv_out(conv->H, conv->KH, conv->stride, conv->pad);
+    pr.OW = conv_out(conv->W, conv->KW, conv->stride, conv->pad);
+    long long M = (long long)conv->batch * pr.OH * pr.OW;
+    long long K = (long long)conv->KH * conv->KW * conv->Cin;
+    if (M <= 0 || M > 0x7fffffffLL || K > 0x7fffffffLL) return ABFT_E_SHAPE;
+    pr.M = (int)M;
+    pr.K = (int)K;
+    pr.N = N;
+    pr.lda = pr.K;
+    return ABFT_OK;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------- //
+// plans
+// ------------------------------------------------------------------------- //
+struct abft_plan {
+    struct Layer {
+        abft_layer_t desc;
+        int mode;
+        void* beta;
+        void* workspace;
+        size_t ws_bytes;
+        double t_us[3];
+    };
+    std::vector<Layer> layers;
+};
+
+// ------------------------------------------------------------------------- //
+// exported functions
+// ------------------------------------------------------------------------- //
+extern "C" {
+
+int abft_gemm(int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb, int b_layout, void* C,
+              int64_t ldc, int dtype, int mode, const void* beta, void* workspace, size_t workspace_bytes,
+              uint32_t* fault_flag, abft_report_t* report, const abft_fault_t* inject, void* stream) {
+    Problem pr;
+    std::memset(&pr, 0, sizeof pr);
+    pr.M = M; pr.N = N; pr.K = K; pr.dtype = dtype; pr.b_layout = b_layout;
+    pr.A = A; pr.lda = lda; pr.B = B; pr.ldb = ldb; pr.C = C; pr.ldc = ldc;
+    pr.conv = false;
+    return run_problem(pr, mode, beta, workspace, workspace_bytes, fault_flag, report, inject,
+                       reinterpret_cast<hipStream_t>(stream));
+}
+
+int abft_conv(const abft_conv_t* conv, int N, const void* x, const void* B, int64_t ldb, int b_layout, void* C,
+              int64_t ldc, int dtype, int mode, const void* beta, void* workspace, size_t workspace_bytes,
+              uint32_t* fault_flag, abft_report_t* report, const abft_fault_t* inject, void* stream) {
+    Problem pr;
+    std::memset(&pr, 0, sizeof pr);
+    if (N <= 0) return ABFT_E_SHAPE;
+    int rc = conv_problem(conv, N, pr);
+    if (rc != ABFT_OK) return rc;
+    pr.dtype = dtype; pr.b_layout = b_layout;
+    pr.A = x; pr.B = B; pr.ldb = ldb; pr.C = C; pr.ldc = ldc;
+    return run_problem(pr, mode, beta, workspace, workspace_bytes, fault_flag, report, inject,
+                       reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode) {
+    if (M <= 0 || N <= 0 || K <= 0 || !valid_dtype(dtype)) return 0;
+    if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
+    if (mode != ABFT_GLOBAL) return 0;
+    return ws_layout(M, N, K, dtype).total;
+}
+
+int abft_weight_checksum(int K, int N, const void* B, int64_t ldb, int b_layout, int dtype, void* beta,
+                         void* stream) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (b_layout != ABFT_B_NK && b_layout != ABFT_B_KN) return ABFT_E_ENUM;
+    if (K <= 0 || N <= 0) return ABFT_E_SHAPE;
+    if (!B || !beta) return ABFT_E_NULL;
+    if (b_layout == ABFT_B_NK ? ldb < K : ldb < N) return ABFT_E_LD;
+    return launch_weight_checksum(K, N, B, ldb, b_layout, dtype, beta, reinterpret_cast<hipStream_t>(stream)) ==
+                   hipSuccess
+               ? ABFT_OK
+               : ABFT_E_HIP;
+}
+
+int abft_activation_checksum(int M, int K, const void* A, int64_t lda, const abft_conv_t* conv, int dtype,
+                             void* alpha, void* stream) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (!A || !alpha) return ABFT_E_NULL;
+    Problem pr;
+    std::memset(&pr, 0, sizeof pr);
+    pr.dtype = dtype;
+    if (conv) {
+        int rc = conv_problem(conv, 1, pr);
+        if (rc != ABFT_OK) return rc;
+        if (pr.M != M || pr.K != K) return ABFT_E_SHAPE;
+    } else {
+        if (M <= 0 || K <= 0) return ABFT_E_SHAPE;
+        if (lda < K) return ABFT_E_LD;
+        pr.M = M; pr.K = K; pr.lda = lda;
+    }
+    pr.A = A;
+    // one slab covering every row, so that each block owns its alpha entries outright
+    return launch_act_checksum(pr, nullptr, alpha, nullptr, M, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+               ? ABFT_OK
+               : ABFT_E_HIP;
+}
+
+double abft_arithmetic_intensity(int M, int N, int K, int dtype) {
+    if (M <= 0 || N <= 0 || K <= 0 || !valid_dtype(dtype)) return 0.0;
+    return intensity(M, N, K, dtype);
+}
+
+double abft_cmr(int dtype) { return valid_dtype(dtype) ? cmr_of(dtype) : 0.0; }
+
+void abft_set_cmr(int dtype, double value) {
+    if (valid_dtype(dtype)) g_cmr_override[dtype] = value > 0.0 ? value : 0.0;
+}
+
+int abft_select(int M, int N, int K, int dtype) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
+    return select_mode(M, N, K, dtype);
+}
+
+int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int* tile_m, int* tile_n, int* k_step) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
+    CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0));
+    if (tile_m) *tile_m = ci.wm;
+    if (tile_n) *tile_n = ci.wn;
+    if (k_step) *k_step = ci.bk_bytes / esize(dtype);
+    return ABFT_OK;
+}
+
+double abft_tolerance_coeff(int K, int dtype, int mode) {
+    if (!valid_dtype(dtype) || K <= 0) return 0.0;
+    return tol_coeff(K, dtype, mode);
+}
+
+int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layers, int profile, void* stream) {
+    if (!plan || !layers) return ABFT_E_NULL;
+    if (n_layers <= 0) return ABFT_E_SHAPE;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    abft_plan* p = new (std::nothrow) abft_plan;
+    if (!p) return ABFT_E_HIP;
+    int rc = ABFT_OK;
+    for (int i = 0; i < n_layers && rc == ABFT_OK; ++i) {
+        abft_plan::Layer L;
+        std::memset(&L, 0, sizeof L);
+        L.desc = layers[i];
+        const abft_layer_t& d = L.desc;
+        if (!valid_dtype(d.dtype)) { rc = ABFT_E_ENUM; break; }
+        if (d.b_layout != ABFT_B_NK && d.b_layout != ABFT_B_KN) { rc = ABFT_E_ENUM; break; }
+        if (d.M <= 0 || d.N <= 0 || d.K <= 0) { rc = ABFT_E_SHAPE; break; }
+        if (!d.B) { rc = ABFT_E_NULL; break; }
+        if (d.has_conv) {
+            Problem pr;
+            std::memset(&pr, 0, sizeof pr);
+            rc = conv_problem(&d.conv, d.N, pr);
+            if (rc != ABFT_OK) break;
+            if (pr.M != d.M || pr.K != d.K) { rc = ABFT_E_SHAPE; break; }
+        }
+        L.mode = select_mode(d.M, d.N, d.K, d.dtype);
+        // offline weight checksum and workspace for the global scheme (kept for either
+        // choice so that profiling can time both)
+        L.ws_bytes = ws_layout(d.M, d.N, d.K, d.dtype).total;
+        if (hipMalloc(&L.beta, (size_t)d.K * 8) != hipSuccess) { rc = ABFT_E_HIP; break; }
+        if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { hipFree(L.beta); rc = ABFT_E_HIP; break; }
+        p->layers.push_back(L);
+        if (launch_weight_checksum(d.K, d.N, d.B, d.ldb, d.b_layout, d.dtype, L.beta, st) != hipSuccess) {
+            rc = ABFT_E_HIP;
+            break;
+        }
+    }
+    if (rc == ABFT_OK && profile) {
+        // pre-deployment profiling (Sec. 5.3): time each scheme on scratch inputs, keep the faster
+        hipEvent_t e0, e1;
+        uint32_t* d_flag = nullptr;
+        if (hipEventCreate(&e0) != hipSuccess || hipEventCreate(&e1) != hipSuccess ||
+            hipMalloc(&d_flag, 4) != hipSuccess)
+            rc = ABFT_E_HIP;
+        for (size_t i = 0; i < p->layers.size() && rc == ABFT_OK; ++i) {
+            abft_plan::Layer& L = p->layers[i];
+            const abft_layer_t& d = L.desc;
+            size_t a_elems = d.has_conv ? (size_t)d.conv.batch * d.conv.H * d.conv.W * d.conv.Cin
+                                        : (size_t)d.M * d.K;
+            void *A = nullptr, *C = nullptr;
+            if (hipMalloc(&A, a_elems * esize(d.dtype)) != hipSuccess) { rc = ABFT_E_HIP; break; }
+            if (hipMalloc(&C, (size_t)d.M * d.N * csize(d.dtype)) != hipSuccess) { hipFree(A); rc = ABFT_E_HIP; break; }
+            hipMemsetAsync(A, 0, a_elems * esize(d.dtype), st);
+            hipMemsetAsync(d_flag, 0, 4, st);
+            const int modes[3] = {ABFT_NONE, ABFT_GLOBAL, ABFT_THREAD};
+            for (int mi = 0; mi < 3 && rc == ABFT_OK; ++mi) {
+                const int reps = 20;
+                for (int r = -3; r < reps && rc == ABFT_OK; ++r) {
+                    if (r == 0) hipEventRecord(e0, st);
+                    int saved = L.mode;
+                    L.mode = modes[mi];
+                    rc = abft_plan_run(p, (int)i, A, d.K, C, d.N, d_flag, stream);
+                    L.mode = saved;
+                }
+                hipEventRecord(e1, st);
+                if (hipEventSynchronize(e1) != hipSuccess) rc = ABFT_E_HIP;
+                float ms = 0.f;
+                hipEventElapsedTime(&ms, e0, e1);
+                L.t_us[mi] = 1000.0 * ms / reps;
+            }
+            if (rc == ABFT_OK) L.mode = L.t_us[1] <= L.t_us[2] ? ABFT_GLOBAL : ABFT_THREAD;
+            hipFree(A);
+            hipFree(C);
+        }
+        if (d_flag) hipFree(d_flag);
+        hipEventDestroy(e0);
+        hipEventDestroy(e1);
+    }
+    if (rc != ABFT_OK) {
+        abft_plan_destroy(p);
+        return rc;
+    }
+    *plan = p;
+    return ABFT_OK;
+}
+
+int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void* C, int64_t ldc,
+                  uint32_t* fault_flag, void* stream) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    abft_plan::Layer& L = plan->layers[layer];
+    const abft_layer_t& d = L.desc;
+    Problem pr;
+    std::memset(&pr, 0, sizeof pr);
+    if (d.has_conv) {
+        int rc = conv_problem(&d.conv, d.N, pr);
+        if (rc != ABFT_OK) return rc;
+    } else {
+        pr.M = d.M; pr.N = d.N; pr.K = d.K; pr.lda = lda;
+    }
+    pr.dtype = d.dtype; pr.b_layout = d.b_layout;
+    pr.A = A; pr.B = d.B; pr.ldb = d.ldb; pr.C = C; pr.ldc = ldc;
+    return run_problem(pr, L.mode, L.beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
+                       reinterpret_cast<hipStream_t>(stream));
+}
+
+int abft_plan_mode(const abft_plan_t* plan, int layer) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    return plan->layers[layer].mode;
+}
+
+int abft_plan_times(const abft_plan_t* plan, int layer, double* out3) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    if (!out3) return ABFT_E_NULL;
+    for (int i = 0; i < 3; ++i) out3[i] = plan->layers[layer].t_us[i];
+    return ABFT_OK;
+}
+
+void abft_plan_destroy(abft_plan_t* plan) {
+    if (!plan) return;
+    for (auto& L : plan->layers) {
+        if (L.beta) hipFree(L.beta);
+        if (L.workspace) hipFree(L.workspace);
+    }
+    delete plan;
+}
+
+const char* abft_strerror(int code) {
+    switch (code) {
+        case ABFT_OK: return "ok";
+        case ABFT_E_NULL: return "a required pointer is NULL";
+        case ABFT_E_SHAPE: return "bad problem shape";
+        case ABFT_E_LD: return "leading dimension smaller than the row length";
+        case ABFT_E_ENUM: return "unknown dtype, mode or layout";
+        case ABFT_E_WORKSPACE: return "workspace missing, misaligned or too small";
+        case ABFT_E_INJECT: return "fault descriptor out of range";
+        case ABFT_E_HIP: return "HIP runtime call failed";
+        case ABFT_E_PLAN: return "bad plan handle or layer index";
+    }
+    return "unknown error code";
+}
+
+int abft_version(void) { return 100; }
+
+}  // extern "C"

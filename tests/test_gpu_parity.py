@@ -1,0 +1,184 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Bit-exact for int8 -> int32; |dC| <= 1e-2|C| + 1e-2 rms(C) for fp16/bf16."""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2104_09455_amd import binding as B
+from paper_2104_09455_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+MODES = [B.NONE, B.GLOBAL, B.THREAD]
+# (M, N, K): one tile; several tiles with ragged edges; skinny; degenerate; unaligned K
+SHAPES = [(64, 64, 64), (200, 136, 264), (130, 70, 333), (1, 64, 13), (16, 1, 256), (1, 1, 1),
+          (300, 520, 1024), (17, 260, 72), (512, 512, 128)]
+
+
+def _oracle_flag(A, Bm, C, dtype, mode, M, N, K, aligned=True):
+    dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
+    if mode == B.GLOBAL:
+        return oracle.global_check(A, Bm, C, dtype)
+    tm, tn, _ = B.abft_tile_shape(M, N, K, dt, aligned)
+    flag, checks = oracle.thread_check(A, Bm, C, dtype, tm, tn)
+    return flag, checks
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("shape", SHAPES)
+def test_clean_parity(shape, mode, dtype):
+    from gpu_util import run_gemm, c_close, normwise_error
+    M, N, K = shape
+    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=100 + M + N + K)
+    print(f"case shape={shape} mode={mode} dtype={dtype}", flush=True)
+    res = run_gemm(A, Bm, dtype, mode)
+    C_ref = oracle.gemm(A, Bm, dtype)
+    assert c_close(res.C, C_ref, dtype), normwise_error(res.C, C_ref)
+    if dtype != "i8":
+        assert normwise_error(res.C, C_ref) < (2.0 ** -10 if dtype == "f16" else 2.0 ** -7)
+    assert res.flag == 0
+    if mode == B.GLOBAL:
+        chk = oracle.global_check(A, Bm, C_ref, dtype)
+        assert res.report.tiles == 1
+        if dtype == "i8":
+            assert res.report.lhs == chk.lhs and res.report.rhs == chk.rhs and res.report.worst_ratio == 0.0
+        else:
+            # checksum side is carried in fp64 on the device
+            assert res.report.rhs == pytest.approx(chk.rhs, rel=1e-11, abs=1e-9)
+            assert abs(res.report.lhs - chk.lhs) <= chk.tau + 1e-300
+            assert res.report.tau == pytest.approx(chk.tau, rel=1e-3)
+            assert res.report.worst_ratio < 0.5
+    if mode == B.THREAD:
+        dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
+        tm, tn, _ = B.abft_tile_shape(M, N, K, dt, K * (1 if dtype == "i8" else 2) % 16 == 0)
+        import math
+        # one comparison per wave tile of the launched grid (tiles past the edge included)
+        assert res.report.tiles >= math.ceil(M / tm) * math.ceil(N / tn)
+        assert res.report.worst_ratio < 0.5
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+@pytest.mark.parametrize("mode", MODES)
+def test_layouts_strides_and_misalignment(mode, dtype):
+    """Row-major K x N weights, padded leading dimensions and operands that are not
+    16-byte aligned all go through the generic loader and must give the same C."""
+    from gpu_util import run_gemm, c_close
+    M, N, K = 96, 80, 136
+    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=7)
+    C_ref = oracle.gemm(A, Bm, dtype)
+    for kw in (dict(layout=B.B_KN), dict(lda_pad=8, ldb_pad=16, ldc_pad=3), dict(lda_pad=1),
+               dict(misalign=1), dict(layout=B.B_KN, ldb_pad=5, misalign=3), dict(use_beta=True)):
+        print(f"case mode={mode} dtype={dtype} {kw}", flush=True)
+        res = run_gemm(A, Bm, dtype, mode, **kw)
+        assert c_close(res.C, C_ref, dtype), kw
+        assert res.flag == 0, kw
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_checksum_vectors(dtype):
+    """alpha = 1^T A and beta = B 1 as the device computes them (Sec. 2.4 step 1)."""
+    import torch
+    from gpu_util import to_dev, DEV
+    dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
+    for (M, N, K) in [(64, 64, 64), (700, 33, 264), (5, 9, 13)]:
+        A, Bm = wl.gemm_operands(M, N, K, dtype, seed=3)
+        a_ref, b_ref = oracle.col_checksum(A, dtype), oracle.row_checksum(Bm, dtype)
+        wide = torch.int64 if dtype == "i8" else torch.float64
+        dA = to_dev(A, dtype)
+        alpha = torch.zeros(K, dtype=wide, device=DEV)
+        B.abft_activation_checksum(M, K, dA, K, dt, alpha)
+        for layout, host in ((B.B_NK, np.ascontiguousarray(Bm.T)), (B.B_KN, Bm)):
+            dB = to_dev(host, dtype)
+            beta = torch.zeros(K, dtype=wide, device=DEV)
+            B.abft_weight_checksum(K, N, dB, host.shape[1], layout, dt, beta)
+            torch.cuda.synchronize()
+            if dtype == "i8":
+                assert np.array_equal(beta.cpu().numpy(), b_ref)
+            else:
+                assert np.allclose(beta.cpu().numpy(), b_ref, rtol=1e-12, atol=1e-12)
+        if dtype == "i8":
+            assert np.array_equal(alpha.cpu().numpy(), a_ref)
+        else:
+            assert np.allclose(alpha.cpu().numpy(), a_ref, rtol=1e-12, atol=1e-12)
+
+
+@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD])
+@pytest.mark.parametrize("shape", [(64, 64, 64), (200, 136, 256)])
+def test_int8_injected_faults_always_flagged(shape, mode):
+    """Every single-bit flip of an int32 accumulator changes the sum exactly: 100 % detection."""
+    from gpu_util import run_gemm
+    M, N, K = shape
+    A, Bm = wl.gemm_operands(M, N, K, "i8", seed=21)
+    C_ref = oracle.gemm(A, Bm, "i8")
+    _, _, ks = B.abft_tile_shape(M, N, K, B.I8)
+    rng = np.random.default_rng(22)
+    for t in range(40):
+        i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
+        k_after = -1 if (t % 2 == 0 or K <= ks) else ks * int(rng.integers(1, K // ks))
+        if k_after >= K:
+            k_after = -1
+        print(f"case shape={shape} mode={mode} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        res = run_gemm(A, Bm, "i8", mode, inject=B.Fault(i, j, bit, k_after))
+        C_bad = oracle.inject(A, Bm, C_ref, "i8", i, j, bit, k_after)
+        want = ((C_bad + 2 ** 31) % 2 ** 32) - 2 ** 31  # the int32 register wraps
+        assert np.array_equal(res.C, want)
+        assert res.flag == 1
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD])
+def test_fp_injected_faults_match_oracle_outside_band(mode, dtype):
+    """|delta| >= 2 tau must be flagged, |delta| <= tau/2 must not (don't-care in between);
+    non-finite results must be flagged."""
+    import math
+    from gpu_util import run_gemm
+    M, N, K = 64, 64, 64
+    dt = B.F16 if dtype == "f16" else B.BF16
+    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=31)
+    C_ref = oracle.gemm(A, Bm, dtype)
+    tm, tn, ks = B.abft_tile_shape(M, N, K, dt)
+    rng = np.random.default_rng(32)
+    counts = {"must": 0, "mustnot": 0, "band": 0}
+    for t in range(60):
+        i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
+        print(f"case mode={mode} dtype={dtype} fault=({i},{j},bit {bit})", flush=True)
+        res = run_gemm(A, Bm, dtype, mode, inject=B.Fault(i, j, bit, -1))
+        C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit)
+        if mode == B.GLOBAL:
+            chk = oracle.global_check(A, Bm, C_bad, dtype)
+        else:
+            r0, c0 = i // tm * tm, j // tn * tn
+            chk = oracle.tile_check(A, Bm, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
+        if not math.isfinite(C_bad[i, j]):
+            assert res.flag == 1
+            counts["must"] += 1
+            continue
+        delta = abs(chk.residual)
+        if delta >= 2 * chk.tau:
+            assert res.flag == 1, (i, j, bit, delta, chk.tau)
+            counts["must"] += 1
+        elif delta <= chk.tau / 2:
+            assert res.flag == 0, (i, j, bit, delta, chk.tau)
+            counts["mustnot"] += 1
+        else:
+            counts["band"] += 1
+    assert counts["must"] > 5 and counts["mustnot"] > 5
+
+
+def test_results_are_deterministic():
+    from gpu_util import run_gemm
+    A, Bm = wl.gemm_operands(300, 520, 1024, "f16", seed=41)
+    first = run_gemm(A, Bm, "f16", B.GLOBAL)
+    for _ in range(5):
+        again = run_gemm(A, Bm, "f16", B.GLOBAL)
+        assert np.array_equal(first.C, again.C)
+        assert first.report.lhs == again.report.lhs and first.report.rhs == again.report.rhs
+
+
+def test_auto_mode_follows_selector():
+    from gpu_util import run_gemm, c_close
+    A, Bm = wl.gemm_operands(64, 64, 64, "f16", seed=42)
+    res = run_gemm(A, Bm, "f16", B.AUTO)
+    assert res.flag == 0 and res.report.tiles >= 4  # 64^3 is bandwidth bound -> thread-level tiles
+    assert c_close(res.C, oracle.gemm(A, Bm, "f16"), "f16")

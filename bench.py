@@ -1,0 +1,372 @@
+#!/usr/bin/env python3
+"""Benchmark of the ABFT-protected GEMM path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dlrm|resnet50|square] [--no-extras]
+
+A step is one pass of the whole protected path over one batch of synthetic input:
+every linear layer of the workload runs through ``abft_gemm`` / ``abft_conv`` with the
+scheme the intensity-guided selector picks for it (activation checksum, matrix
+product with fused checksum epilogue, comparison).  Inputs are resident in HBM before
+the timed region.  One JSON line is printed: whole-pass protected TFLOP/s, the ABFT
+overhead against the same kernels run unprotected, the roofline figure of the dominant
+kernel (HIP events around that kernel inside the timed region) and the CPU oracle
+timed on a bounded sample.  Short extra legs report the other benchmark configurations.
+"""
+from __future__ import annotations
+
+import argparse
+import ctypes
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+import torch  # noqa: E402
+
+from paper_2104_09455_amd import binding as B  # noqa: E402
+from paper_2104_09455_amd import workloads as wl  # noqa: E402
+
+PEAK = {"f16": 2516.6e12, "bf16": 2516.6e12, "i8": 5033.2e12}  # dense MFMA, op/s
+HBM = 8.0e12
+DT = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}
+TORCH_IN = {"f16": torch.float16, "bf16": torch.bfloat16, "i8": torch.int8}
+TORCH_OUT = {"f16": torch.float16, "bf16": torch.bfloat16, "i8": torch.int32}
+ESIZE = {"f16": 2, "bf16": 2, "i8": 1}
+CSIZE = {"f16": 2, "bf16": 2, "i8": 4}
+
+
+# --------------------------------------------------------------------------- #
+# HIP events straight from the runtime (torch events only see torch's own stream)
+# --------------------------------------------------------------------------- #
+class Hip:
+    def __init__(self):
+        self.rt = ctypes.CDLL("libamdhip64.so")
+        self.rt.hipEventCreate.argtypes = [ctypes.POINTER(ctypes.c_void_p)]
+        self.rt.hipEventRecord.argtypes = [ctypes.c_void_p, ctypes.c_void_p]
+        self.rt.hipEventSynchronize.argtypes = [ctypes.c_void_p]
+        self.rt.hipEventElapsedTime.argtypes = [ctypes.POINTER(ctypes.c_float), ctypes.c_void_p, ctypes.c_void_p]
+        self.rt.hipEventDestroy.argtypes = [ctypes.c_void_p]
+
+    def event(self):
+        e = ctypes.c_void_p()
+        assert self.rt.hipEventCreate(ctypes.byref(e)) == 0
+        return e.value
+
+    def record(self, e, stream):
+        assert self.rt.hipEventRecord(e, stream) == 0
+
+    def elapsed_ms(self, e0, e1):
+        assert self.rt.hipEventSynchronize(e1) == 0
+        ms = ctypes.c_float()
+        assert self.rt.hipEventElapsedTime(ctypes.byref(ms), e0, e1) == 0
+        return ms.value
+
+    def destroy(self, e):
+        self.rt.hipEventDestroy(e)
+
+
+# --------------------------------------------------------------------------- #
+# one protected layer with its device buffers
+# --------------------------------------------------------------------------- #
+class LayerRun:
+    def __init__(self, layer: wl.Layer, dtype: str, gen: torch.Generator, dist_a="uniform_01", dist_b="weights"):
+        self.layer, self.dtype = layer, dtype
+        self.dt = DT[dtype]
+        M, N, K = layer.M, layer.N, layer.K
+        dev = "cuda:0"
+        a_shape = (layer.conv.batch, layer.conv.H, layer.conv.W, layer.conv.Cin) if layer.conv else (M, K)
+        if dtype == "i8":
+            self.A = torch.randint(-128, 128, a_shape, generator=gen, device=dev, dtype=torch.int32).to(torch.int8)
+            self.B = torch.randint(-128, 128, (N, K), generator=gen, device=dev, dtype=torch.int32).to(torch.int8)
+        else:
+            a = torch.rand(a_shape, generator=gen, device=dev) if dist_a == "uniform_01" else (
+                torch.randn(a_shape, generator=gen, device=dev) if dist_a == "normal" else
+                torch.rand(a_shape, generator=gen, device=dev) * 2 - 1)
+            b = torch.randn((N, K), generator=gen, device=dev)
+            if dist_b == "weights":
+                b = b * 0.02
+            self.A, self.B = a.to(TORCH_IN[dtype]), b.to(TORCH_IN[dtype])  # B stored N x K (ABFT_B_NK)
+        self.C = torch.zeros((M, N), dtype=TORCH_OUT[dtype], device=dev)
+        self.flag = torch.zeros(1, dtype=torch.int32, device=dev)
+        es = ESIZE[dtype]
+        aligned = ((layer.conv.Cin if layer.conv else K) * es) % 16 == 0 and (K * es) % 16 == 0
+        _, rn = B.abft_region_shape(M, N, K, self.dt, aligned)
+        self.beta = torch.zeros(-(-N // rn) * K, dtype=torch.float64, device=dev)  # int64 for i8: same size
+        B.abft_weight_checksum(K, N, self.B, K, B.B_NK, self.dt, self.beta, block_n=rn)  # offline step (Sec. 2.5)
+        self.wsb = B.abft_workspace_bytes(M, N, K, self.dt, B.GLOBAL)
+        self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=dev)
+        self.pick = B.abft_select(M, N, K, self.dt)
+        self.conv = None
+        if layer.conv:
+            c = layer.conv
+            self.conv = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad)
+        self.flops = 2.0 * M * N * K
+        self.bytes = ESIZE[dtype] * (M * K + K * N) + CSIZE[dtype] * M * N
+        self.ai = self.flops / self.bytes
+
+    def run(self, mode, stream=None):
+        L = self.layer
+        if self.conv is not None:
+            B.abft_conv(self.conv, L.N, self.A, self.B, L.K, B.B_NK, self.C, L.N, self.dt, mode, beta=self.beta,
+                        workspace=self.ws, workspace_bytes=self.wsb, fault_flag=self.flag, stream=stream)
+        else:
+            B.abft_gemm(L.M, L.N, L.K, self.A, L.K, self.B, L.K, B.B_NK, self.C, L.N, self.dt, mode,
+                        beta=self.beta, workspace=self.ws, workspace_bytes=self.wsb, fault_flag=self.flag,
+                        stream=stream)
+
+
+def time_mode(hip: Hip, lr: LayerRun, mode: int, reps: int, warm: int, stream) -> float:
+    """Mean microseconds of one call (all kernels of the scheme), HIP events on `stream`."""
+    for _ in range(warm):
+        lr.run(mode, stream)
+    e0, e1 = hip.event(), hip.event()
+    hip.record(e0, stream)
+    for _ in range(reps):
+        lr.run(mode, stream)
+    hip.record(e1, stream)
+    us = 1000.0 * hip.elapsed_ms(e0, e1) / reps
+    hip.destroy(e0)
+    hip.destroy(e1)
+    return us
+
+
+def layer_table(hip, runs, reps, warm, stream, modes=(B.NONE, B.GLOBAL, B.THREAD)):
+    rows = []
+    for lr in runs:
+        t = {m: time_mode(hip, lr, m, reps, warm, stream) for m in modes}
+        pick_t = t[lr.pick]
+        roof = min(PEAK[lr.dtype], lr.ai * HBM)
+        rows.append({
+            "layer": lr.layer.name, "M": lr.layer.M, "N": lr.layer.N, "K": lr.layer.K,
+            "ai": round(lr.ai, 1), "pick": B.MODE_NAMES[lr.pick],
+            "us_none": round(t[B.NONE], 2), "us_global": round(t[B.GLOBAL], 2), "us_thread": round(t[B.THREAD], 2),
+            "ovh_global_pct": round(100 * (t[B.GLOBAL] / t[B.NONE] - 1), 2),
+            "ovh_thread_pct": round(100 * (t[B.THREAD] / t[B.NONE] - 1), 2),
+            "ovh_pick_pct": round(100 * (pick_t / t[B.NONE] - 1), 2),
+            "tflops_pick": round(lr.flops / pick_t / 1e6, 2),
+            "roofline_frac_pick": round(lr.flops / (pick_t * 1e-6) / roof, 4),
+        })
+    return rows
+
+
+def summarize(rows):
+    tn = sum(r["us_none"] for r in rows)
+    tg = sum(r["us_global"] for r in rows)
+    tt = sum(r["us_thread"] for r in rows)
+    tp = sum(r["us_global"] if r["pick"] == "global" else r["us_thread"] for r in rows)
+    best = sum(min(r["us_global"], r["us_thread"]) for r in rows)
+    fl = sum(2.0 * r["M"] * r["N"] * r["K"] for r in rows)
+    return {"layers": len(rows), "us_none": round(tn, 1), "ovh_global_pct": round(100 * (tg / tn - 1), 2),
+            "ovh_thread_pct": round(100 * (tt / tn - 1), 2), "ovh_selector_pct": round(100 * (tp / tn - 1), 2),
+            "ovh_profiled_best_pct": round(100 * (best / tn - 1), 2),
+            "tflops_selector": round(fl / tp / 1e6, 2)}
+
+
+# --------------------------------------------------------------------------- #
+# CPU baseline: the oracle, as it stands, on a bounded sample of the workload
+# --------------------------------------------------------------------------- #
+def cpu_baseline(runs, budget_s=15.0):
+    import oracle
+    from oracle import build as obuild
+    if not os.path.exists(os.path.join(ROOT, "oracle", "libabft_oracle.so")):
+        obuild.build()
+    t_used, flops, desc = 0.0, 0.0, []
+    for lr in runs:
+        L = lr.layer
+        if t_used >= budget_s:
+            break
+        # bound the work per layer: the first rows of A that keep M*N*K <= 4e9 multiply-adds
+        m_s = int(max(1, min(L.M, 4e9 // (L.N * L.K))))
+        A = lr.A
+        if lr.conv is not None:
+            c = L.conv
+            imgs = max(1, min(c.batch, math.ceil(m_s / (c.OH * c.OW))))
+            x = A[:imgs].cpu()
+            xs = x.view(torch.int16).numpy().view(np.float16 if lr.dtype == "f16" else np.uint16) if lr.dtype != "i8" else x.numpy()
+            t0 = time.perf_counter()
+            Aw = oracle.im2col(xs, lr.dtype, c.KH, c.KW, c.stride, c.pad)
+            m_s = Aw.shape[0]
+        else:
+            a = A[:m_s].cpu()
+            Aw = a.view(torch.int16).numpy().view(np.float16 if lr.dtype == "f16" else np.uint16) if lr.dtype != "i8" else a.numpy()
+            t0 = time.perf_counter()
+        b = lr.B.cpu()
+        Bw = b.view(torch.int16).numpy().view(np.float16 if lr.dtype == "f16" else np.uint16) if lr.dtype != "i8" else b.numpy()
+        Bw = np.ascontiguousarray(Bw.T)  # K x N, the oracle's orientation
+        Cw = oracle.gemm(Aw, Bw, lr.dtype)
+        if lr.pick == B.GLOBAL:
+            oracle.global_check(Aw, Bw, Cw, lr.dtype)
+        else:
+            tm, tn, _ = B.abft_tile_shape(L.M, L.N, L.K, lr.dt, True)
+            oracle.thread_check(Aw, Bw, Cw, lr.dtype, tm, tn)
+        t_used += time.perf_counter() - t0
+        flops += 2.0 * m_s * L.N * L.K
+        desc.append(f"{L.name}:{m_s}/{L.M} rows")
+    return {"value": round(flops / t_used / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(),
+            "kind": "oracle", "seconds": round(t_used, 2),
+            "sample": "fp64 triple-loop GEMM + the selected checksum scheme on " + ", ".join(desc[:12]) +
+                      (" ..." if len(desc) > 12 else "")}
+
+
+# --------------------------------------------------------------------------- #
+def build_workload(name, gen):
+    if name == "dlrm":
+        return "configs[1]: DLRM MLPs (bottom 13-512-256-64, top 512-1024-1024-512-256-1), fp16, batch 256", \
+            [LayerRun(l, "f16", gen) for l in wl.dlrm_layers(256)], "f16"
+    if name == "resnet50":
+        return "configs[2]: ResNet-50 53 conv layers as implicit GEMM, fp16, 224x224, batch 64", \
+            [LayerRun(l, "f16", gen) for l in wl.resnet50_layers(64)], "f16"
+    if name == "square":
+        return "configs[3]: square GEMM M=N=K=8192, fp16 N(0,1)", \
+            [LayerRun(wl.Layer("sq8192", 8192, 8192, 8192), "f16", gen, "normal", "normal")], "f16"
+    raise SystemExit(f"unknown workload {name}")
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None)
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--workload", default="dlrm", choices=["dlrm", "resnet50", "square"])
+    ap.add_argument("--no-extras", action="store_true", help="skip the short legs for the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    B.lib()  # fails loudly if libabft.so was not built
+    torch.cuda.set_device(0)
+    hip = Hip()
+    gen = torch.Generator(device="cuda:0")
+    gen.manual_seed(20210409)
+    stream = torch.cuda.current_stream().cuda_stream or None
+
+    label, runs, dtype = build_workload(args.workload, gen)
+    defaults = {"dlrm": (1000, 100), "resnet50": (20, 3), "square": (20, 3)}[args.workload]
+    steps = args.steps if args.steps is not None else defaults[0]
+    warmup = args.warmup if args.warmup is not None else defaults[1]
+
+    # ---- per-layer table (also warms everything up and finds the dominant kernel)
+    reps = 50 if args.workload == "dlrm" else 10
+    rows = layer_table(hip, runs, reps, 3, stream)
+    dom_i = max(range(len(runs)), key=lambda i: rows[i]["us_global" if runs[i].pick == B.GLOBAL else "us_thread"])
+    dom = runs[dom_i]
+
+    # ---- the timed region: exactly `steps` protected passes
+    for _ in range(warmup):
+        for lr in runs:
+            lr.run(lr.pick, stream)
+    ev = [(hip.event(), hip.event()) for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        for i, lr in enumerate(runs):
+            if i == dom_i:
+                B.abft_set_kernel_events(ev[s][0], ev[s][1])
+                lr.run(lr.pick, stream)
+                B.abft_set_kernel_events(None, None)
+            else:
+                lr.run(lr.pick, stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_per_step = 1000.0 * wall / steps
+    total_flops = sum(lr.flops for lr in runs)
+    value = total_flops / (wall / steps) / 1e12
+    flagged = sum(int(lr.flag.item()) for lr in runs)
+
+    kern_us = float(np.mean([1000.0 * hip.elapsed_ms(a, b) for a, b in ev]))
+    for a, b in ev:
+        hip.destroy(a)
+        hip.destroy(b)
+    compute_bound = dom.ai > PEAK[dtype] / HBM
+    if compute_bound:
+        achieved = dom.flops / (kern_us * 1e-6) / 1e12
+        roof = {"bound": "mfma", "achieved": round(achieved, 2), "peak": PEAK[dtype] / 1e12, "unit": "TFLOP/s",
+                "frac": round(achieved / (PEAK[dtype] / 1e12), 4), "traffic": None}
+    else:
+        achieved = dom.bytes / (kern_us * 1e-6) / 1e9
+        roof = {"bound": "hbm", "achieved": round(achieved, 2), "peak": HBM / 1e9, "unit": "GB/s",
+                "frac": round(achieved / (HBM / 1e9), 4), "traffic": None}
+    roof.update({"kernel": f"gemm_kernel[{B.MODE_NAMES[dom.pick]}] on {dom.layer.name} "
+                           f"(M={dom.layer.M},N={dom.layer.N},K={dom.layer.K})",
+                 "avg_launch_us": round(kern_us, 3),
+                 "algorithmic_per_launch": dom.flops if compute_bound else dom.bytes})
+
+    # unprotected pass for the whole-model overhead (same kernels, mode NONE), outside the timed region
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        for lr in runs:
+            lr.run(B.NONE, stream)
+    torch.cuda.synchronize()
+    wall_none = time.perf_counter() - t0
+
+    out = {
+        "metric": "protected GEMM TFLOP/s and ABFT overhead % vs unprotected MFMA GEMM per layer",
+        "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": round(ms_per_step, 5), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype, "data": "synthetic",
+        "config": {"workload": label, "layers": len(runs), "selector": "analytic (AI vs CMR)",
+                   "modes_picked": {m: sum(1 for lr in runs if B.MODE_NAMES[lr.pick] == m) for m in ("global", "thread")}},
+        "overhead_pct_host_timed": round(100 * (wall / wall_none - 1), 2),
+        "overhead_pct_device_timed": summarize(rows)["ovh_selector_pct"],
+        "false_alarms": flagged,
+        "roofline": roof,
+        "summary": summarize(rows),
+        "layers": rows if len(rows) <= 16 else rows[:3] + [{"...": f"{len(rows) - 6} more"}] + rows[-3:],
+        "paper_context": "NVIDIA T4, FP16: DLRM MLP-Bottom/Top batch 1 overhead 5.16/5.61 % (intensity-guided) vs "
+                         "23.50/18.16 % (global); ResNet-50 HD 4.21 % vs 8.49 %; square 2048^3 global 1 %, thread 14 %",
+    }
+
+    if not args.no_extras:
+        extra = {}
+        try:
+            if args.workload != "square":
+                for n, dts in ((4096, ("f16", "bf16")), (8192, ("f16", "bf16", "i8"))):
+                    for d in dts:
+                        lr = LayerRun(wl.Layer(f"sq{n}", n, n, n), d, gen, "normal", "normal")
+                        r = layer_table(hip, [lr], 5, 2, stream)[0]
+                        extra[f"square{n}_{d}"] = {k: r[k] for k in ("pick", "us_none", "ovh_global_pct", "ovh_thread_pct",
+                                                                      "tflops_pick", "roofline_frac_pick")}
+                        del lr
+                        torch.cuda.empty_cache()
+            if args.workload != "dlrm":
+                for b in (1, 16, 256):
+                    rs = [LayerRun(l, "f16", gen) for l in wl.dlrm_layers(b)]
+                    extra[f"dlrm_b{b}"] = summarize(layer_table(hip, rs, 50, 3, stream))
+            else:
+                for b in (1, 16):
+                    rs = [LayerRun(l, "f16", gen) for l in wl.dlrm_layers(b)]
+                    extra[f"dlrm_b{b}"] = summarize(layer_table(hip, rs, 50, 3, stream))
+            if args.workload != "resnet50":
+                for b in (1, 64):
+                    rs = [LayerRun(l, "f16", gen) for l in wl.resnet50_layers(b)]
+                    extra[f"resnet50_b{b}"] = summarize(layer_table(hip, rs, 5, 2, stream))
+                    del rs
+                    torch.cuda.empty_cache()
+            sweep = []
+            for m in wl.sweep_m():
+                lr = LayerRun(wl.Layer(f"m{m}", m, 4096, 4096), "f16", gen, "normal", "normal")
+                r = layer_table(hip, [lr], 10, 2, stream)[0]
+                sweep.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
+            extra["sweep_N4096_K4096"] = sweep
+        except Exception as e:  # extras never invalidate the main measurement
+            extra["error"] = repr(e)
+        out["extra"] = extra
+
+    if not args.no_cpu:
+        out["cpu_baseline"] = cpu_baseline(runs)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

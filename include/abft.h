@@ -47,8 +47,10 @@ extern "C" {
 #define ABFT_E_PLAN (-8)       /* bad plan handle or layer index */
 
 /* ---- enums --------------------------------------------------------------- */
-/* Protection scheme.  GLOBAL: one checksum comparison for the whole product
- * (Sec. 2.4-2.5).  THREAD: the paper's one-sided thread-level scheme (Sec. 5.2.2),
+/* Protection scheme.  GLOBAL: kernel-level ABFT (Sec. 2.4-2.5): activation and weight
+ * checksums are formed outside the product kernel, the output summation is fused into
+ * its epilogue and a separate kernel compares them -- per workgroup tile of C, so for a
+ * product that fits one tile this is the single whole-matrix comparison.  THREAD: the paper's one-sided thread-level scheme (Sec. 5.2.2),
  * carried out per wavefront register tile.  AUTO: whatever abft_select returns
  * (intensity-guided ABFT, Sec. 5.3). */
 typedef enum { ABFT_NONE = 0, ABFT_GLOBAL = 1, ABFT_THREAD = 2, ABFT_AUTO = 3 } abft_mode_t;
@@ -86,17 +88,18 @@ typedef struct {
     int32_t KH, KW, stride, pad;
 } abft_conv_t;
 
-/* What the checksum comparison saw; optional diagnostics written by the device.
- *  GLOBAL: lhs = output summation sum(C), rhs = checksum dot product (1^T A)(B 1),
- *          tau = tolerance used, worst_ratio = |lhs - rhs| / tau (0 if tau = 0 and equal,
- *          +inf if tau = 0 and different), tiles = 1.
- *  THREAD: lhs / rhs / tau are those of the tile with the largest ratio seen,
- *          worst_ratio that ratio, tiles = number of tile comparisons made.
- * Must be zero-filled by the caller before the call. */
+/* What the checksum comparisons saw; optional diagnostics written by the device.
+ * Both schemes make one comparison per region of C: GLOBAL per workgroup tile
+ * (abft_region_shape), THREAD per wavefront register tile (abft_tile_shape).
+ * lhs = output summation of the region with the largest |lhs - rhs| / tau seen,
+ * rhs = its checksum product, tau = its tolerance, worst_ratio = that ratio (0 when
+ * tau = 0 and both sides are equal, +inf when they differ or are not finite),
+ * tiles = number of comparisons made.  Must be zero-filled by the caller before the call. */
 typedef struct {
     double lhs, rhs, tau, worst_ratio;
     uint64_t tiles;
-    uint64_t reserved[3];
+    double frob, l1;   /* ||C_S||_F and sum |C_ij| of the region lhs/rhs/tau belong to (l1: GLOBAL only) */
+    uint64_t reserved;
 } abft_report_t;
 
 /* ---- the protected product ------------------------------------------------ */
@@ -106,9 +109,10 @@ typedef struct {
  *   B   : K x N in the order `b_layout` says, ldb >= K (NK) or >= N (KN).
  *   C   : M x N row-major, ldc >= N; fp16 / bf16 (rounded to nearest even from the
  *         fp32 accumulators) or int32.
- *   beta: optional weight checksum beta[k] = sum_n B[k][n] made earlier by
- *         abft_weight_checksum (K doubles, or K int64 for I8).  Used by GLOBAL only;
- *         NULL makes the call compute it into the workspace first.  THREAD never
+ *   beta: optional weight checksums made earlier by abft_weight_checksum with block_n =
+ *         the region_n of abft_region_shape for this problem (ceil(N/region_n) x K doubles,
+ *         int64 for I8).  Used by GLOBAL only; NULL makes the call compute them into the
+ *         workspace first.  THREAD never
  *         reads it: it recomputes tile-local weight checksums in registers (Sec. 5.2.1).
  *   workspace / workspace_bytes: scratch of at least abft_workspace_bytes(...) bytes,
  *         256-byte aligned; may be NULL when that size is 0.
@@ -133,10 +137,11 @@ int abft_conv(const abft_conv_t *conv /* host */, int N, const void *x, const vo
 /* Bytes of workspace abft_gemm / abft_conv need for this problem (0 for NONE / THREAD). */
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
 
-/* Offline weight checksum (Sec. 2.5): beta[k] = sum_n B[k][n], k = 0..K-1, written as
- * K doubles (F16 / BF16) or K int64 (I8) to `beta`. */
-int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, void *beta,
-                         void *stream);
+/* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns:
+ * beta[b*K + k] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n], written as
+ * doubles (F16 / BF16) or int64 (I8).  block_n <= 0 or >= N gives the plain K-vector B.1 . */
+int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
+                         void *beta, void *stream);
 
 /* Activation checksum (Sec. 2.4 step 1): alpha[k] = sum_m A[m][k] as K doubles / int64.
  * `conv` (host, may be NULL) makes A the lowered matrix of the NHWC tensor passed as A. */
@@ -165,6 +170,11 @@ int abft_select(int M, int N, int K, int dtype);
  * may be NULL. */
 int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int *tile_m, int *tile_n, int *k_step);
 
+/* Workgroup tiling of C: the GLOBAL scheme makes one comparison per region_m x region_n
+ * block of C (edge blocks clipped) and wants its weight checksums per block of region_n
+ * columns.  `aligned` as for abft_tile_shape. */
+int abft_region_shape(int M, int N, int K, int dtype, int aligned, int *region_m, int *region_n);
+
 /* Comparison tolerance (the paper states none; Sec. 2.4 step 4 says "compare"): a
  * comparison passes when |lhs - rhs| <= coeff * ||C_S||_F, where C_S is the part of C
  * the comparison covers (all of C for GLOBAL, one tile for THREAD) and ||.||_F is taken
@@ -172,6 +182,8 @@ int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int *tile_m, in
  * and u = 2^-22 (F16) / 2^-23 (BF16) for THREAD (precision of the in-register tile
  * checksum).  Returns coeff; 0 for I8 (exact comparison). */
 double abft_tolerance_coeff(int K, int dtype, int mode);
+/* Second term of the GLOBAL tolerance: tau = coeff * ||C_S||_F + bias_coeff * sum |C_ij|. */
+double abft_tolerance_bias_coeff(int K, int dtype, int mode);
 
 /* ---- plans: per-layer selection for a network (Sec. 5.3) ------------------- */
 typedef struct {
@@ -206,6 +218,11 @@ void abft_plan_destroy(abft_plan_t *plan);
 const char *abft_strerror(int code);
 /* Library version, e.g. 100 = 1.0.0. */
 int abft_version(void);
+/* Measurement hook: two hipEvent_t handles (cast to void*) that the following abft_gemm /
+ * abft_conv / abft_plan_run calls of the calling host thread record on their stream
+ * immediately before and after launching the matrix-product kernel itself (not the
+ * checksum pre-pass or the comparison).  NULL, NULL switches it off. */
+void abft_set_kernel_events(void *start_event, void *stop_event);
 
 #ifdef __cplusplus
 }

@@ -302,6 +302,19 @@ void orc_tile_two_sided_f64(int N, int K, const double *A, const double *B, cons
     *rhs = acc;
 }
 
+void orc_tile_two_sided_i8(int N, int K, const int8_t *A, const int8_t *B, const int64_t *C, int r0,
+                           int r1, int c0, int c1, int64_t *lhs, int64_t *rhs) {
+    int64_t acc = 0;
+    for (int k = 0; k < K; ++k) {
+        int64_t a = 0, chi = 0;
+        for (int i = r0; i < r1; ++i) a += A[(size_t)i * K + k];
+        for (int j = c0; j < c1; ++j) chi += B[(size_t)k * N + j];
+        acc += a * chi;
+    }
+    *lhs = orc_block_sum_i64(N, C, r0, r1, c0, c1);
+    *rhs = acc;
+}
+
 /* ------------------------------------------------------------------------- *
  * Fault model (Sec. 2.3): one wrong value in C, produced by processing logic.
  * Modelled as one flipped bit in the stored representation of an accumulator:

@@ -38,7 +38,7 @@ class Conv(ctypes.Structure):
 class Report(ctypes.Structure):
     _fields_ = [("lhs", ctypes.c_double), ("rhs", ctypes.c_double), ("tau", ctypes.c_double),
                 ("worst_ratio", ctypes.c_double), ("tiles", ctypes.c_uint64),
-                ("reserved", ctypes.c_uint64 * 3)]
+                ("frob", ctypes.c_double), ("l1", ctypes.c_double), ("reserved", ctypes.c_uint64)]
 
 
 class Layer(ctypes.Structure):
@@ -52,6 +52,7 @@ EXPORTS = [
     "abft_activation_checksum", "abft_arithmetic_intensity", "abft_cmr", "abft_set_cmr",
     "abft_select", "abft_tile_shape", "abft_tolerance_coeff", "abft_plan_create", "abft_plan_run",
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
+    "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
 ]
 
 _lib = None
@@ -76,7 +77,7 @@ def lib() -> ctypes.CDLL:
     L.abft_workspace_bytes.restype = sz
     L.abft_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
     L.abft_weight_checksum.restype = ci
-    L.abft_weight_checksum.argtypes = [ci, ci, vp, i64, ci, ci, vp, vp]
+    L.abft_weight_checksum.argtypes = [ci, ci, vp, i64, ci, ci, ci, vp, vp]
     L.abft_activation_checksum.restype = ci
     L.abft_activation_checksum.argtypes = [ci, ci, vp, i64, ctypes.POINTER(Conv), ci, vp, vp]
     L.abft_arithmetic_intensity.restype = dbl
@@ -89,6 +90,10 @@ def lib() -> ctypes.CDLL:
     L.abft_select.argtypes = [ci, ci, ci, ci]
     L.abft_tile_shape.restype = ci
     L.abft_tile_shape.argtypes = [ci, ci, ci, ci, ci, ip, ip, ip]
+    L.abft_region_shape.restype = ci
+    L.abft_region_shape.argtypes = [ci, ci, ci, ci, ci, ip, ip]
+    L.abft_tolerance_bias_coeff.restype = dbl
+    L.abft_tolerance_bias_coeff.argtypes = [ci, ci, ci]
     L.abft_tolerance_coeff.restype = dbl
     L.abft_tolerance_coeff.argtypes = [ci, ci, ci]
     L.abft_plan_create.restype = ci
@@ -105,6 +110,8 @@ def lib() -> ctypes.CDLL:
     L.abft_strerror.argtypes = [ci]
     L.abft_version.restype = ci
     L.abft_version.argtypes = []
+    L.abft_set_kernel_events.restype = None
+    L.abft_set_kernel_events.argtypes = [vp, vp]
     _lib = L
     return L
 
@@ -181,8 +188,18 @@ def abft_workspace_bytes(M, N, K, dtype, mode) -> int:
     return lib().abft_workspace_bytes(M, N, K, dtype, mode)
 
 
-def abft_weight_checksum(K, N, B, ldb, b_layout, dtype, beta, stream=None) -> None:
-    _check(lib().abft_weight_checksum(K, N, _ptr(B), ldb, b_layout, dtype, _ptr(beta), _stream(stream)))
+def abft_weight_checksum(K, N, B, ldb, b_layout, dtype, beta, block_n=0, stream=None) -> None:
+    _check(lib().abft_weight_checksum(K, N, _ptr(B), ldb, b_layout, dtype, block_n, _ptr(beta), _stream(stream)))
+
+
+def abft_region_shape(M, N, K, dtype, aligned=True):
+    rm, rn = ctypes.c_int(), ctypes.c_int()
+    _check(lib().abft_region_shape(M, N, K, dtype, 1 if aligned else 0, ctypes.byref(rm), ctypes.byref(rn)))
+    return rm.value, rn.value
+
+
+def abft_tolerance_bias_coeff(K, dtype, mode) -> float:
+    return lib().abft_tolerance_bias_coeff(K, dtype, mode)
 
 
 def abft_activation_checksum(M, K, A, lda, dtype, alpha, conv: Optional[Conv] = None, stream=None) -> None:
@@ -234,3 +251,8 @@ def abft_plan_times(plan, layer):
 
 def abft_plan_destroy(plan) -> None:
     lib().abft_plan_destroy(plan)
+
+
+def abft_set_kernel_events(start_event, stop_event) -> None:
+    """hipEvent_t handles (ints) recorded around the matrix-product kernel; None, None = off."""
+    lib().abft_set_kernel_events(start_event, stop_event)

@@ -21,13 +21,18 @@ namespace {
 // ------------------------------------------------------------------------- //
 // constants of the method as built here
 // ------------------------------------------------------------------------- //
-// Tolerance: tau = C_TOL * (2^-24 * sqrt(K) + u_chi) * ||C_S||_F.  2^-24 is the unit
+// Tolerance: tau = C_TOL * (2^-24 * sqrt(K) + u_chi) * ||C_S||_F + C_BIAS * 2^-24 * K * ||C_S||_1
+// (the last term for the global scheme only).  2^-24 is the unit
 // roundoff of the fp32 accumulators; an accumulator that takes K products carries a
 // random-walk error ~ 2^-24 sqrt(K) |C_ij| / 2.4 and the errors of the entries add in
 // quadrature under the output summation.  u_chi covers the tile checksum operand of the
 // thread-level scheme, which is exact to 22 (fp16: two pieces) / 24 (bf16: three
-// pieces) bits of the fp32 column sums.
+// pieces) bits of the fp32 column sums.  The ||.||_1 term covers a small coherent bias of the
+// matrix unit's accumulation (measured: up to 2e-4 * 2^-24 * K per entry, same sign for all
+// entries of a tile with same-sign operands); in the thread-level scheme both sides of the
+// comparison come out of the same unit and the bias cancels.
 constexpr double C_TOL = 8.0;
+constexpr double C_BIAS = 1.0e-3;
 constexpr double U_ACC = 5.9604644775390625e-08;  // 2^-24
 constexpr double U_CHI_F16 = 2.384185791015625e-07;  // 2^-22
 constexpr double U_CHI_BF16 = 1.1920928955078125e-07;  // 2^-23
@@ -35,6 +40,9 @@ constexpr double U_CHI_BF16 = 1.1920928955078125e-07;  // 2^-23
 // MI355X spec-sheet peaks (dense) and HBM3E bandwidth
 constexpr double PEAK_F16 = 2516.6e12, PEAK_I8 = 5033.2e12, HBM_BW = 8.0e12;
 double g_cmr_override[3] = {0.0, 0.0, 0.0};
+
+// optional events recorded around the GEMM kernel launch (abft_set_kernel_events)
+thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 
 inline int esize(int dt) { return dt == ABFT_I8 ? 1 : 2; }
 inline int csize(int dt) { return dt == ABFT_I8 ? 4 : 2; }
@@ -69,14 +77,13 @@ struct PreArgs {
     long long lda;
     int vec;
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
-    const void* beta;     // K doubles / int64, or null
-    void* alpha_out;      // K doubles / int64 (only with gridDim.y == 1), or null
-    void* partial_ab;     // one double / int64 per block, or null
+    void* alpha_out;      // gridDim.y slabs of K doubles / int64: alpha of each slab of rows
     int rows_per_slab;
 };
 
-// Activation checksum alpha[k] = sum_m A[m][k] over a slab of rows, multiplied by
-// beta[k] and summed over the block's k range.  Block = 32 chunk columns x 8 row lanes.
+// Activation checksum alpha_s[k] = sum over the rows m of slab s of A[m][k] (Sec. 2.4
+// step 1), one slab per row block of the product's workgroup tiling.
+// Block = 32 chunk columns x 8 row lanes.
 template <int DT>
 __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
     constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
@@ -165,38 +172,32 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 #pragma unroll
     for (int e = 0; e < EPC; ++e) red[ty][tx][e] = s[e];
     __syncthreads();
-    Wide dot = 0;
     if (ty == 0) {
+        Wide* out = reinterpret_cast<Wide*>(p.alpha_out) + (long long)blockIdx.y * p.K;
 #pragma unroll
         for (int e = 0; e < EPC; ++e) {
             Wide a = 0;
             for (int y = 0; y < 8; ++y) a += red[y][tx][e];
-            const int k = k0 + e;
-            if (k < p.K) {
-                if (p.alpha_out) reinterpret_cast<Wide*>(p.alpha_out)[k] = a;
-                if (p.beta) dot += a * reinterpret_cast<const Wide*>(p.beta)[k];
-            }
+            if (k0 + e < p.K) out[k0 + e] = a;
         }
-    }
-    if (tid < 64 && p.partial_ab) {
-        dot = wave_sum(dot);
-        if (tid == 0) reinterpret_cast<Wide*>(p.partial_ab)[blockIdx.y * gridDim.x + blockIdx.x] = dot;
     }
 }
 
-// Weight checksum beta[k] = sum_n B[k][n] for any storage order (element strides).
-// Block = 32 values of k x 8 lanes over n.  Offline step: not tuned.
+// Weight checksum per block of columns: beta_b[k] = sum over the columns n of block b of
+// B[k][n] (Sec. 2.5, offline), for any storage order (element strides).
+// Block = 32 values of k x 8 lanes over n; blockIdx.y = column block.  Not tuned: offline.
 template <int DT>
 __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int K, int N, long long sn,
-                                                              long long sk, void* beta) {
+                                                              long long sk, int block_n, void* beta) {
     constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
     typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
     __shared__ Wide red[8][32];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int k = blockIdx.x * 32 + tx;
+    const int n_begin = blockIdx.y * block_n, n_end = min(N, n_begin + block_n);
     Wide s = 0;
     if (k < K) {
-        for (int n = ty; n < N; n += 8) {
+        for (int n = n_begin + ty; n < n_end; n += 8) {
             const char* src = B + ((long long)n * sn + (long long)k * sk) * ESIZE;
             if constexpr (DT == DT_F16) s += (double)(float)*reinterpret_cast<const _Float16*>(src);
             else if constexpr (DT == DT_BF16) s += (double)(float)*reinterpret_cast<const __bf16*>(src);
@@ -208,58 +209,80 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
     if (ty == 0 && k < K) {
         Wide a = 0;
         for (int y = 0; y < 8; ++y) a += red[y][tx];
-        reinterpret_cast<Wide*>(beta)[k] = a;
+        reinterpret_cast<Wide*>(beta)[(long long)blockIdx.y * K + k] = a;
     }
 }
 
-// Final reduction and comparison of the global scheme: one workgroup.
+// Checksum dot products and comparison of the global scheme (Sec. 2.4 steps 2-4, Sec. 2.5
+// step 5), one comparison per workgroup tile (i, j) of the product:
+//     sum of C over the tile   vs   sum_k alpha_i[k] * beta_j[k]
+// with alpha_i the activation checksum of row block i and beta_j the weight checksum of
+// column block j.  Summed over all tiles this is the whole-matrix identity; comparing per
+// tile keeps the rounding noise of the fp32 accumulators (which has a small coherent
+// bias that grows with the number of entries summed) far below the tolerance.
+// Grid: (tiles_m, ceil(tiles_n / 8)); a block streams alpha_i once against 8 beta_j.
 template <bool IS_INT>
-__global__ __launch_bounds__(256) void compare_kernel(const void* partials_c, int n_c, const void* partials_ab,
-                                                      int n_ab, double tol_coeff, unsigned int* flag,
-                                                      Report* report) {
+__global__ __launch_bounds__(256) void dot_compare_kernel(const void* alpha_slabs, const void* beta_blocks,
+                                                          const double* partials, int K, int tiles_n,
+                                                          double tol_frob, double tol_l1, unsigned int* flag,
+                                                          Report* report) {
     typedef typename std::conditional<IS_INT, long long, double>::type Wide;
-    __shared__ Wide red[3][4];
-    const Wide* pc = reinterpret_cast<const Wide*>(partials_c);
-    const Wide* pab = reinterpret_cast<const Wide*>(partials_ab);
-    Wide sc = 0, f2 = 0, sab = 0;
-    for (int i = threadIdx.x; i < n_c; i += 256) {
-        sc += pc[2 * i];
-        f2 += pc[2 * i + 1];
+    constexpr int TJ = 8;
+    __shared__ Wide red[TJ][4];
+    const int i = blockIdx.x, j0 = blockIdx.y * TJ;
+    const Wide* alpha = reinterpret_cast<const Wide*>(alpha_slabs) + (long long)i * K;
+    const Wide* beta = reinterpret_cast<const Wide*>(beta_blocks);
+    Wide dot[TJ];
+#pragma unroll
+    for (int t = 0; t < TJ; ++t) dot[t] = 0;
+    for (int k = threadIdx.x; k < K; k += 256) {
+        const Wide a = alpha[k];
+#pragma unroll
+        for (int t = 0; t < TJ; ++t)
+            if (j0 + t < tiles_n) dot[t] += a * beta[(long long)(j0 + t) * K + k];
     }
-    for (int i = threadIdx.x; i < n_ab; i += 256) sab += pab[i];
-    sc = wave_sum(sc);
-    f2 = wave_sum(f2);
-    sab = wave_sum(sab);
     const int wave = threadIdx.x >> 6;
-    if ((threadIdx.x & 63) == 0) {
-        red[0][wave] = sc;
-        red[1][wave] = f2;
-        red[2][wave] = sab;
+#pragma unroll
+    for (int t = 0; t < TJ; ++t) {
+        Wide v = wave_sum(dot[t]);
+        if ((threadIdx.x & 63) == 0) red[t][wave] = v;
     }
     __syncthreads();
-    if (threadIdx.x == 0) {
-        sc = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
-        f2 = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
-        sab = (red[2][0] + red[2][1]) + (red[2][2] + red[2][3]);
+    if (threadIdx.x < TJ && j0 + threadIdx.x < tiles_n) {
+        const int t = threadIdx.x, j = j0 + t;
+        const Wide sab = (red[t][0] + red[t][1]) + (red[t][2] + red[t][3]);
+        const double* pt = partials + 4 * ((long long)i * tiles_n + j);
         bool bad;
-        double tau = 0.0, ratio;
+        double tau = 0.0, ratio, lhs, frob = 0.0, l1 = 0.0;
         if constexpr (IS_INT) {
+            const long long sc = reinterpret_cast<const long long*>(pt)[0];
             bad = sc != sab;
             ratio = bad ? __builtin_huge_val() : 0.0;
+            lhs = (double)sc;
         } else {
-            tau = tol_coeff * __builtin_sqrt(f2);
-            double res = __builtin_fabs(sc - sab);
-            bool finite = __builtin_isfinite(sc) && __builtin_isfinite(sab) && __builtin_isfinite(f2);
+            const double sc = pt[0], f2 = pt[1];
+            l1 = pt[2];
+            frob = __builtin_sqrt(f2);
+            tau = tol_frob * frob + tol_l1 * l1;
+            const double res = __builtin_fabs(sc - sab);
+            // a sum of squares beyond the fp32 range cannot come from a fault-free tile
+            const bool finite = __builtin_isfinite(sc) && __builtin_isfinite(sab) && __builtin_isfinite(f2);
             bad = !finite || !(res <= tau);
             ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+            lhs = sc;
         }
         if (bad) atomicOr(flag, 1u);
         if (report) {
-            report->lhs = (double)sc;
-            report->rhs = (double)sab;
-            report->tau = tau;
-            report->worst_ratio = ratio;
-            report->tiles = 1;
+            atomicAdd(&report->tiles, 1ull);
+            unsigned long long old = atomicMax(reinterpret_cast<unsigned long long*>(&report->worst_ratio),
+                                               bitcast<unsigned long long>(ratio));
+            if (bitcast<unsigned long long>(ratio) >= old) {
+                report->lhs = lhs;
+                report->rhs = (double)sab;
+                report->tau = tau;
+                report->frob = frob;
+                report->l1 = l1;
+            }
         }
     }
 }
@@ -296,28 +319,32 @@ bool b_vectorisable(const Problem& pr) {
 int conv_out(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
 
 struct WsLayout {
-    size_t off_pc, off_pab, off_beta, total;
-    int n_pc_max, n_pab;
+    size_t off_pc, off_alpha, off_beta, total;
 };
 
 int pre_grid_x(int K, int dt) { return (int)cdiv(K, 32 * (16 / esize(dt))); }
-constexpr int PRE_ROWS_PER_SLAB = 256;
 
-WsLayout ws_layout(int M, int N, int K, int dt) {
+// Workspace of the global scheme for the tile configuration `cfg`: per-tile output
+// summations, per-row-block activation checksums, per-column-block weight checksums
+// (the last only used when the caller passes no precomputed ones).
+WsLayout ws_layout(int M, int N, int K, int cfg) {
+    CfgInfo ci = cfg_info_host(cfg);
+    const size_t tm = (size_t)cdiv(M, ci.bm), tn = (size_t)cdiv(N, ci.bn);
     WsLayout w;
-    long long n_pc = 0;
-    for (int id = 0; id < CFG_COUNT; ++id) {
-        CfgInfo ci = cfg_info_host(id);
-        long long t = cdiv(M, ci.bm) * cdiv(N, ci.bn);
-        if (t > n_pc) n_pc = t;
-    }
-    w.n_pc_max = (int)n_pc;
-    w.n_pab = pre_grid_x(K, dt) * (int)cdiv(M, PRE_ROWS_PER_SLAB);
     w.off_pc = 0;
-    w.off_pab = align_up(w.off_pc + (size_t)n_pc * 16, 256);
-    w.off_beta = align_up(w.off_pab + (size_t)w.n_pab * 8, 256);
-    w.total = align_up(w.off_beta + (size_t)K * 8, 256);
+    w.off_alpha = align_up(tm * tn * 32, 256);
+    w.off_beta = align_up(w.off_alpha + tm * (size_t)K * 8, 256);
+    w.total = align_up(w.off_beta + tn * (size_t)K * 8, 256);
     return w;
+}
+
+size_t ws_bytes_any_cfg(int M, int N, int K) {
+    size_t best = 0;
+    for (int id = 0; id < CFG_COUNT; ++id) {
+        size_t t = ws_layout(M, N, K, id).total;
+        if (t > best) best = t;
+    }
+    return best;
 }
 
 double tol_coeff(int K, int dt, int mode) {
@@ -325,6 +352,13 @@ double tol_coeff(int K, int dt, int mode) {
     double u_chi = 0.0;
     if (mode == ABFT_THREAD) u_chi = dt == ABFT_F16 ? U_CHI_F16 : U_CHI_BF16;
     return C_TOL * (U_ACC * std::sqrt((double)K) + u_chi);
+}
+
+// coefficient of the sum of magnitudes (global scheme only): covers the coherent bias of
+// the matrix unit's accumulation, which grows like K per entry instead of sqrt(K)
+double tol_bias_coeff(int K, int dt, int mode) {
+    if (dt == ABFT_I8 || mode != ABFT_GLOBAL) return 0.0;
+    return C_BIAS * U_ACC * (double)K;
 }
 
 double cmr_of(int dt) {
@@ -342,19 +376,22 @@ int select_mode(int M, int N, int K, int dt) {
     return intensity(M, N, K, dt) > cmr_of(dt) ? ABFT_GLOBAL : ABFT_THREAD;
 }
 
-hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, int layout, int dt, void* beta,
-                                  hipStream_t st) {
+hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, int layout, int dt, int block_n,
+                                  void* beta, hipStream_t st) {
     long long sn = layout == ABFT_B_NK ? ldb : 1, sk = layout == ABFT_B_NK ? 1 : ldb;
-    dim3 grid((unsigned)cdiv(K, 32)), block(256);
+    if (block_n <= 0 || block_n > N) block_n = N;
+    dim3 grid((unsigned)cdiv(K, 32), (unsigned)cdiv(N, block_n)), block(256);
     const char* b = reinterpret_cast<const char*>(B);
-    if (dt == ABFT_F16) hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, beta);
-    else if (dt == ABFT_BF16) hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, beta);
-    else hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, beta);
+    if (dt == ABFT_F16)
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta);
+    else if (dt == ABFT_BF16)
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta);
+    else
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta);
     return hipGetLastError();
 }
 
-hipError_t launch_act_checksum(const Problem& pr, const void* beta, void* alpha_out, void* partial_ab,
-                               int rows_per_slab, hipStream_t st) {
+hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_slab, hipStream_t st) {
     PreArgs a;
     std::memset(&a, 0, sizeof a);
     a.A = reinterpret_cast<const char*>(pr.A);
@@ -367,9 +404,7 @@ hipError_t launch_act_checksum(const Problem& pr, const void* beta, void* alpha_
         a.H = pr.cg.H; a.W = pr.cg.W; a.Cin = pr.cg.Cin; a.KH = pr.cg.KH; a.KW = pr.cg.KW;
         a.stride = pr.cg.stride; a.pad = pr.cg.pad; a.OH = pr.OH; a.OW = pr.OW;
     }
-    a.beta = beta;
     a.alpha_out = alpha_out;
-    a.partial_ab = partial_ab;
     a.rows_per_slab = rows_per_slab;
     dim3 grid((unsigned)pre_grid_x(pr.K, pr.dtype), (unsigned)cdiv(pr.M, rows_per_slab)), block(256);
     if (pr.dtype == ABFT_F16) hipLaunchKernelGGL(act_checksum_kernel<DT_F16>, grid, block, 0, st, a);
@@ -439,37 +474,41 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     }
 
     WsLayout w;
+    std::memset(&w, 0, sizeof w);
     char* ws = reinterpret_cast<char*>(workspace);
     const void* beta_used = beta;
     if (mode == ABFT_GLOBAL) {
-        w = ws_layout(pr.M, pr.N, pr.K, pr.dtype);
+        w = ws_layout(pr.M, pr.N, pr.K, cfg);
         if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.total) return ABFT_E_WORKSPACE;
         g.partials = reinterpret_cast<double*>(ws + w.off_pc);
         if (!beta_used) {
-            if (launch_weight_checksum(pr.K, pr.N, pr.B, pr.ldb, pr.b_layout, pr.dtype, ws + w.off_beta, st) != hipSuccess)
+            if (launch_weight_checksum(pr.K, pr.N, pr.B, pr.ldb, pr.b_layout, pr.dtype, ci.bn, ws + w.off_beta,
+                                       st) != hipSuccess)
                 return ABFT_E_HIP;
             beta_used = ws + w.off_beta;
         }
-        // steps 1-2: activation checksum and its dot product with the weight checksum
-        if (launch_act_checksum(pr, beta_used, nullptr, ws + w.off_pab, PRE_ROWS_PER_SLAB, st) != hipSuccess)
-            return ABFT_E_HIP;
+        // step 1: activation checksum of every row block of the tiling
+        if (launch_act_checksum(pr, ws + w.off_alpha, ci.bm, st) != hipSuccess) return ABFT_E_HIP;
     }
 
     hipError_t e;
+    if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return ABFT_E_HIP;
     if (pr.dtype == ABFT_F16) e = launch_gemm_f16(cfg, mode, inj, g, st);
     else if (pr.dtype == ABFT_BF16) e = launch_gemm_bf16(cfg, mode, inj, g, st);
     else e = launch_gemm_i8(cfg, mode, inj, g, st);
     if (e != hipSuccess) return ABFT_E_HIP;
+    if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return ABFT_E_HIP;
 
     if (mode == ABFT_GLOBAL) {
-        const int n_c = g.tiles_m * g.tiles_n;
+        dim3 grid((unsigned)g.tiles_m, (unsigned)cdiv(g.tiles_n, 8));
         if (pr.dtype == ABFT_I8)
-            hipLaunchKernelGGL(compare_kernel<true>, dim3(1), dim3(256), 0, st, (const void*)g.partials, n_c,
-                               (const void*)(ws + w.off_pab), w.n_pab, 0.0, flag, reinterpret_cast<Report*>(report));
-        else
-            hipLaunchKernelGGL(compare_kernel<false>, dim3(1), dim3(256), 0, st, (const void*)g.partials, n_c,
-                               (const void*)(ws + w.off_pab), w.n_pab, g.tol_coeff, flag,
+            hipLaunchKernelGGL(dot_compare_kernel<true>, grid, dim3(256), 0, st, (const void*)(ws + w.off_alpha),
+                               beta_used, (const double*)g.partials, pr.K, g.tiles_n, 0.0, 0.0, flag,
                                reinterpret_cast<Report*>(report));
+        else
+            hipLaunchKernelGGL(dot_compare_kernel<false>, grid, dim3(256), 0, st, (const void*)(ws + w.off_alpha),
+                               beta_used, (const double*)g.partials, pr.K, g.tiles_n, g.tol_coeff,
+                               tol_bias_coeff(pr.K, pr.dtype, mode), flag, reinterpret_cast<Report*>(report));
         if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
     }
     return ABFT_OK;
@@ -504,7 +543,8 @@ struct abft_plan {
     struct Layer {
         abft_layer_t desc;
         int mode;
-        void* beta;
+        void* beta;       // per-column-block weight checksums, blocks of beta_block_n columns
+        int beta_block_n;
         void* workspace;
         size_t ws_bytes;
         double t_us[3];
@@ -547,18 +587,18 @@ size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode) {
     if (M <= 0 || N <= 0 || K <= 0 || !valid_dtype(dtype)) return 0;
     if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
     if (mode != ABFT_GLOBAL) return 0;
-    return ws_layout(M, N, K, dtype).total;
+    return ws_bytes_any_cfg(M, N, K);
 }
 
-int abft_weight_checksum(int K, int N, const void* B, int64_t ldb, int b_layout, int dtype, void* beta,
-                         void* stream) {
+int abft_weight_checksum(int K, int N, const void* B, int64_t ldb, int b_layout, int dtype, int block_n,
+                         void* beta, void* stream) {
     if (!valid_dtype(dtype)) return ABFT_E_ENUM;
     if (b_layout != ABFT_B_NK && b_layout != ABFT_B_KN) return ABFT_E_ENUM;
     if (K <= 0 || N <= 0) return ABFT_E_SHAPE;
     if (!B || !beta) return ABFT_E_NULL;
     if (b_layout == ABFT_B_NK ? ldb < K : ldb < N) return ABFT_E_LD;
-    return launch_weight_checksum(K, N, B, ldb, b_layout, dtype, beta, reinterpret_cast<hipStream_t>(stream)) ==
-                   hipSuccess
+    return launch_weight_checksum(K, N, B, ldb, b_layout, dtype, block_n, beta,
+                                  reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? ABFT_OK
                : ABFT_E_HIP;
 }
@@ -580,8 +620,8 @@ int abft_activation_checksum(int M, int K, const void* A, int64_t lda, const abf
         pr.M = M; pr.K = K; pr.lda = lda;
     }
     pr.A = A;
-    // one slab covering every row, so that each block owns its alpha entries outright
-    return launch_act_checksum(pr, nullptr, alpha, nullptr, M, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+    // one slab covering every row: the plain 1 x K checksum
+    return launch_act_checksum(pr, alpha, M, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? ABFT_OK
                : ABFT_E_HIP;
 }
@@ -613,9 +653,23 @@ int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int* tile_m, in
     return ABFT_OK;
 }
 
+int abft_region_shape(int M, int N, int K, int dtype, int aligned, int* region_m, int* region_n) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
+    CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0));
+    if (region_m) *region_m = ci.bm;
+    if (region_n) *region_n = ci.bn;
+    return ABFT_OK;
+}
+
 double abft_tolerance_coeff(int K, int dtype, int mode) {
     if (!valid_dtype(dtype) || K <= 0) return 0.0;
     return tol_coeff(K, dtype, mode);
+}
+
+double abft_tolerance_bias_coeff(int K, int dtype, int mode) {
+    if (!valid_dtype(dtype) || K <= 0) return 0.0;
+    return tol_bias_coeff(K, dtype, mode);
 }
 
 int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layers, int profile, void* stream) {
@@ -644,11 +698,19 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         L.mode = select_mode(d.M, d.N, d.K, d.dtype);
         // offline weight checksum and workspace for the global scheme (kept for either
         // choice so that profiling can time both)
-        L.ws_bytes = ws_layout(d.M, d.N, d.K, d.dtype).total;
-        if (hipMalloc(&L.beta, (size_t)d.K * 8) != hipSuccess) { rc = ABFT_E_HIP; break; }
-        if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { hipFree(L.beta); rc = ABFT_E_HIP; break; }
+        L.ws_bytes = ws_bytes_any_cfg(d.M, d.N, d.K);
+        {
+            // the tiling the layer will run with when its activations are 16-byte aligned
+            const int es = esize(d.dtype);
+            const bool b16 = d.b_layout == ABFT_B_NK && aligned16(d.B) && (d.K * es) % 16 == 0 && (d.ldb * es) % 16 == 0;
+            const bool a16 = d.has_conv ? (d.conv.Cin * es) % 16 == 0 : (d.K * es) % 16 == 0;
+            L.beta_block_n = cfg_info_host(pick_cfg(d.M, d.N, d.K, d.dtype, a16 && b16)).bn;
+        }
+        if (hipMalloc(&L.beta, (size_t)cdiv(d.N, L.beta_block_n) * d.K * 8) != hipSuccess) { rc = ABFT_E_HIP; break; }
+        if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
         p->layers.push_back(L);
-        if (launch_weight_checksum(d.K, d.N, d.B, d.ldb, d.b_layout, d.dtype, L.beta, st) != hipSuccess) {
+        if (launch_weight_checksum(d.K, d.N, d.B, d.ldb, d.b_layout, d.dtype, L.beta_block_n, L.beta, st) !=
+            hipSuccess) {
             rc = ABFT_E_HIP;
             break;
         }
@@ -667,32 +729,32 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
                                         : (size_t)d.M * d.K;
             void *A = nullptr, *C = nullptr;
             if (hipMalloc(&A, a_elems * esize(d.dtype)) != hipSuccess) { rc = ABFT_E_HIP; break; }
-            if (hipMalloc(&C, (size_t)d.M * d.N * csize(d.dtype)) != hipSuccess) { hipFree(A); rc = ABFT_E_HIP; break; }
-            hipMemsetAsync(A, 0, a_elems * esize(d.dtype), st);
-            hipMemsetAsync(d_flag, 0, 4, st);
+            if (hipMalloc(&C, (size_t)d.M * d.N * csize(d.dtype)) != hipSuccess) { (void)hipFree(A); rc = ABFT_E_HIP; break; }
+            (void)hipMemsetAsync(A, 0, a_elems * esize(d.dtype), st);
+            (void)hipMemsetAsync(d_flag, 0, 4, st);
             const int modes[3] = {ABFT_NONE, ABFT_GLOBAL, ABFT_THREAD};
             for (int mi = 0; mi < 3 && rc == ABFT_OK; ++mi) {
                 const int reps = 20;
                 for (int r = -3; r < reps && rc == ABFT_OK; ++r) {
-                    if (r == 0) hipEventRecord(e0, st);
+                    if (r == 0) (void)hipEventRecord(e0, st);
                     int saved = L.mode;
                     L.mode = modes[mi];
                     rc = abft_plan_run(p, (int)i, A, d.K, C, d.N, d_flag, stream);
                     L.mode = saved;
                 }
-                hipEventRecord(e1, st);
+                (void)hipEventRecord(e1, st);
                 if (hipEventSynchronize(e1) != hipSuccess) rc = ABFT_E_HIP;
                 float ms = 0.f;
-                hipEventElapsedTime(&ms, e0, e1);
+                (void)hipEventElapsedTime(&ms, e0, e1);
                 L.t_us[mi] = 1000.0 * ms / reps;
             }
             if (rc == ABFT_OK) L.mode = L.t_us[1] <= L.t_us[2] ? ABFT_GLOBAL : ABFT_THREAD;
-            hipFree(A);
-            hipFree(C);
+            (void)hipFree(A);
+            (void)hipFree(C);
         }
-        if (d_flag) hipFree(d_flag);
-        hipEventDestroy(e0);
-        hipEventDestroy(e1);
+        if (d_flag) (void)hipFree(d_flag);
+        (void)hipEventDestroy(e0);
+        (void)hipEventDestroy(e1);
     }
     if (rc != ABFT_OK) {
         abft_plan_destroy(p);
@@ -717,7 +779,11 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     }
     pr.dtype = d.dtype; pr.b_layout = d.b_layout;
     pr.A = A; pr.B = d.B; pr.ldb = d.ldb; pr.C = C; pr.ldc = ldc;
-    return run_problem(pr, L.mode, L.beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
+    // the offline checksums fit the tiling chosen for aligned activations; an input that
+    // forces another tiling gets them recomputed into the workspace
+    const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr))).bn;
+    const void* beta = bn_now == L.beta_block_n ? L.beta : nullptr;
+    return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
                        reinterpret_cast<hipStream_t>(stream));
 }
 
@@ -736,8 +802,8 @@ int abft_plan_times(const abft_plan_t* plan, int layer, double* out3) {
 void abft_plan_destroy(abft_plan_t* plan) {
     if (!plan) return;
     for (auto& L : plan->layers) {
-        if (L.beta) hipFree(L.beta);
-        if (L.workspace) hipFree(L.workspace);
+        if (L.beta) (void)hipFree(L.beta);
+        if (L.workspace) (void)hipFree(L.workspace);
     }
     delete plan;
 }
@@ -758,5 +824,10 @@ const char* abft_strerror(int code) {
 }
 
 int abft_version(void) { return 100; }
+
+void abft_set_kernel_events(void* start_event, void* stop_event) {
+    g_ev_start = reinterpret_cast<hipEvent_t>(start_event);
+    g_ev_stop = reinterpret_cast<hipEvent_t>(stop_event);
+}
 
 }  // extern "C"

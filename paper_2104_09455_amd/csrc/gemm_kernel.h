@@ -26,7 +26,8 @@ enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2 };
 struct Report {  // mirrors abft_report_t
     double lhs, rhs, tau, worst_ratio;
     unsigned long long tiles;
-    unsigned long long reserved[3];
+    double frob, l1;
+    unsigned long long reserved;
 };
 
 struct GemmArgs {
@@ -41,7 +42,8 @@ struct GemmArgs {
     // implicit-GEMM geometry (conv != 0): A is an NHWC tensor
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
     // ABFT outputs
-    double* partials;        // GLOBAL: per workgroup {sum, sum of squares} (int64 pair for int8)
+    double* partials;        // GLOBAL: per workgroup tile {sum, sum of squares, sum of magnitudes, -}
+                             // (int8: the int64 sum in the first slot), indexed tile_m * tiles_n + tile_n
     unsigned int* flag;      // THREAD: OR-ed with 1 on mismatch
     Report* report;          // optional diagnostics (THREAD only here)
     double tol_coeff;        // THREAD: tau = tol_coeff * ||C_tile||_F
@@ -599,9 +601,8 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                 if (tid == 0) {
                     long long tot = 0;
                     for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) tot += red[w];
-                    long long* out = reinterpret_cast<long long*>(p.partials) + 2 * (long long)bid;
+                    long long* out = reinterpret_cast<long long*>(p.partials) + 4 * ((long long)tile_m * p.tiles_n + tile_n);
                     out[0] = tot;
-                    out[1] = 0;
                 }
             } else {
                 long long rsum = 0;
@@ -630,7 +631,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
             // groups of four accumulators are summed in fp32 (three roundings), everything
             // above that in fp64, so the summation adds nothing visible to the comparison
             double s = 0.0;
-            float f2 = 0.f;
+            float f2 = 0.f, l1 = 0.f;
 #pragma unroll
             for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -640,25 +641,32 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                         float v0 = acc[i][j][r], v1 = acc[i][j][r + 1], v2 = acc[i][j][r + 2], v3 = acc[i][j][r + 3];
                         s += (double)((v0 + v1) + (v2 + v3));
                         f2 += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
+                        if constexpr (MODE == MODE_GLOBAL)
+                            l1 += (__builtin_fabsf(v0) + __builtin_fabsf(v1)) + (__builtin_fabsf(v2) + __builtin_fabsf(v3));
                     }
             s = wave_sum(s);
             double F2 = wave_sum((double)f2);
             if constexpr (MODE == MODE_GLOBAL) {
+                double L1 = wave_sum((double)l1);
                 double* red = reinterpret_cast<double*>(smem);
                 __syncthreads();
                 if (lane == 0) {
-                    red[2 * wave] = s;
-                    red[2 * wave + 1] = F2;
+                    red[3 * wave] = s;
+                    red[3 * wave + 1] = F2;
+                    red[3 * wave + 2] = L1;
                 }
                 __syncthreads();
                 if (tid == 0) {
-                    double ts = 0.0, tf = 0.0;
+                    double ts = 0.0, tf = 0.0, tl = 0.0;
                     for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) {
-                        ts += red[2 * w];
-                        tf += red[2 * w + 1];
+                        ts += red[3 * w];
+                        tf += red[3 * w + 1];
+                        tl += red[3 * w + 2];
                     }
-                    p.partials[2 * (long long)bid] = ts;
-                    p.partials[2 * (long long)bid + 1] = tf;
+                    double* out = p.partials + 4 * ((long long)tile_m * p.tiles_n + tile_n);
+                    out[0] = ts;
+                    out[1] = tf;
+                    out[2] = tl;
                 }
             } else {
                 double rsum = 0.0;
@@ -684,6 +692,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                             p.report->lhs = s;
                             p.report->rhs = rsum;
                             p.report->tau = tau;
+                            p.report->frob = __builtin_sqrt(F2);
                         }
                     }
                 }

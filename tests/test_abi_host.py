@@ -28,7 +28,7 @@ def _declared_functions():
 
 def test_every_declared_symbol_is_exported(lib):
     names = _declared_functions()
-    assert len(names) >= 18
+    assert len(names) >= 20
     for n in names:
         assert hasattr(lib, n), f"{n} declared in abft.h but not exported"
     assert sorted(B.EXPORTS) == names
@@ -88,6 +88,11 @@ def test_tile_shape_and_tolerance(lib):
     assert B.abft_tolerance_coeff(64, B.F16, B.THREAD) == pytest.approx(8 * (2.0 ** -24 * 8 + 2.0 ** -22))
     assert B.abft_tolerance_coeff(64, B.BF16, B.THREAD) == pytest.approx(8 * (2.0 ** -24 * 8 + 2.0 ** -23))
     assert B.abft_tolerance_coeff(64, B.I8, B.GLOBAL) == 0.0
+    assert B.abft_tolerance_bias_coeff(64, B.F16, B.GLOBAL) == pytest.approx(1e-3 * 2.0 ** -24 * 64)
+    assert B.abft_tolerance_bias_coeff(64, B.F16, B.THREAD) == 0.0
+    assert B.abft_tolerance_bias_coeff(64, B.I8, B.GLOBAL) == 0.0
+    rm, rn = B.abft_region_shape(8192, 8192, 8192, B.F16)
+    assert rm % tm == 0 and rn % tn == 0  # wavefront tiles nest inside workgroup tiles
 
 
 def test_workspace_sizes(lib):

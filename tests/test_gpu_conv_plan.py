@@ -1,0 +1,132 @@
+"""GPU parity for convolutions run as implicit GEMM and for plans (per-layer selection)."""
+import ctypes
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2104_09455_amd import binding as B
+from paper_2104_09455_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+
+DT = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}
+
+CONVS = [
+    # batch, H, W, Cin, Cout, KH, KW, stride, pad
+    wl.Conv(2, 14, 14, 64, 64, 3, 3, 1, 1),     # 3x3, padding taps
+    wl.Conv(1, 14, 14, 256, 128, 1, 1, 1, 0),   # 1x1 = plain GEMM on the NHWC tensor
+    wl.Conv(2, 15, 13, 32, 48, 3, 3, 2, 1),     # stride 2, odd sizes
+    wl.Conv(1, 30, 30, 3, 64, 7, 7, 2, 3),      # first layer: Cin = 3, K = 147 (element-wise gather)
+    wl.Conv(3, 9, 9, 16, 40, 1, 1, 2, 0),       # strided 1x1 (shortcut projection)
+]
+
+
+def _run_conv(c, dtype, mode):
+    import torch
+    from gpu_util import to_dev, c_to_host, read_report, DEV
+    dt = DT[dtype]
+    x, Wm = wl.conv_operands(c, dtype, seed=51 + c.Cin + c.H)
+    M, K, N = c.batch * c.OH * c.OW, c.KH * c.KW * c.Cin, c.Cout
+    dx, dB = to_dev(x, dtype), to_dev(np.ascontiguousarray(Wm.T), dtype)
+    c_t = torch.int32 if dtype == "i8" else (torch.float16 if dtype == "f16" else torch.bfloat16)
+    dC = torch.zeros((M, N), dtype=c_t, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    rep = torch.zeros(ctypes.sizeof(B.Report), dtype=torch.uint8, device=DEV)
+    wsb = B.abft_workspace_bytes(M, N, K, dt, B.GLOBAL)
+    ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device=DEV)
+    conv = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad)
+    B.abft_conv(conv, N, dx, dB, K, B.B_NK, dC, N, dt, mode, workspace=ws, workspace_bytes=wsb,
+                fault_flag=flag, report=rep)
+    torch.cuda.synchronize()
+    return x, Wm, c_to_host(dC, dtype), int(flag.item()), read_report(rep)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+@pytest.mark.parametrize("mode", [B.NONE, B.GLOBAL, B.THREAD])
+@pytest.mark.parametrize("ci", range(len(CONVS)))
+def test_conv_parity(ci, mode, dtype):
+    from gpu_util import c_close
+    c = CONVS[ci]
+    print(f"case conv={c} mode={mode} dtype={dtype}", flush=True)
+    x, Wm, C, flag, rep = _run_conv(c, dtype, mode)
+    A = oracle.im2col(x, dtype, c.KH, c.KW, c.stride, c.pad)
+    C_ref = oracle.gemm(A, Wm, dtype)
+    assert c_close(C, C_ref, dtype)
+    assert flag == 0
+    if mode == B.GLOBAL:
+        M, K = A.shape
+        aligned = (c.Cin * (1 if dtype == "i8" else 2)) % 16 == 0
+        rm, rn = B.abft_region_shape(M, c.Cout, K, DT[dtype], aligned)
+        bad, checks = oracle.global_check_blocks(A, Wm, C_ref, dtype, rm, rn)
+        assert not bad and rep.tiles == len(checks)
+        near = min(checks, key=lambda ch: abs(ch.rhs - rep.rhs))
+        if dtype == "i8":
+            assert rep.lhs == near.lhs and rep.rhs == near.rhs
+        else:
+            assert rep.rhs == pytest.approx(near.rhs, rel=1e-11, abs=1e-9)
+            assert rep.worst_ratio < 0.5
+
+
+def test_conv_activation_checksum_matches_im2col_column_sums():
+    import torch
+    from gpu_util import to_dev, DEV
+    for c in CONVS:
+        x, _ = wl.conv_operands(c, "f16", seed=61)
+        A = oracle.im2col(x, "f16", c.KH, c.KW, c.stride, c.pad)
+        M, K = A.shape
+        alpha = torch.zeros(K, dtype=torch.float64, device=DEV)
+        B.abft_activation_checksum(M, K, to_dev(x, "f16"), K, B.F16, alpha,
+                                   conv=B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad))
+        torch.cuda.synchronize()
+        assert np.allclose(alpha.cpu().numpy(), oracle.col_checksum(A, "f16"), rtol=1e-12, atol=1e-12)
+
+
+def test_plan_runs_every_layer_with_the_selected_scheme():
+    """A plan over a small MLP plus one conv layer: analytic selection equals abft_select,
+    outputs match the oracle, no flag on clean inputs; profiled selection keeps the faster
+    protected scheme (so it can never be slower than either, Sec. 6.2)."""
+    import torch
+    from gpu_util import to_dev, c_to_host, c_close, DEV
+    dims = [(64, 512, 13), (64, 256, 512), (64, 64, 256)]
+    weights, layers, keep = [], [], []
+    for i, (M, N, K) in enumerate(dims):
+        _, Wm = wl.gemm_operands(M, N, K, "f16", seed=70 + i, dist_b="weights")
+        dB = to_dev(np.ascontiguousarray(Wm.T), "f16")
+        keep.append(dB)
+        weights.append(Wm)
+        layers.append(B.Layer(M, N, K, B.F16, B.B_NK, 0, B.Conv(), dB.data_ptr(), K))
+    c = CONVS[0]
+    x, Wc = wl.conv_operands(c, "f16", seed=75)
+    dBc = to_dev(np.ascontiguousarray(Wc.T), "f16")
+    keep.append(dBc)
+    Mc, Kc = c.batch * c.OH * c.OW, c.KH * c.KW * c.Cin
+    layers.append(B.Layer(Mc, c.Cout, Kc, B.F16, B.B_NK, 1,
+                          B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad), dBc.data_ptr(), Kc))
+    for profile in (False, True):
+        plan = B.abft_plan_create(layers, profile=profile)
+        try:
+            flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+            for i, (M, N, K) in enumerate(dims):
+                A, _ = wl.gemm_operands(M, N, K, "f16", seed=80 + i, dist_a="uniform_01")
+                dC = torch.zeros((M, N), dtype=torch.float16, device=DEV)
+                B.abft_plan_run(plan, i, to_dev(A, "f16"), K, dC, N, flag)
+                torch.cuda.synchronize()
+                assert c_close(c_to_host(dC, "f16"), oracle.gemm(A, weights[i], "f16"), "f16")
+                mode = B.abft_plan_mode(plan, i)
+                if not profile:
+                    assert mode == B.abft_select(M, N, K, B.F16)
+                else:
+                    t = B.abft_plan_times(plan, i)
+                    assert all(v > 0 for v in t)
+                    assert mode == (B.GLOBAL if t[1] <= t[2] else B.THREAD)
+            dC = torch.zeros((Mc, c.Cout), dtype=torch.float16, device=DEV)
+            B.abft_plan_run(plan, 3, to_dev(x, "f16"), Kc, dC, c.Cout, flag)
+            torch.cuda.synchronize()
+            A = oracle.im2col(x, "f16", c.KH, c.KW, c.stride, c.pad)
+            assert c_close(c_to_host(dC, "f16"), oracle.gemm(A, Wc, "f16"), "f16")
+            assert int(flag.item()) == 0
+            with pytest.raises(B.AbftError):
+                B.abft_plan_run(plan, 9, dC, 1, dC, 1, flag)
+        finally:
+            B.abft_plan_destroy(plan)

@@ -1,0 +1,120 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times:
+sampled rows of C against the oracle, the checksum identity, and fault-injection
+campaigns (seeded single-bit flips) whose verdicts must match the oracle's."""
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2104_09455_amd import binding as B
+from paper_2104_09455_amd import workloads as wl
+
+pytestmark = pytest.mark.gpu
+DT = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}
+
+
+class Big:
+    """Device-resident operands of one large GEMM (weights stored N x K)."""
+
+    def __init__(self, M, N, K, dtype, seed, dist="normal"):
+        import torch
+        from gpu_util import to_dev, DEV
+        self.M, self.N, self.K, self.dtype, self.dt = M, N, K, dtype, DT[dtype]
+        self.A, self.Bm = wl.gemm_operands(M, N, K, dtype, seed, dist_a=dist, dist_b=dist)
+        self.dA = to_dev(self.A, dtype)
+        self.dB = to_dev(np.ascontiguousarray(self.Bm.T), dtype)
+        c_t = torch.int32 if dtype == "i8" else (torch.float16 if dtype == "f16" else torch.bfloat16)
+        self.dC = torch.zeros((M, N), dtype=c_t, device=DEV)
+        self.flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+        self.rep = torch.zeros(64, dtype=torch.uint8, device=DEV)
+        self.wsb = B.abft_workspace_bytes(M, N, K, self.dt, B.GLOBAL)
+        self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=DEV)
+        self.rm, self.rn = B.abft_region_shape(M, N, K, self.dt, True)
+        self.beta = torch.zeros(-(-N // self.rn) * K, dtype=torch.float64, device=DEV)
+        B.abft_weight_checksum(K, N, self.dB, K, B.B_NK, self.dt, self.beta, block_n=self.rn)
+
+    def run(self, mode, inject=None):
+        import torch
+        from gpu_util import read_report
+        self.flag.zero_()
+        self.rep.zero_()
+        B.abft_gemm(self.M, self.N, self.K, self.dA, self.K, self.dB, self.K, B.B_NK, self.dC, self.N, self.dt,
+                    mode, beta=self.beta, workspace=self.ws, workspace_bytes=self.wsb, fault_flag=self.flag,
+                    report=self.rep, inject=inject)
+        torch.cuda.synchronize()
+        return int(self.flag.item()), read_report(self.rep)
+
+
+@pytest.mark.parametrize("n,dtype", [(4096, "f16"), (4096, "bf16"), (8192, "f16"), (8192, "i8")])
+def test_large_square_sampled_rows_and_identity(n, dtype):
+    from gpu_util import c_to_host, c_close
+    big = Big(n, n, n, dtype, seed=900 + n)
+    rows = np.random.default_rng(n).choice(n, size=6, replace=False)
+    ref = oracle.gemm_rows(big.A, big.Bm, dtype, rows)
+    for mode in (B.GLOBAL, B.THREAD):
+        print(f"case n={n} dtype={dtype} mode={mode}", flush=True)
+        flag, rep = big.run(mode)
+        got = c_to_host(big.dC[rows.tolist()], dtype)
+        assert c_close(got, ref, dtype)
+        assert flag == 0
+        if mode == B.GLOBAL:
+            assert rep.tiles == (n // big.rm) * (n // big.rn)
+            if dtype == "i8":
+                assert rep.worst_ratio == 0.0 and rep.lhs == rep.rhs   # exact identity in every region
+            else:
+                assert rep.worst_ratio < 0.5, rep.worst_ratio
+        else:
+            tm, tn, _ = B.abft_tile_shape(n, n, n, big.dt, True)
+            assert rep.tiles == (n // tm) * (n // tn)
+            assert rep.worst_ratio < 0.5, rep.worst_ratio
+
+
+@pytest.mark.parametrize("dtype,trials", [("i8", 60), ("f16", 60)])
+def test_fault_campaign_global_4096(dtype, trials):
+    """Seeded single-bit flips across C and the running accumulators at 4096^3 under the
+    scheme the selector picks (global).  int8: every flip flagged.  fp16: the verdict equals
+    the oracle's incremental evaluation outside the don't-care band; non-finite always flagged."""
+    n = 4096
+    big = Big(n, n, n, dtype, seed=77)
+    _, _, ks = B.abft_tile_shape(n, n, n, big.dt, True)
+    flag0, rep0 = big.run(B.GLOBAL)
+    assert flag0 == 0
+    rng = np.random.default_rng(78)
+    must = mustnot = band = 0
+    for t in range(trials):
+        i, j, bit = int(rng.integers(n)), int(rng.integers(n)), int(rng.integers(32))
+        k_after = -1 if t % 2 == 0 else ks * int(rng.integers(1, n // ks))
+        print(f"case dtype={dtype} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        flag, rep = big.run(B.GLOBAL, inject=B.Fault(i, j, bit, k_after))
+        if dtype == "i8":
+            assert flag == 1
+            must += 1
+            continue
+        # oracle, incremental: the corrupted element against its clean value
+        kk = n if k_after < 0 else k_after
+        head = oracle.partial_dot(big.A, big.Bm, dtype, i, j, 0, kk)
+        tail = oracle.partial_dot(big.A, big.Bm, dtype, i, j, kk, n)
+        bad = oracle.flip_bit(head, bit, dtype) + tail
+        if not math.isfinite(bad):
+            assert flag == 1
+            must += 1
+            continue
+        delta = abs(bad - (head + tail))
+        # tolerance of the region that holds the element, from the oracle's own block of C
+        r0, c0 = i // big.rm * big.rm, j // big.rn * big.rn
+        Cblk = oracle.gemm(big.A[r0:r0 + big.rm], np.ascontiguousarray(big.Bm[:, c0:c0 + big.rn]), dtype)
+        Cblk[i - r0, j - c0] = bad
+        tau = oracle.tolerance(n, oracle.frob(Cblk), dtype, scheme=1, l1_norm=oracle.l1norm(Cblk))
+        resid0 = rep0.tau * rep0.worst_ratio   # largest clean rounding residual of any region on the device
+        if delta >= 2 * tau + resid0:
+            assert flag == 1, (i, j, bit, delta, tau)
+            must += 1
+        elif delta <= tau / 2 - resid0:
+            assert flag == 0, (i, j, bit, delta, tau)
+            mustnot += 1
+        else:
+            band += 1
+    assert must > 0
+    if dtype != "i8":
+        assert mustnot > 0

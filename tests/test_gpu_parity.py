@@ -15,15 +15,6 @@ SHAPES = [(64, 64, 64), (200, 136, 264), (130, 70, 333), (1, 64, 13), (16, 1, 25
           (300, 520, 1024), (17, 260, 72), (512, 512, 128)]
 
 
-def _oracle_flag(A, Bm, C, dtype, mode, M, N, K, aligned=True):
-    dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
-    if mode == B.GLOBAL:
-        return oracle.global_check(A, Bm, C, dtype)
-    tm, tn, _ = B.abft_tile_shape(M, N, K, dt, aligned)
-    flag, checks = oracle.thread_check(A, Bm, C, dtype, tm, tn)
-    return flag, checks
-
-
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
 @pytest.mark.parametrize("mode", MODES)
 @pytest.mark.parametrize("shape", SHAPES)
@@ -38,20 +29,25 @@ def test_clean_parity(shape, mode, dtype):
     if dtype != "i8":
         assert normwise_error(res.C, C_ref) < (2.0 ** -10 if dtype == "f16" else 2.0 ** -7)
     assert res.flag == 0
+    dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
+    aligned = K * (1 if dtype == "i8" else 2) % 16 == 0
     if mode == B.GLOBAL:
-        chk = oracle.global_check(A, Bm, C_ref, dtype)
-        assert res.report.tiles == 1
+        rm, rn = B.abft_region_shape(M, N, K, dt, aligned)
+        flag, checks = oracle.global_check_blocks(A, Bm, C_ref, dtype, rm, rn)
+        assert not flag
+        assert res.report.tiles == len(checks)
+        # the reported region is one of the oracle's: same checksum product, same tolerance
+        near = min(checks, key=lambda c: abs(c.rhs - res.report.rhs))
         if dtype == "i8":
-            assert res.report.lhs == chk.lhs and res.report.rhs == chk.rhs and res.report.worst_ratio == 0.0
+            assert res.report.lhs == near.lhs and res.report.rhs == near.rhs and res.report.worst_ratio == 0.0
         else:
             # checksum side is carried in fp64 on the device
-            assert res.report.rhs == pytest.approx(chk.rhs, rel=1e-11, abs=1e-9)
-            assert abs(res.report.lhs - chk.lhs) <= chk.tau + 1e-300
-            assert res.report.tau == pytest.approx(chk.tau, rel=1e-3)
+            assert res.report.rhs == pytest.approx(near.rhs, rel=1e-11, abs=1e-9)
+            assert abs(res.report.lhs - near.lhs) <= near.tau + 1e-300
+            assert res.report.tau == pytest.approx(near.tau, rel=1e-3)
             assert res.report.worst_ratio < 0.5
     if mode == B.THREAD:
-        dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
-        tm, tn, _ = B.abft_tile_shape(M, N, K, dt, K * (1 if dtype == "i8" else 2) % 16 == 0)
+        tm, tn, _ = B.abft_tile_shape(M, N, K, dt, aligned)
         import math
         # one comparison per wave tile of the launched grid (tiles past the edge included)
         assert res.report.tiles >= math.ceil(M / tm) * math.ceil(N / tn)
@@ -92,11 +88,19 @@ def test_checksum_vectors(dtype):
             dB = to_dev(host, dtype)
             beta = torch.zeros(K, dtype=wide, device=DEV)
             B.abft_weight_checksum(K, N, dB, host.shape[1], layout, dt, beta)
+            # per block of 16 columns: row checksums of the column blocks
+            nb = -(-N // 16)
+            beta_b = torch.zeros(nb * K, dtype=wide, device=DEV)
+            B.abft_weight_checksum(K, N, dB, host.shape[1], layout, dt, beta_b, block_n=16)
             torch.cuda.synchronize()
+            blocks = np.stack([oracle.row_checksum(np.ascontiguousarray(Bm[:, b * 16:(b + 1) * 16]), dtype)
+                               for b in range(nb)])
             if dtype == "i8":
                 assert np.array_equal(beta.cpu().numpy(), b_ref)
+                assert np.array_equal(beta_b.cpu().numpy().reshape(nb, K), blocks)
             else:
                 assert np.allclose(beta.cpu().numpy(), b_ref, rtol=1e-12, atol=1e-12)
+                assert np.allclose(beta_b.cpu().numpy().reshape(nb, K), blocks, rtol=1e-12, atol=1e-12)
         if dtype == "i8":
             assert np.array_equal(alpha.cpu().numpy(), a_ref)
         else:
@@ -146,7 +150,9 @@ def test_fp_injected_faults_match_oracle_outside_band(mode, dtype):
         res = run_gemm(A, Bm, dtype, mode, inject=B.Fault(i, j, bit, -1))
         C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit)
         if mode == B.GLOBAL:
-            chk = oracle.global_check(A, Bm, C_bad, dtype)
+            rm, rn = B.abft_region_shape(M, N, K, dt)
+            r0, c0 = i // rm * rm, j // rn * rn
+            chk = oracle.region_check(A, Bm, C_bad, dtype, r0, min(r0 + rm, M), c0, min(c0 + rn, N))
         else:
             r0, c0 = i // tm * tm, j // tn * tn
             chk = oracle.tile_check(A, Bm, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))

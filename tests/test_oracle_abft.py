@@ -220,3 +220,40 @@ def test_no_false_alarm_tiles_fp32_accumulated_larger():
         flag, checks = oracle.thread_check(A, B, C32, "f16", 128, 128)
         assert not flag
         assert not oracle.global_check(A, B, C32, "f16").flag
+
+
+# -------------------------------------------------------- per-block global check
+@pytest.mark.parametrize("block", [(16, 16), (64, 64), (7, 20), (256, 256)])
+def test_block_checks_telescope_to_the_whole_matrix_identity(block):
+    """One comparison per block of C: every block passes on clean data, and the block
+    checksum products add up to (1^T A)(B 1) exactly over the integers."""
+    M, N, K = 40, 50, 24
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=13)
+    C = oracle.gemm(A, B, "i8")
+    flag, checks = oracle.global_check_blocks(A, B, C, "i8", *block)
+    assert not flag and all(c.lhs == c.rhs for c in checks)
+    whole = oracle.global_check(A, B, C, "i8")
+    assert sum(c.rhs for c in checks) == whole.rhs and sum(c.lhs for c in checks) == whole.lhs
+    # block checksum product written out with numpy for one block
+    r0, r1, c0, c1 = 0, min(block[0], M), 0, min(block[1], N)
+    want = int(A[r0:r1].astype(np.int64).sum(axis=0) @ B[:, c0:c1].astype(np.int64).sum(axis=1))
+    assert checks[0].rhs == want
+    # a fault is seen by exactly the block that holds it
+    Cf = oracle.inject(A, B, C, "i8", 17, 33, 5)
+    flag, checks = oracle.global_check_blocks(A, B, Cf, "i8", *block)
+    assert flag and sum(c.flag for c in checks) == 1
+
+
+def test_global_tolerance_has_the_bias_term():
+    K = 100
+    C = np.full((4, 5), 2.0)
+    f, l1 = oracle.frob(C), oracle.l1norm(C)
+    assert l1 == 40.0 and f == pytest.approx(2.0 * math.sqrt(20))
+    tau = oracle.tolerance(K, f, "f16", scheme=1, l1_norm=l1)
+    assert tau == pytest.approx(8 * 2.0 ** -24 * 10 * f + 1e-3 * 2.0 ** -24 * 100 * 40)
+    assert oracle.tolerance(K, f, "f16", scheme=2) == pytest.approx(8 * (2.0 ** -24 * 10 + 2.0 ** -22) * f)
+    A, B = wl.gemm_operands(8, 8, 8, "f16", seed=14)
+    Cc = oracle.gemm(A, B, "f16")
+    one = oracle.region_check(A, B, Cc, "f16", 0, 8, 0, 8)
+    whole = oracle.global_check(A, B, Cc, "f16")
+    assert one.tau == pytest.approx(whole.tau) and one.rhs == pytest.approx(whole.rhs, rel=1e-13)

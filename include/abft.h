@@ -93,13 +93,14 @@ typedef struct {
  * (abft_region_shape), THREAD per wavefront register tile (abft_tile_shape).
  * lhs = output summation of the region with the largest |lhs - rhs| / tau seen,
  * rhs = its checksum product, tau = its tolerance, worst_ratio = that ratio (0 when
- * tau = 0 and both sides are equal, +inf when they differ or are not finite),
- * tiles = number of comparisons made.  Must be zero-filled by the caller before the call. */
+ * tau = 0 and both sides are equal, +inf when they differ or are not finite); ties go to
+ * the region with the lowest index.  tiles = number of comparisons made.  Must be zero-filled by the caller before the call. */
 typedef struct {
     double lhs, rhs, tau, worst_ratio;
     uint64_t tiles;
     double frob, l1;   /* ||C_S||_F and sum |C_ij| of the region lhs/rhs/tau belong to (l1: GLOBAL only) */
-    uint64_t reserved;
+    uint32_t lock;     /* used by the device while it updates the block */
+    uint32_t region;   /* 1 + row-major index of that region in the grid of regions */
 } abft_report_t;
 
 /* ---- the protected product ------------------------------------------------ */
@@ -110,7 +111,7 @@ typedef struct {
  *   C   : M x N row-major, ldc >= N; fp16 / bf16 (rounded to nearest even from the
  *         fp32 accumulators) or int32.
  *   beta: optional weight checksums made earlier by abft_weight_checksum with block_n =
- *         the region_n of abft_region_shape for this problem (ceil(N/region_n) x K doubles,
+ *         the region_n of abft_region_shape for this problem (K x ceil(N/region_n) doubles,
  *         int64 for I8).  Used by GLOBAL only; NULL makes the call compute them into the
  *         workspace first.  THREAD never
  *         reads it: it recomputes tile-local weight checksums in registers (Sec. 5.2.1).
@@ -137,8 +138,9 @@ int abft_conv(const abft_conv_t *conv /* host */, int N, const void *x, const vo
 /* Bytes of workspace abft_gemm / abft_conv need for this problem (0 for NONE / THREAD). */
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
 
-/* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns:
- * beta[b*K + k] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n], written as
+/* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns, stored
+ * k-major: with nb = ceil(N / block_n),
+ * beta[k*nb + b] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n], written as
  * doubles (F16 / BF16) or int64 (I8).  block_n <= 0 or >= N gives the plain K-vector B.1 . */
 int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
                          void *beta, void *stream);

@@ -38,7 +38,8 @@ class Conv(ctypes.Structure):
 class Report(ctypes.Structure):
     _fields_ = [("lhs", ctypes.c_double), ("rhs", ctypes.c_double), ("tau", ctypes.c_double),
                 ("worst_ratio", ctypes.c_double), ("tiles", ctypes.c_uint64),
-                ("frob", ctypes.c_double), ("l1", ctypes.c_double), ("reserved", ctypes.c_uint64)]
+                ("frob", ctypes.c_double), ("l1", ctypes.c_double), ("lock", ctypes.c_uint32),
+                ("region", ctypes.c_uint32)]
 
 
 class Layer(ctypes.Structure):

@@ -54,15 +54,15 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // tile configuration choice (host logic)
 // ------------------------------------------------------------------------- //
 int pick_cfg(int M, int N, int K, int dt, bool aligned16) {
-    (void)K;
-    (void)dt;
     if (M <= 16) return CFG_T;
+    // the large tile's direct-to-LDS loads need whole k tiles of 128 bytes
+    const bool large_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);
         return cdiv(M, ci.bm) * cdiv(N, ci.bn);
     };
     // fill the 256 compute units before growing the tile
-    if (aligned16 && tiles(CFG_L) >= 224) return CFG_L;
+    if (large_ok && tiles(CFG_L) >= 224) return CFG_L;
     if (tiles(CFG_M) >= 192) return CFG_M;
     if (tiles(CFG_S) >= 1024) return CFG_M;
     return CFG_S;
@@ -77,8 +77,12 @@ struct PreArgs {
     long long lda;
     int vec;
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
-    void* alpha_out;      // gridDim.y slabs of K doubles / int64: alpha of each slab of rows
-    int rows_per_slab;
+    void* alpha_out;      // K doubles / int64: the plain checksum (single-slab launches only), or null
+    int rows_per_slab;    // rows of one row block of the product's tiling
+    int rows_per_block;   // rows one workgroup sums; divides rows_per_slab
+    const void* beta;     // K x nb (k-major) weight checksums per column block, or null
+    void* partial_dots;   // [slab][nb][subs * gridDim.x] partial checksum dot products, or null
+    int nb;
 };
 
 // Activation checksum alpha_s[k] = sum over the rows m of slab s of A[m][k] (Sec. 2.4
@@ -93,8 +97,10 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 
     const int tid = threadIdx.x, tx = tid & 31, ty = tid >> 5;
     const int k0 = (blockIdx.x * 32 + tx) * EPC;
-    const int row_begin = blockIdx.y * p.rows_per_slab;
-    const int row_end = min(p.M, row_begin + p.rows_per_slab);
+    const int subs = p.rows_per_slab / p.rows_per_block;
+    const int slab = blockIdx.y / subs, sub = blockIdx.y - slab * subs;
+    const int row_begin = slab * p.rows_per_slab + sub * p.rows_per_block;
+    const int row_end = min(p.M, row_begin + p.rows_per_block);
 
     // per-element filter tap for the implicit-GEMM view (k is fixed per thread)
     int e_off[EPC], e_kh[EPC], e_kw[EPC];
@@ -172,13 +178,41 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 #pragma unroll
     for (int e = 0; e < EPC; ++e) red[ty][tx][e] = s[e];
     __syncthreads();
+    __shared__ Wide alpha_s[32 * EPC];
     if (ty == 0) {
-        Wide* out = reinterpret_cast<Wide*>(p.alpha_out) + (long long)blockIdx.y * p.K;
+        Wide* out = reinterpret_cast<Wide*>(p.alpha_out);
 #pragma unroll
         for (int e = 0; e < EPC; ++e) {
             Wide a = 0;
             for (int y = 0; y < 8; ++y) a += red[y][tx][e];
-            if (k0 + e < p.K) out[k0 + e] = a;
+            alpha_s[tx * EPC + e] = (k0 + e < p.K) ? a : (Wide)0;
+            if (out && k0 + e < p.K) out[k0 + e] = a;
+        }
+    }
+    if (!p.partial_dots) return;
+    // Sec. 2.4 step 2, fused: this block's share of the checksum dot products
+    //   P[slab][j][sub, chunk] = sum over the block's rows and k range of A[m][k] * beta_j[k]
+    // lanes run over the column blocks j (beta is k-major, so these reads are contiguous),
+    // the 8 lane groups split the k range
+    __syncthreads();
+    const int kbase = blockIdx.x * 32 * EPC;
+    const int kcount = min(32 * EPC, p.K - kbase);
+    const Wide* beta = reinterpret_cast<const Wide*>(p.beta);
+    Wide* red2 = &red[0][0][0];  // reuse: 8 x 32 values
+    const int n_parts = subs * gridDim.x;
+    Wide* pout = reinterpret_cast<Wide*>(p.partial_dots) + (long long)slab * p.nb * n_parts + sub * gridDim.x + blockIdx.x;
+    for (int jb = 0; jb < p.nb; jb += 32) {
+        const int j = jb + tx;
+        Wide acc = 0;
+        if (j < p.nb)
+            for (int k = ty; k < kcount; k += 8) acc += alpha_s[k] * beta[(long long)(kbase + k) * p.nb + j];
+        __syncthreads();
+        red2[ty * 32 + tx] = acc;
+        __syncthreads();
+        if (ty == 0 && j < p.nb) {
+            Wide tot = 0;
+            for (int y = 0; y < 8; ++y) tot += red2[y * 32 + tx];
+            pout[(long long)j * n_parts] = tot;
         }
     }
 }
@@ -209,82 +243,54 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
     if (ty == 0 && k < K) {
         Wide a = 0;
         for (int y = 0; y < 8; ++y) a += red[y][tx];
-        reinterpret_cast<Wide*>(beta)[(long long)blockIdx.y * K + k] = a;
+        reinterpret_cast<Wide*>(beta)[(long long)k * gridDim.y + blockIdx.y] = a;
     }
 }
 
-// Checksum dot products and comparison of the global scheme (Sec. 2.4 steps 2-4, Sec. 2.5
-// step 5), one comparison per workgroup tile (i, j) of the product:
+// Comparison of the global scheme (Sec. 2.4 steps 3-4, Sec. 2.5 step 5), one comparison per
+// workgroup tile (i, j) of the product:
 //     sum of C over the tile   vs   sum_k alpha_i[k] * beta_j[k]
 // with alpha_i the activation checksum of row block i and beta_j the weight checksum of
-// column block j.  Summed over all tiles this is the whole-matrix identity; comparing per
-// tile keeps the rounding noise of the fp32 accumulators (which has a small coherent
-// bias that grows with the number of entries summed) far below the tolerance.
-// Grid: (tiles_m, ceil(tiles_n / 8)); a block streams alpha_i once against 8 beta_j.
+// column block j; the right-hand side arrives as per-k-range partial dot products from the
+// activation-checksum kernel.  Summed over all tiles this is the whole-matrix identity;
+// comparing per tile keeps the rounding noise of the fp32 accumulators (which has a small
+// coherent bias that grows with the number of entries summed) far below the tolerance.
+// One wavefront per tile.
 template <bool IS_INT>
-__global__ __launch_bounds__(256) void dot_compare_kernel(const void* alpha_slabs, const void* beta_blocks,
-                                                          const double* partials, int K, int tiles_n,
-                                                          double tol_frob, double tol_l1, unsigned int* flag,
-                                                          Report* report) {
+__global__ __launch_bounds__(256) void compare_kernel(const void* partial_dots, int n_parts, const double* partials,
+                                                      int tiles_m, int tiles_n, double tol_frob, double tol_l1,
+                                                      unsigned int* flag, Report* report) {
     typedef typename std::conditional<IS_INT, long long, double>::type Wide;
-    constexpr int TJ = 8;
-    __shared__ Wide red[TJ][4];
-    const int i = blockIdx.x, j0 = blockIdx.y * TJ;
-    const Wide* alpha = reinterpret_cast<const Wide*>(alpha_slabs) + (long long)i * K;
-    const Wide* beta = reinterpret_cast<const Wide*>(beta_blocks);
-    Wide dot[TJ];
-#pragma unroll
-    for (int t = 0; t < TJ; ++t) dot[t] = 0;
-    for (int k = threadIdx.x; k < K; k += 256) {
-        const Wide a = alpha[k];
-#pragma unroll
-        for (int t = 0; t < TJ; ++t)
-            if (j0 + t < tiles_n) dot[t] += a * beta[(long long)(j0 + t) * K + k];
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= tiles_m * tiles_n) return;
+    const int lane = threadIdx.x & 63;
+    const Wide* pd = reinterpret_cast<const Wide*>(partial_dots) + (long long)t * n_parts;
+    Wide sab = 0;
+    for (int c = lane; c < n_parts; c += 64) sab += pd[c];
+    sab = wave_sum(sab);
+    if (lane != 0) return;
+    const double* pt = partials + 4 * (long long)t;
+    bool bad;
+    double tau = 0.0, ratio, lhs, frob = 0.0, l1 = 0.0;
+    if constexpr (IS_INT) {
+        const long long sc = reinterpret_cast<const long long*>(pt)[0];
+        bad = sc != sab;
+        ratio = bad ? __builtin_huge_val() : 0.0;
+        lhs = (double)sc;
+    } else {
+        const double sc = pt[0], f2 = pt[1];
+        l1 = pt[2];
+        frob = __builtin_sqrt(f2);
+        tau = tol_frob * frob + tol_l1 * l1;
+        const double res = __builtin_fabs(sc - sab);
+        // a sum of squares beyond the fp32 range cannot come from a fault-free tile
+        const bool finite = __builtin_isfinite(sc) && __builtin_isfinite(sab) && __builtin_isfinite(f2);
+        bad = !finite || !(res <= tau);
+        ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+        lhs = sc;
     }
-    const int wave = threadIdx.x >> 6;
-#pragma unroll
-    for (int t = 0; t < TJ; ++t) {
-        Wide v = wave_sum(dot[t]);
-        if ((threadIdx.x & 63) == 0) red[t][wave] = v;
-    }
-    __syncthreads();
-    if (threadIdx.x < TJ && j0 + threadIdx.x < tiles_n) {
-        const int t = threadIdx.x, j = j0 + t;
-        const Wide sab = (red[t][0] + red[t][1]) + (red[t][2] + red[t][3]);
-        const double* pt = partials + 4 * ((long long)i * tiles_n + j);
-        bool bad;
-        double tau = 0.0, ratio, lhs, frob = 0.0, l1 = 0.0;
-        if constexpr (IS_INT) {
-            const long long sc = reinterpret_cast<const long long*>(pt)[0];
-            bad = sc != sab;
-            ratio = bad ? __builtin_huge_val() : 0.0;
-            lhs = (double)sc;
-        } else {
-            const double sc = pt[0], f2 = pt[1];
-            l1 = pt[2];
-            frob = __builtin_sqrt(f2);
-            tau = tol_frob * frob + tol_l1 * l1;
-            const double res = __builtin_fabs(sc - sab);
-            // a sum of squares beyond the fp32 range cannot come from a fault-free tile
-            const bool finite = __builtin_isfinite(sc) && __builtin_isfinite(sab) && __builtin_isfinite(f2);
-            bad = !finite || !(res <= tau);
-            ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
-            lhs = sc;
-        }
-        if (bad) atomicOr(flag, 1u);
-        if (report) {
-            atomicAdd(&report->tiles, 1ull);
-            unsigned long long old = atomicMax(reinterpret_cast<unsigned long long*>(&report->worst_ratio),
-                                               bitcast<unsigned long long>(ratio));
-            if (bitcast<unsigned long long>(ratio) >= old) {
-                report->lhs = lhs;
-                report->rhs = (double)sab;
-                report->tau = tau;
-                report->frob = frob;
-                report->l1 = l1;
-            }
-        }
-    }
+    if (bad) atomicOr(flag, 1u);
+    if (report) report_update(report, ratio, lhs, (double)sab, tau, frob, l1, (unsigned)t);
 }
 
 // ------------------------------------------------------------------------- //
@@ -319,21 +325,24 @@ bool b_vectorisable(const Problem& pr) {
 int conv_out(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
 
 struct WsLayout {
-    size_t off_pc, off_alpha, off_beta, total;
+    size_t off_pc, off_pd, off_beta, total;
 };
 
 int pre_grid_x(int K, int dt) { return (int)cdiv(K, 32 * (16 / esize(dt))); }
+// rows one workgroup of the activation-checksum kernel sums
+int pre_rows_per_block(int bm) { return bm < 64 ? bm : 64; }
 
 // Workspace of the global scheme for the tile configuration `cfg`: per-tile output
-// summations, per-row-block activation checksums, per-column-block weight checksums
-// (the last only used when the caller passes no precomputed ones).
+// summations, per-tile partial checksum dot products, per-column-block weight checksums
+// (the last only used when the caller passes no precomputed ones).  Sized for any dtype.
 WsLayout ws_layout(int M, int N, int K, int cfg) {
     CfgInfo ci = cfg_info_host(cfg);
     const size_t tm = (size_t)cdiv(M, ci.bm), tn = (size_t)cdiv(N, ci.bn);
+    const size_t n_parts = (size_t)(ci.bm / pre_rows_per_block(ci.bm)) * (size_t)cdiv(K, 256);
     WsLayout w;
     w.off_pc = 0;
-    w.off_alpha = align_up(tm * tn * 32, 256);
-    w.off_beta = align_up(w.off_alpha + tm * (size_t)K * 8, 256);
+    w.off_pd = align_up(tm * tn * 32, 256);
+    w.off_beta = align_up(w.off_pd + tm * tn * n_parts * 8, 256);
     w.total = align_up(w.off_beta + tn * (size_t)K * 8, 256);
     return w;
 }
@@ -391,7 +400,8 @@ hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, in
     return hipGetLastError();
 }
 
-hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_slab, hipStream_t st) {
+hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_slab, const void* beta, int nb,
+                               void* partial_dots, hipStream_t st) {
     PreArgs a;
     std::memset(&a, 0, sizeof a);
     a.A = reinterpret_cast<const char*>(pr.A);
@@ -406,7 +416,14 @@ hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_
     }
     a.alpha_out = alpha_out;
     a.rows_per_slab = rows_per_slab;
-    dim3 grid((unsigned)pre_grid_x(pr.K, pr.dtype), (unsigned)cdiv(pr.M, rows_per_slab)), block(256);
+    // the plain checksum is one slab summed by one row of blocks; the fused form splits each
+    // row block of the tiling over several blocks to have enough loads in flight
+    a.rows_per_block = alpha_out ? rows_per_slab : pre_rows_per_block(rows_per_slab);
+    a.beta = beta;
+    a.nb = nb;
+    a.partial_dots = partial_dots;
+    const int subs = a.rows_per_slab / a.rows_per_block;
+    dim3 grid((unsigned)pre_grid_x(pr.K, pr.dtype), (unsigned)(cdiv(pr.M, rows_per_slab) * subs)), block(256);
     if (pr.dtype == ABFT_F16) hipLaunchKernelGGL(act_checksum_kernel<DT_F16>, grid, block, 0, st, a);
     else if (pr.dtype == ABFT_BF16) hipLaunchKernelGGL(act_checksum_kernel<DT_BF16>, grid, block, 0, st, a);
     else hipLaunchKernelGGL(act_checksum_kernel<DT_I8>, grid, block, 0, st, a);
@@ -487,8 +504,10 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
                 return ABFT_E_HIP;
             beta_used = ws + w.off_beta;
         }
-        // step 1: activation checksum of every row block of the tiling
-        if (launch_act_checksum(pr, ws + w.off_alpha, ci.bm, st) != hipSuccess) return ABFT_E_HIP;
+        // steps 1-2: activation checksum of every row block of the tiling and its partial dot
+        // products with the weight checksums
+        if (launch_act_checksum(pr, nullptr, ci.bm, beta_used, g.tiles_n, ws + w.off_pd, st) != hipSuccess)
+            return ABFT_E_HIP;
     }
 
     hipError_t e;
@@ -500,14 +519,15 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return ABFT_E_HIP;
 
     if (mode == ABFT_GLOBAL) {
-        dim3 grid((unsigned)g.tiles_m, (unsigned)cdiv(g.tiles_n, 8));
+        dim3 grid((unsigned)cdiv((long long)g.tiles_m * g.tiles_n, 4));
+        const int n_chunks = pre_grid_x(pr.K, pr.dtype) * (ci.bm / pre_rows_per_block(ci.bm));
         if (pr.dtype == ABFT_I8)
-            hipLaunchKernelGGL(dot_compare_kernel<true>, grid, dim3(256), 0, st, (const void*)(ws + w.off_alpha),
-                               beta_used, (const double*)g.partials, pr.K, g.tiles_n, 0.0, 0.0, flag,
+            hipLaunchKernelGGL(compare_kernel<true>, grid, dim3(256), 0, st, (const void*)(ws + w.off_pd), n_chunks,
+                               (const double*)g.partials, g.tiles_m, g.tiles_n, 0.0, 0.0, flag,
                                reinterpret_cast<Report*>(report));
         else
-            hipLaunchKernelGGL(dot_compare_kernel<false>, grid, dim3(256), 0, st, (const void*)(ws + w.off_alpha),
-                               beta_used, (const double*)g.partials, pr.K, g.tiles_n, g.tol_coeff,
+            hipLaunchKernelGGL(compare_kernel<false>, grid, dim3(256), 0, st, (const void*)(ws + w.off_pd), n_chunks,
+                               (const double*)g.partials, g.tiles_m, g.tiles_n, g.tol_coeff,
                                tol_bias_coeff(pr.K, pr.dtype, mode), flag, reinterpret_cast<Report*>(report));
         if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
     }
@@ -621,7 +641,7 @@ int abft_activation_checksum(int M, int K, const void* A, int64_t lda, const abf
     }
     pr.A = A;
     // one slab covering every row: the plain 1 x K checksum
-    return launch_act_checksum(pr, alpha, M, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
+    return launch_act_checksum(pr, alpha, M, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? ABFT_OK
                : ABFT_E_HIP;
 }

@@ -1,0 +1,559 @@
+// Shared device code of the ABFT-protected MFMA GEMM kernels for gfx950 (MI355X).
+//
+// The kernel templates cover the unprotected product, global ABFT (fused output
+// summation, paper Sec. 2.5) and thread-level one-sided ABFT (paper Sec. 5.2.2)
+// carried out per wavefront register tile.  A is M x K (row-major or an NHWC
+// tensor read as an implicit im2col matrix), B is K x N, C is M x N (Sec. 2.1).
+//
+// Data flow per workgroup: 16-byte global loads -> registers -> LDS (double
+// buffered, padded rows) -> ds_read_b128 MFMA fragments -> accumulators.
+#pragma once  // shared device code: types, MFMA wrappers, reductions, tile checksum, epilogue
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace abft {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x16 __attribute__((ext_vector_type(16)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+
+enum { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2 };
+enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2 };
+
+struct Report {  // mirrors abft_report_t
+    double lhs, rhs, tau, worst_ratio;
+    unsigned long long tiles;
+    double frob, l1;
+    unsigned int lock, region;
+};
+
+// Record one comparison in the optional diagnostics block: counts it and, under a small
+// spin lock (one lane per wavefront ever takes it, and only when diagnostics were asked
+// for), keeps the fields of the comparison with the largest ratio -- ties go to the lowest
+// region index, so the outcome does not depend on scheduling.  The spin is bounded; a
+// wavefront that cannot get the lock skips its update.
+__device__ __forceinline__ void report_update(Report* rep, double ratio, double lhs, double rhs, double tau,
+                                              double frob, double l1, unsigned region) {
+    atomicAdd(&rep->tiles, 1ull);
+    bool got = false;
+    for (int spin = 0; spin < (1 << 22) && !got; ++spin) got = atomicCAS(&rep->lock, 0u, 1u) == 0u;
+    if (!got) return;
+    __threadfence();
+    volatile Report* v = rep;
+    const bool first = v->region == 0u;
+    const double cur = v->worst_ratio;
+    if (first || ratio > cur || (ratio == cur && region + 1u < v->region)) {
+        v->worst_ratio = ratio;
+        v->lhs = lhs;
+        v->rhs = rhs;
+        v->tau = tau;
+        v->frob = frob;
+        v->l1 = l1;
+        v->region = region + 1u;
+    }
+    __threadfence();
+    atomicExch(&rep->lock, 0u);
+}
+
+struct GemmArgs {
+    const char* A;
+    const char* B;
+    char* C;
+    int M, N, K;
+    long long lda, ldb, ldc;  // elements
+    // element strides of B for the generic loader: B[k][n] at B + n*b_sn + k*b_sk
+    long long b_sn, b_sk;
+    int a_vec, b_vec;  // operands qualify for 16-byte loads along k
+    // implicit-GEMM geometry (conv != 0): A is an NHWC tensor
+    int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
+    // ABFT outputs
+    double* partials;        // GLOBAL: per workgroup tile {sum, sum of squares, sum of magnitudes, -}
+                             // (int8: the int64 sum in the first slot), indexed tile_m * tiles_n + tile_n
+    unsigned int* flag;      // THREAD: OR-ed with 1 on mismatch
+    Report* report;          // optional diagnostics (THREAD only here)
+    double tol_coeff;        // THREAD: tau = tol_coeff * ||C_tile||_F
+    // fault injection (test hook): flip bit f_bit of accumulator (f_row, f_col)
+    // after k-tile f_kt has been accumulated (f_kt < 0: after the last one)
+    int f_row, f_col, f_bit, f_kt;
+    int tiles_m, tiles_n;    // grid shape in tiles
+};
+
+template <typename To, typename Ti>
+__device__ __forceinline__ To bitcast(const Ti& v) {
+    static_assert(sizeof(To) == sizeof(Ti), "size");
+    return __builtin_bit_cast(To, v);
+}
+
+// ---------------------------------------------------------------------------
+// MFMA wrappers.  Operands travel as 16 bytes per lane.
+// 32x32 shapes: lane l feeds row/column l%32, k-group l/32 (2 groups of 16 bytes);
+//               result register r of lane l is row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+// 16x16 shapes: lane l feeds row/column l%16, k-group l/16 (4 groups);
+//               result register r of lane l is row 4*(l/16) + r, column l%16.
+// ---------------------------------------------------------------------------
+template <int DT, int MI>
+struct Mma;
+
+template <>
+struct Mma<DT_F16, 32> {
+    typedef f32x16 Acc;
+    typedef float AccT;
+    static constexpr int NACC = 16, KBYTES = 32;
+    static __device__ __forceinline__ Acc run(i32x4 a, i32x4 b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(bitcast<f16x8>(a), bitcast<f16x8>(b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<DT_BF16, 32> {
+    typedef f32x16 Acc;
+    typedef float AccT;
+    static constexpr int NACC = 16, KBYTES = 32;
+    static __device__ __forceinline__ Acc run(i32x4 a, i32x4 b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(bitcast<bf16x8>(a), bitcast<bf16x8>(b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<DT_I8, 32> {
+    typedef i32x16 Acc;
+    typedef int AccT;
+    static constexpr int NACC = 16, KBYTES = 32;
+    static __device__ __forceinline__ Acc run(i32x4 a, i32x4 b, Acc c) {
+        return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<DT_F16, 16> {
+    typedef f32x4 Acc;
+    typedef float AccT;
+    static constexpr int NACC = 4, KBYTES = 64;
+    static __device__ __forceinline__ Acc run(i32x4 a, i32x4 b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(bitcast<f16x8>(a), bitcast<f16x8>(b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<DT_BF16, 16> {
+    typedef f32x4 Acc;
+    typedef float AccT;
+    static constexpr int NACC = 4, KBYTES = 64;
+    static __device__ __forceinline__ Acc run(i32x4 a, i32x4 b, Acc c) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bitcast<bf16x8>(a), bitcast<bf16x8>(b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mma<DT_I8, 16> {
+    typedef i32x4 Acc;
+    typedef int AccT;
+    static constexpr int NACC = 4, KBYTES = 64;
+    static __device__ __forceinline__ Acc run(i32x4 a, i32x4 b, Acc c) {
+        return __builtin_amdgcn_mfma_i32_16x16x64_i8(a, b, c, 0, 0, 0);
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Wavefront reductions in registers (DPP within rows of 16 lanes, v_readlane
+// across the four rows).  Fixed order, so results are run-to-run identical.
+// ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ int dpp_i32(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xf, 0xf, true);
+}
+template <int CTRL, typename T>
+__device__ __forceinline__ T dpp_move(T v) {
+    if constexpr (sizeof(T) == 4) {
+        return bitcast<T>(dpp_i32<CTRL>(bitcast<int>(v)));
+    } else {
+        static_assert(sizeof(T) == 8, "4 or 8 bytes");
+        unsigned long long u = bitcast<unsigned long long>(v);
+        int lo = dpp_i32<CTRL>((int)(u & 0xffffffffu));
+        int hi = dpp_i32<CTRL>((int)(u >> 32));
+        u = ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+        return bitcast<T>(u);
+    }
+}
+template <typename T>
+__device__ __forceinline__ T readlane(T v, int lane) {
+    if constexpr (sizeof(T) == 4) {
+        return bitcast<T>(__builtin_amdgcn_readlane(bitcast<int>(v), lane));
+    } else {
+        unsigned long long u = bitcast<unsigned long long>(v);
+        int lo = __builtin_amdgcn_readlane((int)(u & 0xffffffffu), lane);
+        int hi = __builtin_amdgcn_readlane((int)(u >> 32), lane);
+        u = ((unsigned long long)(unsigned)hi << 32) | (unsigned)lo;
+        return bitcast<T>(u);
+    }
+}
+// sum over the 64 lanes, returned in every lane
+template <typename T>
+__device__ __forceinline__ T wave_sum(T v) {
+    v += dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
+    v += dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
+    v += dpp_move<0x141>(v);  // row_half_mirror: the other quad of the half row
+    v += dpp_move<0x140>(v);  // row_mirror: the other half row
+    T a = readlane(v, 0), b = readlane(v, 16), c = readlane(v, 32), d = readlane(v, 48);
+    return (a + b) + (c + d);
+}
+
+// ---------------------------------------------------------------------------
+// Tile configuration
+// ---------------------------------------------------------------------------
+template <int DT_, int MI_, int TM_, int TN_, int WAVES_M_, int WAVES_N_, int BKB_>
+struct Cfg {
+    static constexpr int DT = DT_, MI = MI_, TM = TM_, TN = TN_;
+    static constexpr int WAVES_M = WAVES_M_, WAVES_N = WAVES_N_, BKB = BKB_;
+    static constexpr int ESIZE = (DT_ == DT_I8) ? 1 : 2;  // bytes per input element
+    static constexpr int CSIZE = (DT_ == DT_I8) ? 4 : 2;  // bytes per output element
+    static constexpr int EPC = 16 / ESIZE;                // elements per 16-byte chunk
+    static constexpr int WM = MI_ * TM_, WN = MI_ * TN_;  // wavefront register tile
+    static constexpr int BM = WM * WAVES_M_, BN = WN * WAVES_N_;
+    static constexpr int BK = BKB_ / ESIZE;
+    static constexpr int THREADS = 64 * WAVES_M_ * WAVES_N_;
+    static constexpr int LDS_STRIDE = BKB_ + 16;  // padded row, bytes
+    static constexpr int CPR = BKB_ / 16;         // 16-byte chunks per tile row
+    static constexpr int ROWS_PER_PASS = THREADS / CPR;
+    static constexpr int NA = BM / ROWS_PER_PASS;  // chunks of A per thread per k-tile
+    static constexpr int NB = BN / ROWS_PER_PASS;
+    static constexpr int STAGE_BYTES = (BM + BN) * LDS_STRIDE;
+    static constexpr int LDS_BYTES = 2 * STAGE_BYTES;
+    static_assert(THREADS % CPR == 0, "threads must cover whole tile rows");
+    static_assert(BM % ROWS_PER_PASS == 0 && BN % ROWS_PER_PASS == 0, "tile rows vs threads");
+    static_assert(BKB_ % Mma<DT_, MI_>::KBYTES == 0, "k tile vs MFMA depth");
+};
+
+__device__ __forceinline__ i32x4 ld16(const char* p) { return *reinterpret_cast<const i32x4*>(p); }
+
+// 16 bytes gathered element by element: element e of the chunk is at base + e*stride
+// (bytes) and is taken only while e < n_valid.
+template <int ESIZE>
+__device__ __forceinline__ i32x4 gather16(const char* base, long long stride_bytes, int n_valid) {
+    i32x4 out = {0, 0, 0, 0};
+    if constexpr (ESIZE == 2) {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            unsigned v = 0;
+            if (e < n_valid) v = *reinterpret_cast<const unsigned short*>(base + e * stride_bytes);
+            out[e >> 1] |= (int)(v << (16 * (e & 1)));
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            unsigned v = 0;
+            if (e < n_valid) v = *reinterpret_cast<const unsigned char*>(base + e * stride_bytes);
+            out[e >> 2] |= (int)(v << (8 * (e & 3)));
+        }
+    }
+    return out;
+}
+
+// ---------------------------------------------------------------------------
+// Tile-local weight checksum for the thread-level scheme (Sec. 5.2.1-5.2.2).
+// Input: the TN B-fragments of this k-step (lane = column within the fragment).
+// Output: one B-operand fragment whose columns carry the checksum
+//   chi[k] = sum over the wave tile's columns of B[k][.]
+// split into exactly representable parts, after folding the fragment's columns
+// onto NCOL distinct partial-sum columns with cross-lane moves (registers only):
+//   fp16 : columns [0,H) hold fl16(s), columns [H,2H) hold fl16((s - hi) * 2^11)
+//   bf16 : four groups: hi, mid, lo (three bf16 pieces = 24 bits), zero
+//   int8 : columns [0,H) hold the low signed byte of s, [H,2H) the rest / 256
+// where H = MI/2 (MI/4 for bf16).  Summing the result columns with the matching
+// weights gives sum_k A[i][k] chi[k] (see tile_rhs_weight).
+// ---------------------------------------------------------------------------
+template <int DT, int MI, int TN>
+struct TileChecksum {
+    static __device__ __forceinline__ i32x4 make(const i32x4 (&b)[TN], int lane) {
+        const int col = lane % MI;
+        if constexpr (DT == DT_F16) {
+            float s[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] = 0.f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                f16x8 h = bitcast<f16x8>(b[j]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] += (float)h[e];
+            }
+            f16x8 out;
+            const bool low_part = col >= MI / 2;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float t = s[e] + __shfl_xor(s[e], MI / 2);
+                _Float16 hi = (_Float16)t;
+                _Float16 lo = (_Float16)((t - (float)hi) * 2048.f);
+                out[e] = low_part ? lo : hi;
+            }
+            return bitcast<i32x4>(out);
+        } else if constexpr (DT == DT_BF16) {
+            float s[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) s[e] = 0.f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                bf16x8 h = bitcast<bf16x8>(b[j]);
+#pragma unroll
+                for (int e = 0; e < 8; ++e) s[e] += (float)h[e];
+            }
+            bf16x8 out;
+            const int part = col / (MI / 4);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                float t = s[e] + __shfl_xor(s[e], MI / 2);
+                t = t + __shfl_xor(t, MI / 4);
+                __bf16 hi = (__bf16)t;
+                float d1 = t - (float)hi;
+                __bf16 mid = (__bf16)d1;
+                float d2 = d1 - (float)mid;
+                __bf16 lo = (__bf16)d2;
+                out[e] = part == 0 ? hi : (part == 1 ? mid : (part == 2 ? lo : (__bf16)0.f));
+            }
+            return bitcast<i32x4>(out);
+        } else {
+            int s[16];
+#pragma unroll
+            for (int e = 0; e < 16; ++e) s[e] = 0;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) s[e] += (int)(signed char)(b[j][e >> 2] >> (8 * (e & 3)));
+            }
+            i32x4 out = {0, 0, 0, 0};
+            const bool high_part = col >= MI / 2;
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                int t = s[e] + __shfl_xor(s[e], MI / 2);
+                int lo = (int)(signed char)t;
+                int hi = (t - lo) >> 8;
+                int v = high_part ? hi : lo;
+                out[e >> 2] |= (v & 255) << (8 * (e & 3));
+            }
+            return out;
+        }
+    }
+    // weight of this lane's result column when the checksum product is summed
+    static __device__ __forceinline__ double rhs_weight(int lane) {
+        const int col = lane % MI;
+        if constexpr (DT == DT_F16) return col >= MI / 2 ? (1.0 / 2048.0) : 1.0;
+        if constexpr (DT == DT_BF16) return 1.0;
+        return col >= MI / 2 ? 256.0 : 1.0;
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Per-thread view of the tiling: which wavefront tile this lane works on and which
+// element of C each accumulator register holds.
+// ---------------------------------------------------------------------------
+template <class CFG>
+struct TileCoords {
+    int lane, wave, wave_m, wave_n, lrow, lgrp, bm0, bn0;
+    __device__ __forceinline__ TileCoords(int tile_m, int tile_n) {
+        const int tid = threadIdx.x;
+        lane = tid & 63;
+        wave = tid >> 6;
+        wave_m = wave / CFG::WAVES_N;
+        wave_n = wave % CFG::WAVES_N;
+        lrow = lane % CFG::MI;
+        lgrp = lane / CFG::MI;
+        bm0 = tile_m * CFG::BM;
+        bn0 = tile_n * CFG::BN;
+    }
+    // global row / column of accumulator register r of MFMA tile (i, j) in this lane
+    __device__ __forceinline__ int row(int i, int r) const {
+        int in_tile = (CFG::MI == 32) ? (8 * (r >> 2) + 4 * lgrp + (r & 3)) : (4 * lgrp + r);
+        return bm0 + wave_m * CFG::WM + i * CFG::MI + in_tile;
+    }
+    __device__ __forceinline__ int col(int j) const { return bn0 + wave_n * CFG::WN + j * CFG::MI + lrow; }
+};
+
+// Fault injection (test hook): flips bit f_bit of the accumulator that holds element
+// (f_row, f_col).  The register is identified by a wave-uniform flat index plus the
+// owning lane, so the unrolled loop is a chain of selects.
+template <class CFG>
+__device__ __forceinline__ void inject_fault(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
+                                             const GemmArgs& p, const TileCoords<CFG>& tc) {
+    typedef Mma<CFG::DT, CFG::MI> MMA;
+    typedef typename MMA::AccT AccT;
+    constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
+    const int rr = p.f_row - (tc.bm0 + tc.wave_m * CFG::WM);
+    const int cc = p.f_col - (tc.bn0 + tc.wave_n * CFG::WN);
+    if (rr >= 0 && rr < CFG::WM && cc >= 0 && cc < CFG::WN) {
+        const int i = rr / MI, in_tile = rr % MI;
+        const int j = cc / MI, own_col = cc % MI;
+        int r, own_grp;
+        if (MI == 32) {
+            r = (in_tile >> 3) * 4 + (in_tile & 3);
+            own_grp = (in_tile >> 2) & 1;
+        } else {
+            r = in_tile & 3;
+            own_grp = in_tile >> 2;
+        }
+        const int flat = (i * TN + j) * MMA::NACC + r;
+        const bool mine = (tc.lrow == own_col) && (tc.lgrp == own_grp);
+        const unsigned mask = mine ? (1u << p.f_bit) : 0u;
+#pragma unroll
+        for (int ii = 0; ii < TM; ++ii)
+#pragma unroll
+            for (int jj = 0; jj < TN; ++jj)
+#pragma unroll
+                for (int q = 0; q < MMA::NACC; ++q) {
+                    unsigned w = bitcast<unsigned>(acc[ii][jj][q]);
+                    w ^= ((ii * TN + jj) * MMA::NACC + q == flat) ? mask : 0u;
+                    acc[ii][jj][q] = bitcast<AccT>(w);
+                }
+    }
+}
+
+// Checksum epilogue (taken from the accumulators, before down-conversion) and store of C.
+//  GLOBAL: fused output summation (Sec. 2.5): per workgroup tile {sum, sum of squares,
+//          sum of magnitudes} written to p.partials for the comparison kernel.
+//  THREAD: the wavefront tile's output summation against the sum of its checksum
+//          accumulators (Sec. 5.2.2), compared here; p.flag is touched only on mismatch.
+template <class CFG, int MODE>
+__device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
+                                         typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[MODE == MODE_THREAD ? CFG::TM : 1],
+                                         const GemmArgs& p, int tile_m, int tile_n, char* smem) {
+    typedef Mma<CFG::DT, CFG::MI> MMA;
+    constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
+    constexpr bool IS_INT = CFG::DT == DT_I8;
+    const TileCoords<CFG> tc(tile_m, tile_n);
+    const int tid = threadIdx.x, lane = tc.lane, wave = tc.wave;
+    const int M = p.M, N = p.N;
+    // index of this wavefront's register tile in the grid of wave tiles (row-major)
+    const unsigned wave_tile_index = (unsigned)((tile_m * CFG::WAVES_M + tc.wave_m) * (p.tiles_n * CFG::WAVES_N) +
+                                                tile_n * CFG::WAVES_N + tc.wave_n);
+    (void)wave_tile_index;
+    auto acc_row = [&](int i, int r) { return tc.row(i, r); };
+    auto acc_col = [&](int j) { return tc.col(j); };
+    // ---- checksum epilogue: taken from the accumulators, before down-conversion
+    if constexpr (MODE != MODE_NONE) {
+        if constexpr (IS_INT) {
+            // exact 64-bit sum from 32-bit pieces: low halves (unsigned 16 bits) and high halves
+            // (signed) of up to 256 accumulators each stay far inside int32
+            int s_lo = 0, s_hi = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; ++r) {
+                        s_lo += acc[i][j][r] & 0xffff;
+                        s_hi += acc[i][j][r] >> 16;
+                    }
+            long long s = ((long long)s_hi << 16) + (long long)s_lo;
+            s = wave_sum(s);
+            if constexpr (MODE == MODE_GLOBAL) {
+                long long* red = reinterpret_cast<long long*>(smem);
+                __syncthreads();
+                if (lane == 0) red[wave] = s;
+                __syncthreads();
+                if (tid == 0) {
+                    long long tot = 0;
+                    for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) tot += red[w];
+                    long long* out = reinterpret_cast<long long*>(p.partials) + 4 * ((long long)tile_m * p.tiles_n + tile_n);
+                    out[0] = tot;
+                }
+            } else {
+                int r_lo = 0, r_hi = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; ++r) {
+                        r_lo += chk[i][r] & 0xffff;
+                        r_hi += chk[i][r] >> 16;
+                    }
+                long long rsum = ((long long)r_hi << 16) + (long long)r_lo;
+                const long long w = (lane % MI) >= MI / 2 ? 256 : 1;
+                rsum = wave_sum(rsum * w);
+                if (lane == 0) {
+                    bool bad = s != rsum;
+                    if (bad) atomicOr(p.flag, 1u);
+                    if (p.report)
+                        report_update(p.report, bad ? __builtin_huge_val() : 0.0, (double)s, (double)rsum, 0.0, 0.0, 0.0,
+                                      wave_tile_index);
+                }
+            }
+        } else {
+            // groups of four accumulators are summed in fp32 (three roundings), everything
+            // above that in fp64, so the summation adds nothing visible to the comparison
+            double s = 0.0;
+            float f2 = 0.f, l1 = 0.f;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; r += 4) {
+                        float v0 = acc[i][j][r], v1 = acc[i][j][r + 1], v2 = acc[i][j][r + 2], v3 = acc[i][j][r + 3];
+                        s += (double)((v0 + v1) + (v2 + v3));
+                        f2 += v0 * v0 + v1 * v1 + v2 * v2 + v3 * v3;
+                        if constexpr (MODE == MODE_GLOBAL)
+                            l1 += (__builtin_fabsf(v0) + __builtin_fabsf(v1)) + (__builtin_fabsf(v2) + __builtin_fabsf(v3));
+                    }
+            s = wave_sum(s);
+            double F2 = wave_sum((double)f2);
+            if constexpr (MODE == MODE_GLOBAL) {
+                double L1 = wave_sum((double)l1);
+                double* red = reinterpret_cast<double*>(smem);
+                __syncthreads();
+                if (lane == 0) {
+                    red[3 * wave] = s;
+                    red[3 * wave + 1] = F2;
+                    red[3 * wave + 2] = L1;
+                }
+                __syncthreads();
+                if (tid == 0) {
+                    double ts = 0.0, tf = 0.0, tl = 0.0;
+                    for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) {
+                        ts += red[3 * w];
+                        tf += red[3 * w + 1];
+                        tl += red[3 * w + 2];
+                    }
+                    double* out = p.partials + 4 * ((long long)tile_m * p.tiles_n + tile_n);
+                    out[0] = ts;
+                    out[1] = tf;
+                    out[2] = tl;
+                }
+            } else {
+                double rsum = 0.0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; r += 4)
+                        rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
+                rsum = wave_sum(rsum * TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane));
+                if (lane == 0) {
+                    double tau = p.tol_coeff * __builtin_sqrt(F2);
+                    double res = __builtin_fabs(s - rsum);
+                    // a sum of squares beyond the fp32 range cannot come from a fault-free tile
+                    bool finite = __builtin_isfinite(s) && __builtin_isfinite(rsum) && __builtin_isfinite(F2);
+                    bool bad = !finite || !(res <= tau);
+                    if (bad) atomicOr(p.flag, 1u);
+                    if (p.report) {
+                        double ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+                        report_update(p.report, ratio, s, rsum, tau, __builtin_sqrt(F2), 0.0, wave_tile_index);
+                    }
+                }
+            }
+        }
+    }
+
+    // ---- store C (rounded to the output type)
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = acc_col(j);
+#pragma unroll
+            for (int r = 0; r < MMA::NACC; ++r) {
+                const int row = acc_row(i, r);
+                if (row < M && col < N) {
+                    char* dst = p.C + ((long long)row * p.ldc + col) * CFG::CSIZE;
+                    if constexpr (CFG::DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)acc[i][j][r];
+                    else if constexpr (CFG::DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)acc[i][j][r];
+                    else *reinterpret_cast<int*>(dst) = acc[i][j][r];
+                }
+            }
+        }
+}
+
+}  // namespace abft

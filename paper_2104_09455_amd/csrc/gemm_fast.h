@@ -1,0 +1,236 @@
+// Large-tile ABFT-protected MFMA GEMM kernel for gfx950 (MI355X): the compute-bound path.
+//
+// 256 x 256 x (128 bytes of k) workgroup tile, four wavefronts on a 2 x 2 grid, each
+// owning a 128 x 128 register tile of 4 x 4 MFMA 32x32 blocks (256 accumulators per lane).
+//
+// Data flow: global_load_lds_dwordx4 moves 16-byte chunks from HBM straight into LDS
+// (no staging registers), two LDS stages of 64 KB, rows of 128 bytes stored with an
+// XOR swizzle of the chunk position so that ds_read_b128 fragment reads are free of
+// bank conflicts; out-of-range rows (and convolution padding taps) read from a small
+// block of zeros, so ragged edges need no special case.  Requirements checked by the
+// dispatcher: 16-byte aligned operands with k contiguous, leading dimensions multiples
+// of 16 bytes, K a multiple of the k tile.
+#pragma once
+#include "gemm_common.h"
+
+namespace abft {
+
+// zeros that stand in for rows beyond the matrix edge and for convolution padding
+__device__ __attribute__((aligned(256))) static const char g_zero_chunk[256] = {0};
+
+// Workgroup index -> output tile.  Workgroups are dealt round-robin to the 8 XCDs, each
+// with its own L2; the remap hands every XCD a contiguous run of tiles and walks those in
+// bands of 8 tile rows, so that the tiles resident on an XCD at one time share A row
+// blocks and B column blocks in its L2.
+__device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n, int& tm, int& tn) {
+    const int total = tiles_m * tiles_n;
+    int lin = bid;
+    if ((total & 7) == 0) lin = (bid & 7) * (total >> 3) + (bid >> 3);
+    constexpr int GM = 8;
+    const int per_group = GM * tiles_n;
+    const int group = lin / per_group;
+    const int first_m = group * GM;
+    const int gsz = min(tiles_m - first_m, GM);
+    const int in_group = lin - group * per_group;
+    tn = in_group / gsz;
+    tm = first_m + (in_group - tn * gsz);
+}
+
+template <int DT, int MODE, bool INJ, bool CONV>
+__global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
+    typedef Cfg<DT, 32, 4, 4, 2, 2, 128> CFG;
+    typedef Mma<DT, 32> MMA;
+    typedef typename MMA::Acc Acc;
+    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, BKB = 128;
+    constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
+    constexpr int ROWB = 128;                  // bytes per LDS row
+    constexpr int A_STAGE = BM * ROWB;         // 32 KB
+    constexpr int STAGE = (BM + BN) * ROWB;    // 64 KB
+    constexpr int NQ = 8;                      // 16-byte chunks per thread per operand per k tile
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave_m = wave >> 1, wave_n = wave & 1;
+
+    int tile_m, tile_n;
+    tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    const int bm0 = tile_m * BM, bn0 = tile_n * BN;
+    const int M = p.M, N = p.N;
+    const int nkt = p.K / BK;
+
+    // ---- global -> LDS copy: this lane always fills LDS slot `lane` of a 1 KB block
+    // (8 rows x 8 chunks): row lane/8, position lane%8, which holds chunk (lane%8)^(lane/8)
+    const int crow = lane >> 3;
+    const int ckc = (lane & 7) ^ crow;
+    const char* zero = g_zero_chunk + ckc * 16;
+
+    const char* aptr[NQ];
+    const char* bptr[NQ];
+    unsigned a_valid = 0, b_valid = 0;
+    // convolution: image offset and top-left input pixel of each of this lane's rows
+    long long a_img[CONV ? NQ : 1];
+    int a_ih0[CONV ? NQ : 1], a_iw0[CONV ? NQ : 1];
+    int tap_c = 0, tap_kh = 0, tap_kw = 0;
+#pragma unroll
+    for (int q = 0; q < NQ; ++q) {
+        const int r = (q * 4 + wave) * 8 + crow;
+        const int m = bm0 + r, n = bn0 + r;
+        if (m < M) a_valid |= 1u << q;
+        if (n < N) b_valid |= 1u << q;
+        bptr[q] = n < N ? p.B + ((long long)n * p.ldb) * ESIZE + ckc * 16 : zero;
+        if constexpr (!CONV) {
+            aptr[q] = m < M ? p.A + ((long long)m * p.lda) * ESIZE + ckc * 16 : zero;
+        } else {
+            const int mm = m < M ? m : 0;
+            const int img = mm / (p.OH * p.OW);
+            const int rem = mm - img * (p.OH * p.OW);
+            const int oh = rem / p.OW, ow = rem - oh * p.OW;
+            a_img[q] = (long long)img * p.H * p.W * p.Cin;
+            a_ih0[q] = oh * p.stride - p.pad;
+            a_iw0[q] = ow * p.stride - p.pad;
+            aptr[q] = zero;
+        }
+    }
+    if constexpr (CONV) {
+        const int k = ckc * (16 / ESIZE);
+        const int tap = k / p.Cin;
+        tap_c = k - tap * p.Cin;
+        tap_kh = tap / p.KW;
+        tap_kw = tap - tap_kh * p.KW;
+    }
+
+    auto issue_loads = [&](int stage) {
+        char* abase = smem + stage * STAGE + wave * 1024;
+        char* bbase = abase + A_STAGE;
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            const char* src = aptr[q];
+            if constexpr (CONV) {
+                // a chunk never straddles a filter tap (Cin is a multiple of the chunk length)
+                const int ih = a_ih0[q] + tap_kh, iw = a_iw0[q] + tap_kw;
+                const bool ok = ((a_valid >> q) & 1u) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                src = ok ? p.A + (a_img[q] + ((long long)ih * p.W + iw) * p.Cin + tap_c) * ESIZE : zero;
+            }
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(abase + q * 4096), 16, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NQ; ++q)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
+                                             (__attribute__((address_space(3))) void*)(bbase + q * 4096), 16, 0, 0);
+    };
+    auto advance = [&]() {
+#pragma unroll
+        for (int q = 0; q < NQ; ++q) {
+            if constexpr (!CONV) aptr[q] += ((a_valid >> q) & 1u) ? BKB : 0;
+            bptr[q] += ((b_valid >> q) & 1u) ? BKB : 0;
+        }
+        if constexpr (CONV) {
+            tap_c += BK;
+            while (tap_c >= p.Cin) {
+                tap_c -= p.Cin;
+                if (++tap_kw == p.KW) {
+                    tap_kw = 0;
+                    ++tap_kh;
+                }
+            }
+        }
+    };
+
+    Acc acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    Acc chk[MODE == MODE_THREAD ? TM : 1];
+#pragma unroll
+    for (int i = 0; i < (MODE == MODE_THREAD ? TM : 1); ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) chk[i][r] = 0;
+
+    // ---- fragment reads: lane l reads row l%32 of a 32-row block, k chunk 2*kk + l/32,
+    // stored at position chunk ^ (row & 7); row & 7 == l & 7 for every block
+    const int frow = lane & 31, fgrp = lane >> 5, fx = lane & 7;
+    const int a_off = (wave_m * 128 + frow) * ROWB;
+    const int b_off = A_STAGE + (wave_n * 128 + frow) * ROWB;
+    int pos[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) pos[kk] = ((2 * kk + fgrp) ^ fx) * 16;
+
+    // fragments of one k step: double buffered so that the reads of step kk+1 run under
+    // the MFMAs of step kk
+    i32x4 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](const char* st, int kk, int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+            fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + pos[kk]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+            fb[buf][j] = *reinterpret_cast<const i32x4*>(st + b_off + j * 32 * ROWB + pos[kk]);
+    };
+    auto mma_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
+        if constexpr (MODE == MODE_THREAD) {
+            i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
+        }
+    };
+
+    // Pipeline: tile t lives in LDS stage t & 1 and is copied in while tile t-1 is being
+    // multiplied.  The workgroup barrier sits before the last k step of each tile, whose
+    // fragments are already in registers, so the barrier wait, the issue of the next copies
+    // and the first fragment reads of the next tile all run under those MFMAs.
+    issue_loads(0);
+    if (nkt > 1) {
+        advance();
+        issue_loads(1);
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    __syncthreads();
+    read_frags(smem, 0, 0);
+    for (int kt = 0; kt < nkt; ++kt) {
+        const char* st = smem + (kt & 1) * STAGE;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            read_frags(st, kk + 1, (kk + 1) & 1);
+            mma_step(kk & 1);
+            if constexpr (MODE != MODE_THREAD) {
+#pragma unroll
+                for (int g = 0; g < 8; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                }
+            }
+        }
+        if (kt + 1 < nkt) {
+            // copies of tile kt+1 have landed (this wave's; the barrier makes it everyone's) and
+            // every wave is done reading stage kt & 1, which the copies of tile kt+2 overwrite
+            __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+            __syncthreads();
+            if (kt + 2 < nkt) {
+                advance();
+                issue_loads(kt & 1);
+            }
+            read_frags(smem + ((kt + 1) & 1) * STAGE, 0, 0);
+        }
+        mma_step(1);
+        if constexpr (INJ) {
+            if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
+        }
+    }
+    if constexpr (INJ) {
+        if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
+    }
+    __syncthreads();  // the epilogue reuses LDS
+    epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem);
+}
+
+}  // namespace abft

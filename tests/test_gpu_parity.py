@@ -97,10 +97,10 @@ def test_checksum_vectors(dtype):
                                for b in range(nb)])
             if dtype == "i8":
                 assert np.array_equal(beta.cpu().numpy(), b_ref)
-                assert np.array_equal(beta_b.cpu().numpy().reshape(nb, K), blocks)
+                assert np.array_equal(beta_b.cpu().numpy().reshape(K, nb).T, blocks)
             else:
                 assert np.allclose(beta.cpu().numpy(), b_ref, rtol=1e-12, atol=1e-12)
-                assert np.allclose(beta_b.cpu().numpy().reshape(nb, K), blocks, rtol=1e-12, atol=1e-12)
+                assert np.allclose(beta_b.cpu().numpy().reshape(K, nb).T, blocks, rtol=1e-12, atol=1e-12)
         if dtype == "i8":
             assert np.array_equal(alpha.cpu().numpy(), a_ref)
         else:

@@ -7,6 +7,7 @@
 #include <cmath>
 #include <type_traits>
 #include <cstdio>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -53,19 +54,31 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // ------------------------------------------------------------------------- //
 // tile configuration choice (host logic)
 // ------------------------------------------------------------------------- //
-int pick_cfg(int M, int N, int K, int dt, bool aligned16) {
-    if (M <= 16) return CFG_T;
-    // the large tile's direct-to-LDS loads need whole k tiles of 128 bytes
-    const bool large_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
+// mode: the scheme the product will run with (thread-level prefers wavefront tiles that are
+// wide in N: one checksum MFMA per TN real ones); force >= 0 pins a configuration (tuning aid,
+// environment variable ABFT_FORCE_CFG).
+int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
+    static const int force = [] {
+        const char* e = std::getenv("ABFT_FORCE_CFG");
+        return e ? std::atoi(e) : -1;
+    }();
+    // the direct-to-LDS kernel needs whole k tiles of 128 bytes
+    const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
+    if (force >= 0 && force < CFG_COUNT && (fast_ok || !cfg_info_host(force).fast)) return force;
+    if (M <= 16) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);
         return cdiv(M, ci.bm) * cdiv(N, ci.bn);
     };
-    // fill the 256 compute units before growing the tile
-    if (large_ok && tiles(CFG_L) >= 224) return CFG_L;
-    if (tiles(CFG_M) >= 192) return CFG_M;
-    if (tiles(CFG_S) >= 1024) return CFG_M;
-    return CFG_S;
+    if (fast_ok) {
+        // fill the 256 compute units before growing the tile
+        if (tiles(CFG_F256) >= 224) return CFG_F256;
+        if (tiles(CFG_F128) >= 128) return mode == ABFT_THREAD ? CFG_F128T : CFG_F128;
+        return CFG_F64T;
+    }
+    if (tiles(CFG_G128) >= 192) return CFG_G128;
+    if (tiles(CFG_G64) >= 1024) return CFG_G128;
+    return CFG_G64;
 }
 
 // ------------------------------------------------------------------------- //
@@ -451,7 +464,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
 
     const bool avec = a_vectorisable(pr), bvec = b_vectorisable(pr);
     const bool all16 = avec && bvec;
-    const int cfg = pick_cfg(pr.M, pr.N, pr.K, pr.dtype, all16);
+    const int cfg = pick_cfg(pr.M, pr.N, pr.K, pr.dtype, all16, mode);
     const CfgInfo ci = cfg_info_host(cfg);
     const int bk = ci.bk_bytes / esize(pr.dtype);
 
@@ -666,7 +679,7 @@ int abft_select(int M, int N, int K, int dtype) {
 int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int* tile_m, int* tile_n, int* k_step) {
     if (!valid_dtype(dtype)) return ABFT_E_ENUM;
     if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
-    CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0));
+    CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0, ABFT_THREAD));
     if (tile_m) *tile_m = ci.wm;
     if (tile_n) *tile_n = ci.wn;
     if (k_step) *k_step = ci.bk_bytes / esize(dtype);
@@ -676,7 +689,7 @@ int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int* tile_m, in
 int abft_region_shape(int M, int N, int K, int dtype, int aligned, int* region_m, int* region_n) {
     if (!valid_dtype(dtype)) return ABFT_E_ENUM;
     if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
-    CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0));
+    CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0, ABFT_GLOBAL));
     if (region_m) *region_m = ci.bm;
     if (region_n) *region_n = ci.bn;
     return ABFT_OK;
@@ -724,7 +737,7 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
             const int es = esize(d.dtype);
             const bool b16 = d.b_layout == ABFT_B_NK && aligned16(d.B) && (d.K * es) % 16 == 0 && (d.ldb * es) % 16 == 0;
             const bool a16 = d.has_conv ? (d.conv.Cin * es) % 16 == 0 : (d.K * es) % 16 == 0;
-            L.beta_block_n = cfg_info_host(pick_cfg(d.M, d.N, d.K, d.dtype, a16 && b16)).bn;
+            L.beta_block_n = cfg_info_host(pick_cfg(d.M, d.N, d.K, d.dtype, a16 && b16, ABFT_GLOBAL)).bn;
         }
         if (hipMalloc(&L.beta, (size_t)cdiv(d.N, L.beta_block_n) * d.K * 8) != hipSuccess) { rc = ABFT_E_HIP; break; }
         if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
@@ -801,7 +814,7 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     pr.A = A; pr.B = d.B; pr.ldb = d.ldb; pr.C = C; pr.ldc = ldc;
     // the offline checksums fit the tiling chosen for aligned activations; an input that
     // forces another tiling gets them recomputed into the workspace
-    const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr))).bn;
+    const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr), ABFT_GLOBAL)).bn;
     const void* beta = bn_now == L.beta_block_n ? L.beta : nullptr;
     return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
                        reinterpret_cast<hipStream_t>(stream));

@@ -340,6 +340,72 @@ struct TileChecksum {
 };
 
 // ---------------------------------------------------------------------------
+// Split form of the tile checksum for fp16 (used where the wavefront tile has few rows):
+// no cross-lane step at all.  The column sums s (fp32, one per lane and k) are handed to
+// the matrix unit as two operands, hi = fl16(s) and lo = fl16((s - hi) * 2^11), each
+// multiplied with the A fragments into its own accumulators; the checksum product is
+// sum(hi accumulators) + 2^-11 sum(lo accumulators).  Twice the checksum MFMAs of the
+// folded form, but half the vector work -- the right trade where the matrix unit idles.
+// v_fma_mix_f32 converts and accumulates a half in one instruction.
+// ---------------------------------------------------------------------------
+template <int TN>
+struct TileChecksumSplitF16 {
+    static __device__ __forceinline__ float acc_lo(int packed, float s) {
+        float r;
+        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(s));
+        return r;
+    }
+    static __device__ __forceinline__ float acc_hi(int packed, float s) {
+        float r;
+        asm("v_fma_mix_f32 %0, %1, 1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(s));
+        return r;
+    }
+    // s - (half `sel` of packed), exact
+    static __device__ __forceinline__ float sub_lo(int packed, float s) {
+        float r;
+        asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(s));
+        return r;
+    }
+    static __device__ __forceinline__ float sub_hi(int packed, float s) {
+        float r;
+        asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(s));
+        return r;
+    }
+    static __device__ __forceinline__ void make(const i32x4 (&b)[TN], i32x4& hi, i32x4& lo) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                s0 = acc_lo(b[j][d], s0);
+                s1 = acc_hi(b[j][d], s1);
+            }
+            // round to nearest (v_cvt_pk_f16_f32): hi is within 2^-11 of s, lo within 2^-11 of the
+            // remainder, so hi + 2^-11 lo matches s to 22 bits
+            typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+            f16x2 hp;
+            hp[0] = (_Float16)s0;
+            hp[1] = (_Float16)s1;
+            const int h = bitcast<int>(hp);
+            const float d0 = sub_lo(h, s0) * 2048.f, d1 = sub_hi(h, s1) * 2048.f;
+            f16x2 lp;
+            lp[0] = (_Float16)d0;
+            lp[1] = (_Float16)d1;
+            hi[d] = h;
+            lo[d] = bitcast<int>(lp);
+        }
+    }
+};
+
+// Which form of the tile checksum a configuration uses, and how many checksum
+// accumulators per A fragment that takes.
+template <class CFG>
+struct ChecksumForm {
+    static constexpr bool SPLIT = CFG::DT == DT_F16 && CFG::MI == 32 && CFG::TM <= 2;
+    static constexpr int NCHK = SPLIT ? 2 * CFG::TM : CFG::TM;
+};
+
+// ---------------------------------------------------------------------------
 // Per-thread view of the tiling: which wavefront tile this lane works on and which
 // element of C each accumulator register holds.
 // ---------------------------------------------------------------------------
@@ -410,7 +476,7 @@ __device__ __forceinline__ void inject_fault(typename Mma<CFG::DT, CFG::MI>::Acc
 //          accumulators (Sec. 5.2.2), compared here; p.flag is touched only on mismatch.
 template <class CFG, int MODE>
 __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
-                                         typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[MODE == MODE_THREAD ? CFG::TM : 1],
+                                         typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1],
                                          const GemmArgs& p, int tile_m, int tile_n, char* smem) {
     typedef Mma<CFG::DT, CFG::MI> MMA;
     constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
@@ -515,12 +581,24 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                 }
             } else {
                 double rsum = 0.0;
+                if constexpr (ChecksumForm<CFG>::SPLIT) {
+                    double rlo = 0.0;
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int i = 0; i < TM; ++i)
 #pragma unroll
-                    for (int r = 0; r < MMA::NACC; r += 4)
-                        rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
-                rsum = wave_sum(rsum * TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane));
+                        for (int r = 0; r < MMA::NACC; r += 4) {
+                            rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
+                            rlo += (double)((chk[TM + i][r] + chk[TM + i][r + 1]) + (chk[TM + i][r + 2] + chk[TM + i][r + 3]));
+                        }
+                    rsum = wave_sum(rsum + rlo * (1.0 / 2048.0));
+                } else {
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < MMA::NACC; r += 4)
+                            rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
+                    rsum = wave_sum(rsum * TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane));
+                }
                 if (lane == 0) {
                     double tau = p.tol_coeff * __builtin_sqrt(F2);
                     double res = __builtin_fabs(s - rsum);

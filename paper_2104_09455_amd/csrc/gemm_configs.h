@@ -4,35 +4,49 @@
 
 namespace abft {
 
-// Index into the configuration table.  L/M/S use 32x32 MFMA shapes on square wave
-// grids; T is the skinny path (M <= 16: batch-1 inference) on 16x16 shapes.
-enum CfgId { CFG_L = 0, CFG_M = 1, CFG_S = 2, CFG_T = 3, CFG_COUNT = 4 };
+// Index into the configuration table.
+//  F* run the direct-to-LDS kernel (16-byte aligned operands, K a multiple of 128 bytes):
+//    F256   256 x 256, wavefronts 2 x 2 of 128 x 128, 2 LDS stages   compute-bound products
+//    F128   128 x 128, wavefronts 2 x 2 of  64 x  64, 2 stages       mid-size, unprotected / global
+//    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       mid-size, thread-level (wide tiles:
+//                                                                    one checksum MFMA per four)
+//    F64T    64 x 128, wavefronts 2 x 1 of  32 x 128, 3 stages       small products, any scheme
+//  G* run the generic kernel (any alignment, layout, K):
+//    G128 128 x 128, G64 64 x 64 (32x32 MFMA shapes), G16 16 x 64 (16x16 shapes; M <= 16)
+enum CfgId { CFG_F256 = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
 
 template <int DT, int ID>
 struct CfgOf;
-//                                         MI TM TN WM WN BKB
-template <int DT> struct CfgOf<DT, CFG_L> { typedef Cfg<DT, 32, 4, 4, 2, 2, 128> type; };
-template <int DT> struct CfgOf<DT, CFG_M> { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; };
-template <int DT> struct CfgOf<DT, CFG_S> { typedef Cfg<DT, 32, 1, 1, 2, 2, 128> type; };
-template <int DT> struct CfgOf<DT, CFG_T> { typedef Cfg<DT, 16, 1, 1, 1, 4, 256> type; };
+//                                             MI TM TN WM WN BKB
+template <int DT> struct CfgOf<DT, CFG_F256>  { typedef Cfg<DT, 32, 4, 4, 2, 2, 128> type; static constexpr int NSTAGE = 2; };
+template <int DT> struct CfgOf<DT, CFG_F128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 2; };
+template <int DT> struct CfgOf<DT, CFG_F128T> { typedef Cfg<DT, 32, 1, 4, 4, 1, 128> type; static constexpr int NSTAGE = 2; };
+template <int DT> struct CfgOf<DT, CFG_F64T>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 3; };
+template <int DT> struct CfgOf<DT, CFG_G128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 0; };
+template <int DT> struct CfgOf<DT, CFG_G64>   { typedef Cfg<DT, 32, 1, 1, 2, 2, 128> type; static constexpr int NSTAGE = 0; };
+template <int DT> struct CfgOf<DT, CFG_G16>   { typedef Cfg<DT, 16, 1, 1, 1, 4, 256> type; static constexpr int NSTAGE = 0; };
 
 struct CfgInfo {
-    int bm, bn, bk_bytes, wm, wn, threads, lds_bytes;
+    int bm, bn, bk_bytes, wm, wn, threads, lds_bytes, fast;
 };
 
-template <int DT, int ID>
+template <int ID>
 constexpr CfgInfo cfg_info() {
-    typedef typename CfgOf<DT, ID>::type C;
-    return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, C::LDS_BYTES};
+    typedef typename CfgOf<DT_F16, ID>::type C;  // identical for every dtype (rows / columns / k bytes)
+    constexpr int ns = CfgOf<DT_F16, ID>::NSTAGE;
+    return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS,
+                   ns ? ns * (C::BM + C::BN) * 128 : C::LDS_BYTES, ns ? 1 : 0};
 }
 
-// identical for every dtype (tiles are defined in rows / columns / k-bytes)
 inline CfgInfo cfg_info_host(int id) {
     switch (id) {
-        case CFG_L: return cfg_info<DT_F16, CFG_L>();
-        case CFG_M: return cfg_info<DT_F16, CFG_M>();
-        case CFG_S: return cfg_info<DT_F16, CFG_S>();
-        default: return cfg_info<DT_F16, CFG_T>();
+        case CFG_F256: return cfg_info<CFG_F256>();
+        case CFG_F128: return cfg_info<CFG_F128>();
+        case CFG_F128T: return cfg_info<CFG_F128T>();
+        case CFG_F64T: return cfg_info<CFG_F64T>();
+        case CFG_G128: return cfg_info<CFG_G128>();
+        case CFG_G64: return cfg_info<CFG_G64>();
+        default: return cfg_info<CFG_G16>();
     }
 }
 

@@ -1,13 +1,16 @@
-// Large-tile ABFT-protected MFMA GEMM kernel for gfx950 (MI355X): the compute-bound path.
+// Direct-to-LDS ABFT-protected MFMA GEMM kernel for gfx950 (MI355X): the main path for
+// 16-byte aligned operands.
 //
-// 256 x 256 x (128 bytes of k) workgroup tile, four wavefronts on a 2 x 2 grid, each
-// owning a 128 x 128 register tile of 4 x 4 MFMA 32x32 blocks (256 accumulators per lane).
+// Workgroup tile (32 TM WAVES_M) x (32 TN WAVES_N) x (128 bytes of k); each wavefront owns a
+// (32 TM) x (32 TN) register tile of MFMA 32x32 blocks.  The flagship instance is 256 x 256
+// with four wavefronts of 128 x 128 (256 accumulators per lane); smaller instances with
+// wide-in-N wavefront tiles serve mid-size and bandwidth-bound layers.
 //
 // Data flow: global_load_lds_dwordx4 moves 16-byte chunks from HBM straight into LDS
-// (no staging registers), two LDS stages of 64 KB, rows of 128 bytes stored with an
-// XOR swizzle of the chunk position so that ds_read_b128 fragment reads are free of
-// bank conflicts; out-of-range rows (and convolution padding taps) read from a small
-// block of zeros, so ragged edges need no special case.  Requirements checked by the
+// (no staging registers), NSTAGE LDS stages, rows of 128 bytes stored with an XOR
+// swizzle of the chunk position so that ds_read_b128 fragment reads are free of bank
+// conflicts; out-of-range rows (and convolution padding taps) read from a small block
+// of zeros, so ragged edges need no special case.  Requirements checked by the
 // dispatcher: 16-byte aligned operands with k contiguous, leading dimensions multiples
 // of 16 bytes, K a multiple of the k tile.
 #pragma once
@@ -36,23 +39,40 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
     tm = first_m + (in_group - tn * gsz);
 }
 
-template <int DT, int MODE, bool INJ, bool CONV>
-__global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
-    typedef Cfg<DT, 32, 4, 4, 2, 2, 128> CFG;
+// vmcnt(n) with expcnt / lgkmcnt left open (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
+constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
+
+template <class CFG, int NSTAGE>
+struct FastLayout {
+    static constexpr int ROWB = 128;                            // bytes per LDS row
+    static constexpr int A_STAGE = CFG::BM * ROWB;
+    static constexpr int STAGE = (CFG::BM + CFG::BN) * ROWB;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    static constexpr int WAVES = CFG::WAVES_M * CFG::WAVES_N;
+    static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
+    static constexpr int NQB = CFG::BN / (8 * WAVES);
+    static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
+    static_assert(CFG::MI == 32 && CFG::BKB == 128, "32x32 MFMA shapes, 128-byte k tile");
+    static_assert((NSTAGE - 2) * (NQA + NQB) <= 63, "vmcnt range");
+};
+
+template <class CFG, int NSTAGE, int MODE, bool INJ, bool CONV>
+__global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs p) {
+    typedef FastLayout<CFG, NSTAGE> LAY;
+    constexpr int DT = CFG::DT;
     typedef Mma<DT, 32> MMA;
     typedef typename MMA::Acc Acc;
-    constexpr int TM = 4, TN = 4, BM = 256, BN = 256, BKB = 128;
+    constexpr int TM = CFG::TM, TN = CFG::TN, BM = CFG::BM, BN = CFG::BN, BKB = 128;
     constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
-    constexpr int ROWB = 128;                  // bytes per LDS row
-    constexpr int A_STAGE = BM * ROWB;         // 32 KB
-    constexpr int STAGE = (BM + BN) * ROWB;    // 64 KB
-    constexpr int NQ = 8;                      // 16-byte chunks per thread per operand per k tile
+    constexpr int ROWB = LAY::ROWB, A_STAGE = LAY::A_STAGE, STAGE = LAY::STAGE;
+    constexpr int WAVES = LAY::WAVES, NQA = LAY::NQA, NQB = LAY::NQB;
+    constexpr int NQ = NQA > NQB ? NQA : NQB;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wave_m = wave >> 1, wave_n = wave & 1;
+    const int wave_m = wave / CFG::WAVES_N, wave_n = wave % CFG::WAVES_N;
 
     int tile_m, tile_n;
     tile_of_block(blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
@@ -66,20 +86,24 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
     const int ckc = (lane & 7) ^ crow;
     const char* zero = g_zero_chunk + ckc * 16;
 
-    const char* aptr[NQ];
-    const char* bptr[NQ];
+    const char* aptr[NQA];
+    const char* bptr[NQB];
     unsigned a_valid = 0, b_valid = 0;
     // convolution: image offset and top-left input pixel of each of this lane's rows
-    long long a_img[CONV ? NQ : 1];
-    int a_ih0[CONV ? NQ : 1], a_iw0[CONV ? NQ : 1];
+    long long a_img[CONV ? NQA : 1];
+    int a_ih0[CONV ? NQA : 1], a_iw0[CONV ? NQA : 1];
     int tap_c = 0, tap_kh = 0, tap_kw = 0;
+    (void)NQ;
 #pragma unroll
-    for (int q = 0; q < NQ; ++q) {
-        const int r = (q * 4 + wave) * 8 + crow;
-        const int m = bm0 + r, n = bn0 + r;
-        if (m < M) a_valid |= 1u << q;
+    for (int q = 0; q < NQB; ++q) {
+        const int n = bn0 + (q * WAVES + wave) * 8 + crow;
         if (n < N) b_valid |= 1u << q;
         bptr[q] = n < N ? p.B + ((long long)n * p.ldb) * ESIZE + ckc * 16 : zero;
+    }
+#pragma unroll
+    for (int q = 0; q < NQA; ++q) {
+        const int m = bm0 + (q * WAVES + wave) * 8 + crow;
+        if (m < M) a_valid |= 1u << q;
         if constexpr (!CONV) {
             aptr[q] = m < M ? p.A + ((long long)m * p.lda) * ESIZE + ckc * 16 : zero;
         } else {
@@ -105,7 +129,7 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
         char* abase = smem + stage * STAGE + wave * 1024;
         char* bbase = abase + A_STAGE;
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
+        for (int q = 0; q < NQA; ++q) {
             const char* src = aptr[q];
             if constexpr (CONV) {
                 // a chunk never straddles a filter tap (Cin is a multiple of the chunk length)
@@ -114,19 +138,20 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
                 src = ok ? p.A + (a_img[q] + ((long long)ih * p.W + iw) * p.Cin + tap_c) * ESIZE : zero;
             }
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(abase + q * 4096), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(abase + q * WAVES * 1024), 16, 0, 0);
         }
 #pragma unroll
-        for (int q = 0; q < NQ; ++q)
+        for (int q = 0; q < NQB; ++q)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
-                                             (__attribute__((address_space(3))) void*)(bbase + q * 4096), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(bbase + q * WAVES * 1024), 16, 0, 0);
     };
     auto advance = [&]() {
+        if constexpr (!CONV) {
 #pragma unroll
-        for (int q = 0; q < NQ; ++q) {
-            if constexpr (!CONV) aptr[q] += ((a_valid >> q) & 1u) ? BKB : 0;
-            bptr[q] += ((b_valid >> q) & 1u) ? BKB : 0;
+            for (int q = 0; q < NQA; ++q) aptr[q] += ((a_valid >> q) & 1u) ? BKB : 0;
         }
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) bptr[q] += ((b_valid >> q) & 1u) ? BKB : 0;
         if constexpr (CONV) {
             tap_c += BK;
             while (tap_c >= p.Cin) {
@@ -146,17 +171,19 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-    Acc chk[MODE == MODE_THREAD ? TM : 1];
+    constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
+    constexpr int NCHK = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1;
+    Acc chk[NCHK];
 #pragma unroll
-    for (int i = 0; i < (MODE == MODE_THREAD ? TM : 1); ++i)
+    for (int i = 0; i < NCHK; ++i)
 #pragma unroll
         for (int r = 0; r < 16; ++r) chk[i][r] = 0;
 
     // ---- fragment reads: lane l reads row l%32 of a 32-row block, k chunk 2*kk + l/32,
     // stored at position chunk ^ (row & 7); row & 7 == l & 7 for every block
     const int frow = lane & 31, fgrp = lane >> 5, fx = lane & 7;
-    const int a_off = (wave_m * 128 + frow) * ROWB;
-    const int b_off = A_STAGE + (wave_n * 128 + frow) * ROWB;
+    const int a_off = (wave_m * CFG::WM + frow) * ROWB;
+    const int b_off = A_STAGE + (wave_n * CFG::WN + frow) * ROWB;
     int pos[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) pos[kk] = ((2 * kk + fgrp) ^ fx) * 16;
@@ -177,51 +204,68 @@ __global__ __launch_bounds__(256) void gemm_fast_kernel(const GemmArgs p) {
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
-        if constexpr (MODE == MODE_THREAD) {
+        if constexpr (MODE == MODE_THREAD && SPLIT) {
+            i32x4 xh, xl;
+            TileChecksumSplitF16<TN>::make(fb[buf], xh, xl);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                chk[i] = MMA::run(fa[buf][i], xh, chk[i]);
+                chk[TM + i] = MMA::run(fa[buf][i], xl, chk[TM + i]);
+            }
+        } else if constexpr (MODE == MODE_THREAD) {
             i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
 #pragma unroll
             for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
         }
     };
 
-    // Pipeline: tile t lives in LDS stage t & 1 and is copied in while tile t-1 is being
-    // multiplied.  The workgroup barrier sits before the last k step of each tile, whose
-    // fragments are already in registers, so the barrier wait, the issue of the next copies
-    // and the first fragment reads of the next tile all run under those MFMAs.
-    issue_loads(0);
-    if (nkt > 1) {
-        advance();
-        issue_loads(1);
+    // Pipeline: tile t lives in LDS stage t % NSTAGE and is copied in while earlier tiles are
+    // being multiplied.  The workgroup barrier sits before the last k step of each tile,
+    // whose fragments are already in registers, so the barrier wait, the issue of the next
+    // copies and the first fragment reads of the next tile all run under those MFMAs.
+    constexpr int NL = NQA + NQB;  // copies per wave per tile
+#pragma unroll
+    for (int t = 0; t < NSTAGE; ++t) {
+        if (t < nkt) {
+            if (t > 0) advance();
+            issue_loads(t);
+        }
     }
-    __builtin_amdgcn_s_waitcnt(0x0F70);  // vmcnt(0)
+    if (nkt >= NSTAGE) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NL));  // tile 0 has landed
+    else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
     read_frags(smem, 0, 0);
+    int stage = 0;
     for (int kt = 0; kt < nkt; ++kt) {
-        const char* st = smem + (kt & 1) * STAGE;
+        const char* st = smem + stage * STAGE;
 #pragma unroll
         for (int kk = 0; kk < 3; ++kk) {
             read_frags(st, kk + 1, (kk + 1) & 1);
             mma_step(kk & 1);
             if constexpr (MODE != MODE_THREAD) {
+                constexpr int NF = TM + TN, NM = TM * TN;
 #pragma unroll
-                for (int g = 0; g < 8; ++g) {
-                    __builtin_amdgcn_sched_group_barrier(0x008, 2, 0);  // 2 MFMA
-                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                for (int g = 0; g < NF; ++g) {
+                    __builtin_amdgcn_sched_group_barrier(0x008, (NM + NF - 1) / NF, 0);  // MFMAs
+                    __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                    // 1 LDS read
                 }
             }
         }
+        const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
         if (kt + 1 < nkt) {
-            // copies of tile kt+1 have landed (this wave's; the barrier makes it everyone's) and
-            // every wave is done reading stage kt & 1, which the copies of tile kt+2 overwrite
-            __builtin_amdgcn_s_waitcnt(0x0070);  // vmcnt(0) lgkmcnt(0)
+            // this wave's copies of tile kt+1 have landed (the barrier makes it everyone's) and
+            // every wave is done reading this stage, which the copies of tile kt+NSTAGE overwrite
+            if (kt + NSTAGE < nkt) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 2) * NL) & ~0x0F00);
+            else __builtin_amdgcn_s_waitcnt(0x0070);  // tail: vmcnt(0) lgkmcnt(0)
             __syncthreads();
-            if (kt + 2 < nkt) {
+            if (kt + NSTAGE < nkt) {
                 advance();
-                issue_loads(kt & 1);
+                issue_loads(stage);
             }
-            read_frags(smem + ((kt + 1) & 1) * STAGE, 0, 0);
+            read_frags(smem + next * STAGE, 0, 0);
         }
         mma_step(1);
+        stage = next;
         if constexpr (INJ) {
             if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
         }

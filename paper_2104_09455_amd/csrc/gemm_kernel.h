@@ -187,9 +187,11 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = 0;
-    Acc chk[MODE == MODE_THREAD ? TM : 1];
+    constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
+    constexpr int NCHK = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1;
+    Acc chk[NCHK];
 #pragma unroll
-    for (int i = 0; i < (MODE == MODE_THREAD ? TM : 1); ++i)
+    for (int i = 0; i < NCHK; ++i)
 #pragma unroll
         for (int r = 0; r < MMA::NACC; ++r) chk[i][r] = 0;
 
@@ -222,7 +224,15 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(a[i], b[j], acc[i][j]);
-            if constexpr (MODE == MODE_THREAD) {
+            if constexpr (MODE == MODE_THREAD && SPLIT) {
+                i32x4 xh, xl;
+                TileChecksumSplitF16<TN>::make(b, xh, xl);
+#pragma unroll
+                for (int i = 0; i < TM; ++i) {
+                    chk[i] = MMA::run(a[i], xh, chk[i]);
+                    chk[TM + i] = MMA::run(a[i], xl, chk[TM + i]);
+                }
+            } else if constexpr (MODE == MODE_THREAD) {
                 i32x4 x = TileChecksum<CFG::DT, MI, TN>::make(b, lane);
 #pragma unroll
                 for (int i = 0; i < TM; ++i) chk[i] = MMA::run(a[i], x, chk[i]);

@@ -118,3 +118,67 @@ def test_fault_campaign_global_4096(dtype, trials):
     assert must > 0
     if dtype != "i8":
         assert mustnot > 0
+
+
+def test_ragged_large_uses_the_big_tile_and_matches():
+    """M, N not multiples of the 256-wide tile: edge tiles read zeros, results and checksums
+    are unaffected.  4000 x 4100 x 512 runs on the large-tile kernel."""
+    from gpu_util import c_to_host, c_close
+    M, N, K = 4000, 4100, 512
+    big = Big(M, N, K, "f16", seed=5)
+    assert (big.rm, big.rn) == (256, 256)
+    rows = np.array([0, 255, 256, 3839, 3840, 3999])
+    ref = oracle.gemm_rows(big.A, big.Bm, "f16", rows)
+    for mode in (B.NONE, B.GLOBAL, B.THREAD):
+        print(f"case ragged mode={mode}", flush=True)
+        flag, rep = big.run(mode)
+        assert c_close(c_to_host(big.dC[rows.tolist()], "f16"), ref, "f16")
+        assert flag == 0
+        if mode == B.GLOBAL:
+            assert rep.tiles == 16 * 17 and rep.worst_ratio < 0.5
+            # the reported region against the oracle's evaluation of the same block
+            r = rep.region - 1
+            r0, c0 = (r // 17) * 256, (r % 17) * 256
+            chk = oracle.region_check(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]),
+                                      oracle.gemm(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]), "f16"),
+                                      "f16", 0, min(256, M - r0), 0, min(256, N - c0))
+            assert rep.rhs == pytest.approx(chk.rhs, rel=1e-11, abs=1e-9)
+            assert rep.tau == pytest.approx(chk.tau, rel=1e-3)
+    # injected fault in the last (clipped) tile row / column is still seen
+    for mode in (B.GLOBAL, B.THREAD):
+        flag, _ = big.run(mode, inject=B.Fault(3999, 4099, 29, -1))
+        assert flag == 1
+
+
+def test_large_conv_on_the_big_tile():
+    """3x3 conv 64->256 on 56x56, batch 20 (M = 62720, K = 576): implicit GEMM through the
+    direct-to-LDS kernel, sampled output pixels against the oracle's im2col product."""
+    import ctypes
+    import torch
+    from gpu_util import to_dev, c_to_host, c_close, read_report, DEV
+    c = wl.Conv(20, 56, 56, 64, 256, 3, 3, 1, 1)
+    x, Wm = wl.conv_operands(c, "f16", seed=6)
+    M, K, N = c.batch * c.OH * c.OW, 576, 256
+    assert B.abft_region_shape(M, N, K, B.F16, True) == (256, 256)
+    # oracle on sampled output pixels: lower two images only (pixels are independent per image)
+    A2 = oracle.im2col(x[[0, 19]], "f16", 3, 3, 1, 1)
+    rows2 = np.array([0, 55, 56 * 56 - 1, 56 * 56, 2 * 56 * 56 - 1, 3000])
+    ref = oracle.gemm_rows(A2, Wm, "f16", rows2)
+    rows = np.where(rows2 < 3136, rows2, rows2 - 3136 + 19 * 3136)
+    dx, dB = to_dev(x, "f16"), to_dev(np.ascontiguousarray(Wm.T), "f16")
+    dC = torch.zeros((M, N), dtype=torch.float16, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    rep = torch.zeros(ctypes.sizeof(B.Report), dtype=torch.uint8, device=DEV)
+    wsb = B.abft_workspace_bytes(M, N, K, B.F16, B.GLOBAL)
+    ws = torch.zeros(wsb, dtype=torch.uint8, device=DEV)
+    conv = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad)
+    for mode in (B.NONE, B.GLOBAL, B.THREAD):
+        print(f"case big conv mode={mode}", flush=True)
+        flag.zero_(); rep.zero_(); dC.zero_()
+        B.abft_conv(conv, N, dx, dB, K, B.B_NK, dC, N, B.F16, mode, workspace=ws, workspace_bytes=wsb,
+                    fault_flag=flag, report=rep)
+        torch.cuda.synchronize()
+        assert c_close(c_to_host(dC[rows.tolist()], "f16"), ref, "f16")
+        assert int(flag.item()) == 0
+        if mode != B.NONE:
+            assert read_report(rep).worst_ratio < 0.5

@@ -186,5 +186,8 @@ def test_auto_mode_follows_selector():
     from gpu_util import run_gemm, c_close
     A, Bm = wl.gemm_operands(64, 64, 64, "f16", seed=42)
     res = run_gemm(A, Bm, "f16", B.AUTO)
-    assert res.flag == 0 and res.report.tiles >= 4  # 64^3 is bandwidth bound -> thread-level tiles
+    # 64^3 is bandwidth bound -> thread-level: one comparison per wavefront tile, not per workgroup tile
+    tm, tn, _ = B.abft_tile_shape(64, 64, 64, B.F16)
+    assert res.flag == 0 and res.report.tiles == -(-64 // tm) * -(-64 // tn) and res.report.tau > 0
+    assert res.report.l1 == 0.0   # the ||C||_1 term belongs to the global scheme only
     assert c_close(res.C, oracle.gemm(A, Bm, "f16"), "f16")

@@ -98,7 +98,7 @@ class LayerRun:
         _, rn = B.abft_region_shape(M, N, K, self.dt, aligned)
         self.beta = torch.zeros(-(-N // rn) * K, dtype=torch.float64, device=dev)  # int64 for i8: same size
         B.abft_weight_checksum(K, N, self.B, K, B.B_NK, self.dt, self.beta, block_n=rn)  # offline step (Sec. 2.5)
-        self.wsb = B.abft_workspace_bytes(M, N, K, self.dt, B.GLOBAL)
+        self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
         self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=dev)
         self.pick = B.abft_select(M, N, K, self.dt)
         self.conv = None
@@ -261,27 +261,33 @@ def main():
     dom_i = max(range(len(runs)), key=lambda i: rows[i]["us_global" if runs[i].pick == B.GLOBAL else "us_thread"])
     dom = runs[dom_i]
 
-    # ---- the timed region: exactly `steps` protected passes
+    # ---- a plan over the workload: per-layer scheme by the selector, offline weight checksums
+    def plan_layer(lr):
+        L = lr.layer
+        conv = lr.conv if lr.conv is not None else B.Conv()
+        return B.Layer(L.M, L.N, L.K, lr.dt, B.B_NK, 1 if lr.conv is not None else 0, conv, lr.B.data_ptr(), L.K)
+    plan = B.abft_plan_create([plan_layer(lr) for lr in runs], profile=False)
+    io = B.PlanIO([lr.A for lr in runs], [lr.layer.K for lr in runs], [lr.C for lr in runs],
+                  [lr.layer.N for lr in runs])
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    assert [B.abft_plan_mode(plan, i) for i in range(len(runs))] == [lr.pick for lr in runs]
+
+    # ---- the timed region: exactly `steps` protected passes, one library call per pass
     for _ in range(warmup):
-        for lr in runs:
-            lr.run(lr.pick, stream)
+        B.abft_plan_run_all(plan, io, flag, -1, stream)
     ev = [(hip.event(), hip.event()) for _ in range(steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for s in range(steps):
-        for i, lr in enumerate(runs):
-            if i == dom_i:
-                B.abft_set_kernel_events(ev[s][0], ev[s][1])
-                lr.run(lr.pick, stream)
-                B.abft_set_kernel_events(None, None)
-            else:
-                lr.run(lr.pick, stream)
+        B.abft_set_kernel_events(ev[s][0], ev[s][1])
+        B.abft_plan_run_all(plan, io, flag, dom_i, stream)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
+    B.abft_set_kernel_events(None, None)
     ms_per_step = 1000.0 * wall / steps
     total_flops = sum(lr.flops for lr in runs)
     value = total_flops / (wall / steps) / 1e12
-    flagged = sum(int(lr.flag.item()) for lr in runs)
+    flagged = int(flag.item())
 
     kern_us = float(np.mean([1000.0 * hip.elapsed_ms(a, b) for a, b in ev]))
     for a, b in ev:
@@ -302,13 +308,41 @@ def main():
                  "algorithmic_per_launch": dom.flops if compute_bound else dom.bytes})
 
     # unprotected pass for the whole-model overhead (same kernels, mode NONE), outside the timed region
+    for i in range(len(runs)):
+        B.abft_plan_set_mode(plan, i, B.NONE)
+    for _ in range(warmup):
+        B.abft_plan_run_all(plan, io, flag, -1, stream)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
-        for lr in runs:
-            lr.run(B.NONE, stream)
+        B.abft_plan_run_all(plan, io, flag, -1, stream)
     torch.cuda.synchronize()
     wall_none = time.perf_counter() - t0
+    for i in range(len(runs)):
+        B.abft_plan_set_mode(plan, i, B.AUTO)
+
+    # the same protected pass captured once into a HIP graph and replayed (no host launch cost)
+    graph_ms = None
+    try:
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(cap):
+            B.abft_plan_run_all(plan, io, flag, -1, cap)
+        cap.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            B.abft_plan_run_all(plan, io, flag, -1, cap)
+        for _ in range(max(3, warmup // 10)):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        graph_ms = 1000.0 * (time.perf_counter() - t0) / steps
+    except Exception as e:  # reported, never fatal
+        graph_ms = repr(e)
+    B.abft_plan_destroy(plan)
 
     out = {
         "metric": "protected GEMM TFLOP/s and ABFT overhead % vs unprotected MFMA GEMM per layer",
@@ -320,6 +354,9 @@ def main():
         "overhead_pct_host_timed": round(100 * (wall / wall_none - 1), 2),
         "overhead_pct_device_timed": summarize(rows)["ovh_selector_pct"],
         "false_alarms": flagged,
+        "graph_replay": None if not isinstance(graph_ms, float) else {
+            "ms_per_step": round(graph_ms, 5), "tflops": round(total_flops / (graph_ms * 1e-3) / 1e12, 3)},
+        "graph_replay_error": graph_ms if isinstance(graph_ms, str) else None,
         "roofline": roof,
         "summary": summarize(rows),
         "layers": rows if len(rows) <= 16 else rows[:3] + [{"...": f"{len(rows) - 6} more"}] + rows[-3:],

@@ -73,7 +73,9 @@ typedef enum { ABFT_B_NK = 0, ABFT_B_KN = 1 } abft_blayout_t;
  * before the checksum epilogue.  k_after >= 0: the running accumulator is flipped
  * once the products with k < k_after have been added (must be a positive multiple
  * of the k_step reported by abft_tile_shape and < K); the corruption then stays
- * until the end of the loop. */
+ * until the end of the loop.  When the product is split along k (abft_k_slices, abft_k_ways),
+ * the running accumulator is that of the part holding k_after - 1, and k_after < 0 flips the
+ * finished partial accumulator of the part holding K - 1. */
 typedef struct {
     int64_t row, col;
     int32_t bit;
@@ -116,7 +118,11 @@ typedef struct {
  *         workspace first.  THREAD never
  *         reads it: it recomputes tile-local weight checksums in registers (Sec. 5.2.1).
  *   workspace / workspace_bytes: scratch of at least abft_workspace_bytes(...) bytes,
- *         256-byte aligned; may be NULL when that size is 0.
+ *         256-byte aligned; may be NULL when that size is 0.  Its first 4096 bytes must be
+ *         zero before the first call that uses it; every call leaves them zero, so one
+ *         buffer can be reused by calls on the same stream without clearing it again.
+ *         GLOBAL requires it.  NONE / THREAD use it to split small products along k
+ *         (abft_k_slices) and simply run unsplit when it is NULL or too small.
  *   fault_flag: device uint32, OR-ed with 1 when a comparison fails.  The caller
  *         zeroes it.  May be NULL only for ABFT_NONE.
  *   report: optional device abft_report_t (zero-filled by the caller), else NULL.
@@ -135,7 +141,7 @@ int abft_conv(const abft_conv_t *conv /* host */, int N, const void *x, const vo
               void *workspace, size_t workspace_bytes, uint32_t *fault_flag, abft_report_t *report,
               const abft_fault_t *inject, void *stream);
 
-/* Bytes of workspace abft_gemm / abft_conv need for this problem (0 for NONE / THREAD). */
+/* Bytes of workspace abft_gemm / abft_conv want for this problem (0 when none is used). */
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
 
 /* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns, stored
@@ -177,6 +183,21 @@ int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int *tile_m, in
  * columns.  `aligned` as for abft_tile_shape. */
 int abft_region_shape(int M, int N, int K, int dtype, int aligned, int *region_m, int *region_n);
 
+/* Split along k: small products run as n_slices workgroups per output tile, slice s
+ * multiplying k in [bounds[s], bounds[s+1]); the slices' partial tiles are added in slice
+ * order by the workgroup that finishes last (bit-reproducible).  THREAD makes its tile
+ * comparisons per slice, on the partial products.  bounds (n_slices + 1 entries, at most
+ * max_bounds) and n_slices may be NULL.  n_slices = 1: not split. */
+int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int *n_slices, int *bounds,
+                  int max_bounds);
+
+/* Interleaved split along k inside a workgroup: `ways` wavefronts share each register tile,
+ * wavefront w multiplying the k with (k / step) % ways == w; their partial tiles are added in
+ * wavefront order at the end (bit-reproducible).  THREAD makes its tile comparisons per
+ * wavefront, on those partial products.  ways = 1: not split.  Combines with abft_k_slices
+ * (each slice is then interleaved). */
+int abft_k_ways(int M, int N, int K, int dtype, int aligned, int mode, int *ways, int *step);
+
 /* Comparison tolerance (the paper states none; Sec. 2.4 step 4 says "compare"): a
  * comparison passes when |lhs - rhs| <= coeff * ||C_S||_F, where C_S is the part of C
  * the comparison covers (all of C for GLOBAL, one tile for THREAD) and ||.||_F is taken
@@ -209,6 +230,13 @@ int abft_plan_create(abft_plan_t **plan, const abft_layer_t *layers, int n_layer
 /* Run layer `layer` of the plan with its chosen scheme on input A (or NHWC x), output C. */
 int abft_plan_run(abft_plan_t *plan, int layer, const void *A, int64_t lda, void *C, int64_t ldc,
                   uint32_t *fault_flag, void *stream);
+/* Run every layer of the plan in order in one call: A[i], lda[i], C[i], ldc[i] (host arrays of
+ * device pointers / leading dimensions) are layer i's input and output.  event_layer selects
+ * the one layer whose product kernel the abft_set_kernel_events hook brackets (-1: none). */
+int abft_plan_run_all(abft_plan_t *plan, const void *const *A, const int64_t *lda, void *const *C,
+                      const int64_t *ldc, uint32_t *fault_flag, int event_layer, void *stream);
+/* Override the scheme of a layer (abft_mode_t; ABFT_AUTO re-applies abft_select). */
+int abft_plan_set_mode(abft_plan_t *plan, int layer, int mode);
 /* Scheme chosen for a layer (abft_mode_t) or a negative error. */
 int abft_plan_mode(const abft_plan_t *plan, int layer);
 /* Times measured at creation with profile = 1, in microseconds: out[0..2] = NONE, GLOBAL,

@@ -54,6 +54,7 @@ EXPORTS = [
     "abft_select", "abft_tile_shape", "abft_tolerance_coeff", "abft_plan_create", "abft_plan_run",
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
+    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways",
 ]
 
 _lib = None
@@ -101,6 +102,15 @@ def lib() -> ctypes.CDLL:
     L.abft_plan_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(Layer), ci, ci, vp]
     L.abft_plan_run.restype = ci
     L.abft_plan_run.argtypes = [vp, ci, vp, i64, vp, i64, vp, vp]
+    L.abft_plan_run_all.restype = ci
+    L.abft_plan_run_all.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(vp),
+                                    ctypes.POINTER(i64), vp, ci, vp]
+    L.abft_plan_set_mode.restype = ci
+    L.abft_plan_set_mode.argtypes = [vp, ci, ci]
+    L.abft_k_slices.restype = ci
+    L.abft_k_slices.argtypes = [ci, ci, ci, ci, ci, ci, ip, ip, ci]
+    L.abft_k_ways.restype = ci
+    L.abft_k_ways.argtypes = [ci, ci, ci, ci, ci, ci, ip, ip]
     L.abft_plan_mode.restype = ci
     L.abft_plan_mode.argtypes = [vp, ci]
     L.abft_plan_times.restype = ci
@@ -181,6 +191,32 @@ def abft_tile_shape(M, N, K, dtype, aligned=True):
     return tm.value, tn.value, ks.value
 
 
+def abft_k_slices(M, N, K, dtype, mode, aligned=True):
+    """[(k_begin, k_end), ...] of the slices the product is split into along k."""
+    n = ctypes.c_int()
+    bounds = (ctypes.c_int * 17)()
+    _check(lib().abft_k_slices(M, N, K, dtype, 1 if aligned else 0, mode, ctypes.byref(n), bounds, 17))
+    return [(bounds[i], bounds[i + 1]) for i in range(n.value)]
+
+
+def abft_k_ways(M, N, K, dtype, mode, aligned=True):
+    """(ways, step): wavefront w of `ways` multiplies the k with (k // step) % ways == w."""
+    w, st = ctypes.c_int(), ctypes.c_int()
+    _check(lib().abft_k_ways(M, N, K, dtype, 1 if aligned else 0, mode, ctypes.byref(w), ctypes.byref(st)))
+    return w.value, st.value
+
+
+def abft_k_parts(M, N, K, dtype, mode, aligned=True):
+    """The parts the product is split into along k, as lists of k indices: every contiguous
+    slice of abft_k_slices, interleaved as abft_k_ways says.  One part = range(K): not split."""
+    ways, step = abft_k_ways(M, N, K, dtype, mode, aligned)
+    parts = []
+    for k0, k1 in abft_k_slices(M, N, K, dtype, mode, aligned):
+        for w in range(ways):
+            parts.append([k for k in range(k0, k1) if (k // step) % ways == w])
+    return parts
+
+
 def abft_tolerance_coeff(K, dtype, mode) -> float:
     return lib().abft_tolerance_coeff(K, dtype, mode)
 
@@ -235,6 +271,26 @@ def abft_plan_create(layers, profile=False, stream=None) -> int:
 
 def abft_plan_run(plan, layer, A, lda, C, ldc, fault_flag, stream=None) -> None:
     _check(lib().abft_plan_run(plan, layer, _ptr(A), lda, _ptr(C), ldc, _ptr(fault_flag), _stream(stream)))
+
+
+class PlanIO:
+    """Marshalled per-layer input / output pointers for abft_plan_run_all (built once, reused)."""
+
+    def __init__(self, A, lda, C, ldc):
+        n = len(A)
+        self.A = (ctypes.c_void_p * n)(*[_ptr(a) for a in A])
+        self.C = (ctypes.c_void_p * n)(*[_ptr(c) for c in C])
+        self.lda = (ctypes.c_int64 * n)(*lda)
+        self.ldc = (ctypes.c_int64 * n)(*ldc)
+
+
+def abft_plan_run_all(plan, io: PlanIO, fault_flag, event_layer=-1, stream=None) -> None:
+    _check(lib().abft_plan_run_all(plan, io.A, io.lda, io.C, io.ldc, _ptr(fault_flag), event_layer,
+                                   _stream(stream)))
+
+
+def abft_plan_set_mode(plan, layer, mode) -> None:
+    _check(lib().abft_plan_set_mode(plan, layer, mode))
 
 
 def abft_plan_mode(plan, layer) -> int:

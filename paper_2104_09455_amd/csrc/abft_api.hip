@@ -38,6 +38,10 @@ constexpr double U_ACC = 5.9604644775390625e-08;  // 2^-24
 constexpr double U_CHI_F16 = 2.384185791015625e-07;  // 2^-22
 constexpr double U_CHI_BF16 = 1.1920928955078125e-07;  // 2^-23
 
+// every workspace starts with a header that holds the split-K arrival counters; it must be
+// zero before the first call and is left zero by every call
+constexpr size_t WS_HEADER = 4096;
+
 // MI355X spec-sheet peaks (dense) and HBM3E bandwidth
 constexpr double PEAK_F16 = 2516.6e12, PEAK_I8 = 5033.2e12, HBM_BW = 8.0e12;
 double g_cmr_override[3] = {0.0, 0.0, 0.0};
@@ -74,11 +78,48 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // fill the 256 compute units before growing the tile
         if (tiles(CFG_F256) >= 224) return CFG_F256;
         if (tiles(CFG_F128) >= 128) return mode == ABFT_THREAD ? CFG_F128T : CFG_F128;
-        return CFG_F64T;
+        if (tiles(CFG_F64T) > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
+        // at most one workgroup per compute unit: deep pipeline and more wavefronts per tile;
+        // very few tiles with a long k loop are split along k across workgroups instead
+        const long long nkt = ((long long)K * esize(dt)) / 128;
+        return (tiles(CFG_F64T) <= 64 && nkt >= 64) ? CFG_F64S : CFG_F64K;
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;
     if (tiles(CFG_G64) >= 1024) return CFG_G128;
     return CFG_G64;
+}
+
+// Split-K factor: small grids of the direct-to-LDS kernel are cut along k until about one
+// workgroup per compute unit exists (at most 8 slices, at least one k tile each).  The
+// global scheme compares whole-K tile sums and is never split.
+int pick_ksplit(int M, int N, int K, int dt, int cfg, int mode) {
+    static const int force = [] {
+        const char* e = std::getenv("ABFT_FORCE_KSPLIT");
+        return e ? std::atoi(e) : -1;
+    }();
+    const CfgInfo ci = cfg_info_host(cfg);
+    if (cfg != CFG_F64S || mode == ABFT_GLOBAL) return 1;
+    const long long tiles = cdiv(M, ci.bm) * cdiv(N, ci.bn);
+    const long long nkt = ((long long)K * esize(dt)) / ci.bk_bytes;
+    long long ks = 256 / tiles;
+    // adding the partial tiles costs about as much as several k tiles: keep at least 16 per slice
+    if (ks > nkt / 16) ks = nkt / 16;
+    if (ks > 4) ks = 4;
+    if (force >= 1) ks = force > nkt ? nkt : force;
+    return ks < 1 ? 1 : (int)ks;
+}
+
+struct SplitLayout {
+    size_t off_counters, off_part, total;
+};
+SplitLayout split_layout(int M, int N, int cfg, int ksplit) {
+    const CfgInfo ci = cfg_info_host(cfg);
+    const size_t tiles = (size_t)(cdiv(M, ci.bm) * cdiv(N, ci.bn));
+    SplitLayout s;
+    s.off_counters = 0;  // inside the reserved header (tiles < 256 whenever a product is split)
+    s.off_part = WS_HEADER;
+    s.total = align_up(s.off_part + tiles * (size_t)ksplit * ci.bm * ci.bn * 4, 256);
+    return s;
 }
 
 // ------------------------------------------------------------------------- //
@@ -353,8 +394,8 @@ WsLayout ws_layout(int M, int N, int K, int cfg) {
     const size_t tm = (size_t)cdiv(M, ci.bm), tn = (size_t)cdiv(N, ci.bn);
     const size_t n_parts = (size_t)(ci.bm / pre_rows_per_block(ci.bm)) * (size_t)cdiv(K, 256);
     WsLayout w;
-    w.off_pc = 0;
-    w.off_pd = align_up(tm * tn * 32, 256);
+    w.off_pc = WS_HEADER;
+    w.off_pd = align_up(w.off_pc + tm * tn * 32, 256);
     w.off_beta = align_up(w.off_pd + tm * tn * n_parts * 8, 256);
     w.total = align_up(w.off_beta + tn * (size_t)K * 8, 256);
     return w;
@@ -485,6 +526,20 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     }
     g.tiles_m = (int)cdiv(pr.M, ci.bm);
     g.tiles_n = (int)cdiv(pr.N, ci.bn);
+    g.ksplit = 1;
+    if (mode != ABFT_GLOBAL) {
+        // split-K needs scratch for the partial tiles; without it the product runs unsplit
+        const int ks = pick_ksplit(pr.M, pr.N, pr.K, pr.dtype, cfg, mode);
+        if (ks > 1) {
+            const SplitLayout sl = split_layout(pr.M, pr.N, cfg, ks);
+            char* wsp = reinterpret_cast<char*>(workspace);
+            if (wsp && !(reinterpret_cast<uintptr_t>(wsp) & 255u) && ws_bytes >= sl.total) {
+                g.ksplit = ks;
+                g.counters = reinterpret_cast<unsigned int*>(wsp + sl.off_counters);
+                g.part = wsp + sl.off_part;
+            }
+        }
+    }
     g.flag = flag;
     g.report = reinterpret_cast<Report*>(report);
     g.tol_coeff = tol_coeff(pr.K, pr.dtype, mode);
@@ -619,8 +674,34 @@ int abft_conv(const abft_conv_t* conv, int N, const void* x, const void* B, int6
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode) {
     if (M <= 0 || N <= 0 || K <= 0 || !valid_dtype(dtype)) return 0;
     if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
-    if (mode != ABFT_GLOBAL) return 0;
-    return ws_bytes_any_cfg(M, N, K);
+    if (mode == ABFT_GLOBAL) return ws_bytes_any_cfg(M, N, K);
+    // unprotected / thread-level: scratch only where the product would be split along k
+    // (sized for aligned operands; unaligned ones run unsplit and ignore it)
+    const int cfg = pick_cfg(M, N, K, dtype, true, mode);
+    const int ks = pick_ksplit(M, N, K, dtype, cfg, mode);
+    return ks > 1 ? split_layout(M, N, cfg, ks).total : 0;
+}
+
+int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int* n_slices, int* bounds, int max_bounds) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
+    if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
+    const int cfg = pick_cfg(M, N, K, dtype, aligned != 0, mode);
+    const int ks = pick_ksplit(M, N, K, dtype, cfg, mode);
+    if (n_slices) *n_slices = ks;
+    if (bounds) {
+        if (max_bounds < ks + 1) return ABFT_E_SHAPE;
+        const int bk = cfg_info_host(cfg).bk_bytes / esize(dtype);
+        const int nkt = ks > 1 ? K / bk : 1;
+        const int base = nkt / ks, rem = nkt % ks;
+        int t = 0;
+        for (int s = 0; s < ks; ++s) {
+            bounds[s] = ks > 1 ? t * bk : 0;
+            t += base + (s < rem ? 1 : 0);
+        }
+        bounds[ks] = K;
+    }
+    return ABFT_OK;
 }
 
 int abft_weight_checksum(int K, int N, const void* B, int64_t ldb, int b_layout, int dtype, int block_n,
@@ -657,6 +738,16 @@ int abft_activation_checksum(int M, int K, const void* A, int64_t lda, const abf
     return launch_act_checksum(pr, alpha, M, nullptr, 0, nullptr, reinterpret_cast<hipStream_t>(stream)) == hipSuccess
                ? ABFT_OK
                : ABFT_E_HIP;
+}
+
+int abft_k_ways(int M, int N, int K, int dtype, int aligned, int mode, int* ways, int* step) {
+    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
+    if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
+    if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
+    const CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0, mode));
+    if (ways) *ways = ci.kways;
+    if (step) *step = 32 / esize(dtype);  // one MFMA k step of the 32x32 shapes: 32 bytes of k
+    return ABFT_OK;
 }
 
 double abft_arithmetic_intensity(int M, int N, int K, int dtype) {
@@ -732,6 +823,10 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         // offline weight checksum and workspace for the global scheme (kept for either
         // choice so that profiling can time both)
         L.ws_bytes = ws_bytes_any_cfg(d.M, d.N, d.K);
+        for (int md = ABFT_NONE; md <= ABFT_THREAD; md += 2) {
+            const size_t need = abft_workspace_bytes(d.M, d.N, d.K, d.dtype, md);
+            if (need > L.ws_bytes) L.ws_bytes = need;
+        }
         {
             // the tiling the layer will run with when its activations are 16-byte aligned
             const int es = esize(d.dtype);
@@ -741,6 +836,7 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         }
         if (hipMalloc(&L.beta, (size_t)cdiv(d.N, L.beta_block_n) * d.K * 8) != hipSuccess) { rc = ABFT_E_HIP; break; }
         if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
+        (void)hipMemsetAsync(L.workspace, 0, L.ws_bytes < WS_HEADER ? L.ws_bytes : WS_HEADER, st);
         p->layers.push_back(L);
         if (launch_weight_checksum(d.K, d.N, d.B, d.ldb, d.b_layout, d.dtype, L.beta_block_n, L.beta, st) !=
             hipSuccess) {
@@ -818,6 +914,31 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     const void* beta = bn_now == L.beta_block_n ? L.beta : nullptr;
     return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
                        reinterpret_cast<hipStream_t>(stream));
+}
+
+int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* lda, void* const* C,
+                      const int64_t* ldc, uint32_t* fault_flag, int event_layer, void* stream) {
+    if (!plan) return ABFT_E_PLAN;
+    if (!A || !lda || !C || !ldc) return ABFT_E_NULL;
+    const hipEvent_t ev0 = g_ev_start, ev1 = g_ev_stop;
+    int rc = ABFT_OK;
+    for (int i = 0; i < (int)plan->layers.size() && rc == ABFT_OK; ++i) {
+        // the measurement hook, if set, brackets the product kernel of one layer only
+        g_ev_start = i == event_layer ? ev0 : nullptr;
+        g_ev_stop = i == event_layer ? ev1 : nullptr;
+        rc = abft_plan_run(plan, i, A[i], lda[i], C[i], ldc[i], fault_flag, stream);
+    }
+    g_ev_start = ev0;
+    g_ev_stop = ev1;
+    return rc;
+}
+
+int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    if (mode < ABFT_NONE || mode > ABFT_AUTO) return ABFT_E_ENUM;
+    abft_plan::Layer& L = plan->layers[layer];
+    L.mode = mode == ABFT_AUTO ? select_mode(L.desc.M, L.desc.N, L.desc.K, L.desc.dtype) : mode;
+    return ABFT_OK;
 }
 
 int abft_plan_mode(const abft_plan_t* plan, int layer) {

@@ -79,6 +79,11 @@ struct GemmArgs {
     // after k-tile f_kt has been accumulated (f_kt < 0: after the last one)
     int f_row, f_col, f_bit, f_kt;
     int tiles_m, tiles_n;    // grid shape in tiles
+    // split-K (direct-to-LDS kernel only): ksplit workgroups share a tile, each multiplies a
+    // contiguous range of k tiles; partial tiles meet in `part`, `counters` elects the last
+    int ksplit;
+    char* part;              // [tile][ksplit][BM*BN] fp32 / int32 partial accumulators
+    unsigned int* counters;  // [tile], zero before and after every launch
 };
 
 template <typename To, typename Ti>
@@ -412,10 +417,12 @@ struct ChecksumForm {
 template <class CFG>
 struct TileCoords {
     int lane, wave, wave_m, wave_n, lrow, lgrp, bm0, bn0;
-    __device__ __forceinline__ TileCoords(int tile_m, int tile_n) {
+    // wave_mn: position of the wavefront in the WAVES_M x WAVES_N grid when the workgroup has
+    // more wavefronts than that (several share a register tile along k); -1: tid / 64
+    __device__ __forceinline__ TileCoords(int tile_m, int tile_n, int wave_mn = -1) {
         const int tid = threadIdx.x;
         lane = tid & 63;
-        wave = tid >> 6;
+        wave = wave_mn >= 0 ? wave_mn : tid >> 6;
         wave_m = wave / CFG::WAVES_N;
         wave_n = wave % CFG::WAVES_N;
         lrow = lane % CFG::MI;
@@ -477,11 +484,12 @@ __device__ __forceinline__ void inject_fault(typename Mma<CFG::DT, CFG::MI>::Acc
 template <class CFG, int MODE>
 __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
                                          typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1],
-                                         const GemmArgs& p, int tile_m, int tile_n, char* smem) {
+                                         const GemmArgs& p, int tile_m, int tile_n, char* smem, bool store = true,
+                                         int wave_mn = -1) {
     typedef Mma<CFG::DT, CFG::MI> MMA;
     constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
     constexpr bool IS_INT = CFG::DT == DT_I8;
-    const TileCoords<CFG> tc(tile_m, tile_n);
+    const TileCoords<CFG> tc(tile_m, tile_n, wave_mn);
     const int tid = threadIdx.x, lane = tc.lane, wave = tc.wave;
     const int M = p.M, N = p.N;
     // index of this wavefront's register tile in the grid of wave tiles (row-major)
@@ -615,6 +623,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
         }
     }
 
+    if (!store) return;
     // ---- store C (rounded to the output type)
 #pragma unroll
     for (int i = 0; i < TM; ++i)

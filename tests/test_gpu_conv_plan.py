@@ -130,3 +130,47 @@ def test_plan_runs_every_layer_with_the_selected_scheme():
                 B.abft_plan_run(plan, 9, dC, 1, dC, 1, flag)
         finally:
             B.abft_plan_destroy(plan)
+
+
+def test_plan_run_all_eager_and_under_graph_replay():
+    """One call runs the whole layer list; captured into a HIP graph it must give the eager
+    results on every replay (replayed several times with eager work in between)."""
+    import torch
+    from gpu_util import to_dev, c_to_host, c_close, DEV
+    dims = [(256, 512, 64), (256, 256, 512), (256, 1024, 256), (256, 64, 1024)]
+    keep, layers, As, Cs, refs = [], [], [], [], []
+    for i, (M, N, K) in enumerate(dims):
+        A, Wm = wl.gemm_operands(M, N, K, "f16", seed=90 + i, dist_a="uniform_01", dist_b="weights")
+        dB = to_dev(np.ascontiguousarray(Wm.T), "f16")
+        keep.append(dB)
+        layers.append(B.Layer(M, N, K, B.F16, B.B_NK, 0, B.Conv(), dB.data_ptr(), K))
+        As.append(to_dev(A, "f16"))
+        Cs.append(torch.zeros((M, N), dtype=torch.float16, device=DEV))
+        refs.append(oracle.gemm(A, Wm, "f16"))
+    plan = B.abft_plan_create(layers)
+    try:
+        B.abft_plan_set_mode(plan, 1, B.GLOBAL)  # mix both schemes in the pass
+        io = B.PlanIO(As, [d[2] for d in dims], Cs, [d[1] for d in dims])
+        flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+        B.abft_plan_run_all(plan, io, flag)
+        torch.cuda.synchronize()
+        eager = [c.clone() for c in Cs]
+        for c, r in zip(eager, refs):
+            assert c_close(c_to_host(c, "f16"), r, "f16")
+        assert int(flag.item()) == 0
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            B.abft_plan_run_all(plan, io, flag, -1, cap)
+        for rep in range(4):
+            for c in Cs:
+                c.zero_()                       # eager work between replays
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            for c, e in zip(Cs, eager):
+                assert torch.equal(c, e), rep
+            assert int(flag.item()) == 0
+    finally:
+        B.abft_plan_destroy(plan)

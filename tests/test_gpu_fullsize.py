@@ -28,7 +28,7 @@ class Big:
         self.dC = torch.zeros((M, N), dtype=c_t, device=DEV)
         self.flag = torch.zeros(1, dtype=torch.int32, device=DEV)
         self.rep = torch.zeros(64, dtype=torch.uint8, device=DEV)
-        self.wsb = B.abft_workspace_bytes(M, N, K, self.dt, B.GLOBAL)
+        self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
         self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=DEV)
         self.rm, self.rn = B.abft_region_shape(M, N, K, self.dt, True)
         self.beta = torch.zeros(-(-N // self.rn) * K, dtype=torch.float64, device=DEV)

@@ -49,8 +49,8 @@ def test_clean_parity(shape, mode, dtype):
     if mode == B.THREAD:
         tm, tn, _ = B.abft_tile_shape(M, N, K, dt, aligned)
         import math
-        # one comparison per wave tile of the launched grid (tiles past the edge included)
-        assert res.report.tiles >= math.ceil(M / tm) * math.ceil(N / tn)
+        # one comparison per wave tile of the launched grid (tiles past the edge included) and k part
+        assert res.report.tiles >= math.ceil(M / tm) * math.ceil(N / tn) * len(B.abft_k_parts(M, N, K, dt, mode, aligned))
         assert res.report.worst_ratio < 0.5
 
 
@@ -117,14 +117,21 @@ def test_int8_injected_faults_always_flagged(shape, mode):
     C_ref = oracle.gemm(A, Bm, "i8")
     _, _, ks = B.abft_tile_shape(M, N, K, B.I8)
     rng = np.random.default_rng(22)
+    parts = B.abft_k_parts(M, N, K, B.I8, mode)
     for t in range(40):
         i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
         k_after = -1 if (t % 2 == 0 or K <= ks) else ks * int(rng.integers(1, K // ks))
         if k_after >= K:
             k_after = -1
-        print(f"case shape={shape} mode={mode} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        print(f"case shape={shape} mode={mode} fault=({i},{j},bit {bit},k_after {k_after}) parts={len(parts)}", flush=True)
         res = run_gemm(A, Bm, "i8", mode, inject=B.Fault(i, j, bit, k_after))
-        C_bad = oracle.inject(A, Bm, C_ref, "i8", i, j, bit, k_after)
+        # the accumulator that is hit belongs to the part of k that holds k_after - 1 (K - 1 for a
+        # flip of the finished value) and holds that part's products with k < k_after
+        part = parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)]
+        kk = [k for k in part if k_after < 0 or k < k_after]
+        head = int(A[i, kk].astype(np.int64) @ Bm[kk, j].astype(np.int64))
+        C_bad = C_ref.copy()
+        C_bad[i, j] = oracle.flip_bit(head, bit, "i8") + (int(C_ref[i, j]) - head)
         want = ((C_bad + 2 ** 31) % 2 ** 32) - 2 ** 31  # the int32 register wraps
         assert np.array_equal(res.C, want)
         assert res.flag == 1
@@ -148,14 +155,21 @@ def test_fp_injected_faults_match_oracle_outside_band(mode, dtype):
         i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
         print(f"case mode={mode} dtype={dtype} fault=({i},{j},bit {bit})", flush=True)
         res = run_gemm(A, Bm, dtype, mode, inject=B.Fault(i, j, bit, -1))
-        C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit)
         if mode == B.GLOBAL:
+            C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit)
             rm, rn = B.abft_region_shape(M, N, K, dt)
             r0, c0 = i // rm * rm, j // rn * rn
             chk = oracle.region_check(A, Bm, C_bad, dtype, r0, min(r0 + rm, M), c0, min(c0 + rn, N))
         else:
+            # thread-level: the comparison that sees the fault is the one of the wavefront tile
+            # and k part whose accumulator was hit
+            parts = B.abft_k_parts(M, N, K, dt, mode)
+            idx = parts[oracle.part_of(parts, K - 1)]
+            As, Bs = np.ascontiguousarray(A[:, idx]), np.ascontiguousarray(Bm[idx, :])
+            C_bad = oracle.inject(As, Bs, oracle.gemm(As, Bs, dtype), dtype, i, j, bit)
             r0, c0 = i // tm * tm, j // tn * tn
-            chk = oracle.tile_check(A, Bm, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
+            chk = oracle.tile_check(As, Bs, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
+            chk.tau = oracle.tolerance(K, oracle.frob(C_bad, r0, r0 + tm, c0, c0 + tn), dtype, scheme=2)
         if not math.isfinite(C_bad[i, j]):
             assert res.flag == 1
             counts["must"] += 1
@@ -188,6 +202,62 @@ def test_auto_mode_follows_selector():
     res = run_gemm(A, Bm, "f16", B.AUTO)
     # 64^3 is bandwidth bound -> thread-level: one comparison per wavefront tile, not per workgroup tile
     tm, tn, _ = B.abft_tile_shape(64, 64, 64, B.F16)
-    assert res.flag == 0 and res.report.tiles == -(-64 // tm) * -(-64 // tn) and res.report.tau > 0
+    n_parts = len(B.abft_k_parts(64, 64, 64, B.F16, B.THREAD))
+    assert res.flag == 0 and res.report.tiles == -(-64 // tm) * -(-64 // tn) * n_parts and res.report.tau > 0
     assert res.report.l1 == 0.0   # the ||C||_1 term belongs to the global scheme only
     assert c_close(res.C, oracle.gemm(A, Bm, "f16"), "f16")
+
+
+@pytest.mark.parametrize("shape", [(64, 1024, 4096), (200, 384, 512)])
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+def test_split_k_thread_level(dtype, shape):
+    """Small products are split along k -- across workgroups (slices) or across the wavefronts
+    of a workgroup (ways): partial tiles are added in a fixed order (bit-reproducible), the
+    thread-level comparisons run per part, and a fault is seen by the part that holds it."""
+    import math
+    from gpu_util import run_gemm, c_close
+    M, N, K = shape
+    dt = B.F16 if dtype == "f16" else B.I8
+    parts = B.abft_k_parts(M, N, K, dt, B.THREAD)
+    assert len(parts) > 1 and sorted(k for p in parts for k in p) == list(range(K))
+    assert len(B.abft_k_parts(M, N, K, dt, B.GLOBAL)) == 1      # the global scheme is never split
+    if len(B.abft_k_slices(M, N, K, dt, B.THREAD)) > 1:
+        assert B.abft_workspace_bytes(M, N, K, dt, B.THREAD) > 0
+    tm, tn, ks = B.abft_tile_shape(M, N, K, dt)
+    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=55, dist_a="uniform_01" if dtype == "f16" else "int8",
+                             dist_b="weights" if dtype == "f16" else "int8")
+    C_ref = oracle.gemm(A, Bm, dtype)
+    for mode in (B.NONE, B.THREAD):
+        res = run_gemm(A, Bm, dtype, mode)
+        assert c_close(res.C, C_ref, dtype) and res.flag == 0
+        again = run_gemm(A, Bm, dtype, mode)
+        assert np.array_equal(res.C, again.C)
+        if mode == B.THREAD:
+            # (wavefront tiles of the launched grid that lie wholly past the edge are compared too)
+            assert res.report.tiles >= len(parts) * math.ceil(M / tm) * math.ceil(N / tn)
+            assert res.report.worst_ratio < 0.5
+    rng = np.random.default_rng(56)
+    for t in range(12):
+        i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(20, 32))
+        k_after = -1 if t % 3 == 0 else ks * int(rng.integers(1, K // ks))
+        print(f"case split-k dtype={dtype} shape={shape} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        res = run_gemm(A, Bm, dtype, B.THREAD, inject=B.Fault(i, j, bit, k_after))
+        idx = np.asarray(parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)])
+        As, Bs = np.ascontiguousarray(A[:, idx]), np.ascontiguousarray(Bm[idx, :])
+        Cs = oracle.gemm(As, Bs, dtype)
+        n_before = len(idx) if k_after < 0 else int(np.sum(idx < k_after))
+        Cs_bad = oracle.inject(As, Bs, Cs, dtype, i, j, bit, n_before)
+        r0, c0 = i // tm * tm, j // tn * tn
+        chk = oracle.tile_check(As, Bs, Cs_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
+        if dtype == "i8":
+            assert res.flag == 1
+            want = C_ref + (Cs_bad - Cs)
+            assert np.array_equal(res.C, ((want + 2 ** 31) % 2 ** 32) - 2 ** 31)
+            continue
+        tau = oracle.tolerance(K, oracle.frob(Cs_bad, r0, r0 + tm, c0, c0 + tn), dtype, scheme=2)
+        if not math.isfinite(Cs_bad[i, j]):
+            assert res.flag == 1
+        elif abs(chk.residual) >= 2 * tau:
+            assert res.flag == 1, (abs(chk.residual), tau)
+        elif abs(chk.residual) <= tau / 2:
+            assert res.flag == 0, (abs(chk.residual), tau)

@@ -257,3 +257,31 @@ def test_global_tolerance_has_the_bias_term():
     one = oracle.region_check(A, B, Cc, "f16", 0, 8, 0, 8)
     whole = oracle.global_check(A, B, Cc, "f16")
     assert one.tau == pytest.approx(whole.tau) and one.rhs == pytest.approx(whole.rhs, rel=1e-13)
+
+
+def test_sliced_thread_check_matches_unsliced_on_clean_data_and_sees_faults():
+    M, N, K = 24, 40, 96
+    for dtype in ("i8", "f16"):
+        A, B = wl.gemm_operands(M, N, K, dtype, seed=15)
+        C = oracle.gemm(A, B, dtype)
+        slices = [(0, 32), (32, 64), (64, 96)]
+        flag, checks, total = oracle.thread_check_sliced(A, B, dtype, 16, 32, slices)
+        assert not flag and len(checks) == 3 * 2 * 2
+        if dtype == "i8":
+            assert np.array_equal(total, C)
+            assert sum(c.lhs for c in checks) == int(C.sum())
+        else:
+            assert np.allclose(total, C, rtol=1e-13, atol=1e-13)
+        # a mid-loop fault in the second slice: only that slice's tile sees it
+        flag, checks, bad = oracle.thread_check_sliced(A, B, dtype, 16, 32, slices, fault=(5, 33, 30, 48))
+        assert flag and sum(c.flag for c in checks) == 1
+        want = oracle.inject(A, B, C, dtype, 5, 33, 30, k_after=48, k_begin=32)
+        if dtype == "i8":
+            assert np.array_equal(bad, want)
+        else:
+            assert np.array_equal(np.isfinite(bad), np.isfinite(want))
+        # final flip lands in the last slice's accumulator
+        _, _, bad2 = oracle.thread_check_sliced(A, B, dtype, 16, 32, slices, fault=(0, 0, 3, -1))
+        want2 = oracle.inject(A, B, C, dtype, 0, 0, 3, k_after=-1, k_begin=64)
+        assert np.allclose(bad2, want2, rtol=1e-12, atol=1e-12)
+    assert oracle.slice_of([(0, 32), (32, 64)], 32) == 1

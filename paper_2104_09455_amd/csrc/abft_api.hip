@@ -76,7 +76,7 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     };
     if (fast_ok) {
         // fill the 256 compute units before growing the tile
-        if (tiles(CFG_F256) >= 224) return CFG_F256;
+        if (tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F256 : CFG_F256W;
         if (tiles(CFG_F128) >= 128) return mode == ABFT_THREAD ? CFG_F128T : CFG_F128;
         if (tiles(CFG_F64T) > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
         // at most one workgroup per compute unit: deep pipeline and more wavefronts per tile;
@@ -258,8 +258,20 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
     for (int jb = 0; jb < p.nb; jb += 32) {
         const int j = jb + tx;
         Wide acc = 0;
-        if (j < p.nb)
-            for (int k = ty; k < kcount; k += 8) acc += alpha_s[k] * beta[(long long)(kbase + k) * p.nb + j];
+        if (j < p.nb) {
+            // 32 * EPC / 8 values of k per thread, loaded in independent batches of eight
+            const Wide* bj = beta + (long long)kbase * p.nb + j;
+            for (int k0b = ty; k0b < 32 * EPC; k0b += 64) {
+                Wide bv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int k = k0b + 8 * u;
+                    bv[u] = k < kcount ? bj[(long long)k * p.nb] : (Wide)0;
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) acc += alpha_s[k0b + 8 * u] * bv[u];
+            }
+        }
         __syncthreads();
         red2[ty * 32 + tx] = acc;
         __syncthreads();
@@ -301,52 +313,6 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
     }
 }
 
-// Comparison of the global scheme (Sec. 2.4 steps 3-4, Sec. 2.5 step 5), one comparison per
-// workgroup tile (i, j) of the product:
-//     sum of C over the tile   vs   sum_k alpha_i[k] * beta_j[k]
-// with alpha_i the activation checksum of row block i and beta_j the weight checksum of
-// column block j; the right-hand side arrives as per-k-range partial dot products from the
-// activation-checksum kernel.  Summed over all tiles this is the whole-matrix identity;
-// comparing per tile keeps the rounding noise of the fp32 accumulators (which has a small
-// coherent bias that grows with the number of entries summed) far below the tolerance.
-// One wavefront per tile.
-template <bool IS_INT>
-__global__ __launch_bounds__(256) void compare_kernel(const void* partial_dots, int n_parts, const double* partials,
-                                                      int tiles_m, int tiles_n, double tol_frob, double tol_l1,
-                                                      unsigned int* flag, Report* report) {
-    typedef typename std::conditional<IS_INT, long long, double>::type Wide;
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (t >= tiles_m * tiles_n) return;
-    const int lane = threadIdx.x & 63;
-    const Wide* pd = reinterpret_cast<const Wide*>(partial_dots) + (long long)t * n_parts;
-    Wide sab = 0;
-    for (int c = lane; c < n_parts; c += 64) sab += pd[c];
-    sab = wave_sum(sab);
-    if (lane != 0) return;
-    const double* pt = partials + 4 * (long long)t;
-    bool bad;
-    double tau = 0.0, ratio, lhs, frob = 0.0, l1 = 0.0;
-    if constexpr (IS_INT) {
-        const long long sc = reinterpret_cast<const long long*>(pt)[0];
-        bad = sc != sab;
-        ratio = bad ? __builtin_huge_val() : 0.0;
-        lhs = (double)sc;
-    } else {
-        const double sc = pt[0], f2 = pt[1];
-        l1 = pt[2];
-        frob = __builtin_sqrt(f2);
-        tau = tol_frob * frob + tol_l1 * l1;
-        const double res = __builtin_fabs(sc - sab);
-        // a sum of squares beyond the fp32 range cannot come from a fault-free tile
-        const bool finite = __builtin_isfinite(sc) && __builtin_isfinite(sab) && __builtin_isfinite(f2);
-        bad = !finite || !(res <= tau);
-        ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
-        lhs = sc;
-    }
-    if (bad) atomicOr(flag, 1u);
-    if (report) report_update(report, ratio, lhs, (double)sab, tau, frob, l1, (unsigned)t);
-}
-
 // ------------------------------------------------------------------------- //
 // host helpers
 // ------------------------------------------------------------------------- //
@@ -379,23 +345,26 @@ bool b_vectorisable(const Problem& pr) {
 int conv_out(int in, int k, int stride, int pad) { return (in + 2 * pad - k) / stride + 1; }
 
 struct WsLayout {
-    size_t off_pc, off_pd, off_beta, total;
+    size_t off_pd, off_beta, total;
 };
 
 int pre_grid_x(int K, int dt) { return (int)cdiv(K, 32 * (16 / esize(dt))); }
-// rows one workgroup of the activation-checksum kernel sums
-int pre_rows_per_block(int bm) { return bm < 64 ? bm : 64; }
+// rows one workgroup of the activation-checksum kernel sums: a whole row block of the tiling
+// when that still gives a few workgroups per compute unit, else 64 rows
+int pre_rows_per_block(int bm, int M, int K) {
+    if (bm <= 64) return bm;
+    return cdiv(M, bm) * cdiv(K, 256) >= 512 ? bm : 64;
+}
 
-// Workspace of the global scheme for the tile configuration `cfg`: per-tile output
-// summations, per-tile partial checksum dot products, per-column-block weight checksums
+// Workspace of the global scheme for the tile configuration `cfg`: per-tile partial
+// checksum dot products, per-column-block weight checksums
 // (the last only used when the caller passes no precomputed ones).  Sized for any dtype.
 WsLayout ws_layout(int M, int N, int K, int cfg) {
     CfgInfo ci = cfg_info_host(cfg);
     const size_t tm = (size_t)cdiv(M, ci.bm), tn = (size_t)cdiv(N, ci.bn);
-    const size_t n_parts = (size_t)(ci.bm / pre_rows_per_block(ci.bm)) * (size_t)cdiv(K, 256);
+    const size_t n_parts = (size_t)(ci.bm / (ci.bm < 64 ? ci.bm : 64)) * (size_t)cdiv(K, 256);  // upper bound
     WsLayout w;
-    w.off_pc = WS_HEADER;
-    w.off_pd = align_up(w.off_pc + tm * tn * 32, 256);
+    w.off_pd = WS_HEADER;
     w.off_beta = align_up(w.off_pd + tm * tn * n_parts * 8, 256);
     w.total = align_up(w.off_beta + tn * (size_t)K * 8, 256);
     return w;
@@ -472,7 +441,7 @@ hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_
     a.rows_per_slab = rows_per_slab;
     // the plain checksum is one slab summed by one row of blocks; the fused form splits each
     // row block of the tiling over several blocks to have enough loads in flight
-    a.rows_per_block = alpha_out ? rows_per_slab : pre_rows_per_block(rows_per_slab);
+    a.rows_per_block = alpha_out ? rows_per_slab : pre_rows_per_block(rows_per_slab, pr.M, pr.K);
     a.beta = beta;
     a.nb = nb;
     a.partial_dots = partial_dots;
@@ -565,7 +534,9 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     if (mode == ABFT_GLOBAL) {
         w = ws_layout(pr.M, pr.N, pr.K, cfg);
         if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.total) return ABFT_E_WORKSPACE;
-        g.partials = reinterpret_cast<double*>(ws + w.off_pc);
+        g.partial_dots = ws + w.off_pd;
+        g.n_parts = pre_grid_x(pr.K, pr.dtype) * (ci.bm / pre_rows_per_block(ci.bm, pr.M, pr.K));
+        g.tol_l1 = tol_bias_coeff(pr.K, pr.dtype, mode);
         if (!beta_used) {
             if (launch_weight_checksum(pr.K, pr.N, pr.B, pr.ldb, pr.b_layout, pr.dtype, ci.bn, ws + w.off_beta,
                                        st) != hipSuccess)
@@ -586,19 +557,6 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     if (e != hipSuccess) return ABFT_E_HIP;
     if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return ABFT_E_HIP;
 
-    if (mode == ABFT_GLOBAL) {
-        dim3 grid((unsigned)cdiv((long long)g.tiles_m * g.tiles_n, 4));
-        const int n_chunks = pre_grid_x(pr.K, pr.dtype) * (ci.bm / pre_rows_per_block(ci.bm));
-        if (pr.dtype == ABFT_I8)
-            hipLaunchKernelGGL(compare_kernel<true>, grid, dim3(256), 0, st, (const void*)(ws + w.off_pd), n_chunks,
-                               (const double*)g.partials, g.tiles_m, g.tiles_n, 0.0, 0.0, flag,
-                               reinterpret_cast<Report*>(report));
-        else
-            hipLaunchKernelGGL(compare_kernel<false>, grid, dim3(256), 0, st, (const void*)(ws + w.off_pd), n_chunks,
-                               (const double*)g.partials, g.tiles_m, g.tiles_n, g.tol_coeff,
-                               tol_bias_coeff(pr.K, pr.dtype, mode), flag, reinterpret_cast<Report*>(report));
-        if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
-    }
     return ABFT_OK;
 }
 

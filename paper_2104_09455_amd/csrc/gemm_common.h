@@ -70,9 +70,10 @@ struct GemmArgs {
     // implicit-GEMM geometry (conv != 0): A is an NHWC tensor
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
     // ABFT outputs
-    double* partials;        // GLOBAL: per workgroup tile {sum, sum of squares, sum of magnitudes, -}
-                             // (int8: the int64 sum in the first slot), indexed tile_m * tiles_n + tile_n
-    unsigned int* flag;      // THREAD: OR-ed with 1 on mismatch
+    const void* partial_dots; // GLOBAL: per tile n_parts partial checksum dot products (double / int64)
+    int n_parts;
+    double tol_l1;           // GLOBAL: coefficient of the tile's sum of magnitudes in tau
+    unsigned int* flag;      // OR-ed with 1 on mismatch
     Report* report;          // optional diagnostics (THREAD only here)
     double tol_coeff;        // THREAD: tau = tol_coeff * ||C_tile||_F
     // fault injection (test hook): flip bit f_bit of accumulator (f_row, f_col)
@@ -477,8 +478,9 @@ __device__ __forceinline__ void inject_fault(typename Mma<CFG::DT, CFG::MI>::Acc
 }
 
 // Checksum epilogue (taken from the accumulators, before down-conversion) and store of C.
-//  GLOBAL: fused output summation (Sec. 2.5): per workgroup tile {sum, sum of squares,
-//          sum of magnitudes} written to p.partials for the comparison kernel.
+//  GLOBAL: fused output summation (Sec. 2.5) of the workgroup tile, compared right here with
+//          the tile's checksum dot product (Sec. 2.4 steps 3-4): the partial dot products were
+//          left by the activation-checksum kernel, which ran before on the same stream.
 //  THREAD: the wavefront tile's output summation against the sum of its checksum
 //          accumulators (Sec. 5.2.2), compared here; p.flag is touched only on mismatch.
 template <class CFG, int MODE>
@@ -520,11 +522,23 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                 __syncthreads();
                 if (lane == 0) red[wave] = s;
                 __syncthreads();
-                if (tid == 0) {
+                if (wave == 0) {
+                    // comparison (Sec. 2.4 step 4) for this tile: its output summation against the
+                    // sum of the partial checksum dot products the activation-checksum kernel left
                     long long tot = 0;
                     for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) tot += red[w];
-                    long long* out = reinterpret_cast<long long*>(p.partials) + 4 * ((long long)tile_m * p.tiles_n + tile_n);
-                    out[0] = tot;
+                    const long long t = (long long)tile_m * p.tiles_n + tile_n;
+                    const long long* pd = reinterpret_cast<const long long*>(p.partial_dots) + t * p.n_parts;
+                    long long sab = 0;
+                    for (int c = lane; c < p.n_parts; c += 64) sab += pd[c];
+                    sab = wave_sum(sab);
+                    if (lane == 0) {
+                        const bool bad = tot != sab;
+                        if (bad) atomicOr(p.flag, 1u);
+                        if (p.report)
+                            report_update(p.report, bad ? __builtin_huge_val() : 0.0, (double)tot, (double)sab, 0.0, 0.0,
+                                          0.0, (unsigned)t);
+                    }
                 }
             } else {
                 int r_lo = 0, r_hi = 0;
@@ -575,17 +589,34 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                     red[3 * wave + 2] = L1;
                 }
                 __syncthreads();
-                if (tid == 0) {
+                if (wave == 0) {
+                    // comparison (Sec. 2.4 step 4) for this tile: its output summation against the
+                    // sum of the partial checksum dot products the activation-checksum kernel left
                     double ts = 0.0, tf = 0.0, tl = 0.0;
                     for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) {
                         ts += red[3 * w];
                         tf += red[3 * w + 1];
                         tl += red[3 * w + 2];
                     }
-                    double* out = p.partials + 4 * ((long long)tile_m * p.tiles_n + tile_n);
-                    out[0] = ts;
-                    out[1] = tf;
-                    out[2] = tl;
+                    const long long t = (long long)tile_m * p.tiles_n + tile_n;
+                    const double* pd = reinterpret_cast<const double*>(p.partial_dots) + t * p.n_parts;
+                    double sab = 0.0;
+                    for (int c = lane; c < p.n_parts; c += 64) sab += pd[c];
+                    sab = wave_sum(sab);
+                    if (lane == 0) {
+                        const double frob = __builtin_sqrt(tf);
+                        const double tau = p.tol_coeff * frob + p.tol_l1 * tl;
+                        const double res = __builtin_fabs(ts - sab);
+                        // a sum of squares beyond the fp32 range cannot come from a fault-free tile
+                        const bool finite = __builtin_isfinite(ts) && __builtin_isfinite(sab) && __builtin_isfinite(tf);
+                        const bool bad = !finite || !(res <= tau);
+                        if (bad) atomicOr(p.flag, 1u);
+                        if (p.report) {
+                            const double ratio = !finite ? __builtin_huge_val()
+                                                         : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+                            report_update(p.report, ratio, ts, sab, tau, frob, tl, (unsigned)t);
+                        }
+                    }
                 }
             } else {
                 double rsum = 0.0;

@@ -8,7 +8,7 @@
 //
 // Data flow: global_load_lds_dwordx4 moves 16-byte chunks from HBM straight into LDS
 // (no staging registers), NSTAGE LDS stages, rows of 128 bytes stored with an XOR
-// swizzle of the chunk position so that ds_read_b128 fragment reads are free of bank
+// swizzle of the chunk position (key (row >> 1) & 7) so that ds_read_b128 fragment reads are free of bank
 // conflicts; out-of-range rows (and convolution padding taps) read from a small block
 // of zeros, so ragged edges need no special case.  Requirements checked by the
 // dispatcher: 16-byte aligned operands with k contiguous, leading dimensions multiples
@@ -99,9 +99,13 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     const int nkt = kt_base + (ks < kt_rem ? 1 : 0);
 
     // ---- global -> LDS copy: this lane always fills LDS slot `lane` of a 1 KB block
-    // (8 rows x 8 chunks): row lane/8, position lane%8, which holds chunk (lane%8)^(lane/8)
+    // (8 rows x 8 chunks): row lane/8, position lane%8, which holds chunk (lane%8) ^ key(row)
     const int crow = lane >> 3;
-    const int ckc = (lane & 7) ^ crow;
+    // swizzle key of a row: (row >> 1) & 7.  The LDS serves 16 lanes of a ds_read_b128 at a time
+    // over 64 banks (256 bytes = two rows), so the 8 even and the 8 odd rows of any 16 rows
+    // must each spread over the 8 chunk positions.  Every 1 KB block starts at a row that is a
+    // multiple of 8, and the parity of that multiple is the parity of the wave index.
+    const int ckc = (lane & 7) ^ ((4 * (wave & 1) + (lane >> 4)) & 7);
     const char* zero = g_zero_chunk + ckc * 16;
 
     const char* aptr[NQA];
@@ -142,6 +146,32 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         tap_kh = tap / p.KW;
         tap_kw = tap - tap_kh * p.KW;
     }
+
+    // L2 prefetch (large tile only): with two LDS stages a copy is issued one k tile ahead, less
+    // than an HBM round trip; touching the lines of tile t + 2 when tile t is issued lets the
+    // copies find them in L2.  One 4-byte copy per 128-byte row segment into a dummy LDS area.
+    constexpr bool PREFETCH = NSTAGE == 2 && !CONV && KWAYS == 1 && BM == CFG::THREADS && BN == CFG::THREADS;
+    constexpr int PFD = 2;
+    const char* pfa = zero;
+    const char* pfb = zero;
+    bool pfa_ok = false, pfb_ok = false;
+    if constexpr (PREFETCH) {
+        pfa_ok = bm0 + tid < M;
+        pfb_ok = bn0 + tid < N;
+        if (pfa_ok) pfa = p.A + ((long long)(bm0 + tid) * p.lda + (long long)kt_first * BK) * ESIZE;
+        if (pfb_ok) pfb = p.B + ((long long)(bn0 + tid) * p.ldb + (long long)kt_first * BK) * ESIZE;
+    }
+    auto prefetch_tile = [&](int t) {  // t: k tile index within this workgroup's range
+        if constexpr (PREFETCH) {
+            char* dummy = smem + NSTAGE * STAGE + wave * 256;
+            const long long off = (long long)t * BKB;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pfa_ok ? pfa + off : zero),
+                                             (__attribute__((address_space(3))) void*)dummy, 4, 0, 0);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pfb_ok ? pfb + off : zero),
+                                             (__attribute__((address_space(3))) void*)dummy, 4, 0, 0);
+        }
+    };
+    constexpr int NPF = PREFETCH ? 2 : 0;  // prefetch copies per wave per tile
 
     auto issue_loads = [&](int stage) {
         char* abase = smem + stage * STAGE + wave * 1024;
@@ -198,8 +228,8 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         for (int r = 0; r < 16; ++r) chk[i][r] = 0;
 
     // ---- fragment reads: lane l reads row l%32 of a 32-row block, k chunk 2*kk + l/32,
-    // stored at position chunk ^ (row & 7); row & 7 == l & 7 for every block
-    const int frow = lane & 31, fgrp = lane >> 5, fx = lane & 7;
+    // stored at position chunk ^ ((row >> 1) & 7), which is (l >> 1) & 7 for every block
+    const int frow = lane & 31, fgrp = lane >> 5, fx = (lane >> 1) & 7;
     const int a_off = (wave_m * CFG::WM + frow) * ROWB;
     const int b_off = A_STAGE + (wave_n * CFG::WN + frow) * ROWB;
     int pos[4];
@@ -251,7 +281,13 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
             issue_loads(t);
         }
     }
-    if (nkt >= NSTAGE) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NL));  // tile 0 has landed
+    if constexpr (PREFETCH) {
+        // (waits below count these copies too: they are issued after the tile copies they follow)
+        if (NSTAGE < nkt) prefetch_tile(NSTAGE);
+        if (NSTAGE + 1 < nkt) prefetch_tile(NSTAGE + 1);
+    }
+    if constexpr (PREFETCH) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
+    else if (nkt >= NSTAGE) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NL));  // tile 0 has landed
     else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
     read_frags(smem, 0, 0);
@@ -267,12 +303,15 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
                 read_frags(st, kk + 1, (kk + 1) & 1);
                 mma_step(kk & 1);
                 if constexpr (MODE != MODE_THREAD) {
+                    // fragment reads of the next step go out early, one per MFMA, so that the last
+                    // of them has the rest of the step's MFMAs to land
                     constexpr int NF = TM + TN, NM = TM * TN;
 #pragma unroll
                     for (int g = 0; g < NF; ++g) {
-                        __builtin_amdgcn_sched_group_barrier(0x008, (NM + NF - 1) / NF, 0);  // MFMAs
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);                    // 1 LDS read
+                        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
                     }
+                    __builtin_amdgcn_sched_group_barrier(0x008, NM > NF ? NM - NF : 0, 0);
                 }
             }
         }
@@ -280,12 +319,14 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         if (kt + 1 < nkt) {
             // this wave's copies of tile kt+1 have landed (the barrier makes it everyone's) and
             // every wave is done reading this stage, which the copies of tile kt+NSTAGE overwrite
-            if (kt + NSTAGE < nkt) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 2) * NL) & ~0x0F00);
+            // (the prefetch copies issued after tile kt+1's copies may still be in flight)
+            if (kt + NSTAGE + PFD < nkt) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 2) * NL + NPF) & ~0x0F00);
             else __builtin_amdgcn_s_waitcnt(0x0070);  // tail: vmcnt(0) lgkmcnt(0)
             __syncthreads();
             if (kt + NSTAGE < nkt) {
                 advance();
                 issue_loads(stage);
+                if (kt + NSTAGE + PFD < nkt) prefetch_tile(kt + NSTAGE + PFD);
             }
             read_frags(smem + next * STAGE, 0, KWAYS > 1 ? CUR ^ 1 : 0);
         }

@@ -235,6 +235,9 @@ def main():
     ap.add_argument("--workload", default="dlrm", choices=["dlrm", "resnet50", "square"])
     ap.add_argument("--no-extras", action="store_true", help="skip the short legs for the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
+    ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
+                    help="first run 5 plain element-wise copy kernels that read MIB MiB and write MIB MiB each "
+                         "(calibrates hardware byte counters under a profiler)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1",
@@ -249,6 +252,15 @@ def main():
     gen = torch.Generator(device="cuda:0")
     gen.manual_seed(20210409)
     stream = torch.cuda.current_stream().cuda_stream or None
+
+    if args.copy_probe > 0:
+        src = torch.ones(args.copy_probe * (1 << 18), dtype=torch.float32, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.mul(src, 1.0, out=dst)  # one vectorized element-wise kernel: reads and writes MIB MiB
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
 
     label, runs, dtype = build_workload(args.workload, gen)
     defaults = {"dlrm": (1000, 100), "resnet50": (20, 3), "square": (20, 3)}[args.workload]

@@ -69,7 +69,7 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     // the direct-to-LDS kernel needs whole k tiles of 128 bytes
     const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
     if (force >= 0 && force < CFG_COUNT && (fast_ok || !cfg_info_host(force).fast)) return force;
-    if (M <= 16) return CFG_G16;
+    if (M <= 16 && !fast_ok) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);
         return cdiv(M, ci.bm) * cdiv(N, ci.bn);
@@ -82,7 +82,14 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // at most one workgroup per compute unit: deep pipeline and more wavefronts per tile;
         // very few tiles with a long k loop are split along k across workgroups instead
         const long long nkt = ((long long)K * esize(dt)) / 128;
-        return (tiles(CFG_F64T) <= 64 && nkt >= 64) ? CFG_F64S : CFG_F64K;
+        if (tiles(CFG_F64T) > 64) return CFG_F64K;
+        // a handful of tiles: the time is the latency of one workgroup's k loop, so shrink the
+        // tile to spread the operands over more compute units and let the wavefronts stream
+        // without barriers.  The thread-level scheme takes the tile of two MFMA blocks (its
+        // checksum then needs no cross-lane step).
+        static const bool use_f64s = std::getenv("ABFT_USE_F64S") != nullptr;
+        if (use_f64s && nkt >= 64) return CFG_F64S;
+        return (mode == ABFT_THREAD && N > 32) ? CFG_S64 : CFG_S32;
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;
     if (tiles(CFG_G64) >= 1024) return CFG_G128;
@@ -704,7 +711,7 @@ int abft_k_ways(int M, int N, int K, int dtype, int aligned, int mode, int* ways
     if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
     const CfgInfo ci = cfg_info_host(pick_cfg(M, N, K, dtype, aligned != 0, mode));
     if (ways) *ways = ci.kways;
-    if (step) *step = 32 / esize(dtype);  // one MFMA k step of the 32x32 shapes: 32 bytes of k
+    if (step) *step = ci.kway_bytes / esize(dtype);
     return ABFT_OK;
 }
 

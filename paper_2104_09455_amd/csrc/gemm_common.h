@@ -407,7 +407,7 @@ struct TileChecksumSplitF16 {
 // accumulators per A fragment that takes.
 template <class CFG>
 struct ChecksumForm {
-    static constexpr bool SPLIT = CFG::DT == DT_F16 && CFG::MI == 32 && CFG::TM <= 2;
+    static constexpr bool SPLIT = CFG::DT == DT_F16 && CFG::MI == 32 && CFG::TM <= 2 && CFG::TN >= 2;
     static constexpr int NCHK = SPLIT ? 2 * CFG::TM : CFG::TM;
 };
 

@@ -14,34 +14,46 @@ namespace abft {
 //    F64S    same tile, 6 stages, may be split along k               grids that leave compute units idle
 //    F64K    same tile, 6 stages, 4 wavefronts per register tile     (each takes one k step in four)
 //    F256W  256 x 256, wavefronts 2 x 4 of 128 x  64, 2 stages       two wavefronts per SIMD
+//  S* run the streaming kernel (same operand requirements; four wavefronts split the k tiles of one
+//  register tile between them, each with its own LDS stages, no barrier in the k loop):
+//    S32     32 x  32, 4 stages per wavefront                         a few tiles only: latency-bound layers
+//    S64     32 x  64, 3 stages per wavefront
 //  G* run the generic kernel (any alignment, layout, K):
 //    G128 128 x 128, G64 64 x 64 (32x32 MFMA shapes), G16 16 x 64 (16x16 shapes; M <= 16)
-enum CfgId { CFG_F256 = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_F64S, CFG_F64K, CFG_F256W, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
+enum CfgId { CFG_F256 = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_F64S, CFG_F64K, CFG_F256W, CFG_S32, CFG_S64, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
 
 template <int DT, int ID>
 struct CfgOf;
 //                                             MI TM TN WM WN BKB
-template <int DT> struct CfgOf<DT, CFG_F256>  { typedef Cfg<DT, 32, 4, 4, 2, 2, 128> type; static constexpr int NSTAGE = 2; };
-template <int DT> struct CfgOf<DT, CFG_F128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 2; };
-template <int DT> struct CfgOf<DT, CFG_F128T> { typedef Cfg<DT, 32, 1, 4, 4, 1, 128> type; static constexpr int NSTAGE = 2; };
-template <int DT> struct CfgOf<DT, CFG_F64T>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 3; };
-template <int DT> struct CfgOf<DT, CFG_F64S>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 6; };
-template <int DT> struct CfgOf<DT, CFG_F64K>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 6; };
-template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 32, 4, 2, 2, 4, 128> type; static constexpr int NSTAGE = 2; };
-template <int DT> struct CfgOf<DT, CFG_G128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 0; };
-template <int DT> struct CfgOf<DT, CFG_G64>   { typedef Cfg<DT, 32, 1, 1, 2, 2, 128> type; static constexpr int NSTAGE = 0; };
-template <int DT> struct CfgOf<DT, CFG_G16>   { typedef Cfg<DT, 16, 1, 1, 1, 4, 256> type; static constexpr int NSTAGE = 0; };
+template <int DT> struct CfgOf<DT, CFG_F256>  { typedef Cfg<DT, 32, 4, 4, 2, 2, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F128T> { typedef Cfg<DT, 32, 1, 4, 4, 1, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F64T>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F64S>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 6; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F64K>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 6; static constexpr int KWAYS = 4; };
+template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 32, 4, 2, 2, 4, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_S32>   { typedef Cfg<DT, 32, 1, 1, 1, 1, 128> type; static constexpr int NSTAGE = 4; static constexpr int KWAYS = 4; };
+template <int DT> struct CfgOf<DT, CFG_S64>   { typedef Cfg<DT, 32, 1, 2, 1, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 4; };
+template <int DT> struct CfgOf<DT, CFG_G128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 0; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_G64>   { typedef Cfg<DT, 32, 1, 1, 2, 2, 128> type; static constexpr int NSTAGE = 0; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_G16>   { typedef Cfg<DT, 16, 1, 1, 1, 4, 256> type; static constexpr int NSTAGE = 0; static constexpr int KWAYS = 1; };
 
+constexpr bool cfg_is_stream(int id) { return id == CFG_S32 || id == CFG_S64; }
+
+// threads: of one WAVES_M x WAVES_N grid of wavefronts (the launch has kways times as many);
+// kway_bytes: bytes of k that one wavefront takes in turn when kways wavefronts share a tile
 struct CfgInfo {
-    int bm, bn, bk_bytes, wm, wn, threads, lds_bytes, fast, kways;
+    int bm, bn, bk_bytes, wm, wn, threads, lds_bytes, fast, kways, kway_bytes;
 };
 
 template <int ID>
 constexpr CfgInfo cfg_info() {
     typedef typename CfgOf<DT_F16, ID>::type C;  // identical for every dtype (rows / columns / k bytes)
     constexpr int ns = CfgOf<DT_F16, ID>::NSTAGE;
-    return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS,
-                   ns ? ns * (C::BM + C::BN) * 128 + 1024 : C::LDS_BYTES, ns ? 1 : 0, ID == CFG_F64K ? 4 : 1};
+    constexpr int kw = CfgOf<DT_F16, ID>::KWAYS;
+    constexpr int lds = cfg_is_stream(ID) ? kw * ns * (C::BM + C::BN) * 128
+                                          : (ns ? ns * (C::BM + C::BN) * 128 + 1024 : C::LDS_BYTES);
+    return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, lds, ns ? 1 : 0, kw, cfg_is_stream(ID) ? 128 : 32};
 }
 
 inline CfgInfo cfg_info_host(int id) {
@@ -53,6 +65,8 @@ inline CfgInfo cfg_info_host(int id) {
         case CFG_F64S: return cfg_info<CFG_F64S>();
         case CFG_F64K: return cfg_info<CFG_F64K>();
         case CFG_F256W: return cfg_info<CFG_F256W>();
+        case CFG_S32: return cfg_info<CFG_S32>();
+        case CFG_S64: return cfg_info<CFG_S64>();
         case CFG_G128: return cfg_info<CFG_G128>();
         case CFG_G64: return cfg_info<CFG_G64>();
         default: return cfg_info<CFG_G16>();

@@ -1,0 +1,284 @@
+// Streaming ABFT-protected MFMA GEMM kernel for gfx950 (MI355X): layers of a few output
+// tiles, whose time is the latency of one workgroup's k loop rather than bandwidth or MFMA
+// rate (small-batch MLP layers, batch-1 convolutions).
+//
+// Workgroup tile (32 TM) x (32 TN), four wavefronts that ALL own the whole tile and split
+// the k loop between them: wavefront w multiplies the k tiles t with t % 4 == w (a k tile is
+// 128 bytes of k).  Each wavefront streams its own k tiles from HBM straight into its own
+// ring of LDS stages (global_load_lds_dwordx4) and reads them back as MFMA fragments, so the
+// k loop has no workgroup barrier at all: a wavefront only ever waits for its own copies.
+// The four partial tiles are checked (thread-level scheme: per wavefront, on its partial
+// product) and then added through LDS in wavefront order, every wavefront adding and storing
+// a quarter of the tile.
+//
+// Same operand requirements and LDS row swizzle as the direct-to-LDS kernel.
+#pragma once
+#include "gemm_fast.h"
+
+namespace abft {
+
+template <class CFG, int NST>
+struct StreamLayout {
+    static constexpr int KW = 4;                                 // wavefronts per workgroup
+    static constexpr int WSTAGE = (CFG::BM + CFG::BN) * 128;     // one wavefront's stage
+    static constexpr int LDS_BYTES = KW * NST * WSTAGE;
+    static constexpr int NQA = CFG::BM / 8, NQB = CFG::BN / 8;   // 1 KB copies per k tile
+    static_assert(CFG::WAVES_M == 1 && CFG::WAVES_N == 1 && CFG::MI == 32 && CFG::BKB == 128, "one register tile");
+    static_assert((NST - 1) * (NQA + NQB) <= 63, "vmcnt range");
+    static_assert(LDS_BYTES >= KW * CFG::TM * CFG::TN * 16 * 64 * 4, "LDS for the final sum");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
+};
+
+template <class CFG, int NST, int MODE, bool INJ, bool CONV>
+__global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
+    typedef StreamLayout<CFG, NST> LAY;
+    constexpr int DT = CFG::DT;
+    typedef Mma<DT, 32> MMA;
+    typedef typename MMA::Acc Acc;
+    typedef typename MMA::AccT AccT;
+    constexpr int TM = CFG::TM, TN = CFG::TN, BM = CFG::BM, BN = CFG::BN, BKB = 128;
+    constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
+    constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB;
+    constexpr int ROWB = 128, A_STAGE = BM * ROWB;
+
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    int tile_m, tile_n;
+    tile_of_block((int)blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    const int bm0 = tile_m * BM, bn0 = tile_n * BN;
+    const int M = p.M, N = p.N;
+    const int nkt = p.K / BK;
+    const int n_own = nkt > wave ? (nkt - wave + KW - 1) / KW : 0;  // k tiles wave, wave + 4, ...
+    char* const wbase = smem + wave * (NST * WSTAGE);
+
+    // ---- global -> LDS copy: lane fills slot `lane` of a 1 KB block (8 rows x 8 chunks): row
+    // lane/8, position lane%8, which holds chunk (lane%8) ^ key(row), key(row) = (row >> 1) & 7.
+    // Block q starts at row 8q, so the key is (lane >> 4) + 4 (q & 1): two chunk columns per lane.
+    const int crow = lane >> 3;
+    const int ckc[2] = {(lane & 7) ^ (lane >> 4), (lane & 7) ^ ((lane >> 4) + 4)};
+    const char* aptr[NQA];
+    const char* bptr[NQB];
+    unsigned a_valid = 0, b_valid = 0;
+    long long a_img[CONV ? NQA : 1];
+    int a_ih0[CONV ? NQA : 1], a_iw0[CONV ? NQA : 1];
+    int tap_c[2] = {0, 0}, tap_kh[2] = {0, 0}, tap_kw[2] = {0, 0};  // per chunk column (q parity)
+#pragma unroll
+    for (int q = 0; q < NQB; ++q) {
+        const int n = bn0 + q * 8 + crow;
+        const char* zero = g_zero_chunk + ckc[q & 1] * 16;
+        if (n < N) b_valid |= 1u << q;
+        bptr[q] = n < N ? p.B + ((long long)n * p.ldb + (long long)wave * BK) * ESIZE + ckc[q & 1] * 16 : zero;
+    }
+#pragma unroll
+    for (int q = 0; q < NQA; ++q) {
+        const int m = bm0 + q * 8 + crow;
+        const char* zero = g_zero_chunk + ckc[q & 1] * 16;
+        if (m < M) a_valid |= 1u << q;
+        if constexpr (!CONV) {
+            aptr[q] = m < M ? p.A + ((long long)m * p.lda + (long long)wave * BK) * ESIZE + ckc[q & 1] * 16 : zero;
+        } else {
+            const int mm = m < M ? m : 0;
+            const int img = mm / (p.OH * p.OW);
+            const int rem = mm - img * (p.OH * p.OW);
+            const int oh = rem / p.OW, ow = rem - oh * p.OW;
+            a_img[q] = (long long)img * p.H * p.W * p.Cin;
+            a_ih0[q] = oh * p.stride - p.pad;
+            a_iw0[q] = ow * p.stride - p.pad;
+            aptr[q] = zero;
+        }
+    }
+    if constexpr (CONV) {
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int k = wave * BK + ckc[h] * (16 / ESIZE);
+            const int tap = k / p.Cin;
+            tap_c[h] = k - tap * p.Cin;
+            tap_kh[h] = tap / p.KW;
+            tap_kw[h] = tap - tap_kh[h] * p.KW;
+        }
+    }
+
+    auto issue_loads = [&](int stage) {
+        char* abase = wbase + stage * WSTAGE;
+        char* bbase = abase + A_STAGE;
+#pragma unroll
+        for (int q = 0; q < NQA; ++q) {
+            const char* src = aptr[q];
+            if constexpr (CONV) {
+                // a chunk never straddles a filter tap (Cin is a multiple of the chunk length)
+                const int ih = a_ih0[q] + tap_kh[q & 1], iw = a_iw0[q] + tap_kw[q & 1];
+                const bool ok = ((a_valid >> q) & 1u) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
+                src = ok ? p.A + (a_img[q] + ((long long)ih * p.W + iw) * p.Cin + tap_c[q & 1]) * ESIZE
+                         : g_zero_chunk + ckc[q & 1] * 16;
+            }
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(abase + q * 1024), 16, 0, 0);
+        }
+#pragma unroll
+        for (int q = 0; q < NQB; ++q)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
+                                             (__attribute__((address_space(3))) void*)(bbase + q * 1024), 16, 0, 0);
+    };
+    // to this wavefront's next k tile: KW tiles further along k
+    auto advance = [&]() {
+        if constexpr (!CONV) {
+#pragma unroll
+            for (int q = 0; q < NQA; ++q) aptr[q] += ((a_valid >> q) & 1u) ? KW * BKB : 0;
+        }
+#pragma unroll
+        for (int q = 0; q < NQB; ++q) bptr[q] += ((b_valid >> q) & 1u) ? KW * BKB : 0;
+        if constexpr (CONV) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                tap_c[h] += KW * BK;
+                while (tap_c[h] >= p.Cin) {
+                    tap_c[h] -= p.Cin;
+                    if (++tap_kw[h] == p.KW) {
+                        tap_kw[h] = 0;
+                        ++tap_kh[h];
+                    }
+                }
+            }
+        }
+    };
+
+    Acc acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
+    constexpr int NCHK = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1;
+    Acc chk[NCHK];
+#pragma unroll
+    for (int i = 0; i < NCHK; ++i)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) chk[i][r] = 0;
+
+    // ---- fragment reads: lane l reads row l%32 of a 32-row block, k chunk 2*kk + l/32, stored
+    // at position chunk ^ ((row >> 1) & 7)
+    const int frow = lane & 31, fgrp = lane >> 5, fx = (lane >> 1) & 7;
+    const int a_off = frow * ROWB;
+    const int b_off = A_STAGE + frow * ROWB;
+    int pos[4];
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) pos[kk] = ((2 * kk + fgrp) ^ fx) * 16;
+
+    i32x4 fa[2][TM], fb[2][TN];
+    auto read_frags = [&](const char* st, int kk, int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + pos[kk]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[buf][j] = *reinterpret_cast<const i32x4*>(st + b_off + j * 32 * ROWB + pos[kk]);
+    };
+    auto mma_step = [&](int buf) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
+        if constexpr (MODE == MODE_THREAD && SPLIT) {
+            i32x4 xh, xl;
+            TileChecksumSplitF16<TN>::make(fb[buf], xh, xl);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+                chk[i] = MMA::run(fa[buf][i], xh, chk[i]);
+                chk[TM + i] = MMA::run(fa[buf][i], xl, chk[TM + i]);
+            }
+        } else if constexpr (MODE == MODE_THREAD) {
+            i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
+#pragma unroll
+            for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
+        }
+    };
+
+    // ---- this wavefront's pipeline: own tile i lives in stage i % NST
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        if (s < n_own) {
+            if (s > 0) advance();
+            issue_loads(s);
+        }
+    }
+    constexpr int VM_STEADY = waitcnt_vm((NST - 1) * NL);  // the oldest tile in flight has landed
+    constexpr int VM_ALL = waitcnt_vm(0);
+    if (n_own > 0) {
+        if (n_own >= NST) __builtin_amdgcn_s_waitcnt(VM_STEADY);
+        else __builtin_amdgcn_s_waitcnt(VM_ALL);
+        read_frags(wbase, 0, 0);
+    }
+    int stage = 0;
+    for (int i = 0; i < n_own; ++i) {
+        const char* st = wbase + stage * WSTAGE;
+#pragma unroll
+        for (int kk = 0; kk < 3; ++kk) {
+            read_frags(st, kk + 1, (kk + 1) & 1);
+            mma_step(kk & 1);
+        }
+        const int next = stage + 1 == NST ? 0 : stage + 1;
+        if (i + 1 < n_own) {
+            // every fragment of this stage is in registers: the stage can take tile i + NST
+            __builtin_amdgcn_s_waitcnt(0xC07F);  // lgkmcnt(0)
+            if (i + NST < n_own) {
+                advance();
+                issue_loads(stage);
+                __builtin_amdgcn_s_waitcnt(VM_STEADY);
+            } else {
+                __builtin_amdgcn_s_waitcnt(VM_ALL);
+            }
+            read_frags(wbase + next * WSTAGE, 0, 0);
+        }
+        mma_step(1);
+        stage = next;
+        if constexpr (INJ) {
+            // the running accumulator that holds the products just before k_after
+            if (wave + KW * i == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, 0));
+        }
+    }
+    if constexpr (INJ) {
+        // a fault in a finished accumulator: that of the wavefront holding the last k tile
+        if (p.f_kt < 0 && wave == (nkt - 1) % KW) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, 0));
+    }
+
+    // ---- each wavefront checks its own partial tile, then the partial tiles are added in
+    // wavefront order; wavefront w adds and stores accumulator registers 4w .. 4w+3 of every
+    // MFMA block (rows 8w + 4 (lane / 32) + 0..3 of the block)
+    static_assert(MODE != MODE_GLOBAL, "streaming configurations: unprotected or thread-level");
+    epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
+    __syncthreads();  // the sum reuses every wavefront's stages
+    AccT* red = reinterpret_cast<AccT*>(smem);
+    constexpr int NV = TM * TN * 16;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) red[(wave * NV + (i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
+    __syncthreads();
+    const TileCoords<CFG> tc(tile_m, tile_n, 0);
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            const int col = tc.col(j);
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) {
+                const int r = 4 * wave + rr;
+                AccT v = 0;
+#pragma unroll
+                for (int w = 0; w < KW; ++w) v += red[(w * NV + (i * TN + j) * 16 + r) * 64 + lane];
+                const int row = tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + rr;
+                if (row < M && col < N) {
+                    char* dst = p.C + ((long long)row * p.ldc + col) * CFG::CSIZE;
+                    if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)v;
+                    else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)v;
+                    else *reinterpret_cast<int*>(dst) = v;
+                }
+            }
+        }
+}
+
+}  // namespace abft

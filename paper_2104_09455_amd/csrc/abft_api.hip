@@ -76,7 +76,8 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     };
     if (fast_ok) {
         // fill the 256 compute units before growing the tile
-        if (tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F256 : CFG_F256W;
+        // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
+        if (tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         if (tiles(CFG_F128) >= 128) return mode == ABFT_THREAD ? CFG_F128T : CFG_F128;
         if (tiles(CFG_F64T) > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
         // at most one workgroup per compute unit: deep pipeline and more wavefronts per tile;

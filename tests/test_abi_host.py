@@ -79,7 +79,9 @@ def test_tile_shape_and_tolerance(lib):
     tm, tn, ks = B.abft_tile_shape(8192, 8192, 8192, B.F16)
     assert tm > 0 and tn > 0 and ks > 0 and 8192 % ks == 0
     tm1, tn1, _ = B.abft_tile_shape(1, 1024, 1024, B.F16)
-    assert tm1 == 16  # skinny path
+    assert tm1 == 32  # aligned skinny product: the streaming tile
+    tm2, tn2, _ = B.abft_tile_shape(1, 1024, 1021, B.F16, False)
+    assert tm2 == 16  # unaligned skinny product: the generic 16-row tile
     _, _, ks8 = B.abft_tile_shape(64, 64, 64, B.I8)
     _, _, ks16 = B.abft_tile_shape(64, 64, 64, B.F16)
     assert ks8 == 2 * ks16  # the k tile is fixed in bytes

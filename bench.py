@@ -104,7 +104,7 @@ class LayerRun:
         es = ESIZE[dtype]
         aligned = ((layer.conv.Cin if layer.conv else K) * es) % 16 == 0 and (K * es) % 16 == 0
         _, rn = B.abft_region_shape(M, N, K, self.dt, aligned)
-        self.beta = torch.zeros(-(-N // rn) * K, dtype=torch.float64, device=dev)  # int64 for i8: same size
+        self.beta = torch.zeros(B.abft_beta_bytes(K, N, rn) // 8, dtype=torch.float64, device=dev)
         B.abft_weight_checksum(K, N, self.B, K, B.B_NK, self.dt, self.beta, block_n=rn)  # offline step (Sec. 2.5)
         self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
         self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=dev)

@@ -113,8 +113,8 @@ typedef struct {
  *   C   : M x N row-major, ldc >= N; fp16 / bf16 (rounded to nearest even from the
  *         fp32 accumulators) or int32.
  *   beta: optional weight checksums made earlier by abft_weight_checksum with block_n =
- *         the region_n of abft_region_shape for this problem (K x ceil(N/region_n) doubles,
- *         int64 for I8).  Used by GLOBAL only; NULL makes the call compute them into the
+ *         the region_n of abft_region_shape for this problem (a buffer of abft_beta_bytes).
+ *         Used by GLOBAL only; NULL makes the call compute them into the
  *         workspace first.  THREAD never
  *         reads it: it recomputes tile-local weight checksums in registers (Sec. 5.2.1).
  *   workspace / workspace_bytes: scratch of at least abft_workspace_bytes(...) bytes,
@@ -144,12 +144,19 @@ int abft_conv(const abft_conv_t *conv /* host */, int N, const void *x, const vo
 /* Bytes of workspace abft_gemm / abft_conv want for this problem (0 when none is used). */
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
 
-/* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns, stored
- * k-major: with nb = ceil(N / block_n),
- * beta[k*nb + b] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n], written as
- * doubles (F16 / BF16) or int64 (I8).  block_n <= 0 or >= N gives the plain K-vector B.1 . */
+/* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns: with
+ * nb = ceil(N / block_n), beta_b[k] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n].
+ * The buffer `beta` (device, abft_beta_bytes(K, N, block_n) bytes, 256-byte aligned) receives two
+ * copies: first K x nb values k-major, beta[k*nb + b], as doubles (F16 / BF16) or int64 (I8);
+ * then, at the next multiple of 256 bytes, the copy the product kernel reads inside its loop:
+ * per block b, K floats (F16 / BF16), or K low digits followed by K high digits, one signed
+ * byte each, beta_b[k] = lo + 256 hi (I8; exact for block_n <= 256).
+ * block_n <= 0 or >= N gives the plain K-vector B.1 . */
 int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
                          void *beta, void *stream);
+
+/* Size in bytes of the buffer abft_weight_checksum fills (0 for invalid arguments). */
+size_t abft_beta_bytes(int K, int N, int block_n);
 
 /* Activation checksum (Sec. 2.4 step 1): alpha[k] = sum_m A[m][k] as K doubles / int64.
  * `conv` (host, may be NULL) makes A the lowered matrix of the NHWC tensor passed as A. */

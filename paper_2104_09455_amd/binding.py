@@ -54,7 +54,7 @@ EXPORTS = [
     "abft_select", "abft_tile_shape", "abft_tolerance_coeff", "abft_plan_create", "abft_plan_run",
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
-    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways",
+    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways", "abft_beta_bytes",
 ]
 
 _lib = None
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
                             ctypes.POINTER(Fault), vp]
     L.abft_workspace_bytes.restype = sz
     L.abft_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    L.abft_beta_bytes.restype = sz
+    L.abft_beta_bytes.argtypes = [ci, ci, ci]
     L.abft_weight_checksum.restype = ci
     L.abft_weight_checksum.argtypes = [ci, ci, vp, i64, ci, ci, ci, vp, vp]
     L.abft_activation_checksum.restype = ci
@@ -223,6 +225,10 @@ def abft_tolerance_coeff(K, dtype, mode) -> float:
 
 def abft_workspace_bytes(M, N, K, dtype, mode) -> int:
     return lib().abft_workspace_bytes(M, N, K, dtype, mode)
+
+
+def abft_beta_bytes(K, N, block_n=0) -> int:
+    return lib().abft_beta_bytes(K, N, block_n)
 
 
 def abft_weight_checksum(K, N, B, ldb, b_layout, dtype, beta, block_n=0, stream=None) -> None:

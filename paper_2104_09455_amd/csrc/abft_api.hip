@@ -296,7 +296,7 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 // Block = 32 values of k x 8 lanes over n; blockIdx.y = column block.  Not tuned: offline.
 template <int DT>
 __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int K, int N, long long sn,
-                                                              long long sk, int block_n, void* beta) {
+                                                              long long sk, int block_n, void* beta, char* beta_k) {
     constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
     typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
     __shared__ Wide red[8][32];
@@ -318,6 +318,17 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
         Wide a = 0;
         for (int y = 0; y < 8; ++y) a += red[y][tx];
         reinterpret_cast<Wide*>(beta)[(long long)k * gridDim.y + blockIdx.y] = a;
+        // second copy, per column block along k, for the in-kernel checksum dot product of the
+        // direct-to-LDS kernel: floats, or (int8) balanced base-256 digits, K low then K high
+        if constexpr (DT == DT_I8) {
+            const long long lo = (long long)(signed char)(a & 0xff);
+            const long long hi = (a - lo) >> 8;
+            signed char* d = reinterpret_cast<signed char*>(beta_k) + (long long)blockIdx.y * 2 * K;
+            d[k] = (signed char)lo;
+            d[K + k] = (signed char)(hi < -128 ? -128 : (hi > 127 ? 127 : hi));
+        } else {
+            reinterpret_cast<float*>(beta_k)[(long long)blockIdx.y * K + k] = (float)a;
+        }
     }
 }
 
@@ -367,6 +378,12 @@ int pre_rows_per_block(int bm, int M, int K) {
 // Workspace of the global scheme for the tile configuration `cfg`: per-tile partial
 // checksum dot products, per-column-block weight checksums
 // (the last only used when the caller passes no precomputed ones).  Sized for any dtype.
+// The weight-checksum buffer holds two copies: K x nb wide values (double / int64, k-major) for
+// the activation-checksum kernel's dot products, then, 256-byte aligned, the per-block copy
+// along k for the in-kernel dot product (4 bytes per k and block reserved).
+size_t beta_k_offset(int K, int nb) { return align_up((size_t)K * nb * 8, 256); }
+size_t beta_total_bytes(int K, int nb) { return beta_k_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
+
 WsLayout ws_layout(int M, int N, int K, int cfg) {
     CfgInfo ci = cfg_info_host(cfg);
     const size_t tm = (size_t)cdiv(M, ci.bm), tn = (size_t)cdiv(N, ci.bn);
@@ -374,7 +391,7 @@ WsLayout ws_layout(int M, int N, int K, int cfg) {
     WsLayout w;
     w.off_pd = WS_HEADER;
     w.off_beta = align_up(w.off_pd + tm * tn * n_parts * 8, 256);
-    w.total = align_up(w.off_beta + tn * (size_t)K * 8, 256);
+    w.total = align_up(w.off_beta + beta_total_bytes(K, (int)tn), 256);
     return w;
 }
 
@@ -417,17 +434,19 @@ int select_mode(int M, int N, int K, int dt) {
 }
 
 hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, int layout, int dt, int block_n,
-                                  void* beta, hipStream_t st) {
+                                  void* beta_buf, hipStream_t st) {
     long long sn = layout == ABFT_B_NK ? ldb : 1, sk = layout == ABFT_B_NK ? 1 : ldb;
     if (block_n <= 0 || block_n > N) block_n = N;
+    void* beta = beta_buf;
+    char* beta_k = reinterpret_cast<char*>(beta_buf) + beta_k_offset(K, (int)cdiv(N, block_n));
     dim3 grid((unsigned)cdiv(K, 32), (unsigned)cdiv(N, block_n)), block(256);
     const char* b = reinterpret_cast<const char*>(B);
     if (dt == ABFT_F16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k);
     else if (dt == ABFT_BF16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k);
     else
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k);
     return hipGetLastError();
 }
 
@@ -472,6 +491,22 @@ int validate_common(const Problem& pr, int mode, const uint32_t* flag) {
     if (pr.b_layout == ABFT_B_NK ? pr.ldb < pr.K : pr.ldb < pr.N) return ABFT_E_LD;
     if (pr.ldc < pr.N) return ABFT_E_LD;
     return ABFT_OK;
+}
+
+// Global scheme: where the activation checksum's dot products are formed.  Inside the product
+// kernel (direct-to-LDS configurations) it costs about a tenth of the kernel's time; as a
+// pass of its own over A it costs a launch plus reading A once.  Take the cheaper by estimate
+// (environment variable ABFT_GLOBAL_DOT = fused | pre pins the choice: tuning aid).
+bool fused_global(const Problem& pr, const CfgInfo& ci) {
+    if (!ci.fast) return false;
+    static const int force = [] {
+        const char* e = std::getenv("ABFT_GLOBAL_DOT");
+        return !e ? 0 : (e[0] == 'f' ? 1 : 2);
+    }();
+    if (force) return force == 1;
+    const double t_gemm = 2.0 * pr.M * pr.N * pr.K / (pr.dtype == ABFT_I8 ? 2.0e15 : 1.0e15);
+    const double t_pre = 8.0e-6 + (double)pr.M * pr.K * esize(pr.dtype) / 4.5e12;
+    return 0.09 * t_gemm < t_pre;
 }
 
 int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, size_t ws_bytes, uint32_t* flag,
@@ -537,13 +572,12 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
 
     WsLayout w;
     std::memset(&w, 0, sizeof w);
+    int kmode = mode;  // the kernels' scheme index
     char* ws = reinterpret_cast<char*>(workspace);
     const void* beta_used = beta;
     if (mode == ABFT_GLOBAL) {
         w = ws_layout(pr.M, pr.N, pr.K, cfg);
         if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.total) return ABFT_E_WORKSPACE;
-        g.partial_dots = ws + w.off_pd;
-        g.n_parts = pre_grid_x(pr.K, pr.dtype) * (ci.bm / pre_rows_per_block(ci.bm, pr.M, pr.K));
         g.tol_l1 = tol_bias_coeff(pr.K, pr.dtype, mode);
         if (!beta_used) {
             if (launch_weight_checksum(pr.K, pr.N, pr.B, pr.ldb, pr.b_layout, pr.dtype, ci.bn, ws + w.off_beta,
@@ -551,17 +585,26 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
                 return ABFT_E_HIP;
             beta_used = ws + w.off_beta;
         }
-        // steps 1-2: activation checksum of every row block of the tiling and its partial dot
-        // products with the weight checksums
-        if (launch_act_checksum(pr, nullptr, ci.bm, beta_used, g.tiles_n, ws + w.off_pd, st) != hipSuccess)
-            return ABFT_E_HIP;
+        if (fused_global(pr, ci)) {
+            // the direct-to-LDS kernel forms the activation checksum's dot product with the weight
+            // checksums itself, from the A tiles it multiplies (steps 1-3 inside the product's loop)
+            g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
+        } else {
+            kmode = MODE_GLOBAL_PRE;
+            g.partial_dots = ws + w.off_pd;
+            g.n_parts = pre_grid_x(pr.K, pr.dtype) * (ci.bm / pre_rows_per_block(ci.bm, pr.M, pr.K));
+            // steps 1-2: activation checksum of every row block of the tiling and its partial dot
+            // products with the weight checksums
+            if (launch_act_checksum(pr, nullptr, ci.bm, beta_used, g.tiles_n, ws + w.off_pd, st) != hipSuccess)
+                return ABFT_E_HIP;
+        }
     }
 
     hipError_t e;
     if (g_ev_start && hipEventRecord(g_ev_start, st) != hipSuccess) return ABFT_E_HIP;
-    if (pr.dtype == ABFT_F16) e = launch_gemm_f16(cfg, mode, inj, g, st);
-    else if (pr.dtype == ABFT_BF16) e = launch_gemm_bf16(cfg, mode, inj, g, st);
-    else e = launch_gemm_i8(cfg, mode, inj, g, st);
+    if (pr.dtype == ABFT_F16) e = launch_gemm_f16(cfg, kmode, inj, g, st);
+    else if (pr.dtype == ABFT_BF16) e = launch_gemm_bf16(cfg, kmode, inj, g, st);
+    else e = launch_gemm_i8(cfg, kmode, inj, g, st);
     if (e != hipSuccess) return ABFT_E_HIP;
     if (g_ev_stop && hipEventRecord(g_ev_stop, st) != hipSuccess) return ABFT_E_HIP;
 
@@ -668,6 +711,12 @@ int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int* n_
         bounds[ks] = K;
     }
     return ABFT_OK;
+}
+
+size_t abft_beta_bytes(int K, int N, int block_n) {
+    if (K <= 0 || N <= 0) return 0;
+    if (block_n <= 0 || block_n > N) block_n = N;
+    return beta_total_bytes(K, (int)cdiv(N, block_n));
 }
 
 int abft_weight_checksum(int K, int N, const void* B, int64_t ldb, int b_layout, int dtype, int block_n,
@@ -800,7 +849,7 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
             const bool a16 = d.has_conv ? (d.conv.Cin * es) % 16 == 0 : (d.K * es) % 16 == 0;
             L.beta_block_n = cfg_info_host(pick_cfg(d.M, d.N, d.K, d.dtype, a16 && b16, ABFT_GLOBAL)).bn;
         }
-        if (hipMalloc(&L.beta, (size_t)cdiv(d.N, L.beta_block_n) * d.K * 8) != hipSuccess) { rc = ABFT_E_HIP; break; }
+        if (hipMalloc(&L.beta, beta_total_bytes(d.K, (int)cdiv(d.N, L.beta_block_n))) != hipSuccess) { rc = ABFT_E_HIP; break; }
         if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
         (void)hipMemsetAsync(L.workspace, 0, L.ws_bytes < WS_HEADER ? L.ws_bytes : WS_HEADER, st);
         p->layers.push_back(L);

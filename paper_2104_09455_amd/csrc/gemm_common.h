@@ -21,7 +21,9 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 
 enum { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2 };
-enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2 };
+// MODE_GLOBAL_PRE (kernel-internal): the global scheme with the checksum dot products left by
+// the activation-checksum kernel instead of formed inside the product's loop
+enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3 };
 
 struct Report {  // mirrors abft_report_t
     double lhs, rhs, tau, worst_ratio;
@@ -70,7 +72,10 @@ struct GemmArgs {
     // implicit-GEMM geometry (conv != 0): A is an NHWC tensor
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
     // ABFT outputs
-    const void* partial_dots; // GLOBAL: per tile n_parts partial checksum dot products (double / int64)
+    const char* beta_k;       // GLOBAL, direct-to-LDS kernel: weight checksums per column block for the in-kernel
+                              // checksum dot product: float[K] per block (fp16 / bf16), or K low digits then
+                              // K high digits (balanced base 256, one byte each) per block (int8)
+    const void* partial_dots; // GLOBAL otherwise: per tile n_parts partial checksum dot products (double / int64)
     int n_parts;
     double tol_l1;           // GLOBAL: coefficient of the tile's sum of magnitudes in tau
     unsigned int* flag;      // OR-ed with 1 on mismatch
@@ -403,6 +408,22 @@ struct TileChecksumSplitF16 {
     }
 };
 
+// acc + (half SEL of `packed`, an fp16 or bf16 value) * b, in fp32
+template <int DT, int SEL>
+__device__ __forceinline__ float mul_add_half(int packed, float b, float acc) {
+    if constexpr (DT == DT_F16) {
+        float r;
+        if constexpr (SEL == 0)
+            asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[0,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(b), "v"(acc));
+        else
+            asm("v_fma_mix_f32 %0, %1, %2, %3 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(b), "v"(acc));
+        return r;
+    } else {
+        const float a = bitcast<float>(SEL == 0 ? (packed << 16) : (int)(packed & 0xffff0000));
+        return __builtin_fmaf(a, b, acc);
+    }
+}
+
 // Which form of the tile checksum a configuration uses, and how many checksum
 // accumulators per A fragment that takes.
 template <class CFG>
@@ -479,15 +500,17 @@ __device__ __forceinline__ void inject_fault(typename Mma<CFG::DT, CFG::MI>::Acc
 
 // Checksum epilogue (taken from the accumulators, before down-conversion) and store of C.
 //  GLOBAL: fused output summation (Sec. 2.5) of the workgroup tile, compared right here with
-//          the tile's checksum dot product (Sec. 2.4 steps 3-4): the partial dot products were
-//          left by the activation-checksum kernel, which ran before on the same stream.
+//          the tile's checksum dot product (Sec. 2.4 steps 3-4).  lane_dot (a double, or a
+//          long long for int8) is this lane's share of that dot product when the kernel formed
+//          it itself from the A fragments and the weight checksums; null: the partial dot
+//          products were left by the activation-checksum kernel, which ran before on the stream.
 //  THREAD: the wavefront tile's output summation against the sum of its checksum
 //          accumulators (Sec. 5.2.2), compared here; p.flag is touched only on mismatch.
 template <class CFG, int MODE>
 __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
                                          typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1],
                                          const GemmArgs& p, int tile_m, int tile_n, char* smem, bool store = true,
-                                         int wave_mn = -1) {
+                                         int wave_mn = -1, const void* lane_dot = nullptr) {
     typedef Mma<CFG::DT, CFG::MI> MMA;
     constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
     constexpr bool IS_INT = CFG::DT == DT_I8;
@@ -519,19 +542,28 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             s = wave_sum(s);
             if constexpr (MODE == MODE_GLOBAL) {
                 long long* red = reinterpret_cast<long long*>(smem);
+                long long wdot = 0;
+                if (lane_dot) wdot = wave_sum(*reinterpret_cast<const long long*>(lane_dot));
                 __syncthreads();
-                if (lane == 0) red[wave] = s;
+                if (lane == 0) {
+                    red[2 * wave] = s;
+                    red[2 * wave + 1] = wdot;
+                }
                 __syncthreads();
                 if (wave == 0) {
                     // comparison (Sec. 2.4 step 4) for this tile: its output summation against the
                     // sum of the partial checksum dot products the activation-checksum kernel left
-                    long long tot = 0;
-                    for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) tot += red[w];
+                    long long tot = 0, sab = 0;
+                    for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) {
+                        tot += red[2 * w];
+                        sab += red[2 * w + 1];
+                    }
                     const long long t = (long long)tile_m * p.tiles_n + tile_n;
-                    const long long* pd = reinterpret_cast<const long long*>(p.partial_dots) + t * p.n_parts;
-                    long long sab = 0;
-                    for (int c = lane; c < p.n_parts; c += 64) sab += pd[c];
-                    sab = wave_sum(sab);
+                    if (!lane_dot) {
+                        const long long* pd = reinterpret_cast<const long long*>(p.partial_dots) + t * p.n_parts;
+                        for (int c = lane; c < p.n_parts; c += 64) sab += pd[c];
+                        sab = wave_sum(sab);
+                    }
                     if (lane == 0) {
                         const bool bad = tot != sab;
                         if (bad) atomicOr(p.flag, 1u);
@@ -581,28 +613,33 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             double F2 = wave_sum((double)f2);
             if constexpr (MODE == MODE_GLOBAL) {
                 double L1 = wave_sum((double)l1);
+                double wdot = 0.0;
+                if (lane_dot) wdot = wave_sum(*reinterpret_cast<const double*>(lane_dot));
                 double* red = reinterpret_cast<double*>(smem);
                 __syncthreads();
                 if (lane == 0) {
-                    red[3 * wave] = s;
-                    red[3 * wave + 1] = F2;
-                    red[3 * wave + 2] = L1;
+                    red[4 * wave] = s;
+                    red[4 * wave + 1] = F2;
+                    red[4 * wave + 2] = L1;
+                    red[4 * wave + 3] = wdot;
                 }
                 __syncthreads();
                 if (wave == 0) {
                     // comparison (Sec. 2.4 step 4) for this tile: its output summation against the
                     // sum of the partial checksum dot products the activation-checksum kernel left
-                    double ts = 0.0, tf = 0.0, tl = 0.0;
+                    double ts = 0.0, tf = 0.0, tl = 0.0, sab = 0.0;
                     for (int w = 0; w < CFG::WAVES_M * CFG::WAVES_N; ++w) {
-                        ts += red[3 * w];
-                        tf += red[3 * w + 1];
-                        tl += red[3 * w + 2];
+                        ts += red[4 * w];
+                        tf += red[4 * w + 1];
+                        tl += red[4 * w + 2];
+                        sab += red[4 * w + 3];
                     }
                     const long long t = (long long)tile_m * p.tiles_n + tile_n;
-                    const double* pd = reinterpret_cast<const double*>(p.partial_dots) + t * p.n_parts;
-                    double sab = 0.0;
-                    for (int c = lane; c < p.n_parts; c += 64) sab += pd[c];
-                    sab = wave_sum(sab);
+                    if (!lane_dot) {
+                        const double* pd = reinterpret_cast<const double*>(p.partial_dots) + t * p.n_parts;
+                        for (int c = lane; c < p.n_parts; c += 64) sab += pd[c];
+                        sab = wave_sum(sab);
+                    }
                     if (lane == 0) {
                         const double frob = __builtin_sqrt(tf);
                         const double tau = p.tol_coeff * frob + p.tol_l1 * tl;

@@ -50,17 +50,21 @@ constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 template <class CFG, int NSTAGE, int KWAYS>
 struct FastLayout {
     static constexpr int ROWB = 128;                            // bytes per LDS row
-    static constexpr int A_STAGE = CFG::BM * ROWB;
-    static constexpr int STAGE = (CFG::BM + CFG::BN) * ROWB;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE;
     static constexpr int WAVES = CFG::WAVES_M * CFG::WAVES_N * KWAYS;
+    static constexpr int A_STAGE = CFG::BM * ROWB;
+    static constexpr int AB_STAGE = (CFG::BM + CFG::BN) * ROWB;
+    // global scheme: every wavefront also copies the k tile's 256 bytes of weight checksums
+    // (of the workgroup's column block) into a slot of its own behind the operand tiles
+    static constexpr int BETA_SLOT = 256;
+    static constexpr int STAGE = AB_STAGE + WAVES * BETA_SLOT;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE;
     static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
     static_assert(CFG::MI == 32 && CFG::BKB == 128, "32x32 MFMA shapes, 128-byte k tile");
     static_assert(KWAYS == 1 || KWAYS == 4, "one wavefront per k step or one per tile");
     static_assert(KWAYS == 1 || NSTAGE * STAGE >= WAVES * CFG::TM * CFG::TN * 16 * 64 * 4, "LDS for the final sum");
-    static_assert((NSTAGE - 2) * (NQA + NQB) <= 63, "vmcnt range");
+    static_assert((NSTAGE - 2) * (NQA + NQB + 1) <= 63, "vmcnt range");
 };
 
 template <class CFG, int NSTAGE, int MODE, bool INJ, bool CONV, bool SPLITK, int KWAYS>
@@ -74,6 +78,10 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     constexpr int ROWB = LAY::ROWB, A_STAGE = LAY::A_STAGE, STAGE = LAY::STAGE;
     constexpr int WAVES = LAY::WAVES, NQA = LAY::NQA, NQB = LAY::NQB;
     constexpr int NQ = NQA > NQB ? NQA : NQB;
+    constexpr bool GDOT = MODE == MODE_GLOBAL;  // in-kernel checksum dot product
+    constexpr int EMODE = MODE == MODE_GLOBAL_PRE ? MODE_GLOBAL : MODE;  // the epilogue's scheme
+    constexpr bool IS_INT = DT == DT_I8;
+    typedef typename std::conditional<IS_INT, long long, double>::type Wide;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -139,6 +147,15 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
             aptr[q] = zero;
         }
     }
+    // weight checksums of this tile's column block: lane l copies bytes 4l .. 4l+3 of the k tile's
+    // 256 (fp16 / bf16: float l of 64; int8: low digits in lanes 0-31, high digits in lanes 32-63)
+    const char* beta_ptr = zero;
+    if constexpr (GDOT) {
+        const long long blk = (long long)tile_n * p.K;
+        if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (long long)kt_first * BK + (lane & 31) * 4;
+        else beta_ptr = p.beta_k + (blk + (long long)kt_first * BK + lane) * 4;
+    }
+    constexpr int BETA_ADV = IS_INT ? BK : BK * 4;
     if constexpr (CONV) {
         const int k = kt_first * BK + ckc * (16 / ESIZE);
         const int tap = k / p.Cin;
@@ -192,8 +209,13 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         for (int q = 0; q < NQB; ++q)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
                                              (__attribute__((address_space(3))) void*)(bbase + q * WAVES * 1024), 16, 0, 0);
+        if constexpr (GDOT)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)beta_ptr,
+                                             (__attribute__((address_space(3))) void*)(smem + stage * STAGE + LAY::AB_STAGE + wave * LAY::BETA_SLOT),
+                                             4, 0, 0);
     };
     auto advance = [&]() {
+        if constexpr (GDOT) beta_ptr += BETA_ADV;
         if constexpr (!CONV) {
 #pragma unroll
             for (int q = 0; q < NQA; ++q) aptr[q] += ((a_valid >> q) & 1u) ? BKB : 0;
@@ -239,6 +261,48 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
 
     // fragments of one k step: double buffered so that the reads of step kk+1 run under
     // the MFMAs of step kk
+    // Global scheme, in-kernel checksum dot product (Sec. 2.4 steps 1-3 fused into the loop):
+    // sum over the tile's rows m and all k of A[m][k] * beta_j[k].  Every lane re-reads from LDS
+    // the NQA chunks of the A tile that it copied itself (row-major slots, free of bank
+    // conflicts; together the lanes cover the tile exactly once) and multiplies them with the
+    // 8 (16 for int8) weight checksums of its k chunk, with vector FMAs / dot4 that run beside
+    // the MFMAs.  Per k tile the fp32 / int32 partial sums move into a wide accumulator.
+    const int beta_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + ckc * (IS_INT ? 16 : 32);
+    float dot_f[4] = {0.f, 0.f, 0.f, 0.f};
+    int dot_lo = 0, dot_hi = 0;
+    Wide lane_dot = 0;
+    auto dot_tile = [&](const char* st) {
+        if constexpr (GDOT) {
+            const i32x4 b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
+            const i32x4 b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
+#pragma unroll
+            for (int q = 0; q < NQA; ++q) {
+                const i32x4 c = *reinterpret_cast<const i32x4*>(st + (q * WAVES + wave) * 1024 + lane * 16);
+                if constexpr (IS_INT) {
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        dot_lo = __builtin_amdgcn_sdot4(c[d], b0[d], dot_lo, false);  // low digits
+                        dot_hi = __builtin_amdgcn_sdot4(c[d], b1[d], dot_hi, false);  // high digits
+                    }
+                } else {
+#pragma unroll
+                    for (int d = 0; d < 4; ++d) {
+                        const float w0 = bitcast<float>(d < 2 ? b0[2 * d] : b1[2 * d - 4]);
+                        const float w1 = bitcast<float>(d < 2 ? b0[2 * d + 1] : b1[2 * d - 3]);
+                        dot_f[q & 3] = mul_add_half<DT, 0>(c[d], w0, dot_f[q & 3]);
+                        dot_f[q & 3] = mul_add_half<DT, 1>(c[d], w1, dot_f[q & 3]);
+                    }
+                }
+            }
+            if constexpr (IS_INT) {
+                lane_dot += (long long)dot_lo + 256ll * (long long)dot_hi;
+                dot_lo = dot_hi = 0;
+            } else {
+                lane_dot += (double)((dot_f[0] + dot_f[1]) + (dot_f[2] + dot_f[3]));
+                dot_f[0] = dot_f[1] = dot_f[2] = dot_f[3] = 0.f;
+            }
+        }
+    };
     i32x4 fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* st, int kk, int buf) {
         const int ps = KWAYS > 1 ? pos_k : pos[kk];
@@ -273,7 +337,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     // being multiplied.  The workgroup barrier sits before the last k step of each tile,
     // whose fragments are already in registers, so the barrier wait, the issue of the next
     // copies and the first fragment reads of the next tile all run under those MFMAs.
-    constexpr int NL = NQA + NQB;  // copies per wave per tile
+    constexpr int NL = NQA + NQB + (GDOT ? 1 : 0);  // copies per wave per tile
 #pragma unroll
     for (int t = 0; t < NSTAGE; ++t) {
         if (t < nkt) {
@@ -290,13 +354,13 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     else if (nkt >= NSTAGE) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NL));  // tile 0 has landed
     else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
-    read_frags(smem, 0, 0);
     int stage = 0;
     // one k tile; CUR is the fragment buffer that holds the step multiplied after the barrier
     // (a compile-time constant, so that the fragment arrays stay in registers)
     auto tile_step = [&](int kt, auto cur_c) {
         constexpr int CUR = decltype(cur_c)::value;
         const char* st = smem + stage * STAGE;
+        dot_tile(st);
         if constexpr (KWAYS == 1) {
 #pragma unroll
             for (int kk = 0; kk < 3; ++kk) {
@@ -304,14 +368,18 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
                 mma_step(kk & 1);
                 if constexpr (MODE != MODE_THREAD) {
                     // fragment reads of the next step go out early, one per MFMA, so that the last
-                    // of them has the rest of the step's MFMAs to land
+                    // of them has the rest of the step's MFMAs to land; the global scheme's reads
+                    // and vector FMAs of the checksum dot product are spread between the MFMAs
                     constexpr int NF = TM + TN, NM = TM * TN;
 #pragma unroll
-                    for (int g = 0; g < NF; ++g) {
+                    for (int g = 0; g < NM; ++g) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);  // 1 LDS read
+                        if (g < NF) {  // LDS reads
+                            if (GDOT && kk == 0) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                            else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+                        }
+                        if constexpr (GDOT) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // 2 VALU
                     }
-                    __builtin_amdgcn_sched_group_barrier(0x008, NM > NF ? NM - NF : 0, 0);
                 }
             }
         }
@@ -338,6 +406,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
                 inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, wave_mn));
         }
     };
+    read_frags(smem, 0, 0);
     if constexpr (KWAYS == 1) {
         // the last of the four k steps sits in buffer 1
         for (int kt = 0; kt < nkt; ++kt) tile_step(kt, std::integral_constant<int, 1>());
@@ -357,9 +426,9 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     if constexpr (KWAYS > 1) {
         // ---- several wavefronts per register tile: each checks its own partial tile (thread-level
         // scheme), then the partial tiles are added through LDS in wavefront order
-        static_assert(MODE != MODE_GLOBAL && !SPLITK, "k-ways configurations: unprotected or thread-level, unsplit");
+        static_assert(EMODE != MODE_GLOBAL && !SPLITK, "k-ways configurations: unprotected or thread-level, unsplit");
         typedef typename MMA::AccT AccT;
-        epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, wave_mn);
+        epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, false, wave_mn);
         AccT* red = reinterpret_cast<AccT*>(smem);
         constexpr int NV = TM * TN * 16;
 #pragma unroll
@@ -387,12 +456,12 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         return;
     }
     if (!SPLITK || ksplit <= 1) {
-        epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem);
+        epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &lane_dot : nullptr);
         return;
     }
     // ---- split-K: check this slice's partial tile (thread-level scheme), publish it, and let
     // the workgroup that arrives last add the slices in slice order and store C
-    epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false);
+    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, false);
     typedef typename MMA::AccT AccT;
     constexpr int TILE_ELEMS = BM * BN;
     typedef AccT Acc4 __attribute__((ext_vector_type(4)));

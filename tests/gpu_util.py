@@ -69,7 +69,7 @@ def run_gemm(A, Bm, dtype, mode, layout=B.B_NK, inject=None, use_beta=False, wan
         aligned = misalign == 0 and (K * es) % 16 == 0 and (lda * es) % 16 == 0 and (ldb * es) % 16 == 0 \
             and layout == B.B_NK
         _, rn = B.abft_region_shape(M, N, K, dt, aligned)
-        beta = torch.zeros(-(-N // rn) * K, dtype=torch.float64, device=DEV)
+        beta = torch.zeros(B.abft_beta_bytes(K, N, rn) // 8, dtype=torch.float64, device=DEV)
         B.abft_weight_checksum(K, N, dB.data_ptr() + misalign * es, ldb, layout, dt, beta, block_n=rn)
     B.abft_gemm(M, N, K, dA.data_ptr() + misalign * es, lda, dB.data_ptr() + misalign * es, ldb, layout,
                 dC, ldc, dt, mode, beta=beta, workspace=ws, workspace_bytes=wsb, fault_flag=flag,

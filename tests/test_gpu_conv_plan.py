@@ -64,7 +64,7 @@ def test_conv_parity(ci, mode, dtype):
         if dtype == "i8":
             assert rep.lhs == near.lhs and rep.rhs == near.rhs
         else:
-            assert rep.rhs == pytest.approx(near.rhs, rel=1e-11, abs=1e-9)
+            assert abs(rep.rhs - near.rhs) <= 0.1 * near.tau + 1e-9
             assert rep.worst_ratio < 0.5
 
 

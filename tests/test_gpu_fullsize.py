@@ -31,7 +31,7 @@ class Big:
         self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
         self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=DEV)
         self.rm, self.rn = B.abft_region_shape(M, N, K, self.dt, True)
-        self.beta = torch.zeros(-(-N // self.rn) * K, dtype=torch.float64, device=DEV)
+        self.beta = torch.zeros(B.abft_beta_bytes(K, N, self.rn) // 8, dtype=torch.float64, device=DEV)
         B.abft_weight_checksum(K, N, self.dB, K, B.B_NK, self.dt, self.beta, block_n=self.rn)
 
     def run(self, mode, inject=None):
@@ -142,7 +142,7 @@ def test_ragged_large_uses_the_big_tile_and_matches():
             chk = oracle.region_check(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]),
                                       oracle.gemm(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]), "f16"),
                                       "f16", 0, min(256, M - r0), 0, min(256, N - c0))
-            assert rep.rhs == pytest.approx(chk.rhs, rel=1e-11, abs=1e-9)
+            assert abs(rep.rhs - chk.rhs) <= 0.1 * chk.tau + 1e-9
             assert rep.tau == pytest.approx(chk.tau, rel=1e-3)
     # injected fault in the last (clipped) tile row / column is still seen
     for mode in (B.GLOBAL, B.THREAD):

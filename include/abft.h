@@ -201,8 +201,9 @@ int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int *n_
 /* Interleaved split along k inside a workgroup: `ways` wavefronts share each register tile,
  * wavefront w multiplying the k with (k / step) % ways == w; their partial tiles are added in
  * wavefront order at the end (bit-reproducible).  THREAD makes its tile comparisons per
- * wavefront, on those partial products.  ways = 1: not split.  Combines with abft_k_slices
- * (each slice is then interleaved). */
+ * wavefront, on those partial products; GLOBAL compares the tile of the added-up partial
+ * products (the split then only matters for where an injected fault lands).  ways = 1: not
+ * split.  Combines with abft_k_slices (each slice is then interleaved). */
 int abft_k_ways(int M, int N, int K, int dtype, int aligned, int mode, int *ways, int *step);
 
 /* Comparison tolerance (the paper states none; Sec. 2.4 step 4 says "compare"): a

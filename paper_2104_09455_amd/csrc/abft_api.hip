@@ -77,9 +77,9 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     if (fast_ok) {
         // fill the 256 compute units before growing the tile
         // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
-        if (tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
-        if (tiles(CFG_F128) >= 128) return mode == ABFT_THREAD ? CFG_F128T : CFG_F128;
-        if (tiles(CFG_F64T) > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
+        if (N > 128 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
+        if (tiles(CFG_F128) >= 128) return (mode == ABFT_THREAD || N <= 128) ? CFG_F128T : CFG_F128;
+        if (tiles(CFG_F64T) > 256 || (mode == ABFT_GLOBAL && tiles(CFG_F64T) > 64)) return CFG_F64T;
         // at most one workgroup per compute unit: deep pipeline and more wavefronts per tile;
         // very few tiles with a long k loop are split along k across workgroups instead
         const long long nkt = ((long long)K * esize(dt)) / 128;
@@ -499,6 +499,7 @@ int validate_common(const Problem& pr, int mode, const uint32_t* flag) {
 // (environment variable ABFT_GLOBAL_DOT = fused | pre pins the choice: tuning aid).
 bool fused_global(const Problem& pr, const CfgInfo& ci) {
     if (!ci.fast) return false;
+    if (ci.kways > 1) return true;  // streaming configurations have no other variant
     static const int force = [] {
         const char* e = std::getenv("ABFT_GLOBAL_DOT");
         return !e ? 0 : (e[0] == 'f' ? 1 : 2);

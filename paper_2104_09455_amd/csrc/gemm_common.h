@@ -11,6 +11,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 namespace abft {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
@@ -423,6 +425,46 @@ __device__ __forceinline__ float mul_add_half(int packed, float b, float acc) {
         return __builtin_fmaf(a, b, acc);
     }
 }
+
+// Running checksum dot product of the global scheme inside a product kernel (Sec. 2.4 steps 1-3):
+// sum of A[m][k] * beta[k] over 16-byte chunks of A read back from LDS, each with the weight
+// checksums of its 8 (fp16 / bf16) or 16 (int8) values of k: b0, b1 = 8 floats, or 16 low digits
+// and 16 high digits (balanced base 256).  Products are summed in fp32 / int32 within a k tile
+// (at most a few dozen terms per lane) and in double / int64 above that.
+template <int DT>
+struct ChecksumDot {
+    typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
+    float f[4] = {0.f, 0.f, 0.f, 0.f};
+    int lo = 0, hi = 0;
+    Wide total = 0;
+    __device__ __forceinline__ void chunk(const i32x4& c, const i32x4& b0, const i32x4& b1, int slot) {
+        if constexpr (DT == DT_I8) {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                lo = __builtin_amdgcn_sdot4(c[d], b0[d], lo, false);
+                hi = __builtin_amdgcn_sdot4(c[d], b1[d], hi, false);
+            }
+        } else {
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const float w0 = bitcast<float>(d < 2 ? b0[2 * d] : b1[2 * d - 4]);
+                const float w1 = bitcast<float>(d < 2 ? b0[2 * d + 1] : b1[2 * d - 3]);
+                f[slot & 3] = mul_add_half<DT, 0>(c[d], w0, f[slot & 3]);
+                f[slot & 3] = mul_add_half<DT, 1>(c[d], w1, f[slot & 3]);
+            }
+        }
+    }
+    // end of a k tile
+    __device__ __forceinline__ void flush() {
+        if constexpr (DT == DT_I8) {
+            total += (long long)lo + 256ll * (long long)hi;
+            lo = hi = 0;
+        } else {
+            total += (double)((f[0] + f[1]) + (f[2] + f[3]));
+            f[0] = f[1] = f[2] = f[3] = 0.f;
+        }
+    }
+};
 
 // Which form of the tile checksum a configuration uses, and how many checksum
 // accumulators per A fragment that takes.

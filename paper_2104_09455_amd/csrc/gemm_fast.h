@@ -81,7 +81,6 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     constexpr bool GDOT = MODE == MODE_GLOBAL;  // in-kernel checksum dot product
     constexpr int EMODE = MODE == MODE_GLOBAL_PRE ? MODE_GLOBAL : MODE;  // the epilogue's scheme
     constexpr bool IS_INT = DT == DT_I8;
-    typedef typename std::conditional<IS_INT, long long, double>::type Wide;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
 
@@ -268,39 +267,15 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     // 8 (16 for int8) weight checksums of its k chunk, with vector FMAs / dot4 that run beside
     // the MFMAs.  Per k tile the fp32 / int32 partial sums move into a wide accumulator.
     const int beta_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + ckc * (IS_INT ? 16 : 32);
-    float dot_f[4] = {0.f, 0.f, 0.f, 0.f};
-    int dot_lo = 0, dot_hi = 0;
-    Wide lane_dot = 0;
+    ChecksumDot<DT> dot;
     auto dot_tile = [&](const char* st) {
         if constexpr (GDOT) {
             const i32x4 b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
             const i32x4 b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
 #pragma unroll
-            for (int q = 0; q < NQA; ++q) {
-                const i32x4 c = *reinterpret_cast<const i32x4*>(st + (q * WAVES + wave) * 1024 + lane * 16);
-                if constexpr (IS_INT) {
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        dot_lo = __builtin_amdgcn_sdot4(c[d], b0[d], dot_lo, false);  // low digits
-                        dot_hi = __builtin_amdgcn_sdot4(c[d], b1[d], dot_hi, false);  // high digits
-                    }
-                } else {
-#pragma unroll
-                    for (int d = 0; d < 4; ++d) {
-                        const float w0 = bitcast<float>(d < 2 ? b0[2 * d] : b1[2 * d - 4]);
-                        const float w1 = bitcast<float>(d < 2 ? b0[2 * d + 1] : b1[2 * d - 3]);
-                        dot_f[q & 3] = mul_add_half<DT, 0>(c[d], w0, dot_f[q & 3]);
-                        dot_f[q & 3] = mul_add_half<DT, 1>(c[d], w1, dot_f[q & 3]);
-                    }
-                }
-            }
-            if constexpr (IS_INT) {
-                lane_dot += (long long)dot_lo + 256ll * (long long)dot_hi;
-                dot_lo = dot_hi = 0;
-            } else {
-                lane_dot += (double)((dot_f[0] + dot_f[1]) + (dot_f[2] + dot_f[3]));
-                dot_f[0] = dot_f[1] = dot_f[2] = dot_f[3] = 0.f;
-            }
+            for (int q = 0; q < NQA; ++q)
+                dot.chunk(*reinterpret_cast<const i32x4*>(st + (q * WAVES + wave) * 1024 + lane * 16), b0, b1, q);
+            dot.flush();
         }
     };
     i32x4 fa[2][TM], fb[2][TN];
@@ -456,7 +431,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         return;
     }
     if (!SPLITK || ksplit <= 1) {
-        epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &lane_dot : nullptr);
+        epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &dot.total : nullptr);
         return;
     }
     // ---- split-K: check this slice's partial tile (thread-level scheme), publish it, and let

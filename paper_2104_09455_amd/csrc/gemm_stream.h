@@ -20,11 +20,12 @@ namespace abft {
 template <class CFG, int NST>
 struct StreamLayout {
     static constexpr int KW = 4;                                 // wavefronts per workgroup
-    static constexpr int WSTAGE = (CFG::BM + CFG::BN) * 128;     // one wavefront's stage
+    static constexpr int AB_STAGE = (CFG::BM + CFG::BN) * 128;
+    static constexpr int WSTAGE = AB_STAGE + 256;                // one wavefront's stage: A, B, weight checksums
     static constexpr int LDS_BYTES = KW * NST * WSTAGE;
     static constexpr int NQA = CFG::BM / 8, NQB = CFG::BN / 8;   // 1 KB copies per k tile
     static_assert(CFG::WAVES_M == 1 && CFG::WAVES_N == 1 && CFG::MI == 32 && CFG::BKB == 128, "one register tile");
-    static_assert((NST - 1) * (NQA + NQB) <= 63, "vmcnt range");
+    static_assert((NST - 1) * (NQA + NQB + 1) <= 63, "vmcnt range");
     static_assert(LDS_BYTES >= KW * CFG::TM * CFG::TN * 16 * 64 * 4, "LDS for the final sum");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 };
@@ -38,7 +39,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     typedef typename MMA::AccT AccT;
     constexpr int TM = CFG::TM, TN = CFG::TN, BM = CFG::BM, BN = CFG::BN, BKB = 128;
     constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
-    constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB;
+    constexpr bool GDOT = MODE == MODE_GLOBAL;  // global scheme: in-kernel checksum dot product
+    constexpr bool IS_INT = DT == DT_I8;
+    constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB + (GDOT ? 1 : 0);
     constexpr int ROWB = 128, A_STAGE = BM * ROWB;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -89,6 +92,15 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             aptr[q] = zero;
         }
     }
+    // weight checksums of this tile's column block: lane l copies bytes 4l .. 4l+3 of the k tile's
+    // 256 (fp16 / bf16: float l of 64; int8: low digits in lanes 0-31, high digits in lanes 32-63)
+    const char* beta_ptr = g_zero_chunk;
+    if constexpr (GDOT) {
+        const long long blk = (long long)tile_n * p.K;
+        if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (long long)wave * BK + (lane & 31) * 4;
+        else beta_ptr = p.beta_k + (blk + (long long)wave * BK + lane) * 4;
+    }
+    constexpr int BETA_ADV = KW * (IS_INT ? BK : BK * 4);
     if constexpr (CONV) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -120,9 +132,13 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         for (int q = 0; q < NQB; ++q)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
                                              (__attribute__((address_space(3))) void*)(bbase + q * 1024), 16, 0, 0);
+        if constexpr (GDOT)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)beta_ptr,
+                                             (__attribute__((address_space(3))) void*)(abase + LAY::AB_STAGE), 4, 0, 0);
     };
     // to this wavefront's next k tile: KW tiles further along k
     auto advance = [&]() {
+        if constexpr (GDOT) beta_ptr += BETA_ADV;
         if constexpr (!CONV) {
 #pragma unroll
             for (int q = 0; q < NQA; ++q) aptr[q] += ((a_valid >> q) & 1u) ? KW * BKB : 0;
@@ -168,6 +184,24 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) pos[kk] = ((2 * kk + fgrp) ^ fx) * 16;
 
+    // global scheme: every lane multiplies the A chunks it copied itself with the weight
+    // checksums of their k chunk (two chunk columns per lane: even and odd 1 KB blocks)
+    ChecksumDot<DT> dot;
+    auto dot_tile = [&](const char* st) {
+        if constexpr (GDOT) {
+            i32x4 b0[2], b1[2];
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const char* bs = st + LAY::AB_STAGE + ckc[h] * (IS_INT ? 16 : 32);
+                b0[h] = *reinterpret_cast<const i32x4*>(bs);
+                b1[h] = *reinterpret_cast<const i32x4*>(bs + (IS_INT ? 128 : 16));
+            }
+#pragma unroll
+            for (int q = 0; q < NQA; ++q)
+                dot.chunk(*reinterpret_cast<const i32x4*>(st + q * 1024 + lane * 16), b0[q & 1], b1[q & 1], q);
+            dot.flush();
+        }
+    };
     i32x4 fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* st, int kk, int buf) {
 #pragma unroll
@@ -213,6 +247,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     int stage = 0;
     for (int i = 0; i < n_own; ++i) {
         const char* st = wbase + stage * WSTAGE;
+        dot_tile(st);
 #pragma unroll
         for (int kk = 0; kk < 3; ++kk) {
             read_frags(st, kk + 1, (kk + 1) & 1);
@@ -246,8 +281,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     // ---- each wavefront checks its own partial tile, then the partial tiles are added in
     // wavefront order; wavefront w adds and stores accumulator registers 4w .. 4w+3 of every
     // MFMA block (rows 8w + 4 (lane / 32) + 0..3 of the block)
-    static_assert(MODE != MODE_GLOBAL, "streaming configurations: unprotected or thread-level");
-    epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
+    static_assert(MODE != MODE_GLOBAL_PRE, "streaming configurations form the checksum dot product themselves");
+    if constexpr (MODE == MODE_THREAD) epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
     __syncthreads();  // the sum reuses every wavefront's stages
     AccT* red = reinterpret_cast<AccT*>(smem);
     constexpr int NV = TM * TN * 16;
@@ -259,26 +294,93 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             for (int r = 0; r < 16; ++r) red[(wave * NV + (i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
     __syncthreads();
     const TileCoords<CFG> tc(tile_m, tile_n, 0);
+    typedef typename ChecksumDot<DT>::Wide Wide;
+    // global scheme: the output summation (Sec. 2.5) runs over the finished values as they are stored
+    Wide s_sum = 0;
+    int s_lo = 0, s_hi = 0;
+    float f2 = 0.f, l1 = 0.f;
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
             const int col = tc.col(j);
+            AccT v[4];
 #pragma unroll
             for (int rr = 0; rr < 4; ++rr) {
                 const int r = 4 * wave + rr;
-                AccT v = 0;
+                v[rr] = 0;
 #pragma unroll
-                for (int w = 0; w < KW; ++w) v += red[(w * NV + (i * TN + j) * 16 + r) * 64 + lane];
+                for (int w = 0; w < KW; ++w) v[rr] += red[(w * NV + (i * TN + j) * 16 + r) * 64 + lane];
                 const int row = tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + rr;
                 if (row < M && col < N) {
                     char* dst = p.C + ((long long)row * p.ldc + col) * CFG::CSIZE;
-                    if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)v;
-                    else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)v;
-                    else *reinterpret_cast<int*>(dst) = v;
+                    if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)v[rr];
+                    else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)v[rr];
+                    else *reinterpret_cast<int*>(dst) = v[rr];
+                }
+            }
+            if constexpr (GDOT) {
+                if constexpr (IS_INT) {
+#pragma unroll
+                    for (int rr = 0; rr < 4; ++rr) {
+                        s_lo += v[rr] & 0xffff;
+                        s_hi += v[rr] >> 16;
+                    }
+                } else {
+                    s_sum += (double)((v[0] + v[1]) + (v[2] + v[3]));
+                    f2 += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
+                    l1 += (__builtin_fabsf(v[0]) + __builtin_fabsf(v[1])) + (__builtin_fabsf(v[2]) + __builtin_fabsf(v[3]));
                 }
             }
         }
+    if constexpr (GDOT) {
+        // comparison (Sec. 2.4 step 4) for this tile
+        if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;
+        s_sum = wave_sum(s_sum);
+        const Wide wdot = wave_sum(dot.total);
+        const double F2 = IS_INT ? 0.0 : wave_sum((double)f2);
+        const double L1 = IS_INT ? 0.0 : wave_sum((double)l1);
+        __syncthreads();  // everyone is done reading the partial tiles
+        double* redd = reinterpret_cast<double*>(smem);
+        Wide* redw = reinterpret_cast<Wide*>(smem) + 2 * KW;
+        if (lane == 0) {
+            redd[2 * wave] = F2;
+            redd[2 * wave + 1] = L1;
+            redw[2 * wave] = s_sum;
+            redw[2 * wave + 1] = wdot;
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double tf = 0.0, tl = 0.0;
+            Wide ts = 0, sab = 0;
+            for (int w = 0; w < KW; ++w) {
+                tf += redd[2 * w];
+                tl += redd[2 * w + 1];
+                ts += redw[2 * w];
+                sab += redw[2 * w + 1];
+            }
+            const unsigned t = (unsigned)(tile_m * p.tiles_n + tile_n);
+            if constexpr (IS_INT) {
+                const bool bad = ts != sab;
+                if (bad) atomicOr(p.flag, 1u);
+                if (p.report)
+                    report_update(p.report, bad ? __builtin_huge_val() : 0.0, (double)ts, (double)sab, 0.0, 0.0, 0.0, t);
+            } else {
+                const double frob = __builtin_sqrt(tf);
+                const double tau = p.tol_coeff * frob + p.tol_l1 * tl;
+                const double res = __builtin_fabs((double)ts - (double)sab);
+                // a sum of squares beyond the fp32 range cannot come from a fault-free tile
+                const bool finite = __builtin_isfinite((double)ts) && __builtin_isfinite((double)sab) && __builtin_isfinite(tf);
+                const bool bad = !finite || !(res <= tau);
+                if (bad) atomicOr(p.flag, 1u);
+                if (p.report) {
+                    const double ratio = !finite ? __builtin_huge_val()
+                                                 : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+                    report_update(p.report, ratio, (double)ts, (double)sab, tau, frob, tl, t);
+                }
+            }
+        }
+    }
 }
 
 }  // namespace abft

@@ -229,7 +229,9 @@ def test_split_k_thread_level(dtype, shape):
     dt = B.F16 if dtype == "f16" else B.I8
     parts = B.abft_k_parts(M, N, K, dt, B.THREAD)
     assert len(parts) > 1 and sorted(k for p in parts for k in p) == list(range(K))
-    assert len(B.abft_k_parts(M, N, K, dt, B.GLOBAL)) == 1      # the global scheme is never split
+    # (the global scheme compares whole tiles after the partial tiles are added: its comparisons
+    # are never split, though its accumulators may be, across the wavefronts of a workgroup)
+    assert len(B.abft_k_slices(M, N, K, dt, B.GLOBAL)) == 1
     if len(B.abft_k_slices(M, N, K, dt, B.THREAD)) > 1:
         assert B.abft_workspace_bytes(M, N, K, dt, B.THREAD) > 0
     tm, tn, ks = B.abft_tile_shape(M, N, K, dt)

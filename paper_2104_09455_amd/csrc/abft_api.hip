@@ -79,18 +79,16 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
         if (N > 128 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         if (tiles(CFG_F128) >= 128) return (mode == ABFT_THREAD || N <= 128) ? CFG_F128T : CFG_F128;
-        if (tiles(CFG_F64T) > 256 || (mode == ABFT_GLOBAL && tiles(CFG_F64T) > 64)) return CFG_F64T;
-        // at most one workgroup per compute unit: deep pipeline and more wavefronts per tile;
-        // very few tiles with a long k loop are split along k across workgroups instead
-        const long long nkt = ((long long)K * esize(dt)) / 128;
-        if (tiles(CFG_F64T) > 64) return CFG_F64K;
-        // a handful of tiles: the time is the latency of one workgroup's k loop, so shrink the
-        // tile to spread the operands over more compute units and let the wavefronts stream
-        // without barriers.  The thread-level scheme takes the tile of two MFMA blocks (its
-        // checksum then needs no cross-lane step).
-        static const bool use_f64s = std::getenv("ABFT_USE_F64S") != nullptr;
-        if (use_f64s && nkt >= 64) return CFG_F64S;
-        return (mode == ABFT_THREAD && N > 32) ? CFG_S64 : CFG_S32;
+        // Fewer tiles than that: the time is the latency of a workgroup's k loop and the rate at
+        // which one compute unit can stream its operands, so the streaming configurations take
+        // over (no barriers in the k loop): 64 x 64 tiles while they fill the chip at most twice,
+        // 32-row tiles for a handful of tiles.  The thread-level scheme takes the 32 x 64 tile
+        // there (its checksum then needs no cross-lane step).
+        const long long t64 = tiles(CFG_F64T);
+        if (t64 <= 64) return (mode == ABFT_THREAD && N > 32) ? CFG_S64 : CFG_S32;
+        if (tiles(CFG_S128) <= 512) return CFG_S128;
+        if (t64 > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
+        return CFG_F64K;
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;
     if (tiles(CFG_G64) >= 1024) return CFG_G128;

@@ -18,9 +18,10 @@ namespace abft {
 //  register tile between them, each with its own LDS stages, no barrier in the k loop):
 //    S32     32 x  32, 4 stages per wavefront                         a few tiles only: latency-bound layers
 //    S64     32 x  64, 3 stages per wavefront
+//    S128    64 x  64, 2 stages per wavefront                         up to about one tile per compute unit
 //  G* run the generic kernel (any alignment, layout, K):
 //    G128 128 x 128, G64 64 x 64 (32x32 MFMA shapes), G16 16 x 64 (16x16 shapes; M <= 16)
-enum CfgId { CFG_F256 = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_F64S, CFG_F64K, CFG_F256W, CFG_S32, CFG_S64, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
+enum CfgId { CFG_F256 = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_F64S, CFG_F64K, CFG_F256W, CFG_S32, CFG_S64, CFG_S128, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
 
 template <int DT, int ID>
 struct CfgOf;
@@ -34,11 +35,12 @@ template <int DT> struct CfgOf<DT, CFG_F64K>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 
 template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 32, 4, 2, 2, 4, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_S32>   { typedef Cfg<DT, 32, 1, 1, 1, 1, 128> type; static constexpr int NSTAGE = 4; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_S64>   { typedef Cfg<DT, 32, 1, 2, 1, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 4; };
+template <int DT> struct CfgOf<DT, CFG_S128>  { typedef Cfg<DT, 32, 2, 2, 1, 1, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_G128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 0; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_G64>   { typedef Cfg<DT, 32, 1, 1, 2, 2, 128> type; static constexpr int NSTAGE = 0; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_G16>   { typedef Cfg<DT, 16, 1, 1, 1, 4, 256> type; static constexpr int NSTAGE = 0; static constexpr int KWAYS = 1; };
 
-constexpr bool cfg_is_stream(int id) { return id == CFG_S32 || id == CFG_S64; }
+constexpr bool cfg_is_stream(int id) { return id == CFG_S32 || id == CFG_S64 || id == CFG_S128; }
 
 // threads: of one WAVES_M x WAVES_N grid of wavefronts (the launch has kways times as many);
 // kway_bytes: bytes of k that one wavefront takes in turn when kways wavefronts share a tile
@@ -67,6 +69,7 @@ inline CfgInfo cfg_info_host(int id) {
         case CFG_F256W: return cfg_info<CFG_F256W>();
         case CFG_S32: return cfg_info<CFG_S32>();
         case CFG_S64: return cfg_info<CFG_S64>();
+        case CFG_S128: return cfg_info<CFG_S128>();
         case CFG_G128: return cfg_info<CFG_G128>();
         case CFG_G64: return cfg_info<CFG_G64>();
         default: return cfg_info<CFG_G16>();

@@ -395,6 +395,28 @@ def main():
         B.abft_plan_set_mode(plan, i, B.AUTO)
     B.abft_plan_destroy(plan)
 
+    # the paper's own selection procedure (Sec. 5.3: profile both schemes per layer before
+    # deployment, keep the faster): a second plan made that way, timed like the first
+    prof = None
+    try:
+        plan2 = B.abft_plan_create([plan_layer(lr) for lr in runs], profile=True)
+        picks2 = [B.abft_plan_mode(plan2, i) for i in range(len(runs))]
+        for _ in range(warmup):
+            B.abft_plan_run_all(plan2, io, flag, -1, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.abft_plan_run_all(plan2, io, flag, -1, stream)
+        torch.cuda.synchronize()
+        wall2 = time.perf_counter() - t0
+        B.abft_plan_destroy(plan2)
+        prof = {"value": round(total_flops / (wall2 / steps) / 1e12, 3), "unit": "TFLOP/s",
+                "ms_per_step": round(1000.0 * wall2 / steps, 5),
+                "overhead_pct_whole_pass": round(100 * (wall2 / wall_none - 1), 2),
+                "modes_picked": {m: sum(1 for x in picks2 if B.MODE_NAMES[x] == m) for m in ("global", "thread")}}
+    except Exception as e:  # reported, never fatal
+        prof = {"error": repr(e)}
+
     out = {
         "metric": "protected GEMM TFLOP/s and ABFT overhead % vs unprotected MFMA GEMM per layer",
         "value": round(value, 3), "unit": "TFLOP/s", "n_gpus": 1, "steps": steps, "warmup": warmup,
@@ -406,6 +428,7 @@ def main():
         "overhead_pct_whole_pass": round(100 * (wall / wall_none - 1), 2),
         "overhead_pct_summed_layers": summarize(rows)["ovh_selector_pct"],
         "false_alarms": flagged,
+        "profiled_selector": prof,
         "graph_replay": None if not isinstance(graph_ms, float) else {
             "ms_per_step": round(graph_ms, 5), "tflops": round(total_flops / (graph_ms * 1e-3) / 1e12, 3),
             "unprotected_ms_per_step": None if graph_none_ms is None else round(graph_none_ms, 5)},

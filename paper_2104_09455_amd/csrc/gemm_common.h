@@ -384,7 +384,25 @@ struct TileChecksumSplitF16 {
         asm("v_fma_mix_f32 %0, %1, -1.0, %2 op_sel:[1,0,0] op_sel_hi:[1,0,0]" : "=v"(r) : "v"(packed), "v"(s));
         return r;
     }
+    // weight of the low operand's products in the checksum sum
+    static constexpr double LO_SCALE = TN == 2 ? 1.0 : 1.0 / 2048.0;
     static __device__ __forceinline__ void make(const i32x4 (&b)[TN], i32x4& hi, i32x4& lo) {
+        if constexpr (TN == 2) {
+            // two fragments: an error-free sum in packed fp16 (six instructions per register):
+            // hi = fl16(x + y) and lo = (x + y) - hi exactly, subnormal results included (the
+            // matrix unit takes fp16 subnormals as they are)
+            typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const f16x2 x = bitcast<f16x2>(b[0][d]), y = bitcast<f16x2>(b[1][d]);
+                const f16x2 s = x + y;
+                const f16x2 yy = s - x;
+                const f16x2 e = (x - (s - yy)) + (y - yy);
+                hi[d] = bitcast<int>(s);
+                lo[d] = bitcast<int>(e);
+            }
+            return;
+        }
 #pragma unroll
         for (int d = 0; d < 4; ++d) {
             float s0 = 0.f, s1 = 0.f;
@@ -708,7 +726,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                             rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
                             rlo += (double)((chk[TM + i][r] + chk[TM + i][r + 1]) + (chk[TM + i][r + 2] + chk[TM + i][r + 3]));
                         }
-                    rsum = wave_sum(rsum + rlo * (1.0 / 2048.0));
+                    rsum = wave_sum(rsum + rlo * TileChecksumSplitF16<TN>::LO_SCALE);
                 } else {
 #pragma unroll
                     for (int i = 0; i < TM; ++i)

@@ -77,8 +77,10 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     if (fast_ok) {
         // fill the 256 compute units before growing the tile
         // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
-        if (N > 128 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
-        if (tiles(CFG_F128) >= 128) return (mode == ABFT_THREAD || N <= 128) ? CFG_F128T : CFG_F128;
+        // (a single k tile: the 128 x 128 tile, of which several fit a compute unit at once)
+        const long long nkt_all = ((long long)K * esize(dt)) / 128;
+        if (N > 128 && nkt_all > 1 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
+        if (tiles(CFG_F128) >= 128) return (mode == ABFT_THREAD || N <= 128 || nkt_all <= 1) ? CFG_F128T : CFG_F128;
         // Fewer tiles than that: the time is the latency of a workgroup's k loop and the rate at
         // which one compute unit can stream its operands, so the streaming configurations take
         // over (no barriers in the k loop): 64 x 64 tiles while they fill the chip at most twice,

@@ -16,6 +16,7 @@
 namespace abft {
 
 typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x16 __attribute__((ext_vector_type(16)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
@@ -558,6 +559,46 @@ __device__ __forceinline__ void inject_fault(typename Mma<CFG::DT, CFG::MI>::Acc
     }
 }
 
+// Store of four consecutive rows x four adjacent columns of 16-bit outputs held by a quad of
+// lanes (MFMA 32x32 layout: a lane holds one column of rows r..r+3 in four registers).  The
+// values are rounded, packed in pairs and transposed inside the quad with two DPP exchanges,
+// so that lane q of the quad writes row r + q, all four columns, as one 8-byte store: a quarter
+// of the store instructions of element-wise writing.  `dst` is this lane's 8-byte destination.
+template <int DT>
+__device__ __forceinline__ int pack_out16(float a, float b) {
+    if constexpr (DT == DT_F16) {
+        typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+        f16x2 h;
+        h[0] = (_Float16)a;
+        h[1] = (_Float16)b;
+        return bitcast<int>(h);
+    } else {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 h;
+        h[0] = (__bf16)a;
+        h[1] = (__bf16)b;
+        return bitcast<int>(h);
+    }
+}
+template <int DT>
+__device__ __forceinline__ void store_quad_rows(float v0, float v1, float v2, float v3, char* dst, int lane) {
+    const int p01 = pack_out16<DT>(v0, v1), p23 = pack_out16<DT>(v2, v3);
+    const bool odd = lane & 1, upper = lane & 2;
+    // exchange with lane ^ 1: even lanes collect rows 0 / 2 of columns (c, c+1), odd lanes rows 1 / 3
+    const int r01 = __builtin_amdgcn_update_dpp(0, p01, 0xB1, 0xF, 0xF, false);
+    const int r23 = __builtin_amdgcn_update_dpp(0, p23, 0xB1, 0xF, 0xF, false);
+    const unsigned sel = odd ? 0x03020706u : 0x05040100u;
+    const int q01 = (int)__builtin_amdgcn_perm((unsigned)r01, (unsigned)p01, sel);
+    const int q23 = (int)__builtin_amdgcn_perm((unsigned)r23, (unsigned)p23, sel);
+    // exchange with lane ^ 2: lanes 0, 1 complete rows 0, 1; lanes 2, 3 rows 2, 3
+    const int t = upper ? q01 : q23;
+    const int x = __builtin_amdgcn_update_dpp(0, t, 0x4E, 0xF, 0xF, false);
+    i32x2 out;
+    out[0] = upper ? x : q01;
+    out[1] = upper ? q23 : x;
+    *reinterpret_cast<i32x2*>(dst) = out;
+}
+
 // Checksum epilogue (taken from the accumulators, before down-conversion) and store of C.
 //  GLOBAL: fused output summation (Sec. 2.5) of the workgroup tile, compared right here with
 //          the tile's checksum dot product (Sec. 2.4 steps 3-4).  lane_dot (a double, or a
@@ -753,6 +794,25 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
 
     if (!store) return;
     // ---- store C (rounded to the output type)
+    if constexpr (CFG::CSIZE == 2 && MI == 32) {
+        // wavefront tiles that lie wholly inside C: 8-byte stores of four columns per lane
+        const int wrow0 = tc.bm0 + tc.wave_m * CFG::WM, wcol0 = tc.bn0 + tc.wave_n * CFG::WN;
+        const bool whole = wrow0 + CFG::WM <= M && wcol0 + CFG::WN <= N && (p.ldc & 3) == 0 &&
+                           (reinterpret_cast<uintptr_t>(p.C) & 7u) == 0;
+        if (whole) {
+            const long long ldcb = p.ldc * 2;
+            char* base = p.C + ((long long)(wrow0 + 4 * tc.lgrp + (lane & 3)) * p.ldc + wcol0 + (tc.lrow & ~3)) * 2;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j)
+                        store_quad_rows<CFG::DT>(acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2],
+                                                 acc[i][j][4 * g + 3], base + (i * 32 + 8 * g) * ldcb + j * 64, lane);
+            return;
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll

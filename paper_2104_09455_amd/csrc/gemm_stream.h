@@ -294,6 +294,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             for (int r = 0; r < 16; ++r) red[(wave * NV + (i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
     __syncthreads();
     const TileCoords<CFG> tc(tile_m, tile_n, 0);
+    // tiles that lie wholly inside C take 8-byte stores of four columns per lane
+    const bool whole = tc.bm0 + BM <= M && tc.bn0 + BN <= N && (p.ldc & 3) == 0 &&
+                       (reinterpret_cast<uintptr_t>(p.C) & 7u) == 0;
     typedef typename ChecksumDot<DT>::Wide Wide;
     // global scheme: the output summation (Sec. 2.5) runs over the finished values as they are stored
     Wide s_sum = 0;
@@ -311,12 +314,25 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 v[rr] = 0;
 #pragma unroll
                 for (int w = 0; w < KW; ++w) v[rr] += red[(w * NV + (i * TN + j) * 16 + r) * 64 + lane];
-                const int row = tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + rr;
-                if (row < M && col < N) {
-                    char* dst = p.C + ((long long)row * p.ldc + col) * CFG::CSIZE;
-                    if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)v[rr];
-                    else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)v[rr];
-                    else *reinterpret_cast<int*>(dst) = v[rr];
+            }
+            if constexpr (CFG::CSIZE == 2) {
+                if (whole) {
+                    // rows 8w + 4 (lane / 32) + 0..3 of this block, four columns per lane
+                    char* dst = p.C + ((long long)(tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + (lane & 3)) * p.ldc +
+                                       tc.bn0 + j * 32 + (tc.lrow & ~3)) * 2;
+                    store_quad_rows<DT>(v[0], v[1], v[2], v[3], dst, lane);
+                }
+            }
+            if (CFG::CSIZE != 2 || !whole) {
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int row = tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + rr;
+                    if (row < M && col < N) {
+                        char* dst = p.C + ((long long)row * p.ldc + col) * CFG::CSIZE;
+                        if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)v[rr];
+                        else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)v[rr];
+                        else *reinterpret_cast<int*>(dst) = v[rr];
+                    }
                 }
             }
             if constexpr (GDOT) {

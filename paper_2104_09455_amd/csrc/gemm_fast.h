@@ -163,32 +163,6 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         tap_kw = tap - tap_kh * p.KW;
     }
 
-    // L2 prefetch (large tile only): with two LDS stages a copy is issued one k tile ahead, less
-    // than an HBM round trip; touching the lines of tile t + 2 when tile t is issued lets the
-    // copies find them in L2.  One 4-byte copy per 128-byte row segment into a dummy LDS area.
-    constexpr bool PREFETCH = NSTAGE == 2 && !CONV && KWAYS == 1 && BM == CFG::THREADS && BN == CFG::THREADS;
-    constexpr int PFD = 2;
-    const char* pfa = zero;
-    const char* pfb = zero;
-    bool pfa_ok = false, pfb_ok = false;
-    if constexpr (PREFETCH) {
-        pfa_ok = bm0 + tid < M;
-        pfb_ok = bn0 + tid < N;
-        if (pfa_ok) pfa = p.A + ((long long)(bm0 + tid) * p.lda + (long long)kt_first * BK) * ESIZE;
-        if (pfb_ok) pfb = p.B + ((long long)(bn0 + tid) * p.ldb + (long long)kt_first * BK) * ESIZE;
-    }
-    auto prefetch_tile = [&](int t) {  // t: k tile index within this workgroup's range
-        if constexpr (PREFETCH) {
-            char* dummy = smem + NSTAGE * STAGE + wave * 256;
-            const long long off = (long long)t * BKB;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pfa_ok ? pfa + off : zero),
-                                             (__attribute__((address_space(3))) void*)dummy, 4, 0, 0);
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(pfb_ok ? pfb + off : zero),
-                                             (__attribute__((address_space(3))) void*)dummy, 4, 0, 0);
-        }
-    };
-    constexpr int NPF = PREFETCH ? 2 : 0;  // prefetch copies per wave per tile
-
     auto issue_loads = [&](int stage) {
         char* abase = smem + stage * STAGE + wave * 1024;
         char* bbase = abase + A_STAGE;
@@ -320,13 +294,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
             issue_loads(t);
         }
     }
-    if constexpr (PREFETCH) {
-        // (waits below count these copies too: they are issued after the tile copies they follow)
-        if (NSTAGE < nkt) prefetch_tile(NSTAGE);
-        if (NSTAGE + 1 < nkt) prefetch_tile(NSTAGE + 1);
-    }
-    if constexpr (PREFETCH) __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
-    else if (nkt >= NSTAGE) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NL));  // tile 0 has landed
+    if (nkt >= NSTAGE) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 1) * NL));  // tile 0 has landed
     else __builtin_amdgcn_s_waitcnt(waitcnt_vm(0));
     __syncthreads();
     int stage = 0;
@@ -362,14 +330,12 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         if (kt + 1 < nkt) {
             // this wave's copies of tile kt+1 have landed (the barrier makes it everyone's) and
             // every wave is done reading this stage, which the copies of tile kt+NSTAGE overwrite
-            // (the prefetch copies issued after tile kt+1's copies may still be in flight)
-            if (kt + NSTAGE + PFD < nkt) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 2) * NL + NPF) & ~0x0F00);
+            if (kt + NSTAGE < nkt) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 2) * NL) & ~0x0F00);
             else __builtin_amdgcn_s_waitcnt(0x0070);  // tail: vmcnt(0) lgkmcnt(0)
             __syncthreads();
             if (kt + NSTAGE < nkt) {
                 advance();
                 issue_loads(stage);
-                if (kt + NSTAGE + PFD < nkt) prefetch_tile(kt + NSTAGE + PFD);
             }
             read_frags(smem + next * STAGE, 0, KWAYS > 1 ? CUR ^ 1 : 0);
         }

@@ -107,28 +107,42 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                 regs[t] = v;
             }
         } else {
-#pragma unroll
-            for (int t = 0; t < NA; ++t) {
-                int m = bm0 + r0 + t * RPP;
-                i32x4 v = {0, 0, 0, 0};
+            // element gather (channel counts that are no multiple of the chunk): the filter taps of
+            // this thread's EPC values of k are the same for all its rows, so they are taken apart once
+            int e_kh[EPC], e_kw[EPC], e_off[EPC];
+            {
                 int c = tap_c, kh = tap_kh, kw = tap_kw;
 #pragma unroll
                 for (int e = 0; e < EPC; ++e) {
-                    int ih = a_ih0[t] + kh, iw = a_iw0[t] + kw;
-                    unsigned x = 0;
-                    if (m < M && k0 + e < K && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
-                        const char* src = p.A + (a_row_off[t] + ((long long)ih * p.W + iw) * p.Cin + c) * ESIZE;
-                        x = ESIZE == 2 ? (unsigned)*reinterpret_cast<const unsigned short*>(src)
-                                       : (unsigned)*reinterpret_cast<const unsigned char*>(src);
-                    }
-                    if constexpr (ESIZE == 2) v[e >> 1] |= (int)(x << (16 * (e & 1)));
-                    else v[e >> 2] |= (int)(x << (8 * (e & 3)));
+                    e_kh[e] = k0 + e < K ? kh : (1 << 28);  // beyond K: never in range
+                    e_kw[e] = kw;
+                    e_off[e] = (kh * p.W + kw) * p.Cin + c;
                     if (++c == p.Cin) {
                         c = 0;
                         if (++kw == p.KW) {
                             kw = 0;
                             ++kh;
                         }
+                    }
+                }
+            }
+#pragma unroll
+            for (int t = 0; t < NA; ++t) {
+                const int m = bm0 + r0 + t * RPP;
+                i32x4 v = {0, 0, 0, 0};
+                if (m < M) {
+                    const char* base = p.A + (a_row_off[t] + ((long long)a_ih0[t] * p.W + a_iw0[t]) * p.Cin) * ESIZE;
+#pragma unroll
+                    for (int e = 0; e < EPC; ++e) {
+                        const unsigned ih = (unsigned)(a_ih0[t] + e_kh[e]), iw = (unsigned)(a_iw0[t] + e_kw[e]);
+                        unsigned x = 0;
+                        if (ih < (unsigned)p.H && iw < (unsigned)p.W) {
+                            const char* src = base + (long long)e_off[e] * ESIZE;
+                            x = ESIZE == 2 ? (unsigned)*reinterpret_cast<const unsigned short*>(src)
+                                           : (unsigned)*reinterpret_cast<const unsigned char*>(src);
+                        }
+                        if constexpr (ESIZE == 2) v[e >> 1] |= (int)(x << (16 * (e & 1)));
+                        else v[e >> 2] |= (int)(x << (8 * (e & 3)));
                     }
                 }
                 regs[t] = v;

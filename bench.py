@@ -106,13 +106,15 @@ class LayerRun:
         _, rn = B.abft_region_shape(M, N, K, self.dt, aligned)
         self.beta = torch.zeros(B.abft_beta_bytes(K, N, rn) // 8, dtype=torch.float64, device=dev)
         B.abft_weight_checksum(K, N, self.B, K, B.B_NK, self.dt, self.beta, block_n=rn)  # offline step (Sec. 2.5)
-        self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
-        self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=dev)
         self.pick = B.abft_select(M, N, K, self.dt)
         self.conv = None
         if layer.conv:
             c = layer.conv
             self.conv = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad)
+            self.wsb = max(B.abft_conv_workspace_bytes(self.conv, N, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
+        else:
+            self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
+        self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=dev)
         self.flops = 2.0 * M * N * K
         self.bytes = ESIZE[dtype] * (M * K + K * N) + CSIZE[dtype] * M * N
         self.ai = self.flops / self.bytes

@@ -144,6 +144,13 @@ int abft_conv(const abft_conv_t *conv /* host */, int N, const void *x, const vo
 /* Bytes of workspace abft_gemm / abft_conv want for this problem (0 when none is used). */
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
 
+/* The same for a convolution, given its geometry (conv: host).  A convolution whose channel
+ * count does not fill 16-byte chunks (an RGB first layer) runs several times faster when the
+ * workspace has this size: the call then copies the input once with its zero border and
+ * re-orders the weights (both into the workspace) so that the product can read whole chunks.
+ * With a workspace of only abft_workspace_bytes the same call gathers element by element. */
+size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int dtype, int mode);
+
 /* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns: with
  * nb = ceil(N / block_n), beta_b[k] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n].
  * The buffer `beta` (device, abft_beta_bytes(K, N, block_n) bytes, 256-byte aligned) receives two

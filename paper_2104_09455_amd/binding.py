@@ -54,7 +54,7 @@ EXPORTS = [
     "abft_select", "abft_tile_shape", "abft_tolerance_coeff", "abft_plan_create", "abft_plan_run",
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
-    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways", "abft_beta_bytes",
+    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
 ]
 
 _lib = None
@@ -78,6 +78,8 @@ def lib() -> ctypes.CDLL:
                             ctypes.POINTER(Fault), vp]
     L.abft_workspace_bytes.restype = sz
     L.abft_workspace_bytes.argtypes = [ci, ci, ci, ci, ci]
+    L.abft_conv_workspace_bytes.restype = sz
+    L.abft_conv_workspace_bytes.argtypes = [ctypes.POINTER(Conv), ci, ci, ci]
     L.abft_beta_bytes.restype = sz
     L.abft_beta_bytes.argtypes = [ci, ci, ci]
     L.abft_weight_checksum.restype = ci
@@ -225,6 +227,10 @@ def abft_tolerance_coeff(K, dtype, mode) -> float:
 
 def abft_workspace_bytes(M, N, K, dtype, mode) -> int:
     return lib().abft_workspace_bytes(M, N, K, dtype, mode)
+
+
+def abft_conv_workspace_bytes(conv, N, dtype, mode) -> int:
+    return lib().abft_conv_workspace_bytes(ctypes.byref(conv), N, dtype, mode)
 
 
 def abft_beta_bytes(K, N, block_n=0) -> int:

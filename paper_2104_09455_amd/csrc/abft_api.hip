@@ -8,6 +8,7 @@
 #include <type_traits>
 #include <cstdio>
 #include <cstdlib>
+#include <algorithm>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -139,6 +140,8 @@ struct PreArgs {
     long long lda;
     int vec;
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
+    long long imgpitch, rowpitch;  // as in GemmArgs
+    int pix;
     void* alpha_out;      // K doubles / int64: the plain checksum (single-slab launches only), or null
     int rows_per_slab;    // rows of one row block of the product's tiling
     int rows_per_block;   // rows one workgroup sums; divides rows_per_slab
@@ -201,18 +204,18 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
                 int rem = m - img * (p.OH * p.OW);
                 int oh = rem / p.OW, ow = rem - oh * p.OW;
                 int ih0 = oh * p.stride - p.pad, iw0 = ow * p.stride - p.pad;
-                const char* base = p.A + (long long)img * p.H * p.W * p.Cin * ESIZE;
+                const char* base = p.A + (long long)img * p.imgpitch * ESIZE;
                 if (p.vec) {
                     int ih = ih0 + e_kh[0], iw = iw0 + e_kw[0];
                     if (ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
-                        v = ld16(base + (((long long)ih * p.W + iw) * p.Cin + e_off[0]) * ESIZE);
+                        v = ld16(base + ((long long)ih * p.rowpitch + (long long)iw * p.pix + e_off[0]) * ESIZE);
                 } else {
 #pragma unroll
                     for (int e = 0; e < EPC; ++e) {
                         int ih = ih0 + e_kh[e], iw = iw0 + e_kw[e];
                         unsigned x = 0;
                         if (k0 + e < p.K && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W) {
-                            const char* src = base + (((long long)ih * p.W + iw) * p.Cin + e_off[e]) * ESIZE;
+                            const char* src = base + ((long long)ih * p.rowpitch + (long long)iw * p.pix + e_off[e]) * ESIZE;
                             x = ESIZE == 2 ? (unsigned)*reinterpret_cast<const unsigned short*>(src)
                                            : (unsigned)*reinterpret_cast<const unsigned char*>(src);
                         }
@@ -333,6 +336,63 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
 }
 
 // ------------------------------------------------------------------------- //
+// Convolutions with few input channels (ResNet's first layer: Cin = 3), lowered to row
+// segments.  For a filter row kh the KW taps x Cin channels are one contiguous run of the
+// input row, so k is re-ordered as (kh, run position) with every run padded to whole 16-byte
+// chunks, the input is copied once with its zero border (so no chunk needs masking) and the
+// product reads whole chunks instead of gathering single elements.
+// ------------------------------------------------------------------------- //
+// padded copy of the NHWC input: out[img][r][x] (row pitch rowp elements), r over H + 2 pad rows,
+// x over the padded row; one 16-byte chunk per thread
+template <int ESIZE>
+__global__ __launch_bounds__(256) void conv_pad_kernel(const char* x, char* out, int H, int WC, int pad, int padC,
+                                                      int Hp, long long rowp, long long chunks_per_row,
+                                                      long long total_chunks) {
+    constexpr int EPC = 16 / ESIZE;
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total_chunks) return;
+    const long long row = t / chunks_per_row;
+    const long long e0 = (t - row * chunks_per_row) * EPC;
+    const long long img = row / Hp;
+    const int ih = (int)(row - img * Hp) - pad;
+    i32x4 v = {0, 0, 0, 0};
+    if (ih >= 0 && ih < H) {
+        const char* src = x + ((img * H + ih) * (long long)WC) * ESIZE;
+#pragma unroll
+        for (int e = 0; e < EPC; ++e) {
+            const long long xe = e0 + e - padC;
+            unsigned val = 0;
+            if (xe >= 0 && xe < WC)
+                val = ESIZE == 2 ? (unsigned)*reinterpret_cast<const unsigned short*>(src + xe * 2)
+                                 : (unsigned)*reinterpret_cast<const unsigned char*>(src + xe);
+            if (ESIZE == 2) v[e >> 1] |= (int)(val << (16 * (e & 1)));
+            else v[e >> 2] |= (int)(val << (8 * (e & 3)));
+        }
+    }
+    *reinterpret_cast<i32x4*>(out + (row * rowp + e0) * ESIZE) = v;
+}
+
+// weights in the lowered order: out[n][kh * segp + r] = B[k = (kh KW + r / Cin) Cin + r % Cin][n] for
+// r < KW Cin and kh < KH, else 0
+template <int ESIZE>
+__global__ __launch_bounds__(256) void conv_weights_kernel(const char* B, long long sn, long long sk, char* out, int N,
+                                                          int Kp, int segp, int seg, int KH) {
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= (long long)N * Kp) return;
+    const int n = (int)(t / Kp), kp = (int)(t - (long long)n * Kp);
+    const int kh = kp / segp, r = kp - kh * segp;
+    if (ESIZE == 2) {
+        unsigned short v = 0;
+        if (r < seg && kh < KH) v = *reinterpret_cast<const unsigned short*>(B + ((long long)n * sn + (long long)(kh * seg + r) * sk) * 2);
+        reinterpret_cast<unsigned short*>(out)[t] = v;
+    } else {
+        unsigned char v = 0;
+        if (r < seg && kh < KH) v = *reinterpret_cast<const unsigned char*>(B + ((long long)n * sn + (long long)(kh * seg + r) * sk));
+        reinterpret_cast<unsigned char*>(out)[t] = v;
+    }
+}
+
+// ------------------------------------------------------------------------- //
 // host helpers
 // ------------------------------------------------------------------------- //
 struct Problem {
@@ -346,6 +406,9 @@ struct Problem {
     bool conv;
     abft_conv_t cg;
     int OH, OW;
+    long long imgpitch, rowpitch;  // conv: input element (img, ih, iw, c) at img*imgpitch + ih*rowpitch + iw*pix + c
+    int pix;
+    int tol_K;                     // K the tolerance is taken for (differs from K for a lowered convolution)
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -353,6 +416,7 @@ bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) ==
 bool a_vectorisable(const Problem& pr) {
     const int es = esize(pr.dtype);
     if (!aligned16(pr.A)) return false;
+    // (a lowered convolution reads chunks at 4-byte aligned addresses: 16-byte loads still apply)
     if (pr.conv) return (pr.cg.Cin * es) % 16 == 0;
     return (pr.K * es) % 16 == 0 && (pr.lda * es) % 16 == 0;
 }
@@ -461,6 +525,7 @@ hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_
     a.vec = a_vectorisable(pr) ? 1 : 0;
     a.conv = pr.conv ? 1 : 0;
     if (pr.conv) {
+        a.imgpitch = pr.imgpitch; a.rowpitch = pr.rowpitch; a.pix = pr.pix;
         a.H = pr.cg.H; a.W = pr.cg.W; a.Cin = pr.cg.Cin; a.KH = pr.cg.KH; a.KW = pr.cg.KW;
         a.stride = pr.cg.stride; a.pad = pr.cg.pad; a.OH = pr.OH; a.OW = pr.OW;
     }
@@ -534,6 +599,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     g.a_vec = avec; g.b_vec = bvec;
     g.conv = pr.conv ? 1 : 0;
     if (pr.conv) {
+        g.imgpitch = pr.imgpitch; g.rowpitch = pr.rowpitch; g.pix = pr.pix;
         g.H = pr.cg.H; g.W = pr.cg.W; g.Cin = pr.cg.Cin; g.KH = pr.cg.KH; g.KW = pr.cg.KW;
         g.stride = pr.cg.stride; g.pad = pr.cg.pad; g.OH = pr.OH; g.OW = pr.OW;
     }
@@ -555,7 +621,8 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     }
     g.flag = flag;
     g.report = reinterpret_cast<Report*>(report);
-    g.tol_coeff = tol_coeff(pr.K, pr.dtype, mode);
+    const int tol_K = pr.tol_K > 0 ? pr.tol_K : pr.K;
+    g.tol_coeff = tol_coeff(tol_K, pr.dtype, mode);
     g.f_row = g.f_col = -1; g.f_bit = 0; g.f_kt = -1;
 
     bool inj = false;
@@ -579,7 +646,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     if (mode == ABFT_GLOBAL) {
         w = ws_layout(pr.M, pr.N, pr.K, cfg);
         if (!ws || (reinterpret_cast<uintptr_t>(ws) & 255u) || ws_bytes < w.total) return ABFT_E_WORKSPACE;
-        g.tol_l1 = tol_bias_coeff(pr.K, pr.dtype, mode);
+        g.tol_l1 = tol_bias_coeff(tol_K, pr.dtype, mode);
         if (!beta_used) {
             if (launch_weight_checksum(pr.K, pr.N, pr.B, pr.ldb, pr.b_layout, pr.dtype, ci.bn, ws + w.off_beta,
                                        st) != hipSuccess)
@@ -629,7 +696,112 @@ int conv_problem(const abft_conv_t* conv, int N, Problem& pr) {
     pr.K = (int)K;
     pr.N = N;
     pr.lda = pr.K;
+    pr.pix = conv->Cin;
+    pr.rowpitch = (long long)conv->W * conv->Cin;
+    pr.imgpitch = pr.rowpitch * conv->H;
     return ABFT_OK;
+}
+
+// Lowering of a convolution with few input channels to row segments (see conv_pad_kernel).
+struct ConvLowering {
+    bool ok;
+    int seg, segp, Kp, Hp;
+    long long rowp;
+    size_t xp_bytes, bp_bytes;
+};
+ConvLowering conv_lowering(const Problem& pr) {
+    ConvLowering lw;
+    std::memset(&lw, 0, sizeof lw);
+    if (!pr.conv) return lw;
+    const abft_conv_t& c = pr.cg;
+    const int es = esize(pr.dtype), epc = 16 / es;
+    if ((c.Cin * es) % 16 == 0) return lw;                      // chunks already line up with the channels
+    if ((long long)c.KW * c.Cin > 64) return lw;                // long runs gain little
+    if (((long long)c.stride * c.Cin * es) % 4 != 0) return lw;  // chunk addresses must be 4-byte aligned
+    lw.seg = c.KW * c.Cin;
+    lw.segp = (int)align_up((size_t)lw.seg, (size_t)epc);
+    // whole k tiles of 128 bytes, so that the direct-to-LDS kernel applies (the tail multiplies
+    // input rows below the window, or zeros, with zero weights)
+    lw.Kp = (int)align_up((size_t)c.KH * lw.segp, (size_t)(128 / es));
+    lw.Hp = c.H + 2 * c.pad;
+    const long long need = std::max((long long)(c.W + 2 * c.pad) * c.Cin,
+                                    (long long)(pr.OW - 1) * c.stride * c.Cin + lw.segp);
+    lw.rowp = (long long)align_up((size_t)need, (size_t)epc);
+    lw.xp_bytes = align_up((size_t)c.batch * lw.Hp * lw.rowp * es, 256);
+    lw.bp_bytes = align_up((size_t)pr.N * lw.Kp * es, 256);
+    lw.ok = true;
+    return lw;
+}
+
+size_t plain_workspace_bytes(int M, int N, int K, int dtype, int mode);
+
+// bytes of workspace that let a convolution run lowered: the lowered product's own scratch, the
+// padded input, the re-ordered weights
+size_t lowered_workspace_bytes(const Problem& pr, const ConvLowering& lw, int mode) {
+    return align_up(plain_workspace_bytes(pr.M, pr.N, lw.Kp, pr.dtype, mode), 256) + lw.xp_bytes + lw.bp_bytes;
+}
+
+// a convolution: lowered to row segments when it qualifies and the workspace has the room
+int run_conv(const Problem& pr, int mode, const void* beta, void* workspace, size_t ws_bytes, uint32_t* flag,
+             abft_report_t* report, const abft_fault_t* inject, hipStream_t st) {
+    const ConvLowering lw = conv_lowering(pr);
+    if (mode == ABFT_AUTO) mode = select_mode(pr.M, pr.N, pr.K, pr.dtype);
+    if (!lw.ok || inject || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+        ws_bytes < lowered_workspace_bytes(pr, lw, mode) || !pr.A || !pr.B)
+        return run_problem(pr, mode, beta, workspace, ws_bytes, flag, report, inject, st);
+    const abft_conv_t& c = pr.cg;
+    const int es = esize(pr.dtype);
+    const size_t inner = align_up(plain_workspace_bytes(pr.M, pr.N, lw.Kp, pr.dtype, mode), 256);
+    char* xp = reinterpret_cast<char*>(workspace) + inner;
+    char* bp = xp + lw.xp_bytes;
+    {
+        const long long chunks_per_row = lw.rowp / (16 / es);
+        const long long total = (long long)c.batch * lw.Hp * chunks_per_row;
+        dim3 grid((unsigned)cdiv(total, 256)), block(256);
+        if (es == 2)
+            hipLaunchKernelGGL(conv_pad_kernel<2>, grid, block, 0, st, reinterpret_cast<const char*>(pr.A), xp, c.H,
+                               c.W * c.Cin, c.pad, c.pad * c.Cin, lw.Hp, lw.rowp, chunks_per_row, total);
+        else
+            hipLaunchKernelGGL(conv_pad_kernel<1>, grid, block, 0, st, reinterpret_cast<const char*>(pr.A), xp, c.H,
+                               c.W * c.Cin, c.pad, c.pad * c.Cin, lw.Hp, lw.rowp, chunks_per_row, total);
+        if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
+        const long long sn = pr.b_layout == ABFT_B_NK ? pr.ldb : 1, sk = pr.b_layout == ABFT_B_NK ? 1 : pr.ldb;
+        dim3 grid2((unsigned)cdiv((long long)pr.N * lw.Kp, 256));
+        if (es == 2)
+            hipLaunchKernelGGL(conv_weights_kernel<2>, grid2, block, 0, st, reinterpret_cast<const char*>(pr.B), sn, sk,
+                               bp, pr.N, lw.Kp, lw.segp, lw.seg, c.KH);
+        else
+            hipLaunchKernelGGL(conv_weights_kernel<1>, grid2, block, 0, st, reinterpret_cast<const char*>(pr.B), sn, sk,
+                               bp, pr.N, lw.Kp, lw.segp, lw.seg, c.KH);
+        if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
+    }
+    Problem q = pr;
+    q.A = xp;
+    q.B = bp;
+    q.b_layout = ABFT_B_NK;
+    q.ldb = lw.Kp;
+    q.K = lw.Kp;
+    q.lda = lw.Kp;
+    q.tol_K = pr.K;
+    q.cg.H = lw.Hp;
+    q.cg.W = (pr.OW - 1) * c.stride + 1;  // every window start lies inside the padded row
+    q.cg.Cin = lw.segp;
+    q.cg.KW = 1;
+    q.cg.pad = 0;
+    q.pix = c.Cin;
+    q.rowpitch = lw.rowp;
+    q.imgpitch = lw.rowp * lw.Hp;
+    return run_problem(q, mode, nullptr, workspace, inner, flag, report, nullptr, st);
+}
+
+size_t plain_workspace_bytes(int M, int N, int K, int dtype, int mode) {
+    if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
+    if (mode == ABFT_GLOBAL) return ws_bytes_any_cfg(M, N, K);
+    // unprotected / thread-level: scratch only where the product would be split along k
+    // (sized for aligned operands; unaligned ones run unsplit and ignore it)
+    const int cfg = pick_cfg(M, N, K, dtype, true, mode);
+    const int ks = pick_ksplit(M, N, K, dtype, cfg, mode);
+    return ks > 1 ? split_layout(M, N, cfg, ks).total : 0;
 }
 
 }  // namespace
@@ -677,19 +849,24 @@ int abft_conv(const abft_conv_t* conv, int N, const void* x, const void* B, int6
     if (rc != ABFT_OK) return rc;
     pr.dtype = dtype; pr.b_layout = b_layout;
     pr.A = x; pr.B = B; pr.ldb = ldb; pr.C = C; pr.ldc = ldc;
-    return run_problem(pr, mode, beta, workspace, workspace_bytes, fault_flag, report, inject,
-                       reinterpret_cast<hipStream_t>(stream));
+    return run_conv(pr, mode, beta, workspace, workspace_bytes, fault_flag, report, inject,
+                    reinterpret_cast<hipStream_t>(stream));
 }
 
 size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode) {
     if (M <= 0 || N <= 0 || K <= 0 || !valid_dtype(dtype)) return 0;
-    if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
-    if (mode == ABFT_GLOBAL) return ws_bytes_any_cfg(M, N, K);
-    // unprotected / thread-level: scratch only where the product would be split along k
-    // (sized for aligned operands; unaligned ones run unsplit and ignore it)
-    const int cfg = pick_cfg(M, N, K, dtype, true, mode);
-    const int ks = pick_ksplit(M, N, K, dtype, cfg, mode);
-    return ks > 1 ? split_layout(M, N, cfg, ks).total : 0;
+    return plain_workspace_bytes(M, N, K, dtype, mode);
+}
+
+size_t abft_conv_workspace_bytes(const abft_conv_t* conv, int N, int dtype, int mode) {
+    Problem pr;
+    std::memset(&pr, 0, sizeof pr);
+    if (N <= 0 || !valid_dtype(dtype) || conv_problem(conv, N, pr) != ABFT_OK) return 0;
+    pr.dtype = dtype;
+    if (mode == ABFT_AUTO) mode = select_mode(pr.M, pr.N, pr.K, dtype);
+    const ConvLowering lw = conv_lowering(pr);
+    const size_t plain = plain_workspace_bytes(pr.M, pr.N, pr.K, dtype, mode);
+    return lw.ok ? std::max(plain, lowered_workspace_bytes(pr, lw, mode)) : plain;
 }
 
 int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int* n_slices, int* bounds, int max_bounds) {
@@ -839,8 +1016,9 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         // offline weight checksum and workspace for the global scheme (kept for either
         // choice so that profiling can time both)
         L.ws_bytes = ws_bytes_any_cfg(d.M, d.N, d.K);
-        for (int md = ABFT_NONE; md <= ABFT_THREAD; md += 2) {
-            const size_t need = abft_workspace_bytes(d.M, d.N, d.K, d.dtype, md);
+        for (int md = ABFT_NONE; md <= ABFT_THREAD; ++md) {
+            const size_t need = d.has_conv ? abft_conv_workspace_bytes(&d.conv, d.N, d.dtype, md)
+                                           : abft_workspace_bytes(d.M, d.N, d.K, d.dtype, md);
             if (need > L.ws_bytes) L.ws_bytes = need;
         }
         {
@@ -928,6 +1106,9 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     // forces another tiling gets them recomputed into the workspace
     const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr), ABFT_GLOBAL)).bn;
     const void* beta = bn_now == L.beta_block_n ? L.beta : nullptr;
+    if (pr.conv)
+        return run_conv(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
+                        reinterpret_cast<hipStream_t>(stream));
     return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
                        reinterpret_cast<hipStream_t>(stream));
 }

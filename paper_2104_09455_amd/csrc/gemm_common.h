@@ -74,6 +74,10 @@ struct GemmArgs {
     int a_vec, b_vec;  // operands qualify for 16-byte loads along k
     // implicit-GEMM geometry (conv != 0): A is an NHWC tensor
     int conv, H, W, Cin, KH, KW, stride, pad, OH, OW;
+    // input element (img, ih, iw, c) sits at img * imgpitch + ih * rowpitch + iw * pix + c (a plain
+    // NHWC tensor: pix = Cin, rowpitch = W Cin, imgpitch = H W Cin)
+    long long imgpitch, rowpitch;
+    int pix;
     // ABFT outputs
     const char* beta_k;       // GLOBAL, direct-to-LDS kernel: weight checksums per column block for the in-kernel
                               // checksum dot product: float[K] per block (fp16 / bf16), or K low digits then

@@ -140,7 +140,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
             const int img = mm / (p.OH * p.OW);
             const int rem = mm - img * (p.OH * p.OW);
             const int oh = rem / p.OW, ow = rem - oh * p.OW;
-            a_img[q] = (long long)img * p.H * p.W * p.Cin;
+            a_img[q] = (long long)img * p.imgpitch;
             a_ih0[q] = oh * p.stride - p.pad;
             a_iw0[q] = ow * p.stride - p.pad;
             aptr[q] = zero;
@@ -173,7 +173,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
                 // a chunk never straddles a filter tap (Cin is a multiple of the chunk length)
                 const int ih = a_ih0[q] + tap_kh, iw = a_iw0[q] + tap_kw;
                 const bool ok = ((a_valid >> q) & 1u) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-                src = ok ? p.A + (a_img[q] + ((long long)ih * p.W + iw) * p.Cin + tap_c) * ESIZE : zero;
+                src = ok ? p.A + (a_img[q] + (long long)ih * p.rowpitch + (long long)iw * p.pix + tap_c) * ESIZE : zero;
             }
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(abase + q * WAVES * 1024), 16, 0, 0);

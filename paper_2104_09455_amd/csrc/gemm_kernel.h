@@ -60,7 +60,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
             int img = mm / (p.OH * p.OW);
             int rem = mm - img * (p.OH * p.OW);
             int oh = rem / p.OW, ow = rem - oh * p.OW;
-            a_row_off[t] = (long long)img * p.H * p.W * p.Cin;
+            a_row_off[t] = (long long)img * p.imgpitch;
             a_ih0[t] = oh * p.stride - p.pad;
             a_iw0[t] = ow * p.stride - p.pad;
         }
@@ -103,20 +103,21 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                 int ih = a_ih0[t] + tap_kh, iw = a_iw0[t] + tap_kw;
                 i32x4 v = {0, 0, 0, 0};
                 if (m < M && k0 < K && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W)
-                    v = ld16(p.A + (a_row_off[t] + ((long long)ih * p.W + iw) * p.Cin + tap_c) * ESIZE);
+                    v = ld16(p.A + (a_row_off[t] + (long long)ih * p.rowpitch + (long long)iw * p.pix + tap_c) * ESIZE);
                 regs[t] = v;
             }
         } else {
             // element gather (channel counts that are no multiple of the chunk): the filter taps of
             // this thread's EPC values of k are the same for all its rows, so they are taken apart once
-            int e_kh[EPC], e_kw[EPC], e_off[EPC];
+            int e_kh[EPC], e_kw[EPC];
+            long long e_off[EPC];
             {
                 int c = tap_c, kh = tap_kh, kw = tap_kw;
 #pragma unroll
                 for (int e = 0; e < EPC; ++e) {
                     e_kh[e] = k0 + e < K ? kh : (1 << 28);  // beyond K: never in range
                     e_kw[e] = kw;
-                    e_off[e] = (kh * p.W + kw) * p.Cin + c;
+                    e_off[e] = kh * p.rowpitch + (long long)kw * p.pix + c;
                     if (++c == p.Cin) {
                         c = 0;
                         if (++kw == p.KW) {
@@ -131,13 +132,13 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                 const int m = bm0 + r0 + t * RPP;
                 i32x4 v = {0, 0, 0, 0};
                 if (m < M) {
-                    const char* base = p.A + (a_row_off[t] + ((long long)a_ih0[t] * p.W + a_iw0[t]) * p.Cin) * ESIZE;
+                    const char* base = p.A + (a_row_off[t] + a_ih0[t] * p.rowpitch + (long long)a_iw0[t] * p.pix) * ESIZE;
 #pragma unroll
                     for (int e = 0; e < EPC; ++e) {
                         const unsigned ih = (unsigned)(a_ih0[t] + e_kh[e]), iw = (unsigned)(a_iw0[t] + e_kw[e]);
                         unsigned x = 0;
                         if (ih < (unsigned)p.H && iw < (unsigned)p.W) {
-                            const char* src = base + (long long)e_off[e] * ESIZE;
+                            const char* src = base + e_off[e] * ESIZE;
                             x = ESIZE == 2 ? (unsigned)*reinterpret_cast<const unsigned short*>(src)
                                            : (unsigned)*reinterpret_cast<const unsigned char*>(src);
                         }

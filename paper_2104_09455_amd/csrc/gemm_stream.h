@@ -86,7 +86,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             const int img = mm / (p.OH * p.OW);
             const int rem = mm - img * (p.OH * p.OW);
             const int oh = rem / p.OW, ow = rem - oh * p.OW;
-            a_img[q] = (long long)img * p.H * p.W * p.Cin;
+            a_img[q] = (long long)img * p.imgpitch;
             a_ih0[q] = oh * p.stride - p.pad;
             a_iw0[q] = ow * p.stride - p.pad;
             aptr[q] = zero;
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 // a chunk never straddles a filter tap (Cin is a multiple of the chunk length)
                 const int ih = a_ih0[q] + tap_kh[q & 1], iw = a_iw0[q] + tap_kw[q & 1];
                 const bool ok = ((a_valid >> q) & 1u) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
-                src = ok ? p.A + (a_img[q] + ((long long)ih * p.W + iw) * p.Cin + tap_c[q & 1]) * ESIZE
+                src = ok ? p.A + (a_img[q] + (long long)ih * p.rowpitch + (long long)iw * p.pix + tap_c[q & 1]) * ESIZE
                          : g_zero_chunk + ckc[q & 1] * 16;
             }
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,

@@ -22,7 +22,7 @@ CONVS = [
 ]
 
 
-def _run_conv(c, dtype, mode):
+def _run_conv(c, dtype, mode, lowered=False):
     import torch
     from gpu_util import to_dev, c_to_host, read_report, DEV
     dt = DT[dtype]
@@ -33,9 +33,12 @@ def _run_conv(c, dtype, mode):
     dC = torch.zeros((M, N), dtype=c_t, device=DEV)
     flag = torch.zeros(1, dtype=torch.int32, device=DEV)
     rep = torch.zeros(ctypes.sizeof(B.Report), dtype=torch.uint8, device=DEV)
-    wsb = B.abft_workspace_bytes(M, N, K, dt, B.GLOBAL)
-    ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device=DEV)
     conv = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad)
+    wsb = B.abft_workspace_bytes(M, N, K, dt, B.GLOBAL)
+    if lowered:
+        # room for the padded input copy and the re-ordered weights: the call then runs lowered
+        wsb = max(B.abft_conv_workspace_bytes(conv, N, dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
+    ws = torch.zeros(max(wsb, 256), dtype=torch.uint8, device=DEV)
     B.abft_conv(conv, N, dx, dB, K, B.B_NK, dC, N, dt, mode, workspace=ws, workspace_bytes=wsb,
                 fault_flag=flag, report=rep)
     torch.cuda.synchronize()
@@ -66,6 +69,38 @@ def test_conv_parity(ci, mode, dtype):
         else:
             assert abs(rep.rhs - near.rhs) <= 0.1 * near.tau + 1e-9
             assert rep.worst_ratio < 0.5
+
+
+LOWERED = [
+    wl.Conv(1, 30, 30, 3, 64, 7, 7, 2, 3),      # ResNet's first layer in small: 21-element runs padded to 24
+    wl.Conv(2, 17, 23, 3, 40, 7, 7, 2, 3),      # odd sizes, ragged output tile
+    wl.Conv(2, 12, 12, 4, 32, 3, 3, 1, 1),      # Cin = 4, stride 1 (8-byte aligned chunk addresses)
+    wl.Conv(1, 16, 16, 6, 16, 5, 5, 2, 2),      # Cin = 6
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("mode", [B.NONE, B.GLOBAL, B.THREAD])
+@pytest.mark.parametrize("ci", range(len(LOWERED)))
+def test_conv_few_channels_lowered_to_row_segments(ci, mode, dtype):
+    """Convolutions whose channel count does not fill 16-byte chunks, run with the larger workspace:
+    padded input copy + re-ordered weights + chunk-wise product must give the same C as the
+    element-wise gather and as the oracle, and the checks must stay quiet."""
+    from gpu_util import c_close
+    c = LOWERED[ci]
+    print(f"case lowered conv={c} mode={mode} dtype={dtype}", flush=True)
+    conv = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad)
+    M, K = c.batch * c.OH * c.OW, c.KH * c.KW * c.Cin
+    assert B.abft_conv_workspace_bytes(conv, c.Cout, DT[dtype], mode) > B.abft_workspace_bytes(M, c.Cout, K, DT[dtype], mode)
+    x, Wm, C, flag, rep = _run_conv(c, dtype, mode, lowered=True)
+    A = oracle.im2col(x, dtype, c.KH, c.KW, c.stride, c.pad)
+    C_ref = oracle.gemm(A, Wm, dtype)
+    assert c_close(C, C_ref, dtype)
+    assert flag == 0
+    if mode != B.NONE:
+        assert rep.tiles > 0 and rep.worst_ratio < 0.5
+    _, _, C_plain, flag_plain, _ = _run_conv(c, dtype, mode, lowered=False)
+    assert flag_plain == 0 and c_close(C_plain, C_ref, dtype)
 
 
 def test_conv_activation_checksum_matches_im2col_column_sums():

@@ -699,6 +699,12 @@ int conv_problem(const abft_conv_t* conv, int N, Problem& pr) {
     pr.pix = conv->Cin;
     pr.rowpitch = (long long)conv->W * conv->Cin;
     pr.imgpitch = pr.rowpitch * conv->H;
+    // a 1 x 1 filter at stride 1 without padding is the plain product on the NHWC tensor read as
+    // an M x Cin matrix
+    if (conv->KH == 1 && conv->KW == 1 && conv->stride == 1 && conv->pad == 0) {
+        pr.conv = false;
+        pr.lda = conv->Cin;
+    }
     return ABFT_OK;
 }
 

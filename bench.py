@@ -189,6 +189,78 @@ def summarize(rows):
 
 
 # --------------------------------------------------------------------------- #
+# caveats of the latency-bound layers, measured rather than argued
+# --------------------------------------------------------------------------- #
+def cold_cache_leg(layer: wl.Layer, dtype: str, gen, copies=320):
+    """The layer with its operands rotating through `copies` distinct copies (more than the 256 MB
+    Infinity Cache), so that every call streams its weights and activations from HBM: device
+    microseconds per call, unprotected and thread-level, and the HBM rate they amount to."""
+    M, N, K = layer.M, layer.N, layer.K
+    dev = "cuda:0"
+    a = torch.rand((copies, M, K), generator=gen, device=dev).to(TORCH_IN[dtype])
+    b = (torch.randn((copies, N, K), generator=gen, device=dev) * 0.02).to(TORCH_IN[dtype])
+    c = torch.zeros((M, N), dtype=TORCH_OUT[dtype], device=dev)
+    flag = torch.zeros(1, dtype=torch.int32, device=dev)
+    es = ESIZE[dtype]
+    out = {"copies": copies, "MB_per_copy": round((M * K + N * K) * es / 1e6, 2)}
+    for mode in (B.NONE, B.THREAD):
+        cap = torch.cuda.Stream()
+        cap.wait_stream(torch.cuda.current_stream())
+
+        def calls():
+            for i in range(copies):
+                B.abft_gemm(M, N, K, a.data_ptr() + i * M * K * es, K, b.data_ptr() + i * N * K * es, K, B.B_NK,
+                            c, N, DT[dtype], mode, fault_flag=flag, stream=cap.cuda_stream)
+        with torch.cuda.stream(cap):
+            calls()
+        cap.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=cap):
+            calls()
+        g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(3):
+            g.replay()
+        torch.cuda.synchronize()
+        us = 1e6 * (time.perf_counter() - t0) / (3 * copies)
+        out["us_" + B.MODE_NAMES[mode]] = round(us, 2)
+        out["hbm_GBps_" + B.MODE_NAMES[mode]] = round(((M * K + N * K) * es + M * N * CSIZE[dtype]) / us / 1e3, 1)
+        del g
+    out["false_alarms"] = int(flag.item())
+    return out
+
+
+def measured_ceilings(hip, gen):
+    """Own ceilings: an element-wise copy kernel's HBM rate and the best unprotected product."""
+    n = 1 << 28  # 1 GiB of fp32
+    src = torch.ones(n, dtype=torch.float32, device="cuda:0")
+    dst = torch.empty_like(src)
+    for _ in range(2):
+        torch.mul(src, 1.0, out=dst)
+    e0, e1 = hip.event(), hip.event()
+    st = torch.cuda.current_stream().cuda_stream or None
+    hip.record(e0, st)
+    for _ in range(5):
+        torch.mul(src, 1.0, out=dst)
+    hip.record(e1, st)
+    ms = hip.elapsed_ms(e0, e1) / 5
+    hip.destroy(e0)
+    hip.destroy(e1)
+    del src, dst
+    torch.cuda.empty_cache()
+    copy_gbps = 2 * n * 4 / (ms * 1e-3) / 1e9
+    lr = LayerRun(wl.Layer("sq8192", 8192, 8192, 8192), "f16", gen, "normal", "normal")
+    us = time_mode(hip, lr, B.NONE, 5, 2)
+    tf = lr.flops / us / 1e6
+    del lr
+    torch.cuda.empty_cache()
+    return {"copy_GBps": round(copy_gbps, 1), "best_unprotected_fp16_TFLOPs": round(tf, 1),
+            "measured_cmr_fp16": round(tf * 1e12 / (copy_gbps * 1e9), 1),
+            "spec_cmr_fp16": round(PEAK["f16"] / HBM, 1)}
+
+
+# --------------------------------------------------------------------------- #
 # CPU baseline: the oracle, as it stands, on a bounded sample of the workload
 # --------------------------------------------------------------------------- #
 def cpu_baseline(runs, budget_s=15.0):
@@ -474,6 +546,8 @@ def main():
                 r = layer_table(hip, [lr], 10, 2, stream)[0]
                 sweep.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
             extra["sweep_N4096_K4096"] = sweep
+            extra["measured_ceilings"] = measured_ceilings(hip, gen)
+            extra["dlrm_top1_cold_cache"] = cold_cache_leg(wl.Layer("top1", 256, 1024, 1024), "f16", gen)
         except Exception as e:  # extras never invalidate the main measurement
             extra["error"] = repr(e)
         out["extra"] = extra

@@ -67,20 +67,24 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     long long a_img[CONV ? NQA : 1];
     int a_ih0[CONV ? NQA : 1], a_iw0[CONV ? NQA : 1];
     int tap_c[2] = {0, 0}, tap_kh[2] = {0, 0}, tap_kw[2] = {0, 0};  // per chunk column (q parity)
+    // (row pointers: one 64-bit product each for A and B, then uniform steps of 8 rows)
+    const char* const b_row0 = p.B + ((long long)(bn0 + crow) * p.ldb + (long long)wave * BK) * ESIZE;
+    const long long b_step = 8 * p.ldb * ESIZE;
 #pragma unroll
     for (int q = 0; q < NQB; ++q) {
         const int n = bn0 + q * 8 + crow;
-        const char* zero = g_zero_chunk + ckc[q & 1] * 16;
         if (n < N) b_valid |= 1u << q;
-        bptr[q] = n < N ? p.B + ((long long)n * p.ldb + (long long)wave * BK) * ESIZE + ckc[q & 1] * 16 : zero;
+        bptr[q] = n < N ? b_row0 + q * b_step + ckc[q & 1] * 16 : g_zero_chunk + ckc[q & 1] * 16;
     }
+    const char* const a_row0 = p.A + ((long long)(bm0 + crow) * p.lda + (long long)wave * BK) * ESIZE;
+    const long long a_step = 8 * p.lda * ESIZE;
 #pragma unroll
     for (int q = 0; q < NQA; ++q) {
         const int m = bm0 + q * 8 + crow;
         const char* zero = g_zero_chunk + ckc[q & 1] * 16;
         if (m < M) a_valid |= 1u << q;
         if constexpr (!CONV) {
-            aptr[q] = m < M ? p.A + ((long long)m * p.lda + (long long)wave * BK) * ESIZE + ckc[q & 1] * 16 : zero;
+            aptr[q] = m < M ? a_row0 + q * a_step + ckc[q & 1] * 16 : zero;
         } else {
             const int mm = m < M ? m : 0;
             const int img = mm / (p.OH * p.OW);
@@ -160,6 +164,16 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         }
     };
 
+    // ---- this wavefront's pipeline: own tile i lives in stage i % NST.  The first copies go out
+    // before anything else is set up, so that the rest of the prologue runs under their latency.
+#pragma unroll
+    for (int s = 0; s < NST; ++s) {
+        if (s < n_own) {
+            if (s > 0) advance();
+            issue_loads(s);
+        }
+    }
+
     Acc acc[TM][TN];
 #pragma unroll
     for (int i = 0; i < TM; ++i)
@@ -229,14 +243,6 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         }
     };
 
-    // ---- this wavefront's pipeline: own tile i lives in stage i % NST
-#pragma unroll
-    for (int s = 0; s < NST; ++s) {
-        if (s < n_own) {
-            if (s > 0) advance();
-            issue_loads(s);
-        }
-    }
     constexpr int VM_STEADY = waitcnt_vm((NST - 1) * NL);  // the oldest tile in flight has landed
     constexpr int VM_ALL = waitcnt_vm(0);
     if (n_own > 0) {

@@ -55,6 +55,42 @@ def test_clean_parity(shape, mode, dtype):
         assert res.report.worst_ratio < 0.5
 
 
+# shapes chosen so that every tile configuration of the dispatcher runs under test:
+# (shape, wavefront tile of the thread-level scheme, region of the global scheme)
+CONFIG_SHAPES = [
+    ((520, 1040, 128), (64, 64), (64, 64)),        # 64 x 64 streaming tile, ragged edges
+    ((1536, 1536, 128), (32, 128), (128, 128)),    # 128 x 128 tile (wide wavefront tiles for thread-level)
+    ((16500, 64, 256), (32, 128), (128, 128)),     # narrow output: 128 x 128 tile of full-width wavefronts
+    ((300, 520, 1024), (32, 64), (32, 32)),        # a handful of tiles: 32-row streaming tiles
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+@pytest.mark.parametrize("mode", MODES)
+@pytest.mark.parametrize("case", CONFIG_SHAPES)
+def test_every_tile_configuration(case, mode, dtype):
+    from gpu_util import run_gemm, c_close
+    (M, N, K), wave_tile, region = case
+    dt = {"f16": B.F16, "i8": B.I8}[dtype]
+    tm, tn, ks = B.abft_tile_shape(M, N, K, dt)
+    assert (tm, tn) == wave_tile and B.abft_region_shape(M, N, K, dt) == region
+    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=300 + M)
+    print(f"case config shape={(M, N, K)} mode={mode} dtype={dtype}", flush=True)
+    res = run_gemm(A, Bm, dtype, mode)
+    C_ref = oracle.gemm(A, Bm, dtype)
+    assert c_close(res.C, C_ref, dtype)
+    assert res.flag == 0
+    if mode == B.GLOBAL:
+        bad, checks = oracle.global_check_blocks(A, Bm, C_ref, dtype, *region)
+        assert not bad and res.report.tiles == len(checks) and res.report.worst_ratio < 0.5
+    if mode == B.THREAD:
+        assert res.report.worst_ratio < 0.5
+    if mode != B.NONE:
+        # a flipped exponent bit (sign bit for int8) in the last, ragged tile is seen
+        hit = run_gemm(A, Bm, dtype, mode, inject=B.Fault(M - 1, N - 1, 30 if dtype == "f16" else 31, -1))
+        assert hit.flag == 1
+
+
 @pytest.mark.parametrize("dtype", ["f16", "i8"])
 @pytest.mark.parametrize("mode", MODES)
 def test_layouts_strides_and_misalignment(mode, dtype):

@@ -487,7 +487,13 @@ def main():
         prof = {"value": round(total_flops / (wall2 / steps) / 1e12, 3), "unit": "TFLOP/s",
                 "ms_per_step": round(1000.0 * wall2 / steps, 5),
                 "overhead_pct_whole_pass": round(100 * (wall2 / wall_none - 1), 2),
-                "modes_picked": {m: sum(1 for x in picks2 if B.MODE_NAMES[x] == m) for m in ("global", "thread")}}
+                "modes_picked": {m: sum(1 for x in picks2 if B.MODE_NAMES[x] == m) for m in ("global", "thread")},
+                # where the analytic rule and the profile disagree (device times from the layer table)
+                "disagrees_with_analytic": [
+                    {"layer": r["layer"], "ai": r["ai"], "analytic": r["pick"], "profiled": B.MODE_NAMES[x],
+                     "us_global": r["us_global"], "us_thread": r["us_thread"]}
+                    for r, x in zip(rows, picks2) if B.MODE_NAMES[x] != r["pick"]][:12],
+                "n_disagree": sum(1 for r, x in zip(rows, picks2) if B.MODE_NAMES[x] != r["pick"])}
     except Exception as e:  # reported, never fatal
         prof = {"error": repr(e)}
 

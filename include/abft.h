@@ -47,12 +47,15 @@ extern "C" {
 #define ABFT_E_PLAN (-8)       /* bad plan handle or layer index */
 
 /* ---- enums --------------------------------------------------------------- */
-/* Protection scheme.  GLOBAL: kernel-level ABFT (Sec. 2.4-2.5): activation and weight
- * checksums are formed outside the product kernel, the output summation is fused into
- * its epilogue and a separate kernel compares them -- per workgroup tile of C, so for a
- * product that fits one tile this is the single whole-matrix comparison.  THREAD: the paper's one-sided thread-level scheme (Sec. 5.2.2),
- * carried out per wavefront register tile.  AUTO: whatever abft_select returns
- * (intensity-guided ABFT, Sec. 5.3). */
+/* Protection scheme.  GLOBAL: kernel-level ABFT (Sec. 2.4-2.5): the weight checksums are
+ * formed offline, the output summation is fused into the product kernel's epilogue and
+ * compared there with the dot product of activation and weight checksums -- per workgroup
+ * tile of C, so for a product that fits one tile this is the single whole-matrix
+ * comparison.  For 16-byte aligned operands the product kernel forms that dot product
+ * itself from the A tiles it loads (one kernel in all); otherwise, and for very large
+ * products, an activation-checksum kernel runs first.  THREAD: the paper's one-sided
+ * thread-level scheme (Sec. 5.2.2), carried out per wavefront register tile.  AUTO:
+ * whatever abft_select returns (intensity-guided ABFT, Sec. 5.3). */
 typedef enum { ABFT_NONE = 0, ABFT_GLOBAL = 1, ABFT_THREAD = 2, ABFT_AUTO = 3 } abft_mode_t;
 
 /* Operand type.  F16 / BF16: A, B and C are fp16 / bf16, accumulation in fp32.

@@ -6,14 +6,14 @@ namespace abft {
 
 // Index into the configuration table.
 //  F* run the direct-to-LDS kernel (16-byte aligned operands, K a multiple of 128 bytes):
-//    F256   256 x 256, wavefronts 2 x 2 of 128 x 128, 2 LDS stages   compute-bound products
+//    F256W  256 x 256, wavefronts 2 x 4 of 128 x  64 (two per SIMD), 2 LDS stages   compute-bound products
 //    F128   128 x 128, wavefronts 2 x 2 of  64 x  64, 2 stages       mid-size, unprotected / global
-//    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       mid-size, thread-level (wide tiles:
-//                                                                    one checksum MFMA per four)
-//    F64T    64 x 128, wavefronts 2 x 1 of  32 x 128, 3 stages       small products, any scheme
-//    F64S    same tile, 6 stages, may be split along k               grids that leave compute units idle
+//    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       thread-level (wide tiles: two checksum
+//                                                                    MFMAs per four), narrow outputs, K of one k tile
+//    F64T    64 x 128, wavefronts 2 x 1 of  32 x 128, 3 stages       between the streaming tiles and F128
 //    F64K    same tile, 6 stages, 4 wavefronts per register tile     (each takes one k step in four)
-//    F256W  256 x 256, wavefronts 2 x 4 of 128 x  64, 2 stages       two wavefronts per SIMD
+//    F256   256 x 256, wavefronts 2 x 2 of 128 x 128, 2 stages       kept for comparison, not selected
+//    F64S    64 x 128, 6 stages, may be split along k across workgroups   kept, selected only by environment switch
 //  S* run the streaming kernel (same operand requirements; four wavefronts split the k tiles of one
 //  register tile between them, each with its own LDS stages, no barrier in the k loop):
 //    S32     32 x  32, 4 stages per wavefront                         a few tiles only: latency-bound layers

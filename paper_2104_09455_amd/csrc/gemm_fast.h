@@ -3,8 +3,10 @@
 //
 // Workgroup tile (32 TM WAVES_M) x (32 TN WAVES_N) x (128 bytes of k); each wavefront owns a
 // (32 TM) x (32 TN) register tile of MFMA 32x32 blocks.  The flagship instance is 256 x 256
-// with four wavefronts of 128 x 128 (256 accumulators per lane); smaller instances with
-// wide-in-N wavefront tiles serve mid-size and bandwidth-bound layers.
+// with eight wavefronts of 128 x 64, two per SIMD (128 accumulators per lane); smaller
+// instances with wide-in-N wavefront tiles serve mid-size layers.  In the global scheme the
+// kernel also forms the checksum dot product of its tile from the A chunks in LDS and the
+// weight checksums of its column block, which travel with the operand tiles.
 //
 // Data flow: global_load_lds_dwordx4 moves 16-byte chunks from HBM straight into LDS
 // (no staging registers), NSTAGE LDS stages, rows of 128 bytes stored with an XOR

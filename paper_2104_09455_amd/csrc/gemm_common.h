@@ -433,6 +433,54 @@ struct TileChecksumSplitF16 {
     }
 };
 
+// Split form for bf16: the column sums (fp32, exact: a few bf16 values) go out as three bf16
+// operands hi + mid + lo = s exactly (3 x 8 significant bits), each multiplied with the A
+// fragments into its own accumulators.  No cross-lane step.
+template <int TN>
+struct TileChecksumSplitBF16 {
+    static __device__ __forceinline__ float lo_f(int packed) { return bitcast<float>(packed << 16); }
+    static __device__ __forceinline__ float hi_f(int packed) { return bitcast<float>((int)(packed & 0xffff0000)); }
+    static __device__ __forceinline__ int pack(float a, float b) {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        bf16x2 h;
+        h[0] = (__bf16)a;  // round to nearest even
+        h[1] = (__bf16)b;
+        return bitcast<int>(h);
+    }
+    static __device__ __forceinline__ void make(const i32x4 (&b)[TN], i32x4& x0, i32x4& x1, i32x4& x2) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                s0 += lo_f(b[j][d]);
+                s1 += hi_f(b[j][d]);
+            }
+            const int h = pack(s0, s1);
+            const float r0 = s0 - lo_f(h), r1 = s1 - hi_f(h);  // exact remainders
+            const int m = pack(r0, r1);
+            const float q0 = r0 - lo_f(m), q1 = r1 - hi_f(m);
+            x0[d] = h;
+            x1[d] = m;
+            x2[d] = pack(q0, q1);
+        }
+    }
+};
+
+// The split form for either 16-bit type: NP operands x[0..NP) whose accumulators, weighted with
+// scale(piece), add up to the checksum product.
+template <int DT, int TN>
+struct TileChecksumSplit {
+    static constexpr int NP = DT == DT_F16 ? 2 : 3;
+    static __device__ __forceinline__ void make(const i32x4 (&b)[TN], i32x4 (&x)[NP]) {
+        if constexpr (DT == DT_F16) TileChecksumSplitF16<TN>::make(b, x[0], x[1]);
+        else TileChecksumSplitBF16<TN>::make(b, x[0], x[1], x[2]);
+    }
+    static constexpr double scale(int piece) {
+        return (DT == DT_F16 && piece == 1) ? TileChecksumSplitF16<TN>::LO_SCALE : 1.0;
+    }
+};
+
 // acc + (half SEL of `packed`, an fp16 or bf16 value) * b, in fp32
 template <int DT, int SEL>
 __device__ __forceinline__ float mul_add_half(int packed, float b, float acc) {
@@ -493,8 +541,9 @@ struct ChecksumDot {
 // accumulators per A fragment that takes.
 template <class CFG>
 struct ChecksumForm {
-    static constexpr bool SPLIT = CFG::DT == DT_F16 && CFG::MI == 32 && CFG::TM <= 2 && CFG::TN >= 2;
-    static constexpr int NCHK = SPLIT ? 2 * CFG::TM : CFG::TM;
+    static constexpr bool SPLIT = (CFG::DT == DT_F16 || CFG::DT == DT_BF16) && CFG::MI == 32 && CFG::TM <= 2 && CFG::TN >= 2;
+    static constexpr int NP = SPLIT ? (CFG::DT == DT_F16 ? 2 : 3) : 1;  // checksum operands per k step
+    static constexpr int NCHK = NP * CFG::TM;
 };
 
 // ---------------------------------------------------------------------------
@@ -763,15 +812,19 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             } else {
                 double rsum = 0.0;
                 if constexpr (ChecksumForm<CFG>::SPLIT) {
-                    double rlo = 0.0;
+                    typedef TileChecksumSplit<CFG::DT, TN> SPL;
 #pragma unroll
-                    for (int i = 0; i < TM; ++i)
+                    for (int pc = 0; pc < SPL::NP; ++pc) {
+                        double part = 0.0;
 #pragma unroll
-                        for (int r = 0; r < MMA::NACC; r += 4) {
-                            rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
-                            rlo += (double)((chk[TM + i][r] + chk[TM + i][r + 1]) + (chk[TM + i][r + 2] + chk[TM + i][r + 3]));
-                        }
-                    rsum = wave_sum(rsum + rlo * TileChecksumSplitF16<TN>::LO_SCALE);
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int r = 0; r < MMA::NACC; r += 4)
+                                part += (double)((chk[pc * TM + i][r] + chk[pc * TM + i][r + 1]) +
+                                                 (chk[pc * TM + i][r + 2] + chk[pc * TM + i][r + 3]));
+                        rsum += part * SPL::scale(pc);
+                    }
+                    rsum = wave_sum(rsum);
                 } else {
 #pragma unroll
                     for (int i = 0; i < TM; ++i)

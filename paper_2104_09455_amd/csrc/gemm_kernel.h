@@ -240,13 +240,13 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(a[i], b[j], acc[i][j]);
             if constexpr (MODE == MODE_THREAD && SPLIT) {
-                i32x4 xh, xl;
-                TileChecksumSplitF16<TN>::make(b, xh, xl);
+                typedef TileChecksumSplit<CFG::DT, TN> SPL;
+                i32x4 x[SPL::NP];
+                SPL::make(b, x);
 #pragma unroll
-                for (int i = 0; i < TM; ++i) {
-                    chk[i] = MMA::run(a[i], xh, chk[i]);
-                    chk[TM + i] = MMA::run(a[i], xl, chk[TM + i]);
-                }
+                for (int pc = 0; pc < SPL::NP; ++pc)
+#pragma unroll
+                    for (int i = 0; i < TM; ++i) chk[pc * TM + i] = MMA::run(a[i], x[pc], chk[pc * TM + i]);
             } else if constexpr (MODE == MODE_THREAD) {
                 i32x4 x = TileChecksum<CFG::DT, MI, TN>::make(b, lane);
 #pragma unroll

@@ -229,13 +229,13 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
         if constexpr (MODE == MODE_THREAD && SPLIT) {
-            i32x4 xh, xl;
-            TileChecksumSplitF16<TN>::make(fb[buf], xh, xl);
+            typedef TileChecksumSplit<DT, TN> SPL;
+            i32x4 x[SPL::NP];
+            SPL::make(fb[buf], x);
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                chk[i] = MMA::run(fa[buf][i], xh, chk[i]);
-                chk[TM + i] = MMA::run(fa[buf][i], xl, chk[TM + i]);
-            }
+            for (int pc = 0; pc < SPL::NP; ++pc)
+#pragma unroll
+                for (int i = 0; i < TM; ++i) chk[pc * TM + i] = MMA::run(fa[buf][i], x[pc], chk[pc * TM + i]);
         } else if constexpr (MODE == MODE_THREAD) {
             i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
 #pragma unroll

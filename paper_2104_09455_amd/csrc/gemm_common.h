@@ -467,14 +467,40 @@ struct TileChecksumSplitBF16 {
     }
 };
 
-// The split form for either 16-bit type: NP operands x[0..NP) whose accumulators, weighted with
-// scale(piece), add up to the checksum product.
+// Split form for int8: the column sums (at most 10 bits) are formed in packed 16-bit lanes
+// (even and odd bytes of each register apart) and go out as two operands of balanced
+// base-256 digits, s = lo + 256 hi exactly.  No cross-lane step.
+template <int TN>
+struct TileChecksumSplitI8 {
+    typedef short s16x2 __attribute__((ext_vector_type(2)));
+    static __device__ __forceinline__ void make(const i32x4 (&b)[TN], i32x4& lo, i32x4& hi) {
+#pragma unroll
+        for (int d = 0; d < 4; ++d) {
+            s16x2 se = {0, 0}, so = {0, 0};
+#pragma unroll
+            for (int j = 0; j < TN; ++j) {
+                const s16x2 x = bitcast<s16x2>(b[j][d]);
+                se += (s16x2)(x << 8) >> 8;  // bytes 0 and 2, sign extended
+                so += x >> 8;                // bytes 1 and 3
+            }
+            const s16x2 le = (s16x2)(se << 8) >> 8, lod = (s16x2)(so << 8) >> 8;  // low digits
+            const s16x2 he = (se - le) >> 8, hod = (so - lod) >> 8;              // high digits
+            lo[d] = (bitcast<int>(le) & 0x00ff00ff) | ((bitcast<int>(lod) & 0x00ff00ff) << 8);
+            hi[d] = (bitcast<int>(he) & 0x00ff00ff) | ((bitcast<int>(hod) & 0x00ff00ff) << 8);
+        }
+    }
+};
+
+// The split form for any operand type: NP operands x[0..NP) whose accumulators, weighted with
+// scale(piece) (int8: 1 and 256, applied in integers by the epilogue), add up to the checksum
+// product.
 template <int DT, int TN>
 struct TileChecksumSplit {
-    static constexpr int NP = DT == DT_F16 ? 2 : 3;
+    static constexpr int NP = DT == DT_BF16 ? 3 : 2;
     static __device__ __forceinline__ void make(const i32x4 (&b)[TN], i32x4 (&x)[NP]) {
         if constexpr (DT == DT_F16) TileChecksumSplitF16<TN>::make(b, x[0], x[1]);
-        else TileChecksumSplitBF16<TN>::make(b, x[0], x[1], x[2]);
+        else if constexpr (DT == DT_BF16) TileChecksumSplitBF16<TN>::make(b, x[0], x[1], x[2]);
+        else TileChecksumSplitI8<TN>::make(b, x[0], x[1]);
     }
     static constexpr double scale(int piece) {
         return (DT == DT_F16 && piece == 1) ? TileChecksumSplitF16<TN>::LO_SCALE : 1.0;
@@ -541,8 +567,8 @@ struct ChecksumDot {
 // accumulators per A fragment that takes.
 template <class CFG>
 struct ChecksumForm {
-    static constexpr bool SPLIT = (CFG::DT == DT_F16 || CFG::DT == DT_BF16) && CFG::MI == 32 && CFG::TM <= 2 && CFG::TN >= 2;
-    static constexpr int NP = SPLIT ? (CFG::DT == DT_F16 ? 2 : 3) : 1;  // checksum operands per k step
+    static constexpr bool SPLIT = CFG::MI == 32 && CFG::TM <= 2 && CFG::TN >= 2;
+    static constexpr int NP = SPLIT ? (CFG::DT == DT_BF16 ? 3 : 2) : 1;  // checksum operands per k step
     static constexpr int NCHK = NP * CFG::TM;
 };
 
@@ -727,17 +753,37 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                     }
                 }
             } else {
-                int r_lo = 0, r_hi = 0;
+                // (exact 64-bit sums from 16-bit pieces, as above)
+                long long rsum = 0;
+                if constexpr (ChecksumForm<CFG>::SPLIT) {
+                    // accumulators of the low-digit operand, then 256 x those of the high-digit one
 #pragma unroll
-                for (int i = 0; i < TM; ++i)
+                    for (int pc = 0; pc < 2; ++pc) {
+                        int r_lo = 0, r_hi = 0;
 #pragma unroll
-                    for (int r = 0; r < MMA::NACC; ++r) {
-                        r_lo += chk[i][r] & 0xffff;
-                        r_hi += chk[i][r] >> 16;
+                        for (int i = 0; i < TM; ++i)
+#pragma unroll
+                            for (int r = 0; r < MMA::NACC; ++r) {
+                                r_lo += chk[pc * TM + i][r] & 0xffff;
+                                r_hi += chk[pc * TM + i][r] >> 16;
+                            }
+                        const long long part = ((long long)r_hi << 16) + (long long)r_lo;
+                        rsum += pc == 0 ? part : 256 * part;
                     }
-                long long rsum = ((long long)r_hi << 16) + (long long)r_lo;
-                const long long w = (lane % MI) >= MI / 2 ? 256 : 1;
-                rsum = wave_sum(rsum * w);
+                    rsum = wave_sum(rsum);
+                } else {
+                    int r_lo = 0, r_hi = 0;
+#pragma unroll
+                    for (int i = 0; i < TM; ++i)
+#pragma unroll
+                        for (int r = 0; r < MMA::NACC; ++r) {
+                            r_lo += chk[i][r] & 0xffff;
+                            r_hi += chk[i][r] >> 16;
+                        }
+                    rsum = ((long long)r_hi << 16) + (long long)r_lo;
+                    const long long w = (lane % MI) >= MI / 2 ? 256 : 1;
+                    rsum = wave_sum(rsum * w);
+                }
                 if (lane == 0) {
                     bool bad = s != rsum;
                     if (bad) atomicOr(p.flag, 1u);

@@ -527,7 +527,7 @@ def main():
                 for n, dts in ((4096, ("f16", "bf16")), (8192, ("f16", "bf16", "i8"))):
                     for d in dts:
                         lr = LayerRun(wl.Layer(f"sq{n}", n, n, n), d, gen, "normal", "normal")
-                        r = layer_table(hip, [lr], 5, 2, stream)[0]
+                        r = layer_table(hip, [lr], 20 if n <= 4096 else 10, 3, stream)[0]
                         extra[f"square{n}_{d}"] = {k: r[k] for k in ("pick", "us_none", "ovh_global_pct", "ovh_thread_pct",
                                                                       "tflops_pick", "roofline_frac_pick")}
                         del lr
@@ -552,6 +552,13 @@ def main():
                 r = layer_table(hip, [lr], 10, 2, stream)[0]
                 sweep.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
             extra["sweep_N4096_K4096"] = sweep
+            # the paper's Fig. 11 sizes (its T4 numbers: thread-level 2-14 %, global 27 % at 32^3 down to 1 % at 2048^3)
+            fig11 = []
+            for n in wl.square_sizes_paper():
+                lr = LayerRun(wl.Layer(f"sq{n}", n, n, n), "f16", gen, "normal", "normal")
+                r = layer_table(hip, [lr], 20, 2, stream)[0]
+                fig11.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
+            extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
             extra["dlrm_top1_cold_cache"] = cold_cache_leg(wl.Layer("top1", 256, 1024, 1024), "f16", gen)
         except Exception as e:  # extras never invalidate the main measurement

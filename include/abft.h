@@ -160,7 +160,9 @@ size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int 
  * copies: first K x nb values k-major, beta[k*nb + b], as doubles (F16 / BF16) or int64 (I8);
  * then, at the next multiple of 256 bytes, the copy the product kernel reads inside its loop:
  * per block b, K floats (F16 / BF16), or K low digits followed by K high digits, one signed
- * byte each, beta_b[k] = lo + 256 hi (I8; exact for block_n <= 256).
+ * byte each, beta_b[k] = lo + 256 hi (I8; exact for block_n <= 256); F16 has a third copy
+ * behind that (again at the next multiple of 256 bytes): per block, K halves fl16(beta) and K
+ * halves fl16((beta - fl16(beta)) 2^11).
  * block_n <= 0 or >= N gives the plain K-vector B.1 . */
 int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
                          void *beta, void *stream);

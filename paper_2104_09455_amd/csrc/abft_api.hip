@@ -81,15 +81,17 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // (a single k tile: the 128 x 128 tile, of which several fit a compute unit at once)
         const long long nkt_all = ((long long)K * esize(dt)) / 128;
         if (N > 128 && nkt_all > 1 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
-        if (tiles(CFG_F128) >= 128) return (mode == ABFT_THREAD || N <= 128 || nkt_all <= 1) ? CFG_F128T : CFG_F128;
-        // Fewer tiles than that: the time is the latency of a workgroup's k loop and the rate at
-        // which one compute unit can stream its operands, so the streaming configurations take
-        // over (no barriers in the k loop): 64 x 64 tiles while they fill the chip at most twice,
-        // 32-row tiles for a handful of tiles.  The thread-level scheme takes the 32 x 64 tile
-        // there (its checksum then needs no cross-lane step).
+        const bool fills128 = tiles(CFG_F128) >= 128;
+        if (fills128 && N <= 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
+        // Fewer tiles than fill the chip twice at 64 x 64: the time is the latency of a workgroup's
+        // k loop and the rate at which one compute unit can stream its operands, so the streaming
+        // configurations take over (no barriers in the k loop): 64 x 64 tiles, or 32-row tiles
+        // for a handful of tiles.  The thread-level scheme takes the 32 x 64 tile there (its
+        // checksum then needs no cross-lane step).
         const long long t64 = tiles(CFG_F64T);
         if (t64 <= 64) return (mode == ABFT_THREAD && N > 32) ? CFG_S64 : CFG_S32;
         if (tiles(CFG_S128) <= 512) return CFG_S128;
+        if (fills128) return (mode == ABFT_THREAD || nkt_all <= 1) ? CFG_F128T : CFG_F128;
         if (t64 > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
         return CFG_F64K;
     }
@@ -299,7 +301,8 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 // Block = 32 values of k x 8 lanes over n; blockIdx.y = column block.  Not tuned: offline.
 template <int DT>
 __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int K, int N, long long sn,
-                                                              long long sk, int block_n, void* beta, char* beta_k) {
+                                                              long long sk, int block_n, void* beta, char* beta_k,
+                                                              char* beta_p) {
     constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
     typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
     __shared__ Wide red[8][32];
@@ -331,6 +334,13 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
             d[K + k] = (signed char)(hi < -128 ? -128 : (hi > 127 ? 127 : hi));
         } else {
             reinterpret_cast<float*>(beta_k)[(long long)blockIdx.y * K + k] = (float)a;
+            if constexpr (DT == DT_F16) {
+                const _Float16 hi = (_Float16)(float)a;
+                const _Float16 lo = (_Float16)(((float)a - (float)hi) * 2048.f);
+                _Float16* pl = reinterpret_cast<_Float16*>(beta_p) + (long long)blockIdx.y * 2 * K;
+                pl[k] = hi;
+                pl[K + k] = lo;
+            }
         }
     }
 }
@@ -446,7 +456,10 @@ int pre_rows_per_block(int bm, int M, int K) {
 // the activation-checksum kernel's dot products, then, 256-byte aligned, the per-block copy
 // along k for the in-kernel dot product (4 bytes per k and block reserved).
 size_t beta_k_offset(int K, int nb) { return align_up((size_t)K * nb * 8, 256); }
-size_t beta_total_bytes(int K, int nb) { return beta_k_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
+// third copy (fp16 only): per block, K halves hi = fl16(beta) then K halves lo = fl16((beta - hi) 2^11),
+// the two columns of the extra operand with which the streaming kernel forms the dot product
+size_t beta_p_offset(int K, int nb) { return beta_k_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
+size_t beta_total_bytes(int K, int nb) { return beta_p_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
 
 WsLayout ws_layout(int M, int N, int K, int cfg) {
     CfgInfo ci = cfg_info_host(cfg);
@@ -503,14 +516,15 @@ hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, in
     if (block_n <= 0 || block_n > N) block_n = N;
     void* beta = beta_buf;
     char* beta_k = reinterpret_cast<char*>(beta_buf) + beta_k_offset(K, (int)cdiv(N, block_n));
+    char* beta_p = reinterpret_cast<char*>(beta_buf) + beta_p_offset(K, (int)cdiv(N, block_n));
     dim3 grid((unsigned)cdiv(K, 32), (unsigned)cdiv(N, block_n)), block(256);
     const char* b = reinterpret_cast<const char*>(B);
     if (dt == ABFT_F16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k, beta_p);
     else if (dt == ABFT_BF16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k, beta_p);
     else
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k, beta_p);
     return hipGetLastError();
 }
 
@@ -657,6 +671,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
             // the direct-to-LDS kernel forms the activation checksum's dot product with the weight
             // checksums itself, from the A tiles it multiplies (steps 1-3 inside the product's loop)
             g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
+            g.beta_p = reinterpret_cast<const char*>(beta_used) + beta_p_offset(pr.K, g.tiles_n);
         } else {
             kmode = MODE_GLOBAL_PRE;
             g.partial_dots = ws + w.off_pd;

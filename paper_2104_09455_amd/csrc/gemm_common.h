@@ -82,6 +82,8 @@ struct GemmArgs {
     const char* beta_k;       // GLOBAL, direct-to-LDS kernel: weight checksums per column block for the in-kernel
                               // checksum dot product: float[K] per block (fp16 / bf16), or K low digits then
                               // K high digits (balanced base 256, one byte each) per block (int8)
+    const char* beta_p;       // GLOBAL, streaming kernel, fp16: the same checksums as two planes of halves per
+                              // block, K values hi = fl16(beta) then K values lo = fl16((beta - hi) 2^11)
     const void* partial_dots; // GLOBAL otherwise: per tile n_parts partial checksum dot products (double / int64)
     int n_parts;
     double tol_l1;           // GLOBAL: coefficient of the tile's sum of magnitudes in tau

@@ -40,6 +40,11 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     constexpr int TM = CFG::TM, TN = CFG::TN, BM = CFG::BM, BN = CFG::BN, BKB = 128;
     constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
     constexpr bool GDOT = MODE == MODE_GLOBAL;  // global scheme: in-kernel checksum dot product
+    // ... on the matrix unit (fp16, int8): the weight checksums, split in two exact pieces, are two
+    // columns of an extra B operand, multiplied with every A fragment; the unit idles in these
+    // latency-bound products, and the vector FMAs of the other form would cost more.  bf16 (three
+    // pieces) keeps the vector form.
+    constexpr bool MDOT = GDOT && DT != DT_BF16;
     constexpr bool IS_INT = DT == DT_I8;
     constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB + (GDOT ? 1 : 0);
     constexpr int ROWB = 128, A_STAGE = BM * ROWB;
@@ -101,10 +106,13 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     const char* beta_ptr = g_zero_chunk;
     if constexpr (GDOT) {
         const long long blk = (long long)tile_n * p.K;
+        // (int8 digits and fp16 halves: two planes per block, 128 bytes of each per k tile, the first
+        // copied by lanes 0-31, the second by lanes 32-63; bf16: 64 floats per k tile)
         if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (long long)wave * BK + (lane & 31) * 4;
+        else if constexpr (MDOT) beta_ptr = p.beta_p + blk * 4 + (lane >> 5) * 2 * (long long)p.K + (long long)wave * BK * 2 + (lane & 31) * 4;
         else beta_ptr = p.beta_k + (blk + (long long)wave * BK + lane) * 4;
     }
-    constexpr int BETA_ADV = KW * (IS_INT ? BK : BK * 4);
+    constexpr int BETA_ADV = KW * (MDOT ? 128 : BK * 4);
     if constexpr (CONV) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -202,7 +210,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     // checksums of their k chunk (two chunk columns per lane: even and odd 1 KB blocks)
     ChecksumDot<DT> dot;
     auto dot_tile = [&](const char* st) {
-        if constexpr (GDOT) {
+        if constexpr (GDOT && !MDOT) {
             i32x4 b0[2], b1[2];
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
@@ -216,8 +224,25 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             dot.flush();
         }
     };
+    // matrix-unit form: lanes of column 0 / 1 of the extra B operand read the first / second plane of
+    // the weight checksums (their k chunk, like any fragment), all other columns are zero
+    const int gcol = lane & 31;
+    const int gb_off = LAY::AB_STAGE + (gcol == 1 ? 128 : 0) + fgrp * 16;
+    i32x4 fg[2];
+    Acc gchk[MDOT ? TM : 1];
+    if constexpr (MDOT) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) gchk[i][r] = 0;
+    }
     i32x4 fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* st, int kk, int buf) {
+        if constexpr (MDOT) {
+            const i32x4 g = *reinterpret_cast<const i32x4*>(st + gb_off + kk * 32);
+            const i32x4 z = {0, 0, 0, 0};
+            fg[buf] = gcol < 2 ? g : z;
+        }
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + pos[kk]);
 #pragma unroll
@@ -228,6 +253,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
+        if constexpr (MDOT) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) gchk[i] = MMA::run(fa[buf][i], fg[buf], gchk[i]);
+        }
         if constexpr (MODE == MODE_THREAD && SPLIT) {
             typedef TileChecksumSplit<DT, TN> SPL;
             i32x4 x[SPL::NP];
@@ -359,7 +388,30 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         // comparison (Sec. 2.4 step 4) for this tile
         if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;
         s_sum = wave_sum(s_sum);
-        const Wide wdot = wave_sum(dot.total);
+        Wide lane_dot = dot.total;
+        if constexpr (MDOT) {
+            // column 0 of the extra result blocks holds A . (first plane), column 1 A . (second plane)
+            if constexpr (IS_INT) {
+                int g_lo = 0, g_hi = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        g_lo += gchk[i][r] & 0xffff;
+                        g_hi += gchk[i][r] >> 16;
+                    }
+                lane_dot = (((long long)g_hi << 16) + (long long)g_lo) * (gcol == 1 ? 256 : 1);
+            } else {
+                double g = 0.0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < 16; r += 4)
+                        g += (double)((gchk[i][r] + gchk[i][r + 1]) + (gchk[i][r + 2] + gchk[i][r + 3]));
+                lane_dot = g * (gcol == 1 ? 1.0 / 2048.0 : 1.0);
+            }
+        }
+        const Wide wdot = wave_sum(lane_dot);
         const double F2 = IS_INT ? 0.0 : wave_sum((double)f2);
         const double L1 = IS_INT ? 0.0 : wave_sum((double)l1);
         __syncthreads();  // everyone is done reading the partial tiles

@@ -146,6 +146,12 @@ def test_checksum_vectors(dtype):
                 assert np.allclose(beta_b.reshape(K, nb).T, blocks, rtol=1e-12, atol=1e-12)
                 f32 = second[:nb * K * 4].view(np.float32).reshape(nb, K)
                 assert np.array_equal(f32, blocks.astype(np.float32))
+                if dtype == "f16":
+                    # third copy: per block K halves hi = fl16(beta), K halves lo = fl16((beta - hi) 2^11)
+                    third = second[-(-(nb * K * 4) // 256) * 256:][:nb * K * 4].view(np.float16).reshape(nb, 2, K)
+                    hi = f32.astype(np.float16)
+                    lo = ((f32 - hi.astype(np.float32)) * np.float32(2048)).astype(np.float16)
+                    assert np.array_equal(third[:, 0], hi) and np.array_equal(third[:, 1], lo)
         if dtype == "i8":
             assert np.array_equal(alpha.cpu().numpy(), a_ref)
         else:

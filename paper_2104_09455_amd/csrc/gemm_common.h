@@ -811,12 +811,18 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                         if constexpr (MODE == MODE_GLOBAL)
                             l1 += (__builtin_fabsf(v0) + __builtin_fabsf(v1)) + (__builtin_fabsf(v2) + __builtin_fabsf(v3));
                     }
-            s = wave_sum(s);
-            double F2 = wave_sum((double)f2);
+            // cross-lane sums: the norms of the tolerance in fp32; the two sides of the comparison in
+            // fp64, as one sum of their per-lane difference unless the report wants them apart
+            const double F2 = (double)wave_sum(f2);
             if constexpr (MODE == MODE_GLOBAL) {
-                double L1 = wave_sum((double)l1);
+                const double L1 = (double)wave_sum(l1);
                 double wdot = 0.0;
-                if (lane_dot) wdot = wave_sum(*reinterpret_cast<const double*>(lane_dot));
+                if (lane_dot && !p.report) {
+                    s = wave_sum(s - *reinterpret_cast<const double*>(lane_dot));
+                } else {
+                    s = wave_sum(s);
+                    if (lane_dot) wdot = wave_sum(*reinterpret_cast<const double*>(lane_dot));
+                }
                 double* red = reinterpret_cast<double*>(smem);
                 __syncthreads();
                 if (lane == 0) {
@@ -872,14 +878,20 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                                                  (chk[pc * TM + i][r + 2] + chk[pc * TM + i][r + 3]));
                         rsum += part * SPL::scale(pc);
                     }
-                    rsum = wave_sum(rsum);
                 } else {
 #pragma unroll
                     for (int i = 0; i < TM; ++i)
 #pragma unroll
                         for (int r = 0; r < MMA::NACC; r += 4)
                             rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
-                    rsum = wave_sum(rsum * TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane));
+                    rsum *= TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane);
+                }
+                if (p.report) {
+                    s = wave_sum(s);
+                    rsum = wave_sum(rsum);
+                } else {
+                    s = wave_sum(s - rsum);
+                    rsum = 0.0;
                 }
                 if (lane == 0) {
                     double tau = p.tol_coeff * __builtin_sqrt(F2);

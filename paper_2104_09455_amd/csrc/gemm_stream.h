@@ -387,7 +387,6 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     if constexpr (GDOT) {
         // comparison (Sec. 2.4 step 4) for this tile
         if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;
-        s_sum = wave_sum(s_sum);
         Wide lane_dot = dot.total;
         if constexpr (MDOT) {
             // column 0 of the extra result blocks holds A . (first plane), column 1 A . (second plane)
@@ -411,9 +410,17 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 lane_dot = g * (gcol == 1 ? 1.0 / 2048.0 : 1.0);
             }
         }
-        const Wide wdot = wave_sum(lane_dot);
-        const double F2 = IS_INT ? 0.0 : wave_sum((double)f2);
-        const double L1 = IS_INT ? 0.0 : wave_sum((double)l1);
+        // cross-lane sums: the norms of the tolerance in fp32; the two sides of the comparison in
+        // wide arithmetic, as one sum of their per-lane difference unless the report wants them apart
+        Wide wdot = 0;
+        if (p.report) {
+            s_sum = wave_sum(s_sum);
+            wdot = wave_sum(lane_dot);
+        } else {
+            s_sum = wave_sum((Wide)(s_sum - lane_dot));
+        }
+        const double F2 = IS_INT ? 0.0 : (double)wave_sum(f2);
+        const double L1 = IS_INT ? 0.0 : (double)wave_sum(l1);
         __syncthreads();  // everyone is done reading the partial tiles
         double* redd = reinterpret_cast<double*>(smem);
         Wide* redw = reinterpret_cast<Wide*>(smem) + 2 * KW;

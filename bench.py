@@ -263,6 +263,62 @@ def measured_ceilings(hip, gen):
 # --------------------------------------------------------------------------- #
 # CPU baseline: the oracle, as it stands, on a bounded sample of the workload
 # --------------------------------------------------------------------------- #
+def chain_leg(gen, batch=256, steps=300):
+    """DLRM's two MLPs as chains (Sec. 2.4 step 4): ReLU fused into the store of every layer but
+    each MLP's last, layer l's output handed to layer l + 1 as its input, one library call per
+    pass.  Times the pass with the selector's schemes and unprotected (device time, replayed
+    from a graph of the pass)."""
+    layers = wl.dlrm_layers(batch)
+    rs = [LayerRun(l, "f16", gen) for l in layers]
+    plan = B.abft_plan_create([B.Layer(r.layer.M, r.layer.N, r.layer.K, r.dt, B.B_NK, 0, B.Conv(), r.B.data_ptr(),
+                                       r.layer.K) for r in rs], profile=False)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    ins, last = [], []
+    for i, r in enumerate(rs):
+        head = i == 0 or not r.layer.name.startswith(rs[i - 1].layer.name[:3])   # first layer of an MLP
+        ins.append(r.A if head else rs[i - 1].C)
+        if i > 0 and head:
+            last.append(i - 1)
+    last.append(len(rs) - 1)
+    for i in range(len(rs)):
+        B.abft_plan_set_activation(plan, i, B.ACT_NONE if i in last else B.ACT_RELU)
+    io = B.PlanIO(ins, [r.layer.K for r in rs], [r.C for r in rs], [r.layer.N for r in rs])
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+
+    def pass_us():
+        with torch.cuda.stream(side):
+            B.abft_plan_run_all(plan, io, flag, -1, side.cuda_stream)
+        side.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=side):
+            B.abft_plan_run_all(plan, io, flag, -1, side.cuda_stream)
+        for _ in range(10):
+            g.replay()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            g.replay()
+        torch.cuda.synchronize()
+        return 1e6 * (time.perf_counter() - t0) / steps
+
+    res = {"batch": batch, "layers": [r.layer.name for r in rs], "relu_after": [r.layer.name for i, r in enumerate(rs) if i not in last]}
+    try:
+        res["us_selector"] = round(pass_us(), 2)
+        for i in range(len(rs)):
+            B.abft_plan_set_mode(plan, i, B.GLOBAL)
+        res["us_global"] = round(pass_us(), 2)
+        for i in range(len(rs)):
+            B.abft_plan_set_mode(plan, i, B.NONE)
+        res["us_none"] = round(pass_us(), 2)
+        res["ovh_selector_pct"] = round(100 * (res["us_selector"] / res["us_none"] - 1), 2)
+        res["ovh_global_pct"] = round(100 * (res["us_global"] / res["us_none"] - 1), 2)
+        res["false_alarms"] = int(flag.item())
+    finally:
+        B.abft_plan_destroy(plan)
+    return res
+
+
 def cpu_baseline(runs, budget_s=15.0):
     import oracle
     from oracle import build as obuild
@@ -560,6 +616,7 @@ def main():
                 fig11.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
             extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
+            extra["dlrm_mlp_chains_relu"] = chain_leg(gen)
             extra["dlrm_top1_cold_cache"] = cold_cache_leg(wl.Layer("top1", 256, 1024, 1024), "f16", gen)
         except Exception as e:  # extras never invalidate the main measurement
             extra["error"] = repr(e)

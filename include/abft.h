@@ -57,6 +57,8 @@ extern "C" {
  * thread-level scheme (Sec. 5.2.2), carried out per wavefront register tile.  AUTO:
  * whatever abft_select returns (intensity-guided ABFT, Sec. 5.3). */
 typedef enum { ABFT_NONE = 0, ABFT_GLOBAL = 1, ABFT_THREAD = 2, ABFT_AUTO = 3 } abft_mode_t;
+/* Activation function a layer applies to its output as it is stored (Sec. 2.4 step 4). */
+typedef enum { ABFT_ACT_NONE = 0, ABFT_ACT_RELU = 1 } abft_act_t;
 
 /* Operand type.  F16 / BF16: A, B and C are fp16 / bf16, accumulation in fp32.
  * I8: A and B are int8, C is int32, accumulation in int32 (exact). */
@@ -257,6 +259,15 @@ int abft_plan_run_all(abft_plan_t *plan, const void *const *A, const int64_t *ld
                       const int64_t *ldc, uint32_t *fault_flag, int event_layer, void *stream);
 /* Override the scheme of a layer (abft_mode_t; ABFT_AUTO re-applies abft_select). */
 int abft_plan_set_mode(abft_plan_t *plan, int layer, int mode);
+/* Activation function of a layer (abft_act_t; ABFT_ACT_NONE at creation), fused into the store
+ * of C (Sec. 2.4 step 4): every check of the layer sees the accumulators as the product left
+ * them, the stored value is the activation of the accumulator, rounded once to the output
+ * type.  ABFT_ACT_RELU stores max(x, 0) (a NaN stores 0; a protected scheme has flagged it).
+ * With it a chain of layers runs wholly in this library: pass layer l's C as layer l + 1's A
+ * to abft_plan_run_all (fp16 / bf16; int8 layers write int32 and do not chain). */
+int abft_plan_set_activation(abft_plan_t *plan, int layer, int act);
+/* Activation function of a layer (abft_act_t) or a negative error. */
+int abft_plan_activation(const abft_plan_t *plan, int layer);
 /* Scheme chosen for a layer (abft_mode_t) or a negative error. */
 int abft_plan_mode(const abft_plan_t *plan, int layer);
 /* Times measured at creation with profile = 1, in microseconds: out[0..2] = NONE, GLOBAL,

@@ -20,7 +20,9 @@ Parity pins (tests/test_oracle_*.py): the GEMM against brute force and
 rigorous rounding bound in fp64; the tile checks against the global identity
 they telescope to; detection exhaustively over every bit of every element on
 small integer cases; arithmetic intensity / CMR / selector against every value
-the paper prints (Fig. 5, Fig. 11 axis labels, Fig. 10 labels, Sec. 3.3).
+the paper prints (Fig. 5, Fig. 11 axis labels, Fig. 10 labels, Sec. 3.3); the
+layer chain (activation function, storage rounding) against closed forms, every
+representable fp16 / bf16 value and its midpoints, and an exact integer chain.
 Parity unpinned: the constant ``C_TOL`` of the floating-point tolerance -- the
 paper never states a tolerance (it says "equality check"), so only the rounding
 model and the clean-run campaigns of this build support it.
@@ -546,3 +548,46 @@ def im2col(x, dtype, KH, KW, stride, pad):
     if dtype == I8:
         return out.astype(np.int8)
     return out
+
+
+# --------------------------------------------------------------------------- #
+# a chain of layers: activation function and storage rounding (Sec. 2.4 step 4)
+# --------------------------------------------------------------------------- #
+def activation(C, act="relu"):
+    """The activation function a layer applies to its output: "relu" is max(x, 0), None passes."""
+    if act is None or act == "none":
+        return C
+    if act == "relu":
+        return np.maximum(C, 0)
+    raise ValueError(act)
+
+
+def round_out(C, dtype):
+    """fp64 values -> the storage array of the output type, rounded once to nearest, ties to
+    even (numpy.float16, or uint16 bf16 bit patterns); int8 products stay int64."""
+    if dtype == I8:
+        return C
+    C = np.asarray(C, dtype=np.float64)
+    if dtype == F16:
+        with np.errstate(over="ignore"):
+            return C.astype(np.float16)
+    if dtype == BF16:
+        # 8 significant bits; exponent range of binary32 (least normal 2^-126)
+        m, e = np.frexp(C)                              # C = m 2^e, 0.5 <= |m| < 1
+        ulp = np.ldexp(1.0, np.maximum(e, -125) - 8)
+        q = np.rint(C / ulp) * ulp                      # rint: ties to even
+        q = np.where(np.isfinite(C), q, C)
+        big = np.ldexp(255.0, 120)                      # largest finite bf16
+        q = np.where(np.abs(q) > big, np.copysign(np.inf, q), q)
+        return (q.astype(np.float32).view(np.uint32) >> 16).astype(np.uint16)
+    raise ValueError(dtype)
+
+
+def mlp_forward(x, weights, dtype, acts):
+    """A chain of fully-connected layers: layer l computes act_l(a_l . W_l) and hands it, stored
+    in the operand type, to layer l + 1 (a_0 = x).  Returns every layer's stored output."""
+    outs, a = [], x
+    for W, act in zip(weights, acts):
+        a = round_out(activation(gemm(a, W, dtype), act), dtype)
+        outs.append(a)
+    return outs

@@ -16,6 +16,7 @@ LIB_PATH = os.path.join(HERE, "libabft.so")
 
 # enums of abft.h
 NONE, GLOBAL, THREAD, AUTO = 0, 1, 2, 3
+ACT_NONE, ACT_RELU = 0, 1
 F16, BF16, I8 = 0, 1, 2
 B_NK, B_KN = 0, 1
 OK = 0
@@ -55,6 +56,7 @@ EXPORTS = [
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
     "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
+    "abft_plan_set_activation", "abft_plan_activation",
 ]
 
 _lib = None
@@ -111,6 +113,10 @@ def lib() -> ctypes.CDLL:
                                     ctypes.POINTER(i64), vp, ci, vp]
     L.abft_plan_set_mode.restype = ci
     L.abft_plan_set_mode.argtypes = [vp, ci, ci]
+    L.abft_plan_set_activation.restype = ci
+    L.abft_plan_set_activation.argtypes = [vp, ci, ci]
+    L.abft_plan_activation.restype = ci
+    L.abft_plan_activation.argtypes = [vp, ci]
     L.abft_k_slices.restype = ci
     L.abft_k_slices.argtypes = [ci, ci, ci, ci, ci, ci, ip, ip, ci]
     L.abft_k_ways.restype = ci
@@ -303,6 +309,17 @@ def abft_plan_run_all(plan, io: PlanIO, fault_flag, event_layer=-1, stream=None)
 
 def abft_plan_set_mode(plan, layer, mode) -> None:
     _check(lib().abft_plan_set_mode(plan, layer, mode))
+
+
+def abft_plan_set_activation(plan, layer, act) -> None:
+    _check(lib().abft_plan_set_activation(plan, layer, act))
+
+
+def abft_plan_activation(plan, layer) -> int:
+    rc = lib().abft_plan_activation(plan, layer)
+    if rc < 0:
+        raise AbftError(rc)
+    return rc
 
 
 def abft_plan_mode(plan, layer) -> int:

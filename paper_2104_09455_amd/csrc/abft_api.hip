@@ -419,6 +419,7 @@ struct Problem {
     long long imgpitch, rowpitch;  // conv: input element (img, ih, iw, c) at img*imgpitch + ih*rowpitch + iw*pix + c
     int pix;
     int tol_K;                     // K the tolerance is taken for (differs from K for a lowered convolution)
+    int act;                       // abft_act_t applied to the stored values
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -634,6 +635,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
         }
     }
     g.flag = flag;
+    g.act = pr.act;
     g.report = reinterpret_cast<Report*>(report);
     const int tol_K = pr.tol_K > 0 ? pr.tol_K : pr.K;
     g.tol_coeff = tol_coeff(tol_K, pr.dtype, mode);
@@ -839,6 +841,7 @@ struct abft_plan {
         void* workspace;
         size_t ws_bytes;
         double t_us[3];
+        int act;          // abft_act_t applied to the stored output
     };
     std::vector<Layer> layers;
 };
@@ -1123,6 +1126,7 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     }
     pr.dtype = d.dtype; pr.b_layout = d.b_layout;
     pr.A = A; pr.B = d.B; pr.ldb = d.ldb; pr.C = C; pr.ldc = ldc;
+    pr.act = L.act;
     // the offline checksums fit the tiling chosen for aligned activations; an input that
     // forces another tiling gets them recomputed into the workspace
     const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr), ABFT_GLOBAL)).bn;
@@ -1157,6 +1161,18 @@ int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
     abft_plan::Layer& L = plan->layers[layer];
     L.mode = mode == ABFT_AUTO ? select_mode(L.desc.M, L.desc.N, L.desc.K, L.desc.dtype) : mode;
     return ABFT_OK;
+}
+
+int abft_plan_set_activation(abft_plan_t* plan, int layer, int act) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    if (act != ABFT_ACT_NONE && act != ABFT_ACT_RELU) return ABFT_E_ENUM;
+    plan->layers[layer].act = act;
+    return ABFT_OK;
+}
+
+int abft_plan_activation(const abft_plan_t* plan, int layer) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    return plan->layers[layer].act;
 }
 
 int abft_plan_mode(const abft_plan_t* plan, int layer) {

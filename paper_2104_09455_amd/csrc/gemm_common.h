@@ -99,6 +99,9 @@ struct GemmArgs {
     int ksplit;
     char* part;              // [tile][ksplit][BM*BN] fp32 / int32 partial accumulators
     unsigned int* counters;  // [tile], zero before and after every launch
+    // activation function applied to the finished values as they are stored (Sec. 2.4 step 4:
+    // after the checks, which see the accumulators as the product left them): 0 none, 1 max(x, 0)
+    int act;
 };
 
 template <typename To, typename Ti>
@@ -910,6 +913,14 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
     }
 
     if (!store) return;
+    if (p.act) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = acc[i][j][r] > 0 ? acc[i][j][r] : 0;
+    }
     // ---- store C (rounded to the output type)
     if constexpr (CFG::CSIZE == 2 && MI == 32) {
         // wavefront tiles that lie wholly inside C: 8-byte stores of four columns per lane

@@ -350,12 +350,16 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
 #pragma unroll
                 for (int w = 0; w < KW; ++w) v[rr] += red[(w * NV + (i * TN + j) * 16 + r) * 64 + lane];
             }
+            // stored values: after the activation function; the checks below see the product
+            AccT o[4];
+#pragma unroll
+            for (int rr = 0; rr < 4; ++rr) o[rr] = (p.act && !(v[rr] > 0)) ? (AccT)0 : v[rr];
             if constexpr (CFG::CSIZE == 2) {
                 if (whole) {
                     // rows 8w + 4 (lane / 32) + 0..3 of this block, four columns per lane
                     char* dst = p.C + ((long long)(tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + (lane & 3)) * p.ldc +
                                        tc.bn0 + j * 32 + (tc.lrow & ~3)) * 2;
-                    store_quad_rows<DT>(v[0], v[1], v[2], v[3], dst, lane);
+                    store_quad_rows<DT>(o[0], o[1], o[2], o[3], dst, lane);
                 }
             }
             if (CFG::CSIZE != 2 || !whole) {
@@ -364,9 +368,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                     const int row = tc.bm0 + i * 32 + 8 * wave + 4 * tc.lgrp + rr;
                     if (row < M && col < N) {
                         char* dst = p.C + ((long long)row * p.ldc + col) * CFG::CSIZE;
-                        if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)v[rr];
-                        else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)v[rr];
-                        else *reinterpret_cast<int*>(dst) = v[rr];
+                        if constexpr (DT == DT_F16) *reinterpret_cast<_Float16*>(dst) = (_Float16)o[rr];
+                        else if constexpr (DT == DT_BF16) *reinterpret_cast<__bf16*>(dst) = (__bf16)o[rr];
+                        else *reinterpret_cast<int*>(dst) = o[rr];
                     }
                 }
             }

@@ -209,3 +209,89 @@ def test_plan_run_all_eager_and_under_graph_replay():
             assert int(flag.item()) == 0
     finally:
         B.abft_plan_destroy(plan)
+
+
+def _storage(t, dtype):
+    """Device tensor -> the oracle's storage array (numpy.float16, or uint16 bf16 bit patterns)."""
+    import torch
+    if dtype == "f16":
+        return t.cpu().numpy()
+    return t.view(torch.int16).cpu().numpy().view(np.uint16)
+
+
+CHAINS = [
+    # (batch, widths): ragged sizes on the generic kernel; the DLRM top MLP at batch 256 on the
+    # streaming kernels; batch 2048 on the direct-to-LDS kernels
+    (200, [96, 160, 72, 40]),
+    (256, [512, 1024, 1024, 512, 256]),
+    (2048, [256, 512, 128, 64]),
+]
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("modes", ["none", "global", "thread", "mixed"])
+@pytest.mark.parametrize("ci", range(len(CHAINS)))
+def test_mlp_chain_with_fused_relu(ci, modes, dtype):
+    """A chain of layers with ReLU fused into every store but the last (Sec. 2.4 step 4), layer
+    l's C handed to layer l + 1 as its A, in one abft_plan_run_all call.  Each layer against the
+    oracle applied to the very input that layer read on the device (so the parity bar of a single
+    product applies), the whole chain against the oracle's chain, and no check fires: the
+    checks see the accumulators before the activation function."""
+    import torch
+    from gpu_util import to_dev, c_to_host, c_close, DEV
+    M, widths = CHAINS[ci]
+    nl = len(widths) - 1
+    dt = DT[dtype]
+    rng_seed = 300 + ci
+    x, _ = wl.gemm_operands(M, widths[1], widths[0], dtype, seed=rng_seed, dist_a="uniform_01", dist_b="weights")
+    Ws, keep, layers = [], [], []
+    for l in range(nl):
+        K, N = widths[l], widths[l + 1]
+        _, Wm = wl.gemm_operands(8, N, K, dtype, seed=rng_seed + 10 + l, dist_a="uniform_01", dist_b="weights")
+        Ws.append(Wm)
+        dB = to_dev(np.ascontiguousarray(Wm.T), dtype)
+        keep.append(dB)
+        layers.append(B.Layer(M, N, K, dt, B.B_NK, 0, B.Conv(), dB.data_ptr(), K))
+    acts = ["relu"] * (nl - 1) + [None]
+    c_t = torch.float16 if dtype == "f16" else torch.bfloat16
+    dx = to_dev(x, dtype)
+    Cs = [torch.zeros((M, widths[l + 1]), dtype=c_t, device=DEV) for l in range(nl)]
+    plan = B.abft_plan_create(layers)
+    try:
+        pick = {"none": [B.NONE] * nl, "global": [B.GLOBAL] * nl, "thread": [B.THREAD] * nl,
+                "mixed": [(B.GLOBAL, B.THREAD)[l % 2] for l in range(nl)]}[modes]
+        for l in range(nl):
+            B.abft_plan_set_mode(plan, l, pick[l])
+            assert B.abft_plan_activation(plan, l) == B.ACT_NONE
+            B.abft_plan_set_activation(plan, l, B.ACT_RELU if acts[l] else B.ACT_NONE)
+            assert B.abft_plan_activation(plan, l) == (B.ACT_RELU if acts[l] else B.ACT_NONE)
+        io = B.PlanIO([dx] + Cs[:-1], widths[:-1], Cs, widths[1:])
+        flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+        print(f"case chain {ci} modes={modes} dtype={dtype}", flush=True)
+        B.abft_plan_run_all(plan, io, flag)
+        torch.cuda.synchronize()
+        assert int(flag.item()) == 0
+        a = x
+        for l in range(nl):
+            ref = oracle.activation(oracle.gemm(a, Ws[l], dtype), acts[l])
+            got = c_to_host(Cs[l], dtype)
+            assert c_close(got, ref, dtype), l
+            if acts[l]:
+                assert got.min() >= 0.0
+                # ReLU decides a sign: where the oracle is clearly negative the store is exactly zero
+                rms = float(np.sqrt(np.mean(ref * ref)))
+                raw = oracle.gemm(a, Ws[l], dtype)
+                assert np.all(got[raw < -1e-2 * rms] == 0.0)
+            else:
+                assert got.min() < 0.0
+            a = _storage(Cs[l], dtype)            # what the next layer read
+        # end to end: the roundings of the stored activations differ by at most an ulp per layer
+        outs = oracle.mlp_forward(x, Ws, dtype, acts)
+        last = oracle.widen(outs[-1], dtype)
+        got = c_to_host(Cs[-1], dtype)
+        rms = float(np.sqrt(np.mean(last * last)))
+        assert np.all(np.abs(got - last) <= 3e-2 * np.abs(last) + 3e-2 * rms)
+        with pytest.raises(B.AbftError):
+            B.abft_plan_set_activation(plan, 0, 7)
+    finally:
+        B.abft_plan_destroy(plan)

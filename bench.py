@@ -172,6 +172,9 @@ def layer_table(hip, runs, reps, warm, stream, modes=(B.NONE, B.GLOBAL, B.THREAD
             "tflops_pick": round(lr.flops / pick_t / 1e6, 2),
             "roofline_frac_pick": round(lr.flops / (pick_t * 1e-6) / roof, 4),
         })
+        if B.REPLICA in t:   # thread-level replication, single accumulation (Sec. 5.1's baseline)
+            rows[-1]["us_replica"] = round(t[B.REPLICA], 2)
+            rows[-1]["ovh_replica_pct"] = round(100 * (t[B.REPLICA] / t[B.NONE] - 1), 2)
     return rows
 
 
@@ -608,12 +611,14 @@ def main():
                 r = layer_table(hip, [lr], 10, 2, stream)[0]
                 sweep.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
             extra["sweep_N4096_K4096"] = sweep
-            # the paper's Fig. 11 sizes (its T4 numbers: thread-level 2-14 %, global 27 % at 32^3 down to 1 % at 2048^3)
+            # the paper's Fig. 11 sizes (its T4 numbers: thread-level 2-14 %, global 27 % at 32^3 down to 1 % at 2048^3,
+            # replication above 70 % at the two largest sizes)
             fig11 = []
             for n in wl.square_sizes_paper():
                 lr = LayerRun(wl.Layer(f"sq{n}", n, n, n), "f16", gen, "normal", "normal")
-                r = layer_table(hip, [lr], 20, 2, stream)[0]
-                fig11.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
+                r = layer_table(hip, [lr], 20, 2, stream, modes=(B.NONE, B.GLOBAL, B.THREAD, B.REPLICA))[0]
+                fig11.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct",
+                                                "ovh_replica_pct")})
             extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
             extra["dlrm_mlp_chains_relu"] = chain_leg(gen)

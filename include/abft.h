@@ -56,7 +56,18 @@ extern "C" {
  * products, an activation-checksum kernel runs first.  THREAD: the paper's one-sided
  * thread-level scheme (Sec. 5.2.2), carried out per wavefront register tile.  AUTO:
  * whatever abft_select returns (intensity-guided ABFT, Sec. 5.3). */
-typedef enum { ABFT_NONE = 0, ABFT_GLOBAL = 1, ABFT_THREAD = 2, ABFT_AUTO = 3 } abft_mode_t;
+typedef enum {
+    ABFT_NONE = 0,
+    ABFT_GLOBAL = 1,   /* global ABFT, one comparison per workgroup tile (Sec. 2.4, 2.5) */
+    ABFT_THREAD = 2,   /* one-sided thread-level ABFT, one comparison per wavefront tile (Sec. 5.2) */
+    ABFT_AUTO = 3,     /* abft_select decides between GLOBAL and THREAD (Sec. 5.3) */
+    /* Thread-level replication with single accumulation (Sec. 5.1), the baseline the paper weighs
+     * one-sided ABFT against: every MFMA of the product is issued a second time, all those of one A
+     * fragment into one accumulator block, whose sum must equal the sum of the wavefront tile.
+     * Same tiles, comparisons, tolerance, report and k partition as ABFT_THREAD; never chosen by
+     * ABFT_AUTO or by a plan's profile. */
+    ABFT_REPLICA = 4
+} abft_mode_t;
 /* Activation function a layer applies to its output as it is stored (Sec. 2.4 step 4). */
 typedef enum { ABFT_ACT_NONE = 0, ABFT_ACT_RELU = 1 } abft_act_t;
 

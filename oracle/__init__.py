@@ -405,6 +405,28 @@ def thread_check(A, B, C, dtype, tile_m, tile_n, two_sided=False):
     return any(c.flag for c in checks), checks
 
 
+def replica_check(A, B, C, dtype, r0, r1, c0, c1, block_n=32) -> Check:
+    """Thread-level replication with single accumulation for one tile (Sec. 5.1): every product
+    of the tile is formed a second time, the tile's column blocks of width ``block_n`` (the
+    matrix instruction's output width) all added into one block; the sum of that block against
+    the output summation of the tile of the C that is passed in."""
+    Aw, Bw = widen(A, dtype), widen(B, dtype)
+    K = Aw.shape[1]
+    At = np.ascontiguousarray(Aw[r0:r1])
+    acc_t = np.int64 if dtype == I8 else np.float64
+    rep = np.zeros((r1 - r0, block_n), dtype=acc_t)
+    for b0 in range(c0, c1, block_n):
+        blk = gemm(At, np.ascontiguousarray(Bw[:, b0:min(b0 + block_n, c1)]), dtype)
+        rep[:, :blk.shape[1]] += blk
+    lhs = block_sum(C, r0, r1, c0, c1)
+    if dtype == I8:
+        rhs = int(rep.sum())
+        return Check(int(lhs), rhs, 0.0, int(lhs) != rhs)
+    rhs = math.fsum(rep.ravel().tolist())
+    tau = tolerance(K, frob(C, r0, r1, c0, c1), dtype, scheme=2)
+    return Check(lhs, rhs, tau, mismatch(lhs, rhs, tau))
+
+
 # --------------------------------------------------------------------------- #
 # fault injection (fault model of Sec. 2.3)
 # --------------------------------------------------------------------------- #

@@ -15,13 +15,13 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libabft.so")
 
 # enums of abft.h
-NONE, GLOBAL, THREAD, AUTO = 0, 1, 2, 3
+NONE, GLOBAL, THREAD, AUTO, REPLICA = 0, 1, 2, 3, 4
 ACT_NONE, ACT_RELU = 0, 1
 F16, BF16, I8 = 0, 1, 2
 B_NK, B_KN = 0, 1
 OK = 0
 
-MODE_NAMES = {NONE: "none", GLOBAL: "global", THREAD: "thread", AUTO: "auto"}
+MODE_NAMES = {NONE: "none", GLOBAL: "global", THREAD: "thread", AUTO: "auto", REPLICA: "replica"}
 DTYPE_NAMES = {F16: "f16", BF16: "bf16", I8: "i8"}
 
 

@@ -63,6 +63,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // wide in N: one checksum MFMA per TN real ones); force >= 0 pins a configuration (tuning aid,
 // environment variable ABFT_FORCE_CFG).
 int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
+    if (mode == ABFT_REPLICA) mode = ABFT_THREAD;  // checked per wavefront tile alike: the same tiles
     static const int force = [] {
         const char* e = std::getenv("ABFT_FORCE_CFG");
         return e ? std::atoi(e) : -1;
@@ -484,6 +485,7 @@ size_t ws_bytes_any_cfg(int M, int N, int K) {
 
 double tol_coeff(int K, int dt, int mode) {
     if (dt == ABFT_I8) return 0.0;
+    if (mode == ABFT_REPLICA) mode = ABFT_THREAD;  // two fp32 accumulations compared, as there
     double u_chi = 0.0;
     if (mode == ABFT_THREAD) u_chi = dt == ABFT_F16 ? U_CHI_F16 : U_CHI_BF16;
     return C_TOL * (U_ACC * std::sqrt((double)K) + u_chi);
@@ -562,7 +564,7 @@ hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_
 
 int validate_common(const Problem& pr, int mode, const uint32_t* flag) {
     if (!valid_dtype(pr.dtype)) return ABFT_E_ENUM;
-    if (mode < ABFT_NONE || mode > ABFT_AUTO) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_REPLICA) return ABFT_E_ENUM;
     if (pr.b_layout != ABFT_B_NK && pr.b_layout != ABFT_B_KN) return ABFT_E_ENUM;
     if (pr.M <= 0 || pr.N <= 0 || pr.K <= 0) return ABFT_E_SHAPE;
     if (!pr.A || !pr.B || !pr.C) return ABFT_E_NULL;
@@ -1157,7 +1159,7 @@ int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* ld
 
 int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
-    if (mode < ABFT_NONE || mode > ABFT_AUTO) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_REPLICA) return ABFT_E_ENUM;
     abft_plan::Layer& L = plan->layers[layer];
     L.mode = mode == ABFT_AUTO ? select_mode(L.desc.M, L.desc.N, L.desc.K, L.desc.dtype) : mode;
     return ABFT_OK;

@@ -26,7 +26,11 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 enum { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2 };
 // MODE_GLOBAL_PRE (kernel-internal): the global scheme with the checksum dot products left by
 // the activation-checksum kernel instead of formed inside the product's loop
-enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3 };
+enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3, MODE_REPL = 4 };
+// MODE_REPL: thread-level replication with single accumulation (Sec. 5.1): every MFMA of the
+// product is issued a second time into one accumulator block per A fragment; the sum of those
+// blocks must equal the sum of the wavefront tile.  Checked exactly like MODE_THREAD.
+constexpr bool mode_is_wave_level(int mode) { return mode == MODE_THREAD || mode == MODE_REPL; }
 
 struct Report {  // mirrors abft_report_t
     double lhs, rhs, tau, worst_ratio;
@@ -576,6 +580,11 @@ struct ChecksumForm {
     static constexpr int NP = SPLIT ? (CFG::DT == DT_BF16 ? 3 : 2) : 1;  // checksum operands per k step
     static constexpr int NCHK = NP * CFG::TM;
 };
+// Redundant accumulator blocks a wavefront carries under each scheme.
+template <class CFG, int MODE>
+struct CheckRegs {
+    static constexpr int N = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : (MODE == MODE_REPL ? CFG::TM : 1);
+};
 
 // ---------------------------------------------------------------------------
 // Per-thread view of the tiling: which wavefront tile this lane works on and which
@@ -693,7 +702,7 @@ __device__ __forceinline__ void store_quad_rows(float v0, float v1, float v2, fl
 //          accumulators (Sec. 5.2.2), compared here; p.flag is touched only on mismatch.
 template <class CFG, int MODE>
 __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
-                                         typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1],
+                                         typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[(CheckRegs<CFG, MODE>::N)],
                                          const GemmArgs& p, int tile_m, int tile_n, char* smem, bool store = true,
                                          int wave_mn = -1, const void* lane_dot = nullptr) {
     typedef Mma<CFG::DT, CFG::MI> MMA;
@@ -760,7 +769,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             } else {
                 // (exact 64-bit sums from 16-bit pieces, as above)
                 long long rsum = 0;
-                if constexpr (ChecksumForm<CFG>::SPLIT) {
+                if constexpr (MODE != MODE_REPL && ChecksumForm<CFG>::SPLIT) {
                     // accumulators of the low-digit operand, then 256 x those of the high-digit one
 #pragma unroll
                     for (int pc = 0; pc < 2; ++pc) {
@@ -786,11 +795,14 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                             r_hi += chk[i][r] >> 16;
                         }
                     rsum = ((long long)r_hi << 16) + (long long)r_lo;
-                    const long long w = (lane % MI) >= MI / 2 ? 256 : 1;
+                    const long long w = (MODE != MODE_REPL && (lane % MI) >= MI / 2) ? 256 : 1;
                     rsum = wave_sum(rsum * w);
                 }
                 if (lane == 0) {
-                    bool bad = s != rsum;
+                    // (replication: a block that took several products may have wrapped where the
+                    // product's own blocks did not; the two sides still agree modulo 2^32, and a
+                    // flipped bit never changes a sum by a multiple of 2^32)
+                    bool bad = MODE == MODE_REPL ? (unsigned int)(s - rsum) != 0u : s != rsum;
                     if (bad) atomicOr(p.flag, 1u);
                     if (p.report)
                         report_update(p.report, bad ? __builtin_huge_val() : 0.0, (double)s, (double)rsum, 0.0, 0.0, 0.0,
@@ -868,7 +880,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                 }
             } else {
                 double rsum = 0.0;
-                if constexpr (ChecksumForm<CFG>::SPLIT) {
+                if constexpr (MODE != MODE_REPL && ChecksumForm<CFG>::SPLIT) {
                     typedef TileChecksumSplit<CFG::DT, TN> SPL;
 #pragma unroll
                     for (int pc = 0; pc < SPL::NP; ++pc) {
@@ -887,7 +899,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
 #pragma unroll
                         for (int r = 0; r < MMA::NACC; r += 4)
                             rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
-                    rsum *= TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane);
+                    if constexpr (MODE != MODE_REPL) rsum *= TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane);
                 }
                 if (p.report) {
                     s = wave_sum(s);

@@ -217,7 +217,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
     constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
-    constexpr int NCHK = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1;
+    constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
     for (int i = 0; i < NCHK; ++i)
@@ -281,6 +281,12 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
             i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
 #pragma unroll
             for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
+        } else if constexpr (MODE == MODE_REPL) {
+            // every product once more, all of an A fragment's into one block (Sec. 5.1)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) chk[i] = MMA::run(fa[buf][i], fb[buf][j], chk[i]);
         }
     };
 
@@ -311,7 +317,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
             for (int kk = 0; kk < 3; ++kk) {
                 read_frags(st, kk + 1, (kk + 1) & 1);
                 mma_step(kk & 1);
-                if constexpr (MODE != MODE_THREAD) {
+                if constexpr (!mode_is_wave_level(MODE)) {
                     // fragment reads of the next step go out early, one per MFMA, so that the last
                     // of them has the rest of the step's MFMAs to land; the global scheme's reads
                     // and vector FMAs of the checksum dot product are spread between the MFMAs

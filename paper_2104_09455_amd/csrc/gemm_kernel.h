@@ -203,7 +203,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = 0;
     constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
-    constexpr int NCHK = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1;
+    constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
     for (int i = 0; i < NCHK; ++i)
@@ -251,6 +251,12 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
                 i32x4 x = TileChecksum<CFG::DT, MI, TN>::make(b, lane);
 #pragma unroll
                 for (int i = 0; i < TM; ++i) chk[i] = MMA::run(a[i], x, chk[i]);
+            } else if constexpr (MODE == MODE_REPL) {
+                // every product once more, all of an A fragment's into one block (Sec. 5.1)
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int j = 0; j < TN; ++j) chk[i] = MMA::run(a[i], b[j], chk[i]);
             }
         }
         if (more) store_tiles(cur ^ 1, ra, rb);

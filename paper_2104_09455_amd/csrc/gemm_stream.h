@@ -190,7 +190,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
     constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
-    constexpr int NCHK = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : 1;
+    constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
     for (int i = 0; i < NCHK; ++i)
@@ -269,6 +269,12 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
 #pragma unroll
             for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
+        } else if constexpr (MODE == MODE_REPL) {
+            // every product once more, all of an A fragment's into one block (Sec. 5.1)
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) chk[i] = MMA::run(fa[buf][i], fb[buf][j], chk[i]);
         }
     };
 
@@ -317,7 +323,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     // wavefront order; wavefront w adds and stores accumulator registers 4w .. 4w+3 of every
     // MFMA block (rows 8w + 4 (lane / 32) + 0..3 of the block)
     static_assert(MODE != MODE_GLOBAL_PRE, "streaming configurations form the checksum dot product themselves");
-    if constexpr (MODE == MODE_THREAD) epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
+    if constexpr (mode_is_wave_level(MODE)) epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
     __syncthreads();  // the sum reuses every wavefront's stages
     AccT* red = reinterpret_cast<AccT*>(smem);
     constexpr int NV = TM * TN * 16;

@@ -9,7 +9,8 @@ from paper_2104_09455_amd import workloads as wl
 
 pytestmark = pytest.mark.gpu
 
-MODES = [B.NONE, B.GLOBAL, B.THREAD]
+MODES = [B.NONE, B.GLOBAL, B.THREAD, B.REPLICA]
+WAVE_LEVEL = (B.THREAD, B.REPLICA)   # one comparison per wavefront tile
 # (M, N, K): one tile; several tiles with ragged edges; skinny; degenerate; unaligned K
 SHAPES = [(64, 64, 64), (200, 136, 264), (130, 70, 333), (1, 64, 13), (16, 1, 256), (1, 1, 1),
           (300, 520, 1024), (17, 260, 72), (512, 512, 128)]
@@ -47,12 +48,23 @@ def test_clean_parity(shape, mode, dtype):
             assert abs(res.report.lhs - near.lhs) <= near.tau + 1e-300
             assert res.report.tau == pytest.approx(near.tau, rel=1e-3)
             assert res.report.worst_ratio < 0.5
-    if mode == B.THREAD:
+    if mode in WAVE_LEVEL:
         tm, tn, _ = B.abft_tile_shape(M, N, K, dt, aligned)
         import math
         # one comparison per wave tile of the launched grid (tiles past the edge included) and k part
         assert res.report.tiles >= math.ceil(M / tm) * math.ceil(N / tn) * len(B.abft_k_parts(M, N, K, dt, mode, aligned))
         assert res.report.worst_ratio < 0.5
+        if mode == B.REPLICA and len(B.abft_k_parts(M, N, K, dt, mode, aligned)) == 1:
+            # the reported tile is one of the oracle's replication checks: same sides, same tolerance
+            checks = [oracle.replica_check(A, Bm, C_ref, dtype, *t) for t in oracle.tiles(M, N, tm, tn)]
+            assert not any(c.flag for c in checks)
+            near = min(checks, key=lambda c: abs(c.rhs - res.report.rhs))
+            if dtype == "i8":
+                assert res.report.lhs == near.lhs and res.report.rhs == near.rhs
+            else:
+                assert abs(res.report.rhs - near.rhs) <= near.tau + 1e-300
+                assert abs(res.report.lhs - near.lhs) <= near.tau + 1e-300
+                assert res.report.tau == pytest.approx(near.tau, rel=1e-3)
 
 
 # shapes chosen so that every tile configuration of the dispatcher runs under test:
@@ -83,7 +95,7 @@ def test_every_tile_configuration(case, mode, dtype):
     if mode == B.GLOBAL:
         bad, checks = oracle.global_check_blocks(A, Bm, C_ref, dtype, *region)
         assert not bad and res.report.tiles == len(checks) and res.report.worst_ratio < 0.5
-    if mode == B.THREAD:
+    if mode in WAVE_LEVEL:
         assert res.report.worst_ratio < 0.5
     if mode != B.NONE:
         # a flipped exponent bit (sign bit for int8) in the last, ragged tile is seen
@@ -158,7 +170,7 @@ def test_checksum_vectors(dtype):
             assert np.allclose(alpha.cpu().numpy(), a_ref, rtol=1e-12, atol=1e-12)
 
 
-@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD])
+@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD, B.REPLICA])
 @pytest.mark.parametrize("shape", [(64, 64, 64), (200, 136, 256)])
 def test_int8_injected_faults_always_flagged(shape, mode):
     """Every single-bit flip of an int32 accumulator changes the sum exactly: 100 % detection."""
@@ -189,7 +201,7 @@ def test_int8_injected_faults_always_flagged(shape, mode):
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD])
+@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD, B.REPLICA])
 def test_fp_injected_faults_match_oracle_outside_band(mode, dtype):
     """|delta| >= 2 tau must be flagged, |delta| <= tau/2 must not (don't-care in between);
     non-finite results must be flagged."""
@@ -219,7 +231,8 @@ def test_fp_injected_faults_match_oracle_outside_band(mode, dtype):
             As, Bs = np.ascontiguousarray(A[:, idx]), np.ascontiguousarray(Bm[idx, :])
             C_bad = oracle.inject(As, Bs, oracle.gemm(As, Bs, dtype), dtype, i, j, bit)
             r0, c0 = i // tm * tm, j // tn * tn
-            chk = oracle.tile_check(As, Bs, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
+            check = oracle.replica_check if mode == B.REPLICA else oracle.tile_check
+            chk = check(As, Bs, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
             chk.tau = oracle.tolerance(K, oracle.frob(C_bad, r0, r0 + tm, c0, c0 + tn), dtype, scheme=2)
         if not math.isfinite(C_bad[i, j]):
             assert res.flag == 1
@@ -318,7 +331,7 @@ def test_split_k_thread_level(dtype, shape):
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_clean_runs_raise_no_false_alarm(dtype):
-    """Zero false positives: 1000 clean runs per type (250 seeds x two shapes x both schemes), over
+    """Zero false positives: 1500 clean runs per type (250 seeds x two shapes x the three protected schemes), over
     the value distributions of the benchmark configurations, including all-positive operands
     (where the accumulation's coherent bias shows): never a flag, residual below half the tolerance."""
     from gpu_util import run_gemm
@@ -328,7 +341,7 @@ def test_clean_runs_raise_no_false_alarm(dtype):
         da, db = dists[seed % len(dists)]
         for (M, N, K) in ((64, 64, 64), (200, 136, 256)):
             A, Bm = wl.gemm_operands(M, N, K, dtype, seed=7000 + seed, dist_a=da, dist_b=db)
-            for mode in (B.GLOBAL, B.THREAD):
+            for mode in (B.GLOBAL, B.THREAD, B.REPLICA):
                 res = run_gemm(A, Bm, dtype, mode)
                 assert res.flag == 0, (seed, da, db, (M, N, K), mode, res.report.worst_ratio)
                 worst = max(worst, res.report.worst_ratio)

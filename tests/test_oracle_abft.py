@@ -285,3 +285,49 @@ def test_sliced_thread_check_matches_unsliced_on_clean_data_and_sees_faults():
         want2 = oracle.inject(A, B, C, dtype, 0, 0, 3, k_after=-1, k_begin=64)
         assert np.allclose(bad2, want2, rtol=1e-12, atol=1e-12)
     assert oracle.slice_of([(0, 32), (32, 64)], 32) == 1
+
+
+# ------------------------------------------------------------------ replication (Sec. 5.1)
+@pytest.mark.parametrize("block_n", [32, 8, 5])
+def test_replica_check_integer_identity_and_every_bit(block_n):
+    """Single-accumulation replication over the integers: the replicated block sums to the
+    tile's output summation exactly (ragged last block included), agrees with the one-sided
+    tile check's checksum side, and every single-bit flip of every element is flagged."""
+    M, N, K = 6, 13, 9
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=41)
+    C = oracle.gemm(A, B, "i8")
+    r0, r1, c0, c1 = 1, 6, 2, 13
+    chk = oracle.replica_check(A, B, C, "i8", r0, r1, c0, c1, block_n=block_n)
+    want = int((A.astype(np.int64)[r0:r1] @ B.astype(np.int64)[:, c0:c1]).sum())
+    assert chk.lhs == chk.rhs == want and not chk.flag
+    assert chk.rhs == oracle.tile_check(A, B, C, "i8", r0, r1, c0, c1).rhs
+    for i in range(r0, r1):
+        for j in range(c0, c1):
+            for bit in (0, 7, 15, 31):
+                Cb = C.copy()
+                Cb[i, j] = oracle.flip_bit(int(C[i, j]), bit, "i8")
+                assert oracle.replica_check(A, B, Cb, "i8", r0, r1, c0, c1, block_n=block_n).flag
+    # an element outside the tile does not concern it
+    Cb = C.copy()
+    Cb[0, 0] += 1000
+    assert not oracle.replica_check(A, B, Cb, "i8", r0, r1, c0, c1, block_n=block_n).flag
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_replica_check_fp_against_numpy_and_tolerance(dtype):
+    M, N, K = 40, 70, 96
+    A, B = wl.gemm_operands(M, N, K, dtype, seed=43)
+    C = oracle.gemm(A, B, dtype)
+    r0, r1, c0, c1 = 8, 40, 6, 70
+    chk = oracle.replica_check(A, B, C, dtype, r0, r1, c0, c1)
+    Aw, Bw = oracle.widen(A, dtype), oracle.widen(B, dtype)
+    want = float((Aw[r0:r1] @ Bw[:, c0:c1]).sum())
+    scale = float(np.abs(Aw[r0:r1]).sum(axis=0) @ np.abs(Bw[:, c0:c1]).sum(axis=1))
+    assert abs(chk.rhs - want) <= 1e-13 * scale and abs(chk.lhs - want) <= 1e-13 * scale
+    assert not chk.flag
+    assert chk.tau == oracle.tolerance(K, oracle.frob(C, r0, r1, c0, c1), dtype, scheme=2)
+    # a change well above the tolerance is seen, one well below is not
+    for delta, seen in ((4 * chk.tau, True), (chk.tau / 4, False)):
+        Cb = C.copy()
+        Cb[r0 + 3, c0 + 40] += delta
+        assert oracle.replica_check(A, B, Cb, dtype, r0, r1, c0, c1).flag == seen

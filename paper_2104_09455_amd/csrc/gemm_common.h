@@ -47,11 +47,21 @@ struct Report {  // mirrors abft_report_t
 __device__ __forceinline__ void report_update(Report* rep, double ratio, double lhs, double rhs, double tau,
                                               double frob, double l1, unsigned region) {
     atomicAdd(&rep->tiles, 1ull);
+    volatile Report* v = rep;
+    {
+        // A comparison that cannot displace the stored one leaves without the lock.  The stored
+        // entry only ever moves to a larger ratio, or at the same ratio to a lower region, so
+        // losing against what was read (region first, then ratio) means losing against what is
+        // there now; ties are settled without the lock only at ratio 0, where every earlier
+        // entry had ratio 0 as well.
+        const unsigned reg = v->region;
+        const double cur = v->worst_ratio;
+        if (reg != 0u && (ratio < cur || (ratio == 0.0 && cur == 0.0 && region + 1u >= reg))) return;
+    }
     bool got = false;
     for (int spin = 0; spin < (1 << 22) && !got; ++spin) got = atomicCAS(&rep->lock, 0u, 1u) == 0u;
     if (!got) return;
     __threadfence();
-    volatile Report* v = rep;
     const bool first = v->region == 0u;
     const double cur = v->worst_ratio;
     if (first || ratio > cur || (ratio == cur && region + 1u < v->region)) {

@@ -34,16 +34,16 @@ class Big:
         self.beta = torch.zeros(B.abft_beta_bytes(K, N, self.rn) // 8, dtype=torch.float64, device=DEV)
         B.abft_weight_checksum(K, N, self.dB, K, B.B_NK, self.dt, self.beta, block_n=self.rn)
 
-    def run(self, mode, inject=None):
+    def run(self, mode, inject=None, want_report=True):
         import torch
         from gpu_util import read_report
         self.flag.zero_()
         self.rep.zero_()
         B.abft_gemm(self.M, self.N, self.K, self.dA, self.K, self.dB, self.K, B.B_NK, self.dC, self.N, self.dt,
                     mode, beta=self.beta, workspace=self.ws, workspace_bytes=self.wsb, fault_flag=self.flag,
-                    report=self.rep, inject=inject)
+                    report=self.rep if want_report else None, inject=inject)
         torch.cuda.synchronize()
-        return int(self.flag.item()), read_report(self.rep)
+        return int(self.flag.item()), (read_report(self.rep) if want_report else None)
 
 
 @pytest.mark.parametrize("n,dtype", [(4096, "f16"), (4096, "bf16"), (8192, "f16"), (8192, "i8")])
@@ -132,6 +132,65 @@ def test_fault_campaign_global_4096(dtype, trials):
             mustnot += 1
         else:
             band += 1
+    assert must > 0
+    if dtype != "i8":
+        assert mustnot > 0
+
+
+@pytest.mark.parametrize("mode", [B.THREAD, B.REPLICA])
+@pytest.mark.parametrize("dtype,trials", [("i8", 400), ("f16", 400)])
+def test_fault_campaign_wave_level_4096(dtype, trials, mode):
+    """Seeded single-bit flips at 4096^3 under the two wavefront-level schemes (one-sided ABFT,
+    replication): element uniform over 16 wavefront tiles drawn once (whose oracle blocks are
+    computed once each), bit uniform over all 32, half in the finished value and half in the
+    running accumulator.  int8: every flip flagged.  fp16: the verdict equals the oracle's outside
+    the don't-care band around the tolerance of the tile that holds the element."""
+    n = 4096
+    big = Big(n, n, n, dtype, seed=79)
+    tm, tn, ks = B.abft_tile_shape(n, n, n, big.dt, True)
+    assert B.abft_k_ways(n, n, n, big.dt, mode)[0] == 1   # one wavefront per register tile: no k parts
+    flag0, rep0 = big.run(mode)
+    assert flag0 == 0 and rep0.tiles == (n // tm) * (n // tn)
+    rng = np.random.default_rng(80)
+    must = mustnot = 0
+    tiles = [(int(rng.integers(n // tm)), int(rng.integers(n // tn))) for _ in range(16)]
+    blocks = {}
+    for t in range(trials):
+        ti, tj = tiles[t % len(tiles)]
+        i, j, bit = ti * tm + int(rng.integers(tm)), tj * tn + int(rng.integers(tn)), int(rng.integers(32))
+        k_after = -1 if t % 2 == 0 else ks * int(rng.integers(1, n // ks))
+        if t % 50 == 0:
+            print(f"case {t} mode={mode} dtype={dtype} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        flag, _ = big.run(mode, inject=B.Fault(i, j, bit, k_after), want_report=False)
+        if dtype == "i8":
+            assert flag == 1
+            must += 1
+            continue
+        kk = n if k_after < 0 else k_after
+        a_row, b_col = big.A[i:i + 1], np.ascontiguousarray(big.Bm[:, j:j + 1])
+        head = oracle.partial_dot(a_row, b_col, dtype, 0, 0, 0, kk)
+        tail = oracle.partial_dot(a_row, b_col, dtype, 0, 0, kk, n)
+        bad = oracle.flip_bit(head, bit, dtype) + tail
+        if not math.isfinite(bad):
+            assert flag == 1
+            must += 1
+            continue
+        delta = abs(bad - (head + tail))
+        r0, c0 = ti * tm, tj * tn
+        if (r0, c0) not in blocks:
+            blk = oracle.gemm(big.A[r0:r0 + tm], np.ascontiguousarray(big.Bm[:, c0:c0 + tn]), dtype)
+            blocks[(r0, c0)] = (blk, oracle.frob(blk) ** 2)
+        blk, f2_clean = blocks[(r0, c0)]
+        clean = float(blk[i - r0, j - c0])
+        frob_bad = math.sqrt(max(f2_clean - clean * clean + bad * bad, 0.0))
+        tau = oracle.tolerance(n, frob_bad, dtype, scheme=2)
+        resid0 = rep0.tau * rep0.worst_ratio   # largest clean rounding residual of any tile on the device
+        if delta >= 2 * tau + resid0:
+            assert flag == 1, (i, j, bit, delta, tau)
+            must += 1
+        elif delta <= tau / 2 - resid0:
+            assert flag == 0, (i, j, bit, delta, tau)
+            mustnot += 1
     assert must > 0
     if dtype != "i8":
         assert mustnot > 0

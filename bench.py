@@ -156,6 +156,9 @@ def time_mode(hip: Hip, lr: LayerRun, mode: int, reps: int, warm: int, stream=No
     return us
 
 
+ALL_ROWS = []   # every per-layer measurement of this run, for the selector study
+
+
 def layer_table(hip, runs, reps, warm, stream, modes=(B.NONE, B.GLOBAL, B.THREAD)):
     rows = []
     for lr in runs:
@@ -175,7 +178,32 @@ def layer_table(hip, runs, reps, warm, stream, modes=(B.NONE, B.GLOBAL, B.THREAD
         if B.REPLICA in t:   # thread-level replication, single accumulation (Sec. 5.1's baseline)
             rows[-1]["us_replica"] = round(t[B.REPLICA], 2)
             rows[-1]["ovh_replica_pct"] = round(100 * (t[B.REPLICA] / t[B.NONE] - 1), 2)
+        ALL_ROWS.append(dict(rows[-1], dtype=lr.dtype))
     return rows
+
+
+def selector_study(rows):
+    """The analytic rule (global iff AI > CMR, Sec. 5.3) against the measured per-layer optimum over
+    every layer measured in this run, and the threshold that would have served these layers best
+    (scan over the observed intensities; the rule stays 'global above the threshold')."""
+    fp = [r for r in rows if r["dtype"] != "i8"]
+    if not fp:
+        return None
+    def cost(th):
+        t = sum(r["us_global"] if r["ai"] > th else r["us_thread"] for r in fp)
+        miss = sum(1 for r in fp if ((r["us_global"] <= r["us_thread"]) != (r["ai"] > th)))
+        return t, miss
+    best_t = sum(min(r["us_global"], r["us_thread"]) for r in fp)
+    t_none = sum(r["us_none"] for r in fp)
+    cands = [0.0] + sorted({r["ai"] for r in fp})
+    fit = min(cands, key=lambda th: cost(th)[0])
+    ta, ma = cost(314.6)
+    tf, mf = cost(fit)
+    return {"layers": len(fp), "spec_cmr": 314.6,
+            "analytic": {"mispredicted": ma, "ovh_pct": round(100 * (ta / t_none - 1), 2)},
+            "fitted": {"threshold": fit, "mispredicted": mf, "ovh_pct": round(100 * (tf / t_none - 1), 2)},
+            "per_layer_best_ovh_pct": round(100 * (best_t / t_none - 1), 2),
+            "global_faster_on": sum(1 for r in fp if r["us_global"] <= r["us_thread"])}
 
 
 def summarize(rows):
@@ -622,6 +650,7 @@ def main():
             extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
             extra["dlrm_mlp_chains_relu"] = chain_leg(gen)
+            extra["selector_study_fp16_bf16"] = selector_study(ALL_ROWS)
             extra["dlrm_top1_cold_cache"] = cold_cache_leg(wl.Layer("top1", 256, 1024, 1024), "f16", gen)
         except Exception as e:  # extras never invalidate the main measurement
             extra["error"] = repr(e)

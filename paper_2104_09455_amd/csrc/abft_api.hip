@@ -187,7 +187,55 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 #pragma unroll
     for (int e = 0; e < EPC; ++e) s[e] = 0;
 
-    for (int m0 = row_begin + ty; m0 < row_end; m0 += 64) {
+    __shared__ Wide alpha_s[32 * EPC];
+    // Rows whose chunks cannot be read whole (K or the leading dimension is no multiple of a
+    // chunk): one element per thread and row instead.  Thread t takes column t % kb of the kb
+    // columns of a pass and every nrg-th row, so that adjacent lanes read adjacent elements of a
+    // row and the loads of one thread do not wait for each other.
+    const bool by_element = !p.conv && !p.vec;
+    if (by_element) {
+        const int kbase = blockIdx.x * 32 * EPC;
+        const int kb_all = min(32 * EPC, p.K - kbase);   // columns of this block
+        Wide* part = &red[0][0][0];
+        Wide* out = reinterpret_cast<Wide*>(p.alpha_out);
+        for (int c0 = 0; c0 < 32 * EPC; c0 += 256) {     // (int8 blocks span 512 columns: two passes)
+            const int kb = min(256, kb_all - c0);        // columns of this pass; none left: <= 0
+            Wide acc = 0;
+            if (kb > 0) {
+                const int nrg = 256 / kb, col = tid % kb, rg = tid / kb;
+                if (rg < nrg) {
+                    const char* src = p.A + (long long)(kbase + c0 + col) * ESIZE;
+                    for (int m0 = row_begin + rg; m0 < row_end; m0 += 8 * nrg) {
+                        Wide v[8];
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) {
+                            const int m = m0 + u * nrg;
+                            const int mc = m < row_end ? m : m0;   // a valid row; its value is dropped below
+                            const char* q = src + (long long)mc * p.lda * ESIZE;
+                            Wide x;
+                            if constexpr (DT == DT_F16) x = (double)(float)*reinterpret_cast<const _Float16*>(q);
+                            else if constexpr (DT == DT_BF16) x = (double)(float)*reinterpret_cast<const __bf16*>(q);
+                            else x = (long long)*reinterpret_cast<const signed char*>(q);
+                            v[u] = m < row_end ? x : (Wide)0;
+                        }
+#pragma unroll
+                        for (int u = 0; u < 8; ++u) acc += v[u];
+                    }
+                }
+            }
+            part[tid] = acc;
+            __syncthreads();
+            Wide a = 0;
+            if (tid < kb) {
+                const int nrg = 256 / kb;
+                for (int g = 0; g < nrg; ++g) a += part[g * kb + tid];
+                if (out) out[kbase + c0 + tid] = a;
+            }
+            alpha_s[c0 + tid] = a;
+            __syncthreads();
+        }
+    }
+    for (int m0 = row_begin + ty; m0 < row_end && !by_element; m0 += 64) {
         // int8: up to eight rows are summed in int32 first (exact); fp16 / bf16 values are
         // widened and added in fp64 one by one, so the checksum side carries no rounding
         // that could show up in the comparison
@@ -243,11 +291,12 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 #pragma unroll
         for (int e = 0; e < EPC; ++e) s[e] += (Wide)f[e];
     }
+    if (!by_element) {
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) red[ty][tx][e] = s[e];
+        for (int e = 0; e < EPC; ++e) red[ty][tx][e] = s[e];
+    }
     __syncthreads();
-    __shared__ Wide alpha_s[32 * EPC];
-    if (ty == 0) {
+    if (ty == 0 && !by_element) {
         Wide* out = reinterpret_cast<Wide*>(p.alpha_out);
 #pragma unroll
         for (int e = 0; e < EPC; ++e) {

@@ -262,24 +262,28 @@ struct Cfg {
 __device__ __forceinline__ i32x4 ld16(const char* p) { return *reinterpret_cast<const i32x4*>(p); }
 
 // 16 bytes gathered element by element: element e of the chunk is at base + e*stride
-// (bytes) and is taken only while e < n_valid.
+// (bytes) and is taken only while e < n_valid.  Every load reads an element of the run (the
+// index is clamped to the last valid one, the value dropped afterwards), so that the loads
+// carry no condition and go out together instead of one round trip after the other.
 template <int ESIZE>
 __device__ __forceinline__ i32x4 gather16(const char* base, long long stride_bytes, int n_valid) {
     i32x4 out = {0, 0, 0, 0};
+    if (n_valid <= 0) return out;
+    const int last = n_valid - 1;
     if constexpr (ESIZE == 2) {
+        unsigned v[8];
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            unsigned v = 0;
-            if (e < n_valid) v = *reinterpret_cast<const unsigned short*>(base + e * stride_bytes);
-            out[e >> 1] |= (int)(v << (16 * (e & 1)));
-        }
+        for (int e = 0; e < 8; ++e)
+            v[e] = *reinterpret_cast<const unsigned short*>(base + (e < last ? e : last) * stride_bytes);
+#pragma unroll
+        for (int e = 0; e < 8; ++e) out[e >> 1] |= (int)((e <= last ? v[e] : 0u) << (16 * (e & 1)));
     } else {
+        unsigned v[16];
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            unsigned v = 0;
-            if (e < n_valid) v = *reinterpret_cast<const unsigned char*>(base + e * stride_bytes);
-            out[e >> 2] |= (int)(v << (8 * (e & 3)));
-        }
+        for (int e = 0; e < 16; ++e)
+            v[e] = *reinterpret_cast<const unsigned char*>(base + (e < last ? e : last) * stride_bytes);
+#pragma unroll
+        for (int e = 0; e < 16; ++e) out[e >> 2] |= (int)((e <= last ? v[e] : 0u) << (8 * (e & 3)));
     }
     return out;
 }

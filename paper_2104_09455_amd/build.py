@@ -21,6 +21,7 @@ HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
          # keep the compiler from emitting packed-fp32 VALU forms
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
+FLAGS += os.environ.get("ABFT_EXTRA_HIPCC_FLAGS", "").split()   # e.g. -D switches of tuning experiments
 SOURCES = ["gemm_f16.hip", "gemm_bf16.hip", "gemm_i8.hip", "abft_api.hip"]
 
 

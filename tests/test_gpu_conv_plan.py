@@ -295,3 +295,58 @@ def test_mlp_chain_with_fused_relu(ci, modes, dtype):
             B.abft_plan_set_activation(plan, 0, 7)
     finally:
         B.abft_plan_destroy(plan)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "i8"])
+@pytest.mark.parametrize("mode", [B.NONE, B.GLOBAL, B.THREAD, B.REPLICA])
+def test_relu_on_single_layers_of_every_kind(mode, dtype):
+    """ReLU fused into the store for a fully-connected layer (int8 included: int32 outputs), a 3x3
+    convolution, a few-channel first layer (lowered to row segments inside the plan) and a ragged
+    layer on the generic kernel: the stored value is max(x, 0) of what the layer stores without
+    the activation, bit for bit, and clean inputs raise no flag (the checks see the product)."""
+    import torch
+    from gpu_util import to_dev, DEV
+    dt = DT[dtype]
+    c_t = torch.int32 if dtype == "i8" else torch.float16
+    cases = [("fc", (96, 160, 128), None), ("ragged", (70, 50, 37), None), ("conv", None, CONVS[0]),
+             ("first", None, wl.Conv(2, 30, 30, 3, 64, 7, 7, 2, 3))]
+    layers, keep, ins, shapes, refs = [], [], [], [], []
+    for name, mnk, c in cases:
+        if c is None:
+            M, N, K = mnk
+            A, Wm = wl.gemm_operands(M, N, K, dtype, seed=400 + M)
+            conv, has = B.Conv(), 0
+            ins.append(to_dev(A, dtype))
+        else:
+            x, Wm = wl.conv_operands(c, dtype, seed=410 + c.Cin)
+            M, N, K = c.batch * c.OH * c.OW, c.Cout, c.KH * c.KW * c.Cin
+            conv, has = B.Conv(c.batch, c.H, c.W, c.Cin, c.KH, c.KW, c.stride, c.pad), 1
+            ins.append(to_dev(x, dtype))
+            A = oracle.im2col(x, dtype, c.KH, c.KW, c.stride, c.pad)
+        refs.append(oracle.activation(oracle.gemm(A, Wm, dtype), "relu"))
+        dB = to_dev(np.ascontiguousarray(Wm.T), dtype)
+        keep.append(dB)
+        layers.append(B.Layer(M, N, K, dt, B.B_NK, has, conv, dB.data_ptr(), K))
+        shapes.append((M, N, K))
+    plan = B.abft_plan_create(layers)
+    try:
+        flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+        outs = {}
+        for act in (B.ACT_NONE, B.ACT_RELU):
+            Cs = [torch.zeros((M, N), dtype=c_t, device=DEV) for (M, N, K) in shapes]
+            for l in range(len(layers)):
+                B.abft_plan_set_mode(plan, l, mode)
+                B.abft_plan_set_activation(plan, l, act)
+            io = B.PlanIO(ins, [s[2] for s in shapes], Cs, [s[1] for s in shapes])
+            print(f"case relu layers mode={mode} dtype={dtype} act={act}", flush=True)
+            B.abft_plan_run_all(plan, io, flag)
+            torch.cuda.synchronize()
+            outs[act] = Cs
+        assert int(flag.item()) == 0
+        from gpu_util import c_to_host, c_close
+        for plain, relu, ref, (name, _, _) in zip(outs[B.ACT_NONE], outs[B.ACT_RELU], refs, cases):
+            assert bool((plain < 0).any()), name                      # the case exercises the clamp
+            assert c_close(c_to_host(relu, dtype), ref, dtype), name  # against the oracle's max(A.B, 0)
+            assert torch.equal(relu, torch.clamp(plain, min=0)), name
+    finally:
+        B.abft_plan_destroy(plan)

@@ -552,6 +552,27 @@ def main():
         B.abft_plan_run_all(plan, io, flag, -1, stream)
     torch.cuda.synchronize()
     wall_none = time.perf_counter() - t0
+    # the analytic selector with thread-level replication (Sec. 5.1) standing in for one-sided
+    # thread-level ABFT on the layers it assigns to the thread level: same granularity of checks,
+    # the cheaper of the two on this hardware
+    repl = None
+    try:
+        for i, lr in enumerate(runs):
+            B.abft_plan_set_mode(plan, i, B.REPLICA if lr.pick == B.THREAD else lr.pick)
+        for _ in range(warmup):
+            B.abft_plan_run_all(plan, io, flag, -1, stream)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            B.abft_plan_run_all(plan, io, flag, -1, stream)
+        torch.cuda.synchronize()
+        wall_r = time.perf_counter() - t0
+        repl = {"value": round(total_flops / (wall_r / steps) / 1e12, 3), "unit": "TFLOP/s",
+                "ms_per_step": round(1000.0 * wall_r / steps, 5),
+                "overhead_pct_whole_pass": round(100 * (wall_r / wall_none - 1), 2),
+                "false_alarms": int(flag.item())}
+    except Exception as e:  # reported, never fatal
+        repl = {"error": repr(e)}
     for i in range(len(runs)):
         B.abft_plan_set_mode(plan, i, B.AUTO)
     B.abft_plan_destroy(plan)
@@ -596,6 +617,7 @@ def main():
         "overhead_pct_summed_layers": summarize(rows)["ovh_selector_pct"],
         "false_alarms": flagged,
         "profiled_selector": prof,
+        "analytic_selector_with_replication_at_thread_level": repl,
         "graph_replay": None if not isinstance(graph_ms, float) else {
             "ms_per_step": round(graph_ms, 5), "tflops": round(total_flops / (graph_ms * 1e-3) / 1e12, 3),
             "unprotected_ms_per_step": None if graph_none_ms is None else round(graph_none_ms, 5)},

@@ -83,17 +83,21 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         const long long nkt_all = ((long long)K * esize(dt)) / 128;
         if (N > 128 && nkt_all > 1 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         const bool fills128 = tiles(CFG_F128) >= 128;
+        const bool wave_level_wide = mode == ABFT_THREAD;
         if (fills128 && N <= 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
-        // Fewer tiles than fill the chip twice at 64 x 64: the time is the latency of a workgroup's
-        // k loop and the rate at which one compute unit can stream its operands, so the streaming
-        // configurations take over (no barriers in the k loop): 64 x 64 tiles, or 32-row tiles
-        // for a handful of tiles.  The thread-level scheme takes the 32 x 64 tile there (its
-        // checksum then needs no cross-lane step).
+        // Few tiles: the time is the latency of a workgroup's k loop and the rate at which one
+        // compute unit can stream its operands, so the streaming configurations take over (no
+        // barriers in the k loop, four wavefronts sharing the k tiles): the smallest tile that
+        // still fits the chip in one round of workgroups, 64 x 64 for up to two rounds (that one
+        // only with a k loop of at least one tile per wavefront: beyond one round the idle
+        // wavefronts of a short loop cost more than the barriers they save).  The thread-level scheme never takes the
+        // 32 x 32 tile when it can have 32 x 64 (its checksum then needs no cross-lane step).
+        if (tiles(CFG_S32) <= 256) return (wave_level_wide && N > 32) ? CFG_S64 : CFG_S32;
+        if (tiles(CFG_S64) <= 256) return CFG_S64;
+        if (nkt_all >= 4 && tiles(CFG_S128) <= 512) return CFG_S128;
         const long long t64 = tiles(CFG_F64T);
-        if (t64 <= 64) return (mode == ABFT_THREAD && N > 32) ? CFG_S64 : CFG_S32;
-        if (tiles(CFG_S128) <= 512) return CFG_S128;
         if (fills128) return (mode == ABFT_THREAD || nkt_all <= 1) ? CFG_F128T : CFG_F128;
-        if (t64 > 256 || mode == ABFT_GLOBAL) return CFG_F64T;
+        if (t64 > 256 || mode == ABFT_GLOBAL || nkt_all < 4) return CFG_F64T;
         return CFG_F64K;
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;

@@ -319,11 +319,11 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         if (p.f_kt < 0 && wave == (nkt - 1) % KW) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, 0));
     }
 
-    // ---- each wavefront checks its own partial tile, then the partial tiles are added in
-    // wavefront order; wavefront w adds and stores accumulator registers 4w .. 4w+3 of every
-    // MFMA block (rows 8w + 4 (lane / 32) + 0..3 of the block)
+    // ---- the partial tiles are added in wavefront order; wavefront w adds and stores accumulator
+    // registers 4w .. 4w+3 of every MFMA block (rows 8w + 4 (lane / 32) + 0..3 of the block).
+    // Under the wavefront-level schemes each wavefront then checks its own partial tile, from its
+    // registers, while the stores drain: the check's arithmetic is off the critical path.
     static_assert(MODE != MODE_GLOBAL_PRE, "streaming configurations form the checksum dot product themselves");
-    if constexpr (mode_is_wave_level(MODE)) epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
     __syncthreads();  // the sum reuses every wavefront's stages
     AccT* red = reinterpret_cast<AccT*>(smem);
     constexpr int NV = TM * TN * 16;
@@ -394,6 +394,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 }
             }
         }
+    if constexpr (mode_is_wave_level(MODE)) epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
     if constexpr (GDOT) {
         // comparison (Sec. 2.4 step 4) for this tile
         if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;

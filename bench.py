@@ -162,7 +162,11 @@ ALL_ROWS = []   # every per-layer measurement of this run, for the selector stud
 def layer_table(hip, runs, reps, warm, stream, modes=(B.NONE, B.GLOBAL, B.THREAD)):
     rows = []
     for lr in runs:
-        t = {m: time_mode(hip, lr, m, reps, warm, stream) for m in modes}
+        # enough calls per graph replay that the replay's own launch cost (some 10 us) disappears
+        # in the per-call figure: about 1.5 ms of estimated device work, at most 100 calls
+        est_us = max(lr.flops / PEAK[lr.dtype], lr.bytes / HBM) * 1e6 * 2 + 3.0
+        n_calls = max(reps, min(100, int(1500.0 / est_us) + 1))
+        t = {m: time_mode(hip, lr, m, n_calls, warm, stream) for m in modes}
         pick_t = t[lr.pick]
         roof = min(PEAK[lr.dtype], lr.ai * HBM)
         rows.append({

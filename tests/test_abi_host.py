@@ -125,3 +125,37 @@ def test_argument_validation_without_a_gpu(lib):
     assert e.value.code == -8
     bad = B.Conv(1, 2, 2, 8, 3, 3, 1, 0)  # 3x3 filter on a 2x2 image without padding
     assert lib.abft_conv(ctypes.byref(bad), 4, p, p, 72, 0, p, 4, 0, 0, None, None, 0, p, None, None, None) == -2
+
+
+def test_replication_mode_shares_the_thread_level_geometry(lib):
+    """ABFT_REPLICA is checked per wavefront tile like ABFT_THREAD: same workspace, k partition
+    and tolerance coefficient for every shape class the dispatcher knows."""
+    for (M, N, K) in [(64, 64, 64), (256, 1024, 1024), (200, 136, 256), (1536, 1536, 128), (8192, 8192, 8192),
+                      (1, 1024, 1021), (64, 1024, 4096)]:
+        for dt in (B.F16, B.BF16, B.I8):
+            al = (K * (1 if dt == B.I8 else 2)) % 16 == 0
+            assert B.abft_workspace_bytes(M, N, K, dt, B.REPLICA) == B.abft_workspace_bytes(M, N, K, dt, B.THREAD)
+            assert B.abft_k_ways(M, N, K, dt, B.REPLICA, al) == B.abft_k_ways(M, N, K, dt, B.THREAD, al)
+            assert B.abft_k_slices(M, N, K, dt, B.REPLICA, al) == B.abft_k_slices(M, N, K, dt, B.THREAD, al)
+            assert B.abft_tolerance_coeff(K, dt, B.REPLICA) == B.abft_tolerance_coeff(K, dt, B.THREAD)
+            assert B.abft_tolerance_bias_coeff(K, dt, B.REPLICA) == 0.0
+    assert B.MODE_NAMES[B.REPLICA] == "replica"
+
+
+def test_tile_choice_for_few_tiles(lib):
+    """Documented choices of the dispatcher for latency-bound products (region = workgroup tile of
+    the global scheme, tile = wavefront tile of the thread-level scheme)."""
+    # one round of 32 x 32 streaming tiles; the thread-level scheme takes 32 x 64
+    assert B.abft_region_shape(256, 1024, 1024, B.F16) == (32, 32)
+    assert B.abft_tile_shape(256, 1024, 1024, B.F16)[:2] == (32, 64)
+    # more than 256 of those: 32 x 64 for everyone
+    assert B.abft_region_shape(128, 4096, 4096, B.F16) == (32, 64)
+    # more than 256 of those too: 64 x 64 streaming tiles, but only with a k loop of four tiles or more
+    assert B.abft_region_shape(512, 4096, 4096, B.F16) == (64, 64)
+    assert B.abft_region_shape(3136, 512, 128, B.F16) == (64, 128)
+    # the chip is full: 128 x 128, then 256 x 256
+    assert B.abft_region_shape(12544, 512, 1024, B.F16) == (128, 128)
+    assert B.abft_region_shape(8192, 8192, 8192, B.F16) == (256, 256)
+    # streaming tiles split k over four wavefronts
+    assert B.abft_k_ways(256, 1024, 1024, B.F16, B.THREAD)[0] == 4
+    assert B.abft_k_ways(8192, 8192, 8192, B.F16, B.THREAD)[0] == 1

@@ -95,10 +95,9 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         if (tiles(CFG_S32) <= 256) return (wave_level_wide && N > 32) ? CFG_S64 : CFG_S32;
         if (tiles(CFG_S64) <= 256) return CFG_S64;
         if (nkt_all >= 4 && tiles(CFG_S128) <= 512) return CFG_S128;
-        const long long t64 = tiles(CFG_F64T);
         if (fills128) return (mode == ABFT_THREAD || nkt_all <= 1) ? CFG_F128T : CFG_F128;
-        if (t64 > 256 || mode == ABFT_GLOBAL || nkt_all < 4) return CFG_F64T;
-        return CFG_F64K;
+        // (CFG_F64K, CFG_F64S and CFG_F256 are reached through ABFT_FORCE_CFG only)
+        return CFG_F64T;
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;
     if (tiles(CFG_G64) >= 1024) return CFG_G128;

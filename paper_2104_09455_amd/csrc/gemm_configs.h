@@ -11,7 +11,8 @@ namespace abft {
 //    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       thread-level (wide tiles: two checksum
 //                                                                    MFMAs per four), narrow outputs, K of one k tile
 //    F64T    64 x 128, wavefronts 2 x 1 of  32 x 128, 3 stages       between the streaming tiles and F128
-//    F64K    same tile, 6 stages, 4 wavefronts per register tile     (each takes one k step in four)
+//    F64K    same tile, 6 stages, 4 wavefronts per register tile     (each takes one k step in four); its range is now
+//                                                                    covered by the streaming tiles: environment switch only
 //    F256   256 x 256, wavefronts 2 x 2 of 128 x 128, 2 stages       kept for comparison, not selected
 //    F64S    64 x 128, 6 stages, may be split along k across workgroups   kept, selected only by environment switch
 //  S* run the streaming kernel (same operand requirements; four wavefronts split the k tiles of one

@@ -81,7 +81,11 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
         // (a single k tile: the 128 x 128 tile, of which several fit a compute unit at once)
         const long long nkt_all = ((long long)K * esize(dt)) / 128;
-        if (N > 128 && nkt_all > 1 && tiles(CFG_F256) >= 224) return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
+        // (three quarters of the chip filled are enough once the k loop is eight tiles long: measured
+        // on 50176 x 256 x 512 and 12544 x 1024 x 512, 196 tiles each)
+        const long long t256 = tiles(CFG_F256);
+        if (N > 128 && nkt_all > 1 && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
+            return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         const bool fills128 = tiles(CFG_F128) >= 128;
         const bool wave_level_wide = mode == ABFT_THREAD;
         if (fills128 && N <= 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns

@@ -81,24 +81,28 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
         // (a single k tile: the 128 x 128 tile, of which several fit a compute unit at once)
         const long long nkt_all = ((long long)K * esize(dt)) / 128;
-        // (three quarters of the chip filled are enough once the k loop is eight tiles long: measured
-        // on 50176 x 256 x 512 and 12544 x 1024 x 512, 196 tiles each)
+        // The 256 x 256 tile runs one workgroup per compute unit, in rounds of 256: it is taken when
+        // the rounds are at least 70 % full (288 tiles would leave the second round of 6000 x 3072 x
+        // 768 almost empty: 58 us against 48 us on 128 x 128 tiles), from 192 tiles on when the k loop
+        // is eight tiles long or more (50176 x 256 x 512, 12544 x 1024 x 512: 196 tiles each), else from 224.
         const long long t256 = tiles(CFG_F256);
-        if (N > 128 && nkt_all > 1 && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
+        const bool rounds_full = t256 * 10 >= cdiv(t256, 256) * 256 * 7;
+        if (N > 128 && nkt_all > 1 && rounds_full && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
             return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         const bool fills128 = tiles(CFG_F128) >= 128;
         const bool wave_level_wide = mode == ABFT_THREAD;
-        if (fills128 && N <= 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
+        if (fills128 && N < 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
         // Few tiles: the time is the latency of a workgroup's k loop and the rate at which one
         // compute unit can stream its operands, so the streaming configurations take over (no
         // barriers in the k loop, four wavefronts sharing the k tiles): the smallest tile that
         // still fits the chip in one round of workgroups, 64 x 64 for up to two rounds (that one
-        // only with a k loop of at least one tile per wavefront: beyond one round the idle
-        // wavefronts of a short loop cost more than the barriers they save).  The thread-level scheme never takes the
+        // only with a k loop of at least one tile per wavefront, sixteen tiles (thread-level: eight) for a second round:
+        // the idle wavefronts of a short loop cost more than the barriers they save; 3000 x 384 x
+        // 384 takes 9.9 us on 282 such tiles, 8.2 us on 64 x 128 tiles).  The thread-level scheme never takes the
         // 32 x 32 tile when it can have 32 x 64 (its checksum then needs no cross-lane step).
         if (tiles(CFG_S32) <= 256) return (wave_level_wide && N > 32) ? CFG_S64 : CFG_S32;
         if (tiles(CFG_S64) <= 256) return CFG_S64;
-        if (nkt_all >= 4 && tiles(CFG_S128) <= 512) return CFG_S128;
+        if (tiles(CFG_S128) <= 256 ? nkt_all >= 4 : (tiles(CFG_S128) <= 512 && nkt_all >= (mode == ABFT_THREAD ? 8 : 16))) return CFG_S128;
         if (fills128) return (mode == ABFT_THREAD || nkt_all <= 1) ? CFG_F128T : CFG_F128;
         // (CFG_F64K, CFG_F64S and CFG_F256 are reached through ABFT_FORCE_CFG only)
         return CFG_F64T;

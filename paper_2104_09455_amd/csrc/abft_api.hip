@@ -103,7 +103,10 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         if (tiles(CFG_S32) <= 256) return (wave_level_wide && N > 32) ? CFG_S64 : CFG_S32;
         if (tiles(CFG_S64) <= 256) return CFG_S64;
         if (tiles(CFG_S128) <= 256 ? nkt_all >= 4 : (tiles(CFG_S128) <= 512 && nkt_all >= (mode == ABFT_THREAD ? 8 : 16))) return CFG_S128;
-        if (fills128) return (mode == ABFT_THREAD || nkt_all <= 1) ? CFG_F128T : CFG_F128;
+        // (thread-level: the wide wavefront tiles pay off once two workgroups share a compute unit;
+        // with at most one per unit the 64 x 64 wavefront tiles' cheaper checksum wins: 1536 x 2048 x
+        // 2048 takes 37 us against 42 us, 640 x 5120 x 1280 26 us against 30 us)
+        if (fills128) return (nkt_all <= 1 || (mode == ABFT_THREAD && tiles(CFG_F128) > 256)) ? CFG_F128T : CFG_F128;
         // (CFG_F64K, CFG_F64S and CFG_F256 are reached through ABFT_FORCE_CFG only)
         return CFG_F64T;
     }

@@ -72,8 +72,8 @@ def test_clean_parity(shape, mode, dtype):
 CONFIG_SHAPES = [
     ((520, 1040, 512), (64, 64), (64, 64)),        # 64 x 64 streaming tile, ragged edges
     ((520, 1040, 128), (32, 128), (64, 128)),      # the same grid with a short k loop: 64 x 128 direct-to-LDS tile
-    ((1536, 1536, 128), (32, 128), (128, 128)),    # 128 x 128 tile (wide wavefront tiles for thread-level)
-    ((1536, 1536, 256), (32, 128), (128, 128)),    # the same with a k loop: 2 x 2 wavefronts of 64 x 64 unless thread-level
+    ((2304, 2304, 256), (32, 128), (128, 128)),    # 128 x 128 tile, more than one workgroup per compute unit: wide wavefront tiles for thread-level
+    ((1536, 1536, 256), (64, 64), (128, 128)),     # at most one per compute unit: 2 x 2 wavefronts of 64 x 64 for every scheme
     ((16500, 64, 256), (32, 128), (128, 128)),     # narrow output: 128 x 128 tile of full-width wavefronts
     ((300, 520, 1024), (32, 64), (32, 32)),        # one round of 32 x 32 streaming tiles
     ((256, 1100, 512), (32, 64), (32, 64)),        # more than one round of those: 32 x 64 streaming tiles

@@ -70,7 +70,10 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     }();
     // the direct-to-LDS kernel needs whole k tiles of 128 bytes
     const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
-    if (force >= 0 && force < CFG_COUNT && (fast_ok || !cfg_info_host(force).fast)) return force;
+    // (the direct-to-LDS kernel's k-ways variant has no global scheme: a pin on it is not honoured there)
+    const bool force_fits = force >= 0 && force < CFG_COUNT && (fast_ok || !cfg_info_host(force).fast) &&
+                            !(force == CFG_F64K && mode == ABFT_GLOBAL);
+    if (force_fits) return force;
     if (M <= 16 && !fast_ok) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);

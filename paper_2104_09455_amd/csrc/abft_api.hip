@@ -68,33 +68,35 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         const char* e = std::getenv("ABFT_FORCE_CFG");
         return e ? std::atoi(e) : -1;
     }();
-    // the direct-to-LDS kernel needs whole k tiles of 128 bytes
+    // the direct-to-LDS kernel needs whole k tiles of 128 bytes; the streaming kernel takes any whole
+    // number of 16-byte chunks (a short last tile is filled up with zeros)
     const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
     // (the direct-to-LDS kernel's k-ways variant has no global scheme: a pin on it is not honoured there)
-    const bool force_fits = force >= 0 && force < CFG_COUNT && (fast_ok || !cfg_info_host(force).fast) &&
+    const bool force_fits = force >= 0 && force < CFG_COUNT &&
+                            (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force))) &&
                             !(force == CFG_F64K && mode == ABFT_GLOBAL);
     if (force_fits) return force;
-    if (M <= 16 && !fast_ok) return CFG_G16;
+    if (M <= 16 && !aligned16) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);
         return cdiv(M, ci.bm) * cdiv(N, ci.bn);
     };
-    if (fast_ok) {
+    if (aligned16) {
         // fill the 256 compute units before growing the tile
         // (thread-level: the 128 x 128 tile of wide wavefront tiles; the 256 x 256 one would spill)
         // (a single k tile: the 128 x 128 tile, of which several fit a compute unit at once)
-        const long long nkt_all = ((long long)K * esize(dt)) / 128;
+        const long long nkt_all = cdiv((long long)K * esize(dt), 128);
         // The 256 x 256 tile runs one workgroup per compute unit, in rounds of 256: it is taken when
         // the rounds are at least 70 % full (288 tiles would leave the second round of 6000 x 3072 x
         // 768 almost empty: 58 us against 48 us on 128 x 128 tiles), from 192 tiles on when the k loop
         // is eight tiles long or more (50176 x 256 x 512, 12544 x 1024 x 512: 196 tiles each), else from 224.
         const long long t256 = tiles(CFG_F256);
         const bool rounds_full = t256 * 10 >= cdiv(t256, 256) * 256 * 7;
-        if (N > 128 && nkt_all > 1 && rounds_full && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
+        if (fast_ok && N > 128 && nkt_all > 1 && rounds_full && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
             return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         const bool fills128 = tiles(CFG_F128) >= 128;
         const bool wave_level_wide = mode == ABFT_THREAD;
-        if (fills128 && N < 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
+        if (fast_ok && fills128 && N < 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
         // Few tiles: the time is the latency of a workgroup's k loop and the rate at which one
         // compute unit can stream its operands, so the streaming configurations take over (no
         // barriers in the k loop, four wavefronts sharing the k tiles): the smallest tile that
@@ -106,12 +108,14 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         if (tiles(CFG_S32) <= 256) return (wave_level_wide && N > 32) ? CFG_S64 : CFG_S32;
         if (tiles(CFG_S64) <= 256) return CFG_S64;
         if (tiles(CFG_S128) <= 256 ? nkt_all >= 4 : (tiles(CFG_S128) <= 512 && nkt_all >= (mode == ABFT_THREAD ? 8 : 16))) return CFG_S128;
-        // (thread-level: the wide wavefront tiles pay off once two workgroups share a compute unit;
-        // with at most one per unit the 64 x 64 wavefront tiles' cheaper checksum wins: 1536 x 2048 x
-        // 2048 takes 37 us against 42 us, 640 x 5120 x 1280 26 us against 30 us)
-        if (fills128) return (nkt_all <= 1 || (mode == ABFT_THREAD && tiles(CFG_F128) > 256)) ? CFG_F128T : CFG_F128;
-        // (CFG_F64K, CFG_F64S and CFG_F256 are reached through ABFT_FORCE_CFG only)
-        return CFG_F64T;
+        if (fast_ok) {
+            // (thread-level: the wide wavefront tiles pay off once two workgroups share a compute unit;
+            // with at most one per unit the 64 x 64 wavefront tiles' cheaper checksum wins: 1536 x 2048 x
+            // 2048 takes 37 us against 42 us, 640 x 5120 x 1280 26 us against 30 us)
+            if (fills128) return (nkt_all <= 1 || (mode == ABFT_THREAD && tiles(CFG_F128) > 256)) ? CFG_F128T : CFG_F128;
+            // (CFG_F64K, CFG_F64S and CFG_F256 are reached through ABFT_FORCE_CFG only)
+            return CFG_F64T;
+        }
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;
     if (tiles(CFG_G64) >= 1024) return CFG_G128;

@@ -5,7 +5,7 @@
 namespace abft {
 
 // Index into the configuration table.
-//  F* run the direct-to-LDS kernel (16-byte aligned operands, K a multiple of 128 bytes):
+//  F* run the direct-to-LDS kernel (16-byte aligned operands and leading dimensions, K a multiple of 128 bytes):
 //    F256W  256 x 256, wavefronts 2 x 4 of 128 x  64 (two per SIMD), 2 LDS stages   compute-bound products
 //    F128   128 x 128, wavefronts 2 x 2 of  64 x  64, 2 stages       mid-size, unprotected / global
 //    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       thread-level (wide tiles: two checksum
@@ -15,7 +15,7 @@ namespace abft {
 //                                                                    covered by the streaming tiles: environment switch only
 //    F256   256 x 256, wavefronts 2 x 2 of 128 x 128, 2 stages       kept for comparison, not selected
 //    F64S    64 x 128, 6 stages, may be split along k across workgroups   kept, selected only by environment switch
-//  S* run the streaming kernel (same operand requirements; four wavefronts split the k tiles of one
+//  S* run the streaming kernel (same alignment, K any multiple of 16 bytes; four wavefronts split the k tiles of one
 //  register tile between them, each with its own LDS stages, no barrier in the k loop):
 //    S32     32 x  32, 4 stages per wavefront                         a few tiles only: latency-bound layers
 //    S64     32 x  64, 3 stages per wavefront

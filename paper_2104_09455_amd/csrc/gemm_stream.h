@@ -11,7 +11,9 @@
 // product) and then added through LDS in wavefront order, every wavefront adding and storing
 // a quarter of the tile.
 //
-// Same operand requirements and LDS row swizzle as the direct-to-LDS kernel.
+// Same alignment requirements and LDS row swizzle as the direct-to-LDS kernel, but K may be any
+// whole number of 16-byte chunks: the wavefront that owns a short last k tile copies zeros in
+// place of the chunks (and weight checksums) beyond K.
 #pragma once
 #include "gemm_fast.h"
 
@@ -57,8 +59,14 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     tile_of_block((int)blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int bm0 = tile_m * BM, bn0 = tile_n * BN;
     const int M = p.M, N = p.N;
-    const int nkt = p.K / BK;
+    // K is a whole number of 16-byte chunks; the last k tile may hold fewer than eight of them
+    const int nkt = (p.K + BK - 1) / BK;
     const int n_own = nkt > wave ? (nkt - wave + KW - 1) / KW : 0;  // k tiles wave, wave + 4, ...
+    const int rem_chunks = ((p.K * ESIZE) & 127) >> 4;              // chunks of a short last tile, 0: it is whole
+    // the wavefront that owns the short tile (as the last of its own) copies zeros in place of the
+    // chunks, and weight checksums, beyond K
+    const bool owns_short = rem_chunks != 0 && wave == (nkt - 1) % KW;
+    int issued = 0;  // own tiles whose copies have gone out
     char* const wbase = smem + wave * (NST * WSTAGE);
 
     // ---- global -> LDS copy: lane fills slot `lane` of a 1 KB block (8 rows x 8 chunks): row
@@ -113,6 +121,9 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         else beta_ptr = p.beta_k + (blk + (long long)wave * BK + lane) * 4;
     }
     constexpr int BETA_ADV = KW * (MDOT ? 128 : BK * 4);
+    // first k offset (within a k tile) of the four bytes this lane copies: one float, two halves of a
+    // plane, or four digits of a plane
+    const int beta_k0 = IS_INT ? (lane & 31) * 4 : (MDOT ? (lane & 31) * 2 : lane);
     if constexpr (CONV) {
 #pragma unroll
         for (int h = 0; h < 2; ++h) {
@@ -127,6 +138,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     auto issue_loads = [&](int stage) {
         char* abase = wbase + stage * WSTAGE;
         char* bbase = abase + A_STAGE;
+        const bool short_tile = owns_short && issued == n_own - 1;
+        ++issued;
+        // (chunk columns of this lane that lie beyond K in the short tile)
+        const bool cut[2] = {short_tile && ckc[0] >= rem_chunks, short_tile && ckc[1] >= rem_chunks};
 #pragma unroll
         for (int q = 0; q < NQA; ++q) {
             const char* src = aptr[q];
@@ -137,16 +152,22 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 src = ok ? p.A + (a_img[q] + (long long)ih * p.rowpitch + (long long)iw * p.pix + tap_c[q & 1]) * ESIZE
                          : g_zero_chunk + ckc[q & 1] * 16;
             }
+            if (cut[q & 1]) src = g_zero_chunk + ckc[q & 1] * 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(abase + q * 1024), 16, 0, 0);
         }
 #pragma unroll
-        for (int q = 0; q < NQB; ++q)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
+        for (int q = 0; q < NQB; ++q) {
+            const char* src = cut[q & 1] ? g_zero_chunk + ckc[q & 1] * 16 : bptr[q];
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(bbase + q * 1024), 16, 0, 0);
-        if constexpr (GDOT)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)beta_ptr,
+        }
+        if constexpr (GDOT) {
+            // this lane's four bytes of weight checksums cover k offsets beta_k0 .. of the tile
+            const char* src = (short_tile && beta_k0 >= rem_chunks * (16 / ESIZE)) ? g_zero_chunk : beta_ptr;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(abase + LAY::AB_STAGE), 4, 0, 0);
+        }
     };
     // to this wavefront's next k tile: KW tiles further along k
     auto advance = [&]() {

@@ -12,8 +12,9 @@ pytestmark = pytest.mark.gpu
 MODES = [B.NONE, B.GLOBAL, B.THREAD, B.REPLICA]
 WAVE_LEVEL = (B.THREAD, B.REPLICA)   # one comparison per wavefront tile
 # (M, N, K): one tile; several tiles with ragged edges; skinny; degenerate; unaligned K
+# (K a whole number of 16-byte chunks but not of 128-byte k tiles: the streaming kernel's short last tile)
 SHAPES = [(64, 64, 64), (200, 136, 264), (130, 70, 333), (1, 64, 13), (16, 1, 256), (1, 1, 1),
-          (300, 520, 1024), (17, 260, 72), (512, 512, 128)]
+          (300, 520, 1024), (17, 260, 72), (512, 512, 128), (32, 32, 32), (96, 160, 48), (300, 520, 1040)]
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
@@ -174,7 +175,7 @@ def test_checksum_vectors(dtype):
 
 
 @pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD, B.REPLICA])
-@pytest.mark.parametrize("shape", [(64, 64, 64), (200, 136, 256)])
+@pytest.mark.parametrize("shape", [(64, 64, 64), (200, 136, 256), (96, 72, 304)])
 def test_int8_injected_faults_always_flagged(shape, mode):
     """Every single-bit flip of an int32 accumulator changes the sum exactly: 100 % detection."""
     from gpu_util import run_gemm

@@ -68,9 +68,9 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         const char* e = std::getenv("ABFT_FORCE_CFG");
         return e ? std::atoi(e) : -1;
     }();
-    // the direct-to-LDS kernel needs whole k tiles of 128 bytes; the streaming kernel takes any whole
-    // number of 16-byte chunks (a short last tile is filled up with zeros)
-    const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
+    // the direct-to-LDS and streaming kernels take any whole number of 16-byte chunks along k (a
+    // short last k tile is filled up with zeros)
+    const bool fast_ok = aligned16;
     // (the direct-to-LDS kernel's k-ways variant has no global scheme: a pin on it is not honoured there)
     const bool force_fits = force >= 0 && force < CFG_COUNT &&
                             (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force))) &&
@@ -133,7 +133,7 @@ int pick_ksplit(int M, int N, int K, int dt, int cfg, int mode) {
     const CfgInfo ci = cfg_info_host(cfg);
     if (cfg != CFG_F64S || mode == ABFT_GLOBAL) return 1;
     const long long tiles = cdiv(M, ci.bm) * cdiv(N, ci.bn);
-    const long long nkt = ((long long)K * esize(dt)) / ci.bk_bytes;
+    const long long nkt = cdiv((long long)K * esize(dt), ci.bk_bytes);
     long long ks = 256 / tiles;
     // adding the partial tiles costs about as much as several k tiles: keep at least 16 per slice
     if (ks > nkt / 16) ks = nkt / 16;
@@ -975,7 +975,7 @@ int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int* n_
     if (bounds) {
         if (max_bounds < ks + 1) return ABFT_E_SHAPE;
         const int bk = cfg_info_host(cfg).bk_bytes / esize(dtype);
-        const int nkt = ks > 1 ? K / bk : 1;
+        const int nkt = ks > 1 ? (int)cdiv(K, bk) : 1;
         const int base = nkt / ks, rem = nkt % ks;
         int t = 0;
         for (int s = 0; s < ks; ++s) {

@@ -68,9 +68,9 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         const char* e = std::getenv("ABFT_FORCE_CFG");
         return e ? std::atoi(e) : -1;
     }();
-    // the direct-to-LDS and streaming kernels take any whole number of 16-byte chunks along k (a
-    // short last k tile is filled up with zeros)
-    const bool fast_ok = aligned16;
+    // the direct-to-LDS kernel needs whole k tiles of 128 bytes; the streaming kernel takes any whole
+    // number of 16-byte chunks (a variant of it fills a short last tile up with zeros)
+    const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
     // (the direct-to-LDS kernel's k-ways variant has no global scheme: a pin on it is not honoured there)
     const bool force_fits = force >= 0 && force < CFG_COUNT &&
                             (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force))) &&

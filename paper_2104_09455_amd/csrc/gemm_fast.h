@@ -12,9 +12,9 @@
 // (no staging registers), NSTAGE LDS stages, rows of 128 bytes stored with an XOR
 // swizzle of the chunk position (key (row >> 1) & 7) so that ds_read_b128 fragment reads are free of bank
 // conflicts; out-of-range rows (and convolution padding taps) read from a small block
-// of zeros, so ragged edges need no special case; likewise the chunks of a short last k tile
-// beyond K.  Requirements checked by the dispatcher: 16-byte aligned operands with k contiguous,
-// leading dimensions and K multiples of 16 bytes.
+// of zeros, so ragged edges need no special case.  Requirements checked by the
+// dispatcher: 16-byte aligned operands with k contiguous, leading dimensions multiples
+// of 16 bytes, K a multiple of the k tile.
 #pragma once
 #include <type_traits>
 
@@ -102,11 +102,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     const int bm0 = tile_m * BM, bn0 = tile_n * BN;
     const int M = p.M, N = p.N;
     // this workgroup's range of k tiles: slices differ by at most one tile, longer ones first
-    // K is a whole number of 16-byte chunks; the last k tile may hold fewer than eight of them, and
-    // zeros are then copied in place of the chunks (and weight checksums) beyond K
-    const int nkt_all = (p.K + BK - 1) / BK;
-    const int rem_chunks = ((p.K * ESIZE) & 127) >> 4;  // chunks of a short last tile, 0: it is whole
-    int issued = 0;                                     // tiles of this workgroup whose copies have gone out
+    const int nkt_all = p.K / BK;
     const int kt_base = nkt_all / ksplit, kt_rem = nkt_all - kt_base * ksplit;
     const int kt_first = ks * kt_base + (ks < kt_rem ? ks : kt_rem);
     const int nkt = kt_base + (ks < kt_rem ? 1 : 0);
@@ -172,9 +168,6 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     auto issue_loads = [&](int stage) {
         char* abase = smem + stage * STAGE + wave * 1024;
         char* bbase = abase + A_STAGE;
-        const bool short_tile = rem_chunks != 0 && kt_first + issued == nkt_all - 1;
-        ++issued;
-        const bool cut = short_tile && ckc >= rem_chunks;  // this lane's chunk column lies beyond K
 #pragma unroll
         for (int q = 0; q < NQA; ++q) {
             const char* src = aptr[q];
@@ -184,24 +177,17 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
                 const bool ok = ((a_valid >> q) & 1u) && ih >= 0 && ih < p.H && iw >= 0 && iw < p.W;
                 src = ok ? p.A + (a_img[q] + (long long)ih * p.rowpitch + (long long)iw * p.pix + tap_c) * ESIZE : zero;
             }
-            if (cut) src = zero;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(abase + q * WAVES * 1024), 16, 0, 0);
         }
 #pragma unroll
-        for (int q = 0; q < NQB; ++q) {
-            const char* src = cut ? zero : bptr[q];
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+        for (int q = 0; q < NQB; ++q)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
                                              (__attribute__((address_space(3))) void*)(bbase + q * WAVES * 1024), 16, 0, 0);
-        }
-        if constexpr (GDOT) {
-            // (this lane's four bytes of weight checksums: one float, or four digits of a plane)
-            const int beta_k0 = IS_INT ? (lane & 31) * 4 : lane;
-            const char* src = (short_tile && beta_k0 >= rem_chunks * (16 / ESIZE)) ? g_zero_chunk : beta_ptr;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+        if constexpr (GDOT)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)beta_ptr,
                                              (__attribute__((address_space(3))) void*)(smem + stage * STAGE + LAY::AB_STAGE + wave * LAY::BETA_SLOT),
                                              4, 0, 0);
-        }
     };
     auto advance = [&]() {
         if constexpr (GDOT) beta_ptr += BETA_ADV;
@@ -382,9 +368,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     }
     if constexpr (INJ) {
         // a fault in the finished accumulator: with a split along k, that of the last part
-        // (several wavefronts per register tile: the one that multiplies the k step holding K - 1)
-        const int last_way = (KWAYS > 1 && rem_chunks != 0) ? (rem_chunks - 1) >> 1 : KWAYS - 1;
-        if (p.f_kt < 0 && ks == ksplit - 1 && wave_k == last_way)
+        if (p.f_kt < 0 && ks == ksplit - 1 && wave_k == KWAYS - 1)
             inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, wave_mn));
     }
     __syncthreads();  // the epilogue reuses LDS

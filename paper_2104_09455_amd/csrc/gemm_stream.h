@@ -32,7 +32,9 @@ struct StreamLayout {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 };
 
-template <class CFG, int NST, int MODE, bool INJ, bool CONV>
+// RAGGED: K is a whole number of 16-byte chunks but not of k tiles (an instance of its own, so that
+// products of whole k tiles pay nothing for the short last tile)
+template <class CFG, int NST, int MODE, bool INJ, bool CONV, bool RAGGED = false>
 __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     typedef StreamLayout<CFG, NST> LAY;
     constexpr int DT = CFG::DT;
@@ -62,10 +64,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     // K is a whole number of 16-byte chunks; the last k tile may hold fewer than eight of them
     const int nkt = (p.K + BK - 1) / BK;
     const int n_own = nkt > wave ? (nkt - wave + KW - 1) / KW : 0;  // k tiles wave, wave + 4, ...
-    const int rem_chunks = ((p.K * ESIZE) & 127) >> 4;              // chunks of a short last tile, 0: it is whole
+    const int rem_chunks = RAGGED ? ((p.K * ESIZE) & 127) >> 4 : 0;  // chunks of a short last tile, 0: it is whole
     // the wavefront that owns the short tile (as the last of its own) copies zeros in place of the
     // chunks, and weight checksums, beyond K
-    const bool owns_short = rem_chunks != 0 && wave == (nkt - 1) % KW;
+    const bool owns_short = RAGGED && rem_chunks != 0 && wave == (nkt - 1) % KW;
     int issued = 0;  // own tiles whose copies have gone out
     char* const wbase = smem + wave * (NST * WSTAGE);
 
@@ -135,13 +137,14 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         }
     }
 
-    auto issue_loads = [&](int stage) {
+    // SHORT: the tile is the short last one (a wavefront-uniform case of its own, so that whole
+    // tiles pay nothing for it)
+    auto issue_tile = [&](int stage, auto short_c) {
+        constexpr bool SHORT = decltype(short_c)::value;
         char* abase = wbase + stage * WSTAGE;
         char* bbase = abase + A_STAGE;
-        const bool short_tile = owns_short && issued == n_own - 1;
-        ++issued;
         // (chunk columns of this lane that lie beyond K in the short tile)
-        const bool cut[2] = {short_tile && ckc[0] >= rem_chunks, short_tile && ckc[1] >= rem_chunks};
+        const bool cut[2] = {SHORT && ckc[0] >= rem_chunks, SHORT && ckc[1] >= rem_chunks};
 #pragma unroll
         for (int q = 0; q < NQA; ++q) {
             const char* src = aptr[q];
@@ -164,10 +167,21 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         }
         if constexpr (GDOT) {
             // this lane's four bytes of weight checksums cover k offsets beta_k0 .. of the tile
-            const char* src = (short_tile && beta_k0 >= rem_chunks * (16 / ESIZE)) ? g_zero_chunk : beta_ptr;
+            const char* src = (SHORT && beta_k0 >= rem_chunks * (16 / ESIZE)) ? g_zero_chunk : beta_ptr;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(abase + LAY::AB_STAGE), 4, 0, 0);
         }
+    };
+    auto issue_loads = [&](int stage) {
+        if constexpr (RAGGED) {
+            const bool short_tile = owns_short && issued == n_own - 1;
+            ++issued;
+            if (short_tile) {
+                issue_tile(stage, std::true_type());
+                return;
+            }
+        }
+        issue_tile(stage, std::false_type());
     };
     // to this wavefront's next k tile: KW tiles further along k
     auto advance = [&]() {

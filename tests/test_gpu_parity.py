@@ -76,8 +76,6 @@ CONFIG_SHAPES = [
     ((2304, 2304, 256), (32, 128), (128, 128)),    # 128 x 128 tile, more than one workgroup per compute unit: wide wavefront tiles for thread-level
     ((1536, 1536, 256), (64, 64), (128, 128)),     # at most one per compute unit: 2 x 2 wavefronts of 64 x 64 for every scheme
     ((16500, 64, 256), (32, 128), (128, 128)),     # narrow output: 128 x 128 tile of full-width wavefronts
-    ((2000, 2000, 48), (32, 128), (128, 128)),     # a single, short k tile (K no multiple of 128 bytes) on the direct-to-LDS kernel
-    ((1536, 1536, 272), (64, 64), (128, 128)),     # whole k tiles and a short last one
     ((300, 520, 1024), (32, 64), (32, 32)),        # one round of 32 x 32 streaming tiles
     ((256, 1100, 512), (32, 64), (32, 64)),        # more than one round of those: 32 x 64 streaming tiles
 ]

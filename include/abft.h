@@ -85,13 +85,19 @@ typedef enum { ABFT_B_NK = 0, ABFT_B_KN = 1 } abft_blayout_t;
 /* ---- small structs -------------------------------------------------------- */
 /* Test hook for the fault model of Sec. 2.3 (one wrong value in C caused by
  * processing logic): flip bit `bit` (0..31) of the fp32 / int32 accumulator of
- * element (row, col).  k_after < 0: the finished accumulator is flipped just
- * before the checksum epilogue.  k_after >= 0: the running accumulator is flipped
- * once the products with k < k_after have been added (must be a positive multiple
- * of the k_step reported by abft_tile_shape and < K); the corruption then stays
- * until the end of the loop.  When the product is split along k (abft_k_slices, abft_k_ways),
- * the running accumulator is that of the part holding k_after - 1, and k_after < 0 flips the
- * finished partial accumulator of the part holding K - 1. */
+ * element (row, col).
+ *   k_after = -1: the finished accumulator is flipped just before the checksum epilogue.
+ *   k_after >= 0: the running accumulator is flipped once the products with k < k_after have
+ *     been added (must be a positive multiple of the k_step reported by abft_tile_shape and
+ *     < K); the corruption then stays until the end of the loop.
+ *   k_after = -2: the finished value is flipped after the partial sums of the wavefronts that
+ *     share a register tile (abft_k_ways) have been added, just before the checks and the store
+ *     read it; the same as -1 where one wavefront forms the whole sum.
+ * When several wavefronts share a register tile along k (abft_k_ways), the running accumulator
+ * is that of the wavefront holding k_after - 1, and k_after = -1 flips the finished partial
+ * accumulator of the wavefront holding K - 1.
+ * Convolutions: row = output pixel, col = output channel; k counts in the order of abft_conv_t
+ * (a call with k_after >= 0 runs without the lowering to row segments). */
 typedef struct {
     int64_t row, col;
     int32_t bit;
@@ -118,7 +124,7 @@ typedef struct {
     uint64_t tiles;
     double frob, l1;   /* ||C_S||_F and sum |C_ij| of the region lhs/rhs/tau belong to (l1: GLOBAL only) */
     uint32_t lock;     /* used by the device while it updates the block */
-    uint32_t region;   /* 1 + row-major index of that region in the grid of regions */
+    uint32_t region;   /* 1 + row-major index of that region in the partition of C into regions (edge regions clipped) */
 } abft_report_t;
 
 /* ---- the protected product ------------------------------------------------ */
@@ -134,11 +140,10 @@ typedef struct {
  *         workspace first.  THREAD never
  *         reads it: it recomputes tile-local weight checksums in registers (Sec. 5.2.1).
  *   workspace / workspace_bytes: scratch of at least abft_workspace_bytes(...) bytes,
- *         256-byte aligned; may be NULL when that size is 0.  Its first 4096 bytes must be
- *         zero before the first call that uses it; every call leaves them zero, so one
- *         buffer can be reused by calls on the same stream without clearing it again.
- *         GLOBAL requires it.  NONE / THREAD use it to split small products along k
- *         (abft_k_slices) and simply run unsplit when it is NULL or too small.
+ *         256-byte aligned; may be NULL when that size is 0.  Only GLOBAL uses one (partial
+ *         checksum dot products; the weight checksums when `beta` is NULL).  Its contents
+ *         need no initialisation and mean nothing after the call; calls that share a
+ *         workspace must be ordered on one stream.
  *   fault_flag: device uint32, OR-ed with 1 when a comparison fails.  The caller
  *         zeroes it.  May be NULL only for ABFT_NONE.
  *   report: optional device abft_report_t (zero-filled by the caller), else NULL.
@@ -164,7 +169,11 @@ size_t abft_workspace_bytes(int M, int N, int K, int dtype, int mode);
  * count does not fill 16-byte chunks (an RGB first layer) runs several times faster when the
  * workspace has this size: the call then copies the input once with its zero border and
  * re-orders the weights (both into the workspace) so that the product can read whole chunks.
- * With a workspace of only abft_workspace_bytes the same call gathers element by element. */
+ * With a workspace of only abft_workspace_bytes the same call gathers element by element.
+ * The lowered product multiplies the few input values that follow each window's run in its
+ * input row (and, in the last k tile, rows below the window) by zero weights: it assumes finite
+ * activations.  A non-finite activation then also turns outputs of neighbouring windows into
+ * NaN; a protected scheme raises the flag in either form (a non-finite sum fails). */
 size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int dtype, int mode);
 
 /* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns: with
@@ -215,30 +224,27 @@ int abft_tile_shape(int M, int N, int K, int dtype, int aligned, int *tile_m, in
  * columns.  `aligned` as for abft_tile_shape. */
 int abft_region_shape(int M, int N, int K, int dtype, int aligned, int *region_m, int *region_n);
 
-/* Split along k: small products run as n_slices workgroups per output tile, slice s
- * multiplying k in [bounds[s], bounds[s+1]); the slices' partial tiles are added in slice
- * order by the workgroup that finishes last (bit-reproducible).  THREAD makes its tile
- * comparisons per slice, on the partial products.  bounds (n_slices + 1 entries, at most
- * max_bounds) and n_slices may be NULL.  n_slices = 1: not split. */
-int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int *n_slices, int *bounds,
-                  int max_bounds);
-
-/* Interleaved split along k inside a workgroup: `ways` wavefronts share each register tile,
- * wavefront w multiplying the k with (k / step) % ways == w; their partial tiles are added in
- * wavefront order at the end (bit-reproducible).  THREAD makes its tile comparisons per
- * wavefront, on those partial products; GLOBAL compares the tile of the added-up partial
- * products (the split then only matters for where an injected fault lands).  ways = 1: not
- * split.  Combines with abft_k_slices (each slice is then interleaved). */
+/* Split along k inside a workgroup (latency-bound products): `ways` wavefronts share each
+ * register tile, wavefront w multiplying the k with (k / step) % ways == w; their partial
+ * tiles are added in wavefront order at the end (bit-reproducible) and every scheme makes its
+ * comparison on the added-up tile, so the split only matters for where an injected fault
+ * lands (abft_fault_t).  ways = 1: not split. */
 int abft_k_ways(int M, int N, int K, int dtype, int aligned, int mode, int *ways, int *step);
 
-/* Comparison tolerance (the paper states none; Sec. 2.4 step 4 says "compare"): a
- * comparison passes when |lhs - rhs| <= coeff * ||C_S||_F, where C_S is the part of C
- * the comparison covers (all of C for GLOBAL, one tile for THREAD) and ||.||_F is taken
- * from the fp32 accumulators.  coeff = 8 * (2^-24 * sqrt(K) + u), with u = 0 for GLOBAL
- * and u = 2^-22 (F16) / 2^-23 (BF16) for THREAD (precision of the in-register tile
- * checksum).  Returns coeff; 0 for I8 (exact comparison). */
+/* Comparison tolerance (the paper states none; Sec. 2.4 step 4 says "compare").  A comparison
+ * covers a region C_S of C -- one workgroup tile (abft_region_shape) for GLOBAL, one wavefront
+ * register tile (abft_tile_shape) for THREAD / REPLICA -- and passes when
+ *     |lhs - rhs| <= tau = coeff * ||C_S||_F + bias_coeff * sum_{S} |C_ij|
+ * with both norms taken from the fp32 accumulators.
+ *   coeff      = 8 * (2^-24 * sqrt(K) + u): random-walk rounding of K fp32 accumulations per
+ *                entry, added in quadrature over the region, times a safety factor of 8;
+ *                u = 0 for GLOBAL, 2^-22 (F16) / 2^-23 (BF16) for THREAD and REPLICA
+ *                (precision of the in-register tile checksum).
+ *   bias_coeff = 1e-3 * 2^-24 * K for GLOBAL (a same-sign drift of the accumulation that adds
+ *                linearly over a region of same-sign entries), 0 otherwise.
+ * I8 compares exactly: both are 0.  A non-finite side always fails.
+ * abft_tolerance_coeff returns coeff, abft_tolerance_bias_coeff returns bias_coeff. */
 double abft_tolerance_coeff(int K, int dtype, int mode);
-/* Second term of the GLOBAL tolerance: tau = coeff * ||C_S||_F + bias_coeff * sum |C_ij|. */
 double abft_tolerance_bias_coeff(int K, int dtype, int mode);
 
 /* ---- plans: per-layer selection for a network (Sec. 5.3) ------------------- */

@@ -440,25 +440,42 @@ def flip_bit(value, bit: int, dtype: str):
     return float(lib.orc_flip_bit_f32(float(value), bit))
 
 
-def inject(A, B, C, dtype, row, col, bit, k_after=-1, k_begin=0):
+def inject(A, B, C, dtype, row, col, bit, k_after=-1, k_begin=0, k_set=None):
     """Copy of C with one fault in element (row, col).
 
     The accumulator that is hit holds the products k_begin <= k < k_after (k_after < 0 or
-    >= K: up to K); its value is flipped and everything else -- the products before k_begin
-    and from k_after on -- is added to the corrupted value (the fault persists to the end).
-    k_begin = 0, k_after < 0 is a flip of the final value of C[row, col].
+    >= K: up to K) -- with ``k_set`` (a collection of k indices) only those of them whose k is
+    in the set, for an accumulator that takes a subset of the k range.  Its value is flipped and
+    everything else is added to the corrupted value (the fault persists to the end).
+    k_begin = 0, k_after < 0, no k_set: a flip of the final value of C[row, col].
     """
     Cf = np.array(C, copy=True)
     K = A.shape[1]
     if k_after < 0 or k_after > K:
         k_after = K
-    if k_begin == 0 and k_after == K:
+    if k_set is None and k_begin == 0 and k_after == K:
         Cf[row, col] = flip_bit(C[row, col], bit, dtype)
         return Cf
-    before = partial_dot(A, B, dtype, row, col, 0, k_begin)
-    head = partial_dot(A, B, dtype, row, col, k_begin, k_after)
-    tail = partial_dot(A, B, dtype, row, col, k_after, K)
-    Cf[row, col] = flip_bit(head, bit, dtype) + (before + tail)
+    # only row `row` of A and column `col` of B take part
+    a = np.ascontiguousarray(np.asarray(A)[row:row + 1])
+    b = np.ascontiguousarray(np.asarray(B)[:, col:col + 1])
+    hit = range(k_begin, k_after) if k_set is None else sorted(k for k in k_set if k_begin <= k < k_after)
+    inside = np.zeros(K + 1, dtype=bool)
+    inside[list(hit)] = True
+    # maximal runs of consecutive k inside / outside the hit accumulator, each summed in ascending k
+    head = rest = 0 if dtype == I8 else 0.0
+    k = 0
+    while k < K:
+        e = k
+        while e < K and inside[e] == inside[k]:
+            e += 1
+        term = partial_dot(a, b, dtype, 0, 0, k, e)
+        if inside[k]:
+            head += term
+        else:
+            rest += term
+        k = e
+    Cf[row, col] = flip_bit(head, bit, dtype) + rest
     return Cf
 
 
@@ -468,49 +485,6 @@ def part_of(k_parts, k):
         if k in part:
             return s
     raise ValueError(k)
-
-
-def slice_of(k_slices, k):
-    """Index of the slice [k0, k1) that holds k."""
-    return part_of([range(k0, k1) for (k0, k1) in k_slices], k)
-
-
-def thread_check_parts(A, B, dtype, tile_m, tile_n, k_parts, fault=None):
-    """Thread-level ABFT when the product is split along k into parts (each a sorted list of k
-    indices): every part s is its own product C_s = A[:, part] . B[part, :], checked tile by
-    tile like any other (the tolerance uses the full K).  fault = (row, col, bit, k_after)
-    corrupts the accumulator of the part that holds k_after - 1, after its products with
-    k < k_after (k_after < 0: the finished accumulator of the part that holds K - 1).
-    Returns (flag, checks, C) with C the sum of the (possibly corrupted) parts."""
-    Aw, Bw = widen(A, dtype), widen(B, dtype)
-    M, K = Aw.shape
-    N = Bw.shape[1]
-    hit = None
-    if fault is not None:
-        row, col, bit, k_after = fault
-        hit = part_of(k_parts, (K if k_after < 0 else k_after) - 1)
-    total = None
-    checks = []
-    for s, part in enumerate(k_parts):
-        idx = np.asarray(list(part), dtype=np.int64)
-        As, Bs = np.ascontiguousarray(Aw[:, idx]), np.ascontiguousarray(Bw[idx, :])
-        Cs = gemm(As, Bs, dtype)
-        if s == hit:
-            n_before = len(idx) if k_after < 0 else int(np.sum(idx < k_after))
-            Cs = inject(As, Bs, Cs, dtype, row, col, bit, n_before)
-        for (r0, r1, c0, c1) in tiles(M, N, tile_m, tile_n):
-            chk = tile_check(As, Bs, Cs, dtype, r0, r1, c0, c1)
-            if dtype != I8:
-                chk.tau = tolerance(K, frob(Cs, r0, r1, c0, c1), dtype, scheme=2)
-                chk.flag = mismatch(chk.lhs, chk.rhs, chk.tau)
-            checks.append(chk)
-        total = Cs if total is None else total + Cs
-    return any(c.flag for c in checks), checks, total
-
-
-def thread_check_sliced(A, B, dtype, tile_m, tile_n, k_slices, fault=None):
-    """thread_check_parts for contiguous slices [(k0, k1), ...]."""
-    return thread_check_parts(A, B, dtype, tile_m, tile_n, [range(k0, k1) for (k0, k1) in k_slices], fault)
 
 
 # --------------------------------------------------------------------------- #

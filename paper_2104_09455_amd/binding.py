@@ -55,7 +55,7 @@ EXPORTS = [
     "abft_select", "abft_tile_shape", "abft_tolerance_coeff", "abft_plan_create", "abft_plan_run",
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
-    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_slices", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
+    "abft_plan_run_all", "abft_plan_set_mode", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
     "abft_plan_set_activation", "abft_plan_activation",
 ]
 
@@ -117,8 +117,6 @@ def lib() -> ctypes.CDLL:
     L.abft_plan_set_activation.argtypes = [vp, ci, ci]
     L.abft_plan_activation.restype = ci
     L.abft_plan_activation.argtypes = [vp, ci]
-    L.abft_k_slices.restype = ci
-    L.abft_k_slices.argtypes = [ci, ci, ci, ci, ci, ci, ip, ip, ci]
     L.abft_k_ways.restype = ci
     L.abft_k_ways.argtypes = [ci, ci, ci, ci, ci, ci, ip, ip]
     L.abft_plan_mode.restype = ci
@@ -201,14 +199,6 @@ def abft_tile_shape(M, N, K, dtype, aligned=True):
     return tm.value, tn.value, ks.value
 
 
-def abft_k_slices(M, N, K, dtype, mode, aligned=True):
-    """[(k_begin, k_end), ...] of the slices the product is split into along k."""
-    n = ctypes.c_int()
-    bounds = (ctypes.c_int * 17)()
-    _check(lib().abft_k_slices(M, N, K, dtype, 1 if aligned else 0, mode, ctypes.byref(n), bounds, 17))
-    return [(bounds[i], bounds[i + 1]) for i in range(n.value)]
-
-
 def abft_k_ways(M, N, K, dtype, mode, aligned=True):
     """(ways, step): wavefront w of `ways` multiplies the k with (k // step) % ways == w."""
     w, st = ctypes.c_int(), ctypes.c_int()
@@ -217,14 +207,11 @@ def abft_k_ways(M, N, K, dtype, mode, aligned=True):
 
 
 def abft_k_parts(M, N, K, dtype, mode, aligned=True):
-    """The parts the product is split into along k, as lists of k indices: every contiguous
-    slice of abft_k_slices, interleaved as abft_k_ways says.  One part = range(K): not split."""
+    """The parts the accumulators of the product are split into along k, as lists of k indices,
+    as abft_k_ways says (only tells which accumulator an injected fault lands in).  One part =
+    range(K): not split."""
     ways, step = abft_k_ways(M, N, K, dtype, mode, aligned)
-    parts = []
-    for k0, k1 in abft_k_slices(M, N, K, dtype, mode, aligned):
-        for w in range(ways):
-            parts.append([k for k in range(k0, k1) if (k // step) % ways == w])
-    return parts
+    return [[k for k in range(K) if (k // step) % ways == w] for w in range(ways)]
 
 
 def abft_tolerance_coeff(K, dtype, mode) -> float:

@@ -39,9 +39,6 @@ constexpr double U_ACC = 5.9604644775390625e-08;  // 2^-24
 constexpr double U_CHI_F16 = 2.384185791015625e-07;  // 2^-22
 constexpr double U_CHI_BF16 = 1.1920928955078125e-07;  // 2^-23
 
-// every workspace starts with a header that holds the split-K arrival counters; it must be
-// zero before the first call and is left zero by every call
-constexpr size_t WS_HEADER = 4096;
 
 // MI355X spec-sheet peaks (dense) and HBM3E bandwidth
 constexpr double PEAK_F16 = 2516.6e12, PEAK_I8 = 5033.2e12, HBM_BW = 8.0e12;
@@ -71,10 +68,8 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     // the direct-to-LDS kernel needs whole k tiles of 128 bytes; the streaming kernel takes any whole
     // number of 16-byte chunks (a variant of it fills a short last tile up with zeros)
     const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
-    // (the direct-to-LDS kernel's k-ways variant has no global scheme: a pin on it is not honoured there)
     const bool force_fits = force >= 0 && force < CFG_COUNT &&
-                            (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force))) &&
-                            !(force == CFG_F64K && mode == ABFT_GLOBAL);
+                            (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force)));
     if (force_fits) return force;
     if (M <= 16 && !aligned16) return CFG_G16;
     auto tiles = [&](int id) {
@@ -90,7 +85,7 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // the rounds are at least 70 % full (288 tiles would leave the second round of 6000 x 3072 x
         // 768 almost empty: 58 us against 48 us on 128 x 128 tiles), from 192 tiles on when the k loop
         // is eight tiles long or more (50176 x 256 x 512, 12544 x 1024 x 512: 196 tiles each), else from 224.
-        const long long t256 = tiles(CFG_F256);
+        const long long t256 = tiles(CFG_F256W);
         const bool rounds_full = t256 * 10 >= cdiv(t256, 256) * 256 * 7;
         if (fast_ok && N > 128 && nkt_all > 1 && rounds_full && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
             return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
@@ -113,46 +108,12 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
             // with at most one per unit the 64 x 64 wavefront tiles' cheaper checksum wins: 1536 x 2048 x
             // 2048 takes 37 us against 42 us, 640 x 5120 x 1280 26 us against 30 us)
             if (fills128) return (nkt_all <= 1 || (mode == ABFT_THREAD && tiles(CFG_F128) > 256)) ? CFG_F128T : CFG_F128;
-            // (CFG_F64K, CFG_F64S and CFG_F256 are reached through ABFT_FORCE_CFG only)
             return CFG_F64T;
         }
     }
     if (tiles(CFG_G128) >= 192) return CFG_G128;
     if (tiles(CFG_G64) >= 1024) return CFG_G128;
     return CFG_G64;
-}
-
-// Split-K factor: small grids of the direct-to-LDS kernel are cut along k until about one
-// workgroup per compute unit exists (at most 8 slices, at least one k tile each).  The
-// global scheme compares whole-K tile sums and is never split.
-int pick_ksplit(int M, int N, int K, int dt, int cfg, int mode) {
-    static const int force = [] {
-        const char* e = std::getenv("ABFT_FORCE_KSPLIT");
-        return e ? std::atoi(e) : -1;
-    }();
-    const CfgInfo ci = cfg_info_host(cfg);
-    if (cfg != CFG_F64S || mode == ABFT_GLOBAL) return 1;
-    const long long tiles = cdiv(M, ci.bm) * cdiv(N, ci.bn);
-    const long long nkt = cdiv((long long)K * esize(dt), ci.bk_bytes);
-    long long ks = 256 / tiles;
-    // adding the partial tiles costs about as much as several k tiles: keep at least 16 per slice
-    if (ks > nkt / 16) ks = nkt / 16;
-    if (ks > 4) ks = 4;
-    if (force >= 1) ks = force > nkt ? nkt : force;
-    return ks < 1 ? 1 : (int)ks;
-}
-
-struct SplitLayout {
-    size_t off_counters, off_part, total;
-};
-SplitLayout split_layout(int M, int N, int cfg, int ksplit) {
-    const CfgInfo ci = cfg_info_host(cfg);
-    const size_t tiles = (size_t)(cdiv(M, ci.bm) * cdiv(N, ci.bn));
-    SplitLayout s;
-    s.off_counters = 0;  // inside the reserved header (tiles < 256 whenever a product is split)
-    s.off_part = WS_HEADER;
-    s.total = align_up(s.off_part + tiles * (size_t)ksplit * ci.bm * ci.bn * 4, 256);
-    return s;
 }
 
 // ------------------------------------------------------------------------- //
@@ -538,7 +499,7 @@ WsLayout ws_layout(int M, int N, int K, int cfg) {
     const size_t tm = (size_t)cdiv(M, ci.bm), tn = (size_t)cdiv(N, ci.bn);
     const size_t n_parts = (size_t)(ci.bm / (ci.bm < 64 ? ci.bm : 64)) * (size_t)cdiv(K, 256);  // upper bound
     WsLayout w;
-    w.off_pd = WS_HEADER;
+    w.off_pd = 0;
     w.off_beta = align_up(w.off_pd + tm * tn * n_parts * 8, 256);
     w.total = align_up(w.off_beta + beta_total_bytes(K, (int)tn), 256);
     return w;
@@ -692,20 +653,6 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     }
     g.tiles_m = (int)cdiv(pr.M, ci.bm);
     g.tiles_n = (int)cdiv(pr.N, ci.bn);
-    g.ksplit = 1;
-    if (mode != ABFT_GLOBAL) {
-        // split-K needs scratch for the partial tiles; without it the product runs unsplit
-        const int ks = pick_ksplit(pr.M, pr.N, pr.K, pr.dtype, cfg, mode);
-        if (ks > 1) {
-            const SplitLayout sl = split_layout(pr.M, pr.N, cfg, ks);
-            char* wsp = reinterpret_cast<char*>(workspace);
-            if (wsp && !(reinterpret_cast<uintptr_t>(wsp) & 255u) && ws_bytes >= sl.total) {
-                g.ksplit = ks;
-                g.counters = reinterpret_cast<unsigned int*>(wsp + sl.off_counters);
-                g.part = wsp + sl.off_part;
-            }
-        }
-    }
     g.flag = flag;
     g.act = pr.act;
     g.report = reinterpret_cast<Report*>(report);
@@ -715,13 +662,16 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
 
     bool inj = false;
     if (inject) {
-        if (pr.conv) return ABFT_E_INJECT;
         if (inject->row < 0 || inject->row >= pr.M || inject->col < 0 || inject->col >= pr.N) return ABFT_E_INJECT;
         if (inject->bit < 0 || inject->bit > 31) return ABFT_E_INJECT;
+        if (inject->k_after < -2) return ABFT_E_INJECT;
         if (inject->k_after >= 0) {
             if (inject->k_after == 0 || inject->k_after % bk != 0 || inject->k_after >= pr.K) return ABFT_E_INJECT;
             g.f_kt = inject->k_after / bk - 1;
         }
+        // -2: the finished value after the partial tiles of several wavefronts have been added (the
+        // streaming configurations); the same as -1 where one wavefront forms the whole sum
+        if (inject->k_after == -2 && ci.kways > 1) g.f_kt = -2;
         g.f_row = (int)inject->row; g.f_col = (int)inject->col; g.f_bit = inject->bit;
         inj = true;
     }
@@ -836,13 +786,61 @@ size_t lowered_workspace_bytes(const Problem& pr, const ConvLowering& lw, int mo
     return align_up(plain_workspace_bytes(pr.M, pr.N, lw.Kp, pr.dtype, mode), 256) + lw.xp_bytes + lw.bp_bytes;
 }
 
-// a convolution: lowered to row segments when it qualifies and the workspace has the room
+// Weights of a lowered convolution prepared ahead of the call (a plan does this once, offline:
+// the weights are known before inference, Sec. 2.1): the re-ordered N x Kp matrix and, for the
+// global scheme, its weight checksums per block of beta_block_n columns.
+struct LoweredWeights {
+    const void* bp;
+    const void* beta;
+    int beta_block_n;
+};
+
+hipError_t launch_conv_weights(const Problem& pr, const ConvLowering& lw, char* bp, hipStream_t st) {
+    const long long sn = pr.b_layout == ABFT_B_NK ? pr.ldb : 1, sk = pr.b_layout == ABFT_B_NK ? 1 : pr.ldb;
+    dim3 grid((unsigned)cdiv((long long)pr.N * lw.Kp, 256)), block(256);
+    if (esize(pr.dtype) == 2)
+        hipLaunchKernelGGL(conv_weights_kernel<2>, grid, block, 0, st, reinterpret_cast<const char*>(pr.B), sn, sk, bp,
+                           pr.N, lw.Kp, lw.segp, lw.seg, pr.cg.KH);
+    else
+        hipLaunchKernelGGL(conv_weights_kernel<1>, grid, block, 0, st, reinterpret_cast<const char*>(pr.B), sn, sk, bp,
+                           pr.N, lw.Kp, lw.segp, lw.seg, pr.cg.KH);
+    return hipGetLastError();
+}
+
+// the lowered product of a convolution: same C, k re-ordered as (filter row, padded run)
+Problem lowered_problem(const Problem& pr, const ConvLowering& lw, const void* xp, const void* bp) {
+    const abft_conv_t& c = pr.cg;
+    Problem q = pr;
+    q.A = xp;
+    q.B = bp;
+    q.b_layout = ABFT_B_NK;
+    q.ldb = lw.Kp;
+    q.K = lw.Kp;
+    q.lda = lw.Kp;
+    q.tol_K = pr.K;
+    q.cg.H = lw.Hp;
+    q.cg.W = (pr.OW - 1) * c.stride + 1;  // every window start lies inside the padded row
+    q.cg.Cin = lw.segp;
+    q.cg.KW = 1;
+    q.cg.pad = 0;
+    q.pix = c.Cin;
+    q.rowpitch = lw.rowp;
+    q.imgpitch = lw.rowp * lw.Hp;
+    return q;
+}
+
+// a convolution: lowered to row segments when it qualifies and the workspace has the room.
+// A fault planted in a running accumulator (k_after >= 0) counts k in the order of abft_conv_t,
+// which the lowered product does not keep: such a call runs unlowered.
 int run_conv(const Problem& pr, int mode, const void* beta, void* workspace, size_t ws_bytes, uint32_t* flag,
-             abft_report_t* report, const abft_fault_t* inject, hipStream_t st) {
-    const ConvLowering lw = conv_lowering(pr);
+             abft_report_t* report, const abft_fault_t* inject, hipStream_t st, const LoweredWeights* pre = nullptr) {
+    const int rc = validate_common(pr, mode, flag);
+    if (rc != ABFT_OK) return rc;
     if (mode == ABFT_AUTO) mode = select_mode(pr.M, pr.N, pr.K, pr.dtype);
-    if (!lw.ok || inject || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
-        ws_bytes < lowered_workspace_bytes(pr, lw, mode) || !pr.A || !pr.B)
+    const ConvLowering lw = conv_lowering(pr);
+    const size_t own_weights = pre ? 0 : lw.bp_bytes;
+    if (!lw.ok || (inject && inject->k_after >= 0) || !workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) ||
+        ws_bytes < lowered_workspace_bytes(pr, lw, mode) - (lw.bp_bytes - own_weights))
         return run_problem(pr, mode, beta, workspace, ws_bytes, flag, report, inject, st);
     const abft_conv_t& c = pr.cg;
     const int es = esize(pr.dtype);
@@ -860,43 +858,22 @@ int run_conv(const Problem& pr, int mode, const void* beta, void* workspace, siz
             hipLaunchKernelGGL(conv_pad_kernel<1>, grid, block, 0, st, reinterpret_cast<const char*>(pr.A), xp, c.H,
                                c.W * c.Cin, c.pad, c.pad * c.Cin, lw.Hp, lw.rowp, chunks_per_row, total);
         if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
-        const long long sn = pr.b_layout == ABFT_B_NK ? pr.ldb : 1, sk = pr.b_layout == ABFT_B_NK ? 1 : pr.ldb;
-        dim3 grid2((unsigned)cdiv((long long)pr.N * lw.Kp, 256));
-        if (es == 2)
-            hipLaunchKernelGGL(conv_weights_kernel<2>, grid2, block, 0, st, reinterpret_cast<const char*>(pr.B), sn, sk,
-                               bp, pr.N, lw.Kp, lw.segp, lw.seg, c.KH);
-        else
-            hipLaunchKernelGGL(conv_weights_kernel<1>, grid2, block, 0, st, reinterpret_cast<const char*>(pr.B), sn, sk,
-                               bp, pr.N, lw.Kp, lw.segp, lw.seg, c.KH);
-        if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
+        if (!pre && launch_conv_weights(pr, lw, bp, st) != hipSuccess) return ABFT_E_HIP;
     }
-    Problem q = pr;
-    q.A = xp;
-    q.B = bp;
-    q.b_layout = ABFT_B_NK;
-    q.ldb = lw.Kp;
-    q.K = lw.Kp;
-    q.lda = lw.Kp;
-    q.tol_K = pr.K;
-    q.cg.H = lw.Hp;
-    q.cg.W = (pr.OW - 1) * c.stride + 1;  // every window start lies inside the padded row
-    q.cg.Cin = lw.segp;
-    q.cg.KW = 1;
-    q.cg.pad = 0;
-    q.pix = c.Cin;
-    q.rowpitch = lw.rowp;
-    q.imgpitch = lw.rowp * lw.Hp;
-    return run_problem(q, mode, nullptr, workspace, inner, flag, report, nullptr, st);
+    const Problem q = lowered_problem(pr, lw, xp, pre ? pre->bp : bp);
+    // offline weight checksums of the lowered weights fit only the tiling they were made for
+    const void* qbeta = nullptr;
+    if (pre && pre->beta && mode == ABFT_GLOBAL) {
+        const int bn_now = cfg_info_host(pick_cfg(q.M, q.N, q.K, q.dtype, a_vectorisable(q) && b_vectorisable(q), ABFT_GLOBAL)).bn;
+        if (bn_now == pre->beta_block_n) qbeta = pre->beta;
+    }
+    return run_problem(q, mode, qbeta, workspace, inner, flag, report, inject, st);
 }
 
 size_t plain_workspace_bytes(int M, int N, int K, int dtype, int mode) {
     if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
-    if (mode == ABFT_GLOBAL) return ws_bytes_any_cfg(M, N, K);
-    // unprotected / thread-level: scratch only where the product would be split along k
-    // (sized for aligned operands; unaligned ones run unsplit and ignore it)
-    const int cfg = pick_cfg(M, N, K, dtype, true, mode);
-    const int ks = pick_ksplit(M, N, K, dtype, cfg, mode);
-    return ks > 1 ? split_layout(M, N, cfg, ks).total : 0;
+    // only the global scheme keeps anything outside the operands
+    return mode == ABFT_GLOBAL ? ws_bytes_any_cfg(M, N, K) : 0;
 }
 
 }  // namespace
@@ -914,6 +891,11 @@ struct abft_plan {
         size_t ws_bytes;
         double t_us[3];
         int act;          // abft_act_t applied to the stored output
+        // a convolution that runs lowered to row segments: its re-ordered weights and their
+        // checksums, made once at creation
+        void* lowered_B;
+        void* lowered_beta;
+        int lowered_block_n;
     };
     std::vector<Layer> layers;
 };
@@ -963,28 +945,6 @@ size_t abft_conv_workspace_bytes(const abft_conv_t* conv, int N, int dtype, int 
     const ConvLowering lw = conv_lowering(pr);
     const size_t plain = plain_workspace_bytes(pr.M, pr.N, pr.K, dtype, mode);
     return lw.ok ? std::max(plain, lowered_workspace_bytes(pr, lw, mode)) : plain;
-}
-
-int abft_k_slices(int M, int N, int K, int dtype, int aligned, int mode, int* n_slices, int* bounds, int max_bounds) {
-    if (!valid_dtype(dtype)) return ABFT_E_ENUM;
-    if (M <= 0 || N <= 0 || K <= 0) return ABFT_E_SHAPE;
-    if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
-    const int cfg = pick_cfg(M, N, K, dtype, aligned != 0, mode);
-    const int ks = pick_ksplit(M, N, K, dtype, cfg, mode);
-    if (n_slices) *n_slices = ks;
-    if (bounds) {
-        if (max_bounds < ks + 1) return ABFT_E_SHAPE;
-        const int bk = cfg_info_host(cfg).bk_bytes / esize(dtype);
-        const int nkt = ks > 1 ? (int)cdiv(K, bk) : 1;
-        const int base = nkt / ks, rem = nkt % ks;
-        int t = 0;
-        for (int s = 0; s < ks; ++s) {
-            bounds[s] = ks > 1 ? t * bk : 0;
-            t += base + (s < rem ? 1 : 0);
-        }
-        bounds[ks] = K;
-    }
-    return ABFT_OK;
 }
 
 size_t abft_beta_bytes(int K, int N, int block_n) {
@@ -1126,8 +1086,28 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         }
         if (hipMalloc(&L.beta, beta_total_bytes(d.K, (int)cdiv(d.N, L.beta_block_n))) != hipSuccess) { rc = ABFT_E_HIP; break; }
         if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
-        (void)hipMemsetAsync(L.workspace, 0, L.ws_bytes < WS_HEADER ? L.ws_bytes : WS_HEADER, st);
         p->layers.push_back(L);
+        if (d.has_conv) {
+            // few input channels: the layer will run lowered to row segments; its weights are
+            // re-ordered, and their checksums formed, here and now (offline, Sec. 2.5)
+            Problem pr;
+            std::memset(&pr, 0, sizeof pr);
+            (void)conv_problem(&d.conv, d.N, pr);
+            pr.dtype = d.dtype; pr.b_layout = d.b_layout; pr.B = d.B; pr.ldb = d.ldb;
+            const ConvLowering lw = conv_lowering(pr);
+            if (lw.ok) {
+                abft_plan::Layer& PL = p->layers.back();
+                PL.lowered_block_n = cfg_info_host(pick_cfg(d.M, d.N, lw.Kp, d.dtype, true, ABFT_GLOBAL)).bn;
+                if (hipMalloc(&PL.lowered_B, lw.bp_bytes) != hipSuccess ||
+                    hipMalloc(&PL.lowered_beta, beta_total_bytes(lw.Kp, (int)cdiv(d.N, PL.lowered_block_n))) != hipSuccess ||
+                    launch_conv_weights(pr, lw, reinterpret_cast<char*>(PL.lowered_B), st) != hipSuccess ||
+                    launch_weight_checksum(lw.Kp, d.N, PL.lowered_B, lw.Kp, ABFT_B_NK, d.dtype, PL.lowered_block_n,
+                                           PL.lowered_beta, st) != hipSuccess) {
+                    rc = ABFT_E_HIP;
+                    break;
+                }
+            }
+        }
         if (launch_weight_checksum(d.K, d.N, d.B, d.ldb, d.b_layout, d.dtype, L.beta_block_n, L.beta, st) !=
             hipSuccess) {
             rc = ABFT_E_HIP;
@@ -1203,9 +1183,11 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     // forces another tiling gets them recomputed into the workspace
     const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr), ABFT_GLOBAL)).bn;
     const void* beta = bn_now == L.beta_block_n ? L.beta : nullptr;
-    if (pr.conv)
+    if (pr.conv) {
+        const LoweredWeights pre = {L.lowered_B, L.lowered_beta, L.lowered_block_n};
         return run_conv(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
-                        reinterpret_cast<hipStream_t>(stream));
+                        reinterpret_cast<hipStream_t>(stream), L.lowered_B ? &pre : nullptr);
+    }
     return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
                        reinterpret_cast<hipStream_t>(stream));
 }
@@ -1264,6 +1246,8 @@ void abft_plan_destroy(abft_plan_t* plan) {
     for (auto& L : plan->layers) {
         if (L.beta) (void)hipFree(L.beta);
         if (L.workspace) (void)hipFree(L.workspace);
+        if (L.lowered_B) (void)hipFree(L.lowered_B);
+        if (L.lowered_beta) (void)hipFree(L.lowered_beta);
     }
     delete plan;
 }

@@ -108,11 +108,6 @@ struct GemmArgs {
     // after k-tile f_kt has been accumulated (f_kt < 0: after the last one)
     int f_row, f_col, f_bit, f_kt;
     int tiles_m, tiles_n;    // grid shape in tiles
-    // split-K (direct-to-LDS kernel only): ksplit workgroups share a tile, each multiplies a
-    // contiguous range of k tiles; partial tiles meet in `part`, `counters` elects the last
-    int ksplit;
-    char* part;              // [tile][ksplit][BM*BN] fp32 / int32 partial accumulators
-    unsigned int* counters;  // [tile], zero before and after every launch
     // activation function applied to the finished values as they are stored (Sec. 2.4 step 4:
     // after the checks, which see the accumulators as the product left them): 0 none, 1 max(x, 0)
     int act;
@@ -706,6 +701,75 @@ __device__ __forceinline__ void store_quad_rows(float v0, float v1, float v2, fl
     *reinterpret_cast<i32x2*>(dst) = out;
 }
 
+// This lane's share of the sum of a wavefront's redundant accumulator blocks under a
+// wavefront-level scheme, weighted as the form of the tile checksum says, so that the sum over
+// the lanes is the checksum product (Sec. 5.2.2) resp. the replicated output sum (Sec. 5.1).
+// int8: exact 64-bit sums from 16-bit pieces (low halves unsigned, high halves signed, of up to
+// 256 accumulators each: far inside int32).  Floating point: groups of four accumulators are
+// summed in fp32, everything above that in fp64.
+template <class CFG, int MODE>
+__device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long, double>::type lane_check_sum(
+    const typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[(CheckRegs<CFG, MODE>::N)], int lane) {
+    typedef Mma<CFG::DT, CFG::MI> MMA;
+    constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
+    constexpr bool SPLIT_FORM = MODE != MODE_REPL && ChecksumForm<CFG>::SPLIT;
+    if constexpr (CFG::DT == DT_I8) {
+        long long rsum = 0;
+        if constexpr (SPLIT_FORM) {
+            // accumulators of the low-digit operand, then 256 x those of the high-digit one
+#pragma unroll
+            for (int pc = 0; pc < 2; ++pc) {
+                int r_lo = 0, r_hi = 0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; ++r) {
+                        r_lo += chk[pc * TM + i][r] & 0xffff;
+                        r_hi += chk[pc * TM + i][r] >> 16;
+                    }
+                const long long part = ((long long)r_hi << 16) + (long long)r_lo;
+                rsum += pc == 0 ? part : 256 * part;
+            }
+        } else {
+            int r_lo = 0, r_hi = 0;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < MMA::NACC; ++r) {
+                    r_lo += chk[i][r] & 0xffff;
+                    r_hi += chk[i][r] >> 16;
+                }
+            rsum = ((long long)r_hi << 16) + (long long)r_lo;
+            if (MODE != MODE_REPL && (lane % MI) >= MI / 2) rsum *= 256;
+        }
+        return rsum;
+    } else {
+        double rsum = 0.0;
+        if constexpr (SPLIT_FORM) {
+            typedef TileChecksumSplit<CFG::DT, TN> SPL;
+#pragma unroll
+            for (int pc = 0; pc < SPL::NP; ++pc) {
+                double part = 0.0;
+#pragma unroll
+                for (int i = 0; i < TM; ++i)
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; r += 4)
+                        part += (double)((chk[pc * TM + i][r] + chk[pc * TM + i][r + 1]) +
+                                         (chk[pc * TM + i][r + 2] + chk[pc * TM + i][r + 3]));
+                rsum += part * SPL::scale(pc);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int r = 0; r < MMA::NACC; r += 4)
+                    rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
+            if constexpr (MODE != MODE_REPL) rsum *= TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane);
+        }
+        return rsum;
+    }
+}
+
 // Checksum epilogue (taken from the accumulators, before down-conversion) and store of C.
 //  GLOBAL: fused output summation (Sec. 2.5) of the workgroup tile, compared right here with
 //          the tile's checksum dot product (Sec. 2.4 steps 3-4).  lane_dot (a double, or a
@@ -725,10 +789,14 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
     const TileCoords<CFG> tc(tile_m, tile_n, wave_mn);
     const int tid = threadIdx.x, lane = tc.lane, wave = tc.wave;
     const int M = p.M, N = p.N;
-    // index of this wavefront's register tile in the grid of wave tiles (row-major)
-    const unsigned wave_tile_index = (unsigned)((tile_m * CFG::WAVES_M + tc.wave_m) * (p.tiles_n * CFG::WAVES_N) +
-                                                tile_n * CFG::WAVES_N + tc.wave_n);
+    // index of this wavefront's register tile in the partition of C into such tiles (row-major,
+    // edge tiles clipped); a register tile that lies wholly outside C (the launched grid is whole
+    // workgroup tiles) holds zeros and is left out of the diagnostics
+    const int wave_row = tile_m * CFG::WAVES_M + tc.wave_m, wave_col = tile_n * CFG::WAVES_N + tc.wave_n;
+    const bool wave_inside = wave_row * CFG::WM < M && wave_col * CFG::WN < N;
+    const unsigned wave_tile_index = (unsigned)(wave_row * ((N + CFG::WN - 1) / CFG::WN) + wave_col);
     (void)wave_tile_index;
+    (void)wave_inside;
     auto acc_row = [&](int i, int r) { return tc.row(i, r); };
     auto acc_col = [&](int j) { return tc.col(j); };
     // ---- checksum epilogue: taken from the accumulators, before down-conversion
@@ -781,44 +849,14 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                     }
                 }
             } else {
-                // (exact 64-bit sums from 16-bit pieces, as above)
-                long long rsum = 0;
-                if constexpr (MODE != MODE_REPL && ChecksumForm<CFG>::SPLIT) {
-                    // accumulators of the low-digit operand, then 256 x those of the high-digit one
-#pragma unroll
-                    for (int pc = 0; pc < 2; ++pc) {
-                        int r_lo = 0, r_hi = 0;
-#pragma unroll
-                        for (int i = 0; i < TM; ++i)
-#pragma unroll
-                            for (int r = 0; r < MMA::NACC; ++r) {
-                                r_lo += chk[pc * TM + i][r] & 0xffff;
-                                r_hi += chk[pc * TM + i][r] >> 16;
-                            }
-                        const long long part = ((long long)r_hi << 16) + (long long)r_lo;
-                        rsum += pc == 0 ? part : 256 * part;
-                    }
-                    rsum = wave_sum(rsum);
-                } else {
-                    int r_lo = 0, r_hi = 0;
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int r = 0; r < MMA::NACC; ++r) {
-                            r_lo += chk[i][r] & 0xffff;
-                            r_hi += chk[i][r] >> 16;
-                        }
-                    rsum = ((long long)r_hi << 16) + (long long)r_lo;
-                    const long long w = (MODE != MODE_REPL && (lane % MI) >= MI / 2) ? 256 : 1;
-                    rsum = wave_sum(rsum * w);
-                }
+                const long long rsum = wave_sum(lane_check_sum<CFG, MODE>(chk, lane));
                 if (lane == 0) {
                     // (replication: a block that took several products may have wrapped where the
                     // product's own blocks did not; the two sides still agree modulo 2^32, and a
                     // flipped bit never changes a sum by a multiple of 2^32)
                     bool bad = MODE == MODE_REPL ? (unsigned int)(s - rsum) != 0u : s != rsum;
                     if (bad) atomicOr(p.flag, 1u);
-                    if (p.report)
+                    if (p.report && wave_inside)
                         report_update(p.report, bad ? __builtin_huge_val() : 0.0, (double)s, (double)rsum, 0.0, 0.0, 0.0,
                                       wave_tile_index);
                 }
@@ -893,28 +931,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                     }
                 }
             } else {
-                double rsum = 0.0;
-                if constexpr (MODE != MODE_REPL && ChecksumForm<CFG>::SPLIT) {
-                    typedef TileChecksumSplit<CFG::DT, TN> SPL;
-#pragma unroll
-                    for (int pc = 0; pc < SPL::NP; ++pc) {
-                        double part = 0.0;
-#pragma unroll
-                        for (int i = 0; i < TM; ++i)
-#pragma unroll
-                            for (int r = 0; r < MMA::NACC; r += 4)
-                                part += (double)((chk[pc * TM + i][r] + chk[pc * TM + i][r + 1]) +
-                                                 (chk[pc * TM + i][r + 2] + chk[pc * TM + i][r + 3]));
-                        rsum += part * SPL::scale(pc);
-                    }
-                } else {
-#pragma unroll
-                    for (int i = 0; i < TM; ++i)
-#pragma unroll
-                        for (int r = 0; r < MMA::NACC; r += 4)
-                            rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
-                    if constexpr (MODE != MODE_REPL) rsum *= TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane);
-                }
+                double rsum = lane_check_sum<CFG, MODE>(chk, lane);
                 if (p.report) {
                     s = wave_sum(s);
                     rsum = wave_sum(rsum);
@@ -929,7 +946,7 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                     bool finite = __builtin_isfinite(s) && __builtin_isfinite(rsum) && __builtin_isfinite(F2);
                     bool bad = !finite || !(res <= tau);
                     if (bad) atomicOr(p.flag, 1u);
-                    if (p.report) {
+                    if (p.report && wave_inside) {
                         double ratio = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
                         report_update(p.report, ratio, s, rsum, tau, __builtin_sqrt(F2), 0.0, wave_tile_index);
                     }

@@ -11,10 +11,6 @@ namespace abft {
 //    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       thread-level (wide tiles: two checksum
 //                                                                    MFMAs per four), narrow outputs, K of one k tile
 //    F64T    64 x 128, wavefronts 2 x 1 of  32 x 128, 3 stages       between the streaming tiles and F128
-//    F64K    same tile, 6 stages, 4 wavefronts per register tile     (each takes one k step in four); its range is now
-//                                                                    covered by the streaming tiles: environment switch only
-//    F256   256 x 256, wavefronts 2 x 2 of 128 x 128, 2 stages       kept for comparison, not selected
-//    F64S    64 x 128, 6 stages, may be split along k across workgroups   kept, selected only by environment switch
 //  S* run the streaming kernel (same alignment, K any multiple of 16 bytes; four wavefronts split the k tiles of one
 //  register tile between them, each with its own LDS stages, no barrier in the k loop):
 //    S32     32 x  32, 4 stages per wavefront                         a few tiles only: latency-bound layers
@@ -22,17 +18,14 @@ namespace abft {
 //    S128    64 x  64, 2 stages per wavefront                         up to about one tile per compute unit
 //  G* run the generic kernel (any alignment, layout, K):
 //    G128 128 x 128, G64 64 x 64 (32x32 MFMA shapes), G16 16 x 64 (16x16 shapes; M <= 16)
-enum CfgId { CFG_F256 = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_F64S, CFG_F64K, CFG_F256W, CFG_S32, CFG_S64, CFG_S128, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
+enum CfgId { CFG_F256W = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_S32, CFG_S64, CFG_S128, CFG_G128, CFG_G64, CFG_G16, CFG_COUNT };
 
 template <int DT, int ID>
 struct CfgOf;
 //                                             MI TM TN WM WN BKB
-template <int DT> struct CfgOf<DT, CFG_F256>  { typedef Cfg<DT, 32, 4, 4, 2, 2, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F128T> { typedef Cfg<DT, 32, 1, 4, 4, 1, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F64T>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 1; };
-template <int DT> struct CfgOf<DT, CFG_F64S>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 6; static constexpr int KWAYS = 1; };
-template <int DT> struct CfgOf<DT, CFG_F64K>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 6; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 32, 4, 2, 2, 4, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_S32>   { typedef Cfg<DT, 32, 1, 1, 1, 1, 128> type; static constexpr int NSTAGE = 4; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_S64>   { typedef Cfg<DT, 32, 1, 2, 1, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 4; };
@@ -43,7 +36,7 @@ template <int DT> struct CfgOf<DT, CFG_G16>   { typedef Cfg<DT, 16, 1, 1, 1, 4, 
 
 constexpr bool cfg_is_stream(int id) { return id == CFG_S32 || id == CFG_S64 || id == CFG_S128; }
 
-// threads: of one WAVES_M x WAVES_N grid of wavefronts (the launch has kways times as many);
+// threads: of one WAVES_M x WAVES_N grid of wavefronts (a streaming launch has kways times as many);
 // kway_bytes: bytes of k that one wavefront takes in turn when kways wavefronts share a tile
 struct CfgInfo {
     int bm, bn, bk_bytes, wm, wn, threads, lds_bytes, fast, kways, kway_bytes;
@@ -55,18 +48,15 @@ constexpr CfgInfo cfg_info() {
     constexpr int ns = CfgOf<DT_F16, ID>::NSTAGE;
     constexpr int kw = CfgOf<DT_F16, ID>::KWAYS;
     constexpr int lds = cfg_is_stream(ID) ? kw * ns * ((C::BM + C::BN) * 128 + 256)
-                                          : (ns ? ns * ((C::BM + C::BN) * 128 + (C::THREADS / 64) * kw * 256) : C::LDS_BYTES);
+                                          : (ns ? ns * ((C::BM + C::BN) * 128 + (C::THREADS / 64) * 256) : C::LDS_BYTES);
     return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, lds, ns ? 1 : 0, kw, cfg_is_stream(ID) ? 128 : 32};
 }
 
 inline CfgInfo cfg_info_host(int id) {
     switch (id) {
-        case CFG_F256: return cfg_info<CFG_F256>();
         case CFG_F128: return cfg_info<CFG_F128>();
         case CFG_F128T: return cfg_info<CFG_F128T>();
         case CFG_F64T: return cfg_info<CFG_F64T>();
-        case CFG_F64S: return cfg_info<CFG_F64S>();
-        case CFG_F64K: return cfg_info<CFG_F64K>();
         case CFG_F256W: return cfg_info<CFG_F256W>();
         case CFG_S32: return cfg_info<CFG_S32>();
         case CFG_S64: return cfg_info<CFG_S64>();

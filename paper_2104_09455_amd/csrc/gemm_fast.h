@@ -46,13 +46,10 @@ __device__ __forceinline__ void tile_of_block(int bid, int tiles_m, int tiles_n,
 // vmcnt(n) with expcnt / lgkmcnt left open (gfx9 encoding: vmcnt in bits 3:0 and 15:14)
 constexpr int waitcnt_vm(int n) { return (n & 15) | ((n >> 4) << 14) | 0x0F70; }
 
-// KWAYS > 1: that many wavefronts share each register tile, wavefront w of them multiplying
-// the k steps kk with kk % KWAYS == w of every k tile; their partial tiles are added through
-// LDS at the end (fixed order).  More wavefronts per compute unit for grids of few tiles.
-template <class CFG, int NSTAGE, int KWAYS>
+template <class CFG, int NSTAGE>
 struct FastLayout {
     static constexpr int ROWB = 128;                            // bytes per LDS row
-    static constexpr int WAVES = CFG::WAVES_M * CFG::WAVES_N * KWAYS;
+    static constexpr int WAVES = CFG::WAVES_M * CFG::WAVES_N;
     static constexpr int A_STAGE = CFG::BM * ROWB;
     static constexpr int AB_STAGE = (CFG::BM + CFG::BN) * ROWB;
     // global scheme: every wavefront also copies the k tile's 256 bytes of weight checksums
@@ -64,14 +61,12 @@ struct FastLayout {
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
     static_assert(CFG::MI == 32 && CFG::BKB == 128, "32x32 MFMA shapes, 128-byte k tile");
-    static_assert(KWAYS == 1 || KWAYS == 4, "one wavefront per k step or one per tile");
-    static_assert(KWAYS == 1 || NSTAGE * STAGE >= WAVES * CFG::TM * CFG::TN * 16 * 64 * 4, "LDS for the final sum");
     static_assert((NSTAGE - 2) * (NQA + NQB + 1) <= 63, "vmcnt range");
 };
 
-template <class CFG, int NSTAGE, int MODE, bool INJ, bool CONV, bool SPLITK, int KWAYS>
-__global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const GemmArgs p) {
-    typedef FastLayout<CFG, NSTAGE, KWAYS> LAY;
+template <class CFG, int NSTAGE, int MODE, bool INJ, bool CONV>
+__global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs p) {
+    typedef FastLayout<CFG, NSTAGE> LAY;
     constexpr int DT = CFG::DT;
     typedef Mma<DT, 32> MMA;
     typedef typename MMA::Acc Acc;
@@ -88,24 +83,13 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    constexpr int WAVES_MN = CFG::WAVES_M * CFG::WAVES_N;
-    const int wave_k = KWAYS > 1 ? wave / WAVES_MN : 0;  // which k steps of a tile this wavefront multiplies
-    const int wave_mn = KWAYS > 1 ? wave - wave_k * WAVES_MN : wave;
-    const int wave_m = wave_mn / CFG::WAVES_N, wave_n = wave_mn % CFG::WAVES_N;
+    const int wave_m = wave / CFG::WAVES_N, wave_n = wave % CFG::WAVES_N;
 
-    // split-K: ksplit consecutive workgroups share an output tile
-    const int ksplit = SPLITK ? p.ksplit : 1;
-    const int tile_lin = SPLITK ? (int)blockIdx.x / ksplit : (int)blockIdx.x;
-    const int ks = SPLITK ? (int)blockIdx.x - tile_lin * ksplit : 0;
     int tile_m, tile_n;
-    tile_of_block(tile_lin, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    tile_of_block((int)blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int bm0 = tile_m * BM, bn0 = tile_n * BN;
     const int M = p.M, N = p.N;
-    // this workgroup's range of k tiles: slices differ by at most one tile, longer ones first
-    const int nkt_all = p.K / BK;
-    const int kt_base = nkt_all / ksplit, kt_rem = nkt_all - kt_base * ksplit;
-    const int kt_first = ks * kt_base + (ks < kt_rem ? ks : kt_rem);
-    const int nkt = kt_base + (ks < kt_rem ? 1 : 0);
+    const int nkt = p.K / BK;
 
     // ---- global -> LDS copy: this lane always fills LDS slot `lane` of a 1 KB block
     // (8 rows x 8 chunks): row lane/8, position lane%8, which holds chunk (lane%8) ^ key(row)
@@ -129,14 +113,14 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     for (int q = 0; q < NQB; ++q) {
         const int n = bn0 + (q * WAVES + wave) * 8 + crow;
         if (n < N) b_valid |= 1u << q;
-        bptr[q] = n < N ? p.B + ((long long)n * p.ldb + (long long)kt_first * BK) * ESIZE + ckc * 16 : zero;
+        bptr[q] = n < N ? p.B + (long long)n * p.ldb * ESIZE + ckc * 16 : zero;
     }
 #pragma unroll
     for (int q = 0; q < NQA; ++q) {
         const int m = bm0 + (q * WAVES + wave) * 8 + crow;
         if (m < M) a_valid |= 1u << q;
         if constexpr (!CONV) {
-            aptr[q] = m < M ? p.A + ((long long)m * p.lda + (long long)kt_first * BK) * ESIZE + ckc * 16 : zero;
+            aptr[q] = m < M ? p.A + (long long)m * p.lda * ESIZE + ckc * 16 : zero;
         } else {
             const int mm = m < M ? m : 0;
             const int img = mm / (p.OH * p.OW);
@@ -153,12 +137,12 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     const char* beta_ptr = zero;
     if constexpr (GDOT) {
         const long long blk = (long long)tile_n * p.K;
-        if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (long long)kt_first * BK + (lane & 31) * 4;
-        else beta_ptr = p.beta_k + (blk + (long long)kt_first * BK + lane) * 4;
+        if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (lane & 31) * 4;
+        else beta_ptr = p.beta_k + (blk + lane) * 4;
     }
     constexpr int BETA_ADV = IS_INT ? BK : BK * 4;
     if constexpr (CONV) {
-        const int k = kt_first * BK + ckc * (16 / ESIZE);
+        const int k = ckc * (16 / ESIZE);
         const int tap = k / p.Cin;
         tap_c = k - tap * p.Cin;
         tap_kh = tap / p.KW;
@@ -232,7 +216,6 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     int pos[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) pos[kk] = ((2 * kk + fgrp) ^ fx) * 16;
-    const int pos_k = ((2 * wave_k + fgrp) ^ fx) * 16;  // KWAYS > 1: this wavefront's k step
 
     // fragments of one k step: double buffered so that the reads of step kk+1 run under
     // the MFMAs of step kk
@@ -256,7 +239,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
     };
     i32x4 fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* st, int kk, int buf) {
-        const int ps = KWAYS > 1 ? pos_k : pos[kk];
+        const int ps = pos[kk];
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + ps);
@@ -312,7 +295,7 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
         constexpr int CUR = decltype(cur_c)::value;
         const char* st = smem + stage * STAGE;
         dot_tile(st);
-        if constexpr (KWAYS == 1) {
+        {
 #pragma unroll
             for (int kk = 0; kk < 3; ++kk) {
                 read_frags(st, kk + 1, (kk + 1) & 1);
@@ -345,119 +328,24 @@ __global__ __launch_bounds__(CFG::THREADS * KWAYS) void gemm_fast_kernel(const G
                 advance();
                 issue_loads(stage);
             }
-            read_frags(smem + next * STAGE, 0, KWAYS > 1 ? CUR ^ 1 : 0);
+            read_frags(smem + next * STAGE, 0, 0);
         }
         mma_step(CUR);
         stage = next;
         if constexpr (INJ) {
             // the running accumulator that holds the products just before k_after: the last k step
-            if (kt_first + kt == p.f_kt && wave_k == KWAYS - 1)
-                inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, wave_mn));
+            if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
         }
     };
     read_frags(smem, 0, 0);
-    if constexpr (KWAYS == 1) {
-        // the last of the four k steps sits in buffer 1
-        for (int kt = 0; kt < nkt; ++kt) tile_step(kt, std::integral_constant<int, 1>());
-    } else {
-        // this wavefront's single step per tile alternates between the two buffers
-        for (int kt = 0; kt < nkt; kt += 2) {
-            tile_step(kt, std::integral_constant<int, 0>());
-            if (kt + 1 < nkt) tile_step(kt + 1, std::integral_constant<int, 1>());
-        }
-    }
+    // the last of the four k steps sits in buffer 1
+    for (int kt = 0; kt < nkt; ++kt) tile_step(kt, std::integral_constant<int, 1>());
     if constexpr (INJ) {
-        // a fault in the finished accumulator: with a split along k, that of the last part
-        if (p.f_kt < 0 && ks == ksplit - 1 && wave_k == KWAYS - 1)
-            inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, wave_mn));
+        // a fault in the finished accumulator
+        if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
     }
     __syncthreads();  // the epilogue reuses LDS
-    if constexpr (KWAYS > 1) {
-        // ---- several wavefronts per register tile: each checks its own partial tile (thread-level
-        // scheme), then the partial tiles are added through LDS in wavefront order
-        static_assert(EMODE != MODE_GLOBAL && !SPLITK, "k-ways configurations: unprotected or thread-level, unsplit");
-        typedef typename MMA::AccT AccT;
-        epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, false, wave_mn);
-        AccT* red = reinterpret_cast<AccT*>(smem);
-        constexpr int NV = TM * TN * 16;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) red[(wave * NV + (i * TN + j) * 16 + r) * 64 + lane] = acc[i][j][r];
-        __syncthreads();
-        if (wave_k != 0) return;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    AccT v = 0;
-#pragma unroll
-                    for (int w = 0; w < KWAYS; ++w)
-                        v += red[((w * WAVES_MN + wave_mn) * NV + (i * TN + j) * 16 + r) * 64 + lane];
-                    acc[i][j][r] = v;
-                }
-        Acc none0[1];
-        epilogue<CFG, MODE_NONE>(acc, none0, p, tile_m, tile_n, smem, true, wave_mn);
-        return;
-    }
-    if (!SPLITK || ksplit <= 1) {
-        epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &dot.total : nullptr);
-        return;
-    }
-    // ---- split-K: check this slice's partial tile (thread-level scheme), publish it, and let
-    // the workgroup that arrives last add the slices in slice order and store C
-    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, false);
-    typedef typename MMA::AccT AccT;
-    constexpr int TILE_ELEMS = BM * BN;
-    typedef AccT Acc4 __attribute__((ext_vector_type(4)));
-    Acc4* mine = reinterpret_cast<Acc4*>(p.part) + (((long long)tile_lin * ksplit + ks) * TILE_ELEMS) / 4 + tid;
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; r += 4) {
-                Acc4 v = {acc[i][j][r], acc[i][j][r + 1], acc[i][j][r + 2], acc[i][j][r + 3]};
-                mine[((i * TN + j) * 4 + r / 4) * CFG::THREADS] = v;
-            }
-    __threadfence();
-    __syncthreads();
-    unsigned int* sflag = reinterpret_cast<unsigned int*>(smem);
-    if (tid == 0) *sflag = atomicAdd(p.counters + tile_lin, 1u);
-    __syncthreads();
-    const bool last = *sflag == (unsigned)(ksplit - 1);
-    __syncthreads();
-    if (!last) return;
-    __threadfence();
-    if (tid == 0) p.counters[tile_lin] = 0u;  // leave the counter ready for the next launch
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-    const Acc4* all = reinterpret_cast<const Acc4*>(p.part) + ((long long)tile_lin * ksplit * TILE_ELEMS) / 4 + tid;
-    for (int s = 0; s < ksplit; ++s) {
-        const Acc4* src = all + ((long long)s * TILE_ELEMS) / 4;
-#pragma unroll
-        for (int i = 0; i < TM; ++i)
-#pragma unroll
-            for (int j = 0; j < TN; ++j)
-#pragma unroll
-                for (int r = 0; r < 16; r += 4) {
-                    const Acc4 v = src[((i * TN + j) * 4 + r / 4) * CFG::THREADS];
-                    acc[i][j][r] += v[0];
-                    acc[i][j][r + 1] += v[1];
-                    acc[i][j][r + 2] += v[2];
-                    acc[i][j][r + 3] += v[3];
-                }
-    }
-    Acc none[1];
-    epilogue<CFG, MODE_NONE>(acc, none, p, tile_m, tile_n, smem);
+    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &dot.total : nullptr);
 }
 
 }  // namespace abft

@@ -7,9 +7,9 @@
 // 128 bytes of k).  Each wavefront streams its own k tiles from HBM straight into its own
 // ring of LDS stages (global_load_lds_dwordx4) and reads them back as MFMA fragments, so the
 // k loop has no workgroup barrier at all: a wavefront only ever waits for its own copies.
-// The four partial tiles are checked (thread-level scheme: per wavefront, on its partial
-// product) and then added through LDS in wavefront order, every wavefront adding and storing
-// a quarter of the tile.
+// The four partial tiles are added through LDS in wavefront order, every wavefront adding and
+// storing a quarter of the tile; every protected scheme makes its comparison on the added-up
+// tile (one per tile), so the final addition is inside the check as well.
 //
 // Same alignment requirements and LDS row swizzle as the direct-to-LDS kernel, but K may be any
 // whole number of 16-byte chunks: the wavefront that owns a short last k tile copies zeros in
@@ -351,14 +351,19 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     }
     if constexpr (INJ) {
         // a fault in a finished accumulator: that of the wavefront holding the last k tile
-        if (p.f_kt < 0 && wave == (nkt - 1) % KW) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, 0));
+        if (p.f_kt == -1 && wave == (nkt - 1) % KW) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n, 0));
     }
 
     // ---- the partial tiles are added in wavefront order; wavefront w adds and stores accumulator
     // registers 4w .. 4w+3 of every MFMA block (rows 8w + 4 (lane / 32) + 0..3 of the block).
-    // Under the wavefront-level schemes each wavefront then checks its own partial tile, from its
-    // registers, while the stores drain: the check's arithmetic is off the critical path.
+    // Every protected scheme compares the ADDED-UP tile: its output summation (Sec. 2.5) runs over
+    // the finished values as they are stored, so a fault in a partial accumulator and a fault in
+    // this final addition both show.  The other side of the comparison is the tile's checksum
+    // dot product (global scheme) or the sum of the four wavefronts' redundant accumulators
+    // (thread-level schemes: checksum products of the partial products add up to the checksum
+    // product of the whole, Sec. 5.2.2).
     static_assert(MODE != MODE_GLOBAL_PRE, "streaming configurations form the checksum dot product themselves");
+    constexpr bool CHECKED = MODE != MODE_NONE;
     __syncthreads();  // the sum reuses every wavefront's stages
     AccT* red = reinterpret_cast<AccT*>(smem);
     constexpr int NV = TM * TN * 16;
@@ -374,10 +379,22 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     const bool whole = tc.bm0 + BM <= M && tc.bn0 + BN <= N && (p.ldc & 3) == 0 &&
                        (reinterpret_cast<uintptr_t>(p.C) & 7u) == 0;
     typedef typename ChecksumDot<DT>::Wide Wide;
-    // global scheme: the output summation (Sec. 2.5) runs over the finished values as they are stored
     Wide s_sum = 0;
     int s_lo = 0, s_hi = 0;
     float f2 = 0.f, l1 = 0.f;
+    // test hook: a fault in a finished value after the addition (k_after = -2): block, register
+    // and lane that hold element (f_row, f_col)
+    int f_blk = -1, f_rr = 0;
+    if constexpr (INJ) {
+        const int rr = p.f_row - tc.bm0, cc = p.f_col - tc.bn0;
+        if (p.f_kt == -2 && rr >= 0 && rr < BM && cc >= 0 && cc < BN) {
+            const int in_blk = rr & 31, r = (in_blk >> 3) * 4 + (in_blk & 3);
+            if (wave == (r >> 2) && tc.lrow == (cc & 31) && tc.lgrp == ((in_blk >> 2) & 1)) {
+                f_blk = (rr >> 5) * TN + (cc >> 5);
+                f_rr = r & 3;
+            }
+        }
+    }
 #pragma unroll
     for (int i = 0; i < TM; ++i)
 #pragma unroll
@@ -390,6 +407,13 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 v[rr] = 0;
 #pragma unroll
                 for (int w = 0; w < KW; ++w) v[rr] += red[(w * NV + (i * TN + j) * 16 + r) * 64 + lane];
+            }
+            if constexpr (INJ) {
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const unsigned mask = (f_blk == i * TN + j && f_rr == rr) ? (1u << p.f_bit) : 0u;
+                    v[rr] = bitcast<AccT>(bitcast<unsigned>(v[rr]) ^ mask);
+                }
             }
             // stored values: after the activation function; the checks below see the product
             AccT o[4];
@@ -415,7 +439,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                     }
                 }
             }
-            if constexpr (GDOT) {
+            if constexpr (CHECKED) {
                 if constexpr (IS_INT) {
 #pragma unroll
                     for (int rr = 0; rr < 4; ++rr) {
@@ -425,15 +449,17 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                 } else {
                     s_sum += (double)((v[0] + v[1]) + (v[2] + v[3]));
                     f2 += v[0] * v[0] + v[1] * v[1] + v[2] * v[2] + v[3] * v[3];
-                    l1 += (__builtin_fabsf(v[0]) + __builtin_fabsf(v[1])) + (__builtin_fabsf(v[2]) + __builtin_fabsf(v[3]));
+                    if constexpr (GDOT)
+                        l1 += (__builtin_fabsf(v[0]) + __builtin_fabsf(v[1])) + (__builtin_fabsf(v[2]) + __builtin_fabsf(v[3]));
                 }
             }
         }
-    if constexpr (mode_is_wave_level(MODE)) epilogue<CFG, MODE>(acc, chk, p, tile_m, tile_n, smem, false, 0);
-    if constexpr (GDOT) {
-        // comparison (Sec. 2.4 step 4) for this tile
+    if constexpr (CHECKED) {
+        // comparison (Sec. 2.4 step 4 / Sec. 5.2.2) for this tile
         if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;
+        // this lane's share of the other side
         Wide lane_dot = dot.total;
+        if constexpr (mode_is_wave_level(MODE)) lane_dot = lane_check_sum<CFG, MODE>(chk, lane);
         if constexpr (MDOT) {
             // column 0 of the extra result blocks holds A . (first plane), column 1 A . (second plane)
             if constexpr (IS_INT) {
@@ -466,7 +492,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             s_sum = wave_sum((Wide)(s_sum - lane_dot));
         }
         const double F2 = IS_INT ? 0.0 : (double)wave_sum(f2);
-        const double L1 = IS_INT ? 0.0 : (double)wave_sum(l1);
+        const double L1 = (IS_INT || !GDOT) ? 0.0 : (double)wave_sum(l1);
         __syncthreads();  // everyone is done reading the partial tiles
         double* redd = reinterpret_cast<double*>(smem);
         Wide* redw = reinterpret_cast<Wide*>(smem) + 2 * KW;
@@ -488,13 +514,16 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             }
             const unsigned t = (unsigned)(tile_m * p.tiles_n + tile_n);
             if constexpr (IS_INT) {
-                const bool bad = ts != sab;
+                // (replication: a block that took several products may have wrapped where the
+                // product's own blocks did not; the two sides still agree modulo 2^32, and a
+                // flipped bit never changes a sum by a multiple of 2^32)
+                const bool bad = MODE == MODE_REPL ? (unsigned int)(ts - sab) != 0u : ts != sab;
                 if (bad) atomicOr(p.flag, 1u);
                 if (p.report)
                     report_update(p.report, bad ? __builtin_huge_val() : 0.0, (double)ts, (double)sab, 0.0, 0.0, 0.0, t);
             } else {
                 const double frob = __builtin_sqrt(tf);
-                const double tau = p.tol_coeff * frob + p.tol_l1 * tl;
+                const double tau = p.tol_coeff * frob + (GDOT ? p.tol_l1 * tl : 0.0);
                 const double res = __builtin_fabs((double)ts - (double)sab);
                 // a sum of squares beyond the fp32 range cannot come from a fault-free tile
                 const bool finite = __builtin_isfinite((double)ts) && __builtin_isfinite((double)sab) && __builtin_isfinite(tf);

@@ -136,7 +136,6 @@ def test_replication_mode_shares_the_thread_level_geometry(lib):
             al = (K * (1 if dt == B.I8 else 2)) % 16 == 0
             assert B.abft_workspace_bytes(M, N, K, dt, B.REPLICA) == B.abft_workspace_bytes(M, N, K, dt, B.THREAD)
             assert B.abft_k_ways(M, N, K, dt, B.REPLICA, al) == B.abft_k_ways(M, N, K, dt, B.THREAD, al)
-            assert B.abft_k_slices(M, N, K, dt, B.REPLICA, al) == B.abft_k_slices(M, N, K, dt, B.THREAD, al)
             assert B.abft_tolerance_coeff(K, dt, B.REPLICA) == B.abft_tolerance_coeff(K, dt, B.THREAD)
             assert B.abft_tolerance_bias_coeff(K, dt, B.REPLICA) == 0.0
     assert B.MODE_NAMES[B.REPLICA] == "replica"

@@ -63,11 +63,13 @@ def test_conv_parity(ci, mode, dtype):
         rm, rn = B.abft_region_shape(M, c.Cout, K, DT[dtype], aligned)
         bad, checks = oracle.global_check_blocks(A, Wm, C_ref, dtype, rm, rn)
         assert not bad and rep.tiles == len(checks)
-        near = min(checks, key=lambda ch: abs(ch.rhs - rep.rhs))
+        ref = checks[rep.region - 1]   # the oracle's check of the region the device reports
         if dtype == "i8":
-            assert rep.lhs == near.lhs and rep.rhs == near.rhs
+            assert rep.lhs == ref.lhs and rep.rhs == ref.rhs
         else:
-            assert abs(rep.rhs - near.rhs) <= 0.1 * near.tau + 1e-9
+            assert abs(rep.rhs - ref.rhs) <= 0.1 * ref.tau + 1e-9
+            assert abs(rep.lhs - ref.lhs) <= ref.tau
+            assert rep.tau == pytest.approx(ref.tau, rel=1e-3)
             assert rep.worst_ratio < 0.5
 
 

@@ -14,186 +14,151 @@ pytestmark = pytest.mark.gpu
 DT = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}
 
 
-class Big:
-    """Device-resident operands of one large GEMM (weights stored N x K)."""
-
-    def __init__(self, M, N, K, dtype, seed, dist="normal"):
-        import torch
-        from gpu_util import to_dev, DEV
-        self.M, self.N, self.K, self.dtype, self.dt = M, N, K, dtype, DT[dtype]
-        self.A, self.Bm = wl.gemm_operands(M, N, K, dtype, seed, dist_a=dist, dist_b=dist)
-        self.dA = to_dev(self.A, dtype)
-        self.dB = to_dev(np.ascontiguousarray(self.Bm.T), dtype)
-        c_t = torch.int32 if dtype == "i8" else (torch.float16 if dtype == "f16" else torch.bfloat16)
-        self.dC = torch.zeros((M, N), dtype=c_t, device=DEV)
-        self.flag = torch.zeros(1, dtype=torch.int32, device=DEV)
-        self.rep = torch.zeros(64, dtype=torch.uint8, device=DEV)
-        self.wsb = max(B.abft_workspace_bytes(M, N, K, self.dt, m) for m in (B.NONE, B.GLOBAL, B.THREAD))
-        self.ws = torch.zeros(max(self.wsb, 256), dtype=torch.uint8, device=DEV)
-        self.rm, self.rn = B.abft_region_shape(M, N, K, self.dt, True)
-        self.beta = torch.zeros(B.abft_beta_bytes(K, N, self.rn) // 8, dtype=torch.float64, device=DEV)
-        B.abft_weight_checksum(K, N, self.dB, K, B.B_NK, self.dt, self.beta, block_n=self.rn)
-
-    def run(self, mode, inject=None, want_report=True):
-        import torch
-        from gpu_util import read_report
-        self.flag.zero_()
-        self.rep.zero_()
-        B.abft_gemm(self.M, self.N, self.K, self.dA, self.K, self.dB, self.K, B.B_NK, self.dC, self.N, self.dt,
-                    mode, beta=self.beta, workspace=self.ws, workspace_bytes=self.wsb, fault_flag=self.flag,
-                    report=self.rep if want_report else None, inject=inject)
-        torch.cuda.synchronize()
-        return int(self.flag.item()), (read_report(self.rep) if want_report else None)
+def Big(M, N, K, dtype, seed, dist="normal"):
+    from gpu_util import DeviceGemm
+    return DeviceGemm(M, N, K, dtype, seed, dist_a=dist, dist_b=dist)
 
 
-@pytest.mark.parametrize("n,dtype", [(4096, "f16"), (4096, "bf16"), (8192, "f16"), (8192, "i8")])
-def test_large_square_sampled_rows_and_identity(n, dtype):
-    from gpu_util import c_to_host, c_close
+def _check_reported_region(big, rep, mode):
+    """The region the device reports (largest residual / tolerance) against the oracle's check of
+    the region of that index, from the oracle's own block of C."""
+    bm, bn = (big.rm, big.rn) if mode == B.GLOBAL else (big.tm, big.tn)
+    per_row = -(-big.N // bn)
+    r0, c0 = (rep.region - 1) // per_row * bm, (rep.region - 1) % per_row * bn
+    Ab, Bb = big.A[r0:r0 + bm], np.ascontiguousarray(big.Bm[:, c0:c0 + bn])
+    Cb = oracle.gemm(Ab, Bb, big.dtype)
+    h, w = Cb.shape
+    if mode == B.GLOBAL:
+        ref = oracle.region_check(Ab, Bb, Cb, big.dtype, 0, h, 0, w)
+    else:
+        ref = (oracle.replica_check if mode == B.REPLICA else oracle.tile_check)(Ab, Bb, Cb, big.dtype, 0, h, 0, w)
+    assert not ref.flag
+    if big.dtype == "i8":
+        assert rep.lhs == ref.lhs and rep.rhs == ref.rhs and rep.worst_ratio == 0.0
+    else:
+        assert abs(rep.lhs - ref.lhs) <= ref.tau
+        assert abs(rep.rhs - ref.rhs) <= (0.1 if mode == B.GLOBAL else 1.0) * ref.tau
+        assert rep.tau == pytest.approx(ref.tau, rel=1e-3)
+        assert rep.worst_ratio < 0.5, rep.worst_ratio
+
+
+@pytest.mark.parametrize("n,dtype", [(4096, "f16"), (4096, "bf16"), (8192, "f16"), (8192, "bf16"), (8192, "i8")])
+def test_large_square_sampled_rows_columns_and_identity(n, dtype):
+    """The compute-bound squares in every scheme: at least 128 full rows of C that hit every band
+    of 256 rows (first and last row of each band among them) and 128 full columns against the
+    oracle; one comparison per region, none fires, and the region the device reports agrees with
+    the oracle's check of that region; int8: the whole-matrix identity sum(C) = (1^T A)(B 1)
+    holds exactly for the C the device stored."""
+    from gpu_util import c_close, sample_rows
     big = Big(n, n, n, dtype, seed=900 + n)
-    rows = np.random.default_rng(n).choice(n, size=6, replace=False)
-    ref = oracle.gemm_rows(big.A, big.Bm, dtype, rows)
-    for mode in (B.GLOBAL, B.THREAD):
+    rows = sample_rows(n, 128, band=256, seed=n)
+    cols = sample_rows(n, 128, band=256, seed=n + 1)
+    assert len(rows) >= 128 and len(cols) >= 128
+    ref_rows = oracle.gemm(big.A[rows], big.Bm, dtype)
+    ref_cols = oracle.gemm(big.A, np.ascontiguousarray(big.Bm[:, cols]), dtype)
+    for mode in (B.NONE, B.GLOBAL, B.THREAD, B.REPLICA, B.AUTO):
         print(f"case n={n} dtype={dtype} mode={mode}", flush=True)
+        big.dC.zero_()
         flag, rep = big.run(mode)
-        got = c_to_host(big.dC[rows.tolist()], dtype)
-        assert c_close(got, ref, dtype)
+        assert c_close(big.C(rows=rows), ref_rows, dtype)
+        assert c_close(big.C(cols=cols), ref_cols, dtype)
         assert flag == 0
-        if mode == B.GLOBAL:
-            assert rep.tiles == (n // big.rm) * (n // big.rn)
-            if dtype == "i8":
-                assert rep.worst_ratio == 0.0 and rep.lhs == rep.rhs   # exact identity in every region
-            else:
-                assert rep.worst_ratio < 0.5, rep.worst_ratio
-        else:
-            tm, tn, _ = B.abft_tile_shape(n, n, n, big.dt, True)
-            assert rep.tiles == (n // tm) * (n // tn)
-            assert rep.worst_ratio < 0.5, rep.worst_ratio
+        if mode == B.AUTO:
+            assert B.abft_select(n, n, n, big.dt) == B.GLOBAL   # compute bound by Eq. 1
+            mode = B.GLOBAL
+        if mode == B.NONE:
+            continue
+        bm, bn = (big.rm, big.rn) if mode == B.GLOBAL else (big.tm, big.tn)
+        assert rep.tiles == (n // bm) * (n // bn)
+        _check_reported_region(big, rep, mode)
+        if dtype == "i8" and mode == B.GLOBAL:
+            total = int(big.dC.cpu().numpy().astype(np.int64).sum())
+            assert total == oracle.checksum_dot(oracle.col_checksum(big.A, dtype), oracle.row_checksum(big.Bm, dtype))
 
 
-@pytest.mark.parametrize("dtype,trials", [("i8", 1000), ("f16", 1000)])
-def test_fault_campaign_global_4096(dtype, trials):
-    """1000 seeded single-bit flips across C and the running accumulators at 4096^3 under the
-    scheme the selector picks (global): element uniform over C (fp16: uniform over 16 regions
-    drawn once, whose oracle blocks are computed once each), bit uniform over all 32, half in the
-    finished value and half in the running accumulator.  int8: every flip flagged.  fp16: the
-    verdict equals the oracle's incremental evaluation outside the don't-care band; non-finite
-    always flagged."""
-    n = 4096
-    big = Big(n, n, n, dtype, seed=77)
-    _, _, ks = B.abft_tile_shape(n, n, n, big.dt, True)
-    flag0, rep0 = big.run(B.GLOBAL)
-    assert flag0 == 0
-    rng = np.random.default_rng(78)
+def _campaign(n, dtype, mode, trials, seed):
+    """Seeded single-bit flips across C and the running accumulators: element uniform over 16
+    comparison regions drawn once (whose oracle blocks are computed once each; int8: uniform over
+    all of C), bit uniform over all 32, finished value / running accumulator alternating.  int8:
+    every flip flagged.  Floating point: the verdict equals the oracle's incremental evaluation
+    outside the don't-care band around the tolerance of the region that holds the element;
+    non-finite values always flagged."""
+    big = Big(n, n, n, dtype, seed=seed)
+    ks = big.k_step
+    assert B.abft_k_ways(n, n, n, big.dt, mode)[0] == 1   # one wavefront per register tile: no k parts
+    bm, bn = (big.rm, big.rn) if mode == B.GLOBAL else (big.tm, big.tn)
+    flag0, rep0 = big.run(mode)
+    assert flag0 == 0 and rep0.tiles == (n // bm) * (n // bn)
+    resid0 = rep0.tau * rep0.worst_ratio   # largest clean rounding residual of any region on the device
+    rng = np.random.default_rng(seed + 1)
     must = mustnot = band = 0
-    regions = [(int(rng.integers(n // big.rm)), int(rng.integers(n // big.rn))) for _ in range(16)]
+    regions = [(int(rng.integers(n // bm)), int(rng.integers(n // bn))) for _ in range(16)]
     blocks = {}
     for t in range(trials):
         i, j, bit = int(rng.integers(n)), int(rng.integers(n)), int(rng.integers(32))
         if dtype != "i8":
             ri, rj = regions[t % len(regions)]
-            i, j = ri * big.rm + i % big.rm, rj * big.rn + j % big.rn
+            i, j = ri * bm + i % bm, rj * bn + j % bn
         k_after = -1 if t % 2 == 0 else ks * int(rng.integers(1, n // ks))
-        if t % 50 == 0:
-            print(f"case {t} dtype={dtype} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
-        flag, rep = big.run(B.GLOBAL, inject=B.Fault(i, j, bit, k_after))
+        if t % 100 == 0:
+            print(f"case {t} n={n} mode={mode} dtype={dtype} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        flag, _ = big.run(mode, inject=B.Fault(i, j, bit, k_after), want_report=False)
         if dtype == "i8":
-            assert flag == 1
+            assert flag == 1, (i, j, bit, k_after)
             must += 1
             continue
-        # oracle, incremental: the corrupted element against its clean value
+        # oracle, incremental: the corrupted element against its clean value (row i of A and column
+        # j of B only: the oracle widens what it is handed)
         kk = n if k_after < 0 else k_after
-        # (row i of A and column j of B only: the oracle widens what it is handed)
         a_row, b_col = big.A[i:i + 1], np.ascontiguousarray(big.Bm[:, j:j + 1])
         head = oracle.partial_dot(a_row, b_col, dtype, 0, 0, 0, kk)
         tail = oracle.partial_dot(a_row, b_col, dtype, 0, 0, kk, n)
         bad = oracle.flip_bit(head, bit, dtype) + tail
         if not math.isfinite(bad):
-            assert flag == 1
+            assert flag == 1, (i, j, bit, k_after)
             must += 1
             continue
         delta = abs(bad - (head + tail))
-        # tolerance of the region that holds the element, from the oracle's own block of C
-        r0, c0 = i // big.rm * big.rm, j // big.rn * big.rn
+        # tolerance of the region that holds the element, from the oracle's own block of C with the
+        # one corrupted element (the rest of the block is unchanged)
+        r0, c0 = i // bm * bm, j // bn * bn
         if (r0, c0) not in blocks:
-            blk = oracle.gemm(big.A[r0:r0 + big.rm], np.ascontiguousarray(big.Bm[:, c0:c0 + big.rn]), dtype)
+            blk = oracle.gemm(big.A[r0:r0 + bm], np.ascontiguousarray(big.Bm[:, c0:c0 + bn]), dtype)
             blocks[(r0, c0)] = (blk, oracle.frob(blk) ** 2, oracle.l1norm(blk))
         blk, f2_clean, l1_clean = blocks[(r0, c0)]
-        # norms of the block with the one corrupted element (the rest of the block is unchanged)
         clean = float(blk[i - r0, j - c0])
         frob_bad = math.sqrt(max(f2_clean - clean * clean + bad * bad, 0.0))
         l1_bad = l1_clean - abs(clean) + abs(bad)
-        tau = oracle.tolerance(n, frob_bad, dtype, scheme=1, l1_norm=l1_bad)
-        resid0 = rep0.tau * rep0.worst_ratio   # largest clean rounding residual of any region on the device
+        tau = oracle.tolerance(n, frob_bad, dtype, scheme=1 if mode == B.GLOBAL else 2, l1_norm=l1_bad)
         if delta >= 2 * tau + resid0:
-            assert flag == 1, (i, j, bit, delta, tau)
+            assert flag == 1, (i, j, bit, k_after, delta, tau)
             must += 1
         elif delta <= tau / 2 - resid0:
-            assert flag == 0, (i, j, bit, delta, tau)
+            assert flag == 0, (i, j, bit, k_after, delta, tau)
             mustnot += 1
         else:
             band += 1
+    print(f"campaign n={n} {dtype} mode={mode}: {must} flagged as required, {mustnot} silent as required, "
+          f"{band} inside the don't-care band", flush=True)
     assert must > 0
     if dtype != "i8":
         assert mustnot > 0
+
+
+@pytest.mark.parametrize("n", [4096, 8192])
+@pytest.mark.parametrize("dtype", ["i8", "f16", "bf16"])
+def test_fault_campaign_selected_scheme(dtype, n):
+    """1000 trials per size and type under the scheme the selector picks for these compute-bound
+    products (global)."""
+    assert B.abft_select(n, n, n, DT[dtype]) == B.GLOBAL
+    _campaign(n, dtype, B.GLOBAL, 1000, seed=77 + n)
 
 
 @pytest.mark.parametrize("mode", [B.THREAD, B.REPLICA])
-@pytest.mark.parametrize("dtype,trials", [("i8", 400), ("f16", 400)])
-def test_fault_campaign_wave_level_4096(dtype, trials, mode):
-    """Seeded single-bit flips at 4096^3 under the two wavefront-level schemes (one-sided ABFT,
-    replication): element uniform over 16 wavefront tiles drawn once (whose oracle blocks are
-    computed once each), bit uniform over all 32, half in the finished value and half in the
-    running accumulator.  int8: every flip flagged.  fp16: the verdict equals the oracle's outside
-    the don't-care band around the tolerance of the tile that holds the element."""
-    n = 4096
-    big = Big(n, n, n, dtype, seed=79)
-    tm, tn, ks = B.abft_tile_shape(n, n, n, big.dt, True)
-    assert B.abft_k_ways(n, n, n, big.dt, mode)[0] == 1   # one wavefront per register tile: no k parts
-    flag0, rep0 = big.run(mode)
-    assert flag0 == 0 and rep0.tiles == (n // tm) * (n // tn)
-    rng = np.random.default_rng(80)
-    must = mustnot = 0
-    tiles = [(int(rng.integers(n // tm)), int(rng.integers(n // tn))) for _ in range(16)]
-    blocks = {}
-    for t in range(trials):
-        ti, tj = tiles[t % len(tiles)]
-        i, j, bit = ti * tm + int(rng.integers(tm)), tj * tn + int(rng.integers(tn)), int(rng.integers(32))
-        k_after = -1 if t % 2 == 0 else ks * int(rng.integers(1, n // ks))
-        if t % 50 == 0:
-            print(f"case {t} mode={mode} dtype={dtype} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
-        flag, _ = big.run(mode, inject=B.Fault(i, j, bit, k_after), want_report=False)
-        if dtype == "i8":
-            assert flag == 1
-            must += 1
-            continue
-        kk = n if k_after < 0 else k_after
-        a_row, b_col = big.A[i:i + 1], np.ascontiguousarray(big.Bm[:, j:j + 1])
-        head = oracle.partial_dot(a_row, b_col, dtype, 0, 0, 0, kk)
-        tail = oracle.partial_dot(a_row, b_col, dtype, 0, 0, kk, n)
-        bad = oracle.flip_bit(head, bit, dtype) + tail
-        if not math.isfinite(bad):
-            assert flag == 1
-            must += 1
-            continue
-        delta = abs(bad - (head + tail))
-        r0, c0 = ti * tm, tj * tn
-        if (r0, c0) not in blocks:
-            blk = oracle.gemm(big.A[r0:r0 + tm], np.ascontiguousarray(big.Bm[:, c0:c0 + tn]), dtype)
-            blocks[(r0, c0)] = (blk, oracle.frob(blk) ** 2)
-        blk, f2_clean = blocks[(r0, c0)]
-        clean = float(blk[i - r0, j - c0])
-        frob_bad = math.sqrt(max(f2_clean - clean * clean + bad * bad, 0.0))
-        tau = oracle.tolerance(n, frob_bad, dtype, scheme=2)
-        resid0 = rep0.tau * rep0.worst_ratio   # largest clean rounding residual of any tile on the device
-        if delta >= 2 * tau + resid0:
-            assert flag == 1, (i, j, bit, delta, tau)
-            must += 1
-        elif delta <= tau / 2 - resid0:
-            assert flag == 0, (i, j, bit, delta, tau)
-            mustnot += 1
-    assert must > 0
-    if dtype != "i8":
-        assert mustnot > 0
+@pytest.mark.parametrize("n,dtype,trials", [(4096, "i8", 400), (4096, "f16", 400), (4096, "bf16", 200), (8192, "f16", 200)])
+def test_fault_campaign_wave_level(n, dtype, trials, mode):
+    """The same campaign under the two wavefront-level schemes (one-sided ABFT, replication)."""
+    _campaign(n, dtype, mode, trials, seed=79 + n)
 
 
 def test_ragged_large_uses_the_big_tile_and_matches():

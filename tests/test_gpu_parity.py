@@ -38,34 +38,34 @@ def test_clean_parity(shape, mode, dtype):
         flag, checks = oracle.global_check_blocks(A, Bm, C_ref, dtype, rm, rn)
         assert not flag
         assert res.report.tiles == len(checks)
-        # the reported region is one of the oracle's: same checksum product, same tolerance
-        near = min(checks, key=lambda c: abs(c.rhs - res.report.rhs))
+        # the reported region is the oracle's region of that index: same sides, same tolerance
+        ref = checks[res.report.region - 1]
         if dtype == "i8":
-            assert res.report.lhs == near.lhs and res.report.rhs == near.rhs and res.report.worst_ratio == 0.0
+            assert res.report.lhs == ref.lhs and res.report.rhs == ref.rhs and res.report.worst_ratio == 0.0
         else:
             # checksum side: fp32 weight checksums, products summed in fp32 within a k tile and
             # in fp64 above that; its rounding must stay a small part of the tolerance
-            assert abs(res.report.rhs - near.rhs) <= 0.1 * near.tau + 1e-9
-            assert abs(res.report.lhs - near.lhs) <= near.tau + 1e-300
-            assert res.report.tau == pytest.approx(near.tau, rel=1e-3)
+            assert abs(res.report.rhs - ref.rhs) <= 0.1 * ref.tau + 1e-9
+            assert abs(res.report.lhs - ref.lhs) <= ref.tau + 1e-300
+            assert res.report.tau == pytest.approx(ref.tau, rel=1e-3)
             assert res.report.worst_ratio < 0.5
     if mode in WAVE_LEVEL:
         tm, tn, _ = B.abft_tile_shape(M, N, K, dt, aligned)
-        import math
-        # one comparison per wave tile of the launched grid (tiles past the edge included) and k part
-        assert res.report.tiles >= math.ceil(M / tm) * math.ceil(N / tn) * len(B.abft_k_parts(M, N, K, dt, mode, aligned))
+        # one comparison per wavefront register tile of the partition of C
+        regions = list(oracle.tiles(M, N, tm, tn))
+        assert res.report.tiles == len(regions)
         assert res.report.worst_ratio < 0.5
-        if mode == B.REPLICA and len(B.abft_k_parts(M, N, K, dt, mode, aligned)) == 1:
-            # the reported tile is one of the oracle's replication checks: same sides, same tolerance
-            checks = [oracle.replica_check(A, Bm, C_ref, dtype, *t) for t in oracle.tiles(M, N, tm, tn)]
-            assert not any(c.flag for c in checks)
-            near = min(checks, key=lambda c: abs(c.rhs - res.report.rhs))
-            if dtype == "i8":
-                assert res.report.lhs == near.lhs and res.report.rhs == near.rhs
-            else:
-                assert abs(res.report.rhs - near.rhs) <= near.tau + 1e-300
-                assert abs(res.report.lhs - near.lhs) <= near.tau + 1e-300
-                assert res.report.tau == pytest.approx(near.tau, rel=1e-3)
+        # the reported tile is the oracle's tile of that index: same sides, same tolerance
+        check = oracle.replica_check if mode == B.REPLICA else oracle.tile_check
+        ref = check(A, Bm, C_ref, dtype, *regions[res.report.region - 1])
+        assert not ref.flag
+        if dtype == "i8":
+            assert res.report.lhs == ref.lhs and res.report.rhs == ref.rhs
+        else:
+            # both sides are fp32 accumulations on the device
+            assert abs(res.report.rhs - ref.rhs) <= ref.tau + 1e-300
+            assert abs(res.report.lhs - ref.lhs) <= ref.tau + 1e-300
+            assert res.report.tau == pytest.approx(ref.tau, rel=1e-3)
 
 
 # shapes chosen so that every tile configuration of the dispatcher runs under test:
@@ -190,15 +190,18 @@ def test_int8_injected_faults_always_flagged(shape, mode):
         k_after = -1 if (t % 2 == 0 or K <= ks) else ks * int(rng.integers(1, K // ks))
         if k_after >= K:
             k_after = -1
+        if t % 5 == 4:
+            k_after = -2   # after the partial tiles of the wavefronts that share a tile have been added
         print(f"case shape={shape} mode={mode} fault=({i},{j},bit {bit},k_after {k_after}) parts={len(parts)}", flush=True)
         res = run_gemm(A, Bm, "i8", mode, inject=B.Fault(i, j, bit, k_after))
         # the accumulator that is hit belongs to the part of k that holds k_after - 1 (K - 1 for a
-        # flip of the finished value) and holds that part's products with k < k_after
-        part = parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)]
-        kk = [k for k in part if k_after < 0 or k < k_after]
-        head = int(A[i, kk].astype(np.int64) @ Bm[kk, j].astype(np.int64))
-        C_bad = C_ref.copy()
-        C_bad[i, j] = oracle.flip_bit(head, bit, "i8") + (int(C_ref[i, j]) - head)
+        # flip of the finished value) and holds that part's products with k < k_after; after the
+        # addition of the parts it is the finished element itself
+        if k_after == -2:
+            C_bad = oracle.inject(A, Bm, C_ref, "i8", i, j, bit)
+        else:
+            part = parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)]
+            C_bad = oracle.inject(A, Bm, C_ref, "i8", i, j, bit, k_after=k_after, k_set=part)
         want = ((C_bad + 2 ** 31) % 2 ** 32) - 2 ** 31  # the int32 register wraps
         assert np.array_equal(res.C, want)
         assert res.flag == 1
@@ -218,26 +221,26 @@ def test_fp_injected_faults_match_oracle_outside_band(mode, dtype):
     tm, tn, ks = B.abft_tile_shape(M, N, K, dt)
     rng = np.random.default_rng(32)
     counts = {"must": 0, "mustnot": 0, "band": 0}
+    parts = B.abft_k_parts(M, N, K, dt, mode)
     for t in range(60):
         i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(32))
-        print(f"case mode={mode} dtype={dtype} fault=({i},{j},bit {bit})", flush=True)
-        res = run_gemm(A, Bm, dtype, mode, inject=B.Fault(i, j, bit, -1))
-        if mode == B.GLOBAL:
+        k_after = -2 if t % 3 == 2 else -1   # the finished partial accumulator, or the element after the addition
+        print(f"case mode={mode} dtype={dtype} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        res = run_gemm(A, Bm, dtype, mode, inject=B.Fault(i, j, bit, k_after))
+        # every scheme compares the finished tile: the oracle's check of the region that holds the
+        # element, on the C the fault leaves behind
+        if k_after == -2:
             C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit)
+        else:
+            C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit, k_set=parts[oracle.part_of(parts, K - 1)])
+        if mode == B.GLOBAL:
             rm, rn = B.abft_region_shape(M, N, K, dt)
             r0, c0 = i // rm * rm, j // rn * rn
             chk = oracle.region_check(A, Bm, C_bad, dtype, r0, min(r0 + rm, M), c0, min(c0 + rn, N))
         else:
-            # thread-level: the comparison that sees the fault is the one of the wavefront tile
-            # and k part whose accumulator was hit
-            parts = B.abft_k_parts(M, N, K, dt, mode)
-            idx = parts[oracle.part_of(parts, K - 1)]
-            As, Bs = np.ascontiguousarray(A[:, idx]), np.ascontiguousarray(Bm[idx, :])
-            C_bad = oracle.inject(As, Bs, oracle.gemm(As, Bs, dtype), dtype, i, j, bit)
             r0, c0 = i // tm * tm, j // tn * tn
             check = oracle.replica_check if mode == B.REPLICA else oracle.tile_check
-            chk = check(As, Bs, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
-            chk.tau = oracle.tolerance(K, oracle.frob(C_bad, r0, r0 + tm, c0, c0 + tn), dtype, scheme=2)
+            chk = check(A, Bm, C_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
         if not math.isfinite(C_bad[i, j]):
             assert res.flag == 1
             counts["must"] += 1
@@ -270,67 +273,71 @@ def test_auto_mode_follows_selector():
     res = run_gemm(A, Bm, "f16", B.AUTO)
     # 64^3 is bandwidth bound -> thread-level: one comparison per wavefront tile, not per workgroup tile
     tm, tn, _ = B.abft_tile_shape(64, 64, 64, B.F16)
-    n_parts = len(B.abft_k_parts(64, 64, 64, B.F16, B.THREAD))
-    assert res.flag == 0 and res.report.tiles == -(-64 // tm) * -(-64 // tn) * n_parts and res.report.tau > 0
+    assert res.flag == 0 and res.report.tiles == -(-64 // tm) * -(-64 // tn) and res.report.tau > 0
     assert res.report.l1 == 0.0   # the ||C||_1 term belongs to the global scheme only
     assert c_close(res.C, oracle.gemm(A, Bm, "f16"), "f16")
 
 
 @pytest.mark.parametrize("shape", [(64, 1024, 4096), (200, 384, 512)])
-@pytest.mark.parametrize("dtype", ["f16", "i8"])
-def test_split_k_thread_level(dtype, shape):
-    """Small products are split along k -- across workgroups (slices) or across the wavefronts
-    of a workgroup (ways): partial tiles are added in a fixed order (bit-reproducible), the
-    thread-level comparisons run per part, and a fault is seen by the part that holds it."""
+@pytest.mark.parametrize("mode", [B.GLOBAL, B.THREAD, B.REPLICA])
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_faults_where_wavefronts_share_a_tile_along_k(dtype, mode, shape):
+    """Latency-bound products: four wavefronts share each register tile along k, their partial
+    tiles are added in a fixed order (bit-reproducible) and every scheme compares the added-up
+    tile.  A fault in any partial accumulator (mid-loop or finished) and a fault in the finished
+    value after the addition are all seen by the one comparison of the tile that holds them."""
     import math
     from gpu_util import run_gemm, c_close
     M, N, K = shape
-    dt = B.F16 if dtype == "f16" else B.I8
-    parts = B.abft_k_parts(M, N, K, dt, B.THREAD)
-    assert len(parts) > 1 and sorted(k for p in parts for k in p) == list(range(K))
-    # (the global scheme compares whole tiles after the partial tiles are added: its comparisons
-    # are never split, though its accumulators may be, across the wavefronts of a workgroup)
-    assert len(B.abft_k_slices(M, N, K, dt, B.GLOBAL)) == 1
-    if len(B.abft_k_slices(M, N, K, dt, B.THREAD)) > 1:
-        assert B.abft_workspace_bytes(M, N, K, dt, B.THREAD) > 0
+    dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
+    parts = B.abft_k_parts(M, N, K, dt, mode)
+    assert len(parts) == 4 and sorted(k for p in parts for k in p) == list(range(K))
     tm, tn, ks = B.abft_tile_shape(M, N, K, dt)
-    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=55, dist_a="uniform_01" if dtype == "f16" else "int8",
-                             dist_b="weights" if dtype == "f16" else "int8")
+    if mode == B.GLOBAL:
+        tm, tn = B.abft_region_shape(M, N, K, dt)
+    fp = dtype != "i8"
+    A, Bm = wl.gemm_operands(M, N, K, dtype, seed=55, dist_a="uniform_01" if fp else "int8",
+                             dist_b="weights" if fp else "int8")
     C_ref = oracle.gemm(A, Bm, dtype)
-    for mode in (B.NONE, B.THREAD):
-        res = run_gemm(A, Bm, dtype, mode)
-        assert c_close(res.C, C_ref, dtype) and res.flag == 0
-        again = run_gemm(A, Bm, dtype, mode)
-        assert np.array_equal(res.C, again.C)
-        if mode == B.THREAD:
-            # (wavefront tiles of the launched grid that lie wholly past the edge are compared too)
-            assert res.report.tiles >= len(parts) * math.ceil(M / tm) * math.ceil(N / tn)
-            assert res.report.worst_ratio < 0.5
+    res = run_gemm(A, Bm, dtype, mode)
+    assert c_close(res.C, C_ref, dtype) and res.flag == 0
+    again = run_gemm(A, Bm, dtype, mode)
+    assert np.array_equal(res.C, again.C)
+    assert res.report.tiles == math.ceil(M / tm) * math.ceil(N / tn)
+    assert res.report.worst_ratio < 0.5
+    resid0 = res.report.tau * res.report.worst_ratio   # largest clean rounding residual of any tile
     rng = np.random.default_rng(56)
-    for t in range(12):
-        i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(20, 32))
-        k_after = -1 if t % 3 == 0 else ks * int(rng.integers(1, K // ks))
-        print(f"case split-k dtype={dtype} shape={shape} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
-        res = run_gemm(A, Bm, dtype, B.THREAD, inject=B.Fault(i, j, bit, k_after))
-        idx = np.asarray(parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)])
-        As, Bs = np.ascontiguousarray(A[:, idx]), np.ascontiguousarray(Bm[idx, :])
-        Cs = oracle.gemm(As, Bs, dtype)
-        n_before = len(idx) if k_after < 0 else int(np.sum(idx < k_after))
-        Cs_bad = oracle.inject(As, Bs, Cs, dtype, i, j, bit, n_before)
-        r0, c0 = i // tm * tm, j // tn * tn
-        chk = oracle.tile_check(As, Bs, Cs_bad, dtype, r0, min(r0 + tm, M), c0, min(c0 + tn, N))
-        if dtype == "i8":
-            assert res.flag == 1
-            want = C_ref + (Cs_bad - Cs)
-            assert np.array_equal(res.C, ((want + 2 ** 31) % 2 ** 32) - 2 ** 31)
+    seen = {"must": 0, "mustnot": 0}
+    for t in range(15):
+        i, j, bit = int(rng.integers(M)), int(rng.integers(N)), int(rng.integers(12, 32))
+        k_after = (-1, -2, ks * int(rng.integers(1, K // ks)))[t % 3]
+        print(f"case shared-k dtype={dtype} mode={mode} shape={shape} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        got = run_gemm(A, Bm, dtype, mode, inject=B.Fault(i, j, bit, k_after))
+        if k_after == -2:
+            C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit)
+        else:
+            part = parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)]
+            C_bad = oracle.inject(A, Bm, C_ref, dtype, i, j, bit, k_after=k_after, k_set=part)
+        if not fp:
+            assert got.flag == 1
+            assert np.array_equal(got.C, ((C_bad + 2 ** 31) % 2 ** 32) - 2 ** 31)
+            seen["must"] += 1
             continue
-        tau = oracle.tolerance(K, oracle.frob(Cs_bad, r0, r0 + tm, c0, c0 + tn), dtype, scheme=2)
-        if not math.isfinite(Cs_bad[i, j]):
-            assert res.flag == 1
-        elif abs(chk.residual) >= 2 * tau:
-            assert res.flag == 1, (abs(chk.residual), tau)
-        elif abs(chk.residual) <= tau / 2:
-            assert res.flag == 0, (abs(chk.residual), tau)
+        r0, c0 = i // tm * tm, j // tn * tn
+        region = (r0, min(r0 + tm, M), c0, min(c0 + tn, N))
+        if mode == B.GLOBAL:
+            chk = oracle.region_check(A, Bm, C_bad, dtype, *region)
+        else:
+            chk = (oracle.replica_check if mode == B.REPLICA else oracle.tile_check)(A, Bm, C_bad, dtype, *region)
+        if not math.isfinite(C_bad[i, j]):
+            assert got.flag == 1
+        elif abs(chk.residual) >= 2 * chk.tau + resid0:
+            assert got.flag == 1, (abs(chk.residual), chk.tau)
+            seen["must"] += 1
+        elif abs(chk.residual) <= chk.tau / 2 - resid0:
+            assert got.flag == 0, (abs(chk.residual), chk.tau)
+            seen["mustnot"] += 1
+    assert seen["must"] > 0
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])

@@ -259,32 +259,28 @@ def test_global_tolerance_has_the_bias_term():
     assert one.tau == pytest.approx(whole.tau) and one.rhs == pytest.approx(whole.rhs, rel=1e-13)
 
 
-def test_sliced_thread_check_matches_unsliced_on_clean_data_and_sees_faults():
-    M, N, K = 24, 40, 96
+def test_fault_in_an_accumulator_that_holds_a_subset_of_k():
+    """inject(k_set=...): with the set a contiguous range it is the k_begin / k_after form; with an
+    interleaved set the corrupted value is flip(sum over the set below k_after) + every other
+    product, checked against a direct evaluation over the integers."""
+    M, N, K = 6, 7, 96
     for dtype in ("i8", "f16"):
         A, B = wl.gemm_operands(M, N, K, dtype, seed=15)
         C = oracle.gemm(A, B, dtype)
-        slices = [(0, 32), (32, 64), (64, 96)]
-        flag, checks, total = oracle.thread_check_sliced(A, B, dtype, 16, 32, slices)
-        assert not flag and len(checks) == 3 * 2 * 2
-        if dtype == "i8":
-            assert np.array_equal(total, C)
-            assert sum(c.lhs for c in checks) == int(C.sum())
-        else:
-            assert np.allclose(total, C, rtol=1e-13, atol=1e-13)
-        # a mid-loop fault in the second slice: only that slice's tile sees it
-        flag, checks, bad = oracle.thread_check_sliced(A, B, dtype, 16, 32, slices, fault=(5, 33, 30, 48))
-        assert flag and sum(c.flag for c in checks) == 1
-        want = oracle.inject(A, B, C, dtype, 5, 33, 30, k_after=48, k_begin=32)
-        if dtype == "i8":
-            assert np.array_equal(bad, want)
-        else:
-            assert np.array_equal(np.isfinite(bad), np.isfinite(want))
-        # final flip lands in the last slice's accumulator
-        _, _, bad2 = oracle.thread_check_sliced(A, B, dtype, 16, 32, slices, fault=(0, 0, 3, -1))
-        want2 = oracle.inject(A, B, C, dtype, 0, 0, 3, k_after=-1, k_begin=64)
-        assert np.allclose(bad2, want2, rtol=1e-12, atol=1e-12)
-    assert oracle.slice_of([(0, 32), (32, 64)], 32) == 1
+        a = oracle.inject(A, B, C, dtype, 5, 3, 30, k_after=48, k_begin=32)
+        b = oracle.inject(A, B, C, dtype, 5, 3, 30, k_after=48, k_set=range(32, 96))
+        assert np.allclose(a, b, rtol=1e-12, atol=1e-12, equal_nan=True)
+        whole = oracle.inject(A, B, C, dtype, 0, 0, 3, k_set=range(K))
+        assert np.allclose(whole, oracle.inject(A, B, C, dtype, 0, 0, 3), rtol=1e-12, atol=1e-12)
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=16)
+    C = oracle.gemm(A, B, "i8")
+    part = [k for k in range(K) if (k // 16) % 4 == 1]
+    got = oracle.inject(A, B, C, "i8", 2, 4, 9, k_after=64, k_set=part)
+    head = sum(int(A[2, k]) * int(B[k, 4]) for k in part if k < 64)
+    want = C.copy()
+    want[2, 4] = oracle.flip_bit(head, 9, "i8") + (int(C[2, 4]) - head)
+    assert np.array_equal(got, want)
+    assert oracle.part_of([part, [0]], 17) == 0
 
 
 # ------------------------------------------------------------------ replication (Sec. 5.1)

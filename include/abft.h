@@ -154,6 +154,25 @@ int abft_gemm(int M, int N, int K, const void *A, int64_t lda, const void *B, in
               void *workspace, size_t workspace_bytes, uint32_t *fault_flag, abft_report_t *report,
               const abft_fault_t *inject, void *stream);
 
+/* abft_gemm for callers that cannot allocate device memory or pass a workspace: code under HIP
+ * graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments and
+ * results as abft_gemm without `workspace`: the global scheme's scratch (partial checksum dot
+ * products; the weight checksums when `beta` is NULL) lives in an array of
+ * abft_static_scratch_bytes() bytes (8 MiB) inside the library, one copy per GPU the library
+ * runs on, held until the process ends.  The call allocates nothing.  A product that needs more
+ * scratch than that (beyond about 8192^3 with `beta` given) returns ABFT_E_WORKSPACE and
+ * launches nothing.  Nothing in the array needs to be zero: every byte a call reads was written
+ * earlier in the same call.  All calls on one GPU share its array, so calls that may overlap
+ * there (different streams, different host threads) race: order them on one stream.  The first
+ * call on a device looks the array's address up (not a stream operation: make that call outside
+ * graph capture). */
+int abft_gemm_static(int M, int N, int K, const void *A, int64_t lda, const void *B, int64_t ldb,
+                     int b_layout, void *C, int64_t ldc, int dtype, int mode, const void *beta,
+                     uint32_t *fault_flag, abft_report_t *report, const abft_fault_t *inject,
+                     void *stream);
+/* Size of that array in bytes. */
+size_t abft_static_scratch_bytes(void);
+
 /* Same for a convolution executed as an implicit matrix product (Sec. 2.1): x is
  * the NHWC activation tensor; B holds the filters as the K x N matrix described at
  * abft_conv_t; C is (batch*OH*OW) x N row-major, i.e. the NHWC output. */

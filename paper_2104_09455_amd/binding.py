@@ -56,7 +56,7 @@ EXPORTS = [
     "abft_plan_mode", "abft_plan_times", "abft_plan_destroy", "abft_strerror", "abft_version",
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
     "abft_plan_run_all", "abft_plan_set_mode", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
-    "abft_plan_set_activation", "abft_plan_activation",
+    "abft_plan_set_activation", "abft_plan_activation", "abft_gemm_static", "abft_static_scratch_bytes",
 ]
 
 _lib = None
@@ -75,6 +75,11 @@ def lib() -> ctypes.CDLL:
     L.abft_gemm.restype = ci
     L.abft_gemm.argtypes = [ci, ci, ci, vp, i64, vp, i64, ci, vp, i64, ci, ci, vp, vp, sz, vp, vp,
                             ctypes.POINTER(Fault), vp]
+    L.abft_gemm_static.restype = ci
+    L.abft_gemm_static.argtypes = [ci, ci, ci, vp, i64, vp, i64, ci, vp, i64, ci, ci, vp, vp, vp,
+                                   ctypes.POINTER(Fault), vp]
+    L.abft_static_scratch_bytes.restype = sz
+    L.abft_static_scratch_bytes.argtypes = []
     L.abft_conv.restype = ci
     L.abft_conv.argtypes = [ctypes.POINTER(Conv), ci, vp, vp, i64, ci, vp, i64, ci, ci, vp, vp, sz, vp, vp,
                             ctypes.POINTER(Fault), vp]
@@ -256,6 +261,17 @@ def abft_gemm(M, N, K, A, lda, B, ldb, b_layout, C, ldc, dtype, mode, beta=None,
     _check(lib().abft_gemm(M, N, K, _ptr(A), lda, _ptr(B), ldb, b_layout, _ptr(C), ldc, dtype, mode,
                            _ptr(beta), _ptr(workspace), workspace_bytes, _ptr(fault_flag), _ptr(report),
                            ip, _stream(stream)))
+
+
+def abft_gemm_static(M, N, K, A, lda, B, ldb, b_layout, C, ldc, dtype, mode, beta=None, fault_flag=None,
+                     report=None, inject: Optional[Fault] = None, stream=None) -> None:
+    ip = ctypes.byref(inject) if inject is not None else None
+    _check(lib().abft_gemm_static(M, N, K, _ptr(A), lda, _ptr(B), ldb, b_layout, _ptr(C), ldc, dtype, mode,
+                                  _ptr(beta), _ptr(fault_flag), _ptr(report), ip, _stream(stream)))
+
+
+def abft_static_scratch_bytes() -> int:
+    return lib().abft_static_scratch_bytes()
 
 
 def abft_conv(conv: Conv, N, x, B, ldb, b_layout, C, ldc, dtype, mode, beta=None, workspace=None,

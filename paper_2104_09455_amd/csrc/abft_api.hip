@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <algorithm>
 #include <cstring>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -46,6 +47,28 @@ double g_cmr_override[3] = {0.0, 0.0, 0.0};
 
 // optional events recorded around the GEMM kernel launch (abft_set_kernel_events)
 thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
+
+// Scratch of abft_gemm_static: one array per GPU the library runs on, held until the process
+// ends.  The name below is only a host-side stand-in for the array; its device address is asked
+// for once per device (scratch_of_current_device) and that pointer is what kernels are given.
+constexpr size_t STATIC_SCRATCH_BYTES = 8u << 20;
+__device__ __align__(256) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
+constexpr int MAX_DEVICES = 64;
+void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
+std::mutex g_scratch_mutex;
+
+// device address of this GPU's copy of the scratch array (null: the runtime refused)
+void* scratch_of_current_device() {
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return nullptr;
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(g_static_scratch)) != hipSuccess) return nullptr;
+        g_scratch_ptr[dev] = ptr;
+    }
+    return g_scratch_ptr[dev];
+}
 
 inline int esize(int dt) { return dt == ABFT_I8 ? 1 : 2; }
 inline int csize(int dt) { return dt == ABFT_I8 ? 4 : 2; }
@@ -916,6 +939,23 @@ int abft_gemm(int M, int N, int K, const void* A, int64_t lda, const void* B, in
     return run_problem(pr, mode, beta, workspace, workspace_bytes, fault_flag, report, inject,
                        reinterpret_cast<hipStream_t>(stream));
 }
+
+int abft_gemm_static(int M, int N, int K, const void* A, int64_t lda, const void* B, int64_t ldb, int b_layout,
+                     void* C, int64_t ldc, int dtype, int mode, const void* beta, uint32_t* fault_flag,
+                     abft_report_t* report, const abft_fault_t* inject, void* stream) {
+    Problem pr;
+    std::memset(&pr, 0, sizeof pr);
+    pr.M = M; pr.N = N; pr.K = K; pr.dtype = dtype; pr.b_layout = b_layout;
+    pr.A = A; pr.lda = lda; pr.B = B; pr.ldb = ldb; pr.C = C; pr.ldc = ldc;
+    pr.conv = false;
+    void* scratch = scratch_of_current_device();
+    if (!scratch) return ABFT_E_HIP;
+    // (a product whose scratch does not fit comes back as ABFT_E_WORKSPACE before anything is launched)
+    return run_problem(pr, mode, beta, scratch, STATIC_SCRATCH_BYTES, fault_flag, report, inject,
+                       reinterpret_cast<hipStream_t>(stream));
+}
+
+size_t abft_static_scratch_bytes(void) { return STATIC_SCRATCH_BYTES; }
 
 int abft_conv(const abft_conv_t* conv, int N, const void* x, const void* B, int64_t ldb, int b_layout, void* C,
               int64_t ldc, int dtype, int mode, const void* beta, void* workspace, size_t workspace_bytes,

@@ -1,7 +1,7 @@
 #!/usr/bin/env python3
 """Benchmark of the ABFT-protected GEMM path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload dlrm|resnet50|square] [--no-extras]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload square|dlrm|resnet50] [--no-extras]
 
 A step is one pass of the whole protected path over one batch of synthetic input:
 every linear layer of the workload runs through ``abft_gemm`` / ``abft_conv`` with the
@@ -354,47 +354,154 @@ def chain_leg(gen, batch=256, steps=300):
     return res
 
 
-def cpu_baseline(runs, budget_s=15.0):
+def cpu_baseline(runs, budget_s=12.0):
+    """The oracle as it stands on a bounded sample of the workload: row blocks of A (whole images
+    for a convolution) through the fp64 / int64 triple-loop product and the checksum scheme the
+    selector picks, layer after layer until about budget_s seconds of CPU work are spent."""
     import oracle
     from oracle import build as obuild
     if not os.path.exists(os.path.join(ROOT, "oracle", "libabft_oracle.so")):
         obuild.build()
+
+    def host(t, dtype):
+        t = t.cpu()
+        return t.numpy() if dtype == "i8" else t.view(torch.int16).numpy().view(np.float16 if dtype == "f16" else np.uint16)
+
     t_used, flops, desc = 0.0, 0.0, []
     for lr in runs:
         L = lr.layer
         if t_used >= budget_s:
             break
-        # bound the work per layer: the first rows of A that keep M*N*K <= 4e9 multiply-adds
-        m_s = int(max(1, min(L.M, 4e9 // (L.N * L.K))))
-        A = lr.A
-        if lr.conv is not None:
-            c = L.conv
-            imgs = max(1, min(c.batch, math.ceil(m_s / (c.OH * c.OW))))
-            x = A[:imgs].cpu()
-            xs = x.view(torch.int16).numpy().view(np.float16 if lr.dtype == "f16" else np.uint16) if lr.dtype != "i8" else x.numpy()
-            t0 = time.perf_counter()
-            Aw = oracle.im2col(xs, lr.dtype, c.KH, c.KW, c.stride, c.pad)
-            m_s = Aw.shape[0]
-        else:
-            a = A[:m_s].cpu()
-            Aw = a.view(torch.int16).numpy().view(np.float16 if lr.dtype == "f16" else np.uint16) if lr.dtype != "i8" else a.numpy()
-            t0 = time.perf_counter()
-        b = lr.B.cpu()
-        Bw = b.view(torch.int16).numpy().view(np.float16 if lr.dtype == "f16" else np.uint16) if lr.dtype != "i8" else b.numpy()
-        Bw = np.ascontiguousarray(Bw.T)  # K x N, the oracle's orientation
-        Cw = oracle.gemm(Aw, Bw, lr.dtype)
-        if lr.pick == B.GLOBAL:
-            oracle.global_check(Aw, Bw, Cw, lr.dtype)
-        else:
-            tm, tn, _ = B.abft_tile_shape(L.M, L.N, L.K, lr.dt, True)
-            oracle.thread_check(Aw, Bw, Cw, lr.dtype, tm, tn)
-        t_used += time.perf_counter() - t0
-        flops += 2.0 * m_s * L.N * L.K
-        desc.append(f"{L.name}:{m_s}/{L.M} rows")
+        Bw = np.ascontiguousarray(host(lr.B, lr.dtype).T)  # K x N, the oracle's orientation
+        done = 0
+        # blocks of about 2e9 multiply-adds, at most 4096 rows of a layer
+        step = int(max(1, min(L.M, 2e9 // (L.N * L.K))))
+        while done < min(L.M, 4096) and t_used < budget_s:
+            if lr.conv is not None:
+                c = L.conv
+                per = c.OH * c.OW
+                img0 = done // per
+                imgs = max(1, min(c.batch - img0, math.ceil(step / per)))
+                xs = host(lr.A[img0:img0 + imgs], lr.dtype)
+                t0 = time.perf_counter()
+                Aw = oracle.im2col(xs, lr.dtype, c.KH, c.KW, c.stride, c.pad)
+            else:
+                Aw = host(lr.A[done:done + step], lr.dtype)
+                t0 = time.perf_counter()
+            Cw = oracle.gemm(Aw, Bw, lr.dtype)
+            if lr.pick == B.GLOBAL:
+                oracle.global_check(Aw, Bw, Cw, lr.dtype)
+            else:
+                tm, tn, _ = B.abft_tile_shape(L.M, L.N, L.K, lr.dt, True)
+                oracle.thread_check(Aw, Bw, Cw, lr.dtype, tm, tn)
+            t_used += time.perf_counter() - t0
+            flops += 2.0 * Aw.shape[0] * L.N * L.K
+            done += Aw.shape[0]
+        desc.append(f"{L.name}:{done}/{L.M} rows")
     return {"value": round(flops / t_used / 1e12, 6), "unit": "TFLOP/s", "cores": oracle.threads(),
             "kind": "oracle", "seconds": round(t_used, 2),
             "sample": "fp64 triple-loop GEMM + the selected checksum scheme on " + ", ".join(desc[:12]) +
                       (" ..." if len(desc) > 12 else "")}
+
+
+# --------------------------------------------------------------------------- #
+# the comparison tolerance, stated as a number per configuration
+# --------------------------------------------------------------------------- #
+def _report_of(lr: "LayerRun", mode: int):
+    rep = torch.zeros(ctypes.sizeof(B.Report), dtype=torch.uint8, device="cuda:0")
+    lr.flag.zero_()
+    L = lr.layer
+    if lr.conv is not None:
+        B.abft_conv(lr.conv, L.N, lr.A, lr.B, L.K, B.B_NK, lr.C, L.N, lr.dt, mode, beta=lr.beta, workspace=lr.ws,
+                    workspace_bytes=lr.wsb, fault_flag=lr.flag, report=rep)
+    else:
+        B.abft_gemm(L.M, L.N, L.K, lr.A, L.K, lr.B, L.K, B.B_NK, lr.C, L.N, lr.dt, mode, beta=lr.beta,
+                    workspace=lr.ws, workspace_bytes=lr.wsb, fault_flag=lr.flag, report=rep)
+    torch.cuda.synchronize()
+    return B.Report.from_buffer_copy(rep.cpu().numpy().tobytes()), int(lr.flag.item())
+
+
+def tolerance_row(lr: "LayerRun", mode: int, label: str):
+    """tau of the comparison with the largest residual / tau in one clean run, as the device formed
+    it: tau = coeff * ||C_S||_F + bias_coeff * ||C_S||_1 over the region S (workgroup tile for the
+    global scheme, wavefront tile for the thread-level one).  min_flagged_over_rms: the smallest
+    change of one element of C that must be flagged (2 tau), in units of the region's rms(C)."""
+    L = lr.layer
+    if lr.dtype == "i8":
+        return {"config": label, "dtype": "i8", "scheme": B.MODE_NAMES[mode], "tau": 0.0,
+                "note": "exact integer comparison: every single-bit flip changes the sum"}
+    rep, flagged = _report_of(lr, mode)
+    aligned = ((L.conv.Cin if L.conv else L.K) * 2) % 16 == 0
+    rm, rn = (B.abft_region_shape(L.M, L.N, L.K, lr.dt, aligned) if mode == B.GLOBAL
+              else B.abft_tile_shape(L.M, L.N, L.K, lr.dt, aligned)[:2])
+    n_el = min(rm, L.M) * min(rn, L.N)
+    rms = rep.frob / math.sqrt(n_el) if n_el else 0.0
+    return {"config": label, "dtype": lr.dtype, "scheme": B.MODE_NAMES[mode], "region": [rm, rn], "K": L.K,
+            "coeff": B.abft_tolerance_coeff(L.K, lr.dt, mode), "bias_coeff": B.abft_tolerance_bias_coeff(L.K, lr.dt, mode),
+            "tau": float(f"{rep.tau:.4g}"), "frob_region": float(f"{rep.frob:.4g}"), "rms_region": float(f"{rms:.4g}"),
+            "clean_residual_over_tau": round(rep.worst_ratio, 3),
+            "min_flagged_over_rms": float(f"{(2 * rep.tau / rms) if rms else 0.0:.3g}"), "comparisons": rep.tiles,
+            "false_alarm": flagged}
+
+
+def tolerance_leg(gen):
+    """One row per benchmark configuration (representative layers; the scheme the selector picks)."""
+    rows = []
+    def add(layer, dtype, label, da="uniform_01", db="weights", modes=None):
+        lr = LayerRun(layer, dtype, gen, da, db)
+        for m in (modes or (lr.pick,)):
+            rows.append(tolerance_row(lr, m, label))
+        del lr
+        torch.cuda.empty_cache()
+    add(wl.Layer("sq64", 64, 64, 64), "f16", "configs[0] 64^3 U[-1,1]", "uniform_pm1", "uniform_pm1", (B.GLOBAL, B.THREAD))
+    add(wl.Layer("sq64", 64, 64, 64), "i8", "configs[0] 64^3 int8", modes=(B.GLOBAL,))
+    for b in (1, 16, 256):
+        add(wl.dlrm_layers(b)[4], "f16", f"configs[1] DLRM top1 batch {b}")
+    for b in (1, 64):
+        layers = wl.resnet50_layers(b)
+        add(layers[0], "f16", f"configs[2] ResNet-50 conv1 batch {b}")
+        add(layers[28], "f16", f"configs[2] ResNet-50 {layers[28].name} batch {b}")
+        add(layers[-2], "f16", f"configs[2] ResNet-50 {layers[-2].name} batch {b}")
+    for n, dts in ((4096, ("f16", "bf16")), (8192, ("f16", "bf16", "i8"))):
+        for d in dts:
+            add(wl.Layer(f"sq{n}", n, n, n), d, f"configs[3] {n}^3 N(0,1)", "normal", "normal")
+    for m in (1, 256, 512, 8192):
+        add(wl.Layer(f"m{m}", m, 4096, 4096), "f16", f"configs[4] M={m}, N=K=4096 N(0,1)", "normal", "normal")
+    return rows
+
+
+def noise_study(gen):
+    """How large the clean residual of a comparison gets on this GPU, in the units the tolerance is
+    written in: max over seeds and regions of |lhs - rhs| / (2^-24 sqrt(K) ||C_S||_F) (the random-walk
+    part; the tolerance allows 8) and, for the global scheme, of |lhs - rhs| / (2^-24 K ||C_S||_1) (the
+    same-sign drift; the tolerance adds 1e-3 of it).  From the device's own report of the worst region."""
+    u = 2.0 ** -24
+    out = []
+    shapes = ((256, 256, 64), (256, 256, 1024), (1024, 1024, 1024), (1024, 1024, 8192), (4096, 4096, 4096),
+              (2048, 2048, 16384), (8192, 8192, 8192))
+    dists = (("normal", "normal"), ("uniform_pm1", "uniform_pm1"), ("uniform_01", "weights"), ("uniform_01", "uniform_01"))
+    for dtype in ("f16", "bf16"):
+        for da, db in dists:
+            for (M, N, K) in shapes:
+                seeds = 2 if M >= 4096 else 6
+                for mode in (B.GLOBAL, B.THREAD):
+                    walk = drift = ratio = 0.0
+                    flags = 0
+                    for sd in range(seeds):
+                        lr = LayerRun(wl.Layer("n", M, N, K), dtype, gen, da, db)
+                        rep, fl = _report_of(lr, mode)
+                        res = abs(rep.lhs - rep.rhs)
+                        walk = max(walk, res / (u * math.sqrt(K) * rep.frob) if rep.frob else 0.0)
+                        if mode == B.GLOBAL and rep.l1:
+                            drift = max(drift, res / (u * K * rep.l1))
+                        ratio = max(ratio, rep.worst_ratio)
+                        flags += fl
+                        del lr
+                    out.append({"dtype": dtype, "A": da, "B": db, "M": M, "N": N, "K": K, "scheme": B.MODE_NAMES[mode],
+                                "residual_over_u_sqrtK_frob": round(walk, 3), "residual_over_u_K_l1": float(f"{drift:.3g}"),
+                                "residual_over_tau": round(ratio, 3), "false_alarms": flags})
+                    torch.cuda.empty_cache()
+    return out
 
 
 # --------------------------------------------------------------------------- #
@@ -416,7 +523,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None)
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="dlrm", choices=["dlrm", "resnet50", "square"])
+    ap.add_argument("--workload", default="square", choices=["dlrm", "resnet50", "square"])
+    ap.add_argument("--noise-study", action="store_true",
+                    help="only measure the clean residuals of the comparisons against the units of the tolerance "
+                         "and print them as one JSON line")
     ap.add_argument("--no-extras", action="store_true", help="skip the short legs for the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--all-layers", action="store_true", help="print every row of the per-layer table")
@@ -446,6 +556,10 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+
+    if args.noise_study:
+        print(json.dumps({"noise_study": noise_study(gen)}))
+        return
 
     label, runs, dtype = build_workload(args.workload, gen)
     defaults = {"dlrm": (1000, 100), "resnet50": (20, 3), "square": (20, 3)}[args.workload]
@@ -518,11 +632,14 @@ def main():
     # where the global scheme runs one), replayed back to back from a graph (per-layer table): what a
     # kernel trace shows; the bracket in the timed region also holds the dispatch gap of an eager launch
     alone_us = rows[dom_i]["us_" + B.MODE_NAMES[dom.pick]]
+    if tk is not None:
+        roof["traffic_source"] = "looked up: rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under profiles/ (not read in this run)"
     roof.update({"kernel": f"gemm_kernel[{B.MODE_NAMES[dom.pick]}] on {dom.layer.name} "
                            f"(M={dom.layer.M},N={dom.layer.N},K={dom.layer.K})",
                  "avg_launch_us": round(kern_us, 3),
                  "call_device_us": alone_us,
                  "achieved_call_device": round((dom.flops / 1e12 if compute_bound else dom.bytes / 1e9) / (alone_us * 1e-6), 2),
+                 "frac_call_device": round((dom.flops / PEAK[dtype] if compute_bound else dom.bytes / HBM) / (alone_us * 1e-6), 4),
                  "algorithmic_per_launch": dom.flops if compute_bound else dom.bytes})
 
     # whole passes replayed from one graph each: protected (selector's picks), then unprotected
@@ -633,18 +750,26 @@ def main():
             "unprotected_ms_per_step": None if graph_none_ms is None else round(graph_none_ms, 5)},
         "graph_replay_error": graph_ms if isinstance(graph_ms, str) else None,
         "roofline": roof,
+        "tolerance": None,
         "summary": summarize(rows),
         "layers": rows if (len(rows) <= 16 or args.all_layers) else rows[:3] + [{"...": f"{len(rows) - 6} more"}] + rows[-3:],
         "paper_context": "NVIDIA T4, FP16: DLRM MLP-Bottom/Top batch 1 overhead 5.16/5.61 % (intensity-guided) vs "
                          "23.50/18.16 % (global); ResNet-50 HD 4.21 % vs 8.49 %; square 2048^3 global 1 %, thread 14 %",
     }
 
+    try:
+        out["tolerance"] = tolerance_leg(gen)
+    except Exception as e:  # reported, never fatal
+        out["tolerance"] = {"error": repr(e)}
+
     if not args.no_extras:
         extra = {}
         try:
-            if args.workload != "square":
-                for n, dts in ((4096, ("f16", "bf16")), (8192, ("f16", "bf16", "i8"))):
-                    for d in dts:
+            for n, dts in ((4096, ("f16", "bf16")), (8192, ("f16", "bf16", "i8"))):
+                for d in dts:
+                    if args.workload == "square" and (n, d) == (8192, "f16"):
+                        continue   # the headline itself
+                    if True:
                         lr = LayerRun(wl.Layer(f"sq{n}", n, n, n), d, gen, "normal", "normal")
                         r = layer_table(hip, [lr], 20 if n <= 4096 else 10, 3, stream)[0]
                         extra[f"square{n}_{d}"] = {k: r[k] for k in ("pick", "us_none", "ovh_global_pct", "ovh_thread_pct",

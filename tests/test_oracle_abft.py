@@ -259,6 +259,78 @@ def test_global_tolerance_has_the_bias_term():
     assert one.tau == pytest.approx(whole.tau) and one.rhs == pytest.approx(whole.rhs, rel=1e-13)
 
 
+def _accumulate_binary32(A, B):
+    """C = A.B with one binary32 accumulator per entry that takes the K products in ascending k,
+    one round-to-nearest add each (a product of two fp16 / bf16 values is exact in binary32)."""
+    A32, B32 = A.astype(np.float32), B.astype(np.float32)
+    acc = np.zeros((A.shape[0], B.shape[1]), dtype=np.float32)
+    for k in range(A.shape[1]):
+        acc += A32[:, k:k + 1] * B32[k:k + 1, :]
+    return acc.astype(np.float64)
+
+
+@pytest.mark.parametrize("K", [64, 1024, 4096])
+def test_tolerance_constant_against_simulated_binary32_accumulation_and_the_rigorous_bound(K):
+    """C_TOL from both sides, with nothing of the GPU path involved.  Below: a simulated binary32
+    accumulation (plain IEEE arithmetic in numpy) of a 32 x 64 region leaves a residual of the
+    output summation against the exact checksum product that stays under a quarter of tau, for
+    zero-mean and for same-sign operands.  Above: for same-sign operands tau is at most a tenth of
+    the first-order worst-case bound K u sum|a||b| of Higham's analysis of recursive summation, so
+    the comparison is a real test and not the trivial one; and tau is never below 8 u ||C||_F."""
+    M, N = 32, 64
+    u = 2.0 ** -24
+    for da, db in (("normal", "normal"), ("uniform_pm1", "uniform_pm1"), ("uniform_01", "weights"), ("uniform_01", "uniform_01")):
+        worst = 0.0
+        for seed in range(6):
+            A, B = wl.gemm_operands(M, N, K, "f16", seed=900 + seed, dist_a=da, dist_b=db)
+            C32 = _accumulate_binary32(A, B)
+            for scheme in (1, 2):
+                tau = oracle.tolerance(K, oracle.frob(C32), "f16", scheme=scheme, l1_norm=oracle.l1norm(C32))
+                chk = oracle.region_check(A, B, C32, "f16", 0, M, 0, N)
+                worst = max(worst, abs(chk.residual) / tau)
+                assert tau >= 8 * u * oracle.frob(C32)
+                if da == "uniform_01" and db == "uniform_01" and K >= 1024:
+                    assert tau <= 0.1 * K * u * oracle.s_abs(A, B, "f16")
+        assert worst < 0.25, (da, db, worst)
+
+
+def test_drift_term_is_a_thousandth_of_the_worst_case_for_same_sign_data():
+    """C_BIAS: for operands of one sign sum|a||b| = ||C||_1, so the second term of the global
+    tolerance is exactly 1e-3 of the first-order worst-case rounding bound K u ||C||_1."""
+    K = 512
+    A, B = wl.gemm_operands(16, 16, K, "f16", seed=3, dist_a="uniform_01", dist_b="uniform_01")
+    C = oracle.gemm(A, B, "f16")
+    l1 = oracle.l1norm(C)
+    assert l1 == pytest.approx(oracle.s_abs(A, B, "f16"), rel=1e-12)
+    drift = oracle.tolerance(K, 0.0, "f16", scheme=1, l1_norm=l1)
+    assert drift == pytest.approx(1e-3 * K * 2.0 ** -24 * oracle.s_abs(A, B, "f16"), rel=1e-12)
+    assert oracle.tolerance(K, 0.0, "f16", scheme=2, l1_norm=l1) == 0.0
+
+
+def test_precision_of_a_checksum_handed_on_in_pieces():
+    """U_CHI: a binary32 sum of a few fp16 values written as hi + 2^-11 lo with hi = fl16(s) and
+    lo = fl16((s - hi) 2^11) is within 2^-22 |s| of s; a binary32 sum of bf16 values written as
+    three bf16 pieces hi + mid + lo is within 2^-23 |s| (exact, in fact).  Plain numpy conversions."""
+    rng = np.random.default_rng(5)
+    for trial in range(200):
+        n = int(rng.integers(2, 5))
+        v = wl.random_matrix((n, 4096), "f16", ("normal", "uniform_01", "weights")[trial % 3], 7000 + trial)
+        s = v.astype(np.float32).sum(axis=0, dtype=np.float32)          # exact: a few fp16 values
+        hi = s.astype(np.float16)
+        lo = ((s - hi.astype(np.float32)) * np.float32(2048)).astype(np.float16)
+        back = hi.astype(np.float64) + lo.astype(np.float64) / 2048.0
+        big = np.abs(s) >= 2.0 ** -10          # (below that the low piece is a subnormal fp16)
+        assert np.all(np.abs(back - s.astype(np.float64))[big] <= oracle.U_CHI["f16"] * np.abs(s.astype(np.float64))[big])
+        b = wl.bf16_bits_to_f32(wl.random_matrix((n, 4096), "bf16", "normal", 8000 + trial))
+        sb = b.sum(axis=0, dtype=np.float32)
+        p0 = wl.bf16_bits_to_f32(wl.to_bf16_bits(sb))
+        r1 = sb - p0
+        p1 = wl.bf16_bits_to_f32(wl.to_bf16_bits(r1))
+        p2 = wl.bf16_bits_to_f32(wl.to_bf16_bits(r1 - p1))
+        backb = p0.astype(np.float64) + p1.astype(np.float64) + p2.astype(np.float64)
+        assert np.all(np.abs(backb - sb.astype(np.float64)) <= oracle.U_CHI["bf16"] * np.abs(sb.astype(np.float64)))
+
+
 def test_fault_in_an_accumulator_that_holds_a_subset_of_k():
     """inject(k_set=...): with the set a contiguous range it is the k_begin / k_after form; with an
     interleaved set the corrupted value is flip(sum over the set below k_after) + every other

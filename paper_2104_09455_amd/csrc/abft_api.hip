@@ -113,7 +113,6 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         if (fast_ok && N > 128 && nkt_all > 1 && rounds_full && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
             return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
         const bool fills128 = tiles(CFG_F128) >= 128;
-        const bool wave_level_wide = mode == ABFT_THREAD;
         if (fast_ok && fills128 && N < 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
         // Few tiles: the time is the latency of a workgroup's k loop and the rate at which one
         // compute unit can stream its operands, so the streaming configurations take over (no
@@ -121,9 +120,9 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // still fits the chip in one round of workgroups, 64 x 64 for up to two rounds (that one
         // only with a k loop of at least one tile per wavefront, sixteen tiles (thread-level: eight) for a second round:
         // the idle wavefronts of a short loop cost more than the barriers they save; 3000 x 384 x
-        // 384 takes 9.9 us on 282 such tiles, 8.2 us on 64 x 128 tiles).  The thread-level scheme never takes the
-        // 32 x 32 tile when it can have 32 x 64 (its checksum then needs no cross-lane step).
-        if (tiles(CFG_S32) <= 256) return (wave_level_wide && N > 32) ? CFG_S64 : CFG_S32;
+        // 384 takes 9.9 us on 282 such tiles, 8.2 us on 64 x 128 tiles).  (On the 32 x 32 tile the thread-level
+        // scheme's checksum operand is the B fragment itself: no vector work at all.)
+        if (tiles(CFG_S32) <= 256) return CFG_S32;
         if (tiles(CFG_S64) <= 256) return CFG_S64;
         if (tiles(CFG_S128) <= 256 ? nkt_all >= 4 : (tiles(CFG_S128) <= 512 && nkt_all >= (mode == ABFT_THREAD ? 8 : 16))) return CFG_S128;
         if (fast_ok) {

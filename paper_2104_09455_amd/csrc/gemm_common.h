@@ -284,100 +284,22 @@ __device__ __forceinline__ i32x4 gather16(const char* base, long long stride_byt
 }
 
 // ---------------------------------------------------------------------------
-// Tile-local weight checksum for the thread-level scheme (Sec. 5.2.1-5.2.2).
-// Input: the TN B-fragments of this k-step (lane = column within the fragment).
-// Output: one B-operand fragment whose columns carry the checksum
-//   chi[k] = sum over the wave tile's columns of B[k][.]
-// split into exactly representable parts, after folding the fragment's columns
-// onto NCOL distinct partial-sum columns with cross-lane moves (registers only):
-//   fp16 : columns [0,H) hold fl16(s), columns [H,2H) hold fl16((s - hi) * 2^11)
-//   bf16 : four groups: hi, mid, lo (three bf16 pieces = 24 bits), zero
-//   int8 : columns [0,H) hold the low signed byte of s, [H,2H) the rest / 256
-// where H = MI/2 (MI/4 for bf16).  Summing the result columns with the matching
-// weights gives sum_k A[i][k] chi[k] (see tile_rhs_weight).
+// Tile-local weight checksum for the thread-level scheme (Sec. 5.2.1-5.2.2): per k step the
+// checksum of the wavefront tile's B fragments,
+//   chi[k] = sum over the wave tile's columns of B[k][.],
+// goes to the matrix unit as extra B operand(s), multiplied with every A fragment.  A lane holds
+// one column of each of the TN fragments (MFMA block columns), so the vector unit adds the TN
+// fragments element by element and the matrix unit finishes the sum over the 32 columns of
+// the block: summing the checksum accumulators over their columns at the end gives
+// sum_k A[i][k] chi[k].
+//  * Plain form (TN = 1): nothing to add, the operand is the fragment itself (one block
+//    column per wavefront tile: the scheme coincides with replication, Table 1's M_t / 2 extra
+//    MMAs being all of them).
+//  * Split form (TN >= 2): the element-wise sums are handed on in exactly representable
+//    pieces, one operand and one set of accumulators per piece (below).
 // ---------------------------------------------------------------------------
-template <int DT, int MI, int TN>
-struct TileChecksum {
-    static __device__ __forceinline__ i32x4 make(const i32x4 (&b)[TN], int lane) {
-        const int col = lane % MI;
-        if constexpr (DT == DT_F16) {
-            float s[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s[e] = 0.f;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                f16x8 h = bitcast<f16x8>(b[j]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) s[e] += (float)h[e];
-            }
-            f16x8 out;
-            const bool low_part = col >= MI / 2;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float t = s[e] + __shfl_xor(s[e], MI / 2);
-                _Float16 hi = (_Float16)t;
-                _Float16 lo = (_Float16)((t - (float)hi) * 2048.f);
-                out[e] = low_part ? lo : hi;
-            }
-            return bitcast<i32x4>(out);
-        } else if constexpr (DT == DT_BF16) {
-            float s[8];
-#pragma unroll
-            for (int e = 0; e < 8; ++e) s[e] = 0.f;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                bf16x8 h = bitcast<bf16x8>(b[j]);
-#pragma unroll
-                for (int e = 0; e < 8; ++e) s[e] += (float)h[e];
-            }
-            bf16x8 out;
-            const int part = col / (MI / 4);
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                float t = s[e] + __shfl_xor(s[e], MI / 2);
-                t = t + __shfl_xor(t, MI / 4);
-                __bf16 hi = (__bf16)t;
-                float d1 = t - (float)hi;
-                __bf16 mid = (__bf16)d1;
-                float d2 = d1 - (float)mid;
-                __bf16 lo = (__bf16)d2;
-                out[e] = part == 0 ? hi : (part == 1 ? mid : (part == 2 ? lo : (__bf16)0.f));
-            }
-            return bitcast<i32x4>(out);
-        } else {
-            int s[16];
-#pragma unroll
-            for (int e = 0; e < 16; ++e) s[e] = 0;
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) s[e] += (int)(signed char)(b[j][e >> 2] >> (8 * (e & 3)));
-            }
-            i32x4 out = {0, 0, 0, 0};
-            const bool high_part = col >= MI / 2;
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                int t = s[e] + __shfl_xor(s[e], MI / 2);
-                int lo = (int)(signed char)t;
-                int hi = (t - lo) >> 8;
-                int v = high_part ? hi : lo;
-                out[e >> 2] |= (v & 255) << (8 * (e & 3));
-            }
-            return out;
-        }
-    }
-    // weight of this lane's result column when the checksum product is summed
-    static __device__ __forceinline__ double rhs_weight(int lane) {
-        const int col = lane % MI;
-        if constexpr (DT == DT_F16) return col >= MI / 2 ? (1.0 / 2048.0) : 1.0;
-        if constexpr (DT == DT_BF16) return 1.0;
-        return col >= MI / 2 ? 256.0 : 1.0;
-    }
-};
-
 // ---------------------------------------------------------------------------
-// Split form of the tile checksum for fp16 (used where the wavefront tile has few rows):
-// no cross-lane step at all.  The column sums s (fp32, one per lane and k) are handed to
+// Split form of the tile checksum for fp16: no cross-lane step at all.  The column sums s (fp32, one per lane and k) are handed to
 // the matrix unit as two operands, hi = fl16(s) and lo = fl16((s - hi) * 2^11), each
 // multiplied with the A fragments into its own accumulators; the checksum product is
 // sum(hi accumulators) + 2^-11 sum(lo accumulators).  Twice the checksum MFMAs of the
@@ -585,10 +507,29 @@ struct ChecksumDot {
 // accumulators per A fragment that takes.
 template <class CFG>
 struct ChecksumForm {
-    static constexpr bool SPLIT = CFG::MI == 32 && CFG::TM <= 2 && CFG::TN >= 2;
+    static constexpr bool SPLIT = CFG::TN >= 2;
     static constexpr int NP = SPLIT ? (CFG::DT == DT_BF16 ? 3 : 2) : 1;  // checksum operands per k step
     static constexpr int NCHK = NP * CFG::TM;
 };
+// The thread-level scheme's extra MFMAs of one k step (a: A fragments, b: B fragments).
+template <class CFG>
+__device__ __forceinline__ void thread_checksum_step(const i32x4 (&a)[CFG::TM], const i32x4 (&b)[CFG::TN],
+                                                     typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[ChecksumForm<CFG>::NCHK]) {
+    typedef Mma<CFG::DT, CFG::MI> MMA;
+    constexpr int TM = CFG::TM;
+    if constexpr (ChecksumForm<CFG>::SPLIT) {
+        typedef TileChecksumSplit<CFG::DT, CFG::TN> SPL;
+        i32x4 x[SPL::NP];
+        SPL::make(b, x);
+#pragma unroll
+        for (int pc = 0; pc < SPL::NP; ++pc)
+#pragma unroll
+            for (int i = 0; i < TM; ++i) chk[pc * TM + i] = MMA::run(a[i], x[pc], chk[pc * TM + i]);
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) chk[i] = MMA::run(a[i], b[0], chk[i]);
+    }
+}
 // Redundant accumulator blocks a wavefront carries under each scheme.
 template <class CFG, int MODE>
 struct CheckRegs {
@@ -740,7 +681,6 @@ __device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long
                     r_hi += chk[i][r] >> 16;
                 }
             rsum = ((long long)r_hi << 16) + (long long)r_lo;
-            if (MODE != MODE_REPL && (lane % MI) >= MI / 2) rsum *= 256;
         }
         return rsum;
     } else {
@@ -764,7 +704,6 @@ __device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long
 #pragma unroll
                 for (int r = 0; r < MMA::NACC; r += 4)
                     rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));
-            if constexpr (MODE != MODE_REPL) rsum *= TileChecksum<CFG::DT, MI, TN>::rhs_weight(lane);
         }
         return rsum;
     }

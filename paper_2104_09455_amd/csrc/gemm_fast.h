@@ -200,7 +200,6 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-    constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
     constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
@@ -252,18 +251,8 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
-        if constexpr (MODE == MODE_THREAD && SPLIT) {
-            typedef TileChecksumSplit<DT, TN> SPL;
-            i32x4 x[SPL::NP];
-            SPL::make(fb[buf], x);
-#pragma unroll
-            for (int pc = 0; pc < SPL::NP; ++pc)
-#pragma unroll
-                for (int i = 0; i < TM; ++i) chk[pc * TM + i] = MMA::run(fa[buf][i], x[pc], chk[pc * TM + i]);
-        } else if constexpr (MODE == MODE_THREAD) {
-            i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
+        if constexpr (MODE == MODE_THREAD) {
+            thread_checksum_step<CFG>(fa[buf], fb[buf], chk);
         } else if constexpr (MODE == MODE_REPL) {
             // every product once more, all of an A fragment's into one block (Sec. 5.1)
 #pragma unroll
@@ -300,11 +289,17 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             for (int kk = 0; kk < 3; ++kk) {
                 read_frags(st, kk + 1, (kk + 1) & 1);
                 mma_step(kk & 1);
-                if constexpr (!mode_is_wave_level(MODE)) {
+                {
                     // fragment reads of the next step go out early, one per MFMA, so that the last
-                    // of them has the rest of the step's MFMAs to land; the global scheme's reads
-                    // and vector FMAs of the checksum dot product are spread between the MFMAs
-                    constexpr int NF = TM + TN, NM = TM * TN;
+                    // of them has the rest of the step's MFMAs to land; the vector work of the
+                    // protected schemes (global: reads and FMAs of the checksum dot product;
+                    // thread-level: the sums of the B fragments) is spread between the MFMAs
+                    constexpr int NF = TM + TN;
+                    constexpr int NM = TM * TN + (MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : (MODE == MODE_REPL ? TM * TN : 0));
+                    // vector instructions per MFMA slot: the tile checksum's pieces cost about 14
+                    // (fp16, int8) or 22 (bf16) instructions per 16 bytes of each lane's B fragments
+                    constexpr int VT = MODE == MODE_THREAD && ChecksumForm<CFG>::SPLIT
+                                           ? ((DT == DT_BF16 ? 22 : 14) * 4 + NM - 1) / NM : 0;
 #pragma unroll
                     for (int g = 0; g < NM; ++g) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
@@ -313,6 +308,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
                             else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                         }
                         if constexpr (GDOT) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // 2 VALU
+                        if constexpr (VT > 0) __builtin_amdgcn_sched_group_barrier(0x002, VT, 0);
                     }
                 }
             }

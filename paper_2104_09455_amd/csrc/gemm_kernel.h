@@ -202,7 +202,6 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = 0;
-    constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
     constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
@@ -239,19 +238,9 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(a[i], b[j], acc[i][j]);
-            if constexpr (MODE == MODE_THREAD && SPLIT) {
-                typedef TileChecksumSplit<CFG::DT, TN> SPL;
-                i32x4 x[SPL::NP];
-                SPL::make(b, x);
-#pragma unroll
-                for (int pc = 0; pc < SPL::NP; ++pc)
-#pragma unroll
-                    for (int i = 0; i < TM; ++i) chk[pc * TM + i] = MMA::run(a[i], x[pc], chk[pc * TM + i]);
-            } else if constexpr (MODE == MODE_THREAD) {
-                i32x4 x = TileChecksum<CFG::DT, MI, TN>::make(b, lane);
-#pragma unroll
-                for (int i = 0; i < TM; ++i) chk[i] = MMA::run(a[i], x, chk[i]);
-            } else if constexpr (MODE == MODE_REPL) {
+            if constexpr (MODE == MODE_THREAD) {
+            thread_checksum_step<CFG>(a, b, chk);
+        } else if constexpr (MODE == MODE_REPL) {
                 // every product once more, all of an A fragment's into one block (Sec. 5.1)
 #pragma unroll
                 for (int i = 0; i < TM; ++i)

@@ -224,7 +224,6 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         for (int j = 0; j < TN; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-    constexpr bool SPLIT = ChecksumForm<CFG>::SPLIT;
     constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
@@ -292,18 +291,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) gchk[i] = MMA::run(fa[buf][i], fg[buf], gchk[i]);
         }
-        if constexpr (MODE == MODE_THREAD && SPLIT) {
-            typedef TileChecksumSplit<DT, TN> SPL;
-            i32x4 x[SPL::NP];
-            SPL::make(fb[buf], x);
-#pragma unroll
-            for (int pc = 0; pc < SPL::NP; ++pc)
-#pragma unroll
-                for (int i = 0; i < TM; ++i) chk[pc * TM + i] = MMA::run(fa[buf][i], x[pc], chk[pc * TM + i]);
-        } else if constexpr (MODE == MODE_THREAD) {
-            i32x4 x = TileChecksum<DT, 32, TN>::make(fb[buf], lane);
-#pragma unroll
-            for (int i = 0; i < TM; ++i) chk[i] = MMA::run(fa[buf][i], x, chk[i]);
+        if constexpr (MODE == MODE_THREAD) {
+            thread_checksum_step<CFG>(fa[buf], fb[buf], chk);
         } else if constexpr (MODE == MODE_REPL) {
             // every product once more, all of an A fragment's into one block (Sec. 5.1)
 #pragma unroll

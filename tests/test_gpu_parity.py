@@ -76,7 +76,7 @@ CONFIG_SHAPES = [
     ((2304, 2304, 256), (32, 128), (128, 128)),    # 128 x 128 tile, more than one workgroup per compute unit: wide wavefront tiles for thread-level
     ((1536, 1536, 256), (64, 64), (128, 128)),     # at most one per compute unit: 2 x 2 wavefronts of 64 x 64 for every scheme
     ((16500, 64, 256), (32, 128), (128, 128)),     # narrow output: 128 x 128 tile of full-width wavefronts
-    ((300, 520, 1024), (32, 64), (32, 32)),        # one round of 32 x 32 streaming tiles
+    ((300, 520, 1024), (32, 32), (32, 32)),        # one round of 32 x 32 streaming tiles
     ((256, 1100, 512), (32, 64), (32, 64)),        # more than one round of those: 32 x 64 streaming tiles
 ]
 

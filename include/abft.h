@@ -66,7 +66,20 @@ typedef enum {
      * fragment into one accumulator block, whose sum must equal the sum of the wavefront tile.
      * Same tiles, comparisons, tolerance, report and k partition as ABFT_THREAD; never chosen by
      * ABFT_AUTO or by a plan's profile. */
-    ABFT_REPLICA = 4
+    ABFT_REPLICA = 4,
+    /* One-sided thread-level ABFT with the tile checksum of B_t added up in the operand type, as the
+     * paper does it (Sec. 5.2.2: packed half-precision adds): one extra MFMA per A fragment and k
+     * step (Table 1's M_t / 2) and one packed add per further B fragment.  The roundings of those
+     * adds (2^-11 per add in F16, 2^-8 in BF16) widen the tolerance (abft_tolerance_half_coeff):
+     * faults smaller than about an rms of C in one element go unseen.  ABFT_THREAD keeps the
+     * checksum exact instead, at twice (BF16: three times) the extra MFMAs. */
+    ABFT_THREAD_HALF = 5,
+    /* Two-sided thread-level ABFT (Sec. 5.2.1, Table 1 middle column): checksums of both the A
+     * fragments and the B fragments of the wavefront tile, added up in the operand type, one extra
+     * MFMA per k step.  Same tolerance rule as ABFT_THREAD_HALF with both sides' adds. */
+    ABFT_TWOSIDED = 6
+    /* (I8 has no sums in the operand type: ABFT_THREAD_HALF and ABFT_TWOSIDED run as ABFT_THREAD.
+     * Neither is chosen by ABFT_AUTO or by a plan's profile.) */
 } abft_mode_t;
 /* Activation function a layer applies to its output as it is stored (Sec. 2.4 step 4). */
 typedef enum { ABFT_ACT_NONE = 0, ABFT_ACT_RELU = 1 } abft_act_t;
@@ -261,10 +274,18 @@ int abft_k_ways(int M, int N, int K, int dtype, int aligned, int mode, int *ways
  *                (precision of the in-register tile checksum).
  *   bias_coeff = 1e-3 * 2^-24 * K for GLOBAL (a same-sign drift of the accumulation that adds
  *                linearly over a region of same-sign entries), 0 otherwise.
+ * ABFT_THREAD_HALF / ABFT_TWOSIDED add abft_tolerance_half_coeff(...) to coeff.
  * I8 compares exactly: both are 0.  A non-finite side always fails.
  * abft_tolerance_coeff returns coeff, abft_tolerance_bias_coeff returns bias_coeff. */
 double abft_tolerance_coeff(int K, int dtype, int mode);
 double abft_tolerance_bias_coeff(int K, int dtype, int mode);
+/* Further coefficient of ||C_S||_F for ABFT_THREAD_HALF and ABFT_TWOSIDED on wavefront tiles of
+ * tile_m x tile_n (abft_tile_shape): 4 * u_half * sqrt(n_B * tile_m + n_A * tile_n), u_half = 2^-11
+ * (F16) / 2^-8 (BF16), n_B = adds per element of the B-side checksum (MFMA block columns per tile
+ * - 1), n_A the same for the A side (two-sided only).  The errors of the B-side sums enter the
+ * comparison weighted with the column sums of the A tile, which are at most sqrt(tile_m) times
+ * the norms of its columns.  0 for every other scheme and for I8. */
+double abft_tolerance_half_coeff(int dtype, int mode, int tile_m, int tile_n);
 
 /* ---- plans: per-layer selection for a network (Sec. 5.3) ------------------- */
 typedef struct {

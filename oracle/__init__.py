@@ -300,10 +300,32 @@ def l1norm(C, r0=0, r1=None, c0=0, c1=None) -> float:
         return float(np.sum(np.abs(blk)))
 
 
+# Thread-level schemes that add their checksums in the operand type (the paper's packed
+# half-precision adds, Sec. 5.2.2): every such add rounds to U_HALF.  The rounding errors of
+# the B-side checksum enter the comparison weighted with the column sums of the A tile, each at
+# most sqrt(tile rows) times the norm of that column (Cauchy-Schwarz), and the other way round
+# for the A-side checksum of the two-sided scheme.  C_HALF = 4 sits on top of that bound.
+U_HALF = {F16: 2.0 ** -11, BF16: 2.0 ** -8}
+C_HALF = 4.0
+
+
+def half_sum_term(dtype, frob_norm, tile_m, tile_n, two_sided, block=32):
+    """What the roundings of checksums added in the operand type add to the tolerance of a
+    tile_m x tile_n register tile made of block x block outputs of the matrix instruction: the
+    B-side checksum takes tile_n / block - 1 adds per element, the A-side one (two-sided scheme
+    only) tile_m / block - 1."""
+    if dtype == I8:
+        return 0.0
+    n_b = max(tile_n // block - 1, 0)
+    n_a = max(tile_m // block - 1, 0) if two_sided else 0
+    return C_HALF * U_HALF[dtype] * math.sqrt(n_b * tile_m + n_a * tile_n) * frob_norm
+
+
 def tolerance(K: int, frob_norm: float, dtype: str, scheme: int = 1, l1_norm: float = 0.0) -> float:
     """Tolerance of one comparison over a region S of C (fp32 accumulators):
          global (scheme=1):  tau = C_TOL * 2^-24 * sqrt(K) * ||C_S||_F + C_BIAS * 2^-24 * K * ||C_S||_1
          thread (scheme=2):  tau = C_TOL * (2^-24 * sqrt(K) + U_CHI[dtype]) * ||C_S||_F
+       (the schemes that add checksums in the operand type add half_sum_term to the latter)
        0 for int8 (exact comparison)."""
     if dtype == I8:
         return 0.0
@@ -383,23 +405,28 @@ def tiles(M, N, tile_m, tile_n):
             yield r0, min(r0 + tile_m, M), c0, min(c0 + tile_n, N)
 
 
-def tile_check(A, B, C, dtype, r0, r1, c0, c1, two_sided=False) -> Check:
-    """Thread-level ABFT for one tile (Sec. 5.2.2): one-sided by default."""
+def tile_check(A, B, C, dtype, r0, r1, c0, c1, two_sided=False, operand_sums=None) -> Check:
+    """Thread-level ABFT for one tile (Sec. 5.2.2): one-sided by default, two-sided (Sec. 5.2.1)
+    on request.  operand_sums = (tile_m, tile_n): the checksums are added up in the operand type
+    on register tiles of that nominal shape, which widens the tolerance (half_sum_term); the two
+    sides of the comparison are the exact ones either way."""
     lib = _load()
     Aw, Bw = widen(A, dtype), widen(B, dtype)
     K, N = Bw.shape
     C = np.ascontiguousarray(C)
     if dtype == I8:
-        assert not two_sided
         lhs, rhs = ctypes.c_int64(), ctypes.c_int64()
-        lib.orc_tile_one_sided_i8(N, K, _p(Aw, ctypes.c_int8), _p(Bw, ctypes.c_int8),
-                                  _p(C, ctypes.c_int64), r0, r1, c0, c1, ctypes.byref(lhs),
-                                  ctypes.byref(rhs))
+        fn = lib.orc_tile_two_sided_i8 if two_sided else lib.orc_tile_one_sided_i8
+        fn(N, K, _p(Aw, ctypes.c_int8), _p(Bw, ctypes.c_int8), _p(C, ctypes.c_int64), r0, r1, c0, c1,
+           ctypes.byref(lhs), ctypes.byref(rhs))
         return Check(lhs.value, rhs.value, 0.0, lhs.value != rhs.value)
     lhs, rhs = ctypes.c_double(), ctypes.c_double()
     fn = lib.orc_tile_two_sided_f64 if two_sided else lib.orc_tile_one_sided_f64
     fn(N, K, _d(Aw), _d(Bw), _d(C), r0, r1, c0, c1, ctypes.byref(lhs), ctypes.byref(rhs))
-    tau = tolerance(K, frob(C, r0, r1, c0, c1), dtype, scheme=2)
+    f = frob(C, r0, r1, c0, c1)
+    tau = tolerance(K, f, dtype, scheme=2)
+    if operand_sums is not None:
+        tau += half_sum_term(dtype, f, operand_sums[0], operand_sums[1], two_sided)
     return Check(lhs.value, rhs.value, tau, mismatch(lhs.value, rhs.value, tau))
 
 

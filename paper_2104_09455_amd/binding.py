@@ -15,13 +15,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libabft.so")
 
 # enums of abft.h
-NONE, GLOBAL, THREAD, AUTO, REPLICA = 0, 1, 2, 3, 4
+NONE, GLOBAL, THREAD, AUTO, REPLICA, THREAD_HALF, TWOSIDED = 0, 1, 2, 3, 4, 5, 6
 ACT_NONE, ACT_RELU = 0, 1
 F16, BF16, I8 = 0, 1, 2
 B_NK, B_KN = 0, 1
 OK = 0
 
-MODE_NAMES = {NONE: "none", GLOBAL: "global", THREAD: "thread", AUTO: "auto", REPLICA: "replica"}
+MODE_NAMES = {NONE: "none", GLOBAL: "global", THREAD: "thread", AUTO: "auto", REPLICA: "replica",
+              THREAD_HALF: "thread_half", TWOSIDED: "twosided"}
 DTYPE_NAMES = {F16: "f16", BF16: "bf16", I8: "i8"}
 
 
@@ -57,6 +58,7 @@ EXPORTS = [
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
     "abft_plan_run_all", "abft_plan_set_mode", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
     "abft_plan_set_activation", "abft_plan_activation", "abft_gemm_static", "abft_static_scratch_bytes",
+    "abft_tolerance_half_coeff",
 ]
 
 _lib = None
@@ -107,6 +109,8 @@ def lib() -> ctypes.CDLL:
     L.abft_region_shape.argtypes = [ci, ci, ci, ci, ci, ip, ip]
     L.abft_tolerance_bias_coeff.restype = dbl
     L.abft_tolerance_bias_coeff.argtypes = [ci, ci, ci]
+    L.abft_tolerance_half_coeff.restype = dbl
+    L.abft_tolerance_half_coeff.argtypes = [ci, ci, ci, ci]
     L.abft_tolerance_coeff.restype = dbl
     L.abft_tolerance_coeff.argtypes = [ci, ci, ci]
     L.abft_plan_create.restype = ci
@@ -247,6 +251,10 @@ def abft_region_shape(M, N, K, dtype, aligned=True):
 
 def abft_tolerance_bias_coeff(K, dtype, mode) -> float:
     return lib().abft_tolerance_bias_coeff(K, dtype, mode)
+
+
+def abft_tolerance_half_coeff(dtype, mode, tile_m, tile_n) -> float:
+    return lib().abft_tolerance_half_coeff(dtype, mode, tile_m, tile_n)
 
 
 def abft_activation_checksum(M, K, A, lda, dtype, alpha, conv: Optional[Conv] = None, stream=None) -> None:

@@ -39,6 +39,14 @@ constexpr double C_BIAS = 1.0e-3;
 constexpr double U_ACC = 5.9604644775390625e-08;  // 2^-24
 constexpr double U_CHI_F16 = 2.384185791015625e-07;  // 2^-22
 constexpr double U_CHI_BF16 = 1.1920928955078125e-07;  // 2^-23
+// ABFT_THREAD_HALF / ABFT_TWOSIDED add checksums in the operand type: every such add rounds to
+// u_half = 2^-11 (fp16) / 2^-8 (bf16).  The errors of the B-side sums enter the comparison
+// weighted with the column sums of the A tile, which are at most sqrt(tile rows) times the
+// columns' norms (and the other way round for the A-side sums of the two-sided scheme):
+//   tau += C_HALF * u_half * sqrt(n_B * tile_m + n_A * tile_n) * ||C_S||_F
+// with n_B / n_A the number of adds per checksum element (fragments per wavefront tile - 1).
+constexpr double C_HALF = 4.0;
+constexpr double U_HALF_F16 = 4.8828125e-04, U_HALF_BF16 = 3.90625e-03;
 
 
 // MI355X spec-sheet peaks (dense) and HBM3E bandwidth
@@ -83,7 +91,8 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 // wide in N: one checksum MFMA per TN real ones); force >= 0 pins a configuration (tuning aid,
 // environment variable ABFT_FORCE_CFG).
 int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
-    if (mode == ABFT_REPLICA) mode = ABFT_THREAD;  // checked per wavefront tile alike: the same tiles
+    // (every wavefront-level scheme is checked per wavefront tile: the same tiles)
+    if (mode == ABFT_REPLICA || mode == ABFT_THREAD_HALF || mode == ABFT_TWOSIDED) mode = ABFT_THREAD;
     static const int force = [] {
         const char* e = std::getenv("ABFT_FORCE_CFG");
         return e ? std::atoi(e) : -1;
@@ -536,9 +545,18 @@ size_t ws_bytes_any_cfg(int M, int N, int K) {
     return best;
 }
 
+// extra coefficient of ||C_S||_F for the schemes that add checksums in the operand type, on
+// wavefront tiles of tile_m x tile_n (MFMA blocks of mi rows / columns)
+double tol_half_coeff(int dt, int mode, int tile_m, int tile_n, int mi) {
+    if (dt == ABFT_I8 || (mode != ABFT_THREAD_HALF && mode != ABFT_TWOSIDED)) return 0.0;
+    const double n_b = tile_n / mi - 1, n_a = mode == ABFT_TWOSIDED ? tile_m / mi - 1 : 0;
+    return C_HALF * (dt == ABFT_F16 ? U_HALF_F16 : U_HALF_BF16) * std::sqrt(n_b * tile_m + n_a * tile_n);
+}
+
 double tol_coeff(int K, int dt, int mode) {
     if (dt == ABFT_I8) return 0.0;
-    if (mode == ABFT_REPLICA) mode = ABFT_THREAD;  // two fp32 accumulations compared, as there
+    // (two fp32 accumulations compared, as in the thread-level scheme)
+    if (mode == ABFT_REPLICA || mode == ABFT_THREAD_HALF || mode == ABFT_TWOSIDED) mode = ABFT_THREAD;
     double u_chi = 0.0;
     if (mode == ABFT_THREAD) u_chi = dt == ABFT_F16 ? U_CHI_F16 : U_CHI_BF16;
     return C_TOL * (U_ACC * std::sqrt((double)K) + u_chi);
@@ -617,7 +635,7 @@ hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_
 
 int validate_common(const Problem& pr, int mode, const uint32_t* flag) {
     if (!valid_dtype(pr.dtype)) return ABFT_E_ENUM;
-    if (mode < ABFT_NONE || mode > ABFT_REPLICA) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_TWOSIDED) return ABFT_E_ENUM;
     if (pr.b_layout != ABFT_B_NK && pr.b_layout != ABFT_B_KN) return ABFT_E_ENUM;
     if (pr.M <= 0 || pr.N <= 0 || pr.K <= 0) return ABFT_E_SHAPE;
     if (!pr.A || !pr.B || !pr.C) return ABFT_E_NULL;
@@ -679,7 +697,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     g.act = pr.act;
     g.report = reinterpret_cast<Report*>(report);
     const int tol_K = pr.tol_K > 0 ? pr.tol_K : pr.K;
-    g.tol_coeff = tol_coeff(tol_K, pr.dtype, mode);
+    g.tol_coeff = tol_coeff(tol_K, pr.dtype, mode) + tol_half_coeff(pr.dtype, mode, ci.wm, ci.wn, cfg == CFG_G16 ? 16 : 32);
     g.f_row = g.f_col = -1; g.f_bit = 0; g.f_kt = -1;
 
     bool inj = false;
@@ -1079,6 +1097,11 @@ double abft_tolerance_coeff(int K, int dtype, int mode) {
     return tol_coeff(K, dtype, mode);
 }
 
+double abft_tolerance_half_coeff(int dtype, int mode, int tile_m, int tile_n) {
+    if (!valid_dtype(dtype) || tile_m <= 0 || tile_n <= 0) return 0.0;
+    return tol_half_coeff(dtype, mode, tile_m, tile_n, tile_m < 32 ? 16 : 32);
+}
+
 double abft_tolerance_bias_coeff(int K, int dtype, int mode) {
     if (!valid_dtype(dtype) || K <= 0) return 0.0;
     return tol_bias_coeff(K, dtype, mode);
@@ -1250,7 +1273,7 @@ int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* ld
 
 int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
-    if (mode < ABFT_NONE || mode > ABFT_REPLICA) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_TWOSIDED) return ABFT_E_ENUM;
     abft_plan::Layer& L = plan->layers[layer];
     L.mode = mode == ABFT_AUTO ? select_mode(L.desc.M, L.desc.N, L.desc.K, L.desc.dtype) : mode;
     return ABFT_OK;

@@ -26,11 +26,19 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 enum { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2 };
 // MODE_GLOBAL_PRE (kernel-internal): the global scheme with the checksum dot products left by
 // the activation-checksum kernel instead of formed inside the product's loop
-enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3, MODE_REPL = 4 };
+enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3, MODE_REPL = 4, MODE_THREAD_H = 5,
+       MODE_TWOSIDED = 6 };
 // MODE_REPL: thread-level replication with single accumulation (Sec. 5.1): every MFMA of the
 // product is issued a second time into one accumulator block per A fragment; the sum of those
 // blocks must equal the sum of the wavefront tile.  Checked exactly like MODE_THREAD.
-constexpr bool mode_is_wave_level(int mode) { return mode == MODE_THREAD || mode == MODE_REPL; }
+// MODE_THREAD_H: one-sided thread-level ABFT with the tile checksum added up in the operand
+// type, as the paper does it (Sec. 5.2.2: packed half-precision adds): one extra MFMA per A
+// fragment and k step.  MODE_TWOSIDED: two-sided thread-level ABFT (Sec. 5.2.1): the checksums of
+// both the A fragments and the B fragments, added up in the operand type, one extra MFMA per k
+// step.  Both carry the rounding of those adds in their tolerance.
+constexpr bool mode_is_wave_level(int mode) {
+    return mode == MODE_THREAD || mode == MODE_REPL || mode == MODE_THREAD_H || mode == MODE_TWOSIDED;
+}
 
 struct Report {  // mirrors abft_report_t
     double lhs, rhs, tau, worst_ratio;
@@ -533,8 +541,60 @@ __device__ __forceinline__ void thread_checksum_step(const i32x4 (&a)[CFG::TM], 
 // Redundant accumulator blocks a wavefront carries under each scheme.
 template <class CFG, int MODE>
 struct CheckRegs {
-    static constexpr int N = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : (MODE == MODE_REPL ? CFG::TM : 1);
+    static constexpr int N = MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK
+                             : ((MODE == MODE_REPL || MODE == MODE_THREAD_H) ? CFG::TM : 1);
 };
+
+// Element-wise sum of two fragments in the operand type (fp16: one packed add per register;
+// bf16: widened, added and rounded to nearest even).  int8 sums do not fit the operand type:
+// integer layers run the exact scheme instead.
+template <int DT>
+__device__ __forceinline__ i32x4 add_in_operand_type(const i32x4& x, const i32x4& y) {
+    static_assert(DT != DT_I8, "floating-point operands only");
+    i32x4 out;
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        if constexpr (DT == DT_F16) {
+            typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+            out[d] = bitcast<int>((f16x2)(bitcast<f16x2>(x[d]) + bitcast<f16x2>(y[d])));
+        } else {
+            typedef TileChecksumSplitBF16<2> BF;
+            out[d] = BF::pack(BF::lo_f(x[d]) + BF::lo_f(y[d]), BF::hi_f(x[d]) + BF::hi_f(y[d]));
+        }
+    }
+    return out;
+}
+
+// The redundant MFMAs of one k step under a wavefront-level scheme (a: A fragments, b: B
+// fragments of the step; Table 1 of the paper counts exactly these).
+template <class CFG, int MODE>
+__device__ __forceinline__ void check_step(const i32x4 (&a)[CFG::TM], const i32x4 (&b)[CFG::TN],
+                                           typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[(CheckRegs<CFG, MODE>::N)]) {
+    typedef Mma<CFG::DT, CFG::MI> MMA;
+    constexpr int TM = CFG::TM, TN = CFG::TN;
+    if constexpr (MODE == MODE_THREAD) {
+        thread_checksum_step<CFG>(a, b, chk);
+    } else if constexpr (MODE == MODE_REPL) {
+        // every product once more, all of an A fragment's into one block (Sec. 5.1)
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) chk[i] = MMA::run(a[i], b[j], chk[i]);
+    } else if constexpr (MODE == MODE_THREAD_H || MODE == MODE_TWOSIDED) {
+        i32x4 x = b[0];
+#pragma unroll
+        for (int j = 1; j < TN; ++j) x = add_in_operand_type<CFG::DT>(x, b[j]);
+        if constexpr (MODE == MODE_THREAD_H) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) chk[i] = MMA::run(a[i], x, chk[i]);
+        } else {
+            i32x4 y = a[0];
+#pragma unroll
+            for (int i = 1; i < TM; ++i) y = add_in_operand_type<CFG::DT>(y, a[i]);
+            chk[0] = MMA::run(y, x, chk[0]);
+        }
+    }
+}
 
 // ---------------------------------------------------------------------------
 // Per-thread view of the tiling: which wavefront tile this lane works on and which
@@ -653,7 +713,8 @@ __device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long
     const typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[(CheckRegs<CFG, MODE>::N)], int lane) {
     typedef Mma<CFG::DT, CFG::MI> MMA;
     constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
-    constexpr bool SPLIT_FORM = MODE != MODE_REPL && ChecksumForm<CFG>::SPLIT;
+    constexpr bool SPLIT_FORM = MODE == MODE_THREAD && ChecksumForm<CFG>::SPLIT;
+    constexpr int NBLK = CheckRegs<CFG, MODE>::N;
     if constexpr (CFG::DT == DT_I8) {
         long long rsum = 0;
         if constexpr (SPLIT_FORM) {
@@ -674,7 +735,7 @@ __device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long
         } else {
             int r_lo = 0, r_hi = 0;
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < NBLK; ++i)
 #pragma unroll
                 for (int r = 0; r < MMA::NACC; ++r) {
                     r_lo += chk[i][r] & 0xffff;
@@ -700,7 +761,7 @@ __device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < TM; ++i)
+            for (int i = 0; i < NBLK; ++i)
 #pragma unroll
                 for (int r = 0; r < MMA::NACC; r += 4)
                     rsum += (double)((chk[i][r] + chk[i][r + 1]) + (chk[i][r + 2] + chk[i][r + 3]));

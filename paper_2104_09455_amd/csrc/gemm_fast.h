@@ -251,15 +251,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
-        if constexpr (MODE == MODE_THREAD) {
-            thread_checksum_step<CFG>(fa[buf], fb[buf], chk);
-        } else if constexpr (MODE == MODE_REPL) {
-            // every product once more, all of an A fragment's into one block (Sec. 5.1)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) chk[i] = MMA::run(fa[buf][i], fb[buf][j], chk[i]);
-        }
+        if constexpr (mode_is_wave_level(MODE)) check_step<CFG, MODE>(fa[buf], fb[buf], chk);
     };
 
     // Pipeline: tile t lives in LDS stage t % NSTAGE and is copied in while earlier tiles are
@@ -295,11 +287,14 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
                     // protected schemes (global: reads and FMAs of the checksum dot product;
                     // thread-level: the sums of the B fragments) is spread between the MFMAs
                     constexpr int NF = TM + TN;
-                    constexpr int NM = TM * TN + (MODE == MODE_THREAD ? ChecksumForm<CFG>::NCHK : (MODE == MODE_REPL ? TM * TN : 0));
-                    // vector instructions per MFMA slot: the tile checksum's pieces cost about 14
-                    // (fp16, int8) or 22 (bf16) instructions per 16 bytes of each lane's B fragments
-                    constexpr int VT = MODE == MODE_THREAD && ChecksumForm<CFG>::SPLIT
-                                           ? ((DT == DT_BF16 ? 22 : 14) * 4 + NM - 1) / NM : 0;
+                    constexpr int NM = TM * TN + (MODE == MODE_REPL ? TM * TN : (mode_is_wave_level(MODE) ? CheckRegs<CFG, EMODE>::N : 0));
+                    // vector instructions per MFMA slot: the exact tile checksum's pieces cost about
+                    // 14 (fp16, int8) or 22 (bf16) instructions per 16 bytes of each lane's B
+                    // fragments; sums in the operand type one (fp16) or six (bf16) per register
+                    constexpr int VSTEP = MODE == MODE_THREAD && ChecksumForm<CFG>::SPLIT ? (DT == DT_BF16 ? 22 : 14) * 4
+                                          : (MODE == MODE_THREAD_H ? (TN - 1) * 4 * (DT == DT_BF16 ? 6 : 1)
+                                             : (MODE == MODE_TWOSIDED ? (TN + TM - 2) * 4 * (DT == DT_BF16 ? 6 : 1) : 0));
+                    constexpr int VT = (VSTEP + NM - 1) / NM;
 #pragma unroll
                     for (int g = 0; g < NM; ++g) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA

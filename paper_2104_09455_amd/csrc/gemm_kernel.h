@@ -238,15 +238,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_kernel(const GemmArgs p) {
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(a[i], b[j], acc[i][j]);
-            if constexpr (MODE == MODE_THREAD) {
-            thread_checksum_step<CFG>(a, b, chk);
-        } else if constexpr (MODE == MODE_REPL) {
-                // every product once more, all of an A fragment's into one block (Sec. 5.1)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j) chk[i] = MMA::run(a[i], b[j], chk[i]);
-            }
+            if constexpr (mode_is_wave_level(MODE)) check_step<CFG, MODE>(a, b, chk);
         }
         if (more) store_tiles(cur ^ 1, ra, rb);
         __syncthreads();

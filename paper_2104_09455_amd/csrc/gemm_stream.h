@@ -291,15 +291,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) gchk[i] = MMA::run(fa[buf][i], fg[buf], gchk[i]);
         }
-        if constexpr (MODE == MODE_THREAD) {
-            thread_checksum_step<CFG>(fa[buf], fb[buf], chk);
-        } else if constexpr (MODE == MODE_REPL) {
-            // every product once more, all of an A fragment's into one block (Sec. 5.1)
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j) chk[i] = MMA::run(fa[buf][i], fb[buf][j], chk[i]);
-        }
+        if constexpr (mode_is_wave_level(MODE)) check_step<CFG, MODE>(fa[buf], fb[buf], chk);
     };
 
     constexpr int VM_STEADY = waitcnt_vm((NST - 1) * NL);  // the oldest tile in flight has landed

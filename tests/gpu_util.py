@@ -192,3 +192,16 @@ class DeviceConv:
     def C(self, rows=None):
         c = self.dC if rows is None else self.dC[torch.as_tensor(np.asarray(rows), device=DEV)]
         return c_to_host(c, self.dtype)
+
+
+WAVE_LEVEL = (B.THREAD, B.REPLICA, B.THREAD_HALF, B.TWOSIDED)   # one comparison per wavefront tile
+
+
+def wave_check(mode, A, Bm, C, dtype, region, tile):
+    """The oracle's check of one wavefront register tile (region = r0, r1, c0, c1; tile = the
+    nominal tile shape) under the wavefront-level scheme `mode`."""
+    import oracle
+    if mode == B.REPLICA:
+        return oracle.replica_check(A, Bm, C, dtype, *region)
+    return oracle.tile_check(A, Bm, C, dtype, *region, two_sided=mode == B.TWOSIDED,
+                             operand_sums=tuple(tile) if mode in (B.THREAD_HALF, B.TWOSIDED) else None)

@@ -117,7 +117,7 @@ def test_argument_validation_without_a_gpu(lib):
     assert g(M=0) == -2 and g(N=-1) == -2 and g(K=0) == -2
     assert g(A=None) == -1 and g(B=None) == -1 and g(C=None) == -1
     assert g(lda=3) == -3 and g(ldb=3) == -3 and g(ldc=3) == -3
-    assert g(dtype=3) == -4 and g(mode=5) == -4 and g(mode=-1) == -4 and g(layout=2) == -4
+    assert g(dtype=3) == -4 and g(mode=7) == -4 and g(mode=-1) == -4 and g(layout=2) == -4
     assert g(mode=1, flag=None) == -1
     assert g(mode=1) == -5  # global needs a workspace
     with pytest.raises(B.AbftError) as e:
@@ -139,6 +139,25 @@ def test_replication_mode_shares_the_thread_level_geometry(lib):
             assert B.abft_tolerance_coeff(K, dt, B.REPLICA) == B.abft_tolerance_coeff(K, dt, B.THREAD)
             assert B.abft_tolerance_bias_coeff(K, dt, B.REPLICA) == 0.0
     assert B.MODE_NAMES[B.REPLICA] == "replica"
+
+
+def test_operand_type_checksum_schemes_share_the_geometry_and_widen_the_tolerance(lib):
+    """ABFT_THREAD_HALF and ABFT_TWOSIDED run on the thread-level scheme's tiles; their extra
+    tolerance coefficient is 4 u_half sqrt(n_B tile_m + n_A tile_n) (0 for int8 and for the other
+    schemes)."""
+    import math
+    for (M, N, K) in [(64, 64, 64), (256, 4096, 4096), (1536, 1536, 256), (8192, 8192, 8192)]:
+        for mode in (B.THREAD_HALF, B.TWOSIDED):
+            assert B.abft_k_ways(M, N, K, B.F16, mode) == B.abft_k_ways(M, N, K, B.F16, B.THREAD)
+            assert B.abft_workspace_bytes(M, N, K, B.F16, mode) == 0
+            assert B.abft_tolerance_coeff(K, B.F16, mode) == B.abft_tolerance_coeff(K, B.F16, B.THREAD)
+    assert B.abft_tolerance_half_coeff(B.F16, B.THREAD_HALF, 32, 128) == pytest.approx(4 * 2.0 ** -11 * math.sqrt(3 * 32))
+    assert B.abft_tolerance_half_coeff(B.F16, B.TWOSIDED, 64, 64) == pytest.approx(4 * 2.0 ** -11 * math.sqrt(64 + 64))
+    assert B.abft_tolerance_half_coeff(B.BF16, B.THREAD_HALF, 64, 64) == pytest.approx(4 * 2.0 ** -8 * math.sqrt(64))
+    assert B.abft_tolerance_half_coeff(B.F16, B.THREAD_HALF, 32, 32) == 0.0      # nothing is added up
+    assert B.abft_tolerance_half_coeff(B.I8, B.TWOSIDED, 64, 64) == 0.0
+    assert B.abft_tolerance_half_coeff(B.F16, B.THREAD, 64, 64) == 0.0
+    assert B.MODE_NAMES[B.TWOSIDED] == "twosided" and B.MODE_NAMES[B.THREAD_HALF] == "thread_half"
 
 
 def test_tile_choice_for_few_tiles(lib):

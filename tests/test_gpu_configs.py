@@ -296,7 +296,7 @@ def test_sweep_point_every_scheme(M):
     ref = oracle.gemm(np.ascontiguousarray(A[rows]), Bm, "f16")
     want = B.GLOBAL if 2.0 * M * N * K / (2.0 * (M * K + K * N + M * N)) > 2516.6e12 / 8e12 else B.THREAD
     assert B.abft_select(M, N, K, B.F16) == want and (M >= 512) == (want == B.GLOBAL)
-    for mode in SCHEMES + (B.REPLICA,):
+    for mode in SCHEMES + (B.REPLICA, B.THREAD_HALF, B.TWOSIDED):
         print(f"case sweep M={M} mode={mode}", flush=True)
         g.dC.zero_()
         flag, rep = g.run(mode)

@@ -331,6 +331,44 @@ def test_precision_of_a_checksum_handed_on_in_pieces():
         assert np.all(np.abs(backb - sb.astype(np.float64)) <= oracle.U_CHI["bf16"] * np.abs(sb.astype(np.float64)))
 
 
+@pytest.mark.parametrize("tile", [(32, 64), (32, 128), (64, 64), (128, 64)])
+def test_tolerance_of_checksums_added_in_half_precision(tile):
+    """The widened tolerance of the schemes that add their checksums in fp16 (Sec. 5.2.2's packed
+    adds), against a simulation in plain numpy fp16 arithmetic: per k, the tile's B values are
+    added up in fp16 within each class of columns 32 apart (the A values likewise for the
+    two-sided scheme), everything after that exactly.  The residual against the tile's exact
+    output summation stays under half the tolerance -- same-sign activations, where the error is
+    largest, included -- while the exact scheme's tolerance would be overrun; and the integer
+    identity of the two-sided definition holds exactly."""
+    tm, tn = tile
+    for two_sided in (False, True):
+        over_exact = 0
+        for K in (16, 64, 1024):
+            for da, db in (("normal", "normal"), ("uniform_01", "weights"), ("uniform_01", "uniform_01")):
+                for seed in range(4):
+                    A, B = wl.gemm_operands(tm, tn, K, "f16", seed=50 + seed, dist_a=da, dist_b=db)
+                    C = oracle.gemm(A, B, "f16")
+                    chi = B[:, :32].copy()
+                    for j in range(1, tn // 32):
+                        chi = (chi + B[:, 32 * j:32 * j + 32]).astype(np.float16)
+                    if two_sided:
+                        a = A[:32].copy()
+                        for i in range(1, tm // 32):
+                            a = (a + A[32 * i:32 * i + 32]).astype(np.float16)
+                        rhs = float((a.astype(np.float64) @ chi.astype(np.float64)).sum())
+                    else:
+                        rhs = float((A.astype(np.float64) @ chi.astype(np.float64)).sum())
+                    chk = oracle.tile_check(A, B, C, "f16", 0, tm, 0, tn, two_sided=two_sided, operand_sums=tile)
+                    assert abs(chk.lhs - rhs) <= 0.5 * chk.tau, (two_sided, K, da, db, abs(chk.lhs - rhs) / chk.tau)
+                    exact = oracle.tile_check(A, B, C, "f16", 0, tm, 0, tn, two_sided=two_sided)
+                    assert exact.tau < chk.tau and not exact.flag
+                    over_exact += abs(chk.lhs - rhs) > exact.tau
+        assert over_exact > 0
+    Ai, Bi = wl.gemm_operands(tm, tn, 24, "i8", seed=9)
+    two = oracle.tile_check(Ai, Bi, oracle.gemm(Ai, Bi, "i8"), "i8", 0, tm, 0, tn, two_sided=True)
+    assert two.lhs == two.rhs and not two.flag
+
+
 def test_fault_in_an_accumulator_that_holds_a_subset_of_k():
     """inject(k_set=...): with the set a contiguous range it is the k_begin / k_after form; with an
     interleaved set the corrupted value is flip(sum over the set below k_after) + every other

@@ -179,9 +179,12 @@ def layer_table(hip, runs, reps, warm, stream, modes=(B.NONE, B.GLOBAL, B.THREAD
             "tflops_pick": round(lr.flops / pick_t / 1e6, 2),
             "roofline_frac_pick": round(lr.flops / (pick_t * 1e-6) / roof, 4),
         })
-        if B.REPLICA in t:   # thread-level replication, single accumulation (Sec. 5.1's baseline)
-            rows[-1]["us_replica"] = round(t[B.REPLICA], 2)
-            rows[-1]["ovh_replica_pct"] = round(100 * (t[B.REPLICA] / t[B.NONE] - 1), 2)
+        # the other wavefront-level schemes of the paper's design space (Sec. 5.1, 5.2.1, 5.2.2; Table 1):
+        # replication with single accumulation, one-sided with half-precision checksum adds, two-sided
+        for m in (B.REPLICA, B.THREAD_HALF, B.TWOSIDED):
+            if m in t:
+                rows[-1]["us_" + B.MODE_NAMES[m]] = round(t[m], 2)
+                rows[-1]["ovh_" + B.MODE_NAMES[m] + "_pct"] = round(100 * (t[m] / t[B.NONE] - 1), 2)
         ALL_ROWS.append(dict(rows[-1], dtype=lr.dtype))
     return rows
 
@@ -793,17 +796,18 @@ def main():
             sweep = []
             for m in wl.sweep_m():
                 lr = LayerRun(wl.Layer(f"m{m}", m, 4096, 4096), "f16", gen, "normal", "normal")
-                r = layer_table(hip, [lr], 10, 2, stream)[0]
-                sweep.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct")})
+                r = layer_table(hip, [lr], 10, 2, stream, modes=(B.NONE, B.GLOBAL, B.THREAD, B.THREAD_HALF, B.TWOSIDED))[0]
+                sweep.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct",
+                                                "ovh_thread_half_pct", "ovh_twosided_pct")})
             extra["sweep_N4096_K4096"] = sweep
             # the paper's Fig. 11 sizes (its T4 numbers: thread-level 2-14 %, global 27 % at 32^3 down to 1 % at 2048^3,
             # replication above 70 % at the two largest sizes)
             fig11 = []
             for n in wl.square_sizes_paper():
                 lr = LayerRun(wl.Layer(f"sq{n}", n, n, n), "f16", gen, "normal", "normal")
-                r = layer_table(hip, [lr], 20, 2, stream, modes=(B.NONE, B.GLOBAL, B.THREAD, B.REPLICA))[0]
+                r = layer_table(hip, [lr], 20, 2, stream, modes=(B.NONE, B.GLOBAL, B.THREAD, B.REPLICA, B.THREAD_HALF, B.TWOSIDED))[0]
                 fig11.append({k: r[k] for k in ("M", "ai", "pick", "us_none", "ovh_global_pct", "ovh_thread_pct",
-                                                "ovh_replica_pct")})
+                                                "ovh_replica_pct", "ovh_thread_half_pct", "ovh_twosided_pct")})
             extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
             extra["dlrm_mlp_chains_relu"] = chain_leg(gen)

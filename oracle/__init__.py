@@ -398,6 +398,71 @@ def global_check_blocks(A, B, C, dtype, block_m, block_n):
     return any(c.flag for c in checks), checks
 
 
+@dataclass
+class WeightedCheck:
+    """Three comparisons of one region (Sec. 2.4, last paragraph: several checksums from
+    independent linear combinations): plain, rows weighted, columns weighted."""
+    plain: Check
+    rows: Check
+    cols: Check
+
+    @property
+    def flag(self):
+        return self.plain.flag or self.rows.flag or self.cols.flag
+
+
+def weighted_region_check(A, B, C, dtype, r0, r1, c0, c1, block_m=None, block_n=None) -> WeightedCheck:
+    """Global ABFT of the block rows r0..r1 x columns c0..c1 of C with three independent checksum
+    pairs: with 1 the all-ones vector, w the row weights and v the column weights of the block,
+         plain:  (1^T A_S)(B_S 1)  against  sum_ij C_ij
+         rows:   (w^T A_S)(B_S 1)  against  sum_ij w_i C_ij
+         cols:   (1^T A_S)(B_S v)  against  sum_ij v_j C_ij
+    Integer operands: w_i = i + 1, v_j = j + 1 (local indices), exact comparisons.  Floating
+    point: w_i = (i + 1) / block_m, v_j = (j + 1) / block_n (block_m, block_n: the nominal block
+    shape, default the block itself), tolerance as for the global scheme on the weighted block.
+    One wrong element (i, j) of the block off by delta leaves the residuals delta, w_i delta and
+    v_j delta (locate); two wrong elements whose errors cancel in the plain sum still show in the
+    weighted ones unless they share the row and the column weights."""
+    Aw, Bw = widen(A, dtype), widen(B, dtype)
+    K = Aw.shape[1]
+    bm, bn = block_m or (r1 - r0), block_n or (c1 - c0)
+    acc_t = np.int64 if dtype == I8 else np.float64
+    As = np.asarray(Aw[r0:r1], dtype=acc_t)
+    Bs = np.asarray(Bw[:, c0:c1], dtype=acc_t)
+    Cs = np.asarray(C, dtype=acc_t)[r0:r1, c0:c1]
+    w = np.arange(1, r1 - r0 + 1, dtype=acc_t)
+    v = np.arange(1, c1 - c0 + 1, dtype=acc_t)
+    if dtype != I8:
+        w, v = w / bm, v / bn
+    alpha, alpha_w = As.sum(axis=0), (w[:, None] * As).sum(axis=0)     # 1^T A_S, w^T A_S
+    beta, beta_v = Bs.sum(axis=1), (Bs * v[None, :]).sum(axis=1)       # B_S 1,   B_S v
+    out = []
+    for a_vec, b_vec, Cw in ((alpha, beta, Cs), (alpha_w, beta, w[:, None] * Cs), (alpha, beta_v, Cs * v[None, :])):
+        if dtype == I8:
+            lhs, rhs = int(Cw.sum()), int(np.dot(a_vec, b_vec))
+            out.append(Check(lhs, rhs, 0.0, lhs != rhs))
+        else:
+            with np.errstate(over="ignore", invalid="ignore"):
+                lhs, rhs = float(Cw.sum()), float(np.dot(a_vec, b_vec))
+                tau = tolerance(K, float(np.sqrt(np.sum(Cw * Cw))), dtype, scheme=1, l1_norm=float(np.sum(np.abs(Cw))))
+            out.append(Check(lhs, rhs, tau, mismatch(lhs, rhs, tau)))
+    return WeightedCheck(*out)
+
+
+def locate(wc: WeightedCheck, dtype, block_m, block_n):
+    """(row, col, delta) of a single wrong element of the block, local indices, from the three
+    residuals: w_i = rows residual / plain residual, v_j likewise.  None when the plain
+    comparison holds (nothing to locate, or errors that cancel in the plain sum)."""
+    d0 = wc.plain.residual
+    if not wc.plain.flag or d0 == 0:
+        return None
+    if dtype == I8:
+        i, j = wc.rows.residual // d0 - 1, wc.cols.residual // d0 - 1
+    else:
+        i, j = round(block_m * wc.rows.residual / d0) - 1, round(block_n * wc.cols.residual / d0) - 1
+    return int(i), int(j), d0
+
+
 def tiles(M, N, tile_m, tile_n):
     """The partition of C into register tiles (edge tiles clipped), row-major order."""
     for r0 in range(0, M, tile_m):

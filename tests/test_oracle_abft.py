@@ -437,3 +437,73 @@ def test_replica_check_fp_against_numpy_and_tolerance(dtype):
         Cb = C.copy()
         Cb[r0 + 3, c0 + 40] += delta
         assert oracle.replica_check(A, B, Cb, dtype, r0, r1, c0, c1).flag == seen
+
+
+# ------------------------------------------------- several checksums (Sec. 2.4, last paragraph)
+def test_weighted_checks_hold_exactly_on_clean_integers_and_locate_every_single_fault():
+    """Three independent checksum pairs per block: all hold exactly on clean integer data (checked
+    against a direct evaluation), and a single wrong element is located exactly -- every element
+    of a ragged block, several bits."""
+    M, N, K = 11, 14, 9
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=61)
+    C = oracle.gemm(A, B, "i8")
+    r0, r1, c0, c1 = 2, 11, 3, 14
+    wc = oracle.weighted_region_check(A, B, C, "i8", r0, r1, c0, c1)
+    assert not wc.flag
+    blk = C[r0:r1, c0:c1]
+    assert wc.rows.lhs == sum((i + 1) * int(blk[i].sum()) for i in range(r1 - r0))
+    assert wc.cols.lhs == sum((j + 1) * int(blk[:, j].sum()) for j in range(c1 - c0))
+    assert wc.plain.rhs == int(A[r0:r1].astype(np.int64).sum(axis=0) @ B[:, c0:c1].astype(np.int64).sum(axis=1))
+    assert wc.plain.lhs == wc.plain.rhs and wc.rows.lhs == wc.rows.rhs and wc.cols.lhs == wc.cols.rhs
+    for i in range(r0, r1):
+        for j in range(c0, c1):
+            for bit in (0, 13, 31):
+                Cf = oracle.inject(A, B, C, "i8", i, j, bit)
+                bad = oracle.weighted_region_check(A, B, Cf, "i8", r0, r1, c0, c1)
+                assert bad.flag
+                assert oracle.locate(bad, "i8", r1 - r0, c1 - c0) == (i - r0, j - c0, int(Cf[i, j] - C[i, j]))
+
+
+def test_weighted_checks_see_two_faults_that_cancel_in_the_plain_sum():
+    """Two wrong elements with opposite errors leave the plain checksum intact; the weighted
+    ones see them unless the two share both weights (the same element).  Exhaustive over pairs
+    of a small block."""
+    M, N, K = 5, 6, 7
+    A, B = wl.gemm_operands(M, N, K, "i8", seed=62)
+    C = oracle.gemm(A, B, "i8")
+    cells = [(i, j) for i in range(M) for j in range(N)]
+    for a in cells:
+        for b in cells:
+            if a == b:
+                continue
+            Cf = C.copy()
+            Cf[a] += 1000
+            Cf[b] -= 1000
+            wc = oracle.weighted_region_check(A, B, Cf, "i8", 0, M, 0, N)
+            assert not wc.plain.flag            # the single-checksum scheme is blind here
+            assert wc.flag
+            assert wc.rows.flag == (a[0] != b[0]) and wc.cols.flag == (a[1] != b[1])
+            assert oracle.locate(wc, "i8", M, N) is None
+
+
+def test_weighted_checks_in_floating_point():
+    """fp16 operands: clean data passes all three comparisons (also for a binary32-accumulated C),
+    a large single fault is located, and the weighted sums equal the definition."""
+    M, N, K = 32, 64, 128
+    for da, db in (("normal", "normal"), ("uniform_01", "weights"), ("uniform_01", "uniform_01")):
+        A, B = wl.gemm_operands(M, N, K, "f16", seed=63, dist_a=da, dist_b=db)
+        C = oracle.gemm(A, B, "f16")
+        wc = oracle.weighted_region_check(A, B, C, "f16", 0, M, 0, N)
+        assert not wc.flag
+        w = (np.arange(M) + 1) / M
+        assert wc.rows.lhs == pytest.approx(float((w[:, None] * C).sum()), rel=1e-12)
+        assert wc.rows.rhs == pytest.approx(wc.rows.lhs, rel=1e-9, abs=1e-9)
+        C32 = _accumulate_binary32(A, B)
+        wc32 = oracle.weighted_region_check(A, B, C32, "f16", 0, M, 0, N)
+        assert not wc32.flag
+        assert max(abs(c.residual) / c.tau for c in (wc32.plain, wc32.rows, wc32.cols)) < 0.25
+        Cf = oracle.inject(A, B, C, "f16", 17, 41, 27)
+        bad = oracle.weighted_region_check(A, B, Cf, "f16", 0, M, 0, N)
+        if abs(Cf[17, 41] - C[17, 41]) > 100 * bad.plain.tau:
+            i, j, d = oracle.locate(bad, "f16", M, N)
+            assert (i, j) == (17, 41) and d == pytest.approx(Cf[17, 41] - C[17, 41], rel=1e-6)

@@ -45,6 +45,7 @@ extern "C" {
 #define ABFT_E_INJECT (-6)     /* fault descriptor out of range */
 #define ABFT_E_HIP (-7)        /* a HIP runtime call failed (launch, allocation) */
 #define ABFT_E_PLAN (-8)       /* bad plan handle or layer index */
+#define ABFT_E_UNSUPPORTED (-9) /* the scheme is not available for this product (see ABFT_GLOBAL_WEIGHTED) */
 
 /* ---- enums --------------------------------------------------------------- */
 /* Protection scheme.  GLOBAL: kernel-level ABFT (Sec. 2.4-2.5): the weight checksums are
@@ -77,9 +78,20 @@ typedef enum {
     /* Two-sided thread-level ABFT (Sec. 5.2.1, Table 1 middle column): checksums of both the A
      * fragments and the B fragments of the wavefront tile, added up in the operand type, one extra
      * MFMA per k step.  Same tolerance rule as ABFT_THREAD_HALF with both sides' adds. */
-    ABFT_TWOSIDED = 6
+    ABFT_TWOSIDED = 6,
     /* (I8 has no sums in the operand type: ABFT_THREAD_HALF and ABFT_TWOSIDED run as ABFT_THREAD.
      * Neither is chosen by ABFT_AUTO or by a plan's profile.) */
+    /* Global ABFT with several independent checksums (Sec. 2.4, last paragraph): per workgroup tile
+     * three comparisons -- the plain one, one with the tile's rows weighted, one with its columns
+     * weighted (I8: weights i + 1, j + 1; F16: (i + 1) / region_m, (j + 1) / region_n) -- each with
+     * the global scheme's tolerance on the weighted tile.  Two wrong elements whose errors cancel in
+     * the plain sum are still seen unless they share a row and a column; a single wrong element is
+     * located (abft_report_t.fault_row / fault_col / fault_delta).  The extra checksums ride in spare
+     * columns of an extra matrix operand, so the scheme exists where that operand does: products
+     * that run on the latency-bound tiling (up to a few hundred output tiles of at most 64 x 64;
+     * abft_region_shape tells) with F16 or I8 operands; elsewhere the call returns
+     * ABFT_E_UNSUPPORTED.  Workspace, beta and report as for ABFT_GLOBAL. */
+    ABFT_GLOBAL_WEIGHTED = 7
 } abft_mode_t;
 /* Activation function a layer applies to its output as it is stored (Sec. 2.4 step 4). */
 typedef enum { ABFT_ACT_NONE = 0, ABFT_ACT_RELU = 1 } abft_act_t;
@@ -138,6 +150,13 @@ typedef struct {
     double frob, l1;   /* ||C_S||_F and sum |C_ij| of the region lhs/rhs/tau belong to (l1: GLOBAL only) */
     uint32_t lock;     /* used by the device while it updates the block */
     uint32_t region;   /* 1 + row-major index of that region in the partition of C into regions (edge regions clipped) */
+    /* ABFT_GLOBAL_WEIGHTED only (else left as the caller set them): where a single wrong element of
+     * the reported region would sit, from the ratios of the weighted residuals to the plain one
+     * (-1, -1 when the plain comparison held or the ratios point outside the region), by how much
+     * the region's sum is off, and residual / tolerance of the two weighted comparisons
+     * (worst_ratio is then the largest of the three). */
+    int32_t fault_row, fault_col;
+    double fault_delta, ratio_rows, ratio_cols;
 } abft_report_t;
 
 /* ---- the protected product ------------------------------------------------ */
@@ -210,13 +229,16 @@ size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int 
 
 /* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns: with
  * nb = ceil(N / block_n), beta_b[k] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n].
- * The buffer `beta` (device, abft_beta_bytes(K, N, block_n) bytes, 256-byte aligned) receives two
+ * The buffer `beta` (device, abft_beta_bytes(K, N, block_n) bytes, 256-byte aligned) receives three
  * copies: first K x nb values k-major, beta[k*nb + b], as doubles (F16 / BF16) or int64 (I8);
- * then, at the next multiple of 256 bytes, the copy the product kernel reads inside its loop:
- * per block b, K floats (F16 / BF16), or K low digits followed by K high digits, one signed
- * byte each, beta_b[k] = lo + 256 hi (I8; exact for block_n <= 256); F16 has a third copy
- * behind that (again at the next multiple of 256 bytes): per block, K halves fl16(beta) and K
- * halves fl16((beta - fl16(beta)) 2^11).
+ * then, at the next multiple of 256 bytes, the copy the product kernels read inside their loops
+ * (4 bytes per k and block): per block b, K floats (F16 / BF16), or K low digits followed by K
+ * high digits, one signed byte each, beta_b[k] = lo + 256 hi (I8; exact for block_n <= 256);
+ * then, again at the next multiple of 256 bytes, 8 bytes per k and block for the matrix-unit form
+ * of the latency-bound tiling: F16: per block four planes of K halves, fl16(beta),
+ * fl16((beta - fl16(beta)) 2^11) and the same two pieces of the column-weighted checksum
+ * sum_j (j + 1) / block_n * B[k][b*block_n + j] (block_n as passed, also where N is smaller); I8: per block four planes of K signed bytes, the
+ * digits (base 256, balanced, least significant first) of sum_j (j + 1) * B[k][b*block_n + j].
  * block_n <= 0 or >= N gives the plain K-vector B.1 . */
 int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
                          void *beta, void *stream);

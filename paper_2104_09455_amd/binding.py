@@ -15,14 +15,14 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libabft.so")
 
 # enums of abft.h
-NONE, GLOBAL, THREAD, AUTO, REPLICA, THREAD_HALF, TWOSIDED = 0, 1, 2, 3, 4, 5, 6
+NONE, GLOBAL, THREAD, AUTO, REPLICA, THREAD_HALF, TWOSIDED, GLOBAL_WEIGHTED = 0, 1, 2, 3, 4, 5, 6, 7
 ACT_NONE, ACT_RELU = 0, 1
 F16, BF16, I8 = 0, 1, 2
 B_NK, B_KN = 0, 1
 OK = 0
 
 MODE_NAMES = {NONE: "none", GLOBAL: "global", THREAD: "thread", AUTO: "auto", REPLICA: "replica",
-              THREAD_HALF: "thread_half", TWOSIDED: "twosided"}
+              THREAD_HALF: "thread_half", TWOSIDED: "twosided", GLOBAL_WEIGHTED: "global_weighted"}
 DTYPE_NAMES = {F16: "f16", BF16: "bf16", I8: "i8"}
 
 
@@ -41,7 +41,8 @@ class Report(ctypes.Structure):
     _fields_ = [("lhs", ctypes.c_double), ("rhs", ctypes.c_double), ("tau", ctypes.c_double),
                 ("worst_ratio", ctypes.c_double), ("tiles", ctypes.c_uint64),
                 ("frob", ctypes.c_double), ("l1", ctypes.c_double), ("lock", ctypes.c_uint32),
-                ("region", ctypes.c_uint32)]
+                ("region", ctypes.c_uint32), ("fault_row", ctypes.c_int32), ("fault_col", ctypes.c_int32),
+                ("fault_delta", ctypes.c_double), ("ratio_rows", ctypes.c_double), ("ratio_cols", ctypes.c_double)]
 
 
 class Layer(ctypes.Structure):

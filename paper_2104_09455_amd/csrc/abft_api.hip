@@ -93,6 +93,7 @@ inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     // (every wavefront-level scheme is checked per wavefront tile: the same tiles)
     if (mode == ABFT_REPLICA || mode == ABFT_THREAD_HALF || mode == ABFT_TWOSIDED) mode = ABFT_THREAD;
+    if (mode == ABFT_GLOBAL_WEIGHTED) mode = ABFT_GLOBAL;
     static const int force = [] {
         const char* e = std::getenv("ABFT_FORCE_CFG");
         return e ? std::atoi(e) : -1;
@@ -364,45 +365,70 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 // Block = 32 values of k x 8 lanes over n; blockIdx.y = column block.  Not tuned: offline.
 template <int DT>
 __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int K, int N, long long sn,
-                                                              long long sk, int block_n, void* beta, char* beta_k,
-                                                              char* beta_p) {
+                                                              long long sk, int block_n, int wnorm, void* beta,
+                                                              char* beta_k, char* beta_p) {
     constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
     typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
-    __shared__ Wide red[8][32];
+    __shared__ Wide red[2][8][32];
     const int tx = threadIdx.x & 31, ty = threadIdx.x >> 5;
     const int k = blockIdx.x * 32 + tx;
     const int n_begin = blockIdx.y * block_n, n_end = min(N, n_begin + block_n);
-    Wide s = 0;
+    // s: the plain checksum of the block's columns; sv: the same with column j of the block
+    // weighted j + 1 (int8) or (j + 1) / wnorm (floating point; wnorm: the nominal block width, also
+    // where N cuts the block short), the second of the independent linear combinations of Sec. 2.4's
+    // last paragraph
+    Wide s = 0, sv = 0;
     if (k < K) {
         for (int n = n_begin + ty; n < n_end; n += 8) {
             const char* src = B + ((long long)n * sn + (long long)k * sk) * ESIZE;
-            if constexpr (DT == DT_F16) s += (double)(float)*reinterpret_cast<const _Float16*>(src);
-            else if constexpr (DT == DT_BF16) s += (double)(float)*reinterpret_cast<const __bf16*>(src);
-            else s += (long long)*reinterpret_cast<const signed char*>(src);
+            Wide x;
+            if constexpr (DT == DT_F16) x = (double)(float)*reinterpret_cast<const _Float16*>(src);
+            else if constexpr (DT == DT_BF16) x = (double)(float)*reinterpret_cast<const __bf16*>(src);
+            else x = (long long)*reinterpret_cast<const signed char*>(src);
+            s += x;
+            if constexpr (DT == DT_I8) sv += x * (n - n_begin + 1);
+            else sv += x * ((double)(n - n_begin + 1) / (double)wnorm);
         }
     }
-    red[ty][tx] = s;
+    red[0][ty][tx] = s;
+    red[1][ty][tx] = sv;
     __syncthreads();
     if (ty == 0 && k < K) {
-        Wide a = 0;
-        for (int y = 0; y < 8; ++y) a += red[y][tx];
+        Wide a = 0, av = 0;
+        for (int y = 0; y < 8; ++y) {
+            a += red[0][y][tx];
+            av += red[1][y][tx];
+        }
         reinterpret_cast<Wide*>(beta)[(long long)k * gridDim.y + blockIdx.y] = a;
         // second copy, per column block along k, for the in-kernel checksum dot product of the
-        // direct-to-LDS kernel: floats, or (int8) balanced base-256 digits, K low then K high
+        // direct-to-LDS kernel: floats, or (int8) balanced base-256 digits, K low then K high;
+        // third copy (8 bytes per k and block) for the streaming kernel's matrix-unit form: fp16:
+        // four planes of K halves, hi = fl16(beta), lo = fl16((beta - hi) 2^11), and the same two
+        // pieces of the column-weighted checksum; int8: four planes of K digits of the
+        // column-weighted checksum (balanced base 256, least significant first)
         if constexpr (DT == DT_I8) {
             const long long lo = (long long)(signed char)(a & 0xff);
             const long long hi = (a - lo) >> 8;
             signed char* d = reinterpret_cast<signed char*>(beta_k) + (long long)blockIdx.y * 2 * K;
             d[k] = (signed char)lo;
             d[K + k] = (signed char)(hi < -128 ? -128 : (hi > 127 ? 127 : hi));
+            signed char* dv = reinterpret_cast<signed char*>(beta_p) + (long long)blockIdx.y * 8 * K;
+            long long rest = av;
+            for (int q = 0; q < 4; ++q) {
+                const long long digit = (long long)(signed char)(rest & 0xff);
+                dv[(long long)q * K + k] = (signed char)digit;
+                rest = (rest - digit) >> 8;
+            }
         } else {
             reinterpret_cast<float*>(beta_k)[(long long)blockIdx.y * K + k] = (float)a;
             if constexpr (DT == DT_F16) {
+                _Float16* pl = reinterpret_cast<_Float16*>(beta_p) + (long long)blockIdx.y * 4 * K;
                 const _Float16 hi = (_Float16)(float)a;
-                const _Float16 lo = (_Float16)(((float)a - (float)hi) * 2048.f);
-                _Float16* pl = reinterpret_cast<_Float16*>(beta_p) + (long long)blockIdx.y * 2 * K;
                 pl[k] = hi;
-                pl[K + k] = lo;
+                pl[K + k] = (_Float16)(((float)a - (float)hi) * 2048.f);
+                const _Float16 vhi = (_Float16)(float)av;
+                pl[2 * K + k] = vhi;
+                pl[3 * K + k] = (_Float16)(((float)av - (float)vhi) * 2048.f);
             }
         }
     }
@@ -520,10 +546,10 @@ int pre_rows_per_block(int bm, int M, int K) {
 // the activation-checksum kernel's dot products, then, 256-byte aligned, the per-block copy
 // along k for the in-kernel dot product (4 bytes per k and block reserved).
 size_t beta_k_offset(int K, int nb) { return align_up((size_t)K * nb * 8, 256); }
-// third copy (fp16 only): per block, K halves hi = fl16(beta) then K halves lo = fl16((beta - hi) 2^11),
-// the two columns of the extra operand with which the streaming kernel forms the dot product
+// third copy, 8 bytes per k and block: the columns of the extra operand with which the streaming
+// kernel forms its dot products on the matrix unit (see weight_checksum_kernel)
 size_t beta_p_offset(int K, int nb) { return beta_k_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
-size_t beta_total_bytes(int K, int nb) { return beta_p_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
+size_t beta_total_bytes(int K, int nb) { return beta_p_offset(K, nb) + align_up((size_t)K * nb * 8, 256); }
 
 WsLayout ws_layout(int M, int N, int K, int cfg) {
     CfgInfo ci = cfg_info_host(cfg);
@@ -587,6 +613,7 @@ int select_mode(int M, int N, int K, int dt) {
 hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, int layout, int dt, int block_n,
                                   void* beta_buf, hipStream_t st) {
     long long sn = layout == ABFT_B_NK ? ldb : 1, sk = layout == ABFT_B_NK ? 1 : ldb;
+    const int wnorm = block_n > 0 ? block_n : N;
     if (block_n <= 0 || block_n > N) block_n = N;
     void* beta = beta_buf;
     char* beta_k = reinterpret_cast<char*>(beta_buf) + beta_k_offset(K, (int)cdiv(N, block_n));
@@ -594,11 +621,11 @@ hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, in
     dim3 grid((unsigned)cdiv(K, 32), (unsigned)cdiv(N, block_n)), block(256);
     const char* b = reinterpret_cast<const char*>(B);
     if (dt == ABFT_F16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k, beta_p);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p);
     else if (dt == ABFT_BF16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k, beta_p);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p);
     else
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, beta, beta_k, beta_p);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p);
     return hipGetLastError();
 }
 
@@ -635,7 +662,7 @@ hipError_t launch_act_checksum(const Problem& pr, void* alpha_out, int rows_per_
 
 int validate_common(const Problem& pr, int mode, const uint32_t* flag) {
     if (!valid_dtype(pr.dtype)) return ABFT_E_ENUM;
-    if (mode < ABFT_NONE || mode > ABFT_TWOSIDED) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_GLOBAL_WEIGHTED) return ABFT_E_ENUM;
     if (pr.b_layout != ABFT_B_NK && pr.b_layout != ABFT_B_KN) return ABFT_E_ENUM;
     if (pr.M <= 0 || pr.N <= 0 || pr.K <= 0) return ABFT_E_SHAPE;
     if (!pr.A || !pr.B || !pr.C) return ABFT_E_NULL;
@@ -668,6 +695,9 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     int rc = validate_common(pr, mode, flag);
     if (rc != ABFT_OK) return rc;
     if (mode == ABFT_AUTO) mode = select_mode(pr.M, pr.N, pr.K, pr.dtype);
+    // the weighted checks are the global scheme with two more checksum pairs
+    const bool weighted = mode == ABFT_GLOBAL_WEIGHTED;
+    if (weighted) mode = ABFT_GLOBAL;
 
     const bool avec = a_vectorisable(pr), bvec = b_vectorisable(pr);
     const bool all16 = avec && bvec;
@@ -691,6 +721,9 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
         g.H = pr.cg.H; g.W = pr.cg.W; g.Cin = pr.cg.Cin; g.KH = pr.cg.KH; g.KW = pr.cg.KW;
         g.stride = pr.cg.stride; g.pad = pr.cg.pad; g.OH = pr.OH; g.OW = pr.OW;
     }
+    // (they ride in spare columns of the streaming kernel's extra matrix operand: latency-bound
+    // products with fp16 or int8 operands)
+    if (weighted && (!cfg_is_stream(cfg) || pr.dtype == ABFT_BF16)) return ABFT_E_UNSUPPORTED;
     g.tiles_m = (int)cdiv(pr.M, ci.bm);
     g.tiles_n = (int)cdiv(pr.N, ci.bn);
     g.flag = flag;
@@ -731,6 +764,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
                 return ABFT_E_HIP;
             beta_used = ws + w.off_beta;
         }
+        if (weighted) kmode = MODE_GLOBAL_W;
         if (fused_global(pr, ci)) {
             // the direct-to-LDS kernel forms the activation checksum's dot product with the weight
             // checksums itself, from the A tiles it multiplies (steps 1-3 inside the product's loop)
@@ -913,7 +947,7 @@ int run_conv(const Problem& pr, int mode, const void* beta, void* workspace, siz
 size_t plain_workspace_bytes(int M, int N, int K, int dtype, int mode) {
     if (mode == ABFT_AUTO) mode = select_mode(M, N, K, dtype);
     // only the global scheme keeps anything outside the operands
-    return mode == ABFT_GLOBAL ? ws_bytes_any_cfg(M, N, K) : 0;
+    return (mode == ABFT_GLOBAL || mode == ABFT_GLOBAL_WEIGHTED) ? ws_bytes_any_cfg(M, N, K) : 0;
 }
 
 }  // namespace
@@ -1273,7 +1307,7 @@ int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* ld
 
 int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
-    if (mode < ABFT_NONE || mode > ABFT_TWOSIDED) return ABFT_E_ENUM;
+    if (mode < ABFT_NONE || mode > ABFT_GLOBAL_WEIGHTED) return ABFT_E_ENUM;
     abft_plan::Layer& L = plan->layers[layer];
     L.mode = mode == ABFT_AUTO ? select_mode(L.desc.M, L.desc.N, L.desc.K, L.desc.dtype) : mode;
     return ABFT_OK;
@@ -1325,6 +1359,7 @@ const char* abft_strerror(int code) {
         case ABFT_E_INJECT: return "fault descriptor out of range";
         case ABFT_E_HIP: return "HIP runtime call failed";
         case ABFT_E_PLAN: return "bad plan handle or layer index";
+        case ABFT_E_UNSUPPORTED: return "scheme not available for this product";
     }
     return "unknown error code";
 }

@@ -27,7 +27,9 @@ enum { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2 };
 // MODE_GLOBAL_PRE (kernel-internal): the global scheme with the checksum dot products left by
 // the activation-checksum kernel instead of formed inside the product's loop
 enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3, MODE_REPL = 4, MODE_THREAD_H = 5,
-       MODE_TWOSIDED = 6 };
+       MODE_TWOSIDED = 6, MODE_GLOBAL_W = 7 };
+// MODE_GLOBAL_W: the global scheme with three independent checksum pairs per workgroup tile
+// (Sec. 2.4, last paragraph): plain, rows weighted, columns weighted; streaming kernel only.
 // MODE_REPL: thread-level replication with single accumulation (Sec. 5.1): every MFMA of the
 // product is issued a second time into one accumulator block per A fragment; the sum of those
 // blocks must equal the sum of the wavefront tile.  Checked exactly like MODE_THREAD.
@@ -45,6 +47,14 @@ struct Report {  // mirrors abft_report_t
     unsigned long long tiles;
     double frob, l1;
     unsigned int lock, region;
+    // weighted global scheme: where a single wrong element of the reported region would sit
+    int fault_row, fault_col;
+    double fault_delta, ratio_rows, ratio_cols;
+};
+// localisation fields of one comparison (weighted global scheme)
+struct Located {
+    int row, col;
+    double delta, ratio_rows, ratio_cols;
 };
 
 // Record one comparison in the optional diagnostics block: counts it and, under a small
@@ -53,7 +63,7 @@ struct Report {  // mirrors abft_report_t
 // region index, so the outcome does not depend on scheduling.  The spin is bounded; a
 // wavefront that cannot get the lock skips its update.
 __device__ __forceinline__ void report_update(Report* rep, double ratio, double lhs, double rhs, double tau,
-                                              double frob, double l1, unsigned region) {
+                                              double frob, double l1, unsigned region, const Located* loc = nullptr) {
     atomicAdd(&rep->tiles, 1ull);
     volatile Report* v = rep;
     {
@@ -80,6 +90,13 @@ __device__ __forceinline__ void report_update(Report* rep, double ratio, double 
         v->frob = frob;
         v->l1 = l1;
         v->region = region + 1u;
+        if (loc) {
+            v->fault_row = loc->row;
+            v->fault_col = loc->col;
+            v->fault_delta = loc->delta;
+            v->ratio_rows = loc->ratio_rows;
+            v->ratio_cols = loc->ratio_cols;
+        }
     }
     __threadfence();
     atomicExch(&rep->lock, 0u);

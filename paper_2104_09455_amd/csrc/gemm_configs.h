@@ -47,7 +47,7 @@ constexpr CfgInfo cfg_info() {
     typedef typename CfgOf<DT_F16, ID>::type C;  // identical for every dtype (rows / columns / k bytes)
     constexpr int ns = CfgOf<DT_F16, ID>::NSTAGE;
     constexpr int kw = CfgOf<DT_F16, ID>::KWAYS;
-    constexpr int lds = cfg_is_stream(ID) ? kw * ns * ((C::BM + C::BN) * 128 + 256)
+    constexpr int lds = cfg_is_stream(ID) ? kw * ns * ((C::BM + C::BN) * 128 + 768)
                                           : (ns ? ns * ((C::BM + C::BN) * 128 + (C::THREADS / 64) * 256) : C::LDS_BYTES);
     return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, lds, ns ? 1 : 0, kw, cfg_is_stream(ID) ? 128 : 32};
 }

@@ -23,7 +23,7 @@ template <class CFG, int NST>
 struct StreamLayout {
     static constexpr int KW = 4;                                 // wavefronts per workgroup
     static constexpr int AB_STAGE = (CFG::BM + CFG::BN) * 128;
-    static constexpr int WSTAGE = AB_STAGE + 256;                // one wavefront's stage: A, B, weight checksums
+    static constexpr int WSTAGE = AB_STAGE + 768;                // one wavefront's stage: A, B, weight checksums (six planes of 128 bytes)
     static constexpr int LDS_BYTES = KW * NST * WSTAGE;
     static constexpr int NQA = CFG::BM / 8, NQB = CFG::BN / 8;   // 1 KB copies per k tile
     static_assert(CFG::WAVES_M == 1 && CFG::WAVES_N == 1 && CFG::MI == 32 && CFG::BKB == 128, "one register tile");
@@ -43,14 +43,19 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     typedef typename MMA::AccT AccT;
     constexpr int TM = CFG::TM, TN = CFG::TN, BM = CFG::BM, BN = CFG::BN, BKB = 128;
     constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
-    constexpr bool GDOT = MODE == MODE_GLOBAL;  // global scheme: in-kernel checksum dot product
+    constexpr bool WGT = MODE == MODE_GLOBAL_W;  // three independent checksum pairs per tile (Sec. 2.4, last paragraph)
+    constexpr bool GDOT = MODE == MODE_GLOBAL || WGT;  // global scheme: in-kernel checksum dot product
     // ... on the matrix unit (fp16, int8): the weight checksums, split in two exact pieces, are two
     // columns of an extra B operand, multiplied with every A fragment; the unit idles in these
     // latency-bound products, and the vector FMAs of the other form would cost more.  bf16 (three
     // pieces) keeps the vector form.
     constexpr bool MDOT = GDOT && DT != DT_BF16;
     constexpr bool IS_INT = DT == DT_I8;
-    constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB + (GDOT ? 1 : 0);
+    static_assert(!WGT || MDOT, "the weighted checksums ride in spare columns of the matrix-unit form");
+    // copies of weight-checksum planes per k tile: the plain pair, and for the weighted scheme the
+    // column-weighted checksums behind it (fp16: two planes of halves; int8: four planes of digits)
+    constexpr int NBETA = !GDOT ? 0 : (WGT ? (IS_INT ? 3 : 2) : 1);
+    constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB + NBETA;
     constexpr int ROWB = 128, A_STAGE = BM * ROWB;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -114,13 +119,19 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     // weight checksums of this tile's column block: lane l copies bytes 4l .. 4l+3 of the k tile's
     // 256 (fp16 / bf16: float l of 64; int8: low digits in lanes 0-31, high digits in lanes 32-63)
     const char* beta_ptr = g_zero_chunk;
+    const char* betaw_ptr = g_zero_chunk;   // weighted scheme: the column-weighted checksums' planes
     if constexpr (GDOT) {
         const long long blk = (long long)tile_n * p.K;
         // (int8 digits and fp16 halves: two planes per block, 128 bytes of each per k tile, the first
         // copied by lanes 0-31, the second by lanes 32-63; bf16: 64 floats per k tile)
         if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (long long)wave * BK + (lane & 31) * 4;
-        else if constexpr (MDOT) beta_ptr = p.beta_p + blk * 4 + (lane >> 5) * 2 * (long long)p.K + (long long)wave * BK * 2 + (lane & 31) * 4;
+        else if constexpr (MDOT) beta_ptr = p.beta_p + blk * 8 + (lane >> 5) * 2 * (long long)p.K + (long long)wave * BK * 2 + (lane & 31) * 4;
         else beta_ptr = p.beta_k + (blk + (long long)wave * BK + lane) * 4;
+        if constexpr (WGT) {
+            // fp16: planes 2, 3 of the block (halves); int8: four planes of digits in the same region
+            if constexpr (IS_INT) betaw_ptr = p.beta_p + blk * 8 + (lane >> 5) * (long long)p.K + (long long)wave * BK + (lane & 31) * 4;
+            else betaw_ptr = p.beta_p + blk * 8 + (2 + (lane >> 5)) * 2 * (long long)p.K + (long long)wave * BK * 2 + (lane & 31) * 4;
+        }
     }
     constexpr int BETA_ADV = KW * (MDOT ? 128 : BK * 4);
     // first k offset (within a k tile) of the four bytes this lane copies: one float, two halves of a
@@ -167,9 +178,17 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         }
         if constexpr (GDOT) {
             // this lane's four bytes of weight checksums cover k offsets beta_k0 .. of the tile
-            const char* src = (SHORT && beta_k0 >= rem_chunks * (16 / ESIZE)) ? g_zero_chunk : beta_ptr;
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+            const bool past = SHORT && beta_k0 >= rem_chunks * (16 / ESIZE);
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(past ? g_zero_chunk : beta_ptr),
                                              (__attribute__((address_space(3))) void*)(abase + LAY::AB_STAGE), 4, 0, 0);
+            if constexpr (WGT) {
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)(past ? g_zero_chunk : betaw_ptr),
+                                                 (__attribute__((address_space(3))) void*)(abase + LAY::AB_STAGE + 256), 4, 0, 0);
+                if constexpr (IS_INT)   // digits 2 and 3 of the column-weighted checksums
+                    __builtin_amdgcn_global_load_lds(
+                        (const __attribute__((address_space(1))) void*)(past ? g_zero_chunk : betaw_ptr + 2 * (long long)p.K),
+                        (__attribute__((address_space(3))) void*)(abase + LAY::AB_STAGE + 512), 4, 0, 0);
+            }
         }
     };
     auto issue_loads = [&](int stage) {
@@ -186,6 +205,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     // to this wavefront's next k tile: KW tiles further along k
     auto advance = [&]() {
         if constexpr (GDOT) beta_ptr += BETA_ADV;
+        if constexpr (WGT) betaw_ptr += BETA_ADV;
         if constexpr (!CONV) {
 #pragma unroll
             for (int q = 0; q < NQA; ++q) aptr[q] += ((a_valid >> q) & 1u) ? KW * BKB : 0;
@@ -260,8 +280,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     };
     // matrix-unit form: lanes of column 0 / 1 of the extra B operand read the first / second plane of
     // the weight checksums (their k chunk, like any fragment), all other columns are zero
+    // (weighted scheme: the planes of the column-weighted checksums follow in columns 2 ..)
+    constexpr int GCOLS = WGT ? (IS_INT ? 6 : 4) : 2;
     const int gcol = lane & 31;
-    const int gb_off = LAY::AB_STAGE + (gcol == 1 ? 128 : 0) + fgrp * 16;
+    const int gb_off = LAY::AB_STAGE + (gcol < GCOLS ? gcol : 0) * 128 + fgrp * 16;
     i32x4 fg[2];
     Acc gchk[MDOT ? TM : 1];
     if constexpr (MDOT) {
@@ -275,7 +297,7 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
         if constexpr (MDOT) {
             const i32x4 g = *reinterpret_cast<const i32x4*>(st + gb_off + kk * 32);
             const i32x4 z = {0, 0, 0, 0};
-            fg[buf] = gcol < 2 ? g : z;
+            fg[buf] = gcol < GCOLS ? g : z;
         }
 #pragma unroll
         for (int i = 0; i < TM; ++i) fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + pos[kk]);
@@ -363,6 +385,10 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     Wide s_sum = 0;
     int s_lo = 0, s_hi = 0;
     float f2 = 0.f, l1 = 0.f;
+    // weighted scheme: output summations with the rows / the columns of the tile weighted (int8:
+    // weights i + 1 and j + 1; floating point: (i + 1) / BM and (j + 1) / BN), and their norms
+    Wide s_rows = 0, s_cols = 0;
+    float f2_rows = 0.f, l1_rows = 0.f, f2_cols = 0.f, l1_cols = 0.f;
     // test hook: a fault in a finished value after the addition (k_after = -2): block, register
     // and lane that hold element (f_row, f_col)
     int f_blk = -1, f_rr = 0;
@@ -434,7 +460,127 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
                         l1 += (__builtin_fabsf(v[0]) + __builtin_fabsf(v[1])) + (__builtin_fabsf(v[2]) + __builtin_fabsf(v[3]));
                 }
             }
+            if constexpr (WGT) {
+                const int col_l = j * 32 + tc.lrow;
+#pragma unroll
+                for (int rr = 0; rr < 4; ++rr) {
+                    const int row_l = i * 32 + 8 * wave + 4 * tc.lgrp + rr;
+                    if constexpr (IS_INT) {
+                        s_rows += (long long)v[rr] * (row_l + 1);
+                        s_cols += (long long)v[rr] * (col_l + 1);
+                    } else {
+                        const float xr = v[rr] * ((float)(row_l + 1) * (1.0f / BM));
+                        const float xc = v[rr] * ((float)(col_l + 1) * (1.0f / BN));
+                        s_rows += (double)v[rr] * ((double)(row_l + 1) * (1.0 / BM));
+                        s_cols += (double)v[rr] * ((double)(col_l + 1) * (1.0 / BN));
+                        f2_rows += xr * xr;
+                        l1_rows += __builtin_fabsf(xr);
+                        f2_cols += xc * xc;
+                        l1_cols += __builtin_fabsf(xc);
+                    }
+                }
+            }
         }
+    if constexpr (WGT) {
+        // ---- three comparisons for this tile (Sec. 2.4, last paragraph): the plain one, one with
+        // the rows weighted, one with the columns weighted.  Checksum side, from the extra result
+        // blocks: columns 0, 1 hold A . (plain weight checksums, two pieces) row by row, so weighting
+        // their rows gives (w^T A)(B 1); columns 2 .. hold A . (column-weighted weight checksums).
+        if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;
+        Wide d_plain = 0, d_rows = 0, d_cols = 0;
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int row_l = i * 32 + 8 * (r >> 2) + 4 * tc.lgrp + (r & 3);
+                if constexpr (IS_INT) {
+                    const long long g = gchk[i][r];
+                    if (gcol < 2) {
+                        const long long x = gcol == 1 ? 256 * g : g;
+                        d_plain += x;
+                        d_rows += x * (row_l + 1);
+                    } else if (gcol < 6) {
+                        d_cols += g << (8 * (gcol - 2));
+                    }
+                } else {
+                    const double g = (double)gchk[i][r] * ((gcol & 1) ? 1.0 / 2048.0 : 1.0);
+                    if (gcol < 2) {
+                        d_plain += g;
+                        d_rows += g * ((double)(row_l + 1) * (1.0 / BM));
+                    } else if (gcol < 4) {
+                        d_cols += g;
+                    }
+                }
+            }
+        Wide sums[6] = {s_sum, s_rows, s_cols, d_plain, d_rows, d_cols};
+        float norms[6] = {f2, l1, f2_rows, l1_rows, f2_cols, l1_cols};
+#pragma unroll
+        for (int q = 0; q < 6; ++q) {
+            sums[q] = wave_sum(sums[q]);
+            norms[q] = IS_INT ? 0.f : wave_sum(norms[q]);
+        }
+        __syncthreads();  // everyone is done reading the partial tiles
+        double* redd = reinterpret_cast<double*>(smem);
+        Wide* redw = reinterpret_cast<Wide*>(smem) + 6 * KW;
+        if (lane == 0) {
+#pragma unroll
+            for (int q = 0; q < 6; ++q) {
+                redd[6 * wave + q] = (double)norms[q];
+                redw[6 * wave + q] = sums[q];
+            }
+        }
+        __syncthreads();
+        if (tid == 0) {
+            double tn_[6];
+            Wide ts_[6];
+            for (int q = 0; q < 6; ++q) {
+                tn_[q] = 0.0;
+                ts_[q] = 0;
+                for (int w = 0; w < KW; ++w) {
+                    tn_[q] += redd[6 * w + q];
+                    ts_[q] += redw[6 * w + q];
+                }
+            }
+            const unsigned t = (unsigned)(tile_m * p.tiles_n + tile_n);
+            bool bad = false;
+            double ratio[3], tau0 = 0.0;
+            for (int c = 0; c < 3; ++c) {
+                const double res = __builtin_fabs((double)(ts_[c] - ts_[3 + c]));
+                if constexpr (IS_INT) {
+                    const bool differs = ts_[c] != ts_[3 + c];
+                    bad |= differs;
+                    ratio[c] = differs ? __builtin_huge_val() : 0.0;
+                } else {
+                    const double tau = p.tol_coeff * __builtin_sqrt(tn_[2 * c]) + p.tol_l1 * tn_[2 * c + 1];
+                    const bool finite = __builtin_isfinite((double)ts_[c]) && __builtin_isfinite((double)ts_[3 + c]) &&
+                                        __builtin_isfinite(tn_[2 * c]);
+                    bad |= !finite || !(res <= tau);
+                    ratio[c] = !finite ? __builtin_huge_val() : (tau > 0.0 ? res / tau : (res > 0.0 ? __builtin_huge_val() : 0.0));
+                    if (c == 0) tau0 = tau;
+                }
+            }
+            if (bad) atomicOr(p.flag, 1u);
+            if (p.report) {
+                // where a single wrong element of this tile would sit: its weights are the ratios of
+                // the weighted residuals to the plain one
+                Located loc = {-1, -1, 0.0, ratio[1], ratio[2]};
+                const double r0 = (double)(ts_[0] - ts_[3]);
+                if (ratio[0] > 1.0 && r0 != 0.0) {
+                    const double wr = (double)(ts_[1] - ts_[4]) / r0, wc = (double)(ts_[2] - ts_[5]) / r0;
+                    const long long li = __builtin_llrint(IS_INT ? wr : wr * BM) - 1, lj = __builtin_llrint(IS_INT ? wc : wc * BN) - 1;
+                    if (li >= 0 && li < BM && lj >= 0 && lj < BN) {
+                        loc.row = tile_m * BM + (int)li;
+                        loc.col = tile_n * BN + (int)lj;
+                        loc.delta = r0;
+                    }
+                }
+                const double worst = ratio[0] > ratio[1] ? (ratio[0] > ratio[2] ? ratio[0] : ratio[2])
+                                                         : (ratio[1] > ratio[2] ? ratio[1] : ratio[2]);
+                report_update(p.report, worst, (double)ts_[0], (double)ts_[3], tau0, __builtin_sqrt(tn_[0]), tn_[1], t, &loc);
+            }
+        }
+        return;
+    }
     if constexpr (CHECKED) {
         // comparison (Sec. 2.4 step 4 / Sec. 5.2.2) for this tile
         if constexpr (IS_INT) s_sum = ((long long)s_hi << 16) + (long long)s_lo;

@@ -117,7 +117,7 @@ def test_argument_validation_without_a_gpu(lib):
     assert g(M=0) == -2 and g(N=-1) == -2 and g(K=0) == -2
     assert g(A=None) == -1 and g(B=None) == -1 and g(C=None) == -1
     assert g(lda=3) == -3 and g(ldb=3) == -3 and g(ldc=3) == -3
-    assert g(dtype=3) == -4 and g(mode=7) == -4 and g(mode=-1) == -4 and g(layout=2) == -4
+    assert g(dtype=3) == -4 and g(mode=8) == -4 and g(mode=-1) == -4 and g(layout=2) == -4
     assert g(mode=1, flag=None) == -1
     assert g(mode=1) == -5  # global needs a workspace
     with pytest.raises(B.AbftError) as e:

@@ -159,17 +159,29 @@ def test_checksum_vectors(dtype):
                 assert np.array_equal(beta_b.reshape(K, nb).T, blocks)
                 digits = second[:nb * 2 * K].view(np.int8).astype(np.int64).reshape(nb, 2, K)
                 assert np.array_equal(digits[:, 0] + 256 * digits[:, 1], blocks)
+                # third copy: four planes of digits of the column-weighted checksum sum_j (j + 1) B[k][16 b + j]
+                third = second[-(-(nb * K * 4) // 256) * 256:][:nb * K * 8].view(np.int8).astype(np.int64).reshape(nb, 8, K)
+                wsum = np.stack([(Bm[:, b * 16:(b + 1) * 16].astype(np.int64) * (np.arange(min(16, N - b * 16)) + 1)).sum(axis=1)
+                                 for b in range(nb)])
+                assert np.array_equal(sum(third[:, q] * 256 ** q for q in range(4)), wsum)
             else:
                 assert np.allclose(beta, b_ref, rtol=1e-12, atol=1e-12)
                 assert np.allclose(beta_b.reshape(K, nb).T, blocks, rtol=1e-12, atol=1e-12)
                 f32 = second[:nb * K * 4].view(np.float32).reshape(nb, K)
                 assert np.array_equal(f32, blocks.astype(np.float32))
                 if dtype == "f16":
-                    # third copy: per block K halves hi = fl16(beta), K halves lo = fl16((beta - hi) 2^11)
-                    third = second[-(-(nb * K * 4) // 256) * 256:][:nb * K * 4].view(np.float16).reshape(nb, 2, K)
+                    # third copy: per block four planes of K halves: hi = fl16(beta), lo = fl16((beta - hi) 2^11),
+                    # then the same two pieces of the column-weighted checksum sum_j (j + 1) / 16 B[k][16 b + j]
+                    third = second[-(-(nb * K * 4) // 256) * 256:][:nb * K * 8].view(np.float16).reshape(nb, 4, K)
                     hi = f32.astype(np.float16)
                     lo = ((f32 - hi.astype(np.float32)) * np.float32(2048)).astype(np.float16)
                     assert np.array_equal(third[:, 0], hi) and np.array_equal(third[:, 1], lo)
+                    Bw = oracle.widen(Bm, dtype)
+                    wsum = np.stack([(Bw[:, b * 16:(b + 1) * 16] * ((np.arange(min(16, N - b * 16)) + 1) / 16.0)).sum(axis=1)
+                                     for b in range(nb)]).astype(np.float32)
+                    vhi = wsum.astype(np.float16)
+                    assert np.array_equal(third[:, 2], vhi)
+                    assert np.array_equal(third[:, 3], ((wsum - vhi.astype(np.float32)) * np.float32(2048)).astype(np.float16))
         if dtype == "i8":
             assert np.array_equal(alpha.cpu().numpy(), a_ref)
         else:
@@ -367,3 +379,83 @@ def test_clean_runs_raise_no_false_alarm(dtype):
                 worst = max(worst, res.report.worst_ratio)
     print(f"worst residual / tolerance over the campaign ({dtype}): {worst:.3f}", flush=True)
     assert worst < 0.5
+
+
+# ------------------------------------------- several checksums per tile (Sec. 2.4, last paragraph)
+@pytest.mark.parametrize("dtype", ["i8", "f16"])
+@pytest.mark.parametrize("shape", [(64, 64, 64), (200, 384, 512), (256, 1024, 1024), (96, 2048, 192), (512, 2048, 1024)])
+def test_weighted_global_scheme_flags_and_locates(shape, dtype):
+    """ABFT_GLOBAL_WEIGHTED on the latency-bound tiling: clean runs pass all three comparisons of
+    every tile and leave C as the oracle's; a planted fault is flagged, and the reported position
+    and size are those of the planted element (int8: always, exactly; fp16: whenever the fault
+    is far outside the tolerance), equal to what the oracle's weighted check of that tile locates."""
+    import math
+    from gpu_util import DeviceGemm, c_close
+    M, N, K = shape
+    dt = {"f16": B.F16, "i8": B.I8}[dtype]
+    g = DeviceGemm(M, N, K, dtype, seed=800 + M, dist_a="uniform_01" if dtype == "f16" else "int8",
+                   dist_b="weights" if dtype == "f16" else "int8")
+    assert g.rm <= 64 and g.rn <= 64          # the streaming tiles
+    C_ref = oracle.gemm(g.A, g.Bm, dtype)
+    flag, rep = g.run(B.GLOBAL_WEIGHTED)
+    assert flag == 0 and c_close(g.C(), C_ref, dtype)
+    assert rep.tiles == math.ceil(M / g.rm) * math.ceil(N / g.rn)
+    assert rep.worst_ratio < 0.5 and rep.ratio_rows < 0.5 and rep.ratio_cols < 0.5
+    assert (rep.fault_row, rep.fault_col) == (-1, -1)
+    # every tile's three comparisons on the oracle's side as well
+    for t in list(oracle.tiles(M, N, g.rm, g.rn))[:6]:
+        assert not oracle.weighted_region_check(g.A, g.Bm, C_ref, dtype, *t, block_m=g.rm, block_n=g.rn).flag
+    parts = B.abft_k_parts(M, N, K, dt, B.GLOBAL)
+    rng = np.random.default_rng(M + N)
+    located = 0
+    for t in range(24):
+        i, j = int(rng.integers(M)), int(rng.integers(N))
+        bit = int(rng.integers(32)) if dtype == "i8" else (30, int(rng.integers(20, 30)), int(rng.integers(8, 20)))[t % 3]
+        k_after = (-1, -2, g.k_step * int(rng.integers(1, max(2, K // g.k_step))))[t % 3]
+        if k_after >= K:
+            k_after = -1
+        print(f"case weighted dtype={dtype} shape={shape} fault=({i},{j},bit {bit},k_after {k_after})", flush=True)
+        flag, rep = g.run(B.GLOBAL_WEIGHTED, inject=B.Fault(i, j, bit, k_after))
+        if k_after == -2:
+            C_bad = oracle.inject(g.A, g.Bm, C_ref, dtype, i, j, bit)
+        else:
+            C_bad = oracle.inject(g.A, g.Bm, C_ref, dtype, i, j, bit, k_after=k_after,
+                                  k_set=parts[oracle.part_of(parts, (K if k_after < 0 else k_after) - 1)])
+        r0, r1, c0, c1 = g.region_of(i, j, B.GLOBAL)
+        wc = oracle.weighted_region_check(g.A, g.Bm, C_bad, dtype, r0, r1, c0, c1, block_m=g.rm, block_n=g.rn)
+        if dtype == "i8":
+            assert flag == 1 and wc.flag
+            li, lj, delta = oracle.locate(wc, dtype, g.rm, g.rn)
+            assert (r0 + li, c0 + lj) == (i, j)
+            assert (rep.fault_row, rep.fault_col, rep.fault_delta) == (i, j, float(delta))
+            assert np.array_equal(g.C(), ((C_bad + 2 ** 31) % 2 ** 32) - 2 ** 31)
+            located += 1
+            continue
+        if not math.isfinite(C_bad[i, j]):
+            assert flag == 1
+            continue
+        delta = abs(wc.plain.residual)
+        if delta >= 2 * wc.plain.tau:
+            assert flag == 1
+        elif max(abs(c.residual) / c.tau for c in (wc.plain, wc.rows, wc.cols)) <= 0.4:
+            assert flag == 0
+        if delta >= 200 * wc.plain.tau:
+            li, lj, d = oracle.locate(wc, dtype, g.rm, g.rn)
+            assert (r0 + li, c0 + lj) == (i, j)
+            assert (rep.fault_row, rep.fault_col) == (i, j)
+            assert rep.fault_delta == pytest.approx(d, rel=1e-3)
+            located += 1
+    assert located > 3
+
+
+def test_weighted_global_scheme_is_refused_where_it_does_not_exist():
+    import torch
+    from gpu_util import DEV
+    t = torch.zeros(1 << 20, dtype=torch.float16, device=DEV)
+    flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+    ws = torch.zeros(1 << 24, dtype=torch.uint8, device=DEV)
+    for (M, N, K, dt) in [(4096, 4096, 64, B.F16), (64, 64, 64, B.BF16)]:
+        with pytest.raises(B.AbftError) as e:
+            B.abft_gemm(M, N, K, t, K, t, K, B.B_NK, t, N, dt, B.GLOBAL_WEIGHTED, workspace=ws,
+                        workspace_bytes=ws.numel(), fault_flag=flag)
+        assert e.value.code == -9

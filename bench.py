@@ -303,9 +303,10 @@ def measured_ceilings(hip, gen):
 # --------------------------------------------------------------------------- #
 def chain_leg(gen, batch=256, steps=300):
     """DLRM's two MLPs as chains (Sec. 2.4 step 4): ReLU fused into the store of every layer but
-    each MLP's last, layer l's output handed to layer l + 1 as its input, one library call per
-    pass.  Times the pass with the selector's schemes and unprotected (device time, replayed
-    from a graph of the pass)."""
+    each MLP's last, layer l's output handed to layer l + 1 as its input.  Two forms, both timed as
+    device time of a whole pass replayed from a graph: one kernel launch per layer
+    (abft_plan_run_all), and one launch per chain (abft_plan_run_chain: bottom MLP behind its K = 13
+    layer, top MLP), each with the selector's schemes, all-global and unprotected."""
     layers = wl.dlrm_layers(batch)
     rs = [LayerRun(l, "f16", gen) for l in layers]
     plan = B.abft_plan_create([B.Layer(r.layer.M, r.layer.N, r.layer.K, r.dt, B.B_NK, 0, B.Conv(), r.B.data_ptr(),
@@ -323,14 +324,26 @@ def chain_leg(gen, batch=256, steps=300):
     io = B.PlanIO(ins, [r.layer.K for r in rs], [r.C for r in rs], [r.layer.N for r in rs])
     side = torch.cuda.Stream()
     side.wait_stream(torch.cuda.current_stream())
+    n_bot = last[0] + 1                      # layers of the bottom MLP
 
-    def pass_us():
+    def per_layer(st):
+        B.abft_plan_run_all(plan, io, flag, -1, st)
+
+    def one_launch(st):
+        # bottom MLP: its first layer (K = 13) on its own, the rest as one chain; top MLP: one chain
+        B.abft_plan_run(plan, 0, rs[0].A, rs[0].layer.K, rs[0].C, rs[0].layer.N, flag, st)
+        B.abft_plan_run_chain(plan, 1, n_bot - 1, rs[0].C, rs[0].layer.N, [r.C for r in rs[1:n_bot]],
+                              [r.layer.N for r in rs[1:n_bot]], flag, st)
+        B.abft_plan_run_chain(plan, n_bot, len(rs) - n_bot, rs[n_bot].A, rs[n_bot].layer.K, [r.C for r in rs[n_bot:]],
+                              [r.layer.N for r in rs[n_bot:]], flag, st)
+
+    def pass_us(fn):
         with torch.cuda.stream(side):
-            B.abft_plan_run_all(plan, io, flag, -1, side.cuda_stream)
+            fn(side.cuda_stream)
         side.synchronize()
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g, stream=side):
-            B.abft_plan_run_all(plan, io, flag, -1, side.cuda_stream)
+            fn(side.cuda_stream)
         for _ in range(10):
             g.replay()
         torch.cuda.synchronize()
@@ -342,16 +355,16 @@ def chain_leg(gen, batch=256, steps=300):
 
     res = {"batch": batch, "layers": [r.layer.name for r in rs], "relu_after": [r.layer.name for i, r in enumerate(rs) if i not in last]}
     try:
-        res["us_selector"] = round(pass_us(), 2)
-        for i in range(len(rs)):
-            B.abft_plan_set_mode(plan, i, B.GLOBAL)
-        res["us_global"] = round(pass_us(), 2)
-        for i in range(len(rs)):
-            B.abft_plan_set_mode(plan, i, B.NONE)
-        res["us_none"] = round(pass_us(), 2)
-        res["ovh_selector_pct"] = round(100 * (res["us_selector"] / res["us_none"] - 1), 2)
-        res["ovh_global_pct"] = round(100 * (res["us_global"] / res["us_none"] - 1), 2)
+        for label, mode in (("selector", B.AUTO), ("global", B.GLOBAL), ("none", B.NONE)):
+            for i in range(len(rs)):
+                B.abft_plan_set_mode(plan, i, mode)
+            res["us_" + label] = round(pass_us(per_layer), 2)
+            res["us_" + label + "_one_launch_per_chain"] = round(pass_us(one_launch), 2)
+        for form in ("", "_one_launch_per_chain"):
+            res["ovh_selector_pct" + form] = round(100 * (res["us_selector" + form] / res["us_none" + form] - 1), 2)
+            res["ovh_global_pct" + form] = round(100 * (res["us_global" + form] / res["us_none" + form] - 1), 2)
         res["false_alarms"] = int(flag.item())
+        res["chain_status"] = B.abft_plan_chain_status(plan)
     finally:
         B.abft_plan_destroy(plan)
     return res
@@ -810,7 +823,7 @@ def main():
                                                 "ovh_replica_pct", "ovh_thread_half_pct", "ovh_twosided_pct")})
             extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
-            extra["dlrm_mlp_chains_relu"] = chain_leg(gen)
+            extra["dlrm_mlp_chains_relu"] = [chain_leg(gen, b) for b in (1, 16, 256)]
             extra["selector_study_fp16_bf16"] = selector_study(ALL_ROWS)
             extra["dlrm_top1_cold_cache"] = cold_cache_leg(wl.Layer("top1", 256, 1024, 1024), "f16", gen)
         except Exception as e:  # extras never invalidate the main measurement

@@ -336,6 +336,29 @@ int abft_plan_run(abft_plan_t *plan, int layer, const void *A, int64_t lda, void
  * the one layer whose product kernel the abft_set_kernel_events hook brackets (-1: none). */
 int abft_plan_run_all(abft_plan_t *plan, const void *const *A, const int64_t *lda, void *const *C,
                       const int64_t *ldc, uint32_t *fault_flag, int event_layer, void *stream);
+/* Run `count` consecutive layers of the plan, from layer `first`, as a chain (Sec. 2.4 step 4):
+ * layer `first` reads A (lda), every later layer reads the output of the one before it; C[i], ldc[i]
+ * (host arrays, i = 0 .. count - 1) are the layers' outputs, each with the layer's activation
+ * function applied and its scheme's checks made on the product.
+ * When every layer is fully connected in F16 or BF16 with the same batch M, weights in ABFT_B_NK
+ * order with 16-byte aligned rows, K a multiple of 64, 16-byte aligned A / C rows, and scheme NONE,
+ * GLOBAL or THREAD (and count <= 8), the whole chain runs in ONE kernel launch: the batch is cut into
+ * eight slabs of rows, one per die of the GPU, and each die takes its slab through all the layers,
+ * the activations staying in that die's L2 (results, checks and flag are those of the per-layer
+ * calls).  Otherwise the layers run one launch each, as abft_plan_run would.  Calls on one plan must
+ * not overlap (they share the plan's chain state).  The one-launch form never allocates and holds no
+ * memset: it can be captured into a HIP graph. */
+int abft_plan_run_chain(abft_plan_t *plan, int first, int count, const void *A, int64_t lda,
+                        void *const *C, const int64_t *ldc, uint32_t *fault_flag, void *stream);
+/* Status word of the plan's chain launches so far (host pointer; synchronises the stream): 0, or
+ * bit 0: a wait for a previous layer ran out of its bounded number of polls, bit 1: a workgroup was
+ * not placed on the die its index implies.  Either also raised the fault flag of that call and left
+ * its outputs incomplete: call abft_plan_chain_reset before the next chain. */
+int abft_plan_chain_status(abft_plan_t *plan, uint32_t *status /* host */, void *stream);
+/* Clear the chain state (synchronises the stream).  spin_limit: polls one wait may take before it
+ * gives up (< 0: the default, about a second); 0 makes every wait that is not already satisfied give
+ * up at once, which is how the error path is exercised. */
+int abft_plan_chain_reset(abft_plan_t *plan, int spin_limit, void *stream);
 /* Override the scheme of a layer (abft_mode_t; ABFT_AUTO re-applies abft_select). */
 int abft_plan_set_mode(abft_plan_t *plan, int layer, int mode);
 /* Activation function of a layer (abft_act_t; ABFT_ACT_NONE at creation), fused into the store

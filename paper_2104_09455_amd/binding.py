@@ -59,7 +59,7 @@ EXPORTS = [
     "abft_set_kernel_events", "abft_region_shape", "abft_tolerance_bias_coeff",
     "abft_plan_run_all", "abft_plan_set_mode", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
     "abft_plan_set_activation", "abft_plan_activation", "abft_gemm_static", "abft_static_scratch_bytes",
-    "abft_tolerance_half_coeff",
+    "abft_tolerance_half_coeff", "abft_plan_run_chain", "abft_plan_chain_status", "abft_plan_chain_reset",
 ]
 
 _lib = None
@@ -121,6 +121,12 @@ def lib() -> ctypes.CDLL:
     L.abft_plan_run_all.restype = ci
     L.abft_plan_run_all.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64), ctypes.POINTER(vp),
                                     ctypes.POINTER(i64), vp, ci, vp]
+    L.abft_plan_run_chain.restype = ci
+    L.abft_plan_run_chain.argtypes = [vp, ci, ci, vp, i64, ctypes.POINTER(vp), ctypes.POINTER(i64), vp, vp]
+    L.abft_plan_chain_status.restype = ci
+    L.abft_plan_chain_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), vp]
+    L.abft_plan_chain_reset.restype = ci
+    L.abft_plan_chain_reset.argtypes = [vp, ci, vp]
     L.abft_plan_set_mode.restype = ci
     L.abft_plan_set_mode.argtypes = [vp, ci, ci]
     L.abft_plan_set_activation.restype = ci
@@ -317,6 +323,23 @@ class PlanIO:
 def abft_plan_run_all(plan, io: PlanIO, fault_flag, event_layer=-1, stream=None) -> None:
     _check(lib().abft_plan_run_all(plan, io.A, io.lda, io.C, io.ldc, _ptr(fault_flag), event_layer,
                                    _stream(stream)))
+
+
+def abft_plan_run_chain(plan, first, count, A, lda, C, ldc, fault_flag, stream=None) -> None:
+    """C: list of `count` output tensors (or pointers), ldc: their leading dimensions."""
+    cp = (ctypes.c_void_p * count)(*[_ptr(c) for c in C])
+    lp = (ctypes.c_int64 * count)(*ldc)
+    _check(lib().abft_plan_run_chain(plan, first, count, _ptr(A), lda, cp, lp, _ptr(fault_flag), _stream(stream)))
+
+
+def abft_plan_chain_status(plan, stream=None) -> int:
+    st = ctypes.c_uint32()
+    _check(lib().abft_plan_chain_status(plan, ctypes.byref(st), _stream(stream)))
+    return st.value
+
+
+def abft_plan_chain_reset(plan, spin_limit=-1, stream=None) -> None:
+    _check(lib().abft_plan_chain_reset(plan, spin_limit, _stream(stream)))
 
 
 def abft_plan_set_mode(plan, layer, mode) -> None:

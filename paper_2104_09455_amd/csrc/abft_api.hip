@@ -16,6 +16,7 @@
 
 #include "../../include/abft.h"
 #include "gemm_configs.h"
+#include "mlp_chain.h"
 
 using namespace abft;
 
@@ -970,9 +971,26 @@ struct abft_plan {
         void* lowered_B;
         void* lowered_beta;
         int lowered_block_n;
+        // a fully-connected layer that can run inside a chain of layers in one launch
+        // (abft_plan_run_chain): weight checksums per block of 32 columns, its tiling there
+        void* chain_beta;
     };
     std::vector<Layer> layers;
+    // completion flags and status word of the chain kernel (zero at creation; see mlp_chain.h)
+    unsigned* chain_flags = nullptr;
+    int chain_spin_limit = 1 << 20;
 };
+
+namespace {
+
+// Can this layer run inside the chain kernel?  Fully connected, fp16 / bf16, weights with k
+// contiguous and 16-byte aligned rows, K whole k tiles of 128 bytes.
+bool chain_layer_ok(const abft_layer_t& d) {
+    if (d.has_conv || d.dtype == ABFT_I8 || d.b_layout != ABFT_B_NK) return false;
+    return ((long long)d.K * 2) % 128 == 0 && (d.ldb * 2) % 16 == 0 && aligned16(d.B);
+}
+
+}  // namespace
 
 // ------------------------------------------------------------------------- //
 // exported functions
@@ -1183,6 +1201,14 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         if (hipMalloc(&L.beta, beta_total_bytes(d.K, (int)cdiv(d.N, L.beta_block_n))) != hipSuccess) { rc = ABFT_E_HIP; break; }
         if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
         p->layers.push_back(L);
+        if (chain_layer_ok(d)) {
+            abft_plan::Layer& PL = p->layers.back();
+            if (hipMalloc(&PL.chain_beta, beta_total_bytes(d.K, (int)cdiv(d.N, 32))) != hipSuccess ||
+                launch_weight_checksum(d.K, d.N, d.B, d.ldb, d.b_layout, d.dtype, 32, PL.chain_beta, st) != hipSuccess) {
+                rc = ABFT_E_HIP;
+                break;
+            }
+        }
         if (d.has_conv) {
             // few input channels: the layer will run lowered to row segments; its weights are
             // re-ordered, and their checksums formed, here and now (offline, Sec. 2.5)
@@ -1209,6 +1235,12 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
             rc = ABFT_E_HIP;
             break;
         }
+    }
+    if (rc == ABFT_OK) {
+        const size_t bytes = (size_t)(CHAIN_FLAG_WORDS + 64) * sizeof(unsigned);
+        if (hipMalloc(reinterpret_cast<void**>(&p->chain_flags), bytes) != hipSuccess ||
+            hipMemsetAsync(p->chain_flags, 0, bytes, st) != hipSuccess)
+            rc = ABFT_E_HIP;
     }
     if (rc == ABFT_OK && profile) {
         // pre-deployment profiling (Sec. 5.3): time each scheme on scratch inputs, keep the faster
@@ -1305,6 +1337,86 @@ int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* ld
     return rc;
 }
 
+int abft_plan_run_chain(abft_plan_t* plan, int first, int count, const void* A, int64_t lda, void* const* C,
+                        const int64_t* ldc, uint32_t* fault_flag, void* stream) {
+    if (!plan || first < 0 || count <= 0 || first + count > (int)plan->layers.size()) return ABFT_E_PLAN;
+    if (!A || !C || !ldc) return ABFT_E_NULL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    // one launch for the whole chain when every layer qualifies; else layer by layer
+    bool one_launch = count <= CHAIN_MAX_LAYERS && plan->chain_flags != nullptr;
+    const abft_layer_t& d0 = plan->layers[first].desc;
+    bool any_check = false;
+    for (int i = 0; i < count && one_launch; ++i) {
+        const abft_plan::Layer& L = plan->layers[first + i];
+        const abft_layer_t& d = L.desc;
+        const void* a_i = i == 0 ? A : C[i - 1];
+        const int64_t lda_i = i == 0 ? lda : ldc[i - 1];
+        one_launch = L.chain_beta != nullptr && d.dtype == d0.dtype && d.M == d0.M &&
+                     (L.mode == ABFT_NONE || L.mode == ABFT_GLOBAL || L.mode == ABFT_THREAD) && C[i] != nullptr &&
+                     aligned16(a_i) && (lda_i * 2) % 16 == 0 && lda_i >= d.K && ldc[i] >= d.N &&
+                     (i == 0 || d.K == plan->layers[first + i - 1].desc.N);
+        any_check = any_check || L.mode != ABFT_NONE;
+    }
+    if (one_launch && any_check && !fault_flag) return ABFT_E_NULL;
+    if (!one_launch) {
+        int rc = ABFT_OK;
+        for (int i = 0; i < count && rc == ABFT_OK; ++i)
+            rc = abft_plan_run(plan, first + i, i == 0 ? A : C[i - 1], i == 0 ? lda : ldc[i - 1], C[i], ldc[i], fault_flag, stream);
+        return rc;
+    }
+    ChainArgs a;
+    std::memset(&a, 0, sizeof a);
+    a.n_layers = count;
+    a.M = d0.M;
+    a.flags = plan->chain_flags;
+    a.status = plan->chain_flags + CHAIN_FLAG_WORDS;
+    a.fault_flag = fault_flag ? fault_flag : plan->chain_flags + CHAIN_FLAG_WORDS + 1;   // (unprotected chain: a word of the plan's own)
+    a.spin_limit = plan->chain_spin_limit;
+    for (int i = 0; i < count; ++i) {
+        const abft_plan::Layer& L = plan->layers[first + i];
+        const abft_layer_t& d = L.desc;
+        ChainLayer& c = a.layer[i];
+        c.A = reinterpret_cast<const char*>(i == 0 ? A : C[i - 1]);
+        c.lda = i == 0 ? lda : ldc[i - 1];
+        c.B = reinterpret_cast<const char*>(d.B);
+        c.ldb = d.ldb;
+        c.C = reinterpret_cast<char*>(C[i]);
+        c.ldc = ldc[i];
+        c.N = d.N;
+        c.K = d.K;
+        const int nb = (int)cdiv(d.N, 32);
+        c.beta_k = reinterpret_cast<const char*>(L.chain_beta) + beta_k_offset(d.K, nb);
+        c.beta_p = reinterpret_cast<const char*>(L.chain_beta) + beta_p_offset(d.K, nb);
+        c.mode = L.mode;          // ABFT_NONE / GLOBAL / THREAD carry the kernels' own numbers
+        c.act = L.act;
+        c.depends = i > 0;
+        c.tol_coeff = tol_coeff(d.K, d.dtype, L.mode);
+        c.tol_l1 = tol_bias_coeff(d.K, d.dtype, L.mode);
+    }
+    const hipError_t e = d0.dtype == ABFT_F16 ? launch_mlp_chain_f16(a, st) : launch_mlp_chain_bf16(a, st);
+    return e == hipSuccess ? ABFT_OK : ABFT_E_HIP;
+}
+
+int abft_plan_chain_status(abft_plan_t* plan, uint32_t* status, void* stream) {
+    if (!plan || !plan->chain_flags) return ABFT_E_PLAN;
+    if (!status) return ABFT_E_NULL;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (hipMemcpyAsync(status, plan->chain_flags + CHAIN_FLAG_WORDS, sizeof(uint32_t), hipMemcpyDeviceToHost, st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return ABFT_E_HIP;
+    return ABFT_OK;
+}
+
+int abft_plan_chain_reset(abft_plan_t* plan, int spin_limit, void* stream) {
+    if (!plan || !plan->chain_flags) return ABFT_E_PLAN;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    if (hipMemsetAsync(plan->chain_flags, 0, (size_t)(CHAIN_FLAG_WORDS + 64) * sizeof(unsigned), st) != hipSuccess ||
+        hipStreamSynchronize(st) != hipSuccess)
+        return ABFT_E_HIP;
+    plan->chain_spin_limit = spin_limit >= 0 ? spin_limit : (1 << 20);
+    return ABFT_OK;
+}
+
 int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
     if (mode < ABFT_NONE || mode > ABFT_GLOBAL_WEIGHTED) return ABFT_E_ENUM;
@@ -1344,7 +1456,9 @@ void abft_plan_destroy(abft_plan_t* plan) {
         if (L.workspace) (void)hipFree(L.workspace);
         if (L.lowered_B) (void)hipFree(L.lowered_B);
         if (L.lowered_beta) (void)hipFree(L.lowered_beta);
+        if (L.chain_beta) (void)hipFree(L.chain_beta);
     }
+    if (plan->chain_flags) (void)hipFree(plan->chain_flags);
     delete plan;
 }
 

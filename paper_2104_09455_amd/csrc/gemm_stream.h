@@ -32,10 +32,11 @@ struct StreamLayout {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one compute unit");
 };
 
-// RAGGED: K is a whole number of 16-byte chunks but not of k tiles (an instance of its own, so that
-// products of whole k tiles pay nothing for the short last tile)
-template <class CFG, int NST, int MODE, bool INJ, bool CONV, bool RAGGED = false>
-__global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
+// One output tile, by all 256 threads of the workgroup (uniform call: it holds workgroup barriers).
+// FRESH_A: the A operand was written earlier in the same launch by other compute units of this
+// die (a chain of layers in one kernel): its copies go past the compute unit's own cache.
+template <class CFG, int NST, int MODE, bool INJ, bool CONV, bool RAGGED, bool FRESH_A>
+__device__ __forceinline__ void stream_tile(const GemmArgs& p, int tile_m, int tile_n, char* smem) {
     typedef StreamLayout<CFG, NST> LAY;
     constexpr int DT = CFG::DT;
     typedef Mma<DT, 32> MMA;
@@ -58,12 +59,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
     constexpr int KW = LAY::KW, WSTAGE = LAY::WSTAGE, NQA = LAY::NQA, NQB = LAY::NQB, NL = NQA + NQB + NBETA;
     constexpr int ROWB = 128, A_STAGE = BM * ROWB;
 
-    extern __shared__ __attribute__((aligned(16))) char smem[];
-
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    int tile_m, tile_n;
-    tile_of_block((int)blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
     const int bm0 = tile_m * BM, bn0 = tile_n * BN;
     const int M = p.M, N = p.N;
     // K is a whole number of 16-byte chunks; the last k tile may hold fewer than eight of them
@@ -168,7 +165,8 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             }
             if (cut[q & 1]) src = g_zero_chunk + ckc[q & 1] * 16;
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
-                                             (__attribute__((address_space(3))) void*)(abase + q * 1024), 16, 0, 0);
+                                             (__attribute__((address_space(3))) void*)(abase + q * 1024), 16, 0,
+                                             FRESH_A ? 16 : 0);  // (cpol bit 4: device scope, served by the die's L2)
         }
 #pragma unroll
         for (int q = 0; q < NQB; ++q) {
@@ -664,6 +662,16 @@ __global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
             }
         }
     }
+}
+
+// RAGGED: K is a whole number of 16-byte chunks but not of k tiles (an instance of its own, so that
+// products of whole k tiles pay nothing for the short last tile)
+template <class CFG, int NST, int MODE, bool INJ, bool CONV, bool RAGGED = false>
+__global__ __launch_bounds__(256) void gemm_stream_kernel(const GemmArgs p) {
+    extern __shared__ __attribute__((aligned(16))) char smem[];
+    int tile_m, tile_n;
+    tile_of_block((int)blockIdx.x, p.tiles_m, p.tiles_n, tile_m, tile_n);
+    stream_tile<CFG, NST, MODE, INJ, CONV, RAGGED, false>(p, tile_m, tile_n, smem);
 }
 
 }  // namespace abft

@@ -76,6 +76,12 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     constexpr int WAVES = LAY::WAVES, NQA = LAY::NQA, NQB = LAY::NQB;
     constexpr int NQ = NQA > NQB ? NQA : NQB;
     constexpr bool GDOT = MODE == MODE_GLOBAL;  // in-kernel checksum dot product
+    // ... formed on the matrix unit (fp16, int8: the weight checksums, cut into two pieces that the
+    // operand type holds, are two more columns of B) or with vector FMAs (bf16, which wants three
+    // pieces; the 256 x 256 tile, which has no registers left for one more accumulator block)
+    constexpr bool MDOT = GDOT && DT != DT_BF16 && TM * TN <= 4;
+    constexpr bool VDOT = GDOT && !MDOT;
+    static_assert(!MDOT || TM == CFG::WAVES_N, "one block row of the extra product per wavefront of a row of wavefronts");
     constexpr int EMODE = MODE == MODE_GLOBAL_PRE ? MODE_GLOBAL : MODE;  // the epilogue's scheme
     constexpr bool IS_INT = DT == DT_I8;
 
@@ -134,13 +140,15 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     }
     // weight checksums of this tile's column block: lane l copies bytes 4l .. 4l+3 of the k tile's
     // 256 (fp16 / bf16: float l of 64; int8: low digits in lanes 0-31, high digits in lanes 32-63)
+    // (matrix-unit form, fp16: first / second piece as halves in lanes 0-31 / 32-63)
     const char* beta_ptr = zero;
     if constexpr (GDOT) {
         const long long blk = (long long)tile_n * p.K;
         if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (lane & 31) * 4;
+        else if constexpr (MDOT) beta_ptr = p.beta_p + blk * 8 + (lane >> 5) * 2 * (long long)p.K + (lane & 31) * 4;
         else beta_ptr = p.beta_k + (blk + lane) * 4;
     }
-    constexpr int BETA_ADV = IS_INT ? BK : BK * 4;
+    constexpr int BETA_ADV = IS_INT ? BK : (MDOT ? BK * 2 : BK * 4);
     if constexpr (CONV) {
         const int k = ckc * (16 / ESIZE);
         const int tap = k / p.Cin;
@@ -227,7 +235,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     const int beta_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + ckc * (IS_INT ? 16 : 32);
     ChecksumDot<DT> dot;
     auto dot_tile = [&](const char* st) {
-        if constexpr (GDOT) {
+        if constexpr (VDOT) {
             const i32x4 b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
             const i32x4 b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
 #pragma unroll
@@ -236,9 +244,32 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             dot.flush();
         }
     };
+    // Matrix-unit form of that dot product: one more 32-column block of B whose columns hold the
+    // pieces of the weight checksums, multiplied with ONE of the TM blocks of A per wavefront
+    // (wavefront column c of a row of wavefronts takes block row c): one more MFMA per k step and
+    // wavefront.  To read the slot once per k tile instead of once per k step, lane (column g,
+    // half h) keeps the 16 bytes of piece g % 2, k chunk 2 (g / 2) + h of the tile, and at k step kk
+    // only the columns with g / 2 == kk pass them on (the others pass zeros): column 2 kk + s of the
+    // result block then holds A . piece s restricted to the k of step kk, and the columns of equal
+    // parity add up to A . piece s.  Four selects per k step, no other vector arithmetic.
+    const int gcol = lane & 31;
+    const int g_step = gcol >> 1;  // the k step whose chunk this lane holds (>= 4: none)
+    const int gb_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + (gcol & 1) * 128 + (g_step & 3) * 32 + fgrp * 16;
+    i32x4 g_tile = {0, 0, 0, 0};
+    auto read_checksum_frag = [&](const char* st) {
+        if constexpr (MDOT) g_tile = *reinterpret_cast<const i32x4*>(st + gb_off);
+    };
+    auto checksum_frag = [&](int kk) {
+        const i32x4 z = {0, 0, 0, 0};
+        return g_step == kk ? g_tile : z;
+    };
+    Acc gchk;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) gchk[r] = 0;
     i32x4 fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* st, int kk, int buf) {
         const int ps = pos[kk];
+
 #pragma unroll
         for (int i = 0; i < TM; ++i)
             fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + ps);
@@ -246,11 +277,18 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         for (int j = 0; j < TN; ++j)
             fb[buf][j] = *reinterpret_cast<const i32x4*>(st + b_off + j * 32 * ROWB + ps);
     };
-    auto mma_step = [&](int buf) {
+    auto mma_step = [&](int buf, const i32x4& fg) {
 #pragma unroll
         for (int i = 0; i < TM; ++i)
 #pragma unroll
             for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[buf][i], fb[buf][j], acc[i][j]);
+        if constexpr (MDOT) {
+            // (the wavefront's block row: a selection by a wavefront-uniform index)
+            i32x4 a_sel = fa[buf][0];
+#pragma unroll
+            for (int i = 1; i < TM; ++i) a_sel = wave_n == i ? fa[buf][i] : a_sel;
+            gchk = MMA::run(a_sel, fg, gchk);
+        }
         if constexpr (mode_is_wave_level(MODE)) check_step<CFG, MODE>(fa[buf], fb[buf], chk);
     };
 
@@ -280,35 +318,38 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
 #pragma unroll
             for (int kk = 0; kk < 3; ++kk) {
                 read_frags(st, kk + 1, (kk + 1) & 1);
-                mma_step(kk & 1);
+                mma_step(kk & 1, checksum_frag(kk));
                 {
                     // fragment reads of the next step go out early, one per MFMA, so that the last
                     // of them has the rest of the step's MFMAs to land; the vector work of the
                     // protected schemes (global: reads and FMAs of the checksum dot product;
                     // thread-level: the sums of the B fragments) is spread between the MFMAs
                     constexpr int NF = TM + TN;
-                    constexpr int NM = TM * TN + (MODE == MODE_REPL ? TM * TN : (mode_is_wave_level(MODE) ? CheckRegs<CFG, EMODE>::N : 0));
+                    constexpr int NM = TM * TN + (MDOT ? 1 : 0) +
+                                       (MODE == MODE_REPL ? TM * TN : (mode_is_wave_level(MODE) ? CheckRegs<CFG, EMODE>::N : 0));
                     // vector instructions per MFMA slot: the exact tile checksum's pieces cost about
                     // 14 (fp16, int8) or 22 (bf16) instructions per 16 bytes of each lane's B
                     // fragments; sums in the operand type one (fp16) or six (bf16) per register
                     constexpr int VSTEP = MODE == MODE_THREAD && ChecksumForm<CFG>::SPLIT ? (DT == DT_BF16 ? 22 : 14) * 4
                                           : (MODE == MODE_THREAD_H ? (TN - 1) * 4 * (DT == DT_BF16 ? 6 : 1)
-                                             : (MODE == MODE_TWOSIDED ? (TN + TM - 2) * 4 * (DT == DT_BF16 ? 6 : 1) : 0));
+                                             : (MODE == MODE_TWOSIDED ? (TN + TM - 2) * 4 * (DT == DT_BF16 ? 6 : 1)
+                                                : (MDOT ? 4 * TM : 0)));  // (matrix-unit dot: the selects of its operands)
                     constexpr int VT = (VSTEP + NM - 1) / NM;
 #pragma unroll
                     for (int g = 0; g < NM; ++g) {
                         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);  // 1 MFMA
                         if (g < NF) {  // LDS reads
-                            if (GDOT && kk == 0) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
+                            if (VDOT && kk == 0) __builtin_amdgcn_sched_group_barrier(0x100, 2, 0);
                             else __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
                         }
-                        if constexpr (GDOT) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // 2 VALU
+                        if constexpr (VDOT) __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);  // 2 VALU
                         if constexpr (VT > 0) __builtin_amdgcn_sched_group_barrier(0x002, VT, 0);
                     }
                 }
             }
         }
         const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
+        const i32x4 fg_last = checksum_frag(3);  // (before the next tile's chunk replaces this one's)
         if (kt + 1 < nkt) {
             // this wave's copies of tile kt+1 have landed (the barrier makes it everyone's) and
             // every wave is done reading this stage, which the copies of tile kt+NSTAGE overwrite
@@ -320,8 +361,9 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
                 issue_loads(stage);
             }
             read_frags(smem + next * STAGE, 0, 0);
+            read_checksum_frag(smem + next * STAGE);
         }
-        mma_step(CUR);
+        mma_step(CUR, fg_last);
         stage = next;
         if constexpr (INJ) {
             // the running accumulator that holds the products just before k_after: the last k step
@@ -329,6 +371,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         }
     };
     read_frags(smem, 0, 0);
+    read_checksum_frag(smem);
     // the last of the four k steps sits in buffer 1
     for (int kt = 0; kt < nkt; ++kt) tile_step(kt, std::integral_constant<int, 1>());
     if constexpr (INJ) {
@@ -336,6 +379,24 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
     }
     __syncthreads();  // the epilogue reuses LDS
+    if constexpr (MDOT) {
+        // this lane's share of the dot product: even columns hold A . (first piece), odd columns
+        // A . (second piece), which carries a factor 2^11 (fp16) or stands for the digit of weight 256 (int8)
+        if constexpr (IS_INT) {
+            int g_lo = 0, g_hi = 0;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                g_lo += gchk[r] & 0xffff;
+                g_hi += gchk[r] >> 16;
+            }
+            dot.total = (((long long)g_hi << 16) + (long long)g_lo) * ((gcol & 1) ? 256 : 1);
+        } else {
+            double g = 0.0;
+#pragma unroll
+            for (int r = 0; r < 16; r += 4) g += (double)((gchk[r] + gchk[r + 1]) + (gchk[r + 2] + gchk[r + 3]));
+            dot.total = g * ((gcol & 1) ? 1.0 / 2048.0 : 1.0);
+        }
+    }
     epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &dot.total : nullptr);
 }
 

@@ -370,6 +370,61 @@ def chain_leg(gen, batch=256, steps=300):
     return res
 
 
+def handover_leg(gen, M=2048, widths=(4096, 4096, 4096, 4096, 4096), dtype="f16", steps=100):
+    """A chain of mid-size, compute-bound fully-connected layers (ReLU between them) under the global
+    scheme, where a stand-alone call pays 10-20 % for forming the activation checksum inside the
+    product: every layer on its own (abft_plan_run) against the chain run layer by layer with each
+    layer's activation checksums handed over by the epilogue of the layer before it (Sec. 2.4 step
+    4; abft_plan_run_chain).  Device time of a whole pass, eager launches on one stream."""
+    nl = len(widths) - 1
+    rs = [LayerRun(wl.Layer(f"fc{i}", M, widths[i + 1], widths[i]), dtype, gen) for i in range(nl)]
+    plan = B.abft_plan_create([B.Layer(M, widths[i + 1], widths[i], rs[i].dt, B.B_NK, 0, B.Conv(), rs[i].B.data_ptr(),
+                                       widths[i]) for i in range(nl)], profile=False)
+    flag = torch.zeros(1, dtype=torch.int32, device="cuda:0")
+    for i in range(nl):
+        B.abft_plan_set_activation(plan, i, B.ACT_RELU if i + 1 < nl else B.ACT_NONE)
+    Cs, ldc = [r.C for r in rs], [int(w) for w in widths[1:]]
+
+    def alone():
+        for i in range(nl):
+            B.abft_plan_run(plan, i, rs[0].A if i == 0 else Cs[i - 1], widths[i], Cs[i], ldc[i], flag)
+
+    def chain():
+        B.abft_plan_run_chain(plan, 0, nl, rs[0].A, widths[0], Cs, ldc, flag)
+
+    def pass_us(fn):
+        for _ in range(5):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        best = float("inf")
+        for _ in range(3):
+            e0.record()
+            for _ in range(steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            best = min(best, 1e3 * e0.elapsed_time(e1) / steps)
+        return best
+
+    res = {"M": M, "widths": list(widths), "dtype": dtype}
+    try:
+        for label, mode in (("none", B.NONE), ("global", B.GLOBAL)):
+            for i in range(nl):
+                B.abft_plan_set_mode(plan, i, mode)
+            res["us_" + label + "_alone"] = round(pass_us(alone), 2)
+            before = B.abft_handover_launches()
+            res["us_" + label + "_chain"] = round(pass_us(chain), 2)
+            if mode == B.GLOBAL:
+                res["layers_with_handed_over_checksums"] = (B.abft_handover_launches() - before) // (3 * steps + 5)
+        res["ovh_global_alone_pct"] = round(100 * (res["us_global_alone"] / res["us_none_alone"] - 1), 2)
+        res["ovh_global_chain_pct"] = round(100 * (res["us_global_chain"] / res["us_none_chain"] - 1), 2)
+        res["false_alarms"] = int(flag.item())
+    finally:
+        B.abft_plan_destroy(plan)
+    return res
+
+
 def cpu_baseline(runs, budget_s=12.0):
     """The oracle as it stands on a bounded sample of the workload: row blocks of A (whole images
     for a convolution) through the fp64 / int64 triple-loop product and the checksum scheme the
@@ -824,6 +879,10 @@ def main():
             extra["squares_fig11"] = fig11
             extra["measured_ceilings"] = measured_ceilings(hip, gen)
             extra["dlrm_mlp_chains_relu"] = [chain_leg(gen, b) for b in (1, 16, 256)]
+            extra["midsize_chain_handed_over_checksums"] = [
+                handover_leg(gen, m, w, dt) for m, w, dt in ((1024, (4096,) * 5, "f16"), (2048, (4096,) * 5, "f16"),
+                                                             (4096, (4096,) * 5, "f16"), (2048, (2048,) * 5, "f16"),
+                                                             (2048, (4096,) * 5, "bf16"))]
             extra["selector_study_fp16_bf16"] = selector_study(ALL_ROWS)
             extra["dlrm_top1_cold_cache"] = cold_cache_leg(wl.Layer("top1", 256, 1024, 1024), "f16", gen)
         except Exception as e:  # extras never invalidate the main measurement

@@ -340,12 +340,23 @@ int abft_plan_run_all(abft_plan_t *plan, const void *const *A, const int64_t *ld
  * layer `first` reads A (lda), every later layer reads the output of the one before it; C[i], ldc[i]
  * (host arrays, i = 0 .. count - 1) are the layers' outputs, each with the layer's activation
  * function applied and its scheme's checks made on the product.
- * When every layer is fully connected in F16 or BF16 with the same batch M, weights in ABFT_B_NK
+ * When every layer is fully connected in F16 or BF16 with the same batch M, small enough that a
+ * launch of its own would run on 32 x 32 tiles, weights in ABFT_B_NK
  * order with 16-byte aligned rows, K a multiple of 64, 16-byte aligned A / C rows, and scheme NONE,
  * GLOBAL or THREAD (and count <= 8), the whole chain runs in ONE kernel launch: the batch is cut into
  * eight slabs of rows, one per die of the GPU, and each die takes its slab through all the layers,
  * the activations staying in that die's L2 (results, checks and flag are those of the per-layer
- * calls).  Otherwise the layers run one launch each, as abft_plan_run would.  Calls on one plan must
+ * calls).  Otherwise the layers run one launch each, and a layer under ABFT_GLOBAL takes the
+ * checksum of its activations from the layer before it instead of forming it (Sec. 2.4 step 4):
+ * that layer's epilogue adds up, per column and block of 32 rows, the values it stores (after its
+ * activation function, rounded to the output type), which are the column sums of the next layer's
+ * input; the next layer multiplies them with its weight checksums, one multiplication per k, and
+ * compares as always.  This needs F16 / BF16, the same M, the later layer reading the earlier one's
+ * output as a plain M x K matrix (fully connected, or a 1 x 1 convolution of stride 1 without
+ * padding) on the direct-to-LDS kernel and the earlier one not on the streaming kernel; a pair
+ * of layers that does not qualify runs exactly as under
+ * abft_plan_run.  Results are those of
+ * abft_plan_run up to the rounding of the checksums (floats here).  Calls on one plan must
  * not overlap (they share the plan's chain state).  The one-launch form never allocates and holds no
  * memset: it can be captured into a HIP graph. */
 int abft_plan_run_chain(abft_plan_t *plan, int first, int count, const void *A, int64_t lda,
@@ -359,6 +370,14 @@ int abft_plan_chain_status(abft_plan_t *plan, uint32_t *status /* host */, void 
  * gives up (< 0: the default, about a second); 0 makes every wait that is not already satisfied give
  * up at once, which is how the error path is exercised. */
 int abft_plan_chain_reset(abft_plan_t *plan, int spin_limit, void *stream);
+/* Diagnostics of a layer's runs through the plan: `report` (device, zero-filled by the caller,
+ * or NULL) and `inject` (HOST pointer, copied; NULL: none; testing) are handed to every later run
+ * of that layer as abft_gemm takes them.  A chain that holds such a layer runs layer by layer. */
+int abft_plan_set_diagnostics(abft_plan_t *plan, int layer, abft_report_t *report /* device */,
+                              const abft_fault_t *inject /* host */);
+/* How many product launches of this process so far took their activation checksums from the
+ * layer before (abft_plan_run_chain, layer by layer); lets a caller see that a chain qualified. */
+long long abft_handover_launches(void);
 /* Override the scheme of a layer (abft_mode_t; ABFT_AUTO re-applies abft_select). */
 int abft_plan_set_mode(abft_plan_t *plan, int layer, int mode);
 /* Activation function of a layer (abft_act_t; ABFT_ACT_NONE at creation), fused into the store

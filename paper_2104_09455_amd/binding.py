@@ -60,6 +60,7 @@ EXPORTS = [
     "abft_plan_run_all", "abft_plan_set_mode", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
     "abft_plan_set_activation", "abft_plan_activation", "abft_gemm_static", "abft_static_scratch_bytes",
     "abft_tolerance_half_coeff", "abft_plan_run_chain", "abft_plan_chain_status", "abft_plan_chain_reset",
+    "abft_plan_set_diagnostics", "abft_handover_launches",
 ]
 
 _lib = None
@@ -127,6 +128,10 @@ def lib() -> ctypes.CDLL:
     L.abft_plan_chain_status.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), vp]
     L.abft_plan_chain_reset.restype = ci
     L.abft_plan_chain_reset.argtypes = [vp, ci, vp]
+    L.abft_handover_launches.restype = ctypes.c_longlong
+    L.abft_handover_launches.argtypes = []
+    L.abft_plan_set_diagnostics.restype = ci
+    L.abft_plan_set_diagnostics.argtypes = [vp, ci, vp, ctypes.POINTER(Fault)]
     L.abft_plan_set_mode.restype = ci
     L.abft_plan_set_mode.argtypes = [vp, ci, ci]
     L.abft_plan_set_activation.restype = ci
@@ -340,6 +345,15 @@ def abft_plan_chain_status(plan, stream=None) -> int:
 
 def abft_plan_chain_reset(plan, spin_limit=-1, stream=None) -> None:
     _check(lib().abft_plan_chain_reset(plan, spin_limit, _stream(stream)))
+
+
+def abft_handover_launches() -> int:
+    return int(lib().abft_handover_launches())
+
+
+def abft_plan_set_diagnostics(plan, layer, report=None, inject: Optional[Fault] = None) -> None:
+    ip = ctypes.byref(inject) if inject is not None else None
+    _check(lib().abft_plan_set_diagnostics(plan, layer, _ptr(report), ip))
 
 
 def abft_plan_set_mode(plan, layer, mode) -> None:

@@ -10,6 +10,7 @@
 #include <cstdlib>
 #include <algorithm>
 #include <cstring>
+#include <atomic>
 #include <mutex>
 #include <new>
 #include <vector>
@@ -62,6 +63,8 @@ thread_local hipEvent_t g_ev_start = nullptr, g_ev_stop = nullptr;
 // for once per device (scratch_of_current_device) and that pointer is what kernels are given.
 constexpr size_t STATIC_SCRATCH_BYTES = 8u << 20;
 __device__ __align__(256) unsigned char g_static_scratch[STATIC_SCRATCH_BYTES];
+// product launches so far that took their activation checksums from the layer before (diagnostics)
+std::atomic<long long> g_handover_launches{0};
 constexpr int MAX_DEVICES = 64;
 void* g_scratch_ptr[MAX_DEVICES] = {nullptr};
 std::mutex g_scratch_mutex;
@@ -510,6 +513,13 @@ struct Problem {
     int pix;
     int tol_K;                     // K the tolerance is taken for (differs from K for a lowered convolution)
     int act;                       // abft_act_t applied to the stored values
+    // chains of layers (Sec. 2.4 step 4): where this layer's epilogue leaves the activation checksums
+    // of the NEXT layer (per 32-row block, leading dimension ld_alpha_out; see GemmArgs), whether it
+    // did (not every kernel can), and the ones the layer before left for this layer's A
+    float* alpha_out;
+    long long ld_alpha_out;
+    bool* alpha_emitted;
+    const float* alpha_in;
 };
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -733,6 +743,12 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
     const int tol_K = pr.tol_K > 0 ? pr.tol_K : pr.K;
     g.tol_coeff = tol_coeff(tol_K, pr.dtype, mode) + tol_half_coeff(pr.dtype, mode, ci.wm, ci.wn, cfg == CFG_G16 ? 16 : 32);
     g.f_row = g.f_col = -1; g.f_bit = 0; g.f_kt = -1;
+    // (the streaming kernel stores through an epilogue of its own, the 16-row shapes hold other rows per lane)
+    if (pr.alpha_out && pr.dtype != ABFT_I8 && !cfg_is_stream(cfg) && cfg != CFG_G16) {
+        g.alpha_out = pr.alpha_out;
+        g.ld_alpha_out = pr.ld_alpha_out;
+        if (pr.alpha_emitted) *pr.alpha_emitted = true;
+    }
 
     bool inj = false;
     if (inject) {
@@ -766,7 +782,14 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
             beta_used = ws + w.off_beta;
         }
         if (weighted) kmode = MODE_GLOBAL_W;
-        if (fused_global(pr, ci)) {
+        if (pr.alpha_in && !weighted && !pr.conv && pr.dtype != ABFT_I8 && ci.fast && ci.kways == 1) {
+            // steps 1-2 were the previous layer's: its epilogue left the column sums of this
+            // layer's A per 32-row block; one multiplication per lane and k tile is all that is left
+            kmode = MODE_GLOBAL_FED;
+            g_handover_launches.fetch_add(1, std::memory_order_relaxed);
+            g.alpha_in = pr.alpha_in;
+            g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
+        } else if (fused_global(pr, ci)) {
             // the direct-to-LDS kernel forms the activation checksum's dot product with the weight
             // checksums itself, from the A tiles it multiplies (steps 1-3 inside the product's loop)
             g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
@@ -974,11 +997,19 @@ struct abft_plan {
         // a fully-connected layer that can run inside a chain of layers in one launch
         // (abft_plan_run_chain): weight checksums per block of 32 columns, its tiling there
         void* chain_beta;
+        // activation checksums of this layer's input, left by the layer before it in a chain run
+        // layer by layer: ceil(M / 32) x K floats (fully-connected fp16 / bf16 layers)
+        float* alpha32;
+        // diagnostics block and planted fault (test hook) handed to every run of the layer
+        abft_report_t* report;
+        abft_fault_t fault;
+        bool has_fault;
     };
     std::vector<Layer> layers;
     // completion flags and status word of the chain kernel (zero at creation; see mlp_chain.h)
     unsigned* chain_flags = nullptr;
     int chain_spin_limit = 1 << 20;
+
 };
 
 namespace {
@@ -1201,6 +1232,14 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
         if (hipMalloc(&L.beta, beta_total_bytes(d.K, (int)cdiv(d.N, L.beta_block_n))) != hipSuccess) { rc = ABFT_E_HIP; break; }
         if (hipMalloc(&L.workspace, L.ws_bytes) != hipSuccess) { (void)hipFree(L.beta); rc = ABFT_E_HIP; break; }
         p->layers.push_back(L);
+        if (d.dtype != ABFT_I8 && (!d.has_conv || (d.conv.KH == 1 && d.conv.KW == 1 && d.conv.stride == 1 && d.conv.pad == 0))) {
+            // (a layer that reads a plain M x K matrix can take its activation checksums from the layer before)
+            abft_plan::Layer& PL = p->layers.back();
+            if (hipMalloc(reinterpret_cast<void**>(&PL.alpha32), (size_t)cdiv(d.M, 32) * d.K * sizeof(float)) != hipSuccess) {
+                rc = ABFT_E_HIP;
+                break;
+            }
+        }
         if (chain_layer_ok(d)) {
             abft_plan::Layer& PL = p->layers.back();
             if (hipMalloc(&PL.chain_beta, beta_total_bytes(d.K, (int)cdiv(d.N, 32))) != hipSuccess ||
@@ -1291,9 +1330,15 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
     return ABFT_OK;
 }
 
-int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void* C, int64_t ldc,
-                  uint32_t* fault_flag, void* stream) {
-    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+}  // extern "C"
+
+namespace {
+
+// One layer of a plan.  alpha_out (may be null): where to leave the activation checksums of the
+// layer that follows (leading dimension ld_alpha_out), *alpha_emitted set when the kernel that ran
+// could; alpha_in (may be null): those the layer before left for this layer's input.
+int plan_run_layer(abft_plan_t* plan, int layer, const void* A, int64_t lda, void* C, int64_t ldc, uint32_t* fault_flag,
+                   void* stream, float* alpha_out, long long ld_alpha_out, bool* alpha_emitted, const float* alpha_in) {
     abft_plan::Layer& L = plan->layers[layer];
     const abft_layer_t& d = L.desc;
     Problem pr;
@@ -1307,17 +1352,29 @@ int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void
     pr.dtype = d.dtype; pr.b_layout = d.b_layout;
     pr.A = A; pr.B = d.B; pr.ldb = d.ldb; pr.C = C; pr.ldc = ldc;
     pr.act = L.act;
+    pr.alpha_out = alpha_out; pr.ld_alpha_out = ld_alpha_out; pr.alpha_emitted = alpha_emitted; pr.alpha_in = alpha_in;
     // the offline checksums fit the tiling chosen for aligned activations; an input that
     // forces another tiling gets them recomputed into the workspace
     const int bn_now = cfg_info_host(pick_cfg(pr.M, pr.N, pr.K, pr.dtype, a_vectorisable(pr) && b_vectorisable(pr), ABFT_GLOBAL)).bn;
     const void* beta = bn_now == L.beta_block_n ? L.beta : nullptr;
+    const abft_fault_t* fault = L.has_fault ? &L.fault : nullptr;
     if (pr.conv) {
         const LoweredWeights pre = {L.lowered_B, L.lowered_beta, L.lowered_block_n};
-        return run_conv(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
+        return run_conv(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, L.report, fault,
                         reinterpret_cast<hipStream_t>(stream), L.lowered_B ? &pre : nullptr);
     }
-    return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, nullptr, nullptr,
+    return run_problem(pr, L.mode, beta, L.workspace, L.ws_bytes, fault_flag, L.report, fault,
                        reinterpret_cast<hipStream_t>(stream));
+}
+
+}  // namespace
+
+extern "C" {
+
+int abft_plan_run(abft_plan_t* plan, int layer, const void* A, int64_t lda, void* C, int64_t ldc,
+                  uint32_t* fault_flag, void* stream) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    return plan_run_layer(plan, layer, A, lda, C, ldc, fault_flag, stream, nullptr, 0, nullptr, nullptr);
 }
 
 int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* lda, void* const* C,
@@ -1351,7 +1408,9 @@ int abft_plan_run_chain(abft_plan_t* plan, int first, int count, const void* A, 
         const abft_layer_t& d = L.desc;
         const void* a_i = i == 0 ? A : C[i - 1];
         const int64_t lda_i = i == 0 ? lda : ldc[i - 1];
+        // (layers small enough that a launch of their own would run on 32 x 32 tiles too)
         one_launch = L.chain_beta != nullptr && d.dtype == d0.dtype && d.M == d0.M &&
+                     pick_cfg(d.M, d.N, d.K, d.dtype, true, L.mode) == CFG_S32 && !L.report && !L.has_fault &&
                      (L.mode == ABFT_NONE || L.mode == ABFT_GLOBAL || L.mode == ABFT_THREAD) && C[i] != nullptr &&
                      aligned16(a_i) && (lda_i * 2) % 16 == 0 && lda_i >= d.K && ldc[i] >= d.N &&
                      (i == 0 || d.K == plan->layers[first + i - 1].desc.N);
@@ -1359,9 +1418,35 @@ int abft_plan_run_chain(abft_plan_t* plan, int first, int count, const void* A, 
     }
     if (one_launch && any_check && !fault_flag) return ABFT_E_NULL;
     if (!one_launch) {
+        // Layer by layer.  A layer under the global scheme takes its activation checksums from the
+        // epilogue of the layer before it (Sec. 2.4 step 4) when it reads that layer's output as a
+        // plain matrix and both run kernels that can do their part; else it forms them itself.
         int rc = ABFT_OK;
-        for (int i = 0; i < count && rc == ABFT_OK; ++i)
-            rc = abft_plan_run(plan, first + i, i == 0 ? A : C[i - 1], i == 0 ? lda : ldc[i - 1], C[i], ldc[i], fault_flag, stream);
+        const float* alpha_in = nullptr;
+        for (int i = 0; i < count && rc == ABFT_OK; ++i) {
+            float* alpha_out = nullptr;
+            long long ld_alpha = 0;
+            if (i + 1 < count) {
+                const abft_plan::Layer& nx = plan->layers[first + i + 1];
+                const abft_layer_t& d = plan->layers[first + i].desc;
+                if (nx.mode == ABFT_GLOBAL && nx.alpha32 && nx.desc.M == d.M && nx.desc.K == d.N && nx.desc.dtype == d.dtype) {
+                    // (only when the next layer will run on the kernel that takes them)
+                    const abft_layer_t& e = nx.desc;
+                    const int es = esize(e.dtype);
+                    const bool a16 = aligned16(C[i]) && (ldc[i] * es) % 16 == 0 && (e.K * es) % 16 == 0;
+                    const bool b16 = e.b_layout == ABFT_B_NK && aligned16(e.B) && (e.K * es) % 16 == 0 && (e.ldb * es) % 16 == 0;
+                    const CfgInfo ci = cfg_info_host(pick_cfg(e.M, e.N, e.K, e.dtype, a16 && b16, ABFT_GLOBAL));
+                    if (ci.fast && ci.kways == 1) {
+                        alpha_out = nx.alpha32;
+                        ld_alpha = e.K;
+                    }
+                }
+            }
+            bool emitted = false;
+            rc = plan_run_layer(plan, first + i, i == 0 ? A : C[i - 1], i == 0 ? lda : ldc[i - 1], C[i], ldc[i], fault_flag,
+                                stream, alpha_out, ld_alpha, &emitted, alpha_in);
+            alpha_in = emitted ? alpha_out : nullptr;
+        }
         return rc;
     }
     ChainArgs a;
@@ -1417,6 +1502,17 @@ int abft_plan_chain_reset(abft_plan_t* plan, int spin_limit, void* stream) {
     return ABFT_OK;
 }
 
+long long abft_handover_launches(void) { return g_handover_launches.load(std::memory_order_relaxed); }
+
+int abft_plan_set_diagnostics(abft_plan_t* plan, int layer, abft_report_t* report, const abft_fault_t* inject) {
+    if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
+    abft_plan::Layer& L = plan->layers[layer];
+    L.report = report;
+    L.has_fault = inject != nullptr;
+    if (inject) L.fault = *inject;
+    return ABFT_OK;
+}
+
 int abft_plan_set_mode(abft_plan_t* plan, int layer, int mode) {
     if (!plan || layer < 0 || layer >= (int)plan->layers.size()) return ABFT_E_PLAN;
     if (mode < ABFT_NONE || mode > ABFT_GLOBAL_WEIGHTED) return ABFT_E_ENUM;
@@ -1457,6 +1553,7 @@ void abft_plan_destroy(abft_plan_t* plan) {
         if (L.lowered_B) (void)hipFree(L.lowered_B);
         if (L.lowered_beta) (void)hipFree(L.lowered_beta);
         if (L.chain_beta) (void)hipFree(L.chain_beta);
+        if (L.alpha32) (void)hipFree(L.alpha32);
     }
     if (plan->chain_flags) (void)hipFree(plan->chain_flags);
     delete plan;

@@ -27,7 +27,10 @@ enum { DT_F16 = 0, DT_BF16 = 1, DT_I8 = 2 };
 // MODE_GLOBAL_PRE (kernel-internal): the global scheme with the checksum dot products left by
 // the activation-checksum kernel instead of formed inside the product's loop
 enum { MODE_NONE = 0, MODE_GLOBAL = 1, MODE_THREAD = 2, MODE_GLOBAL_PRE = 3, MODE_REPL = 4, MODE_THREAD_H = 5,
-       MODE_TWOSIDED = 6, MODE_GLOBAL_W = 7 };
+       MODE_TWOSIDED = 6, MODE_GLOBAL_W = 7, MODE_GLOBAL_FED = 8 };
+// MODE_GLOBAL_FED (kernel-internal): the global scheme with the activation checksums handed over
+// by the layer before (Sec. 2.4 step 4: the previous layer's epilogue forms them from the values
+// it stores), as column sums per block of 32 rows; direct-to-LDS kernel, fp16 / bf16.
 // MODE_GLOBAL_W: the global scheme with three independent checksum pairs per workgroup tile
 // (Sec. 2.4, last paragraph): plain, rows weighted, columns weighted; streaming kernel only.
 // MODE_REPL: thread-level replication with single accumulation (Sec. 5.1): every MFMA of the
@@ -136,6 +139,13 @@ struct GemmArgs {
     // activation function applied to the finished values as they are stored (Sec. 2.4 step 4:
     // after the checks, which see the accumulators as the product left them): 0 none, 1 max(x, 0)
     int act;
+    // Activation checksums for the NEXT layer (Sec. 2.4 step 4), or null: alpha_out[b * ld_alpha_out + n] =
+    // sum over the rows m of 32-row block b of the value stored at C[m][n] (after the activation
+    // function, rounded to the output type), as a float.  fp16 / bf16, 32 x 32 MFMA shapes.
+    float* alpha_out;
+    long long ld_alpha_out;
+    // MODE_GLOBAL_FED: the same from the layer before, for this layer's A: alpha_in[b * K + k]
+    const float* alpha_in;
 };
 
 template <typename To, typename Ti>
@@ -980,6 +990,28 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             for (int j = 0; j < TN; ++j)
 #pragma unroll
                 for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = acc[i][j][r] > 0 ? acc[i][j][r] : 0;
+    }
+    // ---- activation checksums for the next layer: per 32-row block and column, the sum of the
+    // values as they are stored (a lane holds 16 rows of one column of each MFMA block, the
+    // lane 32 further on the other 16); rows past M hold zeros
+    if constexpr (CFG::CSIZE == 2 && MI == 32) {
+        if (p.alpha_out) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float cs = 0.f;
+#pragma unroll
+                    for (int r = 0; r < MMA::NACC; ++r) {
+                        if constexpr (CFG::DT == DT_F16) cs += (float)(_Float16)acc[i][j][r];
+                        else cs += (float)(__bf16)acc[i][j][r];
+                    }
+                    cs += __shfl_xor(cs, 32);
+                    const int col = acc_col(j);
+                    const int blk = (tc.bm0 + tc.wave_m * CFG::WM) / 32 + i;
+                    if (lane < 32 && col < N && blk * 32 < M) p.alpha_out[(long long)blk * p.ld_alpha_out + col] = cs;
+                }
+        }
     }
     // ---- store C (rounded to the output type)
     if constexpr (CFG::CSIZE == 2 && MI == 32) {

@@ -57,6 +57,11 @@ struct FastLayout {
     static constexpr int BETA_SLOT = 256;
     static constexpr int STAGE = AB_STAGE + WAVES * BETA_SLOT;
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    // Activation checksums handed over by the layer before (and the weight checksums that go with
+    // them) travel in runs of 256 floats, four k tiles at a time, through rings of two 1 KB slots behind
+    // the stages: one ring per wavefront for its 32-row block's sums, one for the workgroup's weight checksums
+    static constexpr int RING_A = NSTAGE * STAGE, RING_B = RING_A + WAVES * 2048;
+    static constexpr int LDS_BYTES_FED = RING_B + 2048;
     static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
@@ -82,7 +87,11 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     constexpr bool MDOT = GDOT && DT != DT_BF16 && TM * TN <= 4;
     constexpr bool VDOT = GDOT && !MDOT;
     static_assert(!MDOT || TM == CFG::WAVES_N, "one block row of the extra product per wavefront of a row of wavefronts");
-    constexpr int EMODE = MODE == MODE_GLOBAL_PRE ? MODE_GLOBAL : MODE;  // the epilogue's scheme
+    // ... or reduced to one multiplication per lane and k tile because the layer before left the
+    // column sums of this layer's A (per block of 32 rows: one block per wavefront here)
+    constexpr bool FED = MODE == MODE_GLOBAL_FED;
+    static_assert(!FED || (DT != DT_I8 && CFG::WAVES_M * CFG::WAVES_N * 32 == BM), "one 32-row block per wavefront");
+    constexpr int EMODE = (MODE == MODE_GLOBAL_PRE || FED) ? MODE_GLOBAL : MODE;  // the epilogue's scheme
     constexpr bool IS_INT = DT == DT_I8;
 
     extern __shared__ __attribute__((aligned(16))) char smem[];
@@ -149,6 +158,34 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         else beta_ptr = p.beta_k + (blk + lane) * 4;
     }
     constexpr int BETA_ADV = IS_INT ? BK : (MDOT ? BK * 2 : BK * 4);
+    // Handed-over activation checksums.  Group g = k tiles 4 g .. 4 g + 3 = floats 256 g .. 256 g + 255 of
+    // this wavefront's row of sums (lane l copies floats 4 l .. 4 l + 3 of the group) and, by wavefront 0
+    // for everyone, of the column block's weight checksums; group g sits in slot g % 2 and is
+    // copied while group g - 1 is in use.  These copies are older than the operand copies any later
+    // wait counts on, so every such wait covers them too.
+    const char* fed_alpha = nullptr;
+    const char* fed_beta = nullptr;
+    if constexpr (FED) {
+        const int blk = tile_m * (BM / 32) + wave;
+        if (blk * 32 < M) fed_alpha = reinterpret_cast<const char*>(p.alpha_in + (long long)blk * p.K);
+        fed_beta = p.beta_k + (long long)tile_n * p.K * 4;
+    }
+    auto issue_group = [&](int g) {
+        if constexpr (FED) {
+            const int f0 = 256 * g + 4 * lane;                 // first of this lane's four floats
+            const bool in_k = f0 + 4 <= p.K;                   // (K is a multiple of 64: whole lanes)
+            const char* src = (fed_alpha && in_k) ? fed_alpha + (long long)f0 * 4 : zero;
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
+                                             (__attribute__((address_space(3))) void*)(smem + LAY::RING_A + (wave * 2 + (g & 1)) * 1024),
+                                             16, 0, 0);
+            if (wave == 0) {
+                const char* srcb = in_k ? fed_beta + (long long)f0 * 4 : zero;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)srcb,
+                                                 (__attribute__((address_space(3))) void*)(smem + LAY::RING_B + (g & 1) * 1024),
+                                                 16, 0, 0);
+            }
+        }
+    };
     if constexpr (CONV) {
         const int k = ckc * (16 / ESIZE);
         const int tap = k / p.Cin;
@@ -234,6 +271,20 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // the MFMAs.  Per k tile the fp32 / int32 partial sums move into a wide accumulator.
     const int beta_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + ckc * (IS_INT ? 16 : 32);
     ChecksumDot<DT> dot;
+    float fed_a = 0.f, fed_b = 0.f;
+    auto fed_tile = [&](int kt) {
+        if constexpr (FED) {
+            // lane l: (column sum of the wavefront's 32 rows at k = l of the tile) x (weight checksum
+            // there); the product is taken one tile later, when the two reads have long landed
+            dot.total += (double)fed_a * (double)fed_b;
+            const int off = ((kt >> 2) & 1) * 1024 + ((kt & 3) * 64 + lane) * 4;
+            fed_a = *reinterpret_cast<const float*>(smem + LAY::RING_A + wave * 2048 + off);
+            fed_b = *reinterpret_cast<const float*>(smem + LAY::RING_B + off);
+            // the slot of the group before is free (everyone read its last tile before the barrier
+            // of that tile): the next group goes there
+            if ((kt & 3) == 0 && kt >= 4 && 4 * ((kt >> 2) + 1) < nkt) issue_group((kt >> 2) + 1);
+        }
+    };
     auto dot_tile = [&](const char* st) {
         if constexpr (VDOT) {
             const i32x4 b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
@@ -297,6 +348,10 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // whose fragments are already in registers, so the barrier wait, the issue of the next
     // copies and the first fragment reads of the next tile all run under those MFMAs.
     constexpr int NL = NQA + NQB + (GDOT ? 1 : 0);  // copies per wave per tile
+    if constexpr (FED) {
+        issue_group(0);
+        if (nkt > 4) issue_group(1);
+    }
 #pragma unroll
     for (int t = 0; t < NSTAGE; ++t) {
         if (t < nkt) {
@@ -314,6 +369,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         constexpr int CUR = decltype(cur_c)::value;
         const char* st = smem + stage * STAGE;
         dot_tile(st);
+        fed_tile(kt);
         {
 #pragma unroll
             for (int kk = 0; kk < 3; ++kk) {
@@ -379,6 +435,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
     }
     __syncthreads();  // the epilogue reuses LDS
+    if constexpr (FED) dot.total += (double)fed_a * (double)fed_b;  // the last tile's
     if constexpr (MDOT) {
         // this lane's share of the dot product: even columns hold A . (first piece), odd columns
         // A . (second piece), which carries a factor 2^11 (fp16) or stands for the digit of weight 256 (int8)
@@ -397,7 +454,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             dot.total = g * ((gcol & 1) ? 1.0 / 2048.0 : 1.0);
         }
     }
-    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, GDOT ? &dot.total : nullptr);
+    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, (GDOT || FED) ? &dot.total : nullptr);
 }
 
 }  // namespace abft

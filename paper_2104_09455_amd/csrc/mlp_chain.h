@@ -135,6 +135,7 @@ __global__ __launch_bounds__(256) void mlp_chain_kernel(const ChainArgs a) {
         g.f_row = g.f_col = -1; g.f_bit = 0; g.f_kt = -1;
         g.tiles_m = tiles_m_all; g.tiles_n = (L.N + 31) / 32;
         g.act = L.act;
+        g.alpha_out = nullptr; g.ld_alpha_out = 0; g.alpha_in = nullptr;
         const int ntiles = (tm1 - tm0) * g.tiles_n;
         for (int t = rank; t < ntiles; t += CHAIN_TEAM) {
             const int tile_m = tm0 + t / g.tiles_n, tile_n = t % g.tiles_n;

@@ -1,0 +1,237 @@
+"""Chains of mid-size layers run layer by layer (abft_plan_run_chain) with the activation
+checksums of a layer under the global scheme handed over by the epilogue of the layer before it
+(Sec. 2.4 step 4): every layer against the oracle on the input it read, the device's comparison
+of its worst region against the oracle's check of that region, the same results as the layers run
+one by one, seeded single-bit faults in a layer that takes handed-over checksums and in one
+that hands them over, and chains in which only some pairs of layers qualify."""
+import ctypes
+import math
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2104_09455_amd import binding as B
+from test_gpu_chain import Chain, _storage, DT
+
+pytestmark = pytest.mark.gpu
+
+# every layer large enough for the direct-to-LDS kernel; the last one (narrow, long k) streams
+WIDTHS = [512, 1024, 1024, 2048, 512]
+M_MID = 4096
+
+
+def _reports(ch):
+    import torch
+    from gpu_util import DEV
+    reps = [torch.zeros(ctypes.sizeof(B.Report), dtype=torch.uint8, device=DEV) for _ in range(ch.nl)]
+    for l, r in enumerate(reps):
+        B.abft_plan_set_diagnostics(ch.plan, l, report=r)
+    return reps
+
+
+def _region(ch, l, a_in, region):
+    """Row / column block of layer l's comparison region `region` (1-based, row-major) and the
+    oracle's check of it, on the input a_in the device's layer read."""
+    K, N = ch.widths[l], ch.widths[l + 1]
+    bm, bn = B.abft_region_shape(ch.M, N, K, DT[ch.dtype], True)
+    per_row = -(-N // bn)
+    r0, c0 = (region - 1) // per_row * bm, (region - 1) % per_row * bn
+    Ab, Bb = a_in[r0:r0 + bm], np.ascontiguousarray(ch.Ws[l][:, c0:c0 + bn])
+    Cb = oracle.gemm(Ab, Bb, ch.dtype)
+    return (r0, c0, bm, bn), oracle.region_check(Ab, Bb, Cb, ch.dtype, 0, Cb.shape[0], 0, Cb.shape[1]), Cb
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_handed_over_checksums_agree_with_the_oracle_and_with_layers_run_alone(dtype):
+    import torch
+    from gpu_util import read_report
+    ch = Chain(M_MID, WIDTHS, dtype, seed=1200, modes=[B.GLOBAL] * 4)
+    try:
+        reps = _reports(ch)
+        x, dx = ch.input(seed=1201)
+        before = B.abft_handover_launches()
+        print(f"case handover chain M={M_MID} widths={WIDTHS} dtype={dtype}", flush=True)
+        ch.run(dx)
+        torch.cuda.synchronize()
+        # layers 1 and 2 read the output of a layer on the direct-to-LDS kernel and run on it themselves
+        assert B.abft_handover_launches() - before == 2
+        assert int(ch.flag.item()) == 0
+        ch.check(x)
+        chained = [c.clone() for c in ch.Cs]
+        got = [read_report(r) for r in reps]
+        a_in = x
+        for l in range(ch.nl):
+            K, N = ch.widths[l], ch.widths[l + 1]
+            bm, bn = B.abft_region_shape(ch.M, N, K, DT[dtype], True)
+            assert got[l].tiles == -(-ch.M // bm) * -(-N // bn), l
+            _, ref, _ = _region(ch, l, a_in, got[l].region)
+            assert not ref.flag
+            assert abs(got[l].lhs - ref.lhs) <= ref.tau, l
+            assert abs(got[l].rhs - ref.rhs) <= 0.1 * ref.tau, l
+            assert got[l].tau == pytest.approx(ref.tau, rel=1e-3)
+            assert got[l].worst_ratio < 0.5, (l, got[l].worst_ratio)
+            a_in = _storage(ch.Cs[l], dtype)
+        # the layers one by one form their activation checksums themselves: same C, bit for bit
+        for r in reps:
+            r.zero_()
+        for l in range(ch.nl):
+            a = dx if l == 0 else ch.Cs[l - 1]
+            B.abft_plan_run(ch.plan, l, a, ch.widths[l], ch.Cs[l], ch.widths[l + 1], ch.flag)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == 2
+        assert int(ch.flag.item()) == 0
+        for l in range(ch.nl):
+            assert torch.equal(ch.Cs[l], chained[l]), l
+            alone = read_report(reps[l])
+            assert alone.tiles == got[l].tiles
+            # (the worst region may differ between the two forms of the right-hand side; the tolerance may not)
+            if alone.region == got[l].region:
+                assert alone.lhs == got[l].lhs
+                assert abs(alone.rhs - got[l].rhs) <= 0.1 * alone.tau
+    finally:
+        ch.close()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("layer", [1, 2])
+def test_seeded_faults_in_a_chain_with_handed_over_checksums(dtype, layer):
+    """Layer 1 takes checksums and hands some over, layer 2 only takes them.  Single-bit flips in
+    finished accumulators of the layer: the verdict equals the oracle's incremental evaluation
+    outside the don't-care band around the region's tolerance; the other layers stay silent."""
+    import torch
+    from gpu_util import read_report
+    ch = Chain(M_MID, WIDTHS, dtype, seed=1300, modes=[B.GLOBAL] * 4)
+    try:
+        reps = _reports(ch)
+        x, dx = ch.input(seed=1301)
+        ch.run(dx)
+        torch.cuda.synchronize()
+        assert int(ch.flag.item()) == 0
+        clean = read_report(reps[layer])
+        resid0 = clean.tau * clean.worst_ratio
+        a_in = _storage(ch.Cs[layer - 1], dtype)           # what the layer reads (a clean run's)
+        K, N = ch.widths[layer], ch.widths[layer + 1]
+        bm, bn = B.abft_region_shape(ch.M, N, K, DT[dtype], True)
+        rng = np.random.default_rng(1302 + layer)
+        blocks = {}
+        must = mustnot = band = 0
+        for t in range(48):
+            i, j = int(rng.integers(ch.M)), int(rng.integers(N))
+            bit = int(rng.integers(32)) if t % 3 else int(rng.integers(24, 31))
+            print(f"case handover fault layer={layer} dtype={dtype} t={t} ({i},{j}) bit {bit}", flush=True)
+            for r in reps:
+                r.zero_()
+            ch.flag.zero_()
+            B.abft_plan_set_diagnostics(ch.plan, layer, report=reps[layer], inject=B.Fault(i, j, bit, -1))
+            ch.run(dx)
+            torch.cuda.synchronize()
+            flag = int(ch.flag.item())
+            others = [read_report(reps[l]).worst_ratio for l in range(ch.nl) if l != layer]
+            a_row, b_col = a_in[i:i + 1], np.ascontiguousarray(ch.Ws[layer][:, j:j + 1])
+            good = oracle.partial_dot(a_row, b_col, dtype, 0, 0, 0, K)
+            bad = oracle.flip_bit(good, bit, dtype)
+            if not math.isfinite(bad):
+                assert flag == 1
+                must += 1
+                continue
+            # (a corrupted output changes what the later layers read, consistently for both of
+            # their sides: they stay silent unless it overflows there)
+            if abs(bad) < 6e4:
+                assert max(others) < 1.0, others
+            r0, c0 = i // bm * bm, j // bn * bn
+            if (r0, c0) not in blocks:
+                blk = oracle.gemm(a_in[r0:r0 + bm], np.ascontiguousarray(ch.Ws[layer][:, c0:c0 + bn]), dtype)
+                blocks[(r0, c0)] = (blk, oracle.frob(blk) ** 2, oracle.l1norm(blk))
+            blk, f2, l1 = blocks[(r0, c0)]
+            cl = float(blk[i - r0, j - c0])
+            delta = abs(bad - good)
+            tau = oracle.tolerance(K, math.sqrt(max(f2 - cl * cl + bad * bad, 0.0)), dtype, scheme=1,
+                                   l1_norm=l1 - abs(cl) + abs(bad))
+            if delta >= 2 * tau + resid0:
+                assert flag == 1, (i, j, bit, delta, tau)
+                must += 1
+            elif delta <= tau / 2 - resid0:
+                assert flag == 0, (i, j, bit, delta, tau)
+                mustnot += 1
+            else:
+                band += 1
+        print(f"handover faults layer {layer} {dtype}: {must} flagged, {mustnot} silent, {band} in the band", flush=True)
+        assert must > 0 and mustnot > 0
+    finally:
+        B.abft_plan_set_diagnostics(ch.plan, layer)
+        ch.close()
+
+
+@pytest.mark.parametrize("modes,expect", [
+    ([B.GLOBAL, B.THREAD, B.GLOBAL, B.GLOBAL], 1),   # layer 1 under another scheme still hands over to layer 2
+    ([B.NONE, B.GLOBAL, B.NONE, B.GLOBAL], 1),       # an unprotected layer hands over; the streamed last layer takes none
+    ([B.THREAD, B.THREAD, B.THREAD, B.THREAD], 0),
+])
+def test_chains_in_which_only_some_layers_qualify(modes, expect):
+    import torch
+    ch = Chain(M_MID, WIDTHS, "f16", seed=1400, modes=modes)
+    try:
+        x, dx = ch.input(seed=1401)
+        before = B.abft_handover_launches()
+        ch.run(dx)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == expect
+        assert int(ch.flag.item()) == 0
+        ch.check(x)
+    finally:
+        ch.close()
+
+
+def test_ragged_batch_and_widths():
+    """M not a multiple of 32, N not a multiple of the tile: the last row block's checksums cover
+    the rows that exist, columns past N are never written."""
+    import torch
+    ch = Chain(3001, [512, 960, 1024, 640], "f16", seed=1500, modes=[B.GLOBAL] * 3)
+    try:
+        x, dx = ch.input(seed=1501)
+        before = B.abft_handover_launches()
+        ch.run(dx)
+        torch.cuda.synchronize()
+        assert int(ch.flag.item()) == 0
+        ch.check(x)
+        assert B.abft_handover_launches() - before >= 1
+    finally:
+        ch.close()
+
+
+def test_handover_chain_under_graph_replay():
+    """The second stream's comparison kernels are captured with the chain (fork after each product,
+    join at the end of the call): every replay gives the eager outputs and a clean flag, and with a
+    fault planted in a layer that takes handed-over checksums every replay raises the flag."""
+    import torch
+    ch = Chain(M_MID, WIDTHS, "f16", seed=1600, modes=[B.GLOBAL] * 4)
+    try:
+        x, dx = ch.input(seed=1601)
+        ch.run(dx)
+        torch.cuda.synchronize()
+        assert int(ch.flag.item()) == 0
+        eager = [c.clone() for c in ch.Cs]
+        for planted in (False, True):
+            if planted:
+                B.abft_plan_set_diagnostics(ch.plan, 2, inject=B.Fault(100, 200, 29, -1))
+            cap = torch.cuda.Stream()
+            cap.wait_stream(torch.cuda.current_stream())
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g, stream=cap):
+                ch.run(dx, cap)
+            for rep in range(3):
+                for c in ch.Cs:
+                    c.zero_()               # eager work between replays
+                ch.flag.zero_()
+                torch.cuda.synchronize()
+                g.replay()
+                torch.cuda.synchronize()
+                print(f"case handover graph planted={planted} replay={rep}", flush=True)
+                assert int(ch.flag.item()) == (1 if planted else 0), (planted, rep)
+                if not planted:
+                    for c, e in zip(ch.Cs, eager):
+                        assert torch.equal(c, e), rep
+    finally:
+        B.abft_plan_set_diagnostics(ch.plan, 2)
+        ch.close()

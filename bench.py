@@ -601,6 +601,10 @@ def main():
     ap.add_argument("--no-extras", action="store_true", help="skip the short legs for the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle baseline")
     ap.add_argument("--all-layers", action="store_true", help="print every row of the per-layer table")
+    ap.add_argument("--probe", default=None, metavar="M,N,K[,DTYPE]",
+                    help="only run one fully-connected layer of that shape ten times under every scheme (each scheme "
+                         "is a kernel of its own name, so hardware counters of a profiler separate them) and print "
+                         "the device times as one JSON line")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="first run 5 plain element-wise copy kernels that read MIB MiB and write MIB MiB each "
                          "(calibrates hardware byte counters under a profiler)")
@@ -630,6 +634,27 @@ def main():
 
     if args.noise_study:
         print(json.dumps({"noise_study": noise_study(gen)}))
+        return
+
+    if args.probe:
+        parts = args.probe.split(",")
+        M, N, K = (int(x) for x in parts[:3])
+        dt = parts[3] if len(parts) > 3 else "f16"
+        lr = LayerRun(wl.Layer("probe", M, N, K), dt, gen, "normal", "normal")
+        res = {"probe": [M, N, K, dt]}
+        modes = [B.NONE, B.GLOBAL, B.THREAD, B.REPLICA] + ([] if dt == "i8" else [B.THREAD_HALF, B.TWOSIDED])
+        for mode in modes:
+            for _ in range(3):
+                lr.run(mode, stream)
+            torch.cuda.synchronize()
+            e0, e1 = hip.event(), hip.event()
+            hip.record(e0, stream)
+            for _ in range(10):
+                lr.run(mode, stream)
+            hip.record(e1, stream)
+            res["us_" + B.MODE_NAMES[mode]] = round(1e3 * hip.elapsed_ms(e0, e1) / 10, 2)
+        res["false_alarms"] = int(lr.flag.item())
+        print(json.dumps(res))
         return
 
     label, runs, dtype = build_workload(args.workload, gen)

@@ -1000,11 +1000,13 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             for (int i = 0; i < TM; ++i)
 #pragma unroll
                 for (int j = 0; j < TN; ++j) {
+                    // (the pairs the store packs: rounded once, widened again inside the addition)
                     float cs = 0.f;
 #pragma unroll
-                    for (int r = 0; r < MMA::NACC; ++r) {
-                        if constexpr (CFG::DT == DT_F16) cs += (float)(_Float16)acc[i][j][r];
-                        else cs += (float)(__bf16)acc[i][j][r];
+                    for (int r = 0; r < MMA::NACC; r += 2) {
+                        const int pk = pack_out16<CFG::DT>(acc[i][j][r], acc[i][j][r + 1]);
+                        cs = mul_add_half<CFG::DT, 0>(pk, 1.0f, cs);
+                        cs = mul_add_half<CFG::DT, 1>(pk, 1.0f, cs);
                     }
                     cs += __shfl_xor(cs, 32);
                     const int col = acc_col(j);

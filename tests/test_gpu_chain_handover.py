@@ -12,6 +12,7 @@ import pytest
 
 import oracle
 from paper_2104_09455_amd import binding as B
+from paper_2104_09455_amd import workloads as wl
 from test_gpu_chain import Chain, _storage, DT
 
 pytestmark = pytest.mark.gpu
@@ -235,3 +236,55 @@ def test_handover_chain_under_graph_replay():
     finally:
         B.abft_plan_set_diagnostics(ch.plan, 2)
         ch.close()
+
+
+def test_bottleneck_pair_a_3x3_convolution_hands_over_to_a_1x1_convolution():
+    """ResNet-50's conv2 -> conv3 of a bottleneck at 56 x 56, batch 16: the 3 x 3 convolution's epilogue
+    leaves the column sums of its (ReLU) output, the 1 x 1 convolution behind it reads that output as a
+    plain M x K matrix and takes them.  Outputs against the oracle (the second layer on the input it
+    read), clean flag, the reported region against the oracle's check of it."""
+    import torch
+    from gpu_util import to_dev, c_to_host, c_close, read_report, DEV
+    c2 = wl.Conv(16, 56, 56, 64, 64, 3, 3, 1, 1)
+    c3 = wl.Conv(16, 56, 56, 64, 256, 1, 1, 1, 0)
+    x, W2 = wl.conv_operands(c2, "f16", seed=1700)
+    _, W3 = wl.conv_operands(c3, "f16", seed=1701)
+    M, K2, K3 = 16 * 56 * 56, 9 * 64, 64
+    dx = to_dev(x, "f16")
+    dW2, dW3 = to_dev(np.ascontiguousarray(W2.T), "f16"), to_dev(np.ascontiguousarray(W3.T), "f16")
+    layers = [B.Layer(M, 64, K2, B.F16, B.B_NK, 1, B.Conv(16, 56, 56, 64, 3, 3, 1, 1), dW2.data_ptr(), K2),
+              B.Layer(M, 256, K3, B.F16, B.B_NK, 1, B.Conv(16, 56, 56, 64, 1, 1, 1, 0), dW3.data_ptr(), K3)]
+    plan = B.abft_plan_create(layers)
+    try:
+        for l in range(2):
+            B.abft_plan_set_mode(plan, l, B.GLOBAL)
+        B.abft_plan_set_activation(plan, 0, B.ACT_RELU)
+        Cs = [torch.zeros((M, 64), dtype=torch.float16, device=DEV), torch.zeros((M, 256), dtype=torch.float16, device=DEV)]
+        flag = torch.zeros(1, dtype=torch.int32, device=DEV)
+        rep = torch.zeros(ctypes.sizeof(B.Report), dtype=torch.uint8, device=DEV)
+        B.abft_plan_set_diagnostics(plan, 1, report=rep)
+        before = B.abft_handover_launches()
+        print("case handover conv3x3 -> conv1x1", flush=True)
+        B.abft_plan_run_chain(plan, 0, 2, dx, K2, Cs, [64, 256], flag)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == 1
+        assert int(flag.item()) == 0
+        rows = np.arange(0, M, 97)
+        A2 = oracle.im2col(x, "f16", 3, 3, 1, 1)
+        ref2 = oracle.activation(oracle.gemm(A2[rows], W2, "f16"), "relu")
+        assert c_close(c_to_host(Cs[0], "f16")[rows], ref2, "f16")
+        a3 = Cs[0].cpu().numpy()                                   # what the second layer read
+        assert c_close(c_to_host(Cs[1], "f16")[rows], oracle.gemm(a3[rows], W3, "f16"), "f16")
+        got = read_report(rep)
+        bm, bn = B.abft_region_shape(M, 256, K3, B.F16, True)
+        per_row = -(-256 // bn)
+        assert got.tiles == -(-M // bm) * per_row
+        r0, c0 = (got.region - 1) // per_row * bm, (got.region - 1) % per_row * bn
+        Ab, Bb = a3[r0:r0 + bm], np.ascontiguousarray(W3[:, c0:c0 + bn])
+        Cb = oracle.gemm(Ab, Bb, "f16")
+        ref = oracle.region_check(Ab, Bb, Cb, "f16", 0, Cb.shape[0], 0, Cb.shape[1])
+        assert not ref.flag
+        assert abs(got.lhs - ref.lhs) <= ref.tau and abs(got.rhs - ref.rhs) <= 0.1 * ref.tau
+        assert got.worst_ratio < 0.5
+    finally:
+        B.abft_plan_destroy(plan)

@@ -332,8 +332,11 @@ int abft_plan_create(abft_plan_t **plan, const abft_layer_t *layers, int n_layer
 int abft_plan_run(abft_plan_t *plan, int layer, const void *A, int64_t lda, void *C, int64_t ldc,
                   uint32_t *fault_flag, void *stream);
 /* Run every layer of the plan in order in one call: A[i], lda[i], C[i], ldc[i] (host arrays of
- * device pointers / leading dimensions) are layer i's input and output.  event_layer selects
- * the one layer whose product kernel the abft_set_kernel_events hook brackets (-1: none). */
+ * device pointers / leading dimensions) are layer i's input and output.  A layer whose input is
+ * the output of the layer before it (A[i] == C[i - 1], lda[i] == ldc[i - 1]) is chained to it and
+ * takes its activation checksums from that layer's epilogue where abft_plan_run_chain would.
+ * event_layer selects the one layer whose product kernel the abft_set_kernel_events hook brackets
+ * (-1: none). */
 int abft_plan_run_all(abft_plan_t *plan, const void *const *A, const int64_t *lda, void *const *C,
                       const int64_t *ldc, uint32_t *fault_flag, int event_layer, void *stream);
 /* Run `count` consecutive layers of the plan, from layer `first`, as a chain (Sec. 2.4 step 4):

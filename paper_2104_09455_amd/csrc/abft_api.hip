@@ -1334,6 +1334,22 @@ int abft_plan_create(abft_plan_t** plan, const abft_layer_t* layers, int n_layer
 
 namespace {
 
+// Does layer `next` of the plan, reading the M x K matrix at (a_next, lda_next) that layer `next - 1`
+// is about to store, want that layer's epilogue to leave the column sums of what it stores?  Under
+// the global scheme, same M, dtype and K = the producer's N, and when it will run on the kernel that
+// takes them.  Returns where they go (the consumer's buffer), or null.
+float* handover_target(const abft_plan_t* plan, int next, const void* a_next, int64_t lda_next) {
+    const abft_plan::Layer& nx = plan->layers[next];
+    const abft_layer_t& d = plan->layers[next - 1].desc;
+    const abft_layer_t& e = nx.desc;
+    if (nx.mode != ABFT_GLOBAL || !nx.alpha32 || e.M != d.M || e.K != d.N || e.dtype != d.dtype) return nullptr;
+    const int es = esize(e.dtype);
+    const bool a16 = aligned16(a_next) && (lda_next * es) % 16 == 0 && (e.K * es) % 16 == 0;
+    const bool b16 = e.b_layout == ABFT_B_NK && aligned16(e.B) && (e.K * es) % 16 == 0 && (e.ldb * es) % 16 == 0;
+    const CfgInfo ci = cfg_info_host(pick_cfg(e.M, e.N, e.K, e.dtype, a16 && b16, ABFT_GLOBAL));
+    return (ci.fast && ci.kways == 1) ? nx.alpha32 : nullptr;
+}
+
 // One layer of a plan.  alpha_out (may be null): where to leave the activation checksums of the
 // layer that follows (leading dimension ld_alpha_out), *alpha_emitted set when the kernel that ran
 // could; alpha_in (may be null): those the layer before left for this layer's input.
@@ -1383,11 +1399,20 @@ int abft_plan_run_all(abft_plan_t* plan, const void* const* A, const int64_t* ld
     if (!A || !lda || !C || !ldc) return ABFT_E_NULL;
     const hipEvent_t ev0 = g_ev_start, ev1 = g_ev_stop;
     int rc = ABFT_OK;
-    for (int i = 0; i < (int)plan->layers.size() && rc == ABFT_OK; ++i) {
+    const int n = (int)plan->layers.size();
+    const float* alpha_in = nullptr;
+    for (int i = 0; i < n && rc == ABFT_OK; ++i) {
         // the measurement hook, if set, brackets the product kernel of one layer only
         g_ev_start = i == event_layer ? ev0 : nullptr;
         g_ev_stop = i == event_layer ? ev1 : nullptr;
-        rc = abft_plan_run(plan, i, A[i], lda[i], C[i], ldc[i], fault_flag, stream);
+        // a layer whose input IS the output of the layer before it (same pointer and leading
+        // dimension) is chained to it: it can take its activation checksums from that layer's epilogue
+        const bool next_chained = i + 1 < n && A[i + 1] == C[i] && lda[i + 1] == ldc[i];
+        float* alpha_out = next_chained ? handover_target(plan, i + 1, C[i], ldc[i]) : nullptr;
+        bool emitted = false;
+        rc = plan_run_layer(plan, i, A[i], lda[i], C[i], ldc[i], fault_flag, stream, alpha_out,
+                            alpha_out ? plan->layers[i + 1].desc.K : 0, &emitted, alpha_in);
+        alpha_in = emitted ? alpha_out : nullptr;
     }
     g_ev_start = ev0;
     g_ev_stop = ev1;
@@ -1424,24 +1449,8 @@ int abft_plan_run_chain(abft_plan_t* plan, int first, int count, const void* A, 
         int rc = ABFT_OK;
         const float* alpha_in = nullptr;
         for (int i = 0; i < count && rc == ABFT_OK; ++i) {
-            float* alpha_out = nullptr;
-            long long ld_alpha = 0;
-            if (i + 1 < count) {
-                const abft_plan::Layer& nx = plan->layers[first + i + 1];
-                const abft_layer_t& d = plan->layers[first + i].desc;
-                if (nx.mode == ABFT_GLOBAL && nx.alpha32 && nx.desc.M == d.M && nx.desc.K == d.N && nx.desc.dtype == d.dtype) {
-                    // (only when the next layer will run on the kernel that takes them)
-                    const abft_layer_t& e = nx.desc;
-                    const int es = esize(e.dtype);
-                    const bool a16 = aligned16(C[i]) && (ldc[i] * es) % 16 == 0 && (e.K * es) % 16 == 0;
-                    const bool b16 = e.b_layout == ABFT_B_NK && aligned16(e.B) && (e.K * es) % 16 == 0 && (e.ldb * es) % 16 == 0;
-                    const CfgInfo ci = cfg_info_host(pick_cfg(e.M, e.N, e.K, e.dtype, a16 && b16, ABFT_GLOBAL));
-                    if (ci.fast && ci.kways == 1) {
-                        alpha_out = nx.alpha32;
-                        ld_alpha = e.K;
-                    }
-                }
-            }
+            float* alpha_out = i + 1 < count ? handover_target(plan, first + i + 1, C[i], ldc[i]) : nullptr;
+            const long long ld_alpha = alpha_out ? plan->layers[first + i + 1].desc.K : 0;
             bool emitted = false;
             rc = plan_run_layer(plan, first + i, i == 0 ? A : C[i - 1], i == 0 ? lda : ldc[i - 1], C[i], ldc[i], fault_flag,
                                 stream, alpha_out, ld_alpha, &emitted, alpha_in);

@@ -123,6 +123,10 @@ def test_argument_validation_without_a_gpu(lib):
     with pytest.raises(B.AbftError) as e:
         B.abft_plan_mode(None, 0)
     assert e.value.code == -8
+    # plan calls without a plan
+    assert lib.abft_plan_set_diagnostics(None, 0, None, None) == -8
+    assert lib.abft_plan_run_chain(None, 0, 1, p, 4, None, None, p, None) == -8
+    assert lib.abft_handover_launches() == 0   # nothing has run in this process
     bad = B.Conv(1, 2, 2, 8, 3, 3, 1, 0)  # 3x3 filter on a 2x2 image without padding
     assert lib.abft_conv(ctypes.byref(bad), 4, p, p, 72, 0, p, 4, 0, 0, None, None, 0, p, None, None, None) == -2
 

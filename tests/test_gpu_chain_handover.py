@@ -288,3 +288,31 @@ def test_bottleneck_pair_a_3x3_convolution_hands_over_to_a_1x1_convolution():
         assert got.worst_ratio < 0.5
     finally:
         B.abft_plan_destroy(plan)
+
+
+def test_run_all_chains_layers_by_their_buffers():
+    """abft_plan_run_all with layer l's output passed as layer l + 1's input hands the checksums
+    over like abft_plan_run_chain; with inputs of their own the layers run independently."""
+    import torch
+    from gpu_util import to_dev
+    ch = Chain(M_MID, WIDTHS, "f16", seed=1800, modes=[B.GLOBAL] * 4)
+    try:
+        x, dx = ch.input(seed=1801)
+        io = B.PlanIO([dx] + ch.Cs[:-1], list(ch.widths[:-1]), ch.Cs, list(ch.widths[1:]))
+        before = B.abft_handover_launches()
+        B.abft_plan_run_all(ch.plan, io, ch.flag, -1)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == 2
+        assert int(ch.flag.item()) == 0
+        ch.check(x)
+        # the same layers on copies of their inputs: no pair is chained
+        ins = [dx] + [c.clone() for c in ch.Cs[:-1]]
+        io2 = B.PlanIO(ins, list(ch.widths[:-1]), ch.Cs, list(ch.widths[1:]))
+        before = B.abft_handover_launches()
+        B.abft_plan_run_all(ch.plan, io2, ch.flag, -1)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == 0
+        assert int(ch.flag.item()) == 0
+        ch.check(x)
+    finally:
+        ch.close()

@@ -5,8 +5,11 @@
 // (32 TM) x (32 TN) register tile of MFMA 32x32 blocks.  The flagship instance is 256 x 256
 // with eight wavefronts of 128 x 64, two per SIMD (128 accumulators per lane); smaller
 // instances with wide-in-N wavefront tiles serve mid-size layers.  In the global scheme the
-// kernel also forms the checksum dot product of its tile from the A chunks in LDS and the
-// weight checksums of its column block, which travel with the operand tiles.
+// kernel also forms the checksum dot product of its tile, from the A tiles it loads and the
+// weight checksums of its column block, which travel with the operand tiles: on the matrix
+// unit (fp16, int8), with vector FMAs on the A chunks in LDS (bf16, the 256 x 256 tile), or,
+// when the layer before handed over the column sums of A, with one multiplication per lane
+// and k tile.
 //
 // Data flow: global_load_lds_dwordx4 moves 16-byte chunks from HBM straight into LDS
 // (no staging registers), NSTAGE LDS stages, rows of 128 bytes stored with an XOR

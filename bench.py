@@ -407,6 +407,26 @@ def handover_leg(gen, M=2048, widths=(4096, 4096, 4096, 4096, 4096), dtype="f16"
             best = min(best, 1e3 * e0.elapsed_time(e1) / steps)
         return best
 
+    def brackets():
+        """HIP events right around each layer's product kernel inside the chain (one layer per pass)."""
+        hip = Hip()
+        io = B.PlanIO([rs[0].A] + Cs[:-1], list(widths[:-1]), Cs, ldc)
+        out = []
+        for layer in range(nl):
+            e0, e1 = hip.event(), hip.event()
+            B.abft_set_kernel_events(e0, e1)
+            tot = 0.0
+            for it in range(15):
+                B.abft_plan_run_all(plan, io, flag, layer)
+                torch.cuda.synchronize()
+                if it >= 5:
+                    tot += 1e3 * hip.elapsed_ms(e0, e1)
+            B.abft_set_kernel_events(None, None)
+            hip.destroy(e0)
+            hip.destroy(e1)
+            out.append(round(tot / 10, 1))
+        return out
+
     res = {"M": M, "widths": list(widths), "dtype": dtype}
     try:
         for label, mode in (("none", B.NONE), ("global", B.GLOBAL)):
@@ -417,6 +437,8 @@ def handover_leg(gen, M=2048, widths=(4096, 4096, 4096, 4096, 4096), dtype="f16"
             res["us_" + label + "_chain"] = round(pass_us(chain), 2)
             if mode == B.GLOBAL:
                 res["layers_with_handed_over_checksums"] = (B.abft_handover_launches() - before) // (3 * steps + 5)
+            # (the first layer's bracket also holds the start from an idle GPU)
+            res["kernel_bracket_us_per_layer_" + label + "_chain"] = brackets()
         res["ovh_global_alone_pct"] = round(100 * (res["us_global_alone"] / res["us_none_alone"] - 1), 2)
         res["ovh_global_chain_pct"] = round(100 * (res["us_global_chain"] / res["us_none_chain"] - 1), 2)
         res["false_alarms"] = int(flag.item())
@@ -605,6 +627,10 @@ def main():
                     help="only run one fully-connected layer of that shape ten times under every scheme (each scheme "
                          "is a kernel of its own name, so hardware counters of a profiler separate them) and print "
                          "the device times as one JSON line")
+    ap.add_argument("--chain", default=None, metavar="M,WIDTH,LAYERS[,DTYPE]",
+                    help="only run the chain leg for LAYERS fully-connected layers of WIDTH x WIDTH at batch M "
+                         "(stand-alone layers against the chain with handed-over activation checksums) and print "
+                         "it as one JSON line")
     ap.add_argument("--copy-probe", type=int, default=0, metavar="MIB",
                     help="first run 5 plain element-wise copy kernels that read MIB MiB and write MIB MiB each "
                          "(calibrates hardware byte counters under a profiler)")
@@ -634,6 +660,12 @@ def main():
 
     if args.noise_study:
         print(json.dumps({"noise_study": noise_study(gen)}))
+        return
+
+    if args.chain:
+        parts = args.chain.split(",")
+        m, width, nl = (int(x) for x in parts[:3])
+        print(json.dumps({"chain": handover_leg(gen, m, (width,) * (nl + 1), parts[3] if len(parts) > 3 else "f16", steps=20)}))
         return
 
     if args.probe:

@@ -229,7 +229,7 @@ size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int 
 
 /* Offline weight checksums (Sec. 2.5), one per block of block_n consecutive columns: with
  * nb = ceil(N / block_n), beta_b[k] = sum over n in [b*block_n, min(N, (b+1)*block_n)) of B[k][n].
- * The buffer `beta` (device, abft_beta_bytes(K, N, block_n) bytes, 256-byte aligned) receives three
+ * The buffer `beta` (device, abft_beta_bytes(K, N, block_n) bytes, 256-byte aligned) receives four
  * copies: first K x nb values k-major, beta[k*nb + b], as doubles (F16 / BF16) or int64 (I8);
  * then, at the next multiple of 256 bytes, the copy the product kernels read inside their loops
  * (4 bytes per k and block): per block b, K floats (F16 / BF16), or K low digits followed by K
@@ -238,7 +238,11 @@ size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int 
  * of the latency-bound tiling: F16: per block four planes of K halves, fl16(beta),
  * fl16((beta - fl16(beta)) 2^11) and the same two pieces of the column-weighted checksum
  * sum_j (j + 1) / block_n * B[k][b*block_n + j] (block_n as passed, also where N is smaller); I8: per block four planes of K signed bytes, the
- * digits (base 256, balanced, least significant first) of sum_j (j + 1) * B[k][b*block_n + j].
+ * digits (base 256, balanced, least significant first) of sum_j (j + 1) * B[k][b*block_n + j];
+ * last, again at a multiple of 256 bytes, per block and per k tile of the large-tile kernel (64
+ * values of k; I8: 128) one record of 1 KB that the kernel copies in with its operand tiles: F16:
+ * 64 halves fl16(beta), 64 halves fl16((beta - fl16(beta)) 2^11), then from byte 256 the 64 floats;
+ * BF16: the 64 floats at byte 256; I8: 128 low digits, 128 high digits.
  * block_n <= 0 or >= N gives the plain K-vector B.1 . */
 int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
                          void *beta, void *stream);

@@ -370,7 +370,7 @@ __global__ __launch_bounds__(256) void act_checksum_kernel(const PreArgs p) {
 template <int DT>
 __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int K, int N, long long sn,
                                                               long long sk, int block_n, int wnorm, void* beta,
-                                                              char* beta_k, char* beta_p) {
+                                                              char* beta_k, char* beta_p, char* beta_r) {
     constexpr int ESIZE = DT == DT_I8 ? 1 : 2;
     typedef typename std::conditional<DT == DT_I8, long long, double>::type Wide;
     __shared__ Wide red[2][8][32];
@@ -410,12 +410,20 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
         // four planes of K halves, hi = fl16(beta), lo = fl16((beta - hi) 2^11), and the same two
         // pieces of the column-weighted checksum; int8: four planes of K digits of the
         // column-weighted checksum (balanced base 256, least significant first)
+        // fourth copy, for the direct-to-LDS kernel: per block and k tile of that kernel (64 values of k;
+        // int8: 128) a record of 1 KB -- fp16: 64 halves fl16(beta), 64 halves fl16((beta - hi) 2^11), then
+        // (at byte 256) 64 floats; bf16: the 64 floats; int8: 128 low digits, 128 high digits
+        constexpr int KT = DT == DT_I8 ? 128 : 64;
+        char* rec = beta_r + ((long long)blockIdx.y * ((K + KT - 1) / KT) + k / KT) * 1024;
+        const int kin = k % KT;
         if constexpr (DT == DT_I8) {
             const long long lo = (long long)(signed char)(a & 0xff);
             const long long hi = (a - lo) >> 8;
             signed char* d = reinterpret_cast<signed char*>(beta_k) + (long long)blockIdx.y * 2 * K;
             d[k] = (signed char)lo;
             d[K + k] = (signed char)(hi < -128 ? -128 : (hi > 127 ? 127 : hi));
+            reinterpret_cast<signed char*>(rec)[kin] = d[k];
+            reinterpret_cast<signed char*>(rec)[128 + kin] = d[K + k];
             signed char* dv = reinterpret_cast<signed char*>(beta_p) + (long long)blockIdx.y * 8 * K;
             long long rest = av;
             for (int q = 0; q < 4; ++q) {
@@ -425,11 +433,14 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
             }
         } else {
             reinterpret_cast<float*>(beta_k)[(long long)blockIdx.y * K + k] = (float)a;
+            reinterpret_cast<float*>(rec + 256)[kin] = (float)a;
             if constexpr (DT == DT_F16) {
                 _Float16* pl = reinterpret_cast<_Float16*>(beta_p) + (long long)blockIdx.y * 4 * K;
                 const _Float16 hi = (_Float16)(float)a;
                 pl[k] = hi;
                 pl[K + k] = (_Float16)(((float)a - (float)hi) * 2048.f);
+                reinterpret_cast<_Float16*>(rec)[kin] = pl[k];
+                reinterpret_cast<_Float16*>(rec + 128)[kin] = pl[K + k];
                 const _Float16 vhi = (_Float16)(float)av;
                 pl[2 * K + k] = vhi;
                 pl[3 * K + k] = (_Float16)(((float)av - (float)vhi) * 2048.f);
@@ -560,7 +571,11 @@ size_t beta_k_offset(int K, int nb) { return align_up((size_t)K * nb * 8, 256); 
 // third copy, 8 bytes per k and block: the columns of the extra operand with which the streaming
 // kernel forms its dot products on the matrix unit (see weight_checksum_kernel)
 size_t beta_p_offset(int K, int nb) { return beta_k_offset(K, nb) + align_up((size_t)K * nb * 4, 256); }
-size_t beta_total_bytes(int K, int nb) { return beta_p_offset(K, nb) + align_up((size_t)K * nb * 8, 256); }
+// fourth copy: one 1 KB record per block and k tile of the direct-to-LDS kernel (64 values of k; int8:
+// 128), which one 16-byte-per-lane copy brings in with the operand tiles (see weight_checksum_kernel);
+// sized for the shorter k tile
+size_t beta_r_offset(int K, int nb) { return beta_p_offset(K, nb) + align_up((size_t)K * nb * 8, 256); }
+size_t beta_total_bytes(int K, int nb) { return beta_r_offset(K, nb) + (size_t)nb * cdiv(K, 64) * 1024; }
 
 WsLayout ws_layout(int M, int N, int K, int cfg) {
     CfgInfo ci = cfg_info_host(cfg);
@@ -629,14 +644,15 @@ hipError_t launch_weight_checksum(int K, int N, const void* B, long long ldb, in
     void* beta = beta_buf;
     char* beta_k = reinterpret_cast<char*>(beta_buf) + beta_k_offset(K, (int)cdiv(N, block_n));
     char* beta_p = reinterpret_cast<char*>(beta_buf) + beta_p_offset(K, (int)cdiv(N, block_n));
+    char* beta_r = reinterpret_cast<char*>(beta_buf) + beta_r_offset(K, (int)cdiv(N, block_n));
     dim3 grid((unsigned)cdiv(K, 32), (unsigned)cdiv(N, block_n)), block(256);
     const char* b = reinterpret_cast<const char*>(B);
     if (dt == ABFT_F16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_F16>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p, beta_r);
     else if (dt == ABFT_BF16)
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_BF16>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p, beta_r);
     else
-        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p);
+        hipLaunchKernelGGL(weight_checksum_kernel<DT_I8>, grid, block, 0, st, b, K, N, sn, sk, block_n, wnorm, beta, beta_k, beta_p, beta_r);
     return hipGetLastError();
 }
 
@@ -788,12 +804,13 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
             kmode = MODE_GLOBAL_FED;
             g_handover_launches.fetch_add(1, std::memory_order_relaxed);
             g.alpha_in = pr.alpha_in;
-            g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
+            g.beta_r = reinterpret_cast<const char*>(beta_used) + beta_r_offset(pr.K, g.tiles_n);
         } else if (fused_global(pr, ci)) {
             // the direct-to-LDS kernel forms the activation checksum's dot product with the weight
             // checksums itself, from the A tiles it multiplies (steps 1-3 inside the product's loop)
             g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
             g.beta_p = reinterpret_cast<const char*>(beta_used) + beta_p_offset(pr.K, g.tiles_n);
+            g.beta_r = reinterpret_cast<const char*>(beta_used) + beta_r_offset(pr.K, g.tiles_n);
         } else {
             kmode = MODE_GLOBAL_PRE;
             g.partial_dots = ws + w.off_pd;

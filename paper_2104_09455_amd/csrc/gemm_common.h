@@ -126,6 +126,8 @@ struct GemmArgs {
                               // K high digits (balanced base 256, one byte each) per block (int8)
     const char* beta_p;       // GLOBAL, streaming kernel, fp16: the same checksums as two planes of halves per
                               // block, K values hi = fl16(beta) then K values lo = fl16((beta - hi) 2^11)
+    const char* beta_r;       // GLOBAL, direct-to-LDS kernel: the same checksums as one 1 KB record per block and k
+                              // tile, copied with the operand tiles (layout: weight_checksum_kernel)
     const void* partial_dots; // GLOBAL otherwise: per tile n_parts partial checksum dot products (double / int64)
     int n_parts;
     double tol_l1;           // GLOBAL: coefficient of the tile's sum of magnitudes in tau

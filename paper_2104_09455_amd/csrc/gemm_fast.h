@@ -55,21 +55,20 @@ struct FastLayout {
     static constexpr int WAVES = CFG::WAVES_M * CFG::WAVES_N;
     static constexpr int A_STAGE = CFG::BM * ROWB;
     static constexpr int AB_STAGE = (CFG::BM + CFG::BN) * ROWB;
-    // global scheme: every wavefront also copies the k tile's 256 bytes of weight checksums
-    // (of the workgroup's column block) into a slot of its own behind the operand tiles
-    static constexpr int BETA_SLOT = 256;
-    static constexpr int STAGE = AB_STAGE + WAVES * BETA_SLOT;
+    // global scheme: behind the operand tiles of a stage, the k tile's record of weight checksums of
+    // the workgroup's column block (1 KB, copied by wavefront 0 like one more group of eight rows of B)
+    static constexpr int BETA_REC = 1024;
+    static constexpr int STAGE = AB_STAGE + BETA_REC;
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
-    // Activation checksums handed over by the layer before (and the weight checksums that go with
-    // them) travel in runs of 256 floats, four k tiles at a time, through rings of two 1 KB slots behind
-    // the stages: one ring per wavefront for its 32-row block's sums, one for the workgroup's weight checksums
-    static constexpr int RING_A = NSTAGE * STAGE, RING_B = RING_A + WAVES * 2048;
-    static constexpr int LDS_BYTES_FED = RING_B + 2048;
+    // Activation checksums handed over by the layer before travel in runs of 256 floats, four k
+    // tiles at a time, through a ring of two 1 KB slots per wavefront (its 32-row block's sums) behind the stages
+    static constexpr int RING_A = NSTAGE * STAGE;
+    static constexpr int LDS_BYTES_FED = RING_A + WAVES * 2048;
     static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
     static_assert(CFG::MI == 32 && CFG::BKB == 128, "32x32 MFMA shapes, 128-byte k tile");
-    static_assert((NSTAGE - 2) * (NQA + NQB + 1) <= 63, "vmcnt range");
+    static_assert((NSTAGE - 2) * (NQA + NQB) <= 63, "vmcnt range");
 };
 
 template <class CFG, int NSTAGE, int MODE, bool INJ, bool CONV>
@@ -150,28 +149,21 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             aptr[q] = zero;
         }
     }
-    // weight checksums of this tile's column block: lane l copies bytes 4l .. 4l+3 of the k tile's
-    // 256 (fp16 / bf16: float l of 64; int8: low digits in lanes 0-31, high digits in lanes 32-63)
-    // (matrix-unit form, fp16: first / second piece as halves in lanes 0-31 / 32-63)
-    const char* beta_ptr = zero;
-    if constexpr (GDOT) {
-        const long long blk = (long long)tile_n * p.K;
-        if constexpr (IS_INT) beta_ptr = p.beta_k + blk * 2 + (lane >> 5) * (long long)p.K + (lane & 31) * 4;
-        else if constexpr (MDOT) beta_ptr = p.beta_p + blk * 8 + (lane >> 5) * 2 * (long long)p.K + (lane & 31) * 4;
-        else beta_ptr = p.beta_k + (blk + lane) * 4;
-    }
-    constexpr int BETA_ADV = IS_INT ? BK : (MDOT ? BK * 2 : BK * 4);
+    // weight checksums of this tile's column block: one record of 1 KB per k tile (layout:
+    // weight_checksum_kernel: fp16 halves hi / lo at bytes 0 / 128 and floats at 256; bf16 the floats;
+    // int8 low / high digits at 0 / 128), copied by one wavefront, 16 bytes per lane
+    constexpr bool BREC = GDOT || FED;
+    const char* beta_rec = zero;
+    int rec_turn = 0;  // the wavefront that copies the next record
+    if constexpr (BREC) beta_rec = p.beta_r + (long long)tile_n * nkt * 1024 + lane * 16;
     // Handed-over activation checksums.  Group g = k tiles 4 g .. 4 g + 3 = floats 256 g .. 256 g + 255 of
-    // this wavefront's row of sums (lane l copies floats 4 l .. 4 l + 3 of the group) and, by wavefront 0
-    // for everyone, of the column block's weight checksums; group g sits in slot g % 2 and is
-    // copied while group g - 1 is in use.  These copies are older than the operand copies any later
-    // wait counts on, so every such wait covers them too.
+    // this wavefront's row of sums (lane l copies floats 4 l .. 4 l + 3 of the group); group g sits in
+    // slot g % 2 and is copied while group g - 1 is in use.  These copies are older than the operand
+    // copies any later wait counts on, so every such wait covers them too.
     const char* fed_alpha = nullptr;
-    const char* fed_beta = nullptr;
     if constexpr (FED) {
         const int blk = tile_m * (BM / 32) + wave;
         if (blk * 32 < M) fed_alpha = reinterpret_cast<const char*>(p.alpha_in + (long long)blk * p.K);
-        fed_beta = p.beta_k + (long long)tile_n * p.K * 4;
     }
     auto issue_group = [&](int g) {
         if constexpr (FED) {
@@ -181,12 +173,6 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(smem + LAY::RING_A + (wave * 2 + (g & 1)) * 1024),
                                              16, 0, 0);
-            if (wave == 0) {
-                const char* srcb = in_k ? fed_beta + (long long)f0 * 4 : zero;
-                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)srcb,
-                                                 (__attribute__((address_space(3))) void*)(smem + LAY::RING_B + (g & 1) * 1024),
-                                                 16, 0, 0);
-            }
         }
     };
     if constexpr (CONV) {
@@ -216,13 +202,16 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         for (int q = 0; q < NQB; ++q)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)bptr[q],
                                              (__attribute__((address_space(3))) void*)(bbase + q * WAVES * 1024), 16, 0, 0);
-        if constexpr (GDOT)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)beta_ptr,
-                                             (__attribute__((address_space(3))) void*)(smem + stage * STAGE + LAY::AB_STAGE + wave * LAY::BETA_SLOT),
-                                             4, 0, 0);
+        if constexpr (BREC) {
+            // (the wavefronts take turns, so that none carries the extra copy every tile)
+            if (rec_turn == wave)
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)beta_rec,
+                                                 (__attribute__((address_space(3))) void*)(smem + stage * STAGE + LAY::AB_STAGE), 16, 0, 0);
+            rec_turn = rec_turn + 1 == WAVES ? 0 : rec_turn + 1;
+        }
     };
     auto advance = [&]() {
-        if constexpr (GDOT) beta_ptr += BETA_ADV;
+        if constexpr (BREC) beta_rec += 1024;
         if constexpr (!CONV) {
 #pragma unroll
             for (int q = 0; q < NQA; ++q) aptr[q] += ((a_valid >> q) & 1u) ? BKB : 0;
@@ -272,17 +261,17 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // conflicts; together the lanes cover the tile exactly once) and multiplies them with the
     // 8 (16 for int8) weight checksums of its k chunk, with vector FMAs / dot4 that run beside
     // the MFMAs.  Per k tile the fp32 / int32 partial sums move into a wide accumulator.
-    const int beta_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + ckc * (IS_INT ? 16 : 32);
+    const int beta_off = LAY::AB_STAGE + (IS_INT ? ckc * 16 : 256 + ckc * 32);  // this lane's k chunk in the record
     ChecksumDot<DT> dot;
     float fed_a = 0.f, fed_b = 0.f;
-    auto fed_tile = [&](int kt) {
+    auto fed_tile = [&](const char* st, int kt) {
         if constexpr (FED) {
             // lane l: (column sum of the wavefront's 32 rows at k = l of the tile) x (weight checksum
             // there); the product is taken one tile later, when the two reads have long landed
             dot.total += (double)fed_a * (double)fed_b;
             const int off = ((kt >> 2) & 1) * 1024 + ((kt & 3) * 64 + lane) * 4;
             fed_a = *reinterpret_cast<const float*>(smem + LAY::RING_A + wave * 2048 + off);
-            fed_b = *reinterpret_cast<const float*>(smem + LAY::RING_B + off);
+            fed_b = *reinterpret_cast<const float*>(st + LAY::AB_STAGE + 256 + lane * 4);
             // the slot of the group before is free (everyone read its last tile before the barrier
             // of that tile): the next group goes there
             if ((kt & 3) == 0 && kt >= 4 && 4 * ((kt >> 2) + 1) < nkt) issue_group((kt >> 2) + 1);
@@ -308,7 +297,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // parity add up to A . piece s.  Four selects per k step, no other vector arithmetic.
     const int gcol = lane & 31;
     const int g_step = gcol >> 1;  // the k step whose chunk this lane holds (>= 4: none)
-    const int gb_off = LAY::AB_STAGE + wave * LAY::BETA_SLOT + (gcol & 1) * 128 + (g_step & 3) * 32 + fgrp * 16;
+    const int gb_off = LAY::AB_STAGE + (gcol & 1) * 128 + (g_step & 3) * 32 + fgrp * 16;
     i32x4 g_tile = {0, 0, 0, 0};
     auto read_checksum_frag = [&](const char* st) {
         if constexpr (MDOT) g_tile = *reinterpret_cast<const i32x4*>(st + gb_off);
@@ -350,7 +339,9 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // being multiplied.  The workgroup barrier sits before the last k step of each tile,
     // whose fragments are already in registers, so the barrier wait, the issue of the next
     // copies and the first fragment reads of the next tile all run under those MFMAs.
-    constexpr int NL = NQA + NQB + (GDOT ? 1 : 0);  // copies per wave per tile
+    // copies per wave per tile (the one more of the wavefront whose turn it is to copy the record makes
+    // its waits at most one copy stricter than needed)
+    constexpr int NL = NQA + NQB;
     if constexpr (FED) {
         issue_group(0);
         if (nkt > 4) issue_group(1);
@@ -372,7 +363,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         constexpr int CUR = decltype(cur_c)::value;
         const char* st = smem + stage * STAGE;
         dot_tile(st);
-        fed_tile(kt);
+        fed_tile(st, kt);
         {
 #pragma unroll
             for (int kk = 0; kk < 3; ++kk) {

@@ -128,7 +128,7 @@ __global__ __launch_bounds__(256) void mlp_chain_kernel(const ChainArgs a) {
         g.b_sn = L.ldb; g.b_sk = 1;
         g.a_vec = g.b_vec = 1;
         g.conv = 0;
-        g.beta_k = L.beta_k; g.beta_p = L.beta_p;
+        g.beta_k = L.beta_k; g.beta_p = L.beta_p; g.beta_r = nullptr;
         g.partial_dots = nullptr; g.n_parts = 0;
         g.tol_l1 = L.tol_l1; g.tol_coeff = L.tol_coeff;
         g.flag = a.fault_flag; g.report = nullptr;

@@ -182,6 +182,26 @@ def test_checksum_vectors(dtype):
                     vhi = wsum.astype(np.float16)
                     assert np.array_equal(third[:, 2], vhi)
                     assert np.array_equal(third[:, 3], ((wsum - vhi.astype(np.float32)) * np.float32(2048)).astype(np.float16))
+            # fourth copy: per block and k tile of the large-tile kernel (64 values of k; int8: 128) a
+            # record of 1 KB behind the third copy: the tile's pieces / floats / digits of the second and third
+            kt = 128 if dtype == "i8" else 64
+            nrec = -(-K // kt)
+            recs = second[-(-(nb * K * 4) // 256) * 256:][-(-(nb * K * 8) // 256) * 256:][:nb * nrec * 1024].reshape(nb, nrec, 1024)
+            for b in range(nb):
+                for t in range(nrec):
+                    n_k = min(kt, K - t * kt)
+                    ks = slice(t * kt, t * kt + n_k)
+                    if dtype == "i8":
+                        d = recs[b, t].view(np.int8).astype(np.int64)
+                        assert np.array_equal(d[:n_k] + 256 * d[128:128 + n_k], blocks[b, ks])
+                    else:
+                        want = blocks[b, ks].astype(np.float32)
+                        assert np.array_equal(recs[b, t][256:256 + 4 * n_k].view(np.float32), want)
+                        if dtype == "f16":
+                            h = want.astype(np.float16)
+                            assert np.array_equal(recs[b, t][:2 * n_k].view(np.float16), h)
+                            assert np.array_equal(recs[b, t][128:128 + 2 * n_k].view(np.float16),
+                                                  ((want - h.astype(np.float32)) * np.float32(2048)).astype(np.float16))
         if dtype == "i8":
             assert np.array_equal(alpha.cpu().numpy(), a_ref)
         else:

@@ -804,7 +804,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
             kmode = MODE_GLOBAL_FED;
             g_handover_launches.fetch_add(1, std::memory_order_relaxed);
             g.alpha_in = pr.alpha_in;
-            g.beta_r = reinterpret_cast<const char*>(beta_used) + beta_r_offset(pr.K, g.tiles_n);
+            g.beta_k = reinterpret_cast<const char*>(beta_used) + beta_k_offset(pr.K, g.tiles_n);
         } else if (fused_global(pr, ci)) {
             // the direct-to-LDS kernel forms the activation checksum's dot product with the weight
             // checksums itself, from the A tiles it multiplies (steps 1-3 inside the product's loop)

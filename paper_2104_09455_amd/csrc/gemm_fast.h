@@ -62,8 +62,10 @@ struct FastLayout {
     static constexpr int LDS_BYTES = NSTAGE * STAGE;
     // Activation checksums handed over by the layer before travel in runs of 256 floats, four k
     // tiles at a time, through a ring of two 1 KB slots per wavefront (its 32-row block's sums) behind the stages
-    static constexpr int RING_A = NSTAGE * STAGE;
-    static constexpr int LDS_BYTES_FED = RING_A + WAVES * 2048;
+    // and, with them, 256 floats of the column block's weight checksums through one such ring for the
+    // workgroup (a quarter of the copies that a record per k tile would take)
+    static constexpr int RING_A = NSTAGE * STAGE, RING_B = RING_A + WAVES * 2048;
+    static constexpr int LDS_BYTES_FED = RING_B + 2048;
     static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
@@ -152,18 +154,21 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // weight checksums of this tile's column block: one record of 1 KB per k tile (layout:
     // weight_checksum_kernel: fp16 halves hi / lo at bytes 0 / 128 and floats at 256; bf16 the floats;
     // int8 low / high digits at 0 / 128), copied by one wavefront, 16 bytes per lane
-    constexpr bool BREC = GDOT || FED;
+    constexpr bool BREC = GDOT;
     const char* beta_rec = zero;
     int rec_turn = 0;  // the wavefront that copies the next record
     if constexpr (BREC) beta_rec = p.beta_r + (long long)tile_n * nkt * 1024 + lane * 16;
     // Handed-over activation checksums.  Group g = k tiles 4 g .. 4 g + 3 = floats 256 g .. 256 g + 255 of
-    // this wavefront's row of sums (lane l copies floats 4 l .. 4 l + 3 of the group); group g sits in
+    // this wavefront's row of sums (lane l copies floats 4 l .. 4 l + 3 of the group) and, by wavefront 0
+    // for everyone, of the column block's weight checksums; group g sits in
     // slot g % 2 and is copied while group g - 1 is in use.  These copies are older than the operand
     // copies any later wait counts on, so every such wait covers them too.
     const char* fed_alpha = nullptr;
+    const char* fed_beta = nullptr;
     if constexpr (FED) {
         const int blk = tile_m * (BM / 32) + wave;
         if (blk * 32 < M) fed_alpha = reinterpret_cast<const char*>(p.alpha_in + (long long)blk * p.K);
+        fed_beta = p.beta_k + (long long)tile_n * p.K * 4;
     }
     auto issue_group = [&](int g) {
         if constexpr (FED) {
@@ -173,6 +178,12 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)src,
                                              (__attribute__((address_space(3))) void*)(smem + LAY::RING_A + (wave * 2 + (g & 1)) * 1024),
                                              16, 0, 0);
+            if (wave == 0) {
+                const char* srcb = in_k ? fed_beta + (long long)f0 * 4 : zero;
+                __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void*)srcb,
+                                                 (__attribute__((address_space(3))) void*)(smem + LAY::RING_B + (g & 1) * 1024),
+                                                 16, 0, 0);
+            }
         }
     };
     if constexpr (CONV) {
@@ -271,7 +282,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             dot.total += (double)fed_a * (double)fed_b;
             const int off = ((kt >> 2) & 1) * 1024 + ((kt & 3) * 64 + lane) * 4;
             fed_a = *reinterpret_cast<const float*>(smem + LAY::RING_A + wave * 2048 + off);
-            fed_b = *reinterpret_cast<const float*>(st + LAY::AB_STAGE + 256 + lane * 4);
+            fed_b = *reinterpret_cast<const float*>(smem + LAY::RING_B + off);
             // the slot of the group before is free (everyone read its last tile before the barrier
             // of that tile): the next group goes there
             if ((kt & 3) == 0 && kt >= 4 && 4 * ((kt >> 2) + 1) < nkt) issue_group((kt >> 2) + 1);

@@ -799,6 +799,24 @@ __device__ __forceinline__ typename std::conditional<CFG::DT == DT_I8, long long
     }
 }
 
+// Which wavefront adds up what every wavefront of the workgroup left in LDS.  Without a scratch
+// area of its own (the sums sit in LDS that held operands): wavefront 0, after a barrier.  With
+// one (epi: the sums at its start, a counter that starts at zero 256 bytes in): whichever
+// wavefront arrives last, so that no wavefront waits.  A wavefront's LDS operations execute in
+// the order it issued them, so the counter value that marks the last arrival is returned only
+// after every earlier arrival's sums are in place.
+template <class CFG>
+__device__ __forceinline__ bool cross_wave_last(char* epi, int lane, int wave) {
+    if (!epi) {
+        __syncthreads();
+        return wave == 0;
+    }
+    unsigned seen = 0;
+    if (lane == 0)
+        seen = __hip_atomic_fetch_add(reinterpret_cast<unsigned*>(epi + 256), 1u, __ATOMIC_ACQ_REL, __HIP_MEMORY_SCOPE_WORKGROUP);
+    return __builtin_amdgcn_readfirstlane(seen) == (unsigned)(CFG::WAVES_M * CFG::WAVES_N - 1);
+}
+
 // Checksum epilogue (taken from the accumulators, before down-conversion) and store of C.
 //  GLOBAL: fused output summation (Sec. 2.5) of the workgroup tile, compared right here with
 //          the tile's checksum dot product (Sec. 2.4 steps 3-4).  lane_dot (a double, or a
@@ -811,7 +829,7 @@ template <class CFG, int MODE>
 __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&acc)[CFG::TM][CFG::TN],
                                          typename Mma<CFG::DT, CFG::MI>::Acc (&chk)[(CheckRegs<CFG, MODE>::N)],
                                          const GemmArgs& p, int tile_m, int tile_n, char* smem, bool store = true,
-                                         int wave_mn = -1, const void* lane_dot = nullptr) {
+                                         int wave_mn = -1, const void* lane_dot = nullptr, char* epi = nullptr) {
     typedef Mma<CFG::DT, CFG::MI> MMA;
     constexpr int MI = CFG::MI, TM = CFG::TM, TN = CFG::TN;
     constexpr bool IS_INT = CFG::DT == DT_I8;
@@ -846,16 +864,15 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
             long long s = ((long long)s_hi << 16) + (long long)s_lo;
             s = wave_sum(s);
             if constexpr (MODE == MODE_GLOBAL) {
-                long long* red = reinterpret_cast<long long*>(smem);
+                long long* red = reinterpret_cast<long long*>(epi ? epi : smem);
                 long long wdot = 0;
                 if (lane_dot) wdot = wave_sum(*reinterpret_cast<const long long*>(lane_dot));
-                __syncthreads();
+                if (!epi) __syncthreads();
                 if (lane == 0) {
                     red[2 * wave] = s;
                     red[2 * wave + 1] = wdot;
                 }
-                __syncthreads();
-                if (wave == 0) {
+                if (cross_wave_last<CFG>(epi, lane, wave)) {
                     // comparison (Sec. 2.4 step 4) for this tile: its output summation against the
                     // sum of the partial checksum dot products the activation-checksum kernel left
                     long long tot = 0, sab = 0;
@@ -919,16 +936,15 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                     s = wave_sum(s);
                     if (lane_dot) wdot = wave_sum(*reinterpret_cast<const double*>(lane_dot));
                 }
-                double* red = reinterpret_cast<double*>(smem);
-                __syncthreads();
+                double* red = reinterpret_cast<double*>(epi ? epi : smem);
+                if (!epi) __syncthreads();
                 if (lane == 0) {
                     red[4 * wave] = s;
                     red[4 * wave + 1] = F2;
                     red[4 * wave + 2] = L1;
                     red[4 * wave + 3] = wdot;
                 }
-                __syncthreads();
-                if (wave == 0) {
+                if (cross_wave_last<CFG>(epi, lane, wave)) {
                     // comparison (Sec. 2.4 step 4) for this tile: its output summation against the
                     // sum of the partial checksum dot products the activation-checksum kernel left
                     double ts = 0.0, tf = 0.0, tl = 0.0, sab = 0.0;

@@ -48,7 +48,7 @@ constexpr CfgInfo cfg_info() {
     constexpr int ns = CfgOf<DT_F16, ID>::NSTAGE;
     constexpr int kw = CfgOf<DT_F16, ID>::KWAYS;
     constexpr int lds = cfg_is_stream(ID) ? kw * ns * ((C::BM + C::BN) * 128 + 768)
-                                          : (ns ? ns * ((C::BM + C::BN) * 128 + 1024) : C::LDS_BYTES);
+                                          : (ns ? ns * ((C::BM + C::BN) * 128 + 1024) + 512 : C::LDS_BYTES);
     return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, lds, ns ? 1 : 0, kw, cfg_is_stream(ID) ? 128 : 32};
 }
 

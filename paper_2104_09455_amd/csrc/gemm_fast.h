@@ -59,13 +59,16 @@ struct FastLayout {
     // the workgroup's column block (1 KB, copied by wavefront 0 like one more group of eight rows of B)
     static constexpr int BETA_REC = 1024;
     static constexpr int STAGE = AB_STAGE + BETA_REC;
-    static constexpr int LDS_BYTES = NSTAGE * STAGE;
+    // global scheme: 512 bytes behind everything else for the cross-wavefront sums of the epilogue
+    // (never aliased with a stage, so that the epilogue waits for no other wavefront)
+    static constexpr int EPI_BYTES = 512;
+    static constexpr int LDS_BYTES = NSTAGE * STAGE + EPI_BYTES;
     // Activation checksums handed over by the layer before travel in runs of 256 floats, four k
     // tiles at a time, through a ring of two 1 KB slots per wavefront (its 32-row block's sums) behind the stages
     // and, with them, 256 floats of the column block's weight checksums through one such ring for the
     // workgroup (a quarter of the copies that a record per k tile would take)
     static constexpr int RING_A = NSTAGE * STAGE, RING_B = RING_A + WAVES * 2048;
-    static constexpr int LDS_BYTES_FED = RING_B + 2048;
+    static constexpr int LDS_BYTES_FED = RING_B + 2048 + EPI_BYTES;
     static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
@@ -109,6 +112,12 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     const int bm0 = tile_m * BM, bn0 = tile_n * BN;
     const int M = p.M, N = p.N;
     const int nkt = p.K / BK;
+    // scratch of the global scheme's epilogue: behind the stages this launch asked for (a k loop
+    // shorter than the pipeline gets no more) or behind the rings of the handed-over sums
+    char* const epi = smem + (FED ? LAY::RING_B + 2048 : (nkt < NSTAGE ? (nkt < 1 ? 1 : nkt) : NSTAGE) * STAGE);
+    if constexpr (EMODE == MODE_GLOBAL) {
+        if (tid == 0) *reinterpret_cast<unsigned*>(epi + 256) = 0u;  // the ticket counter; the barrier after the prologue publishes it
+    }
 
     // ---- global -> LDS copy: this lane always fills LDS slot `lane` of a 1 KB block
     // (8 rows x 8 chunks): row lane/8, position lane%8, which holds chunk (lane%8) ^ key(row)
@@ -439,7 +448,6 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         // a fault in the finished accumulator
         if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
     }
-    __syncthreads();  // the epilogue reuses LDS
     if constexpr (FED) dot.total += (double)fed_a * (double)fed_b;  // the last tile's
     if constexpr (MDOT) {
         // this lane's share of the dot product: even columns hold A . (first piece), odd columns
@@ -459,7 +467,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             dot.total = g * ((gcol & 1) ? 1.0 / 2048.0 : 1.0);
         }
     }
-    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, (GDOT || FED) ? &dot.total : nullptr);
+    epilogue<CFG, EMODE>(acc, chk, p, tile_m, tile_n, smem, true, -1, (GDOT || FED) ? &dot.total : nullptr, epi);
 }
 
 }  // namespace abft

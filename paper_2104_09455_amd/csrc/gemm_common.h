@@ -1033,6 +1033,46 @@ __device__ __forceinline__ void epilogue(typename Mma<CFG::DT, CFG::MI>::Acc (&a
                 }
         }
     }
+    if constexpr (CFG::CSIZE == 2 && MI == 16 && TM % 2 == 0) {
+        // (16x16 shapes, direct-to-LDS kernel: a lane holds 4 rows of one column of each block; two
+        // block rows make a 32-row block, the lanes 16, 32 and 48 further on hold its other rows)
+        if (p.alpha_out) {
+#pragma unroll
+            for (int i = 0; i < TM; i += 2)
+#pragma unroll
+                for (int j = 0; j < TN; ++j) {
+                    float cs = 0.f;
+#pragma unroll
+                    for (int ii = i; ii < i + 2; ++ii)
+#pragma unroll
+                        for (int r = 0; r < MMA::NACC; r += 2) {
+                            const int pk = pack_out16<CFG::DT>(acc[ii][j][r], acc[ii][j][r + 1]);
+                            cs = mul_add_half<CFG::DT, 0>(pk, 1.0f, cs);
+                            cs = mul_add_half<CFG::DT, 1>(pk, 1.0f, cs);
+                        }
+                    cs += __shfl_xor(cs, 16);
+                    cs += __shfl_xor(cs, 32);
+                    const int col = acc_col(j);
+                    const int blk = (tc.bm0 + tc.wave_m * CFG::WM) / 32 + i / 2;
+                    if (lane < 16 && col < N && blk * 32 < M) p.alpha_out[(long long)blk * p.ld_alpha_out + col] = cs;
+                }
+        }
+        // wavefront tiles that lie wholly inside C: 8-byte stores of four columns per lane
+        const int wrow0 = tc.bm0 + tc.wave_m * CFG::WM, wcol0 = tc.bn0 + tc.wave_n * CFG::WN;
+        const bool whole = wrow0 + CFG::WM <= M && wcol0 + CFG::WN <= N && (p.ldc & 3) == 0 &&
+                           (reinterpret_cast<uintptr_t>(p.C) & 7u) == 0;
+        if (whole) {
+            const long long ldcb = p.ldc * 2;
+            char* base = p.C + ((long long)(wrow0 + 4 * tc.lgrp + (lane & 3)) * p.ldc + wcol0 + (tc.lrow & ~3)) * 2;
+#pragma unroll
+            for (int i = 0; i < TM; ++i)
+#pragma unroll
+                for (int j = 0; j < TN; ++j)
+                    store_quad_rows<CFG::DT>(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3],
+                                             base + (i * 16) * ldcb + j * 32, lane);
+            return;
+        }
+    }
     // ---- store C (rounded to the output type)
     if constexpr (CFG::CSIZE == 2 && MI == 32) {
         // wavefront tiles that lie wholly inside C: 8-byte stores of four columns per lane

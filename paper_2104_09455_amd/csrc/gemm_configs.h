@@ -26,7 +26,7 @@ struct CfgOf;
 template <int DT> struct CfgOf<DT, CFG_F128>  { typedef Cfg<DT, 32, 2, 2, 2, 2, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F128T> { typedef Cfg<DT, 32, 1, 4, 4, 1, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F64T>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 1; };
-template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 32, 4, 2, 2, 4, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 16, 8, 4, 2, 4, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_S32>   { typedef Cfg<DT, 32, 1, 1, 1, 1, 128> type; static constexpr int NSTAGE = 4; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_S64>   { typedef Cfg<DT, 32, 1, 2, 1, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_S128>  { typedef Cfg<DT, 32, 2, 2, 1, 1, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 4; };

@@ -72,7 +72,7 @@ struct FastLayout {
     static constexpr int NQA = CFG::BM / (8 * WAVES);           // 1 KB copies per wave per k tile
     static constexpr int NQB = CFG::BN / (8 * WAVES);
     static_assert(CFG::BM % (8 * WAVES) == 0 && CFG::BN % (8 * WAVES) == 0, "tile rows vs waves");
-    static_assert(CFG::MI == 32 && CFG::BKB == 128, "32x32 MFMA shapes, 128-byte k tile");
+    static_assert((CFG::MI == 32 || CFG::MI == 16) && CFG::BKB == 128, "32x32 or 16x16 MFMA shapes, 128-byte k tile");
     static_assert((NSTAGE - 2) * (NQA + NQB) <= 63, "vmcnt range");
 };
 
@@ -80,7 +80,8 @@ template <class CFG, int NSTAGE, int MODE, bool INJ, bool CONV>
 __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs p) {
     typedef FastLayout<CFG, NSTAGE> LAY;
     constexpr int DT = CFG::DT;
-    typedef Mma<DT, 32> MMA;
+    constexpr int MI = CFG::MI;
+    typedef Mma<DT, MI> MMA;
     typedef typename MMA::Acc Acc;
     constexpr int TM = CFG::TM, TN = CFG::TN, BM = CFG::BM, BN = CFG::BN, BKB = 128;
     constexpr int ESIZE = CFG::ESIZE, BK = CFG::BK;
@@ -256,22 +257,24 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
 #pragma unroll
         for (int j = 0; j < TN; ++j)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+            for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = 0;
     constexpr int NCHK = CheckRegs<CFG, MODE>::N;
     Acc chk[NCHK];
 #pragma unroll
     for (int i = 0; i < NCHK; ++i)
 #pragma unroll
-        for (int r = 0; r < 16; ++r) chk[i][r] = 0;
+        for (int r = 0; r < MMA::NACC; ++r) chk[i][r] = 0;
 
     // ---- fragment reads: lane l reads row l%32 of a 32-row block, k chunk 2*kk + l/32,
     // stored at position chunk ^ ((row >> 1) & 7), which is (l >> 1) & 7 for every block
-    const int frow = lane & 31, fgrp = lane >> 5, fx = (lane >> 1) & 7;
+    // (16x16 shapes: row l%16 of a 16-row block, k chunk 4*step + l/16 of the two 64-byte k steps;
+    // the key of a row is still (l >> 1) & 7: blocks start at multiples of 16 rows)
+    const int frow = lane & (MI - 1), fgrp = lane / MI, fx = (lane >> 1) & 7;
     const int a_off = (wave_m * CFG::WM + frow) * ROWB;
     const int b_off = A_STAGE + (wave_n * CFG::WN + frow) * ROWB;
     int pos[4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) pos[kk] = ((2 * kk + fgrp) ^ fx) * 16;
+    for (int kk = 0; kk < 4; ++kk) pos[kk] = MI == 32 ? ((2 * kk + fgrp) ^ fx) * 16 : ((4 * (kk & 1) + fgrp) ^ fx) * 16;
 
     // fragments of one k step: double buffered so that the reads of step kk+1 run under
     // the MFMAs of step kk
@@ -328,17 +331,17 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     };
     Acc gchk;
 #pragma unroll
-    for (int r = 0; r < 16; ++r) gchk[r] = 0;
+    for (int r = 0; r < MMA::NACC; ++r) gchk[r] = 0;
     i32x4 fa[2][TM], fb[2][TN];
     auto read_frags = [&](const char* st, int kk, int buf) {
         const int ps = pos[kk];
 
 #pragma unroll
         for (int i = 0; i < TM; ++i)
-            fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * 32 * ROWB + ps);
+            fa[buf][i] = *reinterpret_cast<const i32x4*>(st + a_off + i * MI * ROWB + ps);
 #pragma unroll
         for (int j = 0; j < TN; ++j)
-            fb[buf][j] = *reinterpret_cast<const i32x4*>(st + b_off + j * 32 * ROWB + ps);
+            fb[buf][j] = *reinterpret_cast<const i32x4*>(st + b_off + j * MI * ROWB + ps);
     };
     auto mma_step = [&](int buf, const i32x4& fg) {
 #pragma unroll
@@ -440,10 +443,71 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
         }
     };
+    // 16x16x32 shapes (two k steps of 64 bytes per tile; at the power limit the chip sustains about an
+    // eighth more of them per second than of the 32x32x16 ones): hand-placed.  A block row i of A is
+    // multiplied with the TN blocks of B, then its fragment is read again in place for the step
+    // after (only the B fragments are double buffered: 8 + 2 x 4 fragment registers instead of
+    // 2 x 12); the vector work of the in-loop dot product goes behind the first block rows of step 0.
+    // The barrier sits between the two steps, as in the 32x32 form.
+    auto tile_step16 = [&](int kt) {
+        const char* st = smem + stage * STAGE;
+        fed_tile(st, kt);
+        i32x4 b0 = {0, 0, 0, 0}, b1 = {0, 0, 0, 0};
+        if constexpr (VDOT) {
+            b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
+            b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
+        }
+        auto half = [&](const char* src, int ps, int cur, bool dots) {
+#pragma unroll
+            for (int i = 0; i < TM; ++i) {
+#pragma unroll
+                for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[0][i], fb[cur][j], acc[i][j]);
+                __builtin_amdgcn_sched_barrier(0);  // (the read below must not move above the MFMAs: it reuses their register)
+                fa[0][i] = *reinterpret_cast<const i32x4*>(src + a_off + i * MI * ROWB + ps);
+                if (i < TN) fb[cur ^ 1][i] = *reinterpret_cast<const i32x4*>(src + b_off + i * MI * ROWB + ps);
+                if constexpr (VDOT) {
+                    // (a piece behind every second block row, so that the other wavefront of the SIMD finds
+                    // room for its MFMAs in between)
+                    if (dots && i % 2 == 0 && i / 2 < NQA)
+                        dot.chunk(*reinterpret_cast<const i32x4*>(st + ((i / 2) * WAVES + wave) * 1024 + lane * 16), b0, b1, i / 2);
+                    if (dots && i == TM - 1) dot.flush();
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        };
+        static_assert(MI == 32 || (TM >= TN && TM >= 2 * LAY::NQA), "placement of the reads and of the dot product's pieces");
+        half(st, pos[1], 0, true);
+        const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
+        const char* src = st;  // (last tile: the reads of the second step fetch nothing that is used)
+        if (kt + 1 < nkt) {
+            if (kt + NSTAGE < nkt) __builtin_amdgcn_s_waitcnt(waitcnt_vm((NSTAGE - 2) * NL) & ~0x0F00);
+            else __builtin_amdgcn_s_waitcnt(0x0070);  // tail: vmcnt(0) lgkmcnt(0)
+            __syncthreads();
+            if (kt + NSTAGE < nkt) {
+                advance();
+                issue_loads(stage);
+            }
+            src = smem + next * STAGE;
+        }
+        half(src, pos[0], 1, false);
+        stage = next;
+        if constexpr (INJ) {
+            if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
+        }
+    };
+    if constexpr (MI == 16) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const i32x4*>(smem + a_off + i * MI * ROWB + pos[0]);
+#pragma unroll
+        for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const i32x4*>(smem + b_off + j * MI * ROWB + pos[0]);
+#pragma nounroll
+        for (int kt = 0; kt < nkt; ++kt) tile_step16(kt);
+    } else {
     read_frags(smem, 0, 0);
     read_checksum_frag(smem);
     // the last of the four k steps sits in buffer 1
     for (int kt = 0; kt < nkt; ++kt) tile_step(kt, std::integral_constant<int, 1>());
+    }
     if constexpr (INJ) {
         // a fault in the finished accumulator
         if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
@@ -455,7 +519,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         if constexpr (IS_INT) {
             int g_lo = 0, g_hi = 0;
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
+            for (int r = 0; r < MMA::NACC; ++r) {
                 g_lo += gchk[r] & 0xffff;
                 g_hi += gchk[r] >> 16;
             }
@@ -463,7 +527,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         } else {
             double g = 0.0;
 #pragma unroll
-            for (int r = 0; r < 16; r += 4) g += (double)((gchk[r] + gchk[r + 1]) + (gchk[r + 2] + gchk[r + 3]));
+            for (int r = 0; r < MMA::NACC; r += 4) g += (double)((gchk[r] + gchk[r + 1]) + (gchk[r + 2] + gchk[r + 3]));
             dot.total = g * ((gcol & 1) ? 1.0 / 2048.0 : 1.0);
         }
     }

@@ -6,7 +6,9 @@ namespace abft {
 
 // Index into the configuration table.
 //  F* run the direct-to-LDS kernel (16-byte aligned operands and leading dimensions, K a multiple of 128 bytes):
-//    F256W  256 x 256, wavefronts 2 x 4 of 128 x  64 (two per SIMD), 2 LDS stages   compute-bound products
+//    F256W  256 x 256, wavefronts 2 x 4 of 128 x  64 (two per SIMD), 2 LDS stages   compute-bound products;
+//                                                                    16x16x32 MFMA shapes (the others 32x32x16): no
+//                                                                    wavefront-level scheme runs on it
 //    F128   128 x 128, wavefronts 2 x 2 of  64 x  64, 2 stages       mid-size, unprotected / global
 //    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       thread-level (wide tiles: two checksum
 //                                                                    MFMAs per four), narrow outputs, K of one k tile

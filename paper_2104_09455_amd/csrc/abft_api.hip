@@ -107,7 +107,8 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     const bool fast_ok = aligned16 && ((long long)K * esize(dt)) % 128 == 0;
     const bool force_fits = force >= 0 && force < CFG_COUNT &&
                             (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force)));
-    if (force_fits) return force;
+    // (the 256 x 256 tile carries no wavefront-level scheme: a forced choice of it does not apply to those)
+    if (force_fits && !(force == CFG_F256W && mode == ABFT_THREAD)) return force;
     if (M <= 16 && !aligned16) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);

@@ -316,3 +316,90 @@ def test_run_all_chains_layers_by_their_buffers():
         ch.check(x)
     finally:
         ch.close()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_handover_between_layers_on_the_256x256_tile(dtype):
+    """Two 4096 x 4096 x 4096 layers: 256 workgroup tiles of 256 x 256 each, the tile whose
+    accumulators have the 16 x 16 layout.  Layer 0's epilogue forms the column sums from that layout,
+    layer 1 takes them.  Sampled rows of both layers against the oracle on the input the device's
+    layer read, the device's worst region against the oracle's check of that region, the same C bit
+    for bit as the layers run one by one, and a seeded fault in the layer that takes the sums."""
+    import torch
+    from gpu_util import read_report, c_to_host, c_close, sample_rows
+    M, widths = 4096, [4096, 4096, 4096]
+    ch = Chain(M, widths, dtype, seed=1900, modes=[B.GLOBAL] * 2)
+    try:
+        reps = _reports(ch)
+        x, dx = ch.input(seed=1901)
+        before = B.abft_handover_launches()
+        print(f"case handover on 256x256 tiles M={M} widths={widths} dtype={dtype}", flush=True)
+        ch.run(dx)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == 1
+        assert int(ch.flag.item()) == 0
+        chained = [c.clone() for c in ch.Cs]
+        got = [read_report(r) for r in reps]
+        rows = sample_rows(M, 24, band=256, seed=1902)
+        a_in = x
+        for l in range(ch.nl):
+            K, N = widths[l], widths[l + 1]
+            bm, bn = B.abft_region_shape(M, N, K, DT[dtype], True)
+            assert (bm, bn) == (256, 256)
+            ref = oracle.activation(oracle.gemm_rows(a_in, ch.Ws[l], dtype, rows), ch.acts[l])
+            assert c_close(c_to_host(ch.Cs[l], dtype)[rows], ref, dtype), l
+            assert got[l].tiles == (M // bm) * (N // bn), l
+            _, chk, _ = _region(ch, l, a_in, got[l].region)
+            assert not chk.flag
+            assert abs(got[l].lhs - chk.lhs) <= chk.tau, l
+            assert abs(got[l].rhs - chk.rhs) <= 0.1 * chk.tau, l
+            assert got[l].tau == pytest.approx(chk.tau, rel=1e-3)
+            assert got[l].worst_ratio < 0.5, (l, got[l].worst_ratio)
+            a_in = _storage(ch.Cs[l], dtype)
+        # one by one: each layer forms its activation checksums itself
+        for r in reps:
+            r.zero_()
+        for l in range(ch.nl):
+            a = dx if l == 0 else ch.Cs[l - 1]
+            B.abft_plan_run(ch.plan, l, a, widths[l], ch.Cs[l], widths[l + 1], ch.flag)
+        torch.cuda.synchronize()
+        assert B.abft_handover_launches() - before == 1
+        assert int(ch.flag.item()) == 0
+        for l in range(ch.nl):
+            assert torch.equal(ch.Cs[l], chained[l]), l
+        # single-bit flips in finished accumulators of layer 1: the verdict equals the oracle's
+        # outside the don't-care band around the region's tolerance
+        clean = got[1]
+        resid0 = clean.tau * clean.worst_ratio
+        a1 = _storage(chained[0], dtype)
+        K, N = widths[1], widths[2]
+        must = mustnot = 0
+        for t, (i, j, bit) in enumerate(((1234, 2345, 30), (17, 4000, 28), (4095, 0, 30), (2048, 255, 2), (300, 3000, 5), (777, 1777, 26))):
+            print(f"case handover fault on 256x256 tiles dtype={dtype} ({i},{j}) bit {bit}", flush=True)
+            ch.flag.zero_()
+            B.abft_plan_set_diagnostics(ch.plan, 1, report=reps[1], inject=B.Fault(i, j, bit, -1))
+            ch.run(dx)
+            torch.cuda.synchronize()
+            flag = int(ch.flag.item())
+            good = oracle.partial_dot(a1[i:i + 1], np.ascontiguousarray(ch.Ws[1][:, j:j + 1]), dtype, 0, 0, 0, K)
+            bad = oracle.flip_bit(good, bit, dtype)
+            if not math.isfinite(bad):
+                assert flag == 1
+                must += 1
+                continue
+            r0, c0 = i // 256 * 256, j // 256 * 256
+            blk = oracle.gemm(a1[r0:r0 + 256], np.ascontiguousarray(ch.Ws[1][:, c0:c0 + 256]), dtype)
+            cl = float(blk[i - r0, j - c0])
+            tau = oracle.tolerance(K, math.sqrt(max(oracle.frob(blk) ** 2 - cl * cl + bad * bad, 0.0)), dtype, scheme=1,
+                                   l1_norm=oracle.l1norm(blk) - abs(cl) + abs(bad))
+            delta = abs(bad - good)
+            if delta >= 2 * tau + resid0:
+                assert flag == 1, (i, j, bit, delta, tau)
+                must += 1
+            elif delta <= tau / 2 - resid0:
+                assert flag == 0, (i, j, bit, delta, tau)
+                mustnot += 1
+        assert must > 0 and mustnot > 0
+    finally:
+        B.abft_plan_set_diagnostics(ch.plan, 1)
+        ch.close()

@@ -161,19 +161,20 @@ def test_fault_campaign_wave_level(n, dtype, trials, mode):
     _campaign(n, dtype, mode, trials, seed=79 + n)
 
 
-def test_ragged_large_uses_the_big_tile_and_matches():
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_ragged_large_uses_the_big_tile_and_matches(dtype):
     """M, N not multiples of the 256-wide tile: edge tiles read zeros, results and checksums
     are unaffected.  4000 x 3900 x 512 runs on the large-tile kernel (16 x 16 tiles: one full round of workgroups)."""
     from gpu_util import c_to_host, c_close
     M, N, K = 4000, 3900, 512
-    big = Big(M, N, K, "f16", seed=5)
+    big = Big(M, N, K, dtype, seed=5)
     assert (big.rm, big.rn) == (256, 256)
     rows = np.array([0, 255, 256, 3839, 3840, 3999])
-    ref = oracle.gemm_rows(big.A, big.Bm, "f16", rows)
+    ref = oracle.gemm_rows(big.A, big.Bm, dtype, rows)
     for mode in (B.NONE, B.GLOBAL, B.THREAD):
-        print(f"case ragged mode={mode}", flush=True)
+        print(f"case ragged mode={mode} dtype={dtype}", flush=True)
         flag, rep = big.run(mode)
-        assert c_close(c_to_host(big.dC[rows.tolist()], "f16"), ref, "f16")
+        assert c_close(c_to_host(big.dC[rows.tolist()], dtype), ref, dtype)
         assert flag == 0
         if mode == B.GLOBAL:
             assert rep.tiles == 16 * 16 and rep.worst_ratio < 0.5
@@ -181,10 +182,13 @@ def test_ragged_large_uses_the_big_tile_and_matches():
             r = rep.region - 1
             r0, c0 = (r // 16) * 256, (r % 16) * 256
             chk = oracle.region_check(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]),
-                                      oracle.gemm(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]), "f16"),
-                                      "f16", 0, min(256, M - r0), 0, min(256, N - c0))
-            assert abs(rep.rhs - chk.rhs) <= 0.1 * chk.tau + 1e-9
-            assert rep.tau == pytest.approx(chk.tau, rel=1e-3)
+                                      oracle.gemm(big.A[r0:r0 + 256], np.ascontiguousarray(big.Bm[:, c0:c0 + 256]), dtype),
+                                      dtype, 0, min(256, M - r0), 0, min(256, N - c0))
+            if dtype == "i8":
+                assert rep.rhs == chk.rhs and rep.lhs == chk.lhs
+            else:
+                assert abs(rep.rhs - chk.rhs) <= 0.1 * chk.tau + 1e-9
+                assert rep.tau == pytest.approx(chk.tau, rel=1e-3)
     # injected fault in the last (clipped) tile row / column is still seen
     for mode in (B.GLOBAL, B.THREAD):
         flag, _ = big.run(mode, inject=B.Fault(3999, 3899, 29, -1))

@@ -295,12 +295,44 @@ def measured_ceilings(hip, gen):
            "measured_cmr_fp16": round(tf * 1e12 / (copy_gbps * 1e9), 1),
            "spec_cmr_fp16": round(PEAK["f16"] / HBM, 1)}
     try:
+        out["mfma_from_registers_TFLOPs"] = mfma_shapes_leg()
+    except Exception as e:
+        out["mfma_from_registers_TFLOPs"] = {"error": repr(e)}
+    try:
         out["sustained_clock_and_library_context"] = clock_context(lr)
     except Exception as e:  # (no rocm-smi, no permission: context only)
         out["sustained_clock_and_library_context"] = {"error": repr(e)}
     del lr
     torch.cuda.empty_cache()
     return out
+
+
+def mfma_shapes_leg(secs=1.0):
+    """What the matrix units sustain from registers alone (abft_mfma_probe: no memory traffic at all),
+    per MFMA shape, on random fp16 operands and on zeros: the measurement behind the 16x16x32 shapes
+    of the 256 x 256 tile.  Under the board's power limit the rate depends on the operands' values."""
+    nbytes = B.abft_mfma_probe_bytes()
+    sink = torch.zeros(1, dtype=torch.float32, device="cuda:0")
+    res = {}
+    for dist in ("random", "zeros"):
+        ops_t = (torch.rand(nbytes // 2, device="cuda:0") * 0.02 - 0.01).to(torch.float16) if dist == "random" \
+            else torch.zeros(nbytes // 2, dtype=torch.float16, device="cuda:0")
+        for shape in (32, 16):
+            iters = 20000
+            B.abft_mfma_probe(shape, B.F16, 200, ops_t, sink)
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            rate = 0.0
+            while time.perf_counter() - t0 < secs:       # (the last batch: the clock has settled by then)
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                ops = sum(B.abft_mfma_probe(shape, B.F16, iters, ops_t, sink) for _ in range(10))
+                e1.record()
+                torch.cuda.synchronize()
+                rate = ops / (e0.elapsed_time(e1) * 1e-3) / 1e12
+            res[f"{'32x32x16' if shape == 32 else '16x16x32'}_{dist}"] = round(rate, 1)
+        del ops_t
+    return res
 
 
 def clock_context(lr, secs=1.5):

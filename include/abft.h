@@ -412,6 +412,18 @@ int abft_version(void);
  * immediately before and after launching the matrix-product kernel itself (not the
  * checksum pre-pass or the comparison).  NULL, NULL switches it off. */
 void abft_set_kernel_events(void *start_event, void *stop_event);
+/* Measurement aid behind the choice of MFMA shape for the 256 x 256 tile (no part of the path, no
+ * passage of the paper): one launch of a kernel that only multiplies, from registers -- one
+ * workgroup of 8 wavefronts per compute unit, each wavefront `iters` times over the 128 x 64 register
+ * tile with MFMAs of `shape` x `shape` (32: 32x32x16, 16: 16x16x32; fp16 / bf16, int8 with twice
+ * the depth).  `operands` (device) supplies the fragments: at least abft_mfma_probe_bytes() bytes
+ * of values of `dtype`; what they hold decides how far the board's power limit lets the clock go.
+ * *ops (host) receives the multiply-adds x 2 of the launch.  `sink` (device, 4 bytes) is written
+ * only in a case that does not occur (it keeps the work alive).  Errors: ABFT_E_ENUM for an unknown
+ * shape or dtype, ABFT_E_NULL, ABFT_E_SHAPE for iters < 1, ABFT_E_HIP. */
+size_t abft_mfma_probe_bytes(void);
+int abft_mfma_probe(int shape, int dtype, int iters, const void *operands /* device */,
+                    float *sink /* device */, double *ops /* host */, void *stream);
 
 #ifdef __cplusplus
 }

@@ -60,7 +60,7 @@ EXPORTS = [
     "abft_plan_run_all", "abft_plan_set_mode", "abft_k_ways", "abft_beta_bytes", "abft_conv_workspace_bytes",
     "abft_plan_set_activation", "abft_plan_activation", "abft_gemm_static", "abft_static_scratch_bytes",
     "abft_tolerance_half_coeff", "abft_plan_run_chain", "abft_plan_chain_status", "abft_plan_chain_reset",
-    "abft_plan_set_diagnostics", "abft_handover_launches",
+    "abft_plan_set_diagnostics", "abft_handover_launches", "abft_mfma_probe", "abft_mfma_probe_bytes",
 ]
 
 _lib = None
@@ -130,6 +130,11 @@ def lib() -> ctypes.CDLL:
     L.abft_plan_chain_reset.argtypes = [vp, ci, vp]
     L.abft_handover_launches.restype = ctypes.c_longlong
     L.abft_handover_launches.argtypes = []
+    L.abft_mfma_probe_bytes.restype = ctypes.c_size_t
+    L.abft_mfma_probe_bytes.argtypes = []
+    L.abft_mfma_probe.restype = ctypes.c_int
+    L.abft_mfma_probe.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p,
+                                  ctypes.POINTER(ctypes.c_double), ctypes.c_void_p]
     L.abft_plan_set_diagnostics.restype = ci
     L.abft_plan_set_diagnostics.argtypes = [vp, ci, vp, ctypes.POINTER(Fault)]
     L.abft_plan_set_mode.restype = ci
@@ -349,6 +354,17 @@ def abft_plan_chain_reset(plan, spin_limit=-1, stream=None) -> None:
 
 def abft_handover_launches() -> int:
     return int(lib().abft_handover_launches())
+
+
+def abft_mfma_probe_bytes() -> int:
+    return int(lib().abft_mfma_probe_bytes())
+
+
+def abft_mfma_probe(shape: int, dtype: int, iters: int, operands, sink, stream=None) -> float:
+    """One launch of the registers-only MFMA kernel; returns the operations (2 x multiply-adds) it did."""
+    ops = ctypes.c_double(0.0)
+    _check(lib().abft_mfma_probe(shape, dtype, iters, _ptr(operands), _ptr(sink), ctypes.byref(ops), stream))
+    return ops.value
 
 
 def abft_plan_set_diagnostics(plan, layer, report=None, inject: Optional[Fault] = None) -> None:

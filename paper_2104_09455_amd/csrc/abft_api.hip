@@ -1607,6 +1607,84 @@ const char* abft_strerror(int code) {
 
 int abft_version(void) { return 100; }
 
+}  // extern "C"
+
+namespace {
+// MFMAs from registers only: each wavefront keeps the fragments of a 128 x 64 register tile
+// (TM + TN fragments of 16 bytes per lane) and multiplies them `iters` times into its TM x TN
+// accumulator blocks.  Nothing else runs, so the rate is what the matrix units sustain for these
+// operand values under the board's power limit.
+template <int DT, int MI>
+__global__ __launch_bounds__(512) void mfma_probe_kernel(const i32x4* src, float* sink, int iters) {
+    typedef abft::Mma<DT, MI> MMA;
+    constexpr int TM = 128 / MI, TN = 64 / MI;
+    const long long t = (long long)blockIdx.x * 512 + threadIdx.x;
+    i32x4 a[TM], b[TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i) a[i] = src[t * 16 + i];
+#pragma unroll
+    for (int j = 0; j < TN; ++j) b[j] = src[t * 16 + TM + j];
+    typename MMA::Acc acc[TM][TN];
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < MMA::NACC; ++r) acc[i][j][r] = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(a[i], b[j], acc[i][j]);
+    }
+    typename MMA::AccT total = 0;
+#pragma unroll
+    for (int i = 0; i < TM; ++i)
+#pragma unroll
+        for (int j = 0; j < TN; ++j)
+#pragma unroll
+            for (int r = 0; r < MMA::NACC; ++r) total += acc[i][j][r];
+    // (no finite sum of these products has this bit pattern's value twice over: never taken)
+    if ((float)total == 12345.678f && iters < 0) sink[0] = (float)total;
+}
+
+int probe_cus() {
+    int dev = 0, n = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return n;
+}
+}  // namespace
+
+extern "C" {
+
+size_t abft_mfma_probe_bytes(void) {
+    const int cus = probe_cus();
+    return (size_t)(cus > 0 ? cus : 256) * 512 * 16 * sizeof(i32x4);
+}
+
+int abft_mfma_probe(int shape, int dtype, int iters, const void* operands, float* sink, double* ops, void* stream) {
+    if (!valid_dtype(dtype) || (shape != 32 && shape != 16)) return ABFT_E_ENUM;
+    if (!operands || !sink || !ops) return ABFT_E_NULL;
+    if (iters < 1) return ABFT_E_SHAPE;
+    const int cus = probe_cus();
+    if (cus <= 0) return ABFT_E_HIP;
+    hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+    const i32x4* src = reinterpret_cast<const i32x4*>(operands);
+    dim3 grid((unsigned)cus), block(512);
+    void (*kern)(const i32x4*, float*, int) = nullptr;
+    if (dtype == ABFT_F16) kern = shape == 32 ? mfma_probe_kernel<abft::DT_F16, 32> : mfma_probe_kernel<abft::DT_F16, 16>;
+    else if (dtype == ABFT_BF16) kern = shape == 32 ? mfma_probe_kernel<abft::DT_BF16, 32> : mfma_probe_kernel<abft::DT_BF16, 16>;
+    else kern = shape == 32 ? mfma_probe_kernel<abft::DT_I8, 32> : mfma_probe_kernel<abft::DT_I8, 16>;
+    hipLaunchKernelGGL(kern, grid, block, 0, st, src, sink, iters);
+    if (hipGetLastError() != hipSuccess) return ABFT_E_HIP;
+    // per wavefront and iteration: 8 MFMAs of 32 x 32 x 16 (16384 multiply-adds each) or 32 of
+    // 16 x 16 x 32 (8192 each); int8 shapes are twice as deep
+    const double macs = (shape == 32 ? 8.0 * 16384.0 : 32.0 * 8192.0) * (dtype == ABFT_I8 ? 2.0 : 1.0);
+    *ops = (double)cus * 8.0 * (double)iters * macs * 2.0;
+    return ABFT_OK;
+}
+
 void abft_set_kernel_events(void* start_event, void* stop_event) {
     g_ev_start = reinterpret_cast<hipEvent_t>(start_event);
     g_ev_stop = reinterpret_cast<hipEvent_t>(stop_event);

@@ -127,6 +127,13 @@ def test_argument_validation_without_a_gpu(lib):
     assert lib.abft_plan_set_diagnostics(None, 0, None, None) == -8
     assert lib.abft_plan_run_chain(None, 0, 1, p, 4, None, None, p, None) == -8
     assert lib.abft_handover_launches() == 0   # nothing has run in this process
+    # the measurement aid checks its arguments before it touches the device
+    ops = ctypes.c_double(0.0)
+    assert lib.abft_mfma_probe(24, 0, 10, p, p, ctypes.byref(ops), None) == -4
+    assert lib.abft_mfma_probe(16, 3, 10, p, p, ctypes.byref(ops), None) == -4
+    assert lib.abft_mfma_probe(16, 0, 10, None, p, ctypes.byref(ops), None) == -1
+    assert lib.abft_mfma_probe(32, 0, 0, p, p, ctypes.byref(ops), None) == -2
+    assert lib.abft_mfma_probe_bytes() % (512 * 256) == 0
     bad = B.Conv(1, 2, 2, 8, 3, 3, 1, 0)  # 3x3 filter on a 2x2 image without padding
     assert lib.abft_conv(ctypes.byref(bad), 4, p, p, 72, 0, p, 4, 0, 0, None, None, 0, p, None, None, None) == -2
 

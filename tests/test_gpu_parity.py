@@ -479,3 +479,21 @@ def test_weighted_global_scheme_is_refused_where_it_does_not_exist():
             B.abft_gemm(M, N, K, t, K, t, K, B.B_NK, t, N, dt, B.GLOBAL_WEIGHTED, workspace=ws,
                         workspace_bytes=ws.numel(), fault_flag=flag)
         assert e.value.code == -9
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+@pytest.mark.parametrize("shape", [32, 16])
+def test_mfma_probe_runs_and_counts_its_operations(shape, dtype):
+    """The measurement aid: launches, leaves its sink alone and reports the operations of one
+    launch: compute units x 8 wavefronts x iterations x the register tile's 128 x 64 x depth x 2."""
+    import torch
+    from gpu_util import DEV
+    dt = {"f16": B.F16, "bf16": B.BF16, "i8": B.I8}[dtype]
+    src = torch.zeros(B.abft_mfma_probe_bytes(), dtype=torch.uint8, device=DEV)
+    sink = torch.full((1,), 7.0, dtype=torch.float32, device=DEV)
+    ops = B.abft_mfma_probe(shape, dt, 50, src, sink)
+    torch.cuda.synchronize()
+    cus = torch.cuda.get_device_properties(0).multi_processor_count
+    depth = (16 if shape == 32 else 32) * (2 if dtype == "i8" else 1)
+    assert ops == cus * 8 * 50 * 128 * 64 * depth * 2
+    assert float(sink.item()) == 7.0

@@ -500,6 +500,8 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         for (int i = 0; i < TM; ++i) fa[0][i] = *reinterpret_cast<const i32x4*>(smem + a_off + i * MI * ROWB + pos[0]);
 #pragma unroll
         for (int j = 0; j < TN; ++j) fb[0][j] = *reinterpret_cast<const i32x4*>(smem + b_off + j * MI * ROWB + pos[0]);
+        // (not unrolled: the unrolled body of the handed-over form spills its copy pointers, and a
+        // reload of those waits, with everything else in flight, at the head of every tile)
 #pragma nounroll
         for (int kt = 0; kt < nkt; ++kt) tile_step16(kt);
     } else {

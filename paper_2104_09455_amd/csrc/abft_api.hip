@@ -715,9 +715,10 @@ bool fused_global(const Problem& pr, const CfgInfo& ci) {
     if (force) return force == 1;
     const double t_gemm = 2.0 * pr.M * pr.N * pr.K / (pr.dtype == ABFT_I8 ? 2.0e15 : 1.0e15);
     const double t_pre = 8.0e-6 + (double)pr.M * pr.K * esize(pr.dtype) / 4.5e12;
-    // (256 x 256 tile: the in-loop form is vector arithmetic on the A chunks for every type; bf16's
-    // three-piece products and int8's digit sums cost about a quarter of the loop, fp16 a tenth)
-    const double in_loop = (ci.bm == 256 && pr.dtype != ABFT_F16) ? 0.25 : 0.09;
+    // (256 x 256 tile, bf16: the in-loop form is vector arithmetic on the A chunks, three-piece
+    // products that cost about a quarter of the loop; the matrix-unit form of the other types a
+    // sixteenth more MFMAs)
+    const double in_loop = (ci.bm == 256 && pr.dtype == ABFT_BF16) ? 0.25 : 0.09;
     return in_loop * t_gemm < t_pre;
 }
 

@@ -92,9 +92,13 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // ... formed on the matrix unit (fp16, int8: the weight checksums, cut into two pieces that the
     // operand type holds, are two more columns of B) or with vector FMAs (bf16, which wants three
     // pieces; the 256 x 256 tile, which has no registers left for one more accumulator block)
-    constexpr bool MDOT = GDOT && DT != DT_BF16 && TM * TN <= 4;
-    constexpr bool VDOT = GDOT && !MDOT;
+    constexpr bool MDOT = GDOT && DT != DT_BF16 && CFG::MI == 32 && TM * TN <= 4;
+    // (16x16 shapes: the same with two block rows of A per wavefront and only the first two columns of
+    // the extra block of B in use: two more MFMAs per 32 and k step)
+    constexpr bool MDOT16 = GDOT && DT != DT_BF16 && CFG::MI == 16;
+    constexpr bool VDOT = GDOT && !MDOT && !MDOT16;
     static_assert(!MDOT || TM == CFG::WAVES_N, "one block row of the extra product per wavefront of a row of wavefronts");
+    static_assert(!MDOT16 || TM == 2 * CFG::WAVES_N, "two block rows of the extra product per wavefront of a row of wavefronts");
     // ... or reduced to one multiplication per lane and k tile because the layer before left the
     // column sums of this layer's A (per block of 32 rows: one block per wavefront here)
     constexpr bool FED = MODE == MODE_GLOBAL_FED;
@@ -457,11 +461,26 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
             b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
         }
+        // matrix-unit dot product: column 0 / 1 of the extra block of B is the first / second piece of
+        // the weight checksums (lane: column l % 16, the 16 bytes of k group l / 16 of the step); the
+        // fragments of both k steps are read here, before the barrier gives the stage away
+        i32x4 fg[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
+        if constexpr (MDOT16) {
+            const i32x4 z = {0, 0, 0, 0};
+            const char* rec = st + LAY::AB_STAGE + (lane & 1) * 128 + fgrp * 16;
+            const i32x4 r0 = *reinterpret_cast<const i32x4*>(rec), r1 = *reinterpret_cast<const i32x4*>(rec + 64);
+            fg[0] = (lane & 15) < 2 ? r0 : z;
+            fg[1] = (lane & 15) < 2 ? r1 : z;
+        }
         auto half = [&](const char* src, int ps, int cur, bool dots) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[0][i], fb[cur][j], acc[i][j]);
+                if constexpr (MDOT16) {
+                    // (wavefront column c of a row of wavefronts takes block rows 2 c and 2 c + 1)
+                    if ((i >> 1) == wave_n) gchk = MMA::run(fa[0][i], fg[cur], gchk);
+                }
                 __builtin_amdgcn_sched_barrier(0);  // (the read below must not move above the MFMAs: it reuses their register)
                 fa[0][i] = *reinterpret_cast<const i32x4*>(src + a_off + i * MI * ROWB + ps);
                 if (i < TN) fb[cur ^ 1][i] = *reinterpret_cast<const i32x4*>(src + b_off + i * MI * ROWB + ps);
@@ -515,7 +534,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
     }
     if constexpr (FED) dot.total += (double)fed_a * (double)fed_b;  // the last tile's
-    if constexpr (MDOT) {
+    if constexpr (MDOT || MDOT16) {
         // this lane's share of the dot product: even columns hold A . (first piece), odd columns
         // A . (second piece), which carries a factor 2^11 (fp16) or stands for the digit of weight 256 (int8)
         if constexpr (IS_INT) {

@@ -93,9 +93,9 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // operand type holds, are two more columns of B) or with vector FMAs (bf16, which wants three
     // pieces; the 256 x 256 tile, which has no registers left for one more accumulator block)
     constexpr bool MDOT = GDOT && DT != DT_BF16 && CFG::MI == 32 && TM * TN <= 4;
-    // (16x16 shapes: the same with two block rows of A per wavefront and only the first two columns of
-    // the extra block of B in use: two more MFMAs per 32 and k step)
-    constexpr bool MDOT16 = GDOT && DT != DT_BF16 && CFG::MI == 16;
+    // (16x16 shapes: the same with two block rows of A per wavefront and only the first two (bf16:
+    // three) columns of the extra block of B in use: two more MFMAs per 32 and k step)
+    constexpr bool MDOT16 = GDOT && CFG::MI == 16;  // (bf16: three pieces, columns 0 to 2)
     constexpr bool VDOT = GDOT && !MDOT && !MDOT16;
     static_assert(!MDOT || TM == CFG::WAVES_N, "one block row of the extra product per wavefront of a row of wavefronts");
     static_assert(!MDOT16 || TM == 2 * CFG::WAVES_N, "two block rows of the extra product per wavefront of a row of wavefronts");
@@ -451,28 +451,25 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // eighth more of them per second than of the 32x32x16 ones): hand-placed.  A block row i of A is
     // multiplied with the TN blocks of B, then its fragment is read again in place for the step
     // after (only the B fragments are double buffered: 8 + 2 x 4 fragment registers instead of
-    // 2 x 12); the vector work of the in-loop dot product goes behind the first block rows of step 0.
-    // The barrier sits between the two steps, as in the 32x32 form.
+    // 2 x 12).  The barrier sits between the two steps, as in the 32x32 form.
     auto tile_step16 = [&](int kt) {
         const char* st = smem + stage * STAGE;
         fed_tile(st, kt);
-        i32x4 b0 = {0, 0, 0, 0}, b1 = {0, 0, 0, 0};
-        if constexpr (VDOT) {
-            b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
-            b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
-        }
+        static_assert(MI == 32 || !VDOT, "16x16 shapes: the in-loop dot product runs on the matrix unit");
         // matrix-unit dot product: column 0 / 1 of the extra block of B is the first / second piece of
         // the weight checksums (lane: column l % 16, the 16 bytes of k group l / 16 of the step); the
         // fragments of both k steps are read here, before the barrier gives the stage away
         i32x4 fg[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
         if constexpr (MDOT16) {
             const i32x4 z = {0, 0, 0, 0};
-            const char* rec = st + LAY::AB_STAGE + (lane & 1) * 128 + fgrp * 16;
+            constexpr int NPC = DT == DT_BF16 ? 3 : 2;  // pieces: at bytes 0 and 128 of the record, bf16's third at 512
+            const int pc = lane & 15;
+            const char* rec = st + LAY::AB_STAGE + (pc == 2 ? 512 : (pc & 1) * 128) + fgrp * 16;
             const i32x4 r0 = *reinterpret_cast<const i32x4*>(rec), r1 = *reinterpret_cast<const i32x4*>(rec + 64);
-            fg[0] = (lane & 15) < 2 ? r0 : z;
-            fg[1] = (lane & 15) < 2 ? r1 : z;
+            fg[0] = pc < NPC ? r0 : z;
+            fg[1] = pc < NPC ? r1 : z;
         }
-        auto half = [&](const char* src, int ps, int cur, bool dots) {
+        auto half = [&](const char* src, int ps, int cur) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -484,18 +481,11 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
                 __builtin_amdgcn_sched_barrier(0);  // (the read below must not move above the MFMAs: it reuses their register)
                 fa[0][i] = *reinterpret_cast<const i32x4*>(src + a_off + i * MI * ROWB + ps);
                 if (i < TN) fb[cur ^ 1][i] = *reinterpret_cast<const i32x4*>(src + b_off + i * MI * ROWB + ps);
-                if constexpr (VDOT) {
-                    // (a piece behind every second block row, so that the other wavefront of the SIMD finds
-                    // room for its MFMAs in between)
-                    if (dots && i % 2 == 0 && i / 2 < NQA)
-                        dot.chunk(*reinterpret_cast<const i32x4*>(st + ((i / 2) * WAVES + wave) * 1024 + lane * 16), b0, b1, i / 2);
-                    if (dots && i == TM - 1) dot.flush();
-                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        static_assert(MI == 32 || (TM >= TN && TM >= 2 * LAY::NQA), "placement of the reads and of the dot product's pieces");
-        half(st, pos[1], 0, true);
+        static_assert(MI == 32 || TM >= TN, "a read of B behind each of the first block rows");
+        half(st, pos[1], 0);
         const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
         const char* src = st;  // (last tile: the reads of the second step fetch nothing that is used)
         if (kt + 1 < nkt) {
@@ -508,7 +498,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             }
             src = smem + next * STAGE;
         }
-        half(src, pos[0], 1, false);
+        half(src, pos[0], 1);
         stage = next;
         if constexpr (INJ) {
             if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
@@ -534,7 +524,25 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
         if (p.f_kt < 0) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
     }
     if constexpr (FED) dot.total += (double)fed_a * (double)fed_b;  // the last tile's
-    if constexpr (MDOT || MDOT16) {
+    if constexpr (MDOT16) {
+        // this lane's share of the dot product: column c of the extra block holds A . (piece c), whose
+        // weight is 1, 2^-11 (fp16) / 2^-8 (bf16) / 256 (int8: the high digit), and bf16's third 2^-16
+        const int pc = lane & 15;
+        if constexpr (IS_INT) {
+            int g_lo = 0, g_hi = 0;
+#pragma unroll
+            for (int r = 0; r < MMA::NACC; ++r) {
+                g_lo += gchk[r] & 0xffff;
+                g_hi += gchk[r] >> 16;
+            }
+            dot.total = (((long long)g_hi << 16) + (long long)g_lo) * (pc == 1 ? 256 : 1);
+        } else {
+            const double g = (double)((gchk[0] + gchk[1]) + (gchk[2] + gchk[3]));
+            const double w1 = DT == DT_F16 ? 1.0 / 2048.0 : 1.0 / 256.0;
+            dot.total = g * (pc == 0 ? 1.0 : (pc == 1 ? w1 : 1.0 / 65536.0));
+        }
+    }
+    if constexpr (MDOT) {
         // this lane's share of the dot product: even columns hold A . (first piece), odd columns
         // A . (second piece), which carries a factor 2^11 (fp16) or stands for the digit of weight 256 (int8)
         if constexpr (IS_INT) {

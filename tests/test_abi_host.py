@@ -182,8 +182,12 @@ def test_tile_choice_for_few_tiles(lib):
     # more than 256 of those too: 64 x 64 streaming tiles, but only with a k loop of four tiles or more
     assert B.abft_region_shape(512, 4096, 4096, B.F16) == (64, 64)
     assert B.abft_region_shape(3136, 512, 128, B.F16) == (64, 128)
-    # the chip is full: 128 x 128, then 256 x 256
-    assert B.abft_region_shape(12544, 512, 1024, B.F16) == (128, 128)
+    # the chip is full: 128 x 128; about one 256 x 128 tile per compute unit with a long k loop: that tile
+    # (the thread-level scheme keeps wavefront tiles of 32-row blocks); then 256 x 256
+    assert B.abft_region_shape(12544, 768, 1024, B.F16) == (128, 128)
+    assert B.abft_region_shape(12544, 512, 1024, B.F16) == (256, 128)
+    assert B.abft_region_shape(12544, 512, 256, B.F16) == (128, 128)
+    assert B.abft_tile_shape(12544, 512, 1024, B.F16)[:2] in ((32, 128), (64, 64))
     assert B.abft_region_shape(8192, 8192, 8192, B.F16) == (256, 256)
     # streaming tiles split k over four wavefronts
     assert B.abft_k_ways(256, 1024, 1024, B.F16, B.THREAD)[0] == 4

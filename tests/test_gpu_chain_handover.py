@@ -319,15 +319,16 @@ def test_run_all_chains_layers_by_their_buffers():
 
 
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
-def test_handover_between_layers_on_the_256x256_tile(dtype):
-    """Two 4096 x 4096 x 4096 layers: 256 workgroup tiles of 256 x 256 each, the tile whose
-    accumulators have the 16 x 16 layout.  Layer 0's epilogue forms the column sums from that layout,
-    layer 1 takes them.  Sampled rows of both layers against the oracle on the input the device's
+@pytest.mark.parametrize("M,region", [(4096, (256, 256)), (2048, (256, 128))])
+def test_handover_between_layers_on_the_256x256_tile(dtype, M, region):
+    """Two M x 4096 x 4096 layers: 256 workgroup tiles each, of 256 x 256 (M = 4096) or 256 x 128
+    (M = 2048): the tiles whose accumulators have the 16 x 16 layout.  Layer 0's epilogue forms the
+    column sums from that layout, layer 1 takes them.  Sampled rows of both layers against the oracle on the input the device's
     layer read, the device's worst region against the oracle's check of that region, the same C bit
     for bit as the layers run one by one, and a seeded fault in the layer that takes the sums."""
     import torch
     from gpu_util import read_report, c_to_host, c_close, sample_rows
-    M, widths = 4096, [4096, 4096, 4096]
+    widths = [4096, 4096, 4096]
     ch = Chain(M, widths, dtype, seed=1900, modes=[B.GLOBAL] * 2)
     try:
         reps = _reports(ch)
@@ -345,7 +346,7 @@ def test_handover_between_layers_on_the_256x256_tile(dtype):
         for l in range(ch.nl):
             K, N = widths[l], widths[l + 1]
             bm, bn = B.abft_region_shape(M, N, K, DT[dtype], True)
-            assert (bm, bn) == (256, 256)
+            assert (bm, bn) == region
             ref = oracle.activation(oracle.gemm_rows(a_in, ch.Ws[l], dtype, rows), ch.acts[l])
             assert c_close(c_to_host(ch.Cs[l], dtype)[rows], ref, dtype), l
             assert got[l].tiles == (M // bm) * (N // bn), l
@@ -374,7 +375,7 @@ def test_handover_between_layers_on_the_256x256_tile(dtype):
         a1 = _storage(chained[0], dtype)
         K, N = widths[1], widths[2]
         must = mustnot = 0
-        for t, (i, j, bit) in enumerate(((1234, 2345, 30), (17, 4000, 28), (4095, 0, 30), (2048, 255, 2), (300, 3000, 5), (777, 1777, 26))):
+        for t, (i, j, bit) in enumerate(((1234, 2345, 30), (17, 4000, 28), (M - 1, 0, 30), (M // 2, 255, 2), (300, 3000, 5), (777, 1777, 26))):
             print(f"case handover fault on 256x256 tiles dtype={dtype} ({i},{j}) bit {bit}", flush=True)
             ch.flag.zero_()
             B.abft_plan_set_diagnostics(ch.plan, 1, report=reps[1], inject=B.Fault(i, j, bit, -1))
@@ -387,8 +388,8 @@ def test_handover_between_layers_on_the_256x256_tile(dtype):
                 assert flag == 1
                 must += 1
                 continue
-            r0, c0 = i // 256 * 256, j // 256 * 256
-            blk = oracle.gemm(a1[r0:r0 + 256], np.ascontiguousarray(ch.Ws[1][:, c0:c0 + 256]), dtype)
+            r0, c0 = i // region[0] * region[0], j // region[1] * region[1]
+            blk = oracle.gemm(a1[r0:r0 + region[0]], np.ascontiguousarray(ch.Ws[1][:, c0:c0 + region[1]]), dtype)
             cl = float(blk[i - r0, j - c0])
             tau = oracle.tolerance(K, math.sqrt(max(oracle.frob(blk) ** 2 - cl * cl + bad * bad, 0.0)), dtype, scheme=1,
                                    l1_norm=oracle.l1norm(blk) - abs(cl) + abs(bad))

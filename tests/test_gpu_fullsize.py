@@ -227,3 +227,29 @@ def test_large_conv_on_the_big_tile():
         assert int(flag.item()) == 0
         if mode != B.NONE:
             assert read_report(rep).worst_ratio < 0.5
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_ragged_one_round_uses_the_256x128_tile(dtype):
+    """2000 x 3990 x 1024: 8 x 32 tiles of 256 x 128, one round of workgroups, both edges ragged.
+    Unprotected and global run on that tile (three LDS stages, 16 x 16 accumulator blocks), the
+    thread-level scheme on another one; sampled rows against the oracle, the reported region against
+    the oracle's check of it, seeded faults in the clipped last tile."""
+    from gpu_util import c_to_host, c_close
+    M, N, K = 2000, 3990, 1024
+    big = Big(M, N, K, dtype, seed=7)
+    assert (big.rm, big.rn) == (256, 128)
+    rows = np.array([0, 63, 64, 255, 256, 1791, 1792, 1999])
+    ref = oracle.gemm_rows(big.A, big.Bm, dtype, rows)
+    for mode in (B.NONE, B.GLOBAL, B.THREAD):
+        print(f"case one round of 256x128 tiles mode={mode} dtype={dtype}", flush=True)
+        flag, rep = big.run(mode)
+        assert c_close(c_to_host(big.dC[rows.tolist()], dtype), ref, dtype)
+        assert flag == 0
+        if mode == B.GLOBAL:
+            assert rep.tiles == 8 * 32
+            _check_reported_region(big, rep, mode)
+    for mode in (B.GLOBAL, B.THREAD):
+        for (i, j) in ((1999, 3989), (1900, 17)):
+            flag, _ = big.run(mode, inject=B.Fault(i, j, 29, -1))
+            assert flag == 1, (mode, i, j)

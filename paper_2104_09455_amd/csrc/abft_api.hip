@@ -127,13 +127,14 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         const bool rounds_full = t256 * 10 >= cdiv(t256, 256) * 256 * 7;
         if (fast_ok && N > 128 && nkt_all > 1 && rounds_full && (t256 >= 224 || (t256 >= 192 && nkt_all >= 8)))
             return mode == ABFT_THREAD ? CFG_F128T : CFG_F256W;
-        // About one 256 x 128 tile per compute unit (one round, at least two thirds full) with a k loop
-        // of eight tiles or more: that tile keeps three stages in LDS and asks the vector memory
+        // About one 256 x 128 tile per compute unit (one round, more than half full) with a k loop
+        // of six tiles or more: that tile keeps three stages in LDS and asks the vector memory
         // path for three quarters of what 128 x 128 tiles ask per MFMA (2048 x 4096 x 4096: 70 us
-        // against 77 us; 1536 x 4096 x 4096: 59 against 65; 2048 x 3072 x 4096: 56 against 63).  Its
-        // wavefront tiles carry no wavefront-level scheme.
+        // against 77 us; 1536 x 4096 x 4096: 59 against 65; 2048 x 3072 x 4096: 56 against 63;
+        // 144 tiles, 1152 x 4096 x 4096: 52 against 57; 128 tiles, 1024 x 4096 x 4096: 53 against 48;
+        // k loop of four tiles: level).  Its wavefront tiles carry no wavefront-level scheme.
         const long long t256n = tiles(CFG_F256N);
-        if (fast_ok && mode != ABFT_THREAD && N >= 128 && nkt_all >= 8 && t256n >= 176 && t256n <= 256) return CFG_F256N;
+        if (fast_ok && mode != ABFT_THREAD && N >= 128 && nkt_all >= 6 && t256n >= 144 && t256n <= 256) return CFG_F256N;
         const bool fills128 = tiles(CFG_F128) >= 128;
         if (fast_ok && fills128 && N < 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
         // Few tiles: the time is the latency of a workgroup's k loop and the rate at which one

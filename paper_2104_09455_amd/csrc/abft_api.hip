@@ -108,7 +108,7 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     const bool force_fits = force >= 0 && force < CFG_COUNT &&
                             (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force)));
     // (the 256 x 256 tile carries no wavefront-level scheme: a forced choice of it does not apply to those)
-    if (force_fits && !((force == CFG_F256W || force == CFG_F256N) && mode == ABFT_THREAD)) return force;
+    if (force_fits && !((force == CFG_F256W || force == CFG_F256N || force == CFG_F256S) && mode == ABFT_THREAD)) return force;
     if (M <= 16 && !aligned16) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);
@@ -135,6 +135,13 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
         // k loop of four tiles: level).  Its wavefront tiles carry no wavefront-level scheme.
         const long long t256n = tiles(CFG_F256N);
         if (fast_ok && mode != ABFT_THREAD && N >= 128 && nkt_all >= 6 && t256n >= 144 && t256n <= 256) return CFG_F256N;
+        // Outputs of at most 64 columns and very many rows (ResNet-50's first stage at batch 64: 200704
+        // rows): 256 x 64 tiles with three stages.  3 x 3 convolution 64 -> 64: 46 us against 52 us
+        // unprotected, 52 against 63 global; K = 64: 17 against 23 us global, level unprotected; k loops
+        // of two to five tiles: slower unprotected (33 against 30 us at K = 256).
+        if (fast_ok && mode != ABFT_THREAD && N <= 64 && N > 32 && M >= 65536 &&
+            (nkt_all >= 6 || (nkt_all == 1 && mode == ABFT_GLOBAL)))
+            return CFG_F256S;
         const bool fills128 = tiles(CFG_F128) >= 128;
         if (fast_ok && fills128 && N < 128) return CFG_F128T;  // narrow outputs: every wavefront spans all columns
         // Few tiles: the time is the latency of a workgroup's k loop and the rate at which one

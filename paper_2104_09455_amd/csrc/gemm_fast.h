@@ -480,11 +480,15 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
                 }
                 __builtin_amdgcn_sched_barrier(0);  // (the read below must not move above the MFMAs: it reuses their register)
                 fa[0][i] = *reinterpret_cast<const i32x4*>(src + a_off + i * MI * ROWB + ps);
-                if (i < TN) fb[cur ^ 1][i] = *reinterpret_cast<const i32x4*>(src + b_off + i * MI * ROWB + ps);
+                // (the TN fragments of B spread over the first block rows: one each, or TN / TM each)
+                constexpr int BPG = TN > TM ? TN / TM : 1;
+#pragma unroll
+                for (int j = i * BPG; j < (i + 1) * BPG && j < TN; ++j)
+                    fb[cur ^ 1][j] = *reinterpret_cast<const i32x4*>(src + b_off + j * MI * ROWB + ps);
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
-        static_assert(MI == 32 || TM >= TN, "a read of B behind each of the first block rows");
+        static_assert(MI == 32 || TM >= TN || TN % TM == 0, "the reads of B behind the block rows");
         half(st, pos[1], 0);
         const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
         const char* src = st;  // (last tile: the reads of the second step fetch nothing that is used)

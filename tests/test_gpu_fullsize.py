@@ -195,21 +195,24 @@ def test_ragged_large_uses_the_big_tile_and_matches(dtype):
         assert flag == 1
 
 
-def test_large_conv_on_the_big_tile():
-    """3x3 conv 64->256 on 56x56, batch 20 (M = 62720, K = 576): implicit GEMM through the
-    direct-to-LDS kernel, sampled output pixels against the oracle's im2col product."""
+@pytest.mark.parametrize("batch,cout,region", [(20, 256, (256, 256)), (21, 64, (256, 64))])
+def test_large_conv_on_the_big_tile(batch, cout, region):
+    """3x3 conv 64->256 on 56x56, batch 20 (M = 62720, K = 576) on 256 x 256 tiles, and 64->64 at
+    batch 21 (M = 65856) on 256 x 64 tiles: implicit GEMM through the direct-to-LDS kernel, sampled
+    output pixels against the oracle's im2col product."""
     import ctypes
     import torch
     from gpu_util import to_dev, c_to_host, c_close, read_report, DEV
-    c = wl.Conv(20, 56, 56, 64, 256, 3, 3, 1, 1)
+    c = wl.Conv(batch, 56, 56, 64, cout, 3, 3, 1, 1)
     x, Wm = wl.conv_operands(c, "f16", seed=6)
-    M, K, N = c.batch * c.OH * c.OW, 576, 256
-    assert B.abft_region_shape(M, N, K, B.F16, True) == (256, 256)
-    # oracle on sampled output pixels: lower two images only (pixels are independent per image)
-    A2 = oracle.im2col(x[[0, 19]], "f16", 3, 3, 1, 1)
+    M, K, N = c.batch * c.OH * c.OW, 576, cout
+    assert B.abft_region_shape(M, N, K, B.F16, True) == region
+    # oracle on sampled output pixels: first and last image only (pixels are independent per image)
+    last = batch - 1
+    A2 = oracle.im2col(x[[0, last]], "f16", 3, 3, 1, 1)
     rows2 = np.array([0, 55, 56 * 56 - 1, 56 * 56, 2 * 56 * 56 - 1, 3000])
     ref = oracle.gemm_rows(A2, Wm, "f16", rows2)
-    rows = np.where(rows2 < 3136, rows2, rows2 - 3136 + 19 * 3136)
+    rows = np.where(rows2 < 3136, rows2, rows2 - 3136 + last * 3136)
     dx, dB = to_dev(x, "f16"), to_dev(np.ascontiguousarray(Wm.T), "f16")
     dC = torch.zeros((M, N), dtype=torch.float16, device=DEV)
     flag = torch.zeros(1, dtype=torch.int32, device=DEV)
@@ -251,5 +254,30 @@ def test_ragged_one_round_uses_the_256x128_tile(dtype):
             _check_reported_region(big, rep, mode)
     for mode in (B.GLOBAL, B.THREAD):
         for (i, j) in ((1999, 3989), (1900, 17)):
+            flag, _ = big.run(mode, inject=B.Fault(i, j, 29, -1))
+            assert flag == 1, (mode, i, j)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16", "i8"])
+def test_narrow_output_with_many_rows_uses_the_256x64_tile(dtype):
+    """70000 x 60 x 1024: 274 tiles of 256 x 64 (the last clipped in rows, all clipped in columns).
+    Unprotected and global run on that tile, the thread-level scheme on another one; sampled rows
+    against the oracle, the reported region against the oracle's check of it, seeded faults."""
+    from gpu_util import c_to_host, c_close
+    M, N, K = 70000, 60, 1024
+    big = Big(M, N, K, dtype, seed=8)
+    assert (big.rm, big.rn) == (256, 64)
+    rows = np.array([0, 31, 32, 255, 256, 69887, 69888, 69999])
+    ref = oracle.gemm_rows(big.A, big.Bm, dtype, rows)
+    for mode in (B.NONE, B.GLOBAL, B.THREAD):
+        print(f"case 256x64 tiles mode={mode} dtype={dtype}", flush=True)
+        flag, rep = big.run(mode)
+        assert c_close(c_to_host(big.dC[rows.tolist()], dtype), ref, dtype)
+        assert flag == 0
+        if mode == B.GLOBAL:
+            assert rep.tiles == 274
+            _check_reported_region(big, rep, mode)
+    for mode in (B.GLOBAL, B.THREAD):
+        for (i, j) in ((69999, 59), (40000, 0)):
             flag, _ = big.run(mode, inject=B.Fault(i, j, 29, -1))
             assert flag == 1, (mode, i, j)

@@ -108,7 +108,7 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
     const bool force_fits = force >= 0 && force < CFG_COUNT &&
                             (fast_ok || !cfg_info_host(force).fast || (aligned16 && cfg_is_stream(force)));
     // (the 256 x 256 tile carries no wavefront-level scheme: a forced choice of it does not apply to those)
-    if (force_fits && !((force == CFG_F256W || force == CFG_F256N || force == CFG_F256S) && mode == ABFT_THREAD)) return force;
+    if (force_fits && !((force == CFG_F256W || force == CFG_F256N || force == CFG_F256S || force == CFG_F128E) && mode == ABFT_THREAD)) return force;
     if (M <= 16 && !aligned16) return CFG_G16;
     auto tiles = [&](int id) {
         CfgInfo ci = cfg_info_host(id);
@@ -159,6 +159,13 @@ int pick_cfg(int M, int N, int K, int dt, bool aligned16, int mode) {
             // (thread-level: the wide wavefront tiles pay off once two workgroups share a compute unit;
             // with at most one per unit the 64 x 64 wavefront tiles' cheaper checksum wins: 1536 x 2048 x
             // 2048 takes 37 us against 42 us, 640 x 5120 x 1280 26 us against 30 us)
+            // At most one 128 x 128 tile per compute unit (one round): eight wavefronts of 32 x 64 on the
+            // 16x16x32 shapes with three stages instead of four wavefronts of 64 x 64 with two: the second
+            // wavefront per SIMD and the deeper pipeline hide what a second workgroup would (1024 x 4096 x
+            // 4096: 40-43 us against 46-48; 2048^3: 22 against 26; 12544 x 256 x 2304: 25 against 28;
+            // global the same tenth).  Two rounds: slower (3072 x 4096 x 4096: 115 against 91 us on two
+            // workgroups per unit).  No wavefront-level scheme on it.
+            if (fills128 && mode != ABFT_THREAD && tiles(CFG_F128) <= 256 && nkt_all >= 4) return CFG_F128E;
             if (fills128) return (nkt_all <= 1 || (mode == ABFT_THREAD && tiles(CFG_F128) > 256)) ? CFG_F128T : CFG_F128;
             return CFG_F64T;
         }
@@ -827,7 +834,9 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
             beta_used = ws + w.off_beta;
         }
         if (weighted) kmode = MODE_GLOBAL_W;
-        if (pr.alpha_in && !weighted && !pr.conv && pr.dtype != ABFT_I8 && ci.fast && ci.kways == 1) {
+        // (not on the eight-wavefront 128 x 128 tile: its wavefront tiles are so small that the sums' ring
+        // costs more than the extra MFMA of the in-loop form: 46 against 44.5 us at 1024 x 4096 x 4096)
+        if (pr.alpha_in && !weighted && !pr.conv && pr.dtype != ABFT_I8 && ci.fast && ci.kways == 1 && cfg != CFG_F128E) {
             // steps 1-2 were the previous layer's: its epilogue left the column sums of this
             // layer's A per 32-row block; one multiplication per lane and k tile is all that is left
             kmode = MODE_GLOBAL_FED;
@@ -1392,8 +1401,9 @@ float* handover_target(const abft_plan_t* plan, int next, const void* a_next, in
     const int es = esize(e.dtype);
     const bool a16 = aligned16(a_next) && (lda_next * es) % 16 == 0 && (e.K * es) % 16 == 0;
     const bool b16 = e.b_layout == ABFT_B_NK && aligned16(e.B) && (e.K * es) % 16 == 0 && (e.ldb * es) % 16 == 0;
-    const CfgInfo ci = cfg_info_host(pick_cfg(e.M, e.N, e.K, e.dtype, a16 && b16, ABFT_GLOBAL));
-    return (ci.fast && ci.kways == 1) ? nx.alpha32 : nullptr;
+    const int cfg = pick_cfg(e.M, e.N, e.K, e.dtype, a16 && b16, ABFT_GLOBAL);
+    const CfgInfo ci = cfg_info_host(cfg);
+    return (ci.fast && ci.kways == 1 && cfg != CFG_F128E) ? nx.alpha32 : nullptr;
 }
 
 // One layer of a plan.  alpha_out (may be null): where to leave the activation checksums of the

@@ -14,6 +14,11 @@ namespace abft {
 //    F256S  256 x  64, wavefronts 8 x 1 of  32 x  64, 3 stages, 16x16x32 shapes       outputs of at most 64 columns
 //                                                                    (many rows), unprotected / global
 //    F128   128 x 128, wavefronts 2 x 2 of  64 x  64, 2 stages       mid-size, unprotected / global
+//    F128E  128 x 128, wavefronts 4 x 2 of  32 x  64 (two per SIMD), 3 stages, 16x16x32 shapes
+//                                                                    at most one such tile per compute unit: the second
+//                                                                    wavefront per SIMD and the third stage stand in for
+//                                                                    the second workgroup that would hide the latencies;
+//                                                                    unprotected / global
 //    F128T  128 x 128, wavefronts 4 x 1 of  32 x 128, 2 stages       thread-level (wide tiles: two checksum
 //                                                                    MFMAs per four), narrow outputs, K of one k tile
 //    F64T    64 x 128, wavefronts 2 x 1 of  32 x 128, 3 stages       between the streaming tiles and F128
@@ -24,7 +29,7 @@ namespace abft {
 //    S128    64 x  64, 2 stages per wavefront                         up to about one tile per compute unit
 //  G* run the generic kernel (any alignment, layout, K):
 //    G128 128 x 128, G64 64 x 64 (32x32 MFMA shapes), G16 16 x 64 (16x16 shapes; M <= 16)
-enum CfgId { CFG_F256W = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_S32, CFG_S64, CFG_S128, CFG_G128, CFG_G64, CFG_G16, CFG_F256N, CFG_F256S, CFG_COUNT };
+enum CfgId { CFG_F256W = 0, CFG_F128, CFG_F128T, CFG_F64T, CFG_S32, CFG_S64, CFG_S128, CFG_G128, CFG_G64, CFG_G16, CFG_F256N, CFG_F256S, CFG_F128E, CFG_COUNT };
 
 template <int DT, int ID>
 struct CfgOf;
@@ -35,6 +40,7 @@ template <int DT> struct CfgOf<DT, CFG_F64T>  { typedef Cfg<DT, 32, 1, 4, 2, 1, 
 template <int DT> struct CfgOf<DT, CFG_F256W> { typedef Cfg<DT, 16, 8, 4, 2, 4, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F256N> { typedef Cfg<DT, 16, 4, 4, 4, 2, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_F256S> { typedef Cfg<DT, 16, 2, 4, 8, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 1; };
+template <int DT> struct CfgOf<DT, CFG_F128E> { typedef Cfg<DT, 16, 2, 4, 4, 2, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 1; };
 template <int DT> struct CfgOf<DT, CFG_S32>   { typedef Cfg<DT, 32, 1, 1, 1, 1, 128> type; static constexpr int NSTAGE = 4; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_S64>   { typedef Cfg<DT, 32, 1, 2, 1, 1, 128> type; static constexpr int NSTAGE = 3; static constexpr int KWAYS = 4; };
 template <int DT> struct CfgOf<DT, CFG_S128>  { typedef Cfg<DT, 32, 2, 2, 1, 1, 128> type; static constexpr int NSTAGE = 2; static constexpr int KWAYS = 4; };
@@ -68,6 +74,7 @@ inline CfgInfo cfg_info_host(int id) {
         case CFG_F256W: return cfg_info<CFG_F256W>();
         case CFG_F256N: return cfg_info<CFG_F256N>();
         case CFG_F256S: return cfg_info<CFG_F256S>();
+        case CFG_F128E: return cfg_info<CFG_F128E>();
         case CFG_S32: return cfg_info<CFG_S32>();
         case CFG_S64: return cfg_info<CFG_S64>();
         case CFG_S128: return cfg_info<CFG_S128>();

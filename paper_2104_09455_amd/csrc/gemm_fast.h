@@ -98,11 +98,13 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     constexpr bool MDOT16 = GDOT && CFG::MI == 16;  // (bf16: three pieces, columns 0 to 2)
     constexpr bool VDOT = GDOT && !MDOT && !MDOT16;
     static_assert(!MDOT || TM == CFG::WAVES_N, "one block row of the extra product per wavefront of a row of wavefronts");
-    static_assert(!MDOT16 || TM == 2 * CFG::WAVES_N, "two block rows of the extra product per wavefront of a row of wavefronts");
+    static_assert(!MDOT16 || TM % CFG::WAVES_N == 0, "the block rows of the extra product split evenly over a row of wavefronts");
     // ... or reduced to one multiplication per lane and k tile because the layer before left the
     // column sums of this layer's A (per block of 32 rows: one block per wavefront here)
     constexpr bool FED = MODE == MODE_GLOBAL_FED;
-    static_assert(!FED || (DT != DT_I8 && CFG::WAVES_M * CFG::WAVES_N * 32 == BM), "one 32-row block per wavefront");
+    // (one 32-row block per wavefront, or per row of wavefronts whose first one then takes it)
+    constexpr bool FED_PER_ROW = CFG::WAVES_M * CFG::WAVES_N * 32 != BM;
+    static_assert(!FED || (DT != DT_I8 && (!FED_PER_ROW || CFG::WM == 32)), "a 32-row block per wavefront or per row of wavefronts");
     constexpr int EMODE = (MODE == MODE_GLOBAL_PRE || FED) ? MODE_GLOBAL : MODE;  // the epilogue's scheme
     constexpr bool IS_INT = DT == DT_I8;
 
@@ -179,13 +181,17 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // copies any later wait counts on, so every such wait covers them too.
     const char* fed_alpha = nullptr;
     const char* fed_beta = nullptr;
+    // (a row of wavefronts per block: one of them takes it, chosen so that the takers sit on different
+    // SIMDs -- wavefront w runs on SIMD w % 4 --, wavefront 0, which copies the weight checksums, among them)
+    const bool fed_on = !FED_PER_ROW || wave_n == ((wave_m >> 1) % CFG::WAVES_N);
     if constexpr (FED) {
-        const int blk = tile_m * (BM / 32) + wave;
-        if (blk * 32 < M) fed_alpha = reinterpret_cast<const char*>(p.alpha_in + (long long)blk * p.K);
+        const int blk = tile_m * (BM / 32) + (FED_PER_ROW ? wave_m : wave);
+        if (blk * 32 < M && fed_on) fed_alpha = reinterpret_cast<const char*>(p.alpha_in + (long long)blk * p.K);
         fed_beta = p.beta_k + (long long)tile_n * p.K * 4;
     }
     auto issue_group = [&](int g) {
         if constexpr (FED) {
+            if (!fed_on) return;
             const int f0 = 256 * g + 4 * lane;                 // first of this lane's four floats
             const bool in_k = f0 + 4 <= p.K;                   // (K is a multiple of 64: whole lanes)
             const char* src = (fed_alpha && in_k) ? fed_alpha + (long long)f0 * 4 : zero;
@@ -293,6 +299,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     float fed_a = 0.f, fed_b = 0.f;
     auto fed_tile = [&](const char* st, int kt) {
         if constexpr (FED) {
+            if (!fed_on) return;
             // lane l: (column sum of the wavefront's 32 rows at k = l of the tile) x (weight checksum
             // there); the product is taken one tile later, when the two reads have long landed
             dot.total += (double)fed_a * (double)fed_b;
@@ -475,8 +482,8 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
 #pragma unroll
                 for (int j = 0; j < TN; ++j) acc[i][j] = MMA::run(fa[0][i], fb[cur][j], acc[i][j]);
                 if constexpr (MDOT16) {
-                    // (wavefront column c of a row of wavefronts takes block rows 2 c and 2 c + 1)
-                    if ((i >> 1) == wave_n) gchk = MMA::run(fa[0][i], fg[cur], gchk);
+                    // (wavefront column c of a row of wavefronts takes its share of the block rows: 2 c and 2 c + 1 of eight over four)
+                    if (i / (TM / CFG::WAVES_N) == wave_n) gchk = MMA::run(fa[0][i], fg[cur], gchk);
                 }
                 __builtin_amdgcn_sched_barrier(0);  // (the read below must not move above the MFMAs: it reuses their register)
                 fa[0][i] = *reinterpret_cast<const i32x4*>(src + a_off + i * MI * ROWB + ps);

@@ -17,9 +17,11 @@ from test_gpu_chain import Chain, _storage, DT
 
 pytestmark = pytest.mark.gpu
 
-# every layer large enough for the direct-to-LDS kernel; the last one (narrow, long k) streams
+# every layer on the direct-to-LDS kernel; layers 1 (128 x 128 tiles, two workgroups per compute unit)
+# and 2 (256 x 256 tiles) take handed-over sums, the last one (narrow: one round of 128 x 128 tiles on
+# eight wavefronts each) forms its own in the loop
 WIDTHS = [512, 1024, 1024, 2048, 512]
-M_MID = 4096
+M_MID = 8192
 
 
 def _reports(ch):
@@ -188,7 +190,7 @@ def test_ragged_batch_and_widths():
     """M not a multiple of 32, N not a multiple of the tile: the last row block's checksums cover
     the rows that exist, columns past N are never written."""
     import torch
-    ch = Chain(3001, [512, 960, 1024, 640], "f16", seed=1500, modes=[B.GLOBAL] * 3)
+    ch = Chain(6001, [512, 960, 1024, 640], "f16", seed=1500, modes=[B.GLOBAL] * 3)
     try:
         x, dx = ch.input(seed=1501)
         before = B.abft_handover_launches()

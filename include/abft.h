@@ -242,8 +242,7 @@ size_t abft_conv_workspace_bytes(const abft_conv_t *conv /* host */, int N, int 
  * last, again at a multiple of 256 bytes, per block and per k tile of the large-tile kernel (64
  * values of k; I8: 128) one record of 1 KB that the kernel copies in with its operand tiles: F16:
  * 64 halves fl16(beta), 64 halves fl16((beta - fl16(beta)) 2^11), then from byte 256 the 64 floats;
- * BF16: the 64 floats at byte 256 and, at bytes 0, 128 and 512, 64 bf16 values each: p0 = bf(beta),
- * p1 = bf((beta - p0) 2^8), p2 = bf(((beta - p0) 2^8 - p1) 2^8); I8: 128 low digits, 128 high digits.
+ * BF16: the 64 floats at byte 256; I8: 128 low digits, 128 high digits.
  * block_n <= 0 or >= N gives the plain K-vector B.1 . */
 int abft_weight_checksum(int K, int N, const void *B, int64_t ldb, int b_layout, int dtype, int block_n,
                          void *beta, void *stream);

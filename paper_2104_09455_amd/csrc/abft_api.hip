@@ -435,8 +435,7 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
         // column-weighted checksum (balanced base 256, least significant first)
         // fourth copy, for the direct-to-LDS kernel: per block and k tile of that kernel (64 values of k;
         // int8: 128) a record of 1 KB -- fp16: 64 halves fl16(beta), 64 halves fl16((beta - hi) 2^11), then
-        // (at byte 256) 64 floats; bf16: the 64 floats there, three bf16 pieces at bytes 0, 128 and 512;
-        // int8: 128 low digits, 128 high digits
+        // (at byte 256) 64 floats; bf16: the 64 floats; int8: 128 low digits, 128 high digits
         constexpr int KT = DT == DT_I8 ? 128 : 64;
         char* rec = beta_r + ((long long)blockIdx.y * ((K + KT - 1) / KT) + k / KT) * 1024;
         const int kin = k % KT;
@@ -468,17 +467,6 @@ __global__ __launch_bounds__(256) void weight_checksum_kernel(const char* B, int
                 const _Float16 vhi = (_Float16)(float)av;
                 pl[2 * K + k] = vhi;
                 pl[3 * K + k] = (_Float16)(((float)av - (float)vhi) * 2048.f);
-            } else {
-                // bf16 record: three pieces at bytes 0, 128 and 512: p0 = bf(beta), p1 = bf((beta - p0) 2^8),
-                // p2 = bf(((beta - p0) 2^8 - p1) 2^8) (every difference exact in fp32)
-                const float af = (float)a;
-                const __bf16 p0 = (__bf16)af;
-                const float r1 = (af - (float)p0) * 256.f;
-                const __bf16 p1 = (__bf16)r1;
-                const float r2 = (r1 - (float)p1) * 256.f;
-                reinterpret_cast<__bf16*>(rec)[kin] = p0;
-                reinterpret_cast<__bf16*>(rec + 128)[kin] = p1;
-                reinterpret_cast<__bf16*>(rec + 512)[kin] = (__bf16)r2;
             }
         }
     }

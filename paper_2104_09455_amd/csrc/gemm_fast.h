@@ -93,9 +93,12 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     // operand type holds, are two more columns of B) or with vector FMAs (bf16, which wants three
     // pieces; the 256 x 256 tile, which has no registers left for one more accumulator block)
     constexpr bool MDOT = GDOT && DT != DT_BF16 && CFG::MI == 32 && TM * TN <= 4;
-    // (16x16 shapes: the same with two block rows of A per wavefront and only the first two (bf16:
-    // three) columns of the extra block of B in use: two more MFMAs per 32 and k step)
-    constexpr bool MDOT16 = GDOT && CFG::MI == 16;  // (bf16: three pieces, columns 0 to 2)
+    // (16x16 shapes, int8: the same with the block rows of A split over a row of wavefronts and only the
+    // first two columns of the extra block of B in use)
+    // int8 only: on all-positive fp16 / bf16 operands and short k loops its fp32 sums of whole block
+    // rows times the (large) weight checksums came to 0.6-1.0 of the comparison's tolerance, against
+    // 0.1-0.2 for the vector form, which leaves fp32 after eight products
+    constexpr bool MDOT16 = GDOT && CFG::MI == 16 && DT == DT_I8;
     constexpr bool VDOT = GDOT && !MDOT && !MDOT16;
     static_assert(!MDOT || TM == CFG::WAVES_N, "one block row of the extra product per wavefront of a row of wavefronts");
     static_assert(!MDOT16 || TM % CFG::WAVES_N == 0, "the block rows of the extra product split evenly over a row of wavefronts");
@@ -462,21 +465,25 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     auto tile_step16 = [&](int kt) {
         const char* st = smem + stage * STAGE;
         fed_tile(st, kt);
-        static_assert(MI == 32 || !VDOT, "16x16 shapes: the in-loop dot product runs on the matrix unit");
+        i32x4 b0 = {0, 0, 0, 0}, b1 = {0, 0, 0, 0};
+        if constexpr (VDOT) {
+            b0 = *reinterpret_cast<const i32x4*>(st + beta_off);
+            b1 = *reinterpret_cast<const i32x4*>(st + beta_off + (IS_INT ? 128 : 16));
+        }
         // matrix-unit dot product: column 0 / 1 of the extra block of B is the first / second piece of
         // the weight checksums (lane: column l % 16, the 16 bytes of k group l / 16 of the step); the
         // fragments of both k steps are read here, before the barrier gives the stage away
         i32x4 fg[2] = {{0, 0, 0, 0}, {0, 0, 0, 0}};
         if constexpr (MDOT16) {
             const i32x4 z = {0, 0, 0, 0};
-            constexpr int NPC = DT == DT_BF16 ? 3 : 2;  // pieces: at bytes 0 and 128 of the record, bf16's third at 512
+            constexpr int NPC = 2;  // the low and the high digits: at bytes 0 and 128 of the record
             const int pc = lane & 15;
-            const char* rec = st + LAY::AB_STAGE + (pc == 2 ? 512 : (pc & 1) * 128) + fgrp * 16;
+            const char* rec = st + LAY::AB_STAGE + (pc & 1) * 128 + fgrp * 16;
             const i32x4 r0 = *reinterpret_cast<const i32x4*>(rec), r1 = *reinterpret_cast<const i32x4*>(rec + 64);
             fg[0] = pc < NPC ? r0 : z;
             fg[1] = pc < NPC ? r1 : z;
         }
-        auto half = [&](const char* src, int ps, int cur) {
+        auto half = [&](const char* src, int ps, int cur, bool dots) {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
 #pragma unroll
@@ -492,11 +499,23 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
 #pragma unroll
                 for (int j = i * BPG; j < (i + 1) * BPG && j < TN; ++j)
                     fb[cur ^ 1][j] = *reinterpret_cast<const i32x4*>(src + b_off + j * MI * ROWB + ps);
+                if constexpr (VDOT) {
+                    // vector form of the in-loop dot product: this lane's NQA chunks of A (the ones it
+                    // copied) spread over the block rows of the first step, the flush behind the last
+                    constexpr int CPG = NQA > TM ? NQA / TM : 1, DSTR = NQA > TM ? 1 : TM / NQA;
+                    static_assert(NQA > TM ? NQA % TM == 0 : TM % NQA == 0, "chunks of A over block rows");
+                    if (dots && i % DSTR == 0) {
+#pragma unroll
+                        for (int q = (i / DSTR) * CPG; q < (i / DSTR + 1) * CPG && q < NQA; ++q)
+                            dot.chunk(*reinterpret_cast<const i32x4*>(st + (q * WAVES + wave) * 1024 + lane * 16), b0, b1, q);
+                    }
+                    if (dots && i == TM - 1) dot.flush();
+                }
                 __builtin_amdgcn_sched_barrier(0);
             }
         };
         static_assert(MI == 32 || TM >= TN || TN % TM == 0, "the reads of B behind the block rows");
-        half(st, pos[1], 0);
+        half(st, pos[1], 0, true);
         const int next = stage + 1 == NSTAGE ? 0 : stage + 1;
         const char* src = st;  // (last tile: the reads of the second step fetch nothing that is used)
         if (kt + 1 < nkt) {
@@ -509,7 +528,7 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
             }
             src = smem + next * STAGE;
         }
-        half(src, pos[0], 1);
+        half(src, pos[0], 1, false);
         stage = next;
         if constexpr (INJ) {
             if (kt == p.f_kt) inject_fault<CFG>(acc, p, TileCoords<CFG>(tile_m, tile_n));
@@ -536,22 +555,14 @@ __global__ __launch_bounds__(CFG::THREADS) void gemm_fast_kernel(const GemmArgs 
     }
     if constexpr (FED) dot.total += (double)fed_a * (double)fed_b;  // the last tile's
     if constexpr (MDOT16) {
-        // this lane's share of the dot product: column c of the extra block holds A . (piece c), whose
-        // weight is 1, 2^-11 (fp16) / 2^-8 (bf16) / 256 (int8: the high digit), and bf16's third 2^-16
-        const int pc = lane & 15;
-        if constexpr (IS_INT) {
-            int g_lo = 0, g_hi = 0;
+        // this lane's share of the dot product: column 0 / 1 of the extra block holds A . (low / high digits)
+        int g_lo = 0, g_hi = 0;
 #pragma unroll
-            for (int r = 0; r < MMA::NACC; ++r) {
-                g_lo += gchk[r] & 0xffff;
-                g_hi += gchk[r] >> 16;
-            }
-            dot.total = (((long long)g_hi << 16) + (long long)g_lo) * (pc == 1 ? 256 : 1);
-        } else {
-            const double g = (double)((gchk[0] + gchk[1]) + (gchk[2] + gchk[3]));
-            const double w1 = DT == DT_F16 ? 1.0 / 2048.0 : 1.0 / 256.0;
-            dot.total = g * (pc == 0 ? 1.0 : (pc == 1 ? w1 : 1.0 / 65536.0));
+        for (int r = 0; r < MMA::NACC; ++r) {
+            g_lo += gchk[r] & 0xffff;
+            g_hi += gchk[r] >> 16;
         }
+        dot.total = (((long long)g_hi << 16) + (long long)g_lo) * ((lane & 15) == 1 ? 256 : 1);
     }
     if constexpr (MDOT) {
         // this lane's share of the dot product: even columns hold A . (first piece), odd columns

@@ -202,21 +202,6 @@ def test_checksum_vectors(dtype):
                             assert np.array_equal(recs[b, t][:2 * n_k].view(np.float16), h)
                             assert np.array_equal(recs[b, t][128:128 + 2 * n_k].view(np.float16),
                                                   ((want - h.astype(np.float32)) * np.float32(2048)).astype(np.float16))
-                        else:
-                            # bf16: three pieces (round to nearest even on the upper 16 bits of fp32), each the
-                            # rounded rest of the one before times 2^8; together they give the float back
-                            def bf(x):
-                                u = np.ascontiguousarray(x, dtype=np.float32).view(np.uint32).astype(np.uint64)
-                                return (((u + 0x7FFF + ((u >> 16) & 1)) >> 16) << 16).astype(np.uint32).view(np.float32)
-                            p0 = bf(want)
-                            r1 = (want - p0) * np.float32(256)
-                            p1 = bf(r1)
-                            p2 = bf((r1 - p1) * np.float32(256))
-                            for off, piece in ((0, p0), (128, p1), (512, p2)):
-                                got = recs[b, t][off:off + 2 * n_k].view(np.uint16).astype(np.uint32) << 16
-                                assert np.array_equal(got.view(np.float32), piece), off
-                            back = p0.astype(np.float64) + p1.astype(np.float64) / 256 + p2.astype(np.float64) / 65536
-                            assert np.all(np.abs(back - want) <= 2.0 ** -23 * np.abs(want))
         if dtype == "i8":
             assert np.array_equal(alpha.cpu().numpy(), a_ref)
         else:

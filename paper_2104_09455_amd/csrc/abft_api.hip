@@ -823,7 +823,7 @@ int run_problem(const Problem& pr, int mode, const void* beta, void* workspace, 
         }
         if (weighted) kmode = MODE_GLOBAL_W;
         // (not on the eight-wavefront 128 x 128 tile: its wavefront tiles are so small that the sums' ring
-        // costs more than the extra MFMA of the in-loop form: 46 against 44.5 us at 1024 x 4096 x 4096)
+        // costs more than the in-loop form: 46 against 44.5 us at 1024 x 4096 x 4096)
         if (pr.alpha_in && !weighted && !pr.conv && pr.dtype != ABFT_I8 && ci.fast && ci.kways == 1 && cfg != CFG_F128E) {
             // steps 1-2 were the previous layer's: its epilogue left the column sums of this
             // layer's A per 32-row block; one multiplication per lane and k tile is all that is left

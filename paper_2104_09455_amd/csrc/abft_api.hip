@@ -737,7 +737,12 @@ bool fused_global(const Problem& pr, const CfgInfo& ci) {
     if (force) return force == 1;
     const double t_gemm = 2.0 * pr.M * pr.N * pr.K / (pr.dtype == ABFT_I8 ? 2.0e15 : 1.0e15);
     const double t_pre = 8.0e-6 + (double)pr.M * pr.K * esize(pr.dtype) / 4.5e12;
-    const double in_loop = 0.09;
+    // share of the product's time that the in-loop form costs: about a tenth on the 32x32-shape tiles
+    // (matrix-unit form, or vector form on 64 x 64 wavefront tiles) and for int8 everywhere; the vector
+    // form of fp16 / bf16 on the 16x16-shape tiles: a tenth for fp16 on the 256 x 256 tile, a quarter for
+    // bf16 there (three-piece products), a fifth on the smaller tiles (less work per wavefront to hide it in)
+    double in_loop = 0.09;
+    if (pr.dtype != ABFT_I8 && ci.mi == 16) in_loop = ci.bm == 256 && ci.bn == 256 ? (pr.dtype == ABFT_BF16 ? 0.25 : 0.09) : 0.2;
     return in_loop * t_gemm < t_pre;
 }
 

@@ -53,7 +53,7 @@ constexpr bool cfg_is_stream(int id) { return id == CFG_S32 || id == CFG_S64 || 
 // threads: of one WAVES_M x WAVES_N grid of wavefronts (a streaming launch has kways times as many);
 // kway_bytes: bytes of k that one wavefront takes in turn when kways wavefronts share a tile
 struct CfgInfo {
-    int bm, bn, bk_bytes, wm, wn, threads, lds_bytes, fast, kways, kway_bytes;
+    int bm, bn, bk_bytes, wm, wn, threads, lds_bytes, fast, kways, kway_bytes, mi;
 };
 
 template <int ID>
@@ -63,7 +63,7 @@ constexpr CfgInfo cfg_info() {
     constexpr int kw = CfgOf<DT_F16, ID>::KWAYS;
     constexpr int lds = cfg_is_stream(ID) ? kw * ns * ((C::BM + C::BN) * 128 + 768)
                                           : (ns ? ns * ((C::BM + C::BN) * 128 + 1024) + 512 : C::LDS_BYTES);
-    return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, lds, ns ? 1 : 0, kw, cfg_is_stream(ID) ? 128 : 32};
+    return CfgInfo{C::BM, C::BN, C::BKB, C::WM, C::WN, C::THREADS, lds, ns ? 1 : 0, kw, cfg_is_stream(ID) ? 128 : 32, C::MI};
 }
 
 inline CfgInfo cfg_info_host(int id) {

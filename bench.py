@@ -42,8 +42,8 @@ CSIZE = {"f16": 2, "bf16": 2, "i8": 4}
 # profiles/*_hbm_traffic.md: (FETCH_SIZE KiB, WRITE_SIZE KiB) per dispatch and the scale factors the
 # copy probe of the same runs gave (2.0 and 1.0).  Keyed by (layer, M, N, K, dtype, mode).
 TRAFFIC_KIB = {
-    ("top1", 256, 1024, 1024, "f16", "thread"): (3129.6, 517.9),
-    ("sq8192", 8192, 8192, 8192, "f16", "global"): (786920.9, 133318.3),
+    ("top1", 256, 1024, 1024, "f16", "thread"): (3129.5, 518.1),
+    ("sq8192", 8192, 8192, 8192, "f16", "global"): (786912.9, 134962.9),
 }
 TRAFFIC_SCALE = (2.0, 1.0)
 
